@@ -1,0 +1,145 @@
+// Seeded synthetic-input generator, device side (gfx950).
+//
+// This file belongs to the input generator, not to the embedding-bag library and not to the
+// CPU oracle: it holds none of the gather/pool arithmetic.  It provides
+//   * gen_fill_table  - fill a row-major [nrows, D] slab of an embedding-table arena with
+//                       procedural values that the host generator reproduces bit for bit, so
+//                       100+ GB arenas never need a host copy;
+//   * gen_copy_bytes  - a plain device-to-device copy kernel of known size, used to calibrate
+//                       the HBM byte counters of the profiler;
+//   * gen_scrub_cache - stream over a scratch buffer to push earlier data out of L2 / MALL.
+//
+// Value function (shared, by construction, with inputgen/gen.py::table_values):
+//   z  = seed + arena_row * K_ROW + col * K_COL              (mod 2^64)
+//   z  = finaliser of the SplitMix64 generator (Steele, Lea, Flood 2014) applied to z
+//   kind 0 ("normal"): s = sum of the four 16-bit fields of z - 131070   (Irwin-Hall, n = 4)
+//                      v = (float)s * (0.1f / 37837.2f)      -> approx N(0, 0.1^2)
+//   kind 1 ("int")   : v = (float)((int)(z >> 60) - 8)        -> integers in [-8, 7]
+//   f16 tables store v rounded to half, round-to-nearest-even.
+// Only integer operations, one exact int->float conversion and one correctly rounded fp32
+// multiply are used, so numpy on the host and this kernel agree in every bit.
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+namespace {
+
+constexpr uint64_t K_ROW = 0x9E3779B97F4A7C15ull;
+constexpr uint64_t K_COL = 0xD1B54A32D192ED03ull;
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+__device__ __forceinline__ float value_at(uint64_t seed, uint64_t row, uint64_t col, int kind) {
+  const uint64_t z = mix64(seed + row * K_ROW + col * K_COL);
+  if (kind == 1) return (float)((int)(z >> 60) - 8);
+  const int s = (int)(z & 0xFFFF) + (int)((z >> 16) & 0xFFFF) + (int)((z >> 32) & 0xFFFF) +
+                (int)((z >> 48) & 0xFFFF) - 131070;
+  return __fmul_rn((float)s, 0.1f / 37837.2f);
+}
+
+// One thread produces one 16-byte vector (4 floats or 8 halves); D is a multiple of the
+// vector width, so a vector never straddles two rows.
+template <bool F16>
+__global__ __launch_bounds__(256) void fill_kernel(void* __restrict__ dst, uint64_t first_row,
+                                                   uint64_t nvec, uint32_t D, uint64_t seed,
+                                                   int kind) {
+  constexpr uint32_t EPV = F16 ? 8 : 4;
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += stride) {
+    const uint64_t e0 = v * EPV;
+    const uint64_t row = e0 / D;
+    const uint64_t col = e0 - row * D;
+    float x[EPV];
+#pragma unroll
+    for (uint32_t k = 0; k < EPV; ++k) x[k] = value_at(seed, first_row + row, col + k, kind);
+    if constexpr (F16) {
+      union { uint4 u; __half h[8]; } pk;
+#pragma unroll
+      for (uint32_t k = 0; k < EPV; ++k) pk.h[k] = __float2half_rn(x[k]);
+      reinterpret_cast<uint4*>(dst)[v] = pk.u;
+    } else {
+      reinterpret_cast<float4*>(dst)[v] = make_float4(x[0], x[1], x[2], x[3]);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
+                                                   const uint4* __restrict__ src, uint64_t nvec) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += stride)
+    dst[v] = src[v];
+}
+
+__global__ __launch_bounds__(256) void scrub_kernel(uint4* __restrict__ buf, uint64_t nvec) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += stride) {
+    uint4 x = buf[v];
+    x.x += 1u;
+    buf[v] = x;
+  }
+}
+
+unsigned grid_for(uint64_t nvec) {
+  uint64_t blocks = (nvec + 255) / 256;
+  const uint64_t cap = 256ull * 32ull;  // 32 workgroups per CU keeps every CU busy
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  return (unsigned)blocks;
+}
+
+}  // namespace
+
+extern "C" {
+
+// dst: DEVICE pointer to the first element of arena row `first_row` ([nrows, D] row-major).
+// dtype: 0 = fp32, 1 = fp16.  kind: 0 = normal, 1 = int.  Returns 0, or a negative code for a
+// bad argument / a positive hipError_t for a failed launch.
+int gen_fill_table(void* dst, int64_t first_row, int64_t nrows, int32_t D, int32_t dtype,
+                   uint64_t seed, int32_t kind, void* stream) {
+  if (nrows == 0) return 0;
+  if (!dst || nrows < 0 || first_row < 0 || D <= 0) return -1;
+  if (dtype != 0 && dtype != 1) return -2;
+  if (kind != 0 && kind != 1) return -3;
+  const uint32_t epv = dtype == 1 ? 8 : 4;
+  if (D % epv != 0) return -4;
+  if ((reinterpret_cast<uintptr_t>(dst) & 15) != 0) return -5;
+  const uint64_t nvec = (uint64_t)nrows * (uint64_t)D / epv;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dtype == 1)
+    hipLaunchKernelGGL(fill_kernel<true>, dim3(grid_for(nvec)), dim3(256), 0, s, dst,
+                       (uint64_t)first_row, nvec, (uint32_t)D, seed, kind);
+  else
+    hipLaunchKernelGGL(fill_kernel<false>, dim3(grid_for(nvec)), dim3(256), 0, s, dst,
+                       (uint64_t)first_row, nvec, (uint32_t)D, seed, kind);
+  return (int)hipGetLastError();
+}
+
+// Plain copy of nbytes (multiple of 16; both DEVICE pointers 16-byte aligned).
+int gen_copy_bytes(void* dst, const void* src, int64_t nbytes, void* stream) {
+  if (nbytes == 0) return 0;
+  if (!dst || !src || nbytes < 0 || (nbytes & 15)) return -1;
+  if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15) return -5;
+  const uint64_t nvec = (uint64_t)nbytes / 16;
+  hipLaunchKernelGGL(copy_kernel, dim3(grid_for(nvec)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<uint4*>(dst),
+                     static_cast<const uint4*>(src), nvec);
+  return (int)hipGetLastError();
+}
+
+// Read-modify-write over a scratch DEVICE buffer (nbytes multiple of 16) to evict caches.
+int gen_scrub_cache(void* buf, int64_t nbytes, void* stream) {
+  if (nbytes == 0) return 0;
+  if (!buf || nbytes < 0 || (nbytes & 15)) return -1;
+  if (reinterpret_cast<uintptr_t>(buf) & 15) return -5;
+  const uint64_t nvec = (uint64_t)nbytes / 16;
+  hipLaunchKernelGGL(scrub_kernel, dim3(grid_for(nvec)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<uint4*>(buf), nvec);
+  return (int)hipGetLastError();
+}
+
+}  // extern "C"

@@ -1,0 +1,369 @@
+"""Seeded synthetic inputs for the multi-table EmbeddingBag forward.
+
+This module is the *input generator*: it serves both the HIP library's tests/bench and the
+CPU oracle's tests, and holds none of the gather/pool arithmetic itself.  Everything is a pure
+function of one 64-bit seed.
+
+Workload shapes follow the paper's statement of the embedding stage (Sec. 3.1: per table a
+batch of BS samples, each pooling "lookups per sample" rows of length ED) and its two
+synthetic access patterns (Sec. 3.2: "random" = uniform on [0, R), "one item" = a single
+repeated row).  The paper's production traces are not available; a Zipf law over a randomly
+permuted row order stands in for their power-law hotness (Sec. 3.2).
+
+Pieces
+------
+* `Workload`           - shape + distributions of one configuration (`workload(name)`).
+* `table_values`       - procedural table values on the host (numpy), bit-identical to the
+                         device fill kernel in `csrc/embgen.hip`.
+* `fill_arena_device`  - run that fill kernel on a device buffer (ctypes, `libembgen.so`).
+* `make_batches`       - CSR offsets + int64 indices (+ optional weights) for K batches.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libembgen.so")
+
+# ----------------------------------------------------------------------------------------
+# procedural table values
+# ----------------------------------------------------------------------------------------
+_K_ROW = np.uint64(0x9E3779B97F4A7C15)
+_K_COL = np.uint64(0xD1B54A32D192ED03)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+_SCALE = np.float32(0.1) / np.float32(37837.2)  # sigma of the 4-field sum is 65536*sqrt(4/12)
+
+KIND_NORMAL = 0
+KIND_INT = 1
+
+
+def _mix64(z: np.ndarray) -> np.ndarray:
+    z = (z ^ (z >> np.uint64(30))) * _M1
+    z = (z ^ (z >> np.uint64(27))) * _M2
+    return z ^ (z >> np.uint64(31))
+
+
+def table_values(seed: int, arena_rows: Sequence[int], D: int, dtype: str = "f32",
+                 kind: int = KIND_NORMAL) -> np.ndarray:
+    """Values of the given arena rows, shape [len(arena_rows), D], float32 or float16.
+
+    kind 0: approximately N(0, 0.1^2) (sum of four 16-bit uniform fields, centred and scaled);
+    kind 1: integers in [-8, 7] (sums of these are exact in fp32 in any order).
+    """
+    rows = np.asarray(arena_rows, dtype=np.uint64).reshape(-1, 1)
+    cols = np.arange(D, dtype=np.uint64).reshape(1, -1)
+    with np.errstate(over="ignore"):
+        z = _mix64(np.uint64(seed & 0xFFFFFFFFFFFFFFFF) + rows * _K_ROW + cols * _K_COL)
+    if kind == KIND_INT:
+        v = ((z >> np.uint64(60)).astype(np.int64) - 8).astype(np.float32)
+    elif kind == KIND_NORMAL:
+        m = np.uint64(0xFFFF)
+        s = ((z & m) + ((z >> np.uint64(16)) & m) + ((z >> np.uint64(32)) & m)
+             + ((z >> np.uint64(48)) & m)).astype(np.int64) - 131070
+        v = s.astype(np.float32) * _SCALE
+    else:
+        raise ValueError("kind must be 0 (normal) or 1 (int)")
+    if dtype == "f16":
+        return v.astype(np.float16)
+    if dtype == "f32":
+        return v
+    raise ValueError("dtype must be 'f32' or 'f16'")
+
+
+def table_values_range(seed: int, first_row: int, nrows: int, D: int, dtype: str = "f32",
+                       kind: int = KIND_NORMAL, chunk_rows: int = 1 << 16) -> np.ndarray:
+    """Rows [first_row, first_row + nrows) of the arena, generated in chunks."""
+    out = np.empty((nrows, D), dtype=np.float16 if dtype == "f16" else np.float32)
+    for r0 in range(0, nrows, chunk_rows):
+        r1 = min(nrows, r0 + chunk_rows)
+        out[r0:r1] = table_values(seed, np.arange(first_row + r0, first_row + r1, dtype=np.uint64),
+                                  D, dtype, kind)
+    return out
+
+
+# ----------------------------------------------------------------------------------------
+# device side (libembgen.so) - only used where a GPU is present
+# ----------------------------------------------------------------------------------------
+_lib = None
+
+
+def load_lib() -> ctypes.CDLL:
+    """Load libembgen.so (after torch, so that the HIP runtime torch ships is the one used)."""
+    global _lib
+    if _lib is None:
+        import torch  # noqa: F401  (loads libamdhip64 first)
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built; run __graft_entry__.build() first")
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.gen_fill_table.restype = ctypes.c_int
+        lib.gen_fill_table.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                       ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64,
+                                       ctypes.c_int32, ctypes.c_void_p]
+        lib.gen_copy_bytes.restype = ctypes.c_int
+        lib.gen_copy_bytes.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                       ctypes.c_void_p]
+        lib.gen_scrub_cache.restype = ctypes.c_int
+        lib.gen_scrub_cache.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def fill_arena_device(dev_ptr: int, first_row: int, nrows: int, D: int, dtype: str, seed: int,
+                      kind: int = KIND_NORMAL, stream: int = 0) -> None:
+    """Fill arena rows [first_row, first_row+nrows) at device address `dev_ptr` (= address of
+    row `first_row`) with `table_values`; asynchronous on `stream` (a hipStream_t as int)."""
+    rc = load_lib().gen_fill_table(ctypes.c_void_p(dev_ptr), first_row, nrows, D,
+                                   1 if dtype == "f16" else 0,
+                                   ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF), kind,
+                                   ctypes.c_void_p(stream))
+    if rc != 0:
+        raise RuntimeError(f"gen_fill_table failed with code {rc}")
+
+
+def copy_bytes_device(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
+    rc = load_lib().gen_copy_bytes(ctypes.c_void_p(dst_ptr), ctypes.c_void_p(src_ptr), nbytes,
+                                   ctypes.c_void_p(stream))
+    if rc != 0:
+        raise RuntimeError(f"gen_copy_bytes failed with code {rc}")
+
+
+def scrub_cache_device(buf_ptr: int, nbytes: int, stream: int = 0) -> None:
+    rc = load_lib().gen_scrub_cache(ctypes.c_void_p(buf_ptr), nbytes, ctypes.c_void_p(stream))
+    if rc != 0:
+        raise RuntimeError(f"gen_scrub_cache failed with code {rc}")
+
+
+# ----------------------------------------------------------------------------------------
+# workloads
+# ----------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    T: int                      # number of tables
+    rows: Tuple[int, ...]       # rows per table (len T)
+    D: int                      # embedding dimension (uniform over tables)
+    dtype: str                  # 'f32' | 'f16' (table storage; output is always fp32)
+    B: int                      # batch (bags per table)
+    pooling: Tuple              # ('fixed', L) | ('uniform', lo, hi) inclusive
+    dists: Tuple[Tuple, ...]    # per table: ('uniform',) | ('zipf', alpha) | ('one_item',)
+    mode: str = "sum"           # 'sum' | 'mean'
+    weighted: bool = False
+    seed: int = 0x5EED0000
+    kind: int = KIND_NORMAL
+    note: str = ""
+
+    @property
+    def elem_bytes(self) -> int:
+        return 2 if self.dtype == "f16" else 4
+
+    @property
+    def row_bytes(self) -> int:
+        return self.D * self.elem_bytes
+
+    @property
+    def total_rows(self) -> int:
+        return int(sum(self.rows))
+
+    @property
+    def table_bytes(self) -> int:
+        return self.total_rows * self.row_bytes
+
+    @property
+    def num_bags(self) -> int:
+        return self.T * self.B
+
+    def table_offsets(self) -> np.ndarray:
+        return np.concatenate([[0], np.cumsum(np.asarray(self.rows, dtype=np.int64))]).astype(np.int64)
+
+
+def _homog(name, T, R, D, dtype, B, pooling, dist, mode="sum", seed_off=0, **kw) -> Workload:
+    return Workload(name=name, T=T, rows=(R,) * T, D=D, dtype=dtype, B=B, pooling=pooling,
+                    dists=(dist,) * T, mode=mode, seed=0x5EED0000 + seed_off, **kw)
+
+
+def workload(name: str) -> Workload:
+    """The five benchmark configurations plus the paper's own shape and small test shapes."""
+    if name == "cfg1":
+        return _homog("cfg1", 8, 100_000, 64, "f32", 256, ("fixed", 20), ("uniform",), seed_off=1)
+    if name == "cfg2":
+        return _homog("cfg2", 26, 1_000_000, 64, "f32", 2048, ("uniform", 1, 40), ("uniform",),
+                      seed_off=2)
+    if name == "cfg3":
+        return _homog("cfg3", 60, 4_000_000, 128, "f32", 4096, ("fixed", 80), ("uniform",),
+                      seed_off=3)
+    if name == "cfg4":
+        return _homog("cfg4", 60, 4_000_000, 128, "f32", 4096, ("uniform", 40, 120),
+                      ("zipf", 1.05), mode="mean", seed_off=4)
+    if name == "cfg5":
+        T = 100
+        return Workload(name="cfg5", T=T, rows=(2_000_000,) * T, D=256, dtype="f16", B=8192,
+                        pooling=("uniform", 1, 100),
+                        dists=(("uniform",),) * (T // 2) + (("zipf", 1.2),) * (T - T // 2),
+                        mode="sum", seed=0x5EED0005,
+                        note="tables 0-49 uniform, tables 50-99 Zipf(1.2)")
+    if name == "paper":  # Sec. 5 model: 250 tables x 500,000 x 128 fp32, BS 2048, pooling 150
+        return _homog("paper", 250, 500_000, 128, "f32", 2048, ("fixed", 150), ("uniform",),
+                      seed_off=6)
+    if name == "paper_one_item":
+        return _homog("paper_one_item", 250, 500_000, 128, "f32", 2048, ("fixed", 150),
+                      ("one_item",), seed_off=7)
+    # ---- small shapes for tests (the oracle finishes these in well under a second) ----
+    if name == "tiny":
+        return Workload(name="tiny", T=3, rows=(8, 5, 7), D=4, dtype="f32", B=4,
+                        pooling=("uniform", 0, 5), dists=(("uniform",),) * 3, seed=0x5EED0010)
+    if name == "small_f32_d64":   # 256-byte rows, ragged bags incl. empty, several chunks
+        return Workload(name="small_f32_d64", T=5, rows=(1000, 37, 4096, 1, 513), D=64,
+                        dtype="f32", B=67, pooling=("uniform", 0, 150),
+                        dists=(("uniform",), ("uniform",), ("zipf", 1.05), ("one_item",),
+                               ("uniform",)), seed=0x5EED0011)
+    if name == "small_f32_d128":  # 512-byte rows
+        return Workload(name="small_f32_d128", T=4, rows=(3000, 129, 2048, 77), D=128,
+                        dtype="f32", B=131, pooling=("uniform", 0, 200),
+                        dists=(("uniform",), ("zipf", 1.2), ("uniform",), ("uniform",)),
+                        seed=0x5EED0012)
+    if name == "small_f16_d256":  # 512-byte fp16 rows
+        return Workload(name="small_f16_d256", T=4, rows=(2000, 65, 1024, 300), D=256,
+                        dtype="f16", B=97, pooling=("uniform", 0, 130),
+                        dists=(("uniform",), ("uniform",), ("zipf", 1.2), ("uniform",)),
+                        seed=0x5EED0013)
+    raise KeyError(f"unknown workload {name!r}")
+
+
+def with_overrides(wl: Workload, **kw) -> Workload:
+    from dataclasses import replace
+    return replace(wl, **kw)
+
+
+# ----------------------------------------------------------------------------------------
+# lengths, offsets, indices, weights
+# ----------------------------------------------------------------------------------------
+_PURPOSE_LEN, _PURPOSE_IDX, _PURPOSE_PERM, _PURPOSE_W = 1, 2, 3, 4
+
+
+def _rng(seed: int, purpose: int, batch_id: int = 0, table: int = 0) -> np.random.Generator:
+    tag = (purpose << 56) | ((batch_id & 0xFFFFFF) << 32) | (table & 0xFFFFFFFF)
+    key = np.array([seed & 0xFFFFFFFFFFFFFFFF, tag], dtype=np.uint64)
+    return np.random.Generator(np.random.Philox(key=key))
+
+
+def make_lengths(wl: Workload, batch_id: int = 0) -> np.ndarray:
+    """Bag lengths in (t, b) order, int64 [T*B]."""
+    n = wl.num_bags
+    if wl.pooling[0] == "fixed":
+        return np.full(n, int(wl.pooling[1]), dtype=np.int64)
+    if wl.pooling[0] == "uniform":
+        lo, hi = int(wl.pooling[1]), int(wl.pooling[2])
+        return _rng(wl.seed, _PURPOSE_LEN, batch_id).integers(lo, hi + 1, size=n, dtype=np.int64)
+    raise ValueError(f"bad pooling spec {wl.pooling!r}")
+
+
+def lengths_to_offsets(lengths: np.ndarray) -> np.ndarray:
+    """CSR offsets with the final total included: int64 [len+1], offsets[0] = 0."""
+    off = np.zeros(len(lengths) + 1, dtype=np.int64)
+    np.cumsum(lengths, out=off[1:])
+    return off
+
+
+_zipf_cdf_cache: Dict[Tuple[int, float], np.ndarray] = {}
+
+
+def zipf_cdf(R: int, alpha: float) -> np.ndarray:
+    """Cumulative distribution of P(k) ~ k^-alpha over ranks k = 1..R (fp64)."""
+    key = (R, float(alpha))
+    if key not in _zipf_cdf_cache:
+        if len(_zipf_cdf_cache) > 4:
+            _zipf_cdf_cache.clear()
+        w = np.arange(1, R + 1, dtype=np.float64) ** (-float(alpha))
+        c = np.cumsum(w)
+        c /= c[-1]
+        _zipf_cdf_cache[key] = c
+    return _zipf_cdf_cache[key]
+
+
+def zipf_ranks(rng: np.random.Generator, R: int, alpha: float, n: int) -> np.ndarray:
+    """n independent 0-based ranks by inverse-CDF sampling."""
+    u = rng.random(n)
+    r = np.searchsorted(zipf_cdf(R, alpha), u, side="right")
+    return np.minimum(r, R - 1).astype(np.int64)
+
+
+def table_permutation(wl: Workload, t: int) -> np.ndarray:
+    """Seeded bijection rank -> row for table t (fixed across batches)."""
+    return _rng(wl.seed, _PURPOSE_PERM, 0, t).permutation(wl.rows[t]).astype(np.int64)
+
+
+def one_item_row(wl: Workload, t: int) -> int:
+    return int(_rng(wl.seed, _PURPOSE_PERM, 0, t).integers(0, wl.rows[t]))
+
+
+@dataclass
+class Batch:
+    offsets: np.ndarray                  # int64 [T*B+1]
+    indices: np.ndarray                  # int64 [NL], table-local row ids, bags in (t,b) order
+    weights: Optional[np.ndarray] = None  # float32 [NL]
+
+    @property
+    def num_lookups(self) -> int:
+        return int(self.offsets[-1])
+
+
+def make_batches(wl: Workload, n_batches: int = 1, first_batch: int = 0) -> List[Batch]:
+    """Generate `n_batches` independent batches (different lengths and indices, same tables).
+    Tables are the outer loop so each Zipf permutation is built once."""
+    ids = list(range(first_batch, first_batch + n_batches))
+    offs = [lengths_to_offsets(make_lengths(wl, k)) for k in ids]
+    idx = [np.empty(int(o[-1]), dtype=np.int64) for o in offs]
+    for t in range(wl.T):
+        R = wl.rows[t]
+        dist = wl.dists[t]
+        perm = table_permutation(wl, t) if dist[0] == "zipf" else None
+        for k, o, ix in zip(ids, offs, idx):
+            s, e = int(o[t * wl.B]), int(o[(t + 1) * wl.B])
+            n = e - s
+            rng = _rng(wl.seed, _PURPOSE_IDX, k, t)
+            if dist[0] == "uniform":
+                ix[s:e] = rng.integers(0, R, size=n, dtype=np.int64)
+            elif dist[0] == "zipf":
+                ix[s:e] = perm[zipf_ranks(rng, R, float(dist[1]), n)]
+            elif dist[0] == "one_item":
+                ix[s:e] = one_item_row(wl, t)
+            else:
+                raise ValueError(f"bad distribution {dist!r}")
+    out = []
+    for k, o, ix in zip(ids, offs, idx):
+        w = None
+        if wl.weighted:
+            w = _rng(wl.seed, _PURPOSE_W, k).uniform(-1.0, 1.0, size=len(ix)).astype(np.float32)
+        out.append(Batch(offsets=o, indices=ix, weights=w))
+    return out
+
+
+def host_arena(wl: Workload) -> np.ndarray:
+    """The whole table arena on the host, [sum R_t, D] (only for shapes that fit in RAM)."""
+    return table_values_range(wl.seed, 0, wl.total_rows, wl.D, wl.dtype, wl.kind)
+
+
+def compact_rows(wl: Workload, batch: Batch, bag_ids: Sequence[int]):
+    """For a subset of bags, build a small self-contained problem (one 'table' holding only the
+    rows those bags touch) so that a host-side checker can evaluate sampled bags of an arena
+    that does not fit in host memory.  Returns (arena_small, indices_small, offsets_small)
+    where bag i of the small problem equals bag bag_ids[i] of the full one."""
+    toff = wl.table_offsets()
+    segs, lens = [], []
+    for g in bag_ids:
+        t = int(g) // wl.B
+        s, e = int(batch.offsets[g]), int(batch.offsets[g + 1])
+        segs.append(batch.indices[s:e] + toff[t])
+        lens.append(e - s)
+    arena_rows = np.concatenate(segs) if segs else np.zeros(0, dtype=np.int64)
+    uniq, inv = np.unique(arena_rows, return_inverse=True)
+    small = table_values(wl.seed, uniq, wl.D, wl.dtype, wl.kind)
+    if len(uniq) == 0:
+        small = np.zeros((1, wl.D), dtype=small.dtype)
+    return small, inv.astype(np.int64), lengths_to_offsets(np.asarray(lens, dtype=np.int64))

@@ -1,0 +1,153 @@
+/*
+ * CPU oracle for the multi-table EmbeddingBag forward.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This is the plain definition of what the embedding stage computes, written out slowly and
+ * obviously: only tests, the smoke check and the benchmark's cpu_baseline leg may use it.  It
+ * shares no code, header, table or helper with the HIP library or with the input generator.
+ *
+ * What is computed (paper Sec. 3.1, Algorithm 1 and the per-thread description that follows
+ * it): for every table t and every sample b of the batch, the bag (t, b) owns the lookups
+ * indices[offsets[t*B+b] .. offsets[t*B+b+1]); each lookup names a row of table t; the bag's
+ * output is the element-wise sum of those rows (a "gather" then a "reduce"), one vector of
+ * length ED per (sample, table).  The output of table t is the [BS, ED] block at columns
+ * t*D .. t*D+D of the [B, out_ld] result.
+ *
+ * Readings taken where the paper is silent or garbled:
+ *   - Algorithm 1 prints the accumulator load/store inside the lookup loop; the accumulator is
+ *     taken to start at zero once per (sample, element) and to be stored once after the last
+ *     lookup, which is what "one [BS, ED] output per table" requires.
+ *   - "mean" appears only in the name of the kernel the paper studies: mean = sum / bag length,
+ *     and an empty bag gives 0.
+ *   - per-sample weights are not in the paper: out = sum_j w_j * row_j, sum mode only.
+ *   - summation order is not fixed by the paper: this oracle adds in index order, in fp64.
+ *
+ * Arithmetic: every table element is widened exactly (fp32 -> fp64, or IEEE half -> fp64) and
+ * accumulated in fp64.  Alongside each output element the oracle returns bound = sum_j |w_j *
+ * x_j| (divided by the bag length in mean mode), the scale of the rounding-error tolerance.
+ *
+ * Parity pins (tests/test_oracle_pins.py): exact rational brute force on tiny inputs, index
+ * histograms through identity tables, the one-item case, mean = sum / len, permutation and
+ * linearity invariants on integer tables, and agreement with a sparse-matrix product and with
+ * torch's CPU embedding_bag as second opinions.  The paper prints no output value of the
+ * operator, so beyond those pins the numbers rest on the definition above.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG (-1)
+#define ORACLE_ERR_OFFSETS (-2)
+#define ORACLE_ERR_INDEX (-3)
+
+/* IEEE 754 binary16 bit pattern -> double, exactly (subnormals, infinities, NaN included). */
+static double half_bits_to_double(uint16_t h) {
+  const int sign = (h >> 15) & 1;
+  const int expo = (h >> 10) & 0x1F;
+  const int frac = h & 0x3FF;
+  double v;
+  if (expo == 0)
+    v = ldexp((double)frac, -24); /* subnormal: frac * 2^-10 * 2^-14 */
+  else if (expo == 31)
+    v = frac ? NAN : INFINITY;
+  else
+    v = ldexp((double)(1024 + frac), expo - 25); /* (1 + frac/1024) * 2^(expo-15) */
+  return sign ? -v : v;
+}
+
+static double table_elem(const void* tables, int dtype, int64_t arena_row, int64_t D, int64_t d) {
+  if (dtype == 1) return half_bits_to_double(((const uint16_t*)tables)[arena_row * D + d]);
+  return (double)((const float*)tables)[arena_row * D + d];
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+void oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
+/*
+ * All pointers are HOST pointers.
+ *   T, B, D        tables, batch, embedding dimension
+ *   dtype          0 = fp32 tables, 1 = fp16 tables (raw half bit patterns)
+ *   mode           0 = sum, 1 = mean
+ *   tables         arena [sum_t R_t, D], row-major
+ *   table_offsets  [T+1] first arena row of each table (so R_t = table_offsets[t+1]-table_offsets[t])
+ *   indices        [NL] table-local row ids
+ *   offsets        [T*B+1] CSR over bags in (t, b) order
+ *   weights        [NL] or NULL (sum mode only)
+ *   out_ld         leading dimension of ref / bound in elements (>= T*D)
+ *   ref, bound     [B, out_ld] fp64 outputs; only columns [0, T*D) are written
+ * Returns ORACLE_OK or a negative code (bad argument, non-monotone offsets, index out of range).
+ */
+int oracle_emb_bag(int32_t T, int64_t B, int32_t D, int32_t dtype, int32_t mode,
+                   const void* tables, const int64_t* table_offsets, const int64_t* indices,
+                   const int64_t* offsets, const float* weights, int64_t out_ld, double* ref,
+                   double* bound) {
+  if (T < 1 || B < 0 || D < 1 || (dtype != 0 && dtype != 1) || (mode != 0 && mode != 1))
+    return ORACLE_ERR_ARG;
+  if (out_ld < (int64_t)T * D) return ORACLE_ERR_ARG;
+  if (weights && mode != 0) return ORACLE_ERR_ARG;
+  if (B == 0) return ORACLE_OK;
+  if (!tables || !table_offsets || !offsets || !ref || !bound) return ORACLE_ERR_ARG;
+
+  const int64_t nbags = (int64_t)T * B;
+  if (offsets[0] != 0) return ORACLE_ERR_OFFSETS;
+  for (int64_t g = 0; g < nbags; ++g)
+    if (offsets[g + 1] < offsets[g]) return ORACLE_ERR_OFFSETS;
+  if (offsets[nbags] > 0 && !indices) return ORACLE_ERR_ARG;
+
+  int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t g = 0; g < nbags; ++g) {
+    const int64_t t = g / B;
+    const int64_t b = g % B;
+    const int64_t R = table_offsets[t + 1] - table_offsets[t];
+    const int64_t s = offsets[g];
+    const int64_t e = offsets[g + 1];
+    int bad = 0;
+    for (int64_t j = s; j < e; ++j)
+      if (indices[j] < 0 || indices[j] >= R) bad = 1;
+    if (bad) {
+#pragma omp atomic write
+      status = ORACLE_ERR_INDEX;
+      continue;
+    }
+    for (int64_t d = 0; d < D; ++d) {
+      double acc = 0.0;
+      double mag = 0.0;
+      for (int64_t j = s; j < e; ++j) {
+        const double x = table_elem(tables, dtype, table_offsets[t] + indices[j], D, d);
+        const double w = weights ? (double)weights[j] : 1.0;
+        acc += w * x;
+        mag += fabs(w * x);
+      }
+      if (mode == 1) {
+        if (e > s) {
+          acc /= (double)(e - s);
+          mag /= (double)(e - s);
+        } else {
+          acc = 0.0;
+          mag = 0.0;
+        }
+      }
+      ref[b * out_ld + t * D + d] = acc;
+      bound[b * out_ld + t * D + d] = mag;
+    }
+  }
+  return status;
+}

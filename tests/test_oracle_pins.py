@@ -1,0 +1,340 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+The paper (Sec. 3.1, Algorithm 1) defines the embedding stage as a per-bag gather + sum of
+table rows; it prints no output value of the operator.  So the oracle is pinned by
+  * exact rational brute force on hand-sized inputs,
+  * closed forms (identity tables -> index histograms, one-item case, len 1, empty bags),
+  * invariants (mean = sum/len, permutation, linearity, weights),
+  * library special cases (sparse incidence matrix x table; torch's CPU embedding_bag),
+each chosen so that a dropped term, wrong index/offset, transposed operand or wrong table base
+fails at least one of them.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from inputgen import gen
+
+
+def _rand_problem(rng, T, rows, D, B, max_len, dtype=np.float32, integer=False):
+    toff = np.concatenate([[0], np.cumsum(rows)]).astype(np.int64)
+    if integer:
+        tables = rng.integers(-8, 8, size=(int(toff[-1]), D)).astype(dtype)
+    else:
+        tables = rng.normal(0, 0.1, size=(int(toff[-1]), D)).astype(dtype)
+    lengths = rng.integers(0, max_len + 1, size=T * B)
+    offsets = gen.lengths_to_offsets(lengths)
+    idx = np.empty(int(offsets[-1]), dtype=np.int64)
+    for t in range(T):
+        s, e = offsets[t * B], offsets[(t + 1) * B]
+        idx[s:e] = rng.integers(0, rows[t], size=e - s)
+    return tables, toff, idx, offsets
+
+
+def _brute_force_fraction(tables, toff, idx, offsets, B, mode, weights=None):
+    """Exact rational arithmetic, pure Python loops, written straight from the definition."""
+    T = len(toff) - 1
+    D = tables.shape[1]
+    out = [[Fraction(0)] * (T * D) for _ in range(B)]
+    mag = [[Fraction(0)] * (T * D) for _ in range(B)]
+    for t in range(T):
+        for b in range(B):
+            lo, hi = int(offsets[t * B + b]), int(offsets[t * B + b + 1])
+            for d in range(D):
+                a = Fraction(0)
+                m = Fraction(0)
+                for j in range(lo, hi):
+                    x = Fraction(float(tables[int(toff[t]) + int(idx[j]), d]))
+                    w = Fraction(float(weights[j])) if weights is not None else Fraction(1)
+                    a += w * x
+                    m += abs(w * x)
+                if mode == "mean":
+                    a = a / (hi - lo) if hi > lo else Fraction(0)
+                    m = m / (hi - lo) if hi > lo else Fraction(0)
+                out[b][t * D + d] = a
+                mag[b][t * D + d] = m
+    return out, mag
+
+
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_brute_force_exact_rational(oracle, mode, dtype):
+    rng = np.random.default_rng(11)
+    T, rows, D, B = 3, [8, 5, 7], 4, 4
+    tables, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 5, dtype)
+    ref, bound = oracle.emb_bag(tables, toff, idx, offsets, B, mode)
+    exact, mag = _brute_force_fraction(tables, toff, idx, offsets, B, mode)
+    for b in range(B):
+        for c in range(T * D):
+            # fp64 accumulation of <= 5 fp32-exact terms: error <= 5 ulp(fp64) of the magnitude
+            tol = 8 * 2.0 ** -53 * float(mag[b][c]) + 1e-300
+            assert abs(ref[b, c] - float(exact[b][c])) <= tol
+            assert abs(bound[b, c] - float(mag[b][c])) <= tol
+
+
+def test_brute_force_weighted(oracle):
+    rng = np.random.default_rng(12)
+    T, rows, D, B = 2, [6, 3], 4, 3
+    tables, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 4)
+    w = rng.uniform(-1, 1, size=len(idx)).astype(np.float32)
+    ref, bound = oracle.emb_bag(tables, toff, idx, offsets, B, "sum", weights=w)
+    exact, mag = _brute_force_fraction(tables, toff, idx, offsets, B, "sum", w)
+    for b in range(B):
+        for c in range(T * D):
+            tol = 16 * 2.0 ** -53 * float(mag[b][c]) + 1e-300
+            assert abs(ref[b, c] - float(exact[b][c])) <= tol
+            assert abs(bound[b, c] - float(mag[b][c])) <= tol
+
+
+def test_hand_worked_example(oracle):
+    """A case small enough to do on paper; values typed in, not computed."""
+    # table 0 has 3 rows, table 1 has 2 rows, D = 2
+    tables = np.array([[1, 2], [10, 20], [100, 200],      # table 0
+                       [-1, 5], [3, -7]], dtype=np.float32)  # table 1
+    toff = np.array([0, 3, 5], dtype=np.int64)
+    B = 2
+    # bags (t,b): (0,0)=[2,0,2]  (0,1)=[]  (1,0)=[1]  (1,1)=[0,1,1,0]
+    idx = np.array([2, 0, 2, 1, 0, 1, 1, 0], dtype=np.int64)
+    offsets = np.array([0, 3, 3, 4, 8], dtype=np.int64)
+    ref, bound = oracle.emb_bag(tables, toff, idx, offsets, B, "sum")
+    assert ref.tolist() == [[201.0, 402.0, 3.0, -7.0], [0.0, 0.0, 4.0, -4.0]]
+    assert bound.tolist() == [[201.0, 402.0, 3.0, 7.0], [0.0, 0.0, 8.0, 24.0]]
+    ref, bound = oracle.emb_bag(tables, toff, idx, offsets, B, "mean")
+    assert ref.tolist() == [[67.0, 134.0, 3.0, -7.0], [0.0, 0.0, 1.0, -1.0]]
+    assert bound.tolist() == [[67.0, 134.0, 3.0, 7.0], [0.0, 0.0, 2.0, 6.0]]
+    # out_ld wider than T*D: extra columns untouched (zero), layout is [b, t*D + d]
+    ref, _ = oracle.emb_bag(tables, toff, idx, offsets, B, "sum", out_ld=6)
+    assert ref.tolist() == [[201.0, 402.0, 3.0, -7.0, 0.0, 0.0], [0.0, 0.0, 4.0, -4.0, 0.0, 0.0]]
+
+
+def test_identity_tables_give_index_histograms(oracle):
+    """With table_t = I (R = D) the output row of bag (t,b) counts how often each index occurs."""
+    rng = np.random.default_rng(13)
+    T, D, B = 3, 16, 9
+    tables = np.concatenate([np.eye(D, dtype=np.float32)] * T)
+    toff = np.arange(T + 1, dtype=np.int64) * D
+    lengths = rng.integers(0, 40, size=T * B)
+    offsets = gen.lengths_to_offsets(lengths)
+    idx = rng.integers(0, D, size=int(offsets[-1]))
+    ref, bound = oracle.emb_bag(tables, toff, idx, offsets, B, "sum")
+    for t in range(T):
+        for b in range(B):
+            s, e = offsets[t * B + b], offsets[t * B + b + 1]
+            hist = np.bincount(idx[s:e], minlength=D).astype(np.float64)
+            assert np.array_equal(ref[b, t * D:(t + 1) * D], hist)
+            assert np.array_equal(bound[b, t * D:(t + 1) * D], hist)
+
+
+def test_table_base_is_respected(oracle):
+    """Tables holding a constant equal to their number: a wrong table base shows at once."""
+    T, D, B, R = 4, 8, 5, [3, 9, 2, 6]
+    toff = np.concatenate([[0], np.cumsum(R)]).astype(np.int64)
+    tables = np.concatenate([np.full((R[t], D), t + 1, dtype=np.float32) for t in range(T)])
+    rng = np.random.default_rng(14)
+    lengths = rng.integers(0, 7, size=T * B)
+    offsets = gen.lengths_to_offsets(lengths)
+    idx = np.concatenate([rng.integers(0, R[t], size=int(offsets[(t + 1) * B] - offsets[t * B]))
+                          for t in range(T)]).astype(np.int64)
+    ref, _ = oracle.emb_bag(tables, toff, idx, offsets, B, "sum")
+    for t in range(T):
+        for b in range(B):
+            assert np.all(ref[b, t * D:(t + 1) * D] == (t + 1) * lengths[t * B + b])
+
+
+def test_one_item_case(oracle):
+    """Paper Sec. 3.2 'one item': every index names the same row -> sum = len*row, mean = row."""
+    rng = np.random.default_rng(15)
+    R, D, B = 50, 12, 6
+    table = rng.normal(0, 0.1, size=(R, D)).astype(np.float32)
+    toff = np.array([0, R], dtype=np.int64)
+    lengths = np.array([1, 2, 4, 8, 16, 64])  # powers of two: len*row is exact in fp64
+    offsets = gen.lengths_to_offsets(lengths)
+    idx = np.full(int(offsets[-1]), 17, dtype=np.int64)
+    s, _ = oracle.emb_bag(table, toff, idx, offsets, B, "sum")
+    m, _ = oracle.emb_bag(table, toff, idx, offsets, B, "mean")
+    for b in range(B):
+        assert np.array_equal(s[b], table[17].astype(np.float64) * lengths[b])
+        assert np.array_equal(m[b], table[17].astype(np.float64))
+
+
+def test_mean_is_sum_over_len_and_edge_lengths(oracle):
+    rng = np.random.default_rng(16)
+    T, rows, D, B = 2, [40, 9], 8, 12
+    tables, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 30)
+    lengths = np.diff(offsets)
+    assert (lengths == 0).any() and (lengths > 1).any()
+    s, sb = oracle.emb_bag(tables, toff, idx, offsets, B, "sum")
+    m, mb = oracle.emb_bag(tables, toff, idx, offsets, B, "mean")
+    for t in range(T):
+        for b in range(B):
+            L = lengths[t * B + b]
+            sl = slice(t * D, (t + 1) * D)
+            if L == 0:
+                assert np.all(s[b, sl] == 0) and np.all(m[b, sl] == 0) and np.all(mb[b, sl] == 0)
+                assert not np.signbit(m[b, sl]).any()
+            else:
+                assert np.array_equal(m[b, sl], s[b, sl] / L)
+                assert np.array_equal(mb[b, sl], sb[b, sl] / L)
+
+
+def test_empty_and_len1_bags(oracle):
+    table = np.arange(12, dtype=np.float32).reshape(3, 4) - 5
+    toff = np.array([0, 3], dtype=np.int64)
+    offsets = np.array([0, 0, 1, 1, 2], dtype=np.int64)  # lengths 0,1,0,1
+    idx = np.array([2, 0], dtype=np.int64)
+    for mode in ("sum", "mean"):
+        r, b = oracle.emb_bag(table, toff, idx, offsets, 4, mode)
+        assert np.array_equal(r, np.array([[0] * 4, table[2], [0] * 4, table[0]], dtype=np.float64))
+        assert np.array_equal(b, np.abs(r))
+    # all bags empty, no indices at all
+    r, b = oracle.emb_bag(table, toff, np.zeros(0, np.int64), np.zeros(5, np.int64), 4, "sum")
+    assert not r.any() and not b.any()
+    # B = 0
+    r, b = oracle.emb_bag(table, toff, np.zeros(0, np.int64), np.zeros(1, np.int64), 0, "sum")
+    assert r.shape == (0, 4)
+
+
+def test_permutation_invariance(oracle):
+    rng = np.random.default_rng(17)
+    T, rows, D, B = 3, [20, 11, 64], 8, 10
+    for integer in (True, False):
+        tables, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 25, integer=integer)
+        r0, b0 = oracle.emb_bag(tables, toff, idx, offsets, B, "sum")
+        idx2 = idx.copy()
+        for g in range(T * B):
+            s, e = offsets[g], offsets[g + 1]
+            idx2[s:e] = rng.permutation(idx2[s:e])
+        r1, b1 = oracle.emb_bag(tables, toff, idx2, offsets, B, "sum")
+        if integer:
+            assert np.array_equal(r0, r1) and np.array_equal(b0, b1)
+        else:
+            assert np.all(np.abs(r0 - r1) <= 1e-14 * b0 + 1e-300)
+
+
+def test_weights(oracle):
+    rng = np.random.default_rng(18)
+    T, rows, D, B = 2, [30, 12], 8, 7
+    tables, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 9)
+    r0, b0 = oracle.emb_bag(tables, toff, idx, offsets, B, "sum")
+    r1, b1 = oracle.emb_bag(tables, toff, idx, offsets, B, "sum",
+                            weights=np.ones(len(idx), np.float32))
+    assert np.array_equal(r0, r1) and np.array_equal(b0, b1)
+    # a selector weight picks out one row of each non-empty bag
+    w = np.zeros(len(idx), np.float32)
+    pick = {}
+    for g in range(T * B):
+        s, e = offsets[g], offsets[g + 1]
+        if e > s:
+            j = int(rng.integers(s, e))
+            w[j] = 2.0
+            pick[g] = j
+    r2, _ = oracle.emb_bag(tables, toff, idx, offsets, B, "sum", weights=w)
+    for g, j in pick.items():
+        t, b = divmod(g, B)
+        assert np.array_equal(r2[b, t * D:(t + 1) * D],
+                              2.0 * tables[toff[t] + idx[j]].astype(np.float64))
+    with pytest.raises(ValueError):
+        oracle.emb_bag(tables, toff, idx, offsets, B, "mean", weights=w)
+
+
+def test_linearity_on_integer_tables(oracle):
+    rng = np.random.default_rng(19)
+    T, rows, D, B = 2, [15, 33], 8, 6
+    A, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 12, integer=True)
+    Bm = rng.integers(-8, 8, size=A.shape).astype(np.float32)
+    ra, _ = oracle.emb_bag(A, toff, idx, offsets, B, "sum")
+    rb, _ = oracle.emb_bag(Bm, toff, idx, offsets, B, "sum")
+    rab, _ = oracle.emb_bag(A + Bm, toff, idx, offsets, B, "sum")
+    assert np.array_equal(rab, ra + rb)
+
+
+def test_bound_is_sum_of_abs_terms(oracle):
+    rng = np.random.default_rng(20)
+    T, rows, D, B = 2, [15, 33], 8, 6
+    A, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 12)
+    w = rng.uniform(-1, 1, len(idx)).astype(np.float32)
+    _, bound = oracle.emb_bag(A, toff, idx, offsets, B, "sum", weights=w)
+    r_abs, _ = oracle.emb_bag(np.abs(A), toff, idx, offsets, B, "sum", weights=np.abs(w))
+    assert np.allclose(bound, r_abs, rtol=1e-15, atol=0)
+    assert np.all(bound >= 0)
+
+
+def test_second_opinion_sparse_matmul(oracle):
+    """Per table, sum pooling is (bag-incidence CSR matrix) x (table): a library SpMM."""
+    import scipy.sparse as sp
+    wl = gen.workload("small_f32_d64")
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    toff = wl.table_offsets()
+    ref, _ = oracle.emb_bag(arena, toff, batch.indices, batch.offsets, wl.B, "sum")
+    for t in range(wl.T):
+        o = batch.offsets[t * wl.B:(t + 1) * wl.B + 1]
+        ix = batch.indices[o[0]:o[-1]]
+        M = sp.csr_matrix((np.ones(len(ix)), ix, o - o[0]), shape=(wl.B, wl.rows[t]))
+        want = M @ arena[toff[t]:toff[t + 1]].astype(np.float64)
+        got = ref[:, t * wl.D:(t + 1) * wl.D]
+        assert np.allclose(got, want, rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("name,mode", [("small_f32_d128", "sum"), ("small_f32_d128", "mean"),
+                                       ("small_f16_d256", "sum")])
+def test_second_opinion_torch_cpu(oracle, name, mode):
+    import torch
+    import torch.nn.functional as F
+    wl = gen.workload(name)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    toff = wl.table_offsets()
+    ref, _ = oracle.emb_bag(arena, toff, batch.indices, batch.offsets, wl.B, mode)
+    for t in range(wl.T):
+        o = batch.offsets[t * wl.B:(t + 1) * wl.B + 1]
+        ix = torch.from_numpy(batch.indices[o[0]:o[-1]])
+        W = torch.from_numpy(arena[toff[t]:toff[t + 1]].astype(np.float64))
+        want = F.embedding_bag(ix, W, torch.from_numpy(o[:-1] - o[0]), mode=mode).numpy()
+        got = ref[:, t * wl.D:(t + 1) * wl.D]
+        assert np.allclose(got, want, rtol=1e-12, atol=1e-15)
+
+
+def test_half_widening_is_exact(oracle):
+    """Every finite half bit pattern, looked up alone, must come back as its exact value."""
+    bits = np.arange(0, 1 << 16, dtype=np.uint16)
+    halves = bits.view(np.float16)
+    finite = np.isfinite(halves)
+    table = halves.reshape(-1, 8)  # 8192 rows of 8
+    R = table.shape[0]
+    toff = np.array([0, R], dtype=np.int64)
+    idx = np.arange(R, dtype=np.int64)
+    offsets = np.arange(R + 1, dtype=np.int64)
+    ref, _ = oracle.emb_bag(table, toff, idx, offsets, R, "sum")
+    got = ref.reshape(-1)
+    want = halves.astype(np.float64)
+    assert np.array_equal(got[finite], want[finite])
+    assert np.all(np.isnan(got[np.isnan(halves)]))
+    assert np.array_equal(got[np.isinf(halves)], want[np.isinf(halves)])
+
+
+def test_rejects_bad_inputs(oracle):
+    table = np.ones((4, 4), np.float32)
+    toff = np.array([0, 4], dtype=np.int64)
+    with pytest.raises(ValueError, match="index out of range"):
+        oracle.emb_bag(table, toff, np.array([4], np.int64), np.array([0, 1], np.int64), 1)
+    with pytest.raises(ValueError, match="index out of range"):
+        oracle.emb_bag(table, toff, np.array([-1], np.int64), np.array([0, 1], np.int64), 1)
+    with pytest.raises(ValueError, match="offsets"):
+        oracle.emb_bag(table, toff, np.array([0, 1], np.int64), np.array([0, 2, 1, 2], np.int64), 3)
+
+
+def test_thread_count_does_not_change_result(oracle):
+    wl = gen.workload("small_f32_d64")
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    n = oracle.num_threads()
+    try:
+        oracle.set_num_threads(1)
+        r1, b1 = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
+        oracle.set_num_threads(max(2, n))
+        r2, b2 = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
+    finally:
+        oracle.set_num_threads(n)
+    assert np.array_equal(r1, r2) and np.array_equal(b1, b2)
