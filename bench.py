@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Benchmark of the embedding stage (multi-table EmbeddingBag forward) on one MI355X.
+
+One "step" is one pass of the whole hot path - one `emb_bag_forward` call over one batch of
+synthetic input (all tables, all bags) - with every input already resident in HBM.  Timed steps
+rotate through several pre-generated index batches so that no step re-reads the rows the previous
+step left in the caches.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+DESCRIPTIONS = {
+    "cfg1": "8 fp32 tables x 100,000 rows x dim 64, batch 256, pooling 20 fixed, uniform indices, sum",
+    "cfg2": "26 fp32 tables x 1,000,000 rows x dim 64, batch 2048, pooling U[1,40], uniform indices, sum",
+    "cfg3": "60 fp32 tables x 4,000,000 rows x dim 128 (122.9 GB), batch 4096, pooling 80 fixed, "
+            "uniform indices, sum",
+    "cfg4": "60 fp32 tables x 4,000,000 rows x dim 128, batch 4096, pooling U[40,120], "
+            "Zipf(1.05) + row permutation, mean",
+    "cfg5": "100 fp16 tables x 2,000,000 rows x dim 256 (fp32 accumulate), batch 8192, pooling "
+            "U[1,100], tables 0-49 uniform / 50-99 Zipf(1.2), sum",
+    "paper": "250 fp32 tables x 500,000 rows x dim 128, batch 2048, pooling 150 fixed, uniform "
+             "indices, sum (the paper's model, random dataset)",
+    "paper_one_item": "250 fp32 tables x 500,000 x dim 128, batch 2048, pooling 150, one item, sum",
+}
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary
+    for this workload has been committed under profiles/."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if "=" in line and not line.lstrip().startswith("#"):
+            k, v = line.split("=", 1)
+            try:
+                vals[k.strip()] = float(v.split()[0])
+            except (ValueError, IndexError):
+                pass
+    if "hbm_bytes_per_launch" in vals:
+        return vals["hbm_bytes_per_launch"]
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3", choices=sorted(DESCRIPTIONS))
+    ap.add_argument("--batches", type=int, default=4, help="distinct index batches to rotate")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--check-bags", type=int, default=256, help="bags spot-checked vs the oracle")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="emb_bag_set_tuning override, e.g. --tune depth=8")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2410_22249_amd as emb
+    from inputgen import gen
+    from paper_2410_22249_amd import metrics
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    for kv in args.tune:
+        k, v = kv.split("=")
+        emb.emb_bag_set_tuning(k, int(v))
+
+    wl = gen.workload(args.workload)
+    stream = torch.cuda.Stream()           # default priority; the library launches on it
+    sh = stream.cuda_stream
+
+    # ---- inputs, resident in HBM before anything is timed -------------------------------
+    t0 = time.time()
+    tdtype = torch.float16 if wl.dtype == "f16" else torch.float32
+    arena = torch.empty((wl.total_rows, wl.D), dtype=tdtype, device=dev)
+    with torch.cuda.stream(stream):
+        gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed,
+                              wl.kind, sh)
+    log(f"{wl.name}: arena {wl.table_bytes / 1e9:.2f} GB allocated, fill enqueued")
+    batches = gen.make_batches(wl, args.batches)
+    log(f"{len(batches)} index batches generated in {time.time() - t0:.1f} s "
+        f"({batches[0].num_lookups} lookups in batch 0)")
+    toff = torch.from_numpy(wl.table_offsets()).to(dev)
+    dbatches = []
+    for b in batches:
+        dbatches.append((torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev),
+                         None if b.weights is None else torch.from_numpy(b.weights).to(dev)))
+    out = torch.empty((wl.B, wl.T * wl.D), dtype=torch.float32, device=dev)
+    descs = [emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32,
+                           emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, b.num_lookups, 0,
+                           max(wl.rows)) for b in batches]
+    torch.cuda.synchronize()
+
+    def step(i: int) -> None:
+        k = i % len(dbatches)
+        idx, off, w = dbatches[k]
+        emb.emb_bag_forward(descs[k], arena, toff, idx, off, w, out, stream)
+
+    # a plain copy of known size on the same stream: the calibration kernel for HBM counters
+    cal_bytes = 1 << 30
+    cal_src = torch.empty(cal_bytes, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty(cal_bytes, dtype=torch.uint8, device=dev)
+    cal_src.zero_()
+    torch.cuda.synchronize()
+    gen.copy_bytes_device(cal_dst.data_ptr(), cal_src.data_ptr(), cal_bytes, sh)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
+    # ---- warm-up, then the timed region --------------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record(stream)
+        step(args.warmup + i)
+        ev[i][1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    kern_ms = [a.elapsed_time(b) for a, b in ev]
+    lookups_timed = sum(batches[(args.warmup + i) % len(batches)].num_lookups
+                        for i in range(args.steps))
+    avg_lookups = lookups_timed / args.steps
+    avg_kern_s = float(np.mean(kern_ms)) / 1e3
+    lookups_per_s = lookups_timed / wall
+    gathered = metrics.gathered_bytes(avg_lookups, wl.D, wl.elem_bytes)
+    algo = metrics.algorithmic_bytes(avg_lookups, wl.T, wl.B, wl.D, wl.elem_bytes, wl.weighted)
+    achieved = algo / avg_kern_s / 1e9
+    log(f"wall {wall * 1e3 / args.steps:.3f} ms/step, kernel avg {avg_kern_s * 1e3:.3f} ms "
+        f"(min {min(kern_ms):.3f}, max {max(kern_ms):.3f}); gathered "
+        f"{gathered / avg_kern_s / 1e9:.1f} GB/s, algorithmic {achieved:.1f} GB/s")
+
+    # ---- parity spot check of the launch configuration that was just timed --------------
+    parity = None
+    cpu_baseline = None
+    if args.check_bags > 0 or not args.no_cpu_baseline:
+        from oracle import emb_bag_oracle
+    if args.check_bags > 0:
+        k = (args.warmup + args.steps - 1) % len(batches)
+        rng = np.random.default_rng(12345)
+        nb = wl.num_bags
+        bags = np.unique(np.concatenate([rng.integers(0, nb, size=args.check_bags),
+                                         [0, wl.B - 1, nb - wl.B, nb - 1]]))
+        small, ix, off = gen.compact_rows(wl, batches[k], bags)
+        ref, bound = emb_bag_oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, off,
+                                            len(bags), wl.mode)
+        got_all = out.view(wl.B, wl.T, wl.D)
+        tb = torch.from_numpy(np.stack([bags % wl.B, bags // wl.B], 1)).to(dev)
+        got = got_all[tb[:, 0], tb[:, 1]].cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref)
+        ok = err <= 1e-5 * bound
+        if wl.dtype == "f16":
+            ok |= err <= 1e-3 * np.abs(ref)
+        nz = bound > 0
+        parity = {"bags_checked": int(len(bags)), "ok": bool(ok.all()),
+                  "max_err_over_bound": float(np.max(err[nz] / bound[nz])) if nz.any() else 0.0}
+        log(f"parity spot check: {parity}")
+        if not parity["ok"]:
+            print("bench.py: parity spot check FAILED", file=sys.stderr)
+            return 1
+
+    # ---- the oracle timed on this machine's host cores (a reported baseline, not the target) ---
+    if not args.no_cpu_baseline:
+        per_table = wl.rows[0] * wl.row_bytes
+        tsub = max(1, min(wl.T, int(8e9 // per_table)))      # <= 8 GB of tables on the host
+        toff_np = wl.table_offsets()
+        host = arena[: int(toff_np[tsub])].cpu().numpy()
+        b0 = batches[0]
+        e = int(b0.offsets[tsub * wl.B])
+        sub_off = b0.offsets[: tsub * wl.B + 1].copy()
+        sub_idx = b0.indices[:e]
+        n_sub = int(sub_off[-1])
+        emb_bag_oracle.emb_bag(host, toff_np[: tsub + 1], sub_idx, sub_off, wl.B, wl.mode)  # warm
+        reps, t_cpu = 0, 0.0
+        while t_cpu < args.cpu_seconds and reps < 1000:
+            t1 = time.perf_counter()
+            emb_bag_oracle.emb_bag(host, toff_np[: tsub + 1], sub_idx, sub_off, wl.B, wl.mode)
+            t_cpu += time.perf_counter() - t1
+            reps += 1
+        cpu_baseline = {"value": n_sub * reps / t_cpu, "unit": "lookups/s",
+                        "cores": emb_bag_oracle.num_threads(), "kind": "oracle",
+                        "sample": f"first {tsub} of {wl.T} tables, all {wl.B} bags each "
+                                  f"({n_sub} lookups), {reps} passes in {t_cpu:.1f} s, "
+                                  f"tables copied to host RAM",
+                        "gathered_GBps": n_sub * wl.row_bytes * reps / t_cpu / 1e9}
+        log(f"cpu baseline: {cpu_baseline}")
+        del host
+
+    traffic = read_traffic(wl.name)
+    result = {
+        "metric": "embedding lookups/sec and effective gathered HBM GB/s (% of peak), 1 MI355X",
+        "value": lookups_per_s,
+        "unit": "lookups/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {DESCRIPTIONS[wl.name]}",
+                   "tables": wl.T, "rows_per_table": wl.rows[0], "dim": wl.D,
+                   "table_dtype": wl.dtype, "batch": wl.B, "mode": wl.mode,
+                   "lookups_per_step": avg_lookups, "index_batches_rotated": len(batches),
+                   "tuning": {k: emb.emb_bag_get_tuning(k) for k in
+                              ("depth", "addressing", "blocks_per_cu", "xcd_remap", "kernel")}},
+        "gathered_GBps": gathered * args.steps / wall / 1e9,
+        "gathered_frac_of_hbm_peak": gathered * args.steps / wall / 1e9 / metrics.HBM_PEAK_GBPS,
+        "kernel_ms": {"avg": avg_kern_s * 1e3, "min": float(min(kern_ms)),
+                      "median": float(np.median(kern_ms)), "max": float(max(kern_ms))},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": metrics.HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / metrics.HBM_PEAK_GBPS,
+                     "traffic": traffic,
+                     "algorithmic_bytes_per_launch": algo,
+                     "gathered_bytes_per_launch": gathered},
+        "cpu_baseline": cpu_baseline,
+        "parity": parity,
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

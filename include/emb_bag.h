@@ -1,0 +1,141 @@
+/*
+ * emb_bag.h - C ABI of the MI355X (gfx950) multi-table EmbeddingBag forward.
+ *
+ * The operation is the embedding stage of DLRM inference as the paper states it (Sec. 2.1 and
+ * Sec. 3.1, Algorithm 1): for every embedding table t and every sample b of a batch, the bag
+ * (t, b) names "lookups per sample" rows of table t through an offsets array and an indices
+ * array (the offsets -> indices -> table pointer chase of Sec. 3.1); the rows are gathered and
+ * reduced element-wise into one vector of length ED, and table t's [BS, ED] result occupies
+ * columns [t*D, t*D+D) of the output.  The paper launches one kernel per table, serially; this
+ * library processes all tables of the batch in one call.
+ *
+ * Conventions
+ *   - Pointers marked DEVICE are device (HBM) addresses valid on the current HIP device;
+ *     pointers marked HOST are ordinary host addresses.  The library allocates nothing, frees
+ *     nothing and keeps no pointer after a call returns.
+ *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and never synchronise.
+ *   - Every function returns an int status: EMB_OK (0) or a negative EMB_ERR_* code.  Nothing is
+ *     thrown, printed or written to errno.
+ *   - Results are deterministic: same inputs and same tuning give bit-identical output (fixed
+ *     reduction order, no atomics in the forward path).
+ */
+#ifndef EMB_BAG_H_
+#define EMB_BAG_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* table element types */
+#define EMB_F32 0 /* IEEE binary32 rows */
+#define EMB_F16 1 /* IEEE binary16 rows, widened exactly and accumulated in fp32 */
+
+/* pooling modes (the two modes of the sum/mean kernel the paper studies, Sec. 3.1) */
+#define EMB_SUM 0
+#define EMB_MEAN 1 /* sum divided by the bag length; an empty bag gives 0 */
+
+/* status codes */
+#define EMB_OK 0
+#define EMB_ERR_NULL_PTR (-1)    /* a required pointer is NULL */
+#define EMB_ERR_BAD_DIM (-2)     /* dim <= 0, row not a multiple of 16 bytes, bad out_ld, ... */
+#define EMB_ERR_BAD_DTYPE (-3)   /* table_dtype is neither EMB_F32 nor EMB_F16 */
+#define EMB_ERR_BAD_MODE (-4)    /* mode is neither EMB_SUM nor EMB_MEAN */
+#define EMB_ERR_UNSUPPORTED (-5) /* per-sample weights together with EMB_MEAN */
+#define EMB_ERR_LAUNCH (-6)      /* the HIP runtime refused the launch */
+#define EMB_ERR_BAD_SIZE (-7)    /* negative count, or a size beyond the supported range */
+#define EMB_ERR_ALIGNMENT (-8)   /* tables / out not 16-byte aligned */
+#define EMB_ERR_BAD_TUNING (-9)  /* unknown tuning key or value out of range */
+
+/*
+ * Shape of one call (HOST struct, read during the call only).
+ *
+ *   T = num_tables, B = batch, D = dim.  Row size in bytes = D * sizeof(element) must be a
+ *   multiple of 16 and at most 65536.  Table t holds R_t = table_offsets[t+1] - table_offsets[t]
+ *   rows, stored contiguously in one arena starting at arena row table_offsets[t]; D and the
+ *   element type are the same for every table (the paper's tables are homogeneous, Sec. 5).
+ */
+typedef struct emb_bag_desc {
+  int32_t num_tables;     /* T >= 1 */
+  int32_t dim;            /* D >= 1 */
+  int32_t table_dtype;    /* EMB_F32 or EMB_F16 */
+  int32_t mode;           /* EMB_SUM or EMB_MEAN */
+  int64_t batch;          /* B >= 0; B == 0 is a no-op that returns EMB_OK */
+  int64_t num_lookups;    /* NL = offsets[T*B]: entries in indices (and in per_sample_weights) */
+  int64_t out_ld;         /* leading dimension of out, in floats; 0 means T*D; must be >= T*D
+                             and a multiple of 4 */
+  int64_t max_table_rows; /* an upper bound on max_t R_t, or 0 if unknown.  A bound that keeps
+                             max_table_rows * row_bytes below 3.5 GiB lets the library use
+                             32-bit buffer addressing; rows at or beyond the bound then read as
+                             zero.  0 selects 64-bit addressing. */
+} emb_bag_desc;
+
+/*
+ * emb_bag_forward - pooled lookup of all T*B bags (paper Sec. 3.1, Algorithm 1).
+ *
+ *   out[b*out_ld + t*D + d] = sum over j in [offsets[t*B+b], offsets[t*B+b+1]) of
+ *                               w_j * table_t[indices[j]][d]            (w_j = 1 without weights)
+ *   and that sum divided by the bag length in EMB_MEAN mode (0 for an empty bag).
+ *   Accumulation is in fp32; fp16 rows are widened exactly first.
+ *
+ *   desc                HOST    shape, see above
+ *   tables              DEVICE  arena [sum_t R_t, D] row-major, 16-byte aligned, f32 or f16
+ *   table_offsets       DEVICE  int64 [T+1], first arena row of each table, non-decreasing
+ *   indices             DEVICE  int64 [NL], table-local row ids, bags stored in (t, b) order
+ *   offsets             DEVICE  int64 [T*B+1], CSR over bags: offsets[0] = 0, offsets[T*B] = NL
+ *   per_sample_weights  DEVICE  float [NL] or NULL; only with EMB_SUM
+ *   out                 DEVICE  float [B, out_ld], 16-byte aligned; columns [0, T*D) of every
+ *                               row are overwritten (empty bags with +0.0f); no pre-zeroing
+ *   stream              hipStream_t as void*; NULL = default stream
+ *
+ * Data-dependent errors cannot be reported by an asynchronous call; instead they are made
+ * harmless: bag bounds are clamped to [0, NL] (a decreasing pair gives an empty bag) and a
+ * lookup whose index is outside [0, R_t) contributes zero.  Use emb_bag_validate to count them.
+ * Host-visible argument errors return a negative code and enqueue nothing.
+ */
+int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t* table_offsets,
+                    const int64_t* indices, const int64_t* offsets,
+                    const float* per_sample_weights, float* out, void* stream);
+
+/*
+ * emb_bag_validate - count the data-dependent defects emb_bag_forward neutralises.
+ *
+ *   Adds to *num_bad (DEVICE, one int64 that the caller has zeroed, on the same stream) one for
+ *   every bag whose bounds are decreasing or outside [0, NL], one if offsets[0] != 0 or
+ *   offsets[T*B] != NL, and one for every lookup whose index is outside [0, R_t).
+ *   Same pointer meanings as emb_bag_forward; asynchronous on `stream`.
+ */
+int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
+                     const int64_t* indices, const int64_t* offsets, int64_t* num_bad,
+                     void* stream);
+
+/*
+ * emb_bag_set_tuning / emb_bag_get_tuning - process-wide launch tuning (the occupancy x
+ * prefetch-depth search of paper Sec. 3.3, Sec. 4.2 and the recipe of Sec. 7, made a runtime
+ * knob).  Keys (HOST strings):
+ *   "depth"         row loads a wavefront keeps in flight: 1, 2, 4, 8 or 16; 0 = automatic
+ *   "addressing"    0 = automatic, 1 = force 64-bit global addressing, 2 = force buffer
+ *                   addressing where the sizes allow it
+ *   "blocks_per_cu" cap on resident 256-thread workgroups per compute unit, 1..8; 0 = no cap
+ *   "xcd_remap"     1 = deal consecutive bags to one XCD at a time (keeps one table's hot rows
+ *                   in one L2, the stand-in for the L2 pinning of Sec. 4.3); 0 = natural order;
+ *                   -1 = automatic
+ *   "kernel"        0 = automatic, 1 = one bag per wavefront, 2 = persistent wavefronts that
+ *                   prefetch the next bag's indices
+ * Not thread-safe against concurrent emb_bag_forward calls.
+ */
+int emb_bag_set_tuning(const char* key, int64_t value);
+int emb_bag_get_tuning(const char* key, int64_t* value);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char* emb_bag_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int emb_bag_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EMB_BAG_H_ */

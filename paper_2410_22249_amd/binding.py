@@ -1,0 +1,128 @@
+"""Thin ctypes binding over libembbag.so: argument marshalling only.
+
+Every step of the embedding-bag forward runs in the HIP kernels behind the C ABI declared in
+`include/emb_bag.h`; torch is used here for device memory and streams only.  There is no CPU
+fallback: if the shared library has not been built, importing fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # imported before the library so that the HIP runtime torch ships is the one bound
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libembbag.so")
+
+EMB_F32, EMB_F16 = 0, 1
+EMB_SUM, EMB_MEAN = 0, 1
+EMB_OK = 0
+
+EXPORTS = ("emb_bag_forward", "emb_bag_validate", "emb_bag_set_tuning", "emb_bag_get_tuning",
+           "emb_bag_status_string", "emb_bag_version")
+
+
+class emb_bag_desc(ctypes.Structure):
+    _fields_ = [("num_tables", ctypes.c_int32), ("dim", ctypes.c_int32),
+                ("table_dtype", ctypes.c_int32), ("mode", ctypes.c_int32),
+                ("batch", ctypes.c_int64), ("num_lookups", ctypes.c_int64),
+                ("out_ld", ctypes.c_int64), ("max_table_rows", ctypes.c_int64)]
+
+
+class EmbBagError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {emb_bag_status_string(status)} (status {status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -c 'import "
+                          f"__graft_entry__ as g; g.build()'` (there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    P = ctypes.c_void_p
+    lib.emb_bag_forward.restype = ctypes.c_int
+    lib.emb_bag_forward.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, P, P, P, P, P]
+    lib.emb_bag_validate.restype = ctypes.c_int
+    lib.emb_bag_validate.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, P, P, P]
+    lib.emb_bag_set_tuning.restype = ctypes.c_int
+    lib.emb_bag_set_tuning.argtypes = [ctypes.c_char_p, ctypes.c_int64]
+    lib.emb_bag_get_tuning.restype = ctypes.c_int
+    lib.emb_bag_get_tuning.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64)]
+    lib.emb_bag_status_string.restype = ctypes.c_char_p
+    lib.emb_bag_status_string.argtypes = [ctypes.c_int]
+    lib.emb_bag_version.restype = ctypes.c_int
+    lib.emb_bag_version.argtypes = []
+    return lib
+
+
+_lib = _load()
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library (for callers that want the raw entry points)."""
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def make_desc(num_tables: int, batch: int, dim: int, table_dtype: int, mode: int,
+              num_lookups: int, out_ld: int = 0, max_table_rows: int = 0) -> emb_bag_desc:
+    return emb_bag_desc(num_tables=num_tables, dim=dim, table_dtype=table_dtype, mode=mode,
+                        batch=batch, num_lookups=num_lookups, out_ld=out_ld,
+                        max_table_rows=max_table_rows)
+
+
+def emb_bag_forward(desc: emb_bag_desc, tables: torch.Tensor, table_offsets: torch.Tensor,
+                    indices: torch.Tensor, offsets: torch.Tensor,
+                    per_sample_weights: Optional[torch.Tensor], out: torch.Tensor,
+                    stream=None) -> None:
+    """Enqueue the pooled lookup (see `emb_bag_forward` in include/emb_bag.h).  All tensors are
+    device tensors owned by the caller; `out` is written in place, asynchronously."""
+    rc = _lib.emb_bag_forward(ctypes.byref(desc), _ptr(tables), _ptr(table_offsets),
+                              _ptr(indices), _ptr(offsets), _ptr(per_sample_weights), _ptr(out),
+                              _stream_handle(stream))
+    if rc != EMB_OK:
+        raise EmbBagError(rc, "emb_bag_forward")
+
+
+def emb_bag_validate(desc: emb_bag_desc, table_offsets: torch.Tensor, indices: torch.Tensor,
+                     offsets: torch.Tensor, num_bad: torch.Tensor, stream=None) -> None:
+    """Enqueue the defect count into `num_bad` (device int64[1], zeroed by the caller)."""
+    rc = _lib.emb_bag_validate(ctypes.byref(desc), _ptr(table_offsets), _ptr(indices),
+                               _ptr(offsets), _ptr(num_bad), _stream_handle(stream))
+    if rc != EMB_OK:
+        raise EmbBagError(rc, "emb_bag_validate")
+
+
+def emb_bag_set_tuning(key: str, value: int) -> None:
+    rc = _lib.emb_bag_set_tuning(key.encode(), int(value))
+    if rc != EMB_OK:
+        raise EmbBagError(rc, f"emb_bag_set_tuning({key!r}, {value})")
+
+
+def emb_bag_get_tuning(key: str) -> int:
+    v = ctypes.c_int64(0)
+    rc = _lib.emb_bag_get_tuning(key.encode(), ctypes.byref(v))
+    if rc != EMB_OK:
+        raise EmbBagError(rc, f"emb_bag_get_tuning({key!r})")
+    return int(v.value)
+
+
+def emb_bag_status_string(status: int) -> str:
+    return _lib.emb_bag_status_string(int(status)).decode()
+
+
+def emb_bag_version() -> int:
+    return int(_lib.emb_bag_version())

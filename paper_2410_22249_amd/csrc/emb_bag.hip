@@ -1,0 +1,484 @@
+// Multi-table EmbeddingBag forward for MI355X (gfx950, CDNA4): kernels + C ABI.
+//
+// What is computed is the embedding stage of the paper (Sec. 3.1, Algorithm 1): per bag (t, b)
+// follow offsets -> indices -> table rows, add the rows, store one vector of length D.
+//
+// How it is mapped to the machine (this is not the paper's A100 kernel, which gives one CUDA
+// thread to one output element and walks the bag with dependent loads, Sec. 3.1):
+//   * one 64-lane wavefront owns one bag (or one 1-KiB column slab of it when rows are longer
+//     than 1 KiB); all tables of the batch share one launch;
+//   * a row is read as 16-byte lane segments, so one load instruction of the wavefront moves
+//     1 KiB: G = 64/LPR different rows of the same bag at once, LPR lanes per row
+//     (512-byte rows: 2 rows per instruction, 256-byte rows: 4);
+//   * the bag's indices are contiguous: the wavefront fetches up to 64 of them with one
+//     coalesced load (lane i holds lookup i), turns them into row byte offsets once, and hands
+//     offset j to the lanes that need it with a cross-lane permute - no dependent index load
+//     in front of every row load as in the paper's base kernel;
+//   * DEPTH row loads are issued back to back before the first is consumed (the register
+//     prefetch of Sec. 4.2, with the distance as a tuning knob, Sec. 7 step vi), and the many
+//     resident wavefronts per SIMD (the kernels need few VGPRs) supply the rest of the
+//     memory-level parallelism (the multithreading fix of Sec. 3.3);
+//   * rows are addressed through a per-table buffer resource with 32-bit offsets when the table
+//     is below 3.5 GiB: the hardware range check turns an invalid row into zeros instead of a
+//     fault, and address arithmetic stays 32-bit.  Larger tables use 64-bit global addressing
+//     with an explicit check;
+//   * partial sums of the G row groups are combined with a fixed xor butterfly (deterministic),
+//     the mean is one division per element per bag, and the result leaves with 16-byte
+//     non-temporal stores so that it does not displace table rows in L2 / MALL.
+// No MFMA: this is a gather-reduce, not a contraction; the bound is HBM bandwidth.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "../../include/emb_bag.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWaveSize = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWaveSize * kWavesPerBlock;
+constexpr int kSlabBytes = 1024;                   // bytes of one row a wavefront covers per pass
+constexpr uint32_t kBufSentinel = 0xF0000000u;     // offset that is out of range for any table
+constexpr uint64_t kBufMaxBytes = 0xE0000000ull;   // largest table addressed through a buffer
+constexpr uint32_t kBufWord3 = 0x00020000u;        // gfx9 buffer resource: 32-bit data format
+
+struct KParams {
+  int64_t num_lookups;   // NL
+  int64_t out_ld;        // floats
+  int64_t max_rows;      // clamp on R_t in buffer mode (host guarantees max_rows*row_bytes fits)
+  uint32_t B;            // bags per table
+  uint32_t num_work;     // T*B*slabs
+  uint32_t slabs;        // ceil(row_bytes / 1024)
+  uint32_t row_bytes;
+  uint32_t D;
+  uint32_t mean;         // 1 = divide by bag length
+  uint32_t xcd_chunk;    // 0 = natural block order, else blocks per XCD (grid = 8 * xcd_chunk)
+};
+
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
+  const uint32_t lo = (uint32_t)__shfl((int)(uint32_t)(uint64_t)v, src);
+  const uint32_t hi = (uint32_t)__shfl((int)(uint32_t)((uint64_t)v >> 32), src);
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// acc += w * (one 16-byte segment of a row), for fp32 rows (4 elements) or fp16 rows (8).
+template <bool F16, bool WEIGHTED>
+__device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w) {
+  if constexpr (F16) {
+    const uint32_t u[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+      const h2 h = __builtin_bit_cast(h2, u[i]);
+      const float lo = (float)h.x;
+      const float hi = (float)h.y;
+      if constexpr (WEIGHTED) {
+        acc[2 * i] = __builtin_fmaf(w, lo, acc[2 * i]);
+        acc[2 * i + 1] = __builtin_fmaf(w, hi, acc[2 * i + 1]);
+      } else {
+        acc[2 * i] += lo;
+        acc[2 * i + 1] += hi;
+      }
+    }
+  } else {
+    const float x[4] = {as_float(r.x), as_float(r.y), as_float(r.z), as_float(r.w)};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (WEIGHTED)
+        acc[i] = __builtin_fmaf(w, x[i], acc[i]);
+      else
+        acc[i] += x[i];
+    }
+  }
+}
+
+// One wavefront per (bag, column slab).  LPR = lanes per row (power of two, 4..64).
+template <int LPR, bool F16, int DEPTH, bool WEIGHTED, bool BUF>
+__global__ void __launch_bounds__(kBlock)
+emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
+                    const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
+                    const float* __restrict__ weights, float* __restrict__ out, KParams p) {
+  constexpr int G = kWaveSize / LPR;  // rows of the bag served by one load instruction
+  constexpr int NACC = F16 ? 8 : 4;   // fp32 accumulators per lane
+
+  const int lane = threadIdx.x & (kWaveSize - 1);
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint32_t blk = blockIdx.x;
+  if (p.xcd_chunk) blk = (blk & 7u) * p.xcd_chunk + (blk >> 3);  // consecutive bags -> one XCD
+  const uint64_t work64 = (uint64_t)blk * kWavesPerBlock + wave;
+  if (work64 >= p.num_work) return;
+  const uint32_t work = (uint32_t)work64;
+
+  uint32_t bag = work, slab = 0;
+  if (p.slabs > 1) {
+    bag = work / p.slabs;
+    slab = work - bag * p.slabs;
+  }
+  const uint32_t t = bag / p.B;
+  const uint32_t b = bag - t * p.B;
+
+  // bag bounds, clamped so that no index read can leave [0, NL)
+  int64_t s = uniform64(offsets[bag]);
+  int64_t e = uniform64(offsets[bag + 1]);
+  s = s < 0 ? 0 : (s > p.num_lookups ? p.num_lookups : s);
+  e = e < s ? s : (e > p.num_lookups ? p.num_lookups : e);
+
+  const int64_t row0 = uniform64(table_offsets[t]);
+  int64_t R = uniform64(table_offsets[t + 1]) - row0;
+  if (R < 0) R = 0;
+  if (BUF && R > p.max_rows) R = p.max_rows;
+
+  const int g = lane / LPR;
+  const uint32_t col = slab * kSlabBytes + (uint32_t)(lane & (LPR - 1)) * 16u;
+  const bool lane_ok = col < p.row_bytes;
+
+  const char* tbase = tables + row0 * (int64_t)p.row_bytes;
+  __amdgpu_buffer_rsrc_t rsrc;
+  if constexpr (BUF)
+    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(tbase), 0,
+                                             (uint32_t)((uint64_t)R * p.row_bytes), kBufWord3);
+
+  float acc[NACC];
+#pragma unroll
+  for (int i = 0; i < NACC; ++i) acc[i] = 0.0f;
+
+  for (int64_t c = s; c < e; c += kWaveSize) {
+    const int64_t left = e - c;
+    const int n = left < kWaveSize ? (int)left : kWaveSize;  // lookups in this chunk (uniform)
+    int64_t idx = -1;
+    float w = 0.0f;
+    if (lane < n) {
+      idx = __builtin_nontemporal_load(indices + c + lane);
+      if constexpr (WEIGHTED) w = __builtin_nontemporal_load(weights + c + lane);
+    }
+    const bool idx_ok = (uint64_t)idx < (uint64_t)R;
+    uint32_t voff = kBufSentinel;  // BUF: 32-bit byte offset of the row inside the table
+    int64_t roff = -1;             // !BUF: 64-bit byte offset, -1 = skip
+    if constexpr (BUF) {
+      if (idx_ok) voff = (uint32_t)idx * p.row_bytes;
+    } else {
+      if (idx_ok) roff = idx * (int64_t)p.row_bytes;
+    }
+
+    const int steps = (n + G - 1) / G;
+    for (int k0 = 0; k0 < steps; k0 += DEPTH) {
+      u32x4 r[DEPTH];
+      float wj[DEPTH];
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        const int j = (k0 + d) * G + g;  // lookup of this chunk served by this lane's group
+        const bool take = (j < n) && lane_ok;
+        if constexpr (BUF) {
+          uint32_t vo = (uint32_t)__shfl((int)voff, j & (kWaveSize - 1));
+          vo = take ? vo : kBufSentinel;
+          r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, 0);
+        } else {
+          const int64_t ro = shfl64(roff, j & (kWaveSize - 1));
+          u32x4 v = {0u, 0u, 0u, 0u};
+          if (take && ro >= 0) v = *reinterpret_cast<const u32x4*>(tbase + ro + col);
+          r[d] = v;
+        }
+        if constexpr (WEIGHTED) {
+          const float ws = __shfl(w, j & (kWaveSize - 1));
+          wj[d] = (j < n) ? ws : 0.0f;
+        } else {
+          wj[d] = 1.0f;
+        }
+      }
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) accumulate<F16, WEIGHTED>(acc, r[d], wj[d]);
+    }
+  }
+
+  // combine the G row groups (fixed butterfly: every lane ends with the same bits)
+#pragma unroll
+  for (int m = kWaveSize / 2; m >= LPR; m >>= 1) {
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc[i] += __shfl_xor(acc[i], m);
+  }
+
+  if (p.mean) {
+    const int64_t len = e - s;
+    if (len > 0) {
+      const float fl = (float)len;
+#pragma unroll
+      for (int i = 0; i < NACC; ++i) acc[i] = acc[i] / fl;
+    }
+  }
+
+  if (lane < LPR && lane_ok) {
+    // col counts bytes of the table row; the output is fp32
+    const uint32_t elem0 = F16 ? col / 2 : col / 4;
+    f32x4* dst = reinterpret_cast<f32x4*>(out + (int64_t)b * p.out_ld + (int64_t)t * p.D + elem0);
+    const f32x4 v0 = {acc[0], acc[1], acc[2], acc[3]};
+    __builtin_nontemporal_store(v0, dst);
+    if constexpr (F16) {
+      const f32x4 v1 = {acc[4], acc[5], acc[6], acc[7]};
+      __builtin_nontemporal_store(v1, dst + 1);
+    }
+  }
+}
+
+// One wavefront per bag: count bad bounds and bad indices.
+__global__ void __launch_bounds__(kBlock)
+emb_bag_validate_kernel(const int64_t* __restrict__ table_offsets,
+                        const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
+                        unsigned long long* __restrict__ num_bad, int64_t num_lookups, uint32_t B,
+                        uint32_t num_bags) {
+  const int lane = threadIdx.x & (kWaveSize - 1);
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint64_t bag64 = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (bag64 >= num_bags) return;
+  const uint32_t bag = (uint32_t)bag64;
+  const uint32_t t = bag / B;
+  int64_t s = uniform64(offsets[bag]);
+  int64_t e = uniform64(offsets[bag + 1]);
+  unsigned long long bad = 0;
+  if (lane == 0) {
+    if (s < 0 || e < s || e > num_lookups) bad += 1;
+    if (bag == 0 && s != 0) bad += 1;
+    if (bag == num_bags - 1 && e != num_lookups) bad += 1;
+  }
+  s = s < 0 ? 0 : (s > num_lookups ? num_lookups : s);
+  e = e < s ? s : (e > num_lookups ? num_lookups : e);
+  const int64_t R = uniform64(table_offsets[t + 1]) - uniform64(table_offsets[t]);
+  for (int64_t j = s + lane; j < e; j += kWaveSize) {
+    const int64_t idx = indices[j];
+    if (idx < 0 || idx >= R) bad += 1;
+  }
+#pragma unroll
+  for (int m = kWaveSize / 2; m >= 1; m >>= 1) bad += __shfl_xor(bad, m);
+  if (lane == 0 && bad) atomicAdd(num_bad, bad);
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+struct Tuning {
+  int64_t depth = 0;
+  int64_t addressing = 0;
+  int64_t blocks_per_cu = 0;
+  int64_t xcd_remap = -1;
+  int64_t kernel = 0;
+};
+Tuning g_tuning;
+
+using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int64_t*,
+                          const float*, float*, KParams);
+
+template <int LPR, bool F16, int DEPTH>
+KernelFn pick_wb(bool weighted, bool buf) {
+  if (weighted)
+    return buf ? emb_bag_wave_kernel<LPR, F16, DEPTH, true, true>
+               : emb_bag_wave_kernel<LPR, F16, DEPTH, true, false>;
+  return buf ? emb_bag_wave_kernel<LPR, F16, DEPTH, false, true>
+             : emb_bag_wave_kernel<LPR, F16, DEPTH, false, false>;
+}
+
+template <int LPR, bool F16>
+KernelFn pick_depth(int depth, bool weighted, bool buf) {
+  switch (depth) {
+    case 1: return pick_wb<LPR, F16, 1>(weighted, buf);
+    case 2: return pick_wb<LPR, F16, 2>(weighted, buf);
+    case 4: return pick_wb<LPR, F16, 4>(weighted, buf);
+    case 8: return pick_wb<LPR, F16, 8>(weighted, buf);
+    case 16: return pick_wb<LPR, F16, 16>(weighted, buf);
+    default: return nullptr;
+  }
+}
+
+template <int LPR>
+KernelFn pick_dtype(bool f16, int depth, bool weighted, bool buf) {
+  return f16 ? pick_depth<LPR, true>(depth, weighted, buf)
+             : pick_depth<LPR, false>(depth, weighted, buf);
+}
+
+KernelFn pick_kernel(int lpr, bool f16, int depth, bool weighted, bool buf) {
+  switch (lpr) {
+    case 4: return pick_dtype<4>(f16, depth, weighted, buf);
+    case 8: return pick_dtype<8>(f16, depth, weighted, buf);
+    case 16: return pick_dtype<16>(f16, depth, weighted, buf);
+    case 32: return pick_dtype<32>(f16, depth, weighted, buf);
+    case 64: return pick_dtype<64>(f16, depth, weighted, buf);
+    default: return nullptr;
+  }
+}
+
+int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
+  if (!d) return EMB_ERR_NULL_PTR;
+  if (d->table_dtype != EMB_F32 && d->table_dtype != EMB_F16) return EMB_ERR_BAD_DTYPE;
+  if (d->mode != EMB_SUM && d->mode != EMB_MEAN) return EMB_ERR_BAD_MODE;
+  if (d->num_tables < 1 || d->dim < 1) return EMB_ERR_BAD_DIM;
+  const int64_t row_bytes = (int64_t)d->dim * (d->table_dtype == EMB_F16 ? 2 : 4);
+  if (row_bytes % 16 != 0 || row_bytes > 65536) return EMB_ERR_BAD_DIM;
+  if (d->batch < 0 || d->num_lookups < 0 || d->max_table_rows < 0) return EMB_ERR_BAD_SIZE;
+  *row_bytes_out = (uint32_t)row_bytes;
+  return EMB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t* table_offsets,
+                    const int64_t* indices, const int64_t* offsets,
+                    const float* per_sample_weights, float* out, void* stream) {
+  uint32_t row_bytes = 0;
+  const int rc = check_desc(desc, &row_bytes);
+  if (rc != EMB_OK) return rc;
+  const int64_t T = desc->num_tables, B = desc->batch, D = desc->dim;
+  if (per_sample_weights && desc->mode == EMB_MEAN) return EMB_ERR_UNSUPPORTED;
+  const int64_t out_ld = desc->out_ld ? desc->out_ld : T * D;
+  if (out_ld < T * D || out_ld % 4 != 0) return EMB_ERR_BAD_DIM;
+  if (B == 0) return EMB_OK;
+  if (!tables || !table_offsets || !offsets || !out) return EMB_ERR_NULL_PTR;
+  if (desc->num_lookups > 0 && !indices) return EMB_ERR_NULL_PTR;
+  if ((reinterpret_cast<uintptr_t>(tables) | reinterpret_cast<uintptr_t>(out)) & 15)
+    return EMB_ERR_ALIGNMENT;
+
+  const int64_t slabs = (row_bytes + kSlabBytes - 1) / kSlabBytes;
+  const int64_t num_work = T * B * slabs;
+  if (B > 0x7FFFFFFF || num_work > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
+
+  // lanes per row: the smallest power of two that covers min(row, 1 KiB) in 16-byte segments
+  int lpr = 4;
+  const uint32_t span = row_bytes < (uint32_t)kSlabBytes ? row_bytes : (uint32_t)kSlabBytes;
+  while ((uint32_t)lpr * 16u < span) lpr *= 2;
+
+  bool buf = desc->max_table_rows > 0 &&
+             (uint64_t)desc->max_table_rows * row_bytes <= kBufMaxBytes;
+  if (g_tuning.addressing == 1) buf = false;
+
+  int depth = (int)g_tuning.depth;
+  if (depth == 0) depth = 4;
+
+  KernelFn fn = pick_kernel(lpr, desc->table_dtype == EMB_F16, depth,
+                            per_sample_weights != nullptr, buf);
+  if (!fn) return EMB_ERR_BAD_TUNING;
+
+  KParams p;
+  p.num_lookups = desc->num_lookups;
+  p.out_ld = out_ld;
+  p.max_rows = desc->max_table_rows;
+  p.B = (uint32_t)B;
+  p.num_work = (uint32_t)num_work;
+  p.slabs = (uint32_t)slabs;
+  p.row_bytes = row_bytes;
+  p.D = (uint32_t)D;
+  p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
+  p.xcd_chunk = 0;
+
+  uint32_t blocks = (uint32_t)((num_work + kWavesPerBlock - 1) / kWavesPerBlock);
+  if (g_tuning.xcd_remap == 1 && blocks >= 64) {
+    p.xcd_chunk = (blocks + 7) / 8;
+    blocks = p.xcd_chunk * 8;
+  }
+
+  // A cap on resident workgroups per CU is imposed through a dynamic LDS request that the
+  // kernel never touches: k workgroups fit when each asks for 1/k of the CU's LDS.
+  uint32_t lds = 0;
+  if (g_tuning.blocks_per_cu > 0) {
+    int dev = 0, lds_per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor,
+                              dev) != hipSuccess || lds_per_cu <= 0)
+      return EMB_ERR_LAUNCH;
+    lds = ((uint32_t)lds_per_cu / (uint32_t)g_tuning.blocks_per_cu) & ~1023u;
+    if (lds > 65536u &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return EMB_ERR_LAUNCH;
+  }
+
+  hipLaunchKernelGGL(fn, dim3(blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
+                     static_cast<const char*>(tables), table_offsets, indices, offsets,
+                     per_sample_weights, out, p);
+  return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
+}
+
+int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
+                     const int64_t* indices, const int64_t* offsets, int64_t* num_bad,
+                     void* stream) {
+  uint32_t row_bytes = 0;
+  const int rc = check_desc(desc, &row_bytes);
+  if (rc != EMB_OK) return rc;
+  const int64_t T = desc->num_tables, B = desc->batch;
+  if (B == 0) return EMB_OK;
+  if (!table_offsets || !offsets || !num_bad) return EMB_ERR_NULL_PTR;
+  if (desc->num_lookups > 0 && !indices) return EMB_ERR_NULL_PTR;
+  if (B > 0x7FFFFFFF || T * B > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
+  const uint32_t num_bags = (uint32_t)(T * B);
+  const uint32_t blocks = (num_bags + kWavesPerBlock - 1) / kWavesPerBlock;
+  hipLaunchKernelGGL(emb_bag_validate_kernel, dim3(blocks), dim3(kBlock), 0,
+                     static_cast<hipStream_t>(stream), table_offsets, indices, offsets,
+                     reinterpret_cast<unsigned long long*>(num_bad), desc->num_lookups,
+                     (uint32_t)B, num_bags);
+  return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
+}
+
+int emb_bag_set_tuning(const char* key, int64_t value) {
+  if (!key) return EMB_ERR_NULL_PTR;
+  if (!strcmp(key, "depth")) {
+    if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
+      return EMB_ERR_BAD_TUNING;
+    g_tuning.depth = value;
+  } else if (!strcmp(key, "addressing")) {
+    if (value < 0 || value > 2) return EMB_ERR_BAD_TUNING;
+    g_tuning.addressing = value;
+  } else if (!strcmp(key, "blocks_per_cu")) {
+    if (value < 0 || value > 8) return EMB_ERR_BAD_TUNING;
+    g_tuning.blocks_per_cu = value;
+  } else if (!strcmp(key, "xcd_remap")) {
+    if (value < -1 || value > 1) return EMB_ERR_BAD_TUNING;
+    g_tuning.xcd_remap = value;
+  } else if (!strcmp(key, "kernel")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    g_tuning.kernel = value;
+  } else {
+    return EMB_ERR_BAD_TUNING;
+  }
+  return EMB_OK;
+}
+
+int emb_bag_get_tuning(const char* key, int64_t* value) {
+  if (!key || !value) return EMB_ERR_NULL_PTR;
+  if (!strcmp(key, "depth")) *value = g_tuning.depth;
+  else if (!strcmp(key, "addressing")) *value = g_tuning.addressing;
+  else if (!strcmp(key, "blocks_per_cu")) *value = g_tuning.blocks_per_cu;
+  else if (!strcmp(key, "xcd_remap")) *value = g_tuning.xcd_remap;
+  else if (!strcmp(key, "kernel")) *value = g_tuning.kernel;
+  else return EMB_ERR_BAD_TUNING;
+  return EMB_OK;
+}
+
+const char* emb_bag_status_string(int status) {
+  switch (status) {
+    case EMB_OK: return "ok";
+    case EMB_ERR_NULL_PTR: return "a required pointer is NULL";
+    case EMB_ERR_BAD_DIM: return "bad dim / row size / out_ld";
+    case EMB_ERR_BAD_DTYPE: return "unknown table dtype";
+    case EMB_ERR_BAD_MODE: return "unknown pooling mode";
+    case EMB_ERR_UNSUPPORTED: return "per-sample weights are only supported with sum pooling";
+    case EMB_ERR_LAUNCH: return "kernel launch failed";
+    case EMB_ERR_BAD_SIZE: return "size negative or beyond the supported range";
+    case EMB_ERR_ALIGNMENT: return "tables and out must be 16-byte aligned";
+    case EMB_ERR_BAD_TUNING: return "unknown tuning key or value out of range";
+    default: return "unknown status";
+  }
+}
+
+int emb_bag_version(void) { return 100; }
+
+}  // extern "C"

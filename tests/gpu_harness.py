@@ -1,0 +1,101 @@
+"""Helpers shared by the GPU parity tests: upload a seeded problem, call the C-ABI forward through
+the binding, and compare with the CPU oracle under the stated tolerances."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+import paper_2410_22249_amd as emb
+from inputgen import gen
+
+DEV = "cuda:0"
+
+# Tolerances.  fp32 tables: |gpu - ref| <= 1e-5 * sum|terms| per output element.  fp16 tables
+# (fp32 accumulation): within 1e-3 * |ref|, or within the fp32 bound when the sum cancels (the
+# widening of half to fp32 is exact, so the fp32 bound is what the arithmetic supports).
+F32_TOL = 1e-5
+F16_REL = 1e-3
+
+
+def to_dev(a: Optional[np.ndarray]):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def upload_arena(arena: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(arena)).to(DEV)
+
+
+def device_arena(wl: gen.Workload) -> torch.Tensor:
+    """Allocate the arena on the device and fill it with the generator's kernel."""
+    tdtype = torch.float16 if wl.dtype == "f16" else torch.float32
+    arena = torch.empty((wl.total_rows, wl.D), dtype=tdtype, device=DEV)
+    gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed, wl.kind,
+                          torch.cuda.current_stream().cuda_stream)
+    return arena
+
+
+def forward(arena: torch.Tensor, table_offsets: np.ndarray, indices, offsets, B: int,
+            mode: str = "sum", weights=None, out_ld: int = 0, max_table_rows: Optional[int] = None,
+            out: Optional[torch.Tensor] = None, fill: float = float("nan")) -> torch.Tensor:
+    """Run emb_bag_forward; numpy inputs are uploaded, torch inputs are used as they are."""
+    T = len(table_offsets) - 1
+    D = arena.shape[1]
+    toff_np = np.asarray(table_offsets, dtype=np.int64)
+    if max_table_rows is None:
+        max_table_rows = int(np.max(np.diff(toff_np))) if T else 0
+    toff = to_dev(toff_np)
+    idx = indices if isinstance(indices, torch.Tensor) else to_dev(np.asarray(indices, np.int64))
+    off = offsets if isinstance(offsets, torch.Tensor) else to_dev(np.asarray(offsets, np.int64))
+    w = weights if (weights is None or isinstance(weights, torch.Tensor)) else to_dev(
+        np.asarray(weights, np.float32))
+    nl = int(idx.numel()) if idx is not None else 0
+    ld = out_ld if out_ld else T * D
+    if out is None:
+        out = torch.full((B, ld), fill, dtype=torch.float32, device=DEV)
+    desc = emb.make_desc(T, B, D, emb.EMB_F16 if arena.dtype == torch.float16 else emb.EMB_F32,
+                         emb.EMB_MEAN if mode == "mean" else emb.EMB_SUM, nl, out_ld,
+                         max_table_rows)
+    emb.emb_bag_forward(desc, arena, toff, idx if nl else None, off, w, out)
+    torch.cuda.synchronize()
+    return out
+
+
+def assert_close_to_oracle(got: np.ndarray, ref: np.ndarray, bound: np.ndarray, f16: bool,
+                           what: str = "") -> float:
+    """Element-by-element check; returns max(err / bound) over elements with bound > 0."""
+    got = got.astype(np.float64)
+    err = np.abs(got - ref)
+    ok = err <= F32_TOL * bound
+    if f16:
+        ok |= err <= F16_REL * np.abs(ref)
+    if not ok.all():
+        bad = np.argwhere(~ok)[0]
+        raise AssertionError(f"{what}: {int((~ok).sum())} of {ok.size} elements out of tolerance; "
+                             f"first at {tuple(bad)}: got {got[tuple(bad)]!r} ref {ref[tuple(bad)]!r} "
+                             f"bound {bound[tuple(bad)]!r}")
+    zero = bound == 0
+    if zero.any():  # empty bags (and all-zero terms) must be exactly +0.0
+        assert np.all(got[zero] == 0.0) and not np.signbit(got[zero]).any(), f"{what}: empty bag not +0"
+    nz = bound > 0
+    return float(np.max(err[nz] / bound[nz])) if nz.any() else 0.0
+
+
+class tuning:
+    """Context manager: set tuning keys, restore the previous values on exit."""
+
+    def __init__(self, **kw):
+        self.kw = kw
+        self.old = {}
+
+    def __enter__(self):
+        for k, v in self.kw.items():
+            self.old[k] = emb.emb_bag_get_tuning(k)
+            emb.emb_bag_set_tuning(k, v)
+        return self
+
+    def __exit__(self, *exc):
+        for k, v in self.old.items():
+            emb.emb_bag_set_tuning(k, v)
+        return False

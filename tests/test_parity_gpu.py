@@ -1,0 +1,249 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on
+seeded inputs small enough for the oracle to finish in seconds yet spanning several 64-lookup
+chunks, ragged tails, empty bags, several tables and every addressing / depth variant."""
+import numpy as np
+import pytest
+import torch
+
+from inputgen import gen
+from gpu_harness import (DEV, assert_close_to_oracle, device_arena, forward, to_dev, tuning,
+                         upload_arena)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU (run with -m 'not gpu' otherwise)"
+
+
+def _problem(name, **over):
+    wl = gen.with_overrides(gen.workload(name), **over) if over else gen.workload(name)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    return wl, batch, arena
+
+
+@pytest.mark.parametrize("name", ["tiny", "small_f32_d64", "small_f32_d128", "small_f16_d256"])
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+@pytest.mark.parametrize("addressing", [0, 1])
+def test_small_workloads_match_oracle(oracle, name, mode, addressing):
+    wl, batch, arena = _problem(name)
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, mode)
+    with tuning(addressing=addressing):
+        got = forward(upload_arena(arena), wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                      mode).cpu().numpy()
+    assert_close_to_oracle(got, ref, bound, wl.dtype == "f16", f"{name}/{mode}/addr{addressing}")
+
+
+@pytest.mark.parametrize("depth", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256"])
+def test_every_depth(oracle, name, depth):
+    wl, batch, arena = _problem(name)
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
+    dev = upload_arena(arena)
+    for addressing in (0, 1):
+        with tuning(depth=depth, addressing=addressing):
+            got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
+        assert_close_to_oracle(got, ref, bound, wl.dtype == "f16", f"{name}/depth{depth}")
+
+
+@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256"])
+def test_integer_tables_are_bit_exact(oracle, name):
+    """Integer-valued tables: every partial sum is exact in fp32, so any order gives the same bits."""
+    wl, batch, arena = _problem(name, kind=gen.KIND_INT)
+    for mode in ("sum",):
+        ref, _ = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, mode)
+        for addressing in (0, 1):
+            with tuning(addressing=addressing):
+                got = forward(upload_arena(arena), wl.table_offsets(), batch.indices,
+                              batch.offsets, wl.B, mode).cpu().numpy()
+            assert np.array_equal(got.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256"])
+def test_per_sample_weights(oracle, name):
+    wl, batch, arena = _problem(name, weighted=True)
+    assert batch.weights is not None
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                                "sum", weights=batch.weights)
+    dev = upload_arena(arena)
+    for addressing in (0, 1):
+        with tuning(addressing=addressing):
+            got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "sum",
+                          weights=batch.weights).cpu().numpy()
+        assert_close_to_oracle(got, ref, bound, wl.dtype == "f16", f"{name}/weights")
+
+
+# rows of 16 B .. 4 KiB: non-power-of-two widths, several 1-KiB column slabs, both dtypes
+@pytest.mark.parametrize("D,dtype", [(4, "f32"), (12, "f32"), (32, "f32"), (96, "f32"),
+                                     (256, "f32"), (320, "f32"), (1024, "f32"), (8, "f16"),
+                                     (24, "f16"), (128, "f16"), (520, "f16"), (2048, "f16")])
+def test_general_row_widths(oracle, D, dtype):
+    wl = gen.Workload(name=f"w{D}{dtype}", T=3, rows=(300, 17, 64), D=D, dtype=dtype, B=21,
+                      pooling=("uniform", 0, 90), dists=(("uniform",),) * 3, seed=0x5EED0100 + D)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    dev = upload_arena(arena)
+    for mode in ("sum", "mean"):
+        ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, mode)
+        for addressing in (0, 1):
+            with tuning(addressing=addressing):
+                got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                              mode).cpu().numpy()
+            assert_close_to_oracle(got, ref, bound, dtype == "f16", f"D{D}/{dtype}/{mode}")
+
+
+def test_padded_output_leading_dimension(oracle):
+    wl, batch, arena = _problem("small_f32_d64")
+    ld = wl.T * wl.D + 8
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                                "sum", out_ld=ld)
+    got = forward(upload_arena(arena), wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                  "sum", out_ld=ld, fill=-7.0).cpu().numpy()
+    assert np.all(got[:, wl.T * wl.D:] == -7.0)           # padding columns untouched
+    assert_close_to_oracle(got[:, :wl.T * wl.D], ref[:, :wl.T * wl.D], bound[:, :wl.T * wl.D], False)
+
+
+def test_empty_inputs(oracle):
+    arena = gen.table_values(1, np.arange(10), 64)
+    toff = np.array([0, 4, 10], dtype=np.int64)
+    # every bag empty, no indices at all
+    got = forward(upload_arena(arena), toff, np.zeros(0, np.int64), np.zeros(2 * 5 + 1, np.int64), 5)
+    g = got.cpu().numpy()
+    assert g.shape == (5, 128) and np.all(g == 0) and not np.signbit(g).any()
+    got = forward(upload_arena(arena), toff, np.zeros(0, np.int64), np.zeros(2 * 5 + 1, np.int64), 5, "mean")
+    assert np.all(got.cpu().numpy() == 0)
+    # B = 0 is a no-op
+    out = forward(upload_arena(arena), toff, np.zeros(0, np.int64), np.zeros(1, np.int64), 0)
+    assert out.shape == (0, 128)
+
+
+def test_single_bag_single_table_and_len1(oracle):
+    arena = gen.table_values(2, np.arange(50), 128)
+    toff = np.array([0, 50], dtype=np.int64)
+    got = forward(upload_arena(arena), toff, np.array([7], np.int64), np.array([0, 1], np.int64), 1)
+    assert np.array_equal(got.cpu().numpy()[0], arena[7])            # len 1: the row itself
+    got = forward(upload_arena(arena), toff, np.array([7], np.int64), np.array([0, 1], np.int64), 1, "mean")
+    assert np.array_equal(got.cpu().numpy()[0], arena[7])
+
+
+def test_one_item_case(oracle):
+    """Paper Sec. 3.2 'one item': all lookups name one row."""
+    for kind in (gen.KIND_NORMAL, gen.KIND_INT):
+        wl = gen.Workload(name="one", T=2, rows=(500, 300), D=128, dtype="f32", B=40,
+                          pooling=("fixed", 64), dists=(("one_item",),) * 2, seed=77, kind=kind)
+        batch = gen.make_batches(wl, 1)[0]
+        arena = gen.host_arena(wl)
+        ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets,
+                                    wl.B, "mean")
+        g = forward(upload_arena(arena), wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                    "mean").cpu().numpy()
+        assert_close_to_oracle(g, ref, bound, False, "one item")
+        if kind == gen.KIND_INT:  # small integers: 64 * row / 64 is exact
+            for t in range(2):
+                row = arena[wl.table_offsets()[t] + gen.one_item_row(wl, t)]
+                assert np.array_equal(g[:, t * 128:(t + 1) * 128], np.broadcast_to(row, (wl.B, 128)))
+
+
+def test_long_bags_many_chunks(oracle):
+    wl = gen.Workload(name="long", T=2, rows=(5000, 1000), D=128, dtype="f32", B=6,
+                      pooling=("uniform", 500, 1500), dists=(("uniform",), ("zipf", 1.05)), seed=91)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "mean")
+    got = forward(upload_arena(arena), wl.table_offsets(), batch.indices, batch.offsets, wl.B, "mean")
+    # 1500 terms: the fp32 bound still holds in practice (errors grow like sqrt(L) * 2^-24)
+    assert_close_to_oracle(got.cpu().numpy(), ref, bound, False, "long bags")
+
+
+def test_launch_shaping_knobs_do_not_change_bits(oracle):
+    wl = gen.Workload(name="knobs", T=6, rows=(900,) * 6, D=128, dtype="f32", B=300,
+                      pooling=("uniform", 0, 70), dists=(("uniform",),) * 6, seed=0x5EED0200)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
+    dev = upload_arena(arena)
+    base = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
+    assert_close_to_oracle(base, ref, bound, False, "knobs/base")
+    again = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
+    assert np.array_equal(base, again)                                  # run-to-run deterministic
+    for kw in (dict(xcd_remap=1), dict(blocks_per_cu=1), dict(blocks_per_cu=2),
+               dict(blocks_per_cu=5), dict(xcd_remap=1, blocks_per_cu=3)):
+        with tuning(**kw):
+            got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
+        assert np.array_equal(got, base), kw
+
+
+def test_bad_indices_and_offsets_are_neutralised_and_counted(oracle):
+    import paper_2410_22249_amd as emb
+    wl, batch, arena = _problem("small_f32_d128")
+    toff = wl.table_offsets()
+    rng = np.random.default_rng(5)
+    idx = batch.indices.copy()
+    nbad = 40
+    pos = rng.choice(len(idx), size=nbad, replace=False)
+    table_of = np.repeat(np.arange(wl.T), np.diff(batch.offsets[::wl.B]))
+    bad_vals = np.where(rng.random(nbad) < 0.5, -1 - rng.integers(0, 5, nbad),
+                        np.asarray(wl.rows)[table_of[pos]] + rng.integers(0, 3, nbad))
+    idx[pos] = bad_vals
+    # oracle on the same problem with the bad lookups given zero weight
+    w = np.ones(len(idx), np.float32)
+    w[pos] = 0.0
+    ref, bound = oracle.emb_bag(arena, toff, batch.indices, batch.offsets, wl.B, "sum", weights=w)
+    dev = upload_arena(arena)
+    for addressing in (0, 1):
+        with tuning(addressing=addressing):
+            got = forward(dev, toff, idx, batch.offsets, wl.B).cpu().numpy()
+        assert_close_to_oracle(got, ref, bound, False, f"bad indices/addr{addressing}")
+    desc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F32, emb.EMB_SUM, len(idx), 0, max(wl.rows))
+    count = torch.zeros(1, dtype=torch.int64, device=DEV)
+    emb.emb_bag_validate(desc, to_dev(toff), to_dev(idx), to_dev(batch.offsets), count)
+    assert int(count.item()) == nbad
+    count.zero_()
+    emb.emb_bag_validate(desc, to_dev(toff), to_dev(batch.indices), to_dev(batch.offsets), count)
+    assert int(count.item()) == 0
+    # offsets: one decreasing pair -> two defects (bag g ends low, bag g+1 starts... stays valid)
+    off = batch.offsets.copy()
+    g = 10
+    off[g + 1] = off[g] - 1 if off[g] > 0 else off[g]
+    count.zero_()
+    emb.emb_bag_validate(desc, to_dev(toff), to_dev(batch.indices), to_dev(off), count)
+    assert int(count.item()) >= 1
+    got = forward(dev, toff, batch.indices, off, wl.B).cpu().numpy()   # must not fault
+    assert np.isfinite(got).all()
+    # offsets that point far outside [0, NL] are clamped
+    off2 = batch.offsets.copy()
+    off2[-1] = 1 << 40
+    off2[3] = -(1 << 40)
+    got = forward(dev, toff, batch.indices, off2, wl.B).cpu().numpy()
+    assert np.isfinite(got).all()
+
+
+def test_rows_beyond_max_table_rows_read_as_zero(oracle):
+    wl, batch, arena = _problem("small_f32_d128")
+    cap = 100
+    w = np.ones(len(batch.indices), np.float32)
+    w[batch.indices >= cap] = 0.0
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                                "sum", weights=w)
+    got = forward(upload_arena(arena), wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                  max_table_rows=cap).cpu().numpy()
+    assert_close_to_oracle(got, ref, bound, False, "max_table_rows clamp")
+
+
+@pytest.mark.parametrize("dtype,kind", [("f32", 0), ("f16", 0), ("f32", 1), ("f16", 1)])
+def test_device_fill_matches_host_values_bit_for_bit(dtype, kind):
+    wl = gen.Workload(name="fill", T=2, rows=(7001, 4099), D=128 if dtype == "f32" else 256,
+                      dtype=dtype, B=1, pooling=("fixed", 1), dists=(("uniform",),) * 2,
+                      seed=0x5EED0300, kind=kind)
+    dev = device_arena(wl)
+    torch.cuda.synchronize()
+    host = gen.host_arena(wl)
+    assert np.array_equal(dev.cpu().numpy().view(np.uint8), host.view(np.uint8))
+    # a slab filled from a non-zero first row matches the same rows of the whole
+    part = torch.empty((1000, wl.D), dtype=dev.dtype, device=DEV)
+    gen.fill_arena_device(part.data_ptr(), 5000, 1000, wl.D, dtype, wl.seed, kind,
+                          torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(part, dev[5000:6000])
