@@ -7,6 +7,7 @@
 //                       100+ GB arenas never need a host copy;
 //   * gen_copy_bytes  - a plain device-to-device copy kernel of known size, used to calibrate
 //                       the HBM byte counters of the profiler;
+//   * gen_read_bytes  - a read-only streaming kernel: the measured read-bandwidth ceiling;
 //   * gen_scrub_cache - stream over a scratch buffer to push earlier data out of L2 / MALL.
 //
 // Value function (shared, by construction, with inputgen/gen.py::table_values):
@@ -84,6 +85,19 @@ __global__ __launch_bounds__(256) void scrub_kernel(uint4* __restrict__ buf, uin
   }
 }
 
+// Read-only stream: every thread xors what it reads and writes one word only if the result is
+// a value that never occurs, so the loads cannot be optimised away and nothing is written.
+__global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src, uint64_t nvec,
+                                                   uint32_t* __restrict__ sink) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  uint32_t x = 0;
+  for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += stride) {
+    const uint4 a = src[v];
+    x ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  if (x == 0x9E3779B9u && sink) *sink = x;
+}
+
 unsigned grid_for(uint64_t nvec) {
   uint64_t blocks = (nvec + 255) / 256;
   const uint64_t cap = 256ull * 32ull;  // 32 workgroups per CU keeps every CU busy
@@ -128,6 +142,19 @@ int gen_copy_bytes(void* dst, const void* src, int64_t nbytes, void* stream) {
   hipLaunchKernelGGL(copy_kernel, dim3(grid_for(nvec)), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<uint4*>(dst),
                      static_cast<const uint4*>(src), nvec);
+  return (int)hipGetLastError();
+}
+
+// Read nbytes (multiple of 16, DEVICE pointer 16-byte aligned) and discard them: a streaming-read
+// bandwidth probe.  `sink` is a DEVICE uint32 that is (practically) never written; may be NULL.
+int gen_read_bytes(const void* src, int64_t nbytes, void* sink, void* stream) {
+  if (nbytes == 0) return 0;
+  if (!src || nbytes < 0 || (nbytes & 15)) return -1;
+  if (reinterpret_cast<uintptr_t>(src) & 15) return -5;
+  const uint64_t nvec = (uint64_t)nbytes / 16;
+  hipLaunchKernelGGL(read_kernel, dim3(grid_for(nvec)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), nvec,
+                     static_cast<uint32_t*>(sink));
   return (int)hipGetLastError();
 }
 

@@ -108,6 +108,9 @@ def load_lib() -> ctypes.CDLL:
         lib.gen_copy_bytes.restype = ctypes.c_int
         lib.gen_copy_bytes.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                        ctypes.c_void_p]
+        lib.gen_read_bytes.restype = ctypes.c_int
+        lib.gen_read_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                       ctypes.c_void_p]
         lib.gen_scrub_cache.restype = ctypes.c_int
         lib.gen_scrub_cache.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
         _lib = lib
@@ -131,6 +134,12 @@ def copy_bytes_device(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) 
                                    ctypes.c_void_p(stream))
     if rc != 0:
         raise RuntimeError(f"gen_copy_bytes failed with code {rc}")
+
+
+def read_bytes_device(src_ptr: int, nbytes: int, stream: int = 0) -> None:
+    rc = load_lib().gen_read_bytes(ctypes.c_void_p(src_ptr), nbytes, None, ctypes.c_void_p(stream))
+    if rc != 0:
+        raise RuntimeError(f"gen_read_bytes failed with code {rc}")
 
 
 def scrub_cache_device(buf_ptr: int, nbytes: int, stream: int = 0) -> None:

@@ -1,0 +1,96 @@
+"""Turn rocprofv3 CSV output into the short text summaries kept under profiles/.
+
+    python -m paper_2410_22249_amd.profile_summary --workload cfg3 \
+        --kernel-stats gpurun_out/prof/kt/cfg3_kernel_stats.csv \
+        --fetch gpurun_out/prof/fetch/cfg3_counter_collection.csv \
+        --write gpurun_out/prof/write/cfg3_counter_collection.csv \
+        [--counters some_other_counter_collection.csv ...] --command "<how it was collected>"
+
+HBM traffic: rocprofv3 reports FETCH_SIZE / WRITE_SIZE in KiB per dispatch.  Each is scaled by
+what the same counter reads for the plain copy kernel of known size that bench.py launches once
+(`copy_kernel`, 1 GiB read + 1 GiB written), so a counter that under- or over-reports by a fixed
+factor on this chip is corrected.
+"""
+from __future__ import annotations
+
+import argparse
+import csv
+import statistics
+import sys
+from collections import defaultdict
+
+EMB = "emb_bag_"
+COPY = "copy_kernel"
+CAL_BYTES = 1 << 30
+
+
+def per_kernel_counter(path):
+    """{counter: {kernel_name: [values per dispatch]}}"""
+    out = defaultdict(lambda: defaultdict(list))
+    for r in csv.DictReader(open(path)):
+        out[r["Counter_Name"]][r["Kernel_Name"]].append(float(r["Counter_Value"]))
+    return out
+
+
+def short(name: str) -> str:
+    name = name.replace("(anonymous namespace)::", "").replace("void ", "")
+    return name.split("(")[0]
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", required=True)
+    ap.add_argument("--kernel-stats")
+    ap.add_argument("--fetch")
+    ap.add_argument("--write")
+    ap.add_argument("--counters", action="append", default=[])
+    ap.add_argument("--command", action="append", default=[])
+    ap.add_argument("--note", action="append", default=[])
+    a = ap.parse_args()
+
+    print(f"# rocprofv3 summary: embedding-bag forward, workload {a.workload}")
+    for c in a.command:
+        print(f"# command: {c}")
+    for n in a.note:
+        print(f"# note: {n}")
+
+    if a.kernel_stats:
+        print("\n## kernel-trace --stats (per kernel)")
+        print(f"{'kernel':70s} {'calls':>6s} {'avg_us':>10s} {'min_us':>10s} {'max_us':>10s} {'pct':>6s}")
+        for r in csv.DictReader(open(a.kernel_stats)):
+            print(f"{short(r['Name'])[:70]:70s} {int(r['Calls']):6d} {float(r['AverageNs']) / 1e3:10.1f} "
+                  f"{float(r['MinNs']) / 1e3:10.1f} {float(r['MaxNs']) / 1e3:10.1f} "
+                  f"{float(r['Percentage']):6.2f}")
+
+    traffic = {}
+    for label, path, counter in (("fetch", a.fetch, "FETCH_SIZE"), ("write", a.write, "WRITE_SIZE")):
+        if not path:
+            continue
+        data = per_kernel_counter(path)[counter]
+        cal = [v for k, vs in data.items() if COPY in k for v in vs]
+        emb = [v for k, vs in data.items() if EMB in k and "validate" not in k for v in vs]
+        if not cal or not emb:
+            print(f"\n## {counter}: calibration copy or embedding kernel not found in {path}")
+            continue
+        scale = (CAL_BYTES / 1024.0) / statistics.mean(cal)
+        med = statistics.median(emb)
+        traffic[label] = med * 1024.0 * scale
+        print(f"\n## {counter} (KiB per dispatch as reported)")
+        print(f"copy_kernel of {CAL_BYTES} bytes reads {statistics.mean(cal):.1f} -> scale factor {scale:.4f}")
+        print(f"embedding kernel: n={len(emb)} median {med:.1f} min {min(emb):.1f} max {max(emb):.1f}")
+        print(f"{label}_bytes_per_launch = {traffic[label]:.0f}")
+    if len(traffic) == 2:
+        print(f"\nhbm_bytes_per_launch = {traffic['fetch'] + traffic['write']:.0f}")
+
+    for path in a.counters:
+        data = per_kernel_counter(path)
+        print(f"\n## counters from {path.split('/')[-2] if '/' in path else path} (embedding kernel, median per dispatch)")
+        for counter, per in sorted(data.items()):
+            emb = [v for k, vs in per.items() if EMB in k and "validate" not in k for v in vs]
+            if emb:
+                print(f"{counter:32s} {statistics.median(emb):18.3f}")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,82 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The table arenas of the large configurations (up to 123 GB) do not fit in host memory, so the
+oracle evaluates a sample of bags one by one: the generator rebuilds exactly the rows those bags
+touch on the host (its values are a pure function of seed, row and column; the device fill is
+checked bit for bit against that function in test_parity_gpu.py).  The sample holds random bags
+plus the first and last bag of every table (table-boundary mistakes show there).  The smallest
+configuration is checked whole, element by element.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2410_22249_amd as emb
+from inputgen import gen
+from gpu_harness import DEV, assert_close_to_oracle, device_arena, to_dev, tuning
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(wl, batch, arena, toff):
+    idx, off = to_dev(batch.indices), to_dev(batch.offsets)
+    out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
+    desc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32,
+                         emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, batch.num_lookups, 0,
+                         max(wl.rows))
+    emb.emb_bag_forward(desc, arena, toff, idx, off, None, out)
+    bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    emb.emb_bag_validate(desc, toff, idx, off, bad)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+    return out, (desc, idx, off)
+
+
+def _sample_bags(wl, n, seed=2024):
+    rng = np.random.default_rng(seed)
+    edge = np.concatenate([np.arange(wl.T) * wl.B, np.arange(wl.T) * wl.B + wl.B - 1])
+    return np.unique(np.concatenate([rng.integers(0, wl.num_bags, size=n), edge]))
+
+
+def test_cfg1_whole_output(oracle):
+    wl = gen.workload("cfg1")
+    batch = gen.make_batches(wl, 1)[0]
+    arena = device_arena(wl)
+    out, _ = _run(wl, batch, arena, to_dev(wl.table_offsets()))
+    host = gen.host_arena(wl)
+    assert np.array_equal(arena.cpu().numpy().view(np.uint8), host.view(np.uint8))
+    ref, bound = oracle.emb_bag(host, wl.table_offsets(), batch.indices, batch.offsets, wl.B, wl.mode)
+    assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, "cfg1 whole")
+
+
+@pytest.mark.parametrize("name,nsample", [("cfg2", 2000), ("cfg3", 600), ("cfg4", 600),
+                                          ("cfg5", 600), ("paper", 400)])
+def test_full_size_sampled_bags(oracle, name, nsample):
+    print(f"\n[fullsize] {name}: generating", flush=True)
+    wl = gen.workload(name)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = device_arena(wl)
+    toff = to_dev(wl.table_offsets())
+    print(f"[fullsize] {name}: {batch.num_lookups} lookups, arena {wl.table_bytes / 1e9:.1f} GB", flush=True)
+    out, (desc, idx, off) = _run(wl, batch, arena, toff)
+    assert bool(torch.isfinite(out).all())                    # every bag was written
+    # run-to-run determinism over the whole output
+    out2 = torch.full_like(out, float("nan"))
+    emb.emb_bag_forward(desc, arena, toff, idx, off, None, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    bags = _sample_bags(wl, nsample)
+    small, ix, soff = gen.compact_rows(wl, batch, bags)
+    ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, soff, len(bags), wl.mode)
+    sel = torch.from_numpy(np.stack([bags % wl.B, bags // wl.B], 1)).to(DEV)
+    got = out.view(wl.B, wl.T, wl.D)[sel[:, 0], sel[:, 1]].cpu().numpy()
+    worst = assert_close_to_oracle(got, ref, bound, wl.dtype == "f16", f"{name} sampled")
+    # the alternative launch shapes give the same bits at full size too
+    for kw in (dict(xcd_remap=1), dict(addressing=1, depth=8)):
+        with tuning(**kw):
+            emb.emb_bag_forward(desc, arena, toff, idx, off, None, out2)
+            torch.cuda.synchronize()
+        assert torch.equal(out, out2), kw
+    print(f"[fullsize] {name}: {len(bags)} bags checked, max err/bound {worst:.3e}", flush=True)
+    del arena, out, out2
+    torch.cuda.empty_cache()
