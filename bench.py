@@ -42,7 +42,7 @@ def log(msg: str) -> None:
 def read_traffic(workload: str):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary
     for this workload has been committed under profiles/."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    path = os.path.join(ROOT, "profiles", f"emb_bag_forward_{workload}.txt")
     if not os.path.exists(path):
         return None
     vals = {}
