@@ -1,0 +1,90 @@
+"""Are the oracle's pins sharp?  Plant one plausible mistake at a time in a COPY of the oracle's C
+source (CPU only), build it, and require that at least one pin from test_oracle_pins.py fails.
+The oracle that the rest of the suite uses is never modified."""
+import importlib.util
+import os
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+import test_oracle_pins as pins
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "emb_bag_oracle.c")
+WRAP = os.path.join(ROOT, "oracle", "emb_bag_oracle.py")
+
+MUTATIONS = {
+    "weight dropped from the sum": ("acc += w * x;", "acc += x;"),
+    "bound without abs": ("mag += fabs(w * x);", "mag += w * x;"),
+    "table base ignored": ("table_offsets[t] + indices[j], D, d)", "indices[j], D, d)"),
+    "first lookup of a bag skipped": ("for (int64_t j = s; j < e; ++j) {", "for (int64_t j = s + 1; j < e; ++j) {"),
+    "last lookup of a bag skipped": ("for (int64_t j = s; j < e; ++j) {", "for (int64_t j = s; j < e - 1; ++j) {"),
+    "bags taken in (b, t) order": ("const int64_t t = g / B;\n    const int64_t b = g % B;",
+                                   "const int64_t t = g % T;\n    const int64_t b = g / T;"),
+    "output transposed within a table block": ("ref[b * out_ld + t * D + d] = acc;",
+                                               "ref[b * out_ld + t * D + (D - 1 - d)] = acc;"),
+    "output block of the wrong table": ("ref[b * out_ld + t * D + d] = acc;",
+                                        "ref[b * out_ld + (T - 1 - t) * D + d] = acc;"),
+    "mean divides by len + 1": ("acc /= (double)(e - s);", "acc /= (double)(e - s + 1);"),
+    "mean of bound forgotten": ("mag /= (double)(e - s);", ""),
+    "columns reversed when reading a row": ("[arena_row * D + d]);\n  return (double)", "[arena_row * D + (D - 1 - d)]);\n  return (double)"),
+    "fp32 rows read with the wrong stride": ("return (double)((const float*)tables)[arena_row * D + d];",
+                                             "return (double)((const float*)tables)[arena_row * (D - 1) + d];"),
+    "half exponent bias off by one": ("expo - 25", "expo - 24"),
+    "half subnormal scale off by one": ("ldexp((double)frac, -24)", "ldexp((double)frac, -25)"),
+    "half sign dropped": ("return sign ? -v : v;", "return v;"),
+    "weights applied in mean mode only": ("const double w = weights ? (double)weights[j] : 1.0;",
+                                          "const double w = (weights && mode == 1) ? (double)weights[j] : 1.0;"),
+}
+
+PIN_FUNCS = [
+    lambda o: pins.test_brute_force_exact_rational(o, "sum", np.float32),
+    lambda o: pins.test_brute_force_exact_rational(o, "mean", np.float16),
+    pins.test_brute_force_weighted,
+    pins.test_hand_worked_example,
+    pins.test_identity_tables_give_index_histograms,
+    pins.test_table_base_is_respected,
+    pins.test_one_item_case,
+    pins.test_mean_is_sum_over_len_and_edge_lengths,
+    pins.test_empty_and_len1_bags,
+    pins.test_weights,
+    pins.test_bound_is_sum_of_abs_terms,
+    pins.test_half_widening_is_exact,
+]
+
+
+def _load_mutant(tmp_path, name, old, new):
+    src = open(SRC).read()
+    assert src.count(old) == 1, f"mutation {name!r}: pattern must occur exactly once"
+    c_path = tmp_path / "mutant.c"
+    so_path = tmp_path / "mutant.so"
+    c_path.write_text(src.replace(old, new))
+    subprocess.run(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-o", str(so_path),
+                    str(c_path), "-lm"], check=True, stderr=subprocess.DEVNULL)
+    spec = importlib.util.spec_from_file_location(f"oracle_mutant_{abs(hash(name))}", WRAP)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    mod.SRC, mod.LIB, mod._lib = str(c_path), str(so_path), None
+    return mod
+
+
+@pytest.mark.parametrize("name", sorted(MUTATIONS))
+def test_planted_mistake_is_caught(tmp_path, name):
+    old, new = MUTATIONS[name]
+    mutant = _load_mutant(tmp_path, name, old, new)
+    caught = []
+    for f in PIN_FUNCS:
+        try:
+            f(mutant)
+        except (AssertionError, ValueError) as ex:
+            caught.append(type(ex).__name__)
+    assert caught, f"no pin noticed: {name}"
+
+
+def test_unmutated_copy_passes_every_pin(tmp_path):
+    src = open(SRC).read()
+    clean = _load_mutant(tmp_path, "identity", "acc += w * x;", "acc += w * x; ")
+    for f in PIN_FUNCS:
+        f(clean)
