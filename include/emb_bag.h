@@ -119,11 +119,11 @@ int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
  *   "addressing"    0 = automatic, 1 = force 64-bit global addressing, 2 = force buffer
  *                   addressing where the sizes allow it
  *   "blocks_per_cu" cap on resident 256-thread workgroups per compute unit, 1..8; 0 = no cap
- *   "xcd_remap"     1 = deal consecutive bags to one XCD at a time (keeps one table's hot rows
- *                   in one L2, the stand-in for the L2 pinning of Sec. 4.3); 0 = natural order;
- *                   -1 = automatic
- *   "kernel"        0 = automatic, 1 = one bag per wavefront, 2 = persistent wavefronts that
- *                   prefetch the next bag's indices
+ *   "xcd_remap"     1 = XCD-affine order: a table's bags are dealt to one or two XCDs, so its hot
+ *                   rows are fetched into one or two of the eight L2s instead of all eight
+ *                   (the stand-in for the L2 pinning of Sec. 4.3); 0 = natural order;
+ *                   -1 = automatic (on for large launches)
+ *   "kernel"        0 = automatic, 1 = one bag per wavefront
  * Not thread-safe against concurrent emb_bag_forward calls.
  */
 int emb_bag_set_tuning(const char* key, int64_t value);

@@ -56,7 +56,12 @@ struct KParams {
   uint32_t row_bytes;
   uint32_t D;
   uint32_t mean;         // 1 = divide by bag length
-  uint32_t xcd_chunk;    // 0 = natural block order, else blocks per XCD (grid = 8 * xcd_chunk)
+  // XCD-affine block order (xcd_bpp = 0: natural order).  Every table is cut into 2^xcd_pshift
+  // pieces of xcd_wpp wavefronts (xcd_bpp workgroups); piece u = t * 2^xcd_pshift + k runs on
+  // XCD u % 8, and an XCD takes its pieces in increasing u.
+  uint32_t xcd_bpp;
+  uint32_t xcd_wpp;
+  uint32_t xcd_pshift;
 };
 
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
@@ -115,11 +120,22 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
 
   const int lane = threadIdx.x & (kWaveSize - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  uint32_t blk = blockIdx.x;
-  if (p.xcd_chunk) blk = (blk & 7u) * p.xcd_chunk + (blk >> 3);  // consecutive bags -> one XCD
-  const uint64_t work64 = (uint64_t)blk * kWavesPerBlock + wave;
-  if (work64 >= p.num_work) return;
-  const uint32_t work = (uint32_t)work64;
+  uint32_t work;
+  if (p.xcd_bpp) {
+    // workgroups are dealt round-robin to the 8 XCDs: blockIdx % 8 names the XCD (and its L2)
+    const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+    const uint32_t ul = slot / p.xcd_bpp;
+    const uint32_t unit = ul * 8u + xcd;
+    const uint32_t w_in_piece = (slot - ul * p.xcd_bpp) * kWavesPerBlock + wave;
+    const uint32_t waves_per_table = p.B * p.slabs;
+    const uint32_t w_in_table = (unit & ((1u << p.xcd_pshift) - 1u)) * p.xcd_wpp + w_in_piece;
+    if (w_in_piece >= p.xcd_wpp || w_in_table >= waves_per_table) return;
+    work = (unit >> p.xcd_pshift) * waves_per_table + w_in_table;
+  } else {
+    const uint64_t work64 = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
+    if (work64 >= p.num_work) return;
+    work = (uint32_t)work64;
+  }
 
   uint32_t bag = work, slab = 0;
   if (p.slabs > 1) {
@@ -362,7 +378,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   if (g_tuning.addressing == 1) buf = false;
 
   int depth = (int)g_tuning.depth;
-  if (depth == 0) depth = 4;
+  if (depth == 0) depth = (desc->table_dtype == EMB_F32 && row_bytes >= 512) ? 8 : 4;
 
   KernelFn fn = pick_kernel(lpr, desc->table_dtype == EMB_F16, depth,
                             per_sample_weights != nullptr, buf);
@@ -378,12 +394,25 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   p.row_bytes = row_bytes;
   p.D = (uint32_t)D;
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
-  p.xcd_chunk = 0;
+  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = 0;
 
   uint32_t blocks = (uint32_t)((num_work + kWavesPerBlock - 1) / kWavesPerBlock);
-  if (g_tuning.xcd_remap == 1 && blocks >= 64) {
-    p.xcd_chunk = (blocks + 7) / 8;
-    blocks = p.xcd_chunk * 8;
+  const bool remap = g_tuning.xcd_remap == 1 || (g_tuning.xcd_remap == -1 && blocks >= 4096);
+  if (remap && blocks >= 64) {
+    // pieces per table: the smallest power of two that makes T * pieces a multiple of 8, so
+    // that every XCD gets the same number of pieces and neighbouring XCDs share a table
+    uint32_t pshift = 0;
+    while (((uint64_t)T << pshift) % 8 != 0) ++pshift;
+    const uint64_t waves_per_table = (uint64_t)B * slabs;
+    const uint64_t wpp = (waves_per_table + (1u << pshift) - 1) >> pshift;
+    const uint64_t bpp = (wpp + kWavesPerBlock - 1) / kWavesPerBlock;
+    const uint64_t grid = ((uint64_t)T << pshift) * bpp;
+    if (grid <= 0x7FFFFFFFull) {
+      p.xcd_bpp = (uint32_t)bpp;
+      p.xcd_wpp = (uint32_t)wpp;
+      p.xcd_pshift = pshift;
+      blocks = (uint32_t)grid;
+    }
   }
 
   // A cap on resident workgroups per CU is imposed through a dynamic LDS request that the

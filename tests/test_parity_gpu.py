@@ -175,6 +175,25 @@ def test_launch_shaping_knobs_do_not_change_bits(oracle):
         assert np.array_equal(got, base), kw
 
 
+@pytest.mark.parametrize("T,B,D", [(1, 700, 64), (3, 333, 128), (5, 129, 64), (8, 64, 128),
+                                   (7, 100, 320), (16, 40, 128), (12, 257, 64)])
+def test_xcd_affine_order_covers_every_bag(oracle, T, B, D):
+    """The XCD-affine block order cuts tables into 1, 2, 4 or 8 pieces depending on T; whatever
+    the split, every bag is written exactly as in the natural order."""
+    wl = gen.Workload(name="xcd", T=T, rows=(500,) * T, D=D, dtype="f32", B=B,
+                      pooling=("uniform", 0, 30), dists=(("uniform",),) * T, seed=0x5EED0400 + T)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
+    dev = upload_arena(arena)
+    with tuning(xcd_remap=0):
+        nat = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
+    assert_close_to_oracle(nat, ref, bound, False, "natural order")
+    with tuning(xcd_remap=1):
+        aff = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
+    assert np.array_equal(nat, aff)
+
+
 def test_bad_indices_and_offsets_are_neutralised_and_counted(oracle):
     import paper_2410_22249_amd as emb
     wl, batch, arena = _problem("small_f32_d128")
