@@ -266,3 +266,46 @@ def test_device_fill_matches_host_values_bit_for_bit(dtype, kind):
                           torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert torch.equal(part, dev[5000:6000])
+
+
+def test_forward_replays_correctly_from_a_hip_graph(oracle):
+    """The forward is one kernel launch with no allocation and no memset, so it can be captured;
+    every replay (with eager work and synchronisations in between) must equal the eager result."""
+    import paper_2410_22249_amd as emb
+    wl = gen.workload("small_f32_d128")
+    b0, b1, b2 = gen.make_batches(wl, 3)
+    arena = upload_arena(gen.host_arena(wl))
+    toff = to_dev(wl.table_offsets())
+    cap = max(b.num_lookups for b in (b0, b1, b2))
+    idx = torch.zeros(cap, dtype=torch.int64, device=DEV)
+    off = torch.zeros(wl.T * wl.B + 1, dtype=torch.int64, device=DEV)
+    out = torch.zeros((wl.B, wl.T * wl.D), dtype=torch.float32, device=DEV)
+    # the descriptor is read at capture time: size it for the largest batch; the shorter
+    # batches simply end earlier in the (clamped) index buffer
+    desc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F32, emb.EMB_SUM, cap, 0, max(wl.rows))
+
+    def load(b):
+        idx[: b.num_lookups].copy_(torch.from_numpy(b.indices))
+        off.copy_(torch.from_numpy(b.offsets))
+
+    load(b0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        emb.emb_bag_forward(desc, arena, toff, idx, off, None, out)        # warm-up on the side stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        emb.emb_bag_forward(desc, arena, toff, idx, off, None, out)
+    for b in (b1, b2, b0, b1):
+        load(b)
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().copy()
+        eager = forward(arena, wl.table_offsets(), b.indices, b.offsets, wl.B).cpu().numpy()
+        assert np.array_equal(got, eager)
+        ref, bound = oracle.emb_bag(gen.host_arena(wl), wl.table_offsets(), b.indices, b.offsets, wl.B)
+        assert_close_to_oracle(got, ref, bound, False, "graph replay")
