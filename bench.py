@@ -32,6 +32,12 @@ DESCRIPTIONS = {
     "paper": "250 fp32 tables x 500,000 rows x dim 128, batch 2048, pooling 150 fixed, uniform "
              "indices, sum (the paper's model, random dataset)",
     "paper_one_item": "250 fp32 tables x 500,000 x dim 128, batch 2048, pooling 150, one item, sum",
+    "paper_high": "paper's model, Zipf(1.3396) stand-in for its high-hot trace (4.05 % unique)",
+    "paper_med": "paper's model, Zipf(1.0234) stand-in for its med-hot trace (20.5 % unique)",
+    "paper_low": "paper's model, Zipf(0.6999) stand-in for its low-hot trace (46.21 % unique)",
+    "paper_mix1": "paper's model, Mix1: 100 high / 75 med / 50 low / 25 random tables",
+    "paper_mix2": "paper's model, Mix2: 62 / 63 / 63 / 62",
+    "paper_mix3": "paper's model, Mix3: 25 / 50 / 75 / 100",
 }
 
 
@@ -68,6 +74,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--check-bags", type=int, default=256, help="bags spot-checked vs the oracle")
+    ap.add_argument("--no-hints", action="store_true",
+                    help="do not profile table reuse / pass per-table cache hints")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="emb_bag_set_tuning override, e.g. --tune depth=8")
     args = ap.parse_args()
@@ -111,9 +119,20 @@ def main() -> int:
         dbatches.append((torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev),
                          None if b.weights is None else torch.from_numpy(b.weights).to(dev)))
     out = torch.empty((wl.B, wl.T * wl.D), dtype=torch.float32, device=dev)
-    descs = [emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32,
-                           emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, b.num_lookups, 0,
-                           max(wl.rows)) for b in batches]
+    edt = emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32
+    emode = emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM
+    # Set-up, untimed (the paper profiles table access patterns offline, Sec. 4.3): classify each
+    # table as streaming or re-used from the first index batch, on the device.
+    hints = None
+    if not args.no_hints:
+        hints = torch.zeros(wl.T, dtype=torch.uint8, device=dev)
+        d0 = emb.make_desc(wl.T, wl.B, wl.D, edt, emode, batches[0].num_lookups, 0, max(wl.rows))
+        emb.emb_bag_profile_reuse(d0, dbatches[0][0], dbatches[0][1], 4096, -1, None, None, hints,
+                                  stream)
+        stream.synchronize()
+        log(f"table hints: {int(hints.sum().item())} of {wl.T} tables streaming")
+    descs = [emb.make_desc(wl.T, wl.B, wl.D, edt, emode, b.num_lookups, 0, max(wl.rows), hints)
+             for b in batches]
     torch.cuda.synchronize()
 
     def step(i: int) -> None:
@@ -200,7 +219,7 @@ def main() -> int:
         n_sub = int(sub_off[-1])
         emb_bag_oracle.emb_bag(host, toff_np[: tsub + 1], sub_idx, sub_off, wl.B, wl.mode)  # warm
         reps, t_cpu = 0, 0.0
-        while t_cpu < args.cpu_seconds and reps < 1000:
+        while t_cpu < args.cpu_seconds and reps < 100000:
             t1 = time.perf_counter()
             emb_bag_oracle.emb_bag(host, toff_np[: tsub + 1], sub_idx, sub_off, wl.B, wl.mode)
             t_cpu += time.perf_counter() - t1
@@ -232,6 +251,7 @@ def main() -> int:
                    "tables": wl.T, "rows_per_table": wl.rows[0], "dim": wl.D,
                    "table_dtype": wl.dtype, "batch": wl.B, "mode": wl.mode,
                    "lookups_per_step": avg_lookups, "index_batches_rotated": len(batches),
+                   "streaming_tables": None if hints is None else int(hints.sum().item()),
                    "tuning": {k: emb.emb_bag_get_tuning(k) for k in
                               ("depth", "addressing", "blocks_per_cu", "xcd_remap", "kernel")}},
         "gathered_GBps": gathered * args.steps / wall / 1e9,

@@ -37,6 +37,12 @@ extern "C" {
 #define EMB_SUM 0
 #define EMB_MEAN 1 /* sum divided by the bag length; an empty bag gives 0 */
 
+/* per-table access hints (one byte per table, see emb_bag_desc.table_hints) */
+#define EMB_HINT_DEFAULT 0   /* rows are re-used within a batch: read them with the default cache
+                                policy so that hot rows stay in L2 */
+#define EMB_HINT_STREAMING 1 /* rows are (almost) never re-used within a batch: read them with the
+                                non-temporal policy so that they do not occupy the caches */
+
 /* status codes */
 #define EMB_OK 0
 #define EMB_ERR_NULL_PTR (-1)    /* a required pointer is NULL */
@@ -70,6 +76,11 @@ typedef struct emb_bag_desc {
                              max_table_rows * row_bytes below 3.5 GiB lets the library use
                              32-bit buffer addressing; rows at or beyond the bound then read as
                              zero.  0 selects 64-bit addressing. */
+  const uint8_t* table_hints; /* DEVICE, T bytes of EMB_HINT_*, or NULL (= all EMB_HINT_DEFAULT).
+                             The paper profiles each table's access pattern offline and picks the
+                             cache treatment from it (Sec. 4.3, Sec. 7 steps v-vi); this is where
+                             that choice enters.  Hints change speed only, never results.
+                             emb_bag_profile_reuse can produce them from a sample batch. */
 } emb_bag_desc;
 
 /*
@@ -112,6 +123,28 @@ int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
                      void* stream);
 
 /*
+ * emb_bag_profile_reuse - measure how often each table's lookups repeat, and derive hints.
+ *
+ *   For every table t the first `window` lookups of the batch that go to t (fewer if the table
+ *   receives fewer; window is clamped to [1, 4096]) are examined:
+ *     window_used[t] = number of lookups examined,
+ *     dup_count[t]   = window_used[t] - (number of distinct row ids among them),
+ *     hints[t]       = EMB_HINT_STREAMING if dup_count[t] * 1000 < threshold_permille *
+ *                      window_used[t] (also when window_used[t] == 0), else EMB_HINT_DEFAULT.
+ *   This is the device-side counterpart of the offline hot-index profiling of paper Sec. 4.3:
+ *   uniform-random access (the paper's "random" dataset) shows practically no repeats, the
+ *   power-law datasets show many.  threshold_permille < 0 selects the library default (20).
+ *
+ *   desc, indices, offsets   as in emb_bag_forward (desc->table_hints is ignored)
+ *   dup_count, window_used   DEVICE int32 [T] each, or NULL
+ *   hints                    DEVICE uint8 [T], or NULL
+ *   Asynchronous on `stream`; counts are exact and deterministic.
+ */
+int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
+                          const int64_t* offsets, int32_t window, int32_t threshold_permille,
+                          int32_t* dup_count, int32_t* window_used, uint8_t* hints, void* stream);
+
+/*
  * emb_bag_set_tuning / emb_bag_get_tuning - process-wide launch tuning (the occupancy x
  * prefetch-depth search of paper Sec. 3.3, Sec. 4.2 and the recipe of Sec. 7, made a runtime
  * knob).  Keys (HOST strings):
@@ -123,6 +156,7 @@ int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
  *                   rows are fetched into one or two of the eight L2s instead of all eight
  *                   (the stand-in for the L2 pinning of Sec. 4.3); 0 = natural order;
  *                   -1 = automatic (on for large launches)
+ *   "use_hints"     1 (default) = honour desc->table_hints, 0 = ignore them
  *   "kernel"        0 = automatic, 1 = one bag per wavefront
  * Not thread-safe against concurrent emb_bag_forward calls.
  */

@@ -191,6 +191,21 @@ class Workload:
         return np.concatenate([[0], np.cumsum(np.asarray(self.rows, dtype=np.int64))]).astype(np.int64)
 
 
+# Zipf exponents whose expected unique-access % (R = 500,000 draws over 500,000 rows) equals the
+# paper's table of unique access % per dataset (Sec. 3.2): high 4.05, med 20.50, low 46.21.
+# Found by bisection on  U(alpha) = mean_k [1 - (1 - p_k)^R]  (see expected_unique_fraction).
+PAPER_HOTNESS_ALPHA = {"paper_high": 1.3396, "paper_med": 1.0234, "paper_low": 0.6999}
+PAPER_MIXES = {"paper_mix1": (100, 75, 50, 25), "paper_mix2": (62, 63, 63, 62),
+               "paper_mix3": (25, 50, 75, 100)}
+
+
+def expected_unique_fraction(R: int, alpha: float, n: int) -> float:
+    """Expected fraction of the R rows touched by n independent Zipf(alpha) draws."""
+    p = np.arange(1, R + 1, dtype=np.float64) ** (-float(alpha))
+    p /= p.sum()
+    return float(np.mean(-np.expm1(n * np.log1p(-p))))
+
+
 def _homog(name, T, R, D, dtype, B, pooling, dist, mode="sum", seed_off=0, **kw) -> Workload:
     return Workload(name=name, T=T, rows=(R,) * T, D=D, dtype=dtype, B=B, pooling=pooling,
                     dists=(dist,) * T, mode=mode, seed=0x5EED0000 + seed_off, **kw)
@@ -222,6 +237,18 @@ def workload(name: str) -> Workload:
     if name == "paper_one_item":
         return _homog("paper_one_item", 250, 500_000, 128, "f32", 2048, ("fixed", 150),
                       ("one_item",), seed_off=7)
+    if name in PAPER_HOTNESS_ALPHA:   # Zipf stand-ins for the paper's high / med / low hot traces
+        return _homog(name, 250, 500_000, 128, "f32", 2048, ("fixed", 150),
+                      ("zipf", PAPER_HOTNESS_ALPHA[name]), seed_off=8)
+    if name in PAPER_MIXES:           # Sec. 5 table of heterogeneous mixtures (tables per hotness)
+        hi, me, lo, rnd = PAPER_MIXES[name]
+        dists = ((("zipf", PAPER_HOTNESS_ALPHA["paper_high"]),) * hi
+                 + (("zipf", PAPER_HOTNESS_ALPHA["paper_med"]),) * me
+                 + (("zipf", PAPER_HOTNESS_ALPHA["paper_low"]),) * lo + (("uniform",),) * rnd)
+        T = len(dists)
+        return Workload(name=name, T=T, rows=(500_000,) * T, D=128, dtype="f32", B=2048,
+                        pooling=("fixed", 150), dists=dists, seed=0x5EED0009,
+                        note="tables ordered high, med, low, random")
     # ---- small shapes for tests (the oracle finishes these in well under a second) ----
     if name == "tiny":
         return Workload(name="tiny", T=3, rows=(8, 5, 7), D=4, dtype="f32", B=4,

@@ -19,15 +19,18 @@ EMB_F32, EMB_F16 = 0, 1
 EMB_SUM, EMB_MEAN = 0, 1
 EMB_OK = 0
 
-EXPORTS = ("emb_bag_forward", "emb_bag_validate", "emb_bag_set_tuning", "emb_bag_get_tuning",
-           "emb_bag_status_string", "emb_bag_version")
+EMB_HINT_DEFAULT, EMB_HINT_STREAMING = 0, 1
+
+EXPORTS = ("emb_bag_forward", "emb_bag_validate", "emb_bag_profile_reuse", "emb_bag_set_tuning",
+           "emb_bag_get_tuning", "emb_bag_status_string", "emb_bag_version")
 
 
 class emb_bag_desc(ctypes.Structure):
     _fields_ = [("num_tables", ctypes.c_int32), ("dim", ctypes.c_int32),
                 ("table_dtype", ctypes.c_int32), ("mode", ctypes.c_int32),
                 ("batch", ctypes.c_int64), ("num_lookups", ctypes.c_int64),
-                ("out_ld", ctypes.c_int64), ("max_table_rows", ctypes.c_int64)]
+                ("out_ld", ctypes.c_int64), ("max_table_rows", ctypes.c_int64),
+                ("table_hints", ctypes.c_void_p)]
 
 
 class EmbBagError(RuntimeError):
@@ -36,16 +39,19 @@ class EmbBagError(RuntimeError):
         super().__init__(f"{where}: {emb_bag_status_string(status)} (status {status})")
 
 
-def _load() -> ctypes.CDLL:
-    if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: build it with `python -c 'import "
+def _load(path: str = LIB_PATH) -> ctypes.CDLL:
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -c 'import "
                           f"__graft_entry__ as g; g.build()'` (there is no CPU fallback)")
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(path)
     P = ctypes.c_void_p
     lib.emb_bag_forward.restype = ctypes.c_int
     lib.emb_bag_forward.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, P, P, P, P, P]
     lib.emb_bag_validate.restype = ctypes.c_int
     lib.emb_bag_validate.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, P, P, P]
+    lib.emb_bag_profile_reuse.restype = ctypes.c_int
+    lib.emb_bag_profile_reuse.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, ctypes.c_int32,
+                                          ctypes.c_int32, P, P, P, P]
     lib.emb_bag_set_tuning.restype = ctypes.c_int
     lib.emb_bag_set_tuning.argtypes = [ctypes.c_char_p, ctypes.c_int64]
     lib.emb_bag_get_tuning.restype = ctypes.c_int
@@ -78,10 +84,16 @@ def _stream_handle(stream) -> Optional[int]:
 
 
 def make_desc(num_tables: int, batch: int, dim: int, table_dtype: int, mode: int,
-              num_lookups: int, out_ld: int = 0, max_table_rows: int = 0) -> emb_bag_desc:
+              num_lookups: int, out_ld: int = 0, max_table_rows: int = 0,
+              table_hints: Optional[torch.Tensor] = None) -> emb_bag_desc:
+    """Fill the host descriptor.  `table_hints` is a device uint8 tensor [T] (or None) that the
+    caller keeps alive for as long as the descriptor is used."""
+    if table_hints is not None:
+        if table_hints.dtype != torch.uint8 or table_hints.numel() != num_tables:
+            raise ValueError("table_hints must be a uint8 tensor with one entry per table")
     return emb_bag_desc(num_tables=num_tables, dim=dim, table_dtype=table_dtype, mode=mode,
                         batch=batch, num_lookups=num_lookups, out_ld=out_ld,
-                        max_table_rows=max_table_rows)
+                        max_table_rows=max_table_rows, table_hints=_ptr(table_hints))
 
 
 def emb_bag_forward(desc: emb_bag_desc, tables: torch.Tensor, table_offsets: torch.Tensor,
@@ -104,6 +116,18 @@ def emb_bag_validate(desc: emb_bag_desc, table_offsets: torch.Tensor, indices: t
                                _ptr(offsets), _ptr(num_bad), _stream_handle(stream))
     if rc != EMB_OK:
         raise EmbBagError(rc, "emb_bag_validate")
+
+
+def emb_bag_profile_reuse(desc: emb_bag_desc, indices: torch.Tensor, offsets: torch.Tensor,
+                          window: int, threshold_permille: int,
+                          dup_count: Optional[torch.Tensor], window_used: Optional[torch.Tensor],
+                          hints: Optional[torch.Tensor], stream=None) -> None:
+    """Enqueue the per-table repeat count / hint derivation (device int32[T], int32[T], uint8[T])."""
+    rc = _lib.emb_bag_profile_reuse(ctypes.byref(desc), _ptr(indices), _ptr(offsets), int(window),
+                                    int(threshold_permille), _ptr(dup_count), _ptr(window_used),
+                                    _ptr(hints), _stream_handle(stream))
+    if rc != EMB_OK:
+        raise EmbBagError(rc, "emb_bag_profile_reuse")
 
 
 def emb_bag_set_tuning(key: str, value: int) -> None:

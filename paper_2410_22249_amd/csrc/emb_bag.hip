@@ -56,6 +56,7 @@ struct KParams {
   uint32_t row_bytes;
   uint32_t D;
   uint32_t mean;         // 1 = divide by bag length
+  uint32_t has_hints;    // 1 = table_hints points to T bytes
   // XCD-affine block order (xcd_bpp = 0: natural order).  Every table is cut into 2^xcd_pshift
   // pieces of xcd_wpp wavefronts (xcd_bpp workgroups); piece u = t * 2^xcd_pshift + k runs on
   // XCD u % 8, and an XCD takes its pieces in increasing u.
@@ -109,13 +110,77 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w) {
   }
 }
 
+// The gather of one bag (one column slab of it): walk the bag's lookups in chunks of 64 and add
+// the rows into acc.  NT selects the non-temporal cache policy for the row loads (tables whose
+// rows are not re-used within a batch), the default policy otherwise.
+template <int LPR, bool F16, int DEPTH, bool WEIGHTED, bool BUF, bool NT>
+__device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict__ indices,
+                                           const float* __restrict__ weights, int64_t s,
+                                           int64_t e, int64_t R, uint32_t row_bytes,
+                                           const char* tbase, __amdgpu_buffer_rsrc_t rsrc,
+                                           int lane, int g, uint32_t col, bool lane_ok) {
+  constexpr int G = kWaveSize / LPR;
+  constexpr int kAux = NT ? 2 : 0;  // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
+  for (int64_t c = s; c < e; c += kWaveSize) {
+    const int64_t left = e - c;
+    const int n = left < kWaveSize ? (int)left : kWaveSize;  // lookups in this chunk (uniform)
+    int64_t idx = -1;
+    float w = 0.0f;
+    if (lane < n) {
+      idx = __builtin_nontemporal_load(indices + c + lane);
+      if constexpr (WEIGHTED) w = __builtin_nontemporal_load(weights + c + lane);
+    }
+    const bool idx_ok = (uint64_t)idx < (uint64_t)R;
+    uint32_t voff = kBufSentinel;  // BUF: 32-bit byte offset of the row inside the table
+    int64_t roff = -1;             // !BUF: 64-bit byte offset, -1 = skip
+    if constexpr (BUF) {
+      if (idx_ok) voff = (uint32_t)idx * row_bytes;
+    } else {
+      if (idx_ok) roff = idx * (int64_t)row_bytes;
+    }
+
+    const int steps = (n + G - 1) / G;
+    for (int k0 = 0; k0 < steps; k0 += DEPTH) {
+      u32x4 r[DEPTH];
+      float wj[DEPTH];
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        const int j = (k0 + d) * G + g;  // lookup of this chunk served by this lane's group
+        const bool take = (j < n) && lane_ok;
+        if constexpr (BUF) {
+          uint32_t vo = (uint32_t)__shfl((int)voff, j & (kWaveSize - 1));
+          vo = take ? vo : kBufSentinel;
+          r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
+        } else {
+          const int64_t ro = shfl64(roff, j & (kWaveSize - 1));
+          u32x4 v = {0u, 0u, 0u, 0u};
+          if (take && ro >= 0) {
+            const u32x4* src = reinterpret_cast<const u32x4*>(tbase + ro + col);
+            v = NT ? __builtin_nontemporal_load(src) : *src;
+          }
+          r[d] = v;
+        }
+        if constexpr (WEIGHTED) {
+          const float ws = __shfl(w, j & (kWaveSize - 1));
+          wj[d] = (j < n) ? ws : 0.0f;
+        } else {
+          wj[d] = 1.0f;
+        }
+      }
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) accumulate<F16, WEIGHTED>(acc, r[d], wj[d]);
+    }
+  }
+
+}
+
 // One wavefront per (bag, column slab).  LPR = lanes per row (power of two, 4..64).
 template <int LPR, bool F16, int DEPTH, bool WEIGHTED, bool BUF>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
-                    const float* __restrict__ weights, float* __restrict__ out, KParams p) {
-  constexpr int G = kWaveSize / LPR;  // rows of the bag served by one load instruction
+                    const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
+                    float* __restrict__ out, KParams p) {
   constexpr int NACC = F16 ? 8 : 4;   // fp32 accumulators per lane
 
   const int lane = threadIdx.x & (kWaveSize - 1);
@@ -161,62 +226,20 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
   const bool lane_ok = col < p.row_bytes;
 
   const char* tbase = tables + row0 * (int64_t)p.row_bytes;
-  __amdgpu_buffer_rsrc_t rsrc;
-  if constexpr (BUF)
-    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(tbase), 0,
-                                             (uint32_t)((uint64_t)R * p.row_bytes), kBufWord3);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(tbase), 0, BUF ? (uint32_t)((uint64_t)R * p.row_bytes) : 0u, kBufWord3);
 
   float acc[NACC];
 #pragma unroll
   for (int i = 0; i < NACC; ++i) acc[i] = 0.0f;
 
-  for (int64_t c = s; c < e; c += kWaveSize) {
-    const int64_t left = e - c;
-    const int n = left < kWaveSize ? (int)left : kWaveSize;  // lookups in this chunk (uniform)
-    int64_t idx = -1;
-    float w = 0.0f;
-    if (lane < n) {
-      idx = __builtin_nontemporal_load(indices + c + lane);
-      if constexpr (WEIGHTED) w = __builtin_nontemporal_load(weights + c + lane);
-    }
-    const bool idx_ok = (uint64_t)idx < (uint64_t)R;
-    uint32_t voff = kBufSentinel;  // BUF: 32-bit byte offset of the row inside the table
-    int64_t roff = -1;             // !BUF: 64-bit byte offset, -1 = skip
-    if constexpr (BUF) {
-      if (idx_ok) voff = (uint32_t)idx * p.row_bytes;
-    } else {
-      if (idx_ok) roff = idx * (int64_t)p.row_bytes;
-    }
-
-    const int steps = (n + G - 1) / G;
-    for (int k0 = 0; k0 < steps; k0 += DEPTH) {
-      u32x4 r[DEPTH];
-      float wj[DEPTH];
-#pragma unroll
-      for (int d = 0; d < DEPTH; ++d) {
-        const int j = (k0 + d) * G + g;  // lookup of this chunk served by this lane's group
-        const bool take = (j < n) && lane_ok;
-        if constexpr (BUF) {
-          uint32_t vo = (uint32_t)__shfl((int)voff, j & (kWaveSize - 1));
-          vo = take ? vo : kBufSentinel;
-          r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, 0);
-        } else {
-          const int64_t ro = shfl64(roff, j & (kWaveSize - 1));
-          u32x4 v = {0u, 0u, 0u, 0u};
-          if (take && ro >= 0) v = *reinterpret_cast<const u32x4*>(tbase + ro + col);
-          r[d] = v;
-        }
-        if constexpr (WEIGHTED) {
-          const float ws = __shfl(w, j & (kWaveSize - 1));
-          wj[d] = (j < n) ? ws : 0.0f;
-        } else {
-          wj[d] = 1.0f;
-        }
-      }
-#pragma unroll
-      for (int d = 0; d < DEPTH; ++d) accumulate<F16, WEIGHTED>(acc, r[d], wj[d]);
-    }
-  }
+  const bool streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
+  if (streaming)
+    gather_bag<LPR, F16, DEPTH, WEIGHTED, BUF, true>(acc, indices, weights, s, e, R, p.row_bytes,
+                                                     tbase, rsrc, lane, g, col, lane_ok);
+  else
+    gather_bag<LPR, F16, DEPTH, WEIGHTED, BUF, false>(acc, indices, weights, s, e, R, p.row_bytes,
+                                                      tbase, rsrc, lane, g, col, lane_ok);
 
   // combine the G row groups (fixed butterfly: every lane ends with the same bits)
 #pragma unroll
@@ -279,6 +302,60 @@ emb_bag_validate_kernel(const int64_t* __restrict__ table_offsets,
   if (lane == 0 && bad) atomicAdd(num_bad, bad);
 }
 
+// One workgroup per table: insert the first `window` lookups of the table into an open-addressing
+// hash set in LDS (64-bit compare-and-swap, linear probing) and count the inserts that find their
+// key already present.  The count does not depend on the order of the inserts.
+constexpr int kProfileThreads = 1024;
+constexpr int kProfileMaxWindow = 4096;
+constexpr uint32_t kProfileSlots = 6144;  // load factor <= 2/3: every probe sequence ends
+
+__global__ void __launch_bounds__(kProfileThreads)
+emb_bag_profile_kernel(const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
+                       int32_t* __restrict__ dup_count, int32_t* __restrict__ window_used,
+                       uint8_t* __restrict__ hints, int64_t num_lookups, uint32_t B,
+                       int32_t window, int32_t threshold_permille) {
+  __shared__ unsigned long long slots[kProfileSlots];
+  __shared__ int dups;
+  constexpr unsigned long long kEmpty = ~0ull;
+  const uint32_t t = blockIdx.x;
+  for (uint32_t i = threadIdx.x; i < kProfileSlots; i += kProfileThreads) slots[i] = kEmpty;
+  if (threadIdx.x == 0) dups = 0;
+  __syncthreads();
+
+  int64_t s = offsets[(uint64_t)t * B];
+  int64_t e = offsets[(uint64_t)(t + 1) * B];
+  s = s < 0 ? 0 : (s > num_lookups ? num_lookups : s);
+  e = e < s ? s : (e > num_lookups ? num_lookups : e);
+  const int64_t n64 = e - s;
+  const int n = n64 < window ? (int)n64 : window;
+
+  int mine = 0;
+  for (int i = threadIdx.x; i < n; i += kProfileThreads) {
+    const unsigned long long key = (unsigned long long)indices[s + i];
+    if (key == kEmpty) continue;  // the id -1 is never valid; it is counted as distinct
+    uint32_t slot = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> 40) % kProfileSlots;
+    for (uint32_t probe = 0; probe < kProfileSlots; ++probe) {
+      const unsigned long long old = atomicCAS(&slots[slot], kEmpty, key);
+      if (old == kEmpty) break;
+      if (old == key) {
+        ++mine;
+        break;
+      }
+      slot = slot + 1 == kProfileSlots ? 0 : slot + 1;
+    }
+  }
+  if (mine) atomicAdd(&dups, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int d = dups;
+    if (dup_count) dup_count[t] = d;
+    if (window_used) window_used[t] = n;
+    if (hints)
+      hints[t] = ((int64_t)d * 1000 < (int64_t)threshold_permille * n || n == 0)
+                     ? EMB_HINT_STREAMING : EMB_HINT_DEFAULT;
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
@@ -288,11 +365,12 @@ struct Tuning {
   int64_t blocks_per_cu = 0;
   int64_t xcd_remap = -1;
   int64_t kernel = 0;
+  int64_t use_hints = 1;
 };
 Tuning g_tuning;
 
 using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int64_t*,
-                          const float*, float*, KParams);
+                          const float*, const uint8_t*, float*, KParams);
 
 template <int LPR, bool F16, int DEPTH>
 KernelFn pick_wb(bool weighted, bool buf) {
@@ -394,6 +472,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   p.row_bytes = row_bytes;
   p.D = (uint32_t)D;
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
+  p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
   p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = 0;
 
   uint32_t blocks = (uint32_t)((num_work + kWavesPerBlock - 1) / kWavesPerBlock);
@@ -433,7 +512,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
 
   hipLaunchKernelGGL(fn, dim3(blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
                      static_cast<const char*>(tables), table_offsets, indices, offsets,
-                     per_sample_weights, out, p);
+                     per_sample_weights, desc->table_hints, out, p);
   return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
 }
 
@@ -457,6 +536,27 @@ int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
   return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
 }
 
+int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
+                          const int64_t* offsets, int32_t window, int32_t threshold_permille,
+                          int32_t* dup_count, int32_t* window_used, uint8_t* hints,
+                          void* stream) {
+  uint32_t row_bytes = 0;
+  const int rc = check_desc(desc, &row_bytes);
+  if (rc != EMB_OK) return rc;
+  const int64_t T = desc->num_tables, B = desc->batch;
+  if (B == 0) return EMB_OK;
+  if (!offsets) return EMB_ERR_NULL_PTR;
+  if (desc->num_lookups > 0 && !indices) return EMB_ERR_NULL_PTR;
+  if (B > 0x7FFFFFFF || T * B > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
+  if (window < 1) window = 1;
+  if (window > kProfileMaxWindow) window = kProfileMaxWindow;
+  if (threshold_permille < 0) threshold_permille = 20;
+  hipLaunchKernelGGL(emb_bag_profile_kernel, dim3((uint32_t)T), dim3(kProfileThreads), 0,
+                     static_cast<hipStream_t>(stream), indices, offsets, dup_count, window_used,
+                     hints, desc->num_lookups, (uint32_t)B, window, threshold_permille);
+  return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
+}
+
 int emb_bag_set_tuning(const char* key, int64_t value) {
   if (!key) return EMB_ERR_NULL_PTR;
   if (!strcmp(key, "depth")) {
@@ -475,6 +575,9 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
   } else if (!strcmp(key, "kernel")) {
     if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
     g_tuning.kernel = value;
+  } else if (!strcmp(key, "use_hints")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    g_tuning.use_hints = value;
   } else {
     return EMB_ERR_BAD_TUNING;
   }
@@ -488,6 +591,7 @@ int emb_bag_get_tuning(const char* key, int64_t* value) {
   else if (!strcmp(key, "blocks_per_cu")) *value = g_tuning.blocks_per_cu;
   else if (!strcmp(key, "xcd_remap")) *value = g_tuning.xcd_remap;
   else if (!strcmp(key, "kernel")) *value = g_tuning.kernel;
+  else if (!strcmp(key, "use_hints")) *value = g_tuning.use_hints;
   else return EMB_ERR_BAD_TUNING;
   return EMB_OK;
 }
@@ -508,6 +612,6 @@ const char* emb_bag_status_string(int status) {
   }
 }
 
-int emb_bag_version(void) { return 100; }
+int emb_bag_version(void) { return 200; }
 
 }  // extern "C"

@@ -42,8 +42,9 @@ def test_status_codes_and_strings_match_header():
 
 def test_desc_layout_matches_header():
     import paper_2410_22249_amd as emb
-    assert ctypes.sizeof(emb.emb_bag_desc) == 4 * 4 + 4 * 8
+    assert ctypes.sizeof(emb.emb_bag_desc) == 4 * 4 + 4 * 8 + 8
     assert emb.emb_bag_desc.batch.offset == 16 and emb.emb_bag_desc.max_table_rows.offset == 40
+    assert emb.emb_bag_desc.table_hints.offset == 48
 
 
 def test_generator_library_exports():
@@ -84,6 +85,9 @@ def test_host_side_argument_errors():
     assert fwd(emb.make_desc(**ok), tables=ctypes.c_void_p(0x1008)) == -8
     assert fwd(emb.make_desc(**{**ok, "batch": 1 << 31})) == -7
     assert fwd(emb.make_desc(**{**ok, "batch": 0}), tables=None, out=None) == 0   # no-op
+    assert lib.emb_bag_profile_reuse(None, fake, fake, 64, 20, fake, fake, fake, None) == -1
+    assert lib.emb_bag_profile_reuse(ctypes.byref(emb.make_desc(**ok)), fake, None, 64, 20, fake,
+                                     fake, fake, None) == -1
     assert lib.emb_bag_validate(None, fake, fake, fake, fake, None) == -1
     assert lib.emb_bag_validate(ctypes.byref(emb.make_desc(**ok)), fake, fake, fake, None, None) == -1
 
@@ -91,7 +95,7 @@ def test_host_side_argument_errors():
 def test_tuning_keys():
     import paper_2410_22249_amd as emb
     for key, good, bad in (("depth", 8, 3), ("addressing", 1, 5), ("blocks_per_cu", 2, 9),
-                           ("xcd_remap", 1, 2), ("kernel", 1, 9)):
+                           ("xcd_remap", 1, 2), ("kernel", 1, 9), ("use_hints", 0, 2)):
         old = emb.emb_bag_get_tuning(key)
         emb.emb_bag_set_tuning(key, good)
         assert emb.emb_bag_get_tuning(key) == good

@@ -71,6 +71,24 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     sel = torch.from_numpy(np.stack([bags % wl.B, bags // wl.B], 1)).to(DEV)
     got = out.view(wl.B, wl.T, wl.D)[sel[:, 0], sel[:, 1]].cpu().numpy()
     worst = assert_close_to_oracle(got, ref, bound, wl.dtype == "f16", f"{name} sampled")
+    # hints from the device-side profiler: what the benchmark uses; classification as expected
+    from oracle import reuse_oracle
+    hints = torch.zeros(wl.T, dtype=torch.uint8, device=DEV)
+    dup = torch.zeros(wl.T, dtype=torch.int32, device=DEV)
+    used = torch.zeros(wl.T, dtype=torch.int32, device=DEV)
+    emb.emb_bag_profile_reuse(desc, idx, off, 4096, -1, dup, used, hints)
+    torch.cuda.synchronize()
+    rd, ru, rh = reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B, 4096, 20)
+    assert np.array_equal(dup.cpu().numpy(), rd) and np.array_equal(used.cpu().numpy(), ru)
+    assert np.array_equal(hints.cpu().numpy(), rh)
+    expect = np.array([1 if d[0] == "uniform" else 0 for d in wl.dists], dtype=np.uint8)
+    assert np.array_equal(rh, expect), "uniform tables stream, skewed tables stay cached"
+    hdesc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32,
+                          emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, batch.num_lookups,
+                          0, max(wl.rows), hints)
+    emb.emb_bag_forward(hdesc, arena, toff, idx, off, None, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2), "hints must not change results"
     # the alternative launch shapes give the same bits at full size too
     for kw in (dict(xcd_remap=1), dict(addressing=1, depth=8)):
         with tuning(**kw):

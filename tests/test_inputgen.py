@@ -127,3 +127,20 @@ def test_config_sizes_match_the_stated_shapes():
     p = gen.workload("paper")
     g = GOLD["bytes_per_table"]
     assert (p.B, p.pooling[1], p.D, p.elem_bytes) == (g["batch"], g["lookups_per_sample"], g["dim"], g["elem_bytes"])
+
+
+def test_hotness_ladder_matches_the_papers_unique_access_table():
+    """Sec. 3.2 table: unique access % 4.05 / 20.50 / 46.21 for high / med / low hot."""
+    R = GOLD["unique_access_pct"]["rows"]
+    want = {"paper_high": 4.05, "paper_med": 20.50, "paper_low": 46.21}
+    for name, pct in want.items():
+        alpha = gen.PAPER_HOTNESS_ALPHA[name]
+        assert abs(100 * gen.expected_unique_fraction(R, alpha, R) - pct) < 0.05
+    # and by sampling, for one of them
+    rng = np.random.Generator(np.random.Philox(key=np.array([3, 4], dtype=np.uint64)))
+    ranks = gen.zipf_ranks(rng, R, gen.PAPER_HOTNESS_ALPHA["paper_med"], R)
+    assert abs(100 * len(np.unique(ranks)) / R - 20.50) < 0.3
+    for name, counts in gen.PAPER_MIXES.items():
+        wl = gen.workload(name)
+        assert wl.T == sum(counts) == 250
+        assert sum(d[0] == "uniform" for d in wl.dists) == counts[3]

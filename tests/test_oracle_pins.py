@@ -338,3 +338,35 @@ def test_thread_count_does_not_change_result(oracle):
     finally:
         oracle.set_num_threads(n)
     assert np.array_equal(r1, r2) and np.array_equal(b1, b2)
+
+
+# ---- the reuse-profile oracle (integer work) -------------------------------------------------
+def test_reuse_profile_hand_worked():
+    from oracle import reuse_oracle
+    # T = 2, B = 2.  table 0 lookups: [5,5,7,5 | 9]  table 1 lookups: [ | 1,2,3]
+    idx = np.array([5, 5, 7, 5, 9, 1, 2, 3], dtype=np.int64)
+    off = np.array([0, 4, 5, 5, 8], dtype=np.int64)
+    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 2, 2, 4096, 20)
+    assert dup.tolist() == [2, 0] and used.tolist() == [5, 3] and hints.tolist() == [0, 1]
+    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 2, 2, 2, 20)     # window of 2
+    assert dup.tolist() == [1, 0] and used.tolist() == [2, 2] and hints.tolist() == [0, 1]
+    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 2, 2, 4096, 500)  # 50 % threshold
+    assert hints.tolist() == [1, 1]                                          # 2/5 < 50 %
+    # a table that receives nothing is "streaming"
+    dup, used, hints = reuse_oracle.profile_reuse(np.zeros(0, np.int64), np.zeros(3, np.int64), 2, 1, 8)
+    assert used.tolist() == [0, 0] and hints.tolist() == [1, 1]
+
+
+def test_reuse_profile_closed_forms():
+    from oracle import reuse_oracle
+    n = 3000
+    off = np.array([0, n, 2 * n, 3 * n], dtype=np.int64)
+    rng = np.random.default_rng(3)
+    uni = rng.integers(0, 4_000_000, size=n)
+    idx = np.concatenate([np.arange(n), np.full(n, 42), uni]).astype(np.int64)
+    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 3, 1, 4096)
+    assert used.tolist() == [n, n, n]
+    assert dup[0] == 0 and dup[1] == n - 1
+    # birthday problem: expected repeats of n uniform draws over R rows is about n^2 / (2R) = 1.1
+    assert dup[2] == n - len(np.unique(uni)) and dup[2] < 12
+    assert hints.tolist() == [1, 0, 1]

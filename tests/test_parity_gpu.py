@@ -309,3 +309,64 @@ def test_forward_replays_correctly_from_a_hip_graph(oracle):
         assert np.array_equal(got, eager)
         ref, bound = oracle.emb_bag(gen.host_arena(wl), wl.table_offsets(), b.indices, b.offsets, wl.B)
         assert_close_to_oracle(got, ref, bound, False, "graph replay")
+
+
+def test_table_hints_change_speed_only(oracle):
+    """Streaming hints switch the cache policy of the row loads; results must not move a bit."""
+    import paper_2410_22249_amd as emb
+    for name in ("small_f32_d64", "small_f32_d128", "small_f16_d256"):
+        wl = gen.workload(name)
+        batch = gen.make_batches(wl, 1)[0]
+        host = gen.host_arena(wl)
+        arena = upload_arena(host)
+        toff, idx, off = to_dev(wl.table_offsets()), to_dev(batch.indices), to_dev(batch.offsets)
+        ref, bound = oracle.emb_bag(host, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
+        outs = []
+        for hints_np in (None, np.zeros(wl.T, np.uint8), np.ones(wl.T, np.uint8),
+                         (np.arange(wl.T) % 2).astype(np.uint8)):
+            hints = None if hints_np is None else to_dev(hints_np)
+            for addressing in (0, 1):
+                out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
+                desc = emb.make_desc(wl.T, wl.B, wl.D,
+                                     emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32,
+                                     emb.EMB_SUM, batch.num_lookups, 0, max(wl.rows), hints)
+                with tuning(addressing=addressing):
+                    emb.emb_bag_forward(desc, arena, toff, idx, off, None, out)
+                torch.cuda.synchronize()
+                outs.append(out.cpu().numpy())
+        assert_close_to_oracle(outs[0], ref, bound, wl.dtype == "f16", f"{name}/hints")
+        for o in outs[1:]:
+            assert np.array_equal(o, outs[0])
+
+
+def test_reuse_profile_matches_oracle_bit_for_bit():
+    import paper_2410_22249_amd as emb
+    from oracle import reuse_oracle
+    cases = [gen.workload("small_f32_d64"), gen.workload("small_f32_d128"),
+             gen.Workload(name="prof", T=9, rows=(4_000_000, 50, 1, 100_000, 7, 4_000_000, 300, 9, 2),
+                          D=64, dtype="f32", B=40, pooling=("uniform", 0, 300),
+                          dists=(("uniform",), ("uniform",), ("one_item",), ("zipf", 1.05),
+                                 ("uniform",), ("zipf", 1.2), ("zipf", 0.7), ("uniform",),
+                                 ("one_item",)), seed=0x5EED0500)]
+    for wl in cases:
+        batch = gen.make_batches(wl, 1)[0]
+        idx, off = to_dev(batch.indices), to_dev(batch.offsets)
+        desc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups)
+        for window, thr in ((4096, 20), (100, 20), (1, 20), (5000, 500), (333, -1)):
+            dup = torch.full((wl.T,), -1, dtype=torch.int32, device=DEV)
+            used = torch.full((wl.T,), -1, dtype=torch.int32, device=DEV)
+            hints = torch.full((wl.T,), 9, dtype=torch.uint8, device=DEV)
+            emb.emb_bag_profile_reuse(desc, idx, off, window, thr, dup, used, hints)
+            torch.cuda.synchronize()
+            rd, ru, rh = reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B,
+                                                    window, 20 if thr < 0 else thr)
+            assert np.array_equal(dup.cpu().numpy(), rd), (wl.name, window)
+            assert np.array_equal(used.cpu().numpy(), ru)
+            assert np.array_equal(hints.cpu().numpy(), rh)
+    # no lookups at all
+    desc = emb.make_desc(3, 4, 64, emb.EMB_F32, emb.EMB_SUM, 0)
+    hints = torch.full((3,), 9, dtype=torch.uint8, device=DEV)
+    emb.emb_bag_profile_reuse(desc, None, torch.zeros(13, dtype=torch.int64, device=DEV), 64, 20,
+                              None, None, hints)
+    torch.cuda.synchronize()
+    assert hints.cpu().tolist() == [1, 1, 1]
