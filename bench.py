@@ -261,6 +261,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": metrics.HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / metrics.HBM_PEAK_GBPS,
                      "traffic": traffic,
+                     "traffic_GBps": None if traffic is None else traffic / avg_kern_s / 1e9,
                      "algorithmic_bytes_per_launch": algo,
                      "gathered_bytes_per_launch": gathered},
         "cpu_baseline": cpu_baseline,

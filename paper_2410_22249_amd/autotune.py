@@ -1,0 +1,144 @@
+"""Occupancy x prefetch-depth x cache-policy sweep for one workload shape.
+
+The paper closes with a static profiling recipe (Sec. 7): check whether the kernel is latency- or
+bandwidth-bound, sweep the multithreading level, sweep the prefetch station and distance ("low
+multithreading => larger distance"), decide on pinning from the reuse of the access pattern, and
+combine.  This tool runs that recipe on the MI355X kernels through the public tuning keys:
+
+    python -m paper_2410_22249_amd.autotune --workload cfg3 [--out tuning.json]
+
+It prints one line per setting and a recommendation; `--out` writes the best setting as JSON that
+`apply_tuning()` feeds to `emb_bag_set_tuning`.  Inputs are the seeded synthetic workloads of
+`inputgen`; timing uses HIP events on the launch stream and rotates index batches.
+"""
+from __future__ import annotations
+
+import argparse
+import itertools
+import json
+import os
+import sys
+from typing import Dict, List
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+DEFAULT_GRID = {
+    "blocks_per_cu": [0, 4, 2],        # waves per SIMD: 8 (no cap), 4, 2
+    "depth": [1, 2, 4, 8, 16],
+    "use_hints": [1, 0],
+    "xcd_remap": [1, 0],
+}
+NEUTRAL = {"blocks_per_cu": 0, "depth": 0, "use_hints": 1, "xcd_remap": -1, "addressing": 0}
+
+
+def apply_tuning(settings: Dict[str, int]) -> None:
+    """Apply a {key: value} mapping (e.g. loaded from the JSON this tool writes)."""
+    from . import emb_bag_set_tuning
+    for k, v in settings.items():
+        emb_bag_set_tuning(k, int(v))
+
+
+def _setup(name: str, n_batches: int):
+    import torch
+    import paper_2410_22249_amd as emb
+    from inputgen import gen
+
+    wl = gen.workload(name)
+    dev = "cuda:0"
+    arena = torch.empty((wl.total_rows, wl.D),
+                        dtype=torch.float16 if wl.dtype == "f16" else torch.float32, device=dev)
+    gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed, wl.kind,
+                          torch.cuda.current_stream().cuda_stream)
+    batches = gen.make_batches(wl, n_batches)
+    toff = torch.from_numpy(wl.table_offsets()).to(dev)
+    dev_batches = [(torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev),
+                    None if b.weights is None else torch.from_numpy(b.weights).to(dev))
+                   for b in batches]
+    edt = emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32
+    emode = emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM
+    hints = torch.zeros(wl.T, dtype=torch.uint8, device=dev)
+    d0 = emb.make_desc(wl.T, wl.B, wl.D, edt, emode, batches[0].num_lookups, 0, max(wl.rows))
+    emb.emb_bag_profile_reuse(d0, dev_batches[0][0], dev_batches[0][1], 4096, -1, None, None, hints)
+    descs = [emb.make_desc(wl.T, wl.B, wl.D, edt, emode, b.num_lookups, 0, max(wl.rows), hints)
+             for b in batches]
+    out = torch.empty((wl.B, wl.T * wl.D), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    return wl, arena, toff, dev_batches, descs, out, batches, hints
+
+
+def _time(state, steps: int, warmup: int) -> float:
+    """Average kernel time in seconds over `steps` launches."""
+    import torch
+    import paper_2410_22249_amd as emb
+    wl, arena, toff, dev_batches, descs, out, batches, _ = state
+    n = len(dev_batches)
+    for i in range(warmup):
+        k = i % n
+        emb.emb_bag_forward(descs[k], arena, toff, dev_batches[k][0], dev_batches[k][1],
+                            dev_batches[k][2], out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        k = (warmup + i) % n
+        emb.emb_bag_forward(descs[k], arena, toff, dev_batches[k][0], dev_batches[k][1],
+                            dev_batches[k][2], out)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps / 1e3
+
+
+def main(argv: List[str] = None) -> int:
+    ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batches", type=int, default=4)
+    ap.add_argument("--grid", default=None, help='JSON, e.g. \'{"depth":[2,8],"blocks_per_cu":[0,2]}\'')
+    ap.add_argument("--out", default=None)
+    a = ap.parse_args(argv)
+
+    import numpy as np
+    import paper_2410_22249_amd as emb
+    from paper_2410_22249_amd import metrics
+
+    grid = json.loads(a.grid) if a.grid else DEFAULT_GRID
+    keys = list(grid)
+    state = _setup(a.workload, a.batches)
+    wl, batches, hints = state[0], state[6], state[7]
+    nl = float(np.mean([b.num_lookups for b in batches]))
+    gathered = metrics.gathered_bytes(nl, wl.D, wl.elem_bytes)
+    print(f"# {a.workload}: {nl:.0f} lookups/launch, {gathered / 1e9:.3f} GB gathered, "
+          f"{int(hints.sum().item())}/{wl.T} tables classified streaming")
+    results = []
+    try:
+        for combo in itertools.product(*[grid[k] for k in keys]):
+            setting = dict(zip(keys, combo))
+            apply_tuning({**NEUTRAL, **setting})
+            t = _time(state, a.steps, a.warmup)
+            results.append((t, setting))
+            print(f"{json.dumps(setting):70s} {t * 1e6:10.1f} us  {nl / t / 1e9:7.2f} G lookups/s  "
+                  f"{gathered / t / 1e9:8.0f} GB/s ({100 * gathered / t / 1e9 / metrics.HBM_PEAK_GBPS:5.1f} % of peak)",
+                  flush=True)
+    finally:
+        apply_tuning(NEUTRAL)
+    best_t, best = min(results, key=lambda r: r[0])
+    print(f"# best: {json.dumps(best)} at {best_t * 1e6:.1f} us")
+    # Sec. 7, first step: latency- or bandwidth-bound?  If lowering occupancy at the largest depth
+    # costs nothing, memory-level parallelism is not the limit.
+    if "blocks_per_cu" in grid and "depth" in grid and len(grid["blocks_per_cu"]) > 1:
+        full = min(t for t, s in results if s["blocks_per_cu"] == grid["blocks_per_cu"][0])
+        low = min(t for t, s in results if s["blocks_per_cu"] == grid["blocks_per_cu"][-1])
+        verdict = "bandwidth-bound" if low < 1.03 * full else "latency-sensitive"
+        print(f"# occupancy cap {grid['blocks_per_cu'][-1]} workgroups/CU costs "
+              f"{100 * (low / full - 1):.1f} % at its best depth: {verdict}")
+    if a.out:
+        with open(a.out, "w") as f:
+            json.dump({"workload": a.workload, "tuning": best, "kernel_us": best_t * 1e6}, f, indent=1)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

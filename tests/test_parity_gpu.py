@@ -370,3 +370,39 @@ def test_reuse_profile_matches_oracle_bit_for_bit():
                               None, None, hints)
     torch.cuda.synchronize()
     assert hints.cpu().tolist() == [1, 1, 1]
+
+
+def test_randomised_shapes(oracle):
+    """Forty seeded random problems: table counts, row counts, widths, batch sizes, pooling ranges,
+    dtypes, modes, weights, padded leading dimensions, addressing and launch knobs drawn at random."""
+    rng = np.random.default_rng(0xE3B)
+    for case in range(40):
+        dtype = "f16" if rng.random() < 0.4 else "f32"
+        unit = 8 if dtype == "f16" else 4
+        D = int(unit * rng.integers(1, 80))                      # rows of 16 B .. 1264 B
+        T = int(rng.integers(1, 12))
+        rows = tuple(int(x) for x in rng.integers(1, 3000, size=T))
+        B = int(rng.integers(1, 90))
+        lo = int(rng.integers(0, 4))
+        hi = lo + int(rng.choice([0, 3, 40, 150, 400]))
+        mode = "mean" if rng.random() < 0.4 else "sum"
+        weighted = mode == "sum" and rng.random() < 0.4
+        dists = tuple((("uniform",), ("zipf", 1.1), ("one_item",))[int(rng.integers(0, 3))]
+                      for _ in range(T))
+        wl = gen.Workload(name=f"rnd{case}", T=T, rows=rows, D=D, dtype=dtype, B=B,
+                          pooling=("uniform", lo, hi), dists=dists, mode=mode, weighted=weighted,
+                          seed=0x5EED0600 + case)
+        batch = gen.make_batches(wl, 1)[0]
+        host = gen.host_arena(wl)
+        pad = int(rng.choice([0, 4, 64]))
+        ld = T * D + pad
+        ref, bound = oracle.emb_bag(host, wl.table_offsets(), batch.indices, batch.offsets, B,
+                                    mode, weights=batch.weights, out_ld=ld)
+        kw = dict(addressing=int(rng.integers(0, 2)), depth=int(rng.choice([0, 1, 2, 4, 8, 16])),
+                  xcd_remap=int(rng.integers(-1, 2)), blocks_per_cu=int(rng.choice([0, 0, 3])))
+        with tuning(**kw):
+            got = forward(upload_arena(host), wl.table_offsets(), batch.indices, batch.offsets, B,
+                          mode, weights=batch.weights, out_ld=ld, fill=-3.0).cpu().numpy()
+        what = f"case {case}: T={T} D={D} {dtype} B={B} L=[{lo},{hi}] {mode} w={weighted} {kw}"
+        assert np.all(got[:, T * D:] == -3.0), what
+        assert_close_to_oracle(got[:, :T * D], ref[:, :T * D], bound[:, :T * D], dtype == "f16", what)
