@@ -35,6 +35,12 @@ def build_all(verbose: bool = True) -> None:
             raise RuntimeError(f"hipcc failed for {out}")
 
 
+def ensure_built(verbose: bool = True) -> None:
+    """Build only if a library is missing (tests, smoke() and bench.py load what is there)."""
+    if not all(os.path.exists(os.path.join(ROOT, out)) for out in TARGETS):
+        build_all(verbose=verbose)
+
+
 if __name__ == "__main__":
     build_all()
     sys.exit(0)
