@@ -406,3 +406,49 @@ def test_randomised_shapes(oracle):
         what = f"case {case}: T={T} D={D} {dtype} B={B} L=[{lo},{hi}] {mode} w={weighted} {kw}"
         assert np.all(got[:, T * D:] == -3.0), what
         assert_close_to_oracle(got[:, :T * D], ref[:, :T * D], bound[:, :T * D], dtype == "f16", what)
+
+
+def test_gpu_invariants_without_the_oracle():
+    """The invariants that pin the oracle also hold for the HIP path on its own."""
+    rng = np.random.default_rng(41)
+    # identity tables: output = histogram of the bag's indices (exact)
+    T, D, B = 3, 64, 50
+    tables = np.concatenate([np.eye(D, dtype=np.float32)] * T)
+    toff = np.arange(T + 1, dtype=np.int64) * D
+    lengths = rng.integers(0, 200, size=T * B)
+    offsets = gen.lengths_to_offsets(lengths)
+    idx = rng.integers(0, D, size=int(offsets[-1])).astype(np.int64)
+    dev = upload_arena(tables)
+    got = forward(dev, toff, idx, offsets, B).cpu().numpy()
+    for t in range(T):
+        for b in range(B):
+            s, e = offsets[t * B + b], offsets[t * B + b + 1]
+            assert np.array_equal(got[b, t * D:(t + 1) * D], np.bincount(idx[s:e], minlength=D))
+    # mean = sum / len (one correctly rounded division), empty bags exactly +0
+    tables = rng.normal(0, 0.1, size=(T * D, D)).astype(np.float32)
+    dev = upload_arena(tables)
+    s_out = forward(dev, toff, idx, offsets, B, "sum").cpu().numpy()
+    m_out = forward(dev, toff, idx, offsets, B, "mean").cpu().numpy()
+    L = lengths.reshape(T, B).T                                         # [B, T]
+    Lcol = np.repeat(L, D, axis=1).astype(np.float32)
+    want = np.where(Lcol > 0, s_out / np.maximum(Lcol, 1), 0).astype(np.float32)
+    assert np.array_equal(m_out, want)
+    assert not np.signbit(m_out[Lcol == 0]).any()
+    # permutation invariance inside a bag: exact on integer tables, within tolerance otherwise
+    itab = rng.integers(-8, 8, size=tables.shape).astype(np.float32)
+    idx2 = idx.copy()
+    for gbag in range(T * B):
+        a, b_ = offsets[gbag], offsets[gbag + 1]
+        idx2[a:b_] = rng.permutation(idx2[a:b_])
+    di = upload_arena(itab)
+    assert np.array_equal(forward(di, toff, idx, offsets, B).cpu().numpy(),
+                          forward(di, toff, idx2, offsets, B).cpu().numpy())
+    p1 = forward(dev, toff, idx2, offsets, B, "sum").cpu().numpy()
+    scale = np.abs(tables).max() * np.maximum(Lcol, 1)
+    assert np.all(np.abs(p1 - s_out) <= 2e-5 * scale)
+    # linearity on integer tables
+    jtab = rng.integers(-8, 8, size=tables.shape).astype(np.float32)
+    a1 = forward(di, toff, idx, offsets, B).cpu().numpy()
+    a2 = forward(upload_arena(jtab), toff, idx, offsets, B).cpu().numpy()
+    a12 = forward(upload_arena(itab + jtab), toff, idx, offsets, B).cpu().numpy()
+    assert np.array_equal(a12, a1 + a2)
