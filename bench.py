@@ -111,7 +111,7 @@ def main() -> int:
 
     # ---- inputs, resident in HBM before anything is timed -------------------------------
     t0 = time.time()
-    tdtype = torch.float16 if wl.dtype == "f16" else torch.float32
+    tdtype = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[wl.dtype]
     arena = torch.empty((wl.total_rows, wl.D), dtype=tdtype, device=dev)
     with torch.cuda.stream(stream):
         gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed,
@@ -126,7 +126,7 @@ def main() -> int:
         dbatches.append((torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev),
                          None if b.weights is None else torch.from_numpy(b.weights).to(dev)))
     out = torch.empty((wl.B, wl.T * wl.D), dtype=torch.float32, device=dev)
-    edt = emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32
+    edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16}[wl.dtype]
     emode = emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM
     # Set-up, untimed (the paper profiles table access patterns offline, Sec. 4.3): classify each
     # table as streaming or re-used from the first index batch, on the device.
@@ -216,7 +216,7 @@ def main() -> int:
         got = got_all[tb[:, 0], tb[:, 1]].cpu().numpy().astype(np.float64)
         err = np.abs(got - ref)
         ok = err <= 1e-5 * bound
-        if wl.dtype == "f16":
+        if wl.dtype != "f32":
             ok |= err <= 1e-3 * np.abs(ref)
         nz = bound > 0
         parity = {"bags_checked": int(len(bags)), "ok": bool(ok.all()),

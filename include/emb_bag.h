@@ -32,6 +32,7 @@ extern "C" {
 /* table element types */
 #define EMB_F32 0 /* IEEE binary32 rows */
 #define EMB_F16 1 /* IEEE binary16 rows, widened exactly and accumulated in fp32 */
+#define EMB_BF16 2 /* bfloat16 rows (upper half of a binary32), widened exactly, fp32 accumulation */
 
 /* pooling modes (the two modes of the sum/mean kernel the paper studies, Sec. 3.1) */
 #define EMB_SUM 0
@@ -47,7 +48,7 @@ extern "C" {
 #define EMB_OK 0
 #define EMB_ERR_NULL_PTR (-1)    /* a required pointer is NULL */
 #define EMB_ERR_BAD_DIM (-2)     /* dim <= 0, row not a multiple of 16 bytes, bad out_ld, ... */
-#define EMB_ERR_BAD_DTYPE (-3)   /* table_dtype is neither EMB_F32 nor EMB_F16 */
+#define EMB_ERR_BAD_DTYPE (-3)   /* table_dtype is not EMB_F32, EMB_F16 or EMB_BF16 */
 #define EMB_ERR_BAD_MODE (-4)    /* mode is neither EMB_SUM nor EMB_MEAN */
 #define EMB_ERR_UNSUPPORTED (-5) /* per-sample weights together with EMB_MEAN */
 #define EMB_ERR_LAUNCH (-6)      /* the HIP runtime refused the launch */
@@ -66,7 +67,7 @@ extern "C" {
 typedef struct emb_bag_desc {
   int32_t num_tables;     /* T >= 1 */
   int32_t dim;            /* D >= 1 */
-  int32_t table_dtype;    /* EMB_F32 or EMB_F16 */
+  int32_t table_dtype;    /* EMB_F32, EMB_F16 or EMB_BF16 */
   int32_t mode;           /* EMB_SUM or EMB_MEAN */
   int64_t batch;          /* B >= 0; B == 0 is a no-op that returns EMB_OK */
   int64_t num_lookups;    /* NL = offsets[T*B]: entries in indices (and in per_sample_weights) */
@@ -89,10 +90,10 @@ typedef struct emb_bag_desc {
  *   out[b*out_ld + t*D + d] = sum over j in [offsets[t*B+b], offsets[t*B+b+1]) of
  *                               w_j * table_t[indices[j]][d]            (w_j = 1 without weights)
  *   and that sum divided by the bag length in EMB_MEAN mode (0 for an empty bag).
- *   Accumulation is in fp32; fp16 rows are widened exactly first.
+ *   Accumulation is in fp32; fp16 and bf16 rows are widened exactly first.
  *
  *   desc                HOST    shape, see above
- *   tables              DEVICE  arena [sum_t R_t, D] row-major, 16-byte aligned, f32 or f16
+ *   tables              DEVICE  arena [sum_t R_t, D] row-major, 16-byte aligned, f32 / f16 / bf16
  *   table_offsets       DEVICE  int64 [T+1], first arena row of each table, non-decreasing
  *   indices             DEVICE  int64 [NL], table-local row ids, bags stored in (t, b) order
  *   offsets             DEVICE  int64 [T*B+1], CSR over bags: offsets[0] = 0, offsets[T*B] = NL

@@ -16,7 +16,7 @@
 //   kind 0 ("normal"): s = sum of the four 16-bit fields of z - 131070   (Irwin-Hall, n = 4)
 //                      v = (float)s * (0.1f / 37837.2f)      -> approx N(0, 0.1^2)
 //   kind 1 ("int")   : v = (float)((int)(z >> 60) - 8)        -> integers in [-8, 7]
-//   f16 tables store v rounded to half, round-to-nearest-even.
+//   f16 tables store v rounded to half, bf16 tables v rounded to bfloat16, both to nearest even.
 // Only integer operations, one exact int->float conversion and one correctly rounded fp32
 // multiply are used, so numpy on the host and this kernel agree in every bit.
 
@@ -45,11 +45,18 @@ __device__ __forceinline__ float value_at(uint64_t seed, uint64_t row, uint64_t 
 
 // One thread produces one 16-byte vector (4 floats or 8 halves); D is a multiple of the
 // vector width, so a vector never straddles two rows.
-template <bool F16>
+// fp32 -> bfloat16 bits, round to nearest even (finite inputs only; the generator makes no others)
+__device__ __forceinline__ uint16_t bf16_bits_rn(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+// ELEM: 0 = fp32, 1 = fp16, 2 = bfloat16
+template <int ELEM>
 __global__ __launch_bounds__(256) void fill_kernel(void* __restrict__ dst, uint64_t first_row,
                                                    uint64_t nvec, uint32_t D, uint64_t seed,
                                                    int kind) {
-  constexpr uint32_t EPV = F16 ? 8 : 4;
+  constexpr uint32_t EPV = ELEM == 0 ? 4 : 8;
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
   for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += stride) {
     const uint64_t e0 = v * EPV;
@@ -58,10 +65,15 @@ __global__ __launch_bounds__(256) void fill_kernel(void* __restrict__ dst, uint6
     float x[EPV];
 #pragma unroll
     for (uint32_t k = 0; k < EPV; ++k) x[k] = value_at(seed, first_row + row, col + k, kind);
-    if constexpr (F16) {
+    if constexpr (ELEM == 1) {
       union { uint4 u; __half h[8]; } pk;
 #pragma unroll
       for (uint32_t k = 0; k < EPV; ++k) pk.h[k] = __float2half_rn(x[k]);
+      reinterpret_cast<uint4*>(dst)[v] = pk.u;
+    } else if constexpr (ELEM == 2) {
+      union { uint4 u; uint16_t h[8]; } pk;
+#pragma unroll
+      for (uint32_t k = 0; k < EPV; ++k) pk.h[k] = bf16_bits_rn(x[k]);
       reinterpret_cast<uint4*>(dst)[v] = pk.u;
     } else {
       reinterpret_cast<float4*>(dst)[v] = make_float4(x[0], x[1], x[2], x[3]);
@@ -123,24 +135,27 @@ unsigned grid_for(uint64_t nvec) {
 extern "C" {
 
 // dst: DEVICE pointer to the first element of arena row `first_row` ([nrows, D] row-major).
-// dtype: 0 = fp32, 1 = fp16.  kind: 0 = normal, 1 = int.  Returns 0, or a negative code for a
+// dtype: 0 = fp32, 1 = fp16, 2 = bfloat16.  kind: 0 = normal, 1 = int.  Returns 0, or a negative code for a
 // bad argument / a positive hipError_t for a failed launch.
 int gen_fill_table(void* dst, int64_t first_row, int64_t nrows, int32_t D, int32_t dtype,
                    uint64_t seed, int32_t kind, void* stream) {
   if (nrows == 0) return 0;
   if (!dst || nrows < 0 || first_row < 0 || D <= 0) return -1;
-  if (dtype != 0 && dtype != 1) return -2;
+  if (dtype < 0 || dtype > 2) return -2;
   if (kind != 0 && kind != 1) return -3;
-  const uint32_t epv = dtype == 1 ? 8 : 4;
+  const uint32_t epv = dtype == 0 ? 4 : 8;
   if (D % epv != 0) return -4;
   if ((reinterpret_cast<uintptr_t>(dst) & 15) != 0) return -5;
   const uint64_t nvec = (uint64_t)nrows * (uint64_t)D / epv;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == 1)
-    hipLaunchKernelGGL(fill_kernel<true>, dim3(grid_for(nvec)), dim3(256), 0, s, dst,
+    hipLaunchKernelGGL(fill_kernel<1>, dim3(grid_for(nvec)), dim3(256), 0, s, dst,
+                       (uint64_t)first_row, nvec, (uint32_t)D, seed, kind);
+  else if (dtype == 2)
+    hipLaunchKernelGGL(fill_kernel<2>, dim3(grid_for(nvec)), dim3(256), 0, s, dst,
                        (uint64_t)first_row, nvec, (uint32_t)D, seed, kind);
   else
-    hipLaunchKernelGGL(fill_kernel<false>, dim3(grid_for(nvec)), dim3(256), 0, s, dst,
+    hipLaunchKernelGGL(fill_kernel<0>, dim3(grid_for(nvec)), dim3(256), 0, s, dst,
                        (uint64_t)first_row, nvec, (uint32_t)D, seed, kind);
   return (int)hipGetLastError();
 }

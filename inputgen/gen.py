@@ -53,6 +53,7 @@ def table_values(seed: int, arena_rows: Sequence[int], D: int, dtype: str = "f32
                  kind: int = KIND_NORMAL) -> np.ndarray:
     """Values of the given arena rows, shape [len(arena_rows), D], float32 or float16.
 
+    dtype 'bf16' returns uint16 bit patterns (numpy has no bfloat16).
     kind 0: approximately N(0, 0.1^2) (sum of four 16-bit uniform fields, centred and scaled);
     kind 1: integers in [-8, 7] (sums of these are exact in fp32 in any order).
     """
@@ -71,15 +72,18 @@ def table_values(seed: int, arena_rows: Sequence[int], D: int, dtype: str = "f32
         raise ValueError("kind must be 0 (normal) or 1 (int)")
     if dtype == "f16":
         return v.astype(np.float16)
+    if dtype == "bf16":   # round to nearest even on the bit pattern; returned as uint16 bits
+        u = v.view(np.uint32)
+        return ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)).astype(np.uint16)
     if dtype == "f32":
         return v
-    raise ValueError("dtype must be 'f32' or 'f16'")
+    raise ValueError("dtype must be 'f32', 'f16' or 'bf16'")
 
 
 def table_values_range(seed: int, first_row: int, nrows: int, D: int, dtype: str = "f32",
                        kind: int = KIND_NORMAL, chunk_rows: int = 1 << 16) -> np.ndarray:
     """Rows [first_row, first_row + nrows) of the arena, generated in chunks."""
-    out = np.empty((nrows, D), dtype=np.float16 if dtype == "f16" else np.float32)
+    out = np.empty((nrows, D), dtype={"f16": np.float16, "bf16": np.uint16}.get(dtype, np.float32))
     for r0 in range(0, nrows, chunk_rows):
         r1 = min(nrows, r0 + chunk_rows)
         out[r0:r1] = table_values(seed, np.arange(first_row + r0, first_row + r1, dtype=np.uint64),
@@ -122,7 +126,7 @@ def fill_arena_device(dev_ptr: int, first_row: int, nrows: int, D: int, dtype: s
     """Fill arena rows [first_row, first_row+nrows) at device address `dev_ptr` (= address of
     row `first_row`) with `table_values`; asynchronous on `stream` (a hipStream_t as int)."""
     rc = load_lib().gen_fill_table(ctypes.c_void_p(dev_ptr), first_row, nrows, D,
-                                   1 if dtype == "f16" else 0,
+                                   {"f32": 0, "f16": 1, "bf16": 2}[dtype],
                                    ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF), kind,
                                    ctypes.c_void_p(stream))
     if rc != 0:
@@ -157,7 +161,7 @@ class Workload:
     T: int                      # number of tables
     rows: Tuple[int, ...]       # rows per table (len T)
     D: int                      # embedding dimension (uniform over tables)
-    dtype: str                  # 'f32' | 'f16' (table storage; output is always fp32)
+    dtype: str                  # 'f32' | 'f16' | 'bf16' (table storage; output is always fp32)
     B: int                      # batch (bags per table)
     pooling: Tuple              # ('fixed', L) | ('uniform', lo, hi) inclusive
     dists: Tuple[Tuple, ...]    # per table: ('uniform',) | ('zipf', alpha) | ('one_item',)
@@ -169,7 +173,7 @@ class Workload:
 
     @property
     def elem_bytes(self) -> int:
-        return 2 if self.dtype == "f16" else 4
+        return 4 if self.dtype == "f32" else 2
 
     @property
     def row_bytes(self) -> int:
@@ -263,6 +267,10 @@ def workload(name: str) -> Workload:
                         dtype="f32", B=131, pooling=("uniform", 0, 200),
                         dists=(("uniform",), ("zipf", 1.2), ("uniform",), ("uniform",)),
                         seed=0x5EED0012)
+    if name == "small_bf16_d256":  # 512-byte bfloat16 rows
+        return Workload(name="small_bf16_d256", T=3, rows=(1500, 33, 700), D=256,
+                        dtype="bf16", B=61, pooling=("uniform", 0, 130),
+                        dists=(("uniform",), ("zipf", 1.2), ("uniform",)), seed=0x5EED0014)
     if name == "small_f16_d256":  # 512-byte fp16 rows
         return Workload(name="small_f16_d256", T=4, rows=(2000, 65, 1024, 300), D=256,
                         dtype="f16", B=97, pooling=("uniform", 0, 130),

@@ -21,7 +21,7 @@
  *   - per-sample weights are not in the paper: out = sum_j w_j * row_j, sum mode only.
  *   - summation order is not fixed by the paper: this oracle adds in index order, in fp64.
  *
- * Arithmetic: every table element is widened exactly (fp32 -> fp64, or IEEE half -> fp64) and
+ * Arithmetic: every table element is widened exactly (fp32, IEEE half or bfloat16 -> fp64) and
  * accumulated in fp64.  Alongside each output element the oracle returns bound = sum_j |w_j *
  * x_j| (divided by the bag length in mean mode), the scale of the rounding-error tolerance.
  *
@@ -59,8 +59,17 @@ static double half_bits_to_double(uint16_t h) {
   return sign ? -v : v;
 }
 
+/* bfloat16 bit pattern -> double, exactly: a bfloat16 is the upper 16 bits of an IEEE binary32. */
+static double bf16_bits_to_double(uint16_t h) {
+  const uint32_t u = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
 static double table_elem(const void* tables, int dtype, int64_t arena_row, int64_t D, int64_t d) {
   if (dtype == 1) return half_bits_to_double(((const uint16_t*)tables)[arena_row * D + d]);
+  if (dtype == 2) return bf16_bits_to_double(((const uint16_t*)tables)[arena_row * D + d]);
   return (double)((const float*)tables)[arena_row * D + d];
 }
 
@@ -83,7 +92,8 @@ void oracle_set_num_threads(int n) {
 /*
  * All pointers are HOST pointers.
  *   T, B, D        tables, batch, embedding dimension
- *   dtype          0 = fp32 tables, 1 = fp16 tables (raw half bit patterns)
+ *   dtype          0 = fp32 tables, 1 = fp16 tables (raw half bit patterns),
+ *                  2 = bfloat16 tables (raw bit patterns)
  *   mode           0 = sum, 1 = mean
  *   tables         arena [sum_t R_t, D], row-major
  *   table_offsets  [T+1] first arena row of each table (so R_t = table_offsets[t+1]-table_offsets[t])
@@ -98,7 +108,7 @@ int oracle_emb_bag(int32_t T, int64_t B, int32_t D, int32_t dtype, int32_t mode,
                    const void* tables, const int64_t* table_offsets, const int64_t* indices,
                    const int64_t* offsets, const float* weights, int64_t out_ld, double* ref,
                    double* bound) {
-  if (T < 1 || B < 0 || D < 1 || (dtype != 0 && dtype != 1) || (mode != 0 && mode != 1))
+  if (T < 1 || B < 0 || D < 1 || (dtype < 0 || dtype > 2) || (mode != 0 && mode != 1))
     return ORACLE_ERR_ARG;
   if (out_ld < (int64_t)T * D) return ORACLE_ERR_ARG;
   if (weights && mode != 0) return ORACLE_ERR_ARG;

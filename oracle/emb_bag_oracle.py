@@ -62,7 +62,7 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
             out_ld: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     """Reference output and error-bound scale, both fp64 [B, out_ld].
 
-    tables: [sum R_t, D] float32 or float16 host array; table_offsets int64 [T+1];
+    tables: [sum R_t, D] float32, float16 or uint16 (= bfloat16 bits) host array; table_offsets int64 [T+1];
     indices int64 [NL]; offsets int64 [T*B+1]; weights float32 [NL] or None.
     Raises ValueError on the error codes of the C function.
     """
@@ -72,8 +72,10 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
         dtype = 0
     elif tables.dtype == np.float16:
         dtype = 1
+    elif tables.dtype == np.uint16:   # numpy has no bfloat16: raw bit patterns
+        dtype = 2
     else:
-        raise ValueError("tables must be float32 or float16")
+        raise ValueError("tables must be float32, float16 or uint16 (bfloat16 bit patterns)")
     tables = np.ascontiguousarray(tables)
     table_offsets = np.ascontiguousarray(table_offsets, dtype=np.int64)
     indices = np.ascontiguousarray(indices, dtype=np.int64)

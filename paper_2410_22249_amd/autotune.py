@@ -48,7 +48,7 @@ def _setup(name: str, n_batches: int):
     wl = gen.workload(name)
     dev = "cuda:0"
     arena = torch.empty((wl.total_rows, wl.D),
-                        dtype=torch.float16 if wl.dtype == "f16" else torch.float32, device=dev)
+                        dtype={"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[wl.dtype], device=dev)
     gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed, wl.kind,
                           torch.cuda.current_stream().cuda_stream)
     batches = gen.make_batches(wl, n_batches)
@@ -56,7 +56,7 @@ def _setup(name: str, n_batches: int):
     dev_batches = [(torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev),
                     None if b.weights is None else torch.from_numpy(b.weights).to(dev))
                    for b in batches]
-    edt = emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32
+    edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16}[wl.dtype]
     emode = emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM
     hints = torch.zeros(wl.T, dtype=torch.uint8, device=dev)
     d0 = emb.make_desc(wl.T, wl.B, wl.D, edt, emode, batches[0].num_lookups, 0, max(wl.rows))

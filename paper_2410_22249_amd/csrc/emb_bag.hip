@@ -79,17 +79,24 @@ __device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
 
 __device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
 
-// acc += w * (one 16-byte segment of a row), for fp32 rows (4 elements) or fp16 rows (8).
-template <bool F16, bool WEIGHTED>
+// acc += w * (one 16-byte segment of a row): 4 fp32 elements, or 8 fp16 / bf16 elements widened
+// exactly to fp32.
+template <int ELEM, bool WEIGHTED>
 __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w) {
-  if constexpr (F16) {
+  if constexpr (ELEM != EMB_F32) {
     const uint32_t u[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-      const h2 h = __builtin_bit_cast(h2, u[i]);
-      const float lo = (float)h.x;
-      const float hi = (float)h.y;
+      float lo, hi;
+      if constexpr (ELEM == EMB_F16) {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        const h2 h = __builtin_bit_cast(h2, u[i]);
+        lo = (float)h.x;
+        hi = (float)h.y;
+      } else {  // bfloat16 is the upper half of a binary32: widening is a shift
+        lo = as_float(u[i] << 16);
+        hi = as_float(u[i] & 0xFFFF0000u);
+      }
       if constexpr (WEIGHTED) {
         acc[2 * i] = __builtin_fmaf(w, lo, acc[2 * i]);
         acc[2 * i + 1] = __builtin_fmaf(w, hi, acc[2 * i + 1]);
@@ -113,7 +120,7 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w) {
 // The gather of one bag (one column slab of it): walk the bag's lookups in chunks of 64 and add
 // the rows into acc.  NT selects the non-temporal cache policy for the row loads (tables whose
 // rows are not re-used within a batch), the default policy otherwise.
-template <int LPR, bool F16, int DEPTH, bool WEIGHTED, bool BUF, bool NT>
+template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool BUF, bool NT>
 __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict__ indices,
                                            const float* __restrict__ weights, int64_t s,
                                            int64_t e, int64_t R, uint32_t row_bytes,
@@ -168,20 +175,21 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
         }
       }
 #pragma unroll
-      for (int d = 0; d < DEPTH; ++d) accumulate<F16, WEIGHTED>(acc, r[d], wj[d]);
+      for (int d = 0; d < DEPTH; ++d) accumulate<ELEM, WEIGHTED>(acc, r[d], wj[d]);
     }
   }
 
 }
 
 // One wavefront per (bag, column slab).  LPR = lanes per row (power of two, 4..64).
-template <int LPR, bool F16, int DEPTH, bool WEIGHTED, bool BUF>
+template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool BUF>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
                     const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
                     float* __restrict__ out, KParams p) {
-  constexpr int NACC = F16 ? 8 : 4;   // fp32 accumulators per lane
+  constexpr bool HALF = ELEM != EMB_F32;  // 2-byte elements
+  constexpr int NACC = HALF ? 8 : 4;      // fp32 accumulators per lane
 
   const int lane = threadIdx.x & (kWaveSize - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -235,10 +243,10 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
 
   const bool streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
   if (streaming)
-    gather_bag<LPR, F16, DEPTH, WEIGHTED, BUF, true>(acc, indices, weights, s, e, R, p.row_bytes,
+    gather_bag<LPR, ELEM, DEPTH, WEIGHTED, BUF, true>(acc, indices, weights, s, e, R, p.row_bytes,
                                                      tbase, rsrc, lane, g, col, lane_ok);
   else
-    gather_bag<LPR, F16, DEPTH, WEIGHTED, BUF, false>(acc, indices, weights, s, e, R, p.row_bytes,
+    gather_bag<LPR, ELEM, DEPTH, WEIGHTED, BUF, false>(acc, indices, weights, s, e, R, p.row_bytes,
                                                       tbase, rsrc, lane, g, col, lane_ok);
 
   // combine the G row groups (fixed butterfly: every lane ends with the same bits)
@@ -259,11 +267,11 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
 
   if (lane < LPR && lane_ok) {
     // col counts bytes of the table row; the output is fp32
-    const uint32_t elem0 = F16 ? col / 2 : col / 4;
+    const uint32_t elem0 = HALF ? col / 2 : col / 4;
     f32x4* dst = reinterpret_cast<f32x4*>(out + (int64_t)b * p.out_ld + (int64_t)t * p.D + elem0);
     const f32x4 v0 = {acc[0], acc[1], acc[2], acc[3]};
     __builtin_nontemporal_store(v0, dst);
-    if constexpr (F16) {
+    if constexpr (HALF) {
       const f32x4 v1 = {acc[4], acc[5], acc[6], acc[7]};
       __builtin_nontemporal_store(v1, dst + 1);
     }
@@ -372,50 +380,55 @@ Tuning g_tuning;
 using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int64_t*,
                           const float*, const uint8_t*, float*, KParams);
 
-template <int LPR, bool F16, int DEPTH>
+template <int LPR, int ELEM, int DEPTH>
 KernelFn pick_wb(bool weighted, bool buf) {
   if (weighted)
-    return buf ? emb_bag_wave_kernel<LPR, F16, DEPTH, true, true>
-               : emb_bag_wave_kernel<LPR, F16, DEPTH, true, false>;
-  return buf ? emb_bag_wave_kernel<LPR, F16, DEPTH, false, true>
-             : emb_bag_wave_kernel<LPR, F16, DEPTH, false, false>;
+    return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, true, true>
+               : emb_bag_wave_kernel<LPR, ELEM, DEPTH, true, false>;
+  return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, false, true>
+             : emb_bag_wave_kernel<LPR, ELEM, DEPTH, false, false>;
 }
 
-template <int LPR, bool F16>
+template <int LPR, int ELEM>
 KernelFn pick_depth(int depth, bool weighted, bool buf) {
   switch (depth) {
-    case 1: return pick_wb<LPR, F16, 1>(weighted, buf);
-    case 2: return pick_wb<LPR, F16, 2>(weighted, buf);
-    case 4: return pick_wb<LPR, F16, 4>(weighted, buf);
-    case 8: return pick_wb<LPR, F16, 8>(weighted, buf);
-    case 16: return pick_wb<LPR, F16, 16>(weighted, buf);
+    case 1: return pick_wb<LPR, ELEM, 1>(weighted, buf);
+    case 2: return pick_wb<LPR, ELEM, 2>(weighted, buf);
+    case 4: return pick_wb<LPR, ELEM, 4>(weighted, buf);
+    case 8: return pick_wb<LPR, ELEM, 8>(weighted, buf);
+    case 16: return pick_wb<LPR, ELEM, 16>(weighted, buf);
     default: return nullptr;
   }
 }
 
 template <int LPR>
-KernelFn pick_dtype(bool f16, int depth, bool weighted, bool buf) {
-  return f16 ? pick_depth<LPR, true>(depth, weighted, buf)
-             : pick_depth<LPR, false>(depth, weighted, buf);
+KernelFn pick_dtype(int elem, int depth, bool weighted, bool buf) {
+  switch (elem) {
+    case EMB_F32: return pick_depth<LPR, EMB_F32>(depth, weighted, buf);
+    case EMB_F16: return pick_depth<LPR, EMB_F16>(depth, weighted, buf);
+    case EMB_BF16: return pick_depth<LPR, EMB_BF16>(depth, weighted, buf);
+    default: return nullptr;
+  }
 }
 
-KernelFn pick_kernel(int lpr, bool f16, int depth, bool weighted, bool buf) {
+KernelFn pick_kernel(int lpr, int elem, int depth, bool weighted, bool buf) {
   switch (lpr) {
-    case 4: return pick_dtype<4>(f16, depth, weighted, buf);
-    case 8: return pick_dtype<8>(f16, depth, weighted, buf);
-    case 16: return pick_dtype<16>(f16, depth, weighted, buf);
-    case 32: return pick_dtype<32>(f16, depth, weighted, buf);
-    case 64: return pick_dtype<64>(f16, depth, weighted, buf);
+    case 4: return pick_dtype<4>(elem, depth, weighted, buf);
+    case 8: return pick_dtype<8>(elem, depth, weighted, buf);
+    case 16: return pick_dtype<16>(elem, depth, weighted, buf);
+    case 32: return pick_dtype<32>(elem, depth, weighted, buf);
+    case 64: return pick_dtype<64>(elem, depth, weighted, buf);
     default: return nullptr;
   }
 }
 
 int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
   if (!d) return EMB_ERR_NULL_PTR;
-  if (d->table_dtype != EMB_F32 && d->table_dtype != EMB_F16) return EMB_ERR_BAD_DTYPE;
+  if (d->table_dtype != EMB_F32 && d->table_dtype != EMB_F16 && d->table_dtype != EMB_BF16)
+    return EMB_ERR_BAD_DTYPE;
   if (d->mode != EMB_SUM && d->mode != EMB_MEAN) return EMB_ERR_BAD_MODE;
   if (d->num_tables < 1 || d->dim < 1) return EMB_ERR_BAD_DIM;
-  const int64_t row_bytes = (int64_t)d->dim * (d->table_dtype == EMB_F16 ? 2 : 4);
+  const int64_t row_bytes = (int64_t)d->dim * (d->table_dtype == EMB_F32 ? 4 : 2);
   if (row_bytes % 16 != 0 || row_bytes > 65536) return EMB_ERR_BAD_DIM;
   if (d->batch < 0 || d->num_lookups < 0 || d->max_table_rows < 0) return EMB_ERR_BAD_SIZE;
   *row_bytes_out = (uint32_t)row_bytes;
@@ -458,7 +471,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   int depth = (int)g_tuning.depth;
   if (depth == 0) depth = (desc->table_dtype == EMB_F32 && row_bytes >= 512) ? 8 : 4;
 
-  KernelFn fn = pick_kernel(lpr, desc->table_dtype == EMB_F16, depth,
+  KernelFn fn = pick_kernel(lpr, desc->table_dtype, depth,
                             per_sample_weights != nullptr, buf);
   if (!fn) return EMB_ERR_BAD_TUNING;
 

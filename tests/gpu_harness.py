@@ -24,13 +24,25 @@ def to_dev(a: Optional[np.ndarray]):
 
 
 def upload_arena(arena: np.ndarray) -> torch.Tensor:
-    return torch.from_numpy(np.ascontiguousarray(arena)).to(DEV)
+    """float32 / float16 arrays go up as they are; uint16 arrays hold bfloat16 bit patterns."""
+    arena = np.ascontiguousarray(arena)
+    if arena.dtype == np.uint16:
+        return torch.from_numpy(arena.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(arena).to(DEV)
+
+
+TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+EMB_DTYPE = {torch.float32: emb.EMB_F32, torch.float16: emb.EMB_F16, torch.bfloat16: emb.EMB_BF16}
+
+
+def arena_bytes(arena: torch.Tensor) -> np.ndarray:
+    """Raw bytes of a device arena, for bit-for-bit comparisons with the host generator."""
+    return arena.contiguous().view(torch.uint8).cpu().numpy()
 
 
 def device_arena(wl: gen.Workload) -> torch.Tensor:
     """Allocate the arena on the device and fill it with the generator's kernel."""
-    tdtype = torch.float16 if wl.dtype == "f16" else torch.float32
-    arena = torch.empty((wl.total_rows, wl.D), dtype=tdtype, device=DEV)
+    arena = torch.empty((wl.total_rows, wl.D), dtype=TORCH_DTYPE[wl.dtype], device=DEV)
     gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed, wl.kind,
                           torch.cuda.current_stream().cuda_stream)
     return arena
@@ -54,7 +66,7 @@ def forward(arena: torch.Tensor, table_offsets: np.ndarray, indices, offsets, B:
     ld = out_ld if out_ld else T * D
     if out is None:
         out = torch.full((B, ld), fill, dtype=torch.float32, device=DEV)
-    desc = emb.make_desc(T, B, D, emb.EMB_F16 if arena.dtype == torch.float16 else emb.EMB_F32,
+    desc = emb.make_desc(T, B, D, EMB_DTYPE[arena.dtype],
                          emb.EMB_MEAN if mode == "mean" else emb.EMB_SUM, nl, out_ld,
                          max_table_rows)
     emb.emb_bag_forward(desc, arena, toff, idx if nl else None, off, w, out)

@@ -73,6 +73,7 @@ def test_host_side_argument_errors():
     assert fwd(emb.make_desc(**{**ok, "dim": 0})) == -2
     assert fwd(emb.make_desc(**{**ok, "dim": 6})) == -2                       # 24-byte rows
     assert fwd(emb.make_desc(**{**ok, "dim": 4, "table_dtype": emb.EMB_F16})) == -2  # 8-byte rows
+    assert fwd(emb.make_desc(**{**ok, "dim": 4, "table_dtype": emb.EMB_BF16})) == -2
     assert fwd(emb.make_desc(**{**ok, "dim": 32768})) == -2                   # row > 64 KiB
     assert fwd(emb.make_desc(**{**ok, "batch": -1})) == -7
     assert fwd(emb.make_desc(**{**ok, "num_lookups": -1})) == -7

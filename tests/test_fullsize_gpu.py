@@ -21,7 +21,7 @@ pytestmark = pytest.mark.gpu
 def _run(wl, batch, arena, toff):
     idx, off = to_dev(batch.indices), to_dev(batch.offsets)
     out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
-    desc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32,
+    desc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16}[wl.dtype],
                          emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, batch.num_lookups, 0,
                          max(wl.rows))
     emb.emb_bag_forward(desc, arena, toff, idx, off, None, out)
@@ -70,7 +70,7 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, soff, len(bags), wl.mode)
     sel = torch.from_numpy(np.stack([bags % wl.B, bags // wl.B], 1)).to(DEV)
     got = out.view(wl.B, wl.T, wl.D)[sel[:, 0], sel[:, 1]].cpu().numpy()
-    worst = assert_close_to_oracle(got, ref, bound, wl.dtype == "f16", f"{name} sampled")
+    worst = assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"{name} sampled")
     # hints from the device-side profiler: what the benchmark uses; classification as expected
     from oracle import reuse_oracle
     hints = torch.zeros(wl.T, dtype=torch.uint8, device=DEV)
@@ -83,7 +83,7 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     assert np.array_equal(hints.cpu().numpy(), rh)
     expect = np.array([1 if d[0] == "uniform" else 0 for d in wl.dists], dtype=np.uint8)
     assert np.array_equal(rh, expect), "uniform tables stream, skewed tables stay cached"
-    hdesc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32,
+    hdesc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16}[wl.dtype],
                           emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, batch.num_lookups,
                           0, max(wl.rows), hints)
     emb.emb_bag_forward(hdesc, arena, toff, idx, off, None, out2)

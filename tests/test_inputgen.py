@@ -96,6 +96,12 @@ def test_table_values_distribution_and_determinism():
     assert not np.array_equal(v, gen.table_values(0x5EED0004, np.arange(4096), 128))
     h = gen.table_values(0x5EED0003, np.arange(4096), 128, "f16")
     assert h.dtype == np.float16 and np.array_equal(h, v.astype(np.float16))
+    bf = gen.table_values(0x5EED0003, np.arange(4096), 128, "bf16")
+    assert bf.dtype == np.uint16
+    back = (bf.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    assert np.all(np.abs(back - v) <= np.abs(v) * 2.0 ** -8)               # 8 significant bits
+    torch_bf = __import__("torch").from_numpy(v).to(__import__("torch").bfloat16)
+    assert np.array_equal(torch_bf.view(__import__("torch").int16).numpy().view(np.uint16), bf)
     k = gen.table_values(1, np.arange(512), 64, "f32", gen.KIND_INT)
     assert k.min() == -8 and k.max() == 7 and np.array_equal(k, np.round(k))
     # rows and columns are not interchangeable and no two rows coincide

@@ -35,6 +35,7 @@ MUTATIONS = {
     "half exponent bias off by one": ("expo - 25", "expo - 24"),
     "half subnormal scale off by one": ("ldexp((double)frac, -24)", "ldexp((double)frac, -25)"),
     "half sign dropped": ("return sign ? -v : v;", "return v;"),
+    "bfloat16 shifted one bit short": ("const uint32_t u = (uint32_t)h << 16;", "const uint32_t u = (uint32_t)h << 15;"),
     "weights applied in mean mode only": ("const double w = weights ? (double)weights[j] : 1.0;",
                                           "const double w = (weights && mode == 1) ? (double)weights[j] : 1.0;"),
 }
@@ -52,6 +53,7 @@ PIN_FUNCS = [
     pins.test_weights,
     pins.test_bound_is_sum_of_abs_terms,
     pins.test_half_widening_is_exact,
+    pins.test_bfloat16_widening_is_exact,
 ]
 
 

@@ -314,6 +314,32 @@ def test_half_widening_is_exact(oracle):
     assert np.array_equal(got[np.isinf(halves)], want[np.isinf(halves)])
 
 
+def test_bfloat16_widening_is_exact(oracle):
+    """Every bfloat16 bit pattern, looked up alone, comes back as the binary32 with those upper bits."""
+    bits = np.arange(0, 1 << 16, dtype=np.uint16)
+    with np.errstate(invalid="ignore"):   # signalling NaN patterns are part of the sweep
+        want = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    table = bits.reshape(-1, 8)
+    R = table.shape[0]
+    ref, _ = oracle.emb_bag(table, np.array([0, R], np.int64), np.arange(R, dtype=np.int64),
+                            np.arange(R + 1, dtype=np.int64), R, "sum")
+    got = ref.reshape(-1)
+    fin = np.isfinite(want)
+    assert np.array_equal(got[fin], want[fin])
+    assert np.all(np.isnan(got[np.isnan(want)]))
+    assert np.array_equal(got[np.isinf(want)], want[np.isinf(want)])
+    # and sums of bfloat16 rows agree with the same rows given as float32
+    rng = np.random.default_rng(21)
+    b16 = rng.integers(0x3C00, 0x4100, size=(40, 8)).astype(np.uint16)
+    f32 = (b16.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    idx = rng.integers(0, 40, size=30).astype(np.int64)
+    off = np.array([0, 7, 7, 30], dtype=np.int64)
+    toff = np.array([0, 40], dtype=np.int64)
+    ra, ba = oracle.emb_bag(b16, toff, idx, off, 3, "mean")
+    rb, bb = oracle.emb_bag(f32, toff, idx, off, 3, "mean")
+    assert np.array_equal(ra, rb) and np.array_equal(ba, bb)
+
+
 def test_rejects_bad_inputs(oracle):
     table = np.ones((4, 4), np.float32)
     toff = np.array([0, 4], dtype=np.int64)

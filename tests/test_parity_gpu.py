@@ -6,8 +6,8 @@ import pytest
 import torch
 
 from inputgen import gen
-from gpu_harness import (DEV, assert_close_to_oracle, device_arena, forward, to_dev, tuning,
-                         upload_arena)
+from gpu_harness import (DEV, EMB_DTYPE, TORCH_DTYPE, arena_bytes, assert_close_to_oracle,
+                         device_arena, forward, to_dev, tuning, upload_arena)
 
 pytestmark = pytest.mark.gpu
 
@@ -24,7 +24,8 @@ def _problem(name, **over):
     return wl, batch, arena
 
 
-@pytest.mark.parametrize("name", ["tiny", "small_f32_d64", "small_f32_d128", "small_f16_d256"])
+@pytest.mark.parametrize("name", ["tiny", "small_f32_d64", "small_f32_d128", "small_f16_d256",
+                                  "small_bf16_d256"])
 @pytest.mark.parametrize("mode", ["sum", "mean"])
 @pytest.mark.parametrize("addressing", [0, 1])
 def test_small_workloads_match_oracle(oracle, name, mode, addressing):
@@ -33,11 +34,12 @@ def test_small_workloads_match_oracle(oracle, name, mode, addressing):
     with tuning(addressing=addressing):
         got = forward(upload_arena(arena), wl.table_offsets(), batch.indices, batch.offsets, wl.B,
                       mode).cpu().numpy()
-    assert_close_to_oracle(got, ref, bound, wl.dtype == "f16", f"{name}/{mode}/addr{addressing}")
+    assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"{name}/{mode}/addr{addressing}")
 
 
 @pytest.mark.parametrize("depth", [1, 2, 4, 8, 16])
-@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256"])
+@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
+                                  "small_bf16_d256"])
 def test_every_depth(oracle, name, depth):
     wl, batch, arena = _problem(name)
     ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
@@ -45,10 +47,11 @@ def test_every_depth(oracle, name, depth):
     for addressing in (0, 1):
         with tuning(depth=depth, addressing=addressing):
             got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
-        assert_close_to_oracle(got, ref, bound, wl.dtype == "f16", f"{name}/depth{depth}")
+        assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"{name}/depth{depth}")
 
 
-@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256"])
+@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
+                                  "small_bf16_d256"])
 def test_integer_tables_are_bit_exact(oracle, name):
     """Integer-valued tables: every partial sum is exact in fp32, so any order gives the same bits."""
     wl, batch, arena = _problem(name, kind=gen.KIND_INT)
@@ -61,7 +64,8 @@ def test_integer_tables_are_bit_exact(oracle, name):
             assert np.array_equal(got.astype(np.float64), ref)
 
 
-@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256"])
+@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
+                                  "small_bf16_d256"])
 def test_per_sample_weights(oracle, name):
     wl, batch, arena = _problem(name, weighted=True)
     assert batch.weights is not None
@@ -72,13 +76,14 @@ def test_per_sample_weights(oracle, name):
         with tuning(addressing=addressing):
             got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "sum",
                           weights=batch.weights).cpu().numpy()
-        assert_close_to_oracle(got, ref, bound, wl.dtype == "f16", f"{name}/weights")
+        assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"{name}/weights")
 
 
 # rows of 16 B .. 4 KiB: non-power-of-two widths, several 1-KiB column slabs, both dtypes
 @pytest.mark.parametrize("D,dtype", [(4, "f32"), (12, "f32"), (32, "f32"), (96, "f32"),
                                      (256, "f32"), (320, "f32"), (1024, "f32"), (8, "f16"),
-                                     (24, "f16"), (128, "f16"), (520, "f16"), (2048, "f16")])
+                                     (24, "f16"), (128, "f16"), (520, "f16"), (2048, "f16"),
+                                     (8, "bf16"), (72, "bf16"), (512, "bf16"), (1032, "bf16")])
 def test_general_row_widths(oracle, D, dtype):
     wl = gen.Workload(name=f"w{D}{dtype}", T=3, rows=(300, 17, 64), D=D, dtype=dtype, B=21,
                       pooling=("uniform", 0, 90), dists=(("uniform",),) * 3, seed=0x5EED0100 + D)
@@ -91,7 +96,7 @@ def test_general_row_widths(oracle, D, dtype):
             with tuning(addressing=addressing):
                 got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
                               mode).cpu().numpy()
-            assert_close_to_oracle(got, ref, bound, dtype == "f16", f"D{D}/{dtype}/{mode}")
+            assert_close_to_oracle(got, ref, bound, dtype != "f32", f"D{D}/{dtype}/{mode}")
 
 
 def test_padded_output_leading_dimension(oracle):
@@ -251,7 +256,8 @@ def test_rows_beyond_max_table_rows_read_as_zero(oracle):
     assert_close_to_oracle(got, ref, bound, False, "max_table_rows clamp")
 
 
-@pytest.mark.parametrize("dtype,kind", [("f32", 0), ("f16", 0), ("f32", 1), ("f16", 1)])
+@pytest.mark.parametrize("dtype,kind", [("f32", 0), ("f16", 0), ("bf16", 0), ("f32", 1), ("f16", 1),
+                                        ("bf16", 1)])
 def test_device_fill_matches_host_values_bit_for_bit(dtype, kind):
     wl = gen.Workload(name="fill", T=2, rows=(7001, 4099), D=128 if dtype == "f32" else 256,
                       dtype=dtype, B=1, pooling=("fixed", 1), dists=(("uniform",),) * 2,
@@ -259,7 +265,7 @@ def test_device_fill_matches_host_values_bit_for_bit(dtype, kind):
     dev = device_arena(wl)
     torch.cuda.synchronize()
     host = gen.host_arena(wl)
-    assert np.array_equal(dev.cpu().numpy().view(np.uint8), host.view(np.uint8))
+    assert np.array_equal(arena_bytes(dev), host.view(np.uint8))
     # a slab filled from a non-zero first row matches the same rows of the whole
     part = torch.empty((1000, wl.D), dtype=dev.dtype, device=DEV)
     gen.fill_arena_device(part.data_ptr(), 5000, 1000, wl.D, dtype, wl.seed, kind,
@@ -314,7 +320,7 @@ def test_forward_replays_correctly_from_a_hip_graph(oracle):
 def test_table_hints_change_speed_only(oracle):
     """Streaming hints switch the cache policy of the row loads; results must not move a bit."""
     import paper_2410_22249_amd as emb
-    for name in ("small_f32_d64", "small_f32_d128", "small_f16_d256"):
+    for name in ("small_f32_d64", "small_f32_d128", "small_f16_d256", "small_bf16_d256"):
         wl = gen.workload(name)
         batch = gen.make_batches(wl, 1)[0]
         host = gen.host_arena(wl)
@@ -327,14 +333,13 @@ def test_table_hints_change_speed_only(oracle):
             hints = None if hints_np is None else to_dev(hints_np)
             for addressing in (0, 1):
                 out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
-                desc = emb.make_desc(wl.T, wl.B, wl.D,
-                                     emb.EMB_F16 if wl.dtype == "f16" else emb.EMB_F32,
+                desc = emb.make_desc(wl.T, wl.B, wl.D, EMB_DTYPE[TORCH_DTYPE[wl.dtype]],
                                      emb.EMB_SUM, batch.num_lookups, 0, max(wl.rows), hints)
                 with tuning(addressing=addressing):
                     emb.emb_bag_forward(desc, arena, toff, idx, off, None, out)
                 torch.cuda.synchronize()
                 outs.append(out.cpu().numpy())
-        assert_close_to_oracle(outs[0], ref, bound, wl.dtype == "f16", f"{name}/hints")
+        assert_close_to_oracle(outs[0], ref, bound, wl.dtype != "f32", f"{name}/hints")
         for o in outs[1:]:
             assert np.array_equal(o, outs[0])
 
@@ -377,8 +382,8 @@ def test_randomised_shapes(oracle):
     dtypes, modes, weights, padded leading dimensions, addressing and launch knobs drawn at random."""
     rng = np.random.default_rng(0xE3B)
     for case in range(40):
-        dtype = "f16" if rng.random() < 0.4 else "f32"
-        unit = 8 if dtype == "f16" else 4
+        dtype = ("f32", "f16", "bf16")[int(rng.integers(0, 3))]
+        unit = 4 if dtype == "f32" else 8
         D = int(unit * rng.integers(1, 80))                      # rows of 16 B .. 1264 B
         T = int(rng.integers(1, 12))
         rows = tuple(int(x) for x in rng.integers(1, 3000, size=T))
@@ -405,7 +410,7 @@ def test_randomised_shapes(oracle):
                           mode, weights=batch.weights, out_ld=ld, fill=-3.0).cpu().numpy()
         what = f"case {case}: T={T} D={D} {dtype} B={B} L=[{lo},{hi}] {mode} w={weighted} {kw}"
         assert np.all(got[:, T * D:] == -3.0), what
-        assert_close_to_oracle(got[:, :T * D], ref[:, :T * D], bound[:, :T * D], dtype == "f16", what)
+        assert_close_to_oracle(got[:, :T * D], ref[:, :T * D], bound[:, :T * D], dtype != "f32", what)
 
 
 def test_gpu_invariants_without_the_oracle():
