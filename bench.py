@@ -74,6 +74,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--check-bags", type=int, default=256, help="bags spot-checked vs the oracle")
+    ap.add_argument("--graph", action="store_true",
+                    help="also replay the K timed steps from one captured HIP graph and report "
+                         "its wall time per step (launch overhead removed)")
     ap.add_argument("--no-hints", action="store_true",
                     help="do not profile table reuse / pass per-table cache hints")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
@@ -197,6 +200,24 @@ def main() -> int:
         f"(min {min(kern_ms):.3f}, max {max(kern_ms):.3f}); gathered "
         f"{gathered / avg_kern_s / 1e9:.1f} GB/s, algorithmic {achieved:.1f} GB/s")
 
+    # ---- optional: the same K steps replayed from one HIP graph (serving loops) ------------
+    graph_ms_per_step = None
+    if args.graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for i in range(args.steps):
+                step(args.warmup + i)
+        g.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        reps = 5
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms_per_step = (time.perf_counter() - t1) * 1e3 / (reps * args.steps)
+        log(f"HIP graph replay: {graph_ms_per_step * 1e3:.2f} us per step "
+            f"(eager wall {wall * 1e6 / args.steps:.2f} us per step)")
+
     # ---- parity spot check of the launch configuration that was just timed --------------
     parity = None
     cpu_baseline = None
@@ -273,7 +294,7 @@ def main() -> int:
                    "lookups_per_step": avg_lookups, "index_batches_rotated": len(batches),
                    "streaming_tables": None if hints is None else int(hints.sum().item()),
                    "tuning": {k: emb.emb_bag_get_tuning(k) for k in
-                              ("depth", "addressing", "blocks_per_cu", "xcd_remap", "kernel")}},
+                              ("depth", "addressing", "blocks_per_cu", "xcd_remap", "use_hints", "kernel")}},
         "gathered_GBps": gathered * args.steps / wall / 1e9,
         "gathered_frac_of_hbm_peak": gathered * args.steps / wall / 1e9 / metrics.HBM_PEAK_GBPS,
         "kernel_ms": {"avg": avg_kern_s * 1e3, "min": float(min(kern_ms)),
@@ -286,6 +307,7 @@ def main() -> int:
                      "frac_of_measured_stream_read": achieved / stream_read_gbps,
                      "algorithmic_bytes_per_launch": algo,
                      "gathered_bytes_per_launch": gathered},
+        "graph_replay_ms_per_step": graph_ms_per_step,
         "cpu_baseline": cpu_baseline,
         "parity": parity,
     }
