@@ -5,6 +5,7 @@
 //   * gen_fill_table  - fill a row-major [nrows, D] slab of an embedding-table arena with
 //                       procedural values that the host generator reproduces bit for bit, so
 //                       100+ GB arenas never need a host copy;
+//   * gen_alloc_arena / gen_free_arena - arena memory, optionally physically contiguous;
 //   * gen_copy_bytes  - a plain device-to-device copy kernel of known size, used to calibrate
 //                       the HBM byte counters of the profiler;
 //   * gen_read_bytes  - a read-only streaming kernel: the measured read-bandwidth ceiling;
@@ -159,6 +160,20 @@ int gen_fill_table(void* dst, int64_t first_row, int64_t nrows, int32_t D, int32
                        (uint64_t)first_row, nvec, (uint32_t)D, seed, kind);
   return (int)hipGetLastError();
 }
+
+// Allocate nbytes of device memory for a table arena; *out receives the DEVICE pointer.
+// contiguous != 0 asks the driver for physically contiguous VRAM (hipDeviceMallocContiguous), so
+// that experiments can separate the effect of page-table fragment size from that of physical
+// placement on random row gathers over 100+ GB.  Returns the hipError_t.
+int gen_alloc_arena(void** out, int64_t nbytes, int32_t contiguous) {
+  if (!out || nbytes <= 0) return -1;
+  *out = nullptr;
+  return (int)hipExtMallocWithFlags(out, (size_t)nbytes,
+                                    contiguous ? hipDeviceMallocContiguous : hipDeviceMallocDefault);
+}
+
+// Free an arena from gen_alloc_arena (the caller has synchronised every stream that used it).
+int gen_free_arena(void* ptr) { return ptr ? (int)hipFree(ptr) : 0; }
 
 // Plain copy of nbytes (multiple of 16; both DEVICE pointers 16-byte aligned).
 int gen_copy_bytes(void* dst, const void* src, int64_t nbytes, void* stream) {

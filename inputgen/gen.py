@@ -115,6 +115,11 @@ def load_lib() -> ctypes.CDLL:
         lib.gen_read_bytes.restype = ctypes.c_int
         lib.gen_read_bytes.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                        ctypes.c_void_p]
+        lib.gen_alloc_arena.restype = ctypes.c_int
+        lib.gen_alloc_arena.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int64,
+                                        ctypes.c_int32]
+        lib.gen_free_arena.restype = ctypes.c_int
+        lib.gen_free_arena.argtypes = [ctypes.c_void_p]
         lib.gen_scrub_cache.restype = ctypes.c_int
         lib.gen_scrub_cache.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
         _lib = lib
@@ -131,6 +136,47 @@ def fill_arena_device(dev_ptr: int, first_row: int, nrows: int, D: int, dtype: s
                                    ctypes.c_void_p(stream))
     if rc != 0:
         raise RuntimeError(f"gen_fill_table failed with code {rc}")
+
+
+class DeviceArena:
+    """A table arena allocated straight from HIP, optionally physically contiguous.
+
+    `tensor` is a torch view of the memory ([rows, D], through the CUDA array interface); the arena
+    owns the memory and frees it in `close()` (call it only after the streams that used it have
+    been synchronised).  If the contiguous request is refused the arena falls back to an ordinary
+    allocation and says so in `kind`."""
+
+    _TYPESTR = {"f32": "<f4", "f16": "<f2", "bf16": "<i2"}
+
+    def __init__(self, rows: int, D: int, dtype: str, contiguous: bool = True):
+        import torch
+        self.rows, self.D, self.dtype = int(rows), int(D), dtype
+        self.nbytes = self.rows * self.D * (4 if dtype == "f32" else 2)
+        lib = load_lib()
+        p = ctypes.c_void_p()
+        self.kind = "hip-contiguous" if contiguous else "hip-default"
+        rc = lib.gen_alloc_arena(ctypes.byref(p), self.nbytes, 1 if contiguous else 0)
+        if rc != 0 and contiguous:
+            torch.cuda.synchronize()
+            self.kind = "hip-default (contiguous refused)"
+            rc = lib.gen_alloc_arena(ctypes.byref(p), self.nbytes, 0)
+        if rc != 0 or not p.value:
+            raise MemoryError(f"gen_alloc_arena({self.nbytes}) failed with hipError {rc}")
+        self.ptr = int(p.value)
+        self.__cuda_array_interface__ = {"shape": (self.rows, self.D), "typestr": self._TYPESTR[dtype],
+                                         "data": (self.ptr, False), "version": 2, "strides": None}
+        t = torch.as_tensor(self, device="cuda")
+        self.tensor = t.view(torch.bfloat16) if dtype == "bf16" else t
+        assert self.tensor.data_ptr() == self.ptr
+
+    def data_ptr(self) -> int:
+        return self.ptr
+
+    def close(self) -> None:
+        if getattr(self, "ptr", 0):
+            self.tensor = None
+            load_lib().gen_free_arena(ctypes.c_void_p(self.ptr))
+            self.ptr = 0
 
 
 def copy_bytes_device(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:

@@ -50,7 +50,8 @@ def test_desc_layout_matches_header():
 def test_generator_library_exports():
     from inputgen import gen
     lib = ctypes.CDLL(gen.LIB_PATH)
-    for n in ("gen_fill_table", "gen_copy_bytes", "gen_read_bytes", "gen_scrub_cache"):
+    for n in ("gen_fill_table", "gen_alloc_arena", "gen_free_arena", "gen_copy_bytes", "gen_read_bytes",
+              "gen_scrub_cache"):
         assert hasattr(lib, n)
 
 

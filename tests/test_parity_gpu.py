@@ -457,3 +457,31 @@ def test_gpu_invariants_without_the_oracle():
     a2 = forward(upload_arena(jtab), toff, idx, offsets, B).cpu().numpy()
     a12 = forward(upload_arena(itab + jtab), toff, idx, offsets, B).cpu().numpy()
     assert np.array_equal(a12, a1 + a2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_hip_allocated_arena_gives_the_same_result(oracle, dtype):
+    """Arenas allocated by the generator straight from HIP (physically contiguous on request)
+    are ordinary device memory: same fill, same forward result as a torch allocation."""
+    wl = gen.Workload(name="arena", T=3, rows=(900, 40, 333), D=128 if dtype == "f32" else 256,
+                      dtype=dtype, B=37, pooling=("uniform", 0, 70), dists=(("uniform",),) * 3,
+                      seed=0x5EED0800)
+    batch = gen.make_batches(wl, 1)[0]
+    ref_dev = device_arena(wl)
+    want = forward(ref_dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
+    for contiguous in (True, False):
+        arena = gen.DeviceArena(wl.total_rows, wl.D, dtype, contiguous=contiguous)
+        try:
+            gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, dtype, wl.seed, wl.kind,
+                                  torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            assert np.array_equal(arena_bytes(arena.tensor), arena_bytes(ref_dev))
+            got = forward(arena.tensor, wl.table_offsets(), batch.indices, batch.offsets,
+                          wl.B).cpu().numpy()
+            assert np.array_equal(got, want)
+        finally:
+            torch.cuda.synchronize()
+            arena.close()
+    host = gen.host_arena(wl)
+    ref, bound = oracle.emb_bag(host, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
+    assert_close_to_oracle(want, ref, bound, dtype != "f32", "hip arena")
