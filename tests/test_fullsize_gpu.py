@@ -98,3 +98,36 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     print(f"[fullsize] {name}: {len(bags)} bags checked, max err/bound {worst:.3e}", flush=True)
     del arena, out, out2
     torch.cuda.empty_cache()
+
+
+def test_many_tiny_bags_whole_output(oracle):
+    """16.7 million bags of 0-2 lookups over 16-byte rows: the smallest row the ABI accepts (4 of the
+    64 lanes per row, 16 rows per wave load), a launch of 4 million workgroups, whole output checked."""
+    wl = gen.Workload(name="tiny_bags", T=64, rows=(50_000,) * 64, D=4, dtype="f32", B=1 << 18,
+                      pooling=("uniform", 0, 2), dists=(("uniform",),) * 64, seed=0x5EED0900)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = device_arena(wl)
+    out, _ = _run(wl, batch, arena, to_dev(wl.table_offsets()))
+    host = gen.host_arena(wl)
+    ref, bound = oracle.emb_bag(host, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "sum")
+    assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, "tiny bags")
+
+
+def test_widest_rows(oracle):
+    """64 KiB rows (the ABI's maximum): 64 column slabs per bag."""
+    wl = gen.Workload(name="wide", T=2, rows=(300, 50), D=16384, dtype="f32", B=9,
+                      pooling=("uniform", 0, 70), dists=(("uniform",), ("zipf", 1.1)), mode="mean",
+                      seed=0x5EED0901)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = device_arena(wl)
+    out, _ = _run(wl, batch, arena, to_dev(wl.table_offsets()))
+    host = gen.host_arena(wl)
+    ref, bound = oracle.emb_bag(host, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "mean")
+    assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, "64 KiB rows")
+    wl16 = gen.with_overrides(wl, D=32768, dtype="f16", mode="sum")
+    batch = gen.make_batches(wl16, 1)[0]
+    arena = device_arena(wl16)
+    out, _ = _run(wl16, batch, arena, to_dev(wl16.table_offsets()))
+    host = gen.host_arena(wl16)
+    ref, bound = oracle.emb_bag(host, wl16.table_offsets(), batch.indices, batch.offsets, wl16.B, "sum")
+    assert_close_to_oracle(out.cpu().numpy(), ref, bound, True, "64 KiB f16 rows")
