@@ -32,6 +32,8 @@ DESCRIPTIONS = {
     "paper": "250 fp32 tables x 500,000 rows x dim 128, batch 2048, pooling 150 fixed, uniform "
              "indices, sum (the paper's model, random dataset)",
     "paper_one_item": "250 fp32 tables x 500,000 x dim 128, batch 2048, pooling 150, one item, sum",
+    "cfg3_u8": "cfg3's shape with row-wise quantised rows: 60 tables x 4,000,000 rows x dim 120 "
+               "(uint8 codes + fp32 scale, bias = 128-byte rows), batch 4096, pooling 80, uniform, sum",
     "paper_high": "paper's model, Zipf(1.3396) stand-in for its high-hot trace (4.05 % unique)",
     "paper_med": "paper's model, Zipf(1.0234) stand-in for its med-hot trace (20.5 % unique)",
     "paper_low": "paper's model, Zipf(0.6999) stand-in for its low-hot trace (46.21 % unique)",
@@ -117,7 +119,9 @@ def main() -> int:
 
     # ---- inputs, resident in HBM before anything is timed -------------------------------
     t0 = time.time()
-    tdtype = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[wl.dtype]
+    tdtype = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16,
+              "u8row": torch.uint8}[wl.dtype]
+    width = wl.D + 8 if wl.dtype == "u8row" else wl.D   # elements per stored row
     # The arena is the caller's memory.  Where it lands physically moves cfg3 by about 5 %
     # between allocations of the same size; the contiguous flag itself makes no difference.
     owner = None
@@ -125,7 +129,7 @@ def main() -> int:
         owner = gen.DeviceArena(wl.total_rows, wl.D, wl.dtype, contiguous=True)
         arena, arena_kind = owner.tensor, owner.kind
     else:
-        arena, arena_kind = torch.empty((wl.total_rows, wl.D), dtype=tdtype, device=dev), "torch"
+        arena, arena_kind = torch.empty((wl.total_rows, width), dtype=tdtype, device=dev), "torch"
     with torch.cuda.stream(stream):
         gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed,
                               wl.kind, sh)
@@ -139,7 +143,8 @@ def main() -> int:
         dbatches.append((torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev),
                          None if b.weights is None else torch.from_numpy(b.weights).to(dev)))
     out = torch.empty((wl.B, wl.T * wl.D), dtype=torch.float32, device=dev)
-    edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16}[wl.dtype]
+    edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16,
+           "u8row": emb.EMB_U8ROW}[wl.dtype]
     emode = emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM
     # Set-up, untimed (the paper profiles table access patterns offline, Sec. 4.3): classify each
     # table as streaming or re-used from the first index batch, on the device.
@@ -203,8 +208,9 @@ def main() -> int:
     avg_lookups = lookups_timed / args.steps
     avg_kern_s = float(np.mean(kern_ms)) / 1e3
     lookups_per_s = lookups_timed / wall
-    gathered = metrics.gathered_bytes(avg_lookups, wl.D, wl.elem_bytes)
-    algo = metrics.algorithmic_bytes(avg_lookups, wl.T, wl.B, wl.D, wl.elem_bytes, wl.weighted)
+    gathered = metrics.gathered_bytes(avg_lookups, wl.D, wl.elem_bytes, wl.row_bytes)
+    algo = metrics.algorithmic_bytes(avg_lookups, wl.T, wl.B, wl.D, wl.elem_bytes, wl.weighted,
+                                     wl.row_bytes)
     achieved = algo / avg_kern_s / 1e9
     log(f"wall {wall * 1e3 / args.steps:.3f} ms/step, kernel avg {avg_kern_s * 1e3:.3f} ms "
         f"(min {min(kern_ms):.3f}, max {max(kern_ms):.3f}); gathered "

@@ -33,6 +33,9 @@ extern "C" {
 #define EMB_F32 0 /* IEEE binary32 rows */
 #define EMB_F16 1 /* IEEE binary16 rows, widened exactly and accumulated in fp32 */
 #define EMB_BF16 2 /* bfloat16 rows (upper half of a binary32), widened exactly, fp32 accumulation */
+#define EMB_U8ROW 3 /* row-wise quantised rows: D unsigned 8-bit codes followed by an fp32 scale and
+                       an fp32 bias (row = D + 8 bytes, which must be a multiple of 16 and at most
+                       1024); element d of a row is scale * code_d + bias, accumulated in fp32 */
 
 /* pooling modes (the two modes of the sum/mean kernel the paper studies, Sec. 3.1) */
 #define EMB_SUM 0
@@ -48,7 +51,7 @@ extern "C" {
 #define EMB_OK 0
 #define EMB_ERR_NULL_PTR (-1)    /* a required pointer is NULL */
 #define EMB_ERR_BAD_DIM (-2)     /* dim <= 0, row not a multiple of 16 bytes, bad out_ld, ... */
-#define EMB_ERR_BAD_DTYPE (-3)   /* table_dtype is not EMB_F32, EMB_F16 or EMB_BF16 */
+#define EMB_ERR_BAD_DTYPE (-3)   /* table_dtype is not one of the EMB_* element types */
 #define EMB_ERR_BAD_MODE (-4)    /* mode is neither EMB_SUM nor EMB_MEAN */
 #define EMB_ERR_UNSUPPORTED (-5) /* per-sample weights together with EMB_MEAN */
 #define EMB_ERR_LAUNCH (-6)      /* the HIP runtime refused the launch */
@@ -59,15 +62,15 @@ extern "C" {
 /*
  * Shape of one call (HOST struct, read during the call only).
  *
- *   T = num_tables, B = batch, D = dim.  Row size in bytes = D * sizeof(element) must be a
- *   multiple of 16 and at most 65536.  Table t holds R_t = table_offsets[t+1] - table_offsets[t]
+ *   T = num_tables, B = batch, D = dim.  Row size in bytes = D * sizeof(element) (D + 8 for
+ *   EMB_U8ROW) must be a multiple of 16 and at most 65536 (1024 for EMB_U8ROW).  Table t holds R_t = table_offsets[t+1] - table_offsets[t]
  *   rows, stored contiguously in one arena starting at arena row table_offsets[t]; D and the
  *   element type are the same for every table (the paper's tables are homogeneous, Sec. 5).
  */
 typedef struct emb_bag_desc {
   int32_t num_tables;     /* T >= 1 */
   int32_t dim;            /* D >= 1 */
-  int32_t table_dtype;    /* EMB_F32, EMB_F16 or EMB_BF16 */
+  int32_t table_dtype;    /* EMB_F32, EMB_F16, EMB_BF16 or EMB_U8ROW */
   int32_t mode;           /* EMB_SUM or EMB_MEAN */
   int64_t batch;          /* B >= 0; B == 0 is a no-op that returns EMB_OK */
   int64_t num_lookups;    /* NL = offsets[T*B]: entries in indices (and in per_sample_weights) */
@@ -93,7 +96,8 @@ typedef struct emb_bag_desc {
  *   Accumulation is in fp32; fp16 and bf16 rows are widened exactly first.
  *
  *   desc                HOST    shape, see above
- *   tables              DEVICE  arena [sum_t R_t, D] row-major, 16-byte aligned, f32 / f16 / bf16
+ *   tables              DEVICE  arena [sum_t R_t, D] row-major, 16-byte aligned, f32 / f16 / bf16,
+ *                               or [sum_t R_t, D + 8] bytes for EMB_U8ROW
  *   table_offsets       DEVICE  int64 [T+1], first arena row of each table, non-decreasing
  *   indices             DEVICE  int64 [NL], table-local row ids, bags stored in (t, b) order
  *   offsets             DEVICE  int64 [T*B+1], CSR over bags: offsets[0] = 0, offsets[T*B] = NL

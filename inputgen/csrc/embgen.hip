@@ -82,6 +82,37 @@ __global__ __launch_bounds__(256) void fill_kernel(void* __restrict__ dst, uint6
   }
 }
 
+// Row-wise quantised rows: D one-byte codes, then an fp32 scale and an fp32 bias (D + 8 bytes per
+// row, a multiple of 16).  One thread writes one 16-byte vector of a row.
+__global__ __launch_bounds__(256) void fill_quantised_kernel(uint4* __restrict__ dst,
+                                                             uint64_t first_row, uint64_t nvec,
+                                                             uint32_t D, uint64_t seed, int kind) {
+  const uint32_t vec_per_row = (D + 8) / 16;
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += stride) {
+    const uint64_t row = v / vec_per_row;
+    const uint32_t c0 = (uint32_t)(v - row * vec_per_row) * 16u;
+    const uint64_t arow = first_row + row;
+    union { uint4 u; uint8_t b[16]; uint32_t w[4]; } pk;
+#pragma unroll
+    for (uint32_t k = 0; k < 16; ++k) {
+      const uint32_t col = c0 + k;
+      pk.b[k] = col < D ? (uint8_t)((mix64(seed + arow * K_ROW + (uint64_t)col * K_COL) >> 32) & 0xFF)
+                        : 0;
+    }
+    if (c0 + 16 > D) {  // this vector holds the row's last 8 codes, then scale and bias
+      float scale = 1.0f;
+      if (kind == 0) {
+        const int a = (int)(mix64(seed + arow * K_ROW + (uint64_t)D * K_COL) & 0xFF);
+        scale = __fmul_rn((float)(256 + a), 3.5e-6f);
+      }
+      pk.w[2] = __builtin_bit_cast(uint32_t, scale);
+      pk.w[3] = __builtin_bit_cast(uint32_t, __fmul_rn(-128.0f, scale));
+    }
+    dst[v] = pk.u;
+  }
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
                                                    const uint4* __restrict__ src, uint64_t nvec) {
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
@@ -136,14 +167,23 @@ unsigned grid_for(uint64_t nvec) {
 extern "C" {
 
 // dst: DEVICE pointer to the first element of arena row `first_row` ([nrows, D] row-major).
-// dtype: 0 = fp32, 1 = fp16, 2 = bfloat16.  kind: 0 = normal, 1 = int.  Returns 0, or a negative code for a
+// dtype: 0 = fp32, 1 = fp16, 2 = bfloat16, 3 = row-wise quantised ([nrows, D + 8] bytes).  kind: 0 = normal, 1 = int.  Returns 0, or a negative code for a
 // bad argument / a positive hipError_t for a failed launch.
 int gen_fill_table(void* dst, int64_t first_row, int64_t nrows, int32_t D, int32_t dtype,
                    uint64_t seed, int32_t kind, void* stream) {
   if (nrows == 0) return 0;
   if (!dst || nrows < 0 || first_row < 0 || D <= 0) return -1;
-  if (dtype < 0 || dtype > 2) return -2;
+  if (dtype < 0 || dtype > 3) return -2;
   if (kind != 0 && kind != 1) return -3;
+  if (dtype == 3) {  // quantised rows: D codes + 8 bytes, a whole number of 16-byte vectors
+    if ((D + 8) % 16 != 0) return -4;
+    if ((reinterpret_cast<uintptr_t>(dst) & 15) != 0) return -5;
+    const uint64_t nv = (uint64_t)nrows * (uint64_t)((D + 8) / 16);
+    hipLaunchKernelGGL(fill_quantised_kernel, dim3(grid_for(nv)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<uint4*>(dst),
+                       (uint64_t)first_row, nv, (uint32_t)D, seed, kind);
+    return (int)hipGetLastError();
+  }
   const uint32_t epv = dtype == 0 ? 4 : 8;
   if (D % epv != 0) return -4;
   if ((reinterpret_cast<uintptr_t>(dst) & 15) != 0) return -5;

@@ -58,6 +58,8 @@ def table_values(seed: int, arena_rows: Sequence[int], D: int, dtype: str = "f32
     kind 1: integers in [-8, 7] (sums of these are exact in fp32 in any order).
     """
     rows = np.asarray(arena_rows, dtype=np.uint64).reshape(-1, 1)
+    if dtype == "u8row":
+        return _quantised_rows(seed, rows, D, kind)
     cols = np.arange(D, dtype=np.uint64).reshape(1, -1)
     with np.errstate(over="ignore"):
         z = _mix64(np.uint64(seed & 0xFFFFFFFFFFFFFFFF) + rows * _K_ROW + cols * _K_COL)
@@ -80,10 +82,38 @@ def table_values(seed: int, arena_rows: Sequence[int], D: int, dtype: str = "f32
     raise ValueError("dtype must be 'f32', 'f16' or 'bf16'")
 
 
+_QSCALE = np.float32(3.5e-6)
+
+
+def _quantised_rows(seed: int, rows: np.ndarray, D: int, kind: int) -> np.ndarray:
+    """Row-wise quantised rows, uint8 [n, D + 8]: D codes, fp32 scale, fp32 bias.
+    code = bits 32..39 of the hash of (row, col); the hash of (row, col = D) picks the scale:
+    kind 0: scale = (256 + a) * 3.5e-6 with a in [0, 255], bias = -128 * scale (elements roughly
+    uniform in +-0.17, sigma about 0.1); kind 1: scale = 1, bias = -128 (integers in [-128, 127])."""
+    n = rows.shape[0]
+    cols = np.arange(D + 1, dtype=np.uint64).reshape(1, -1)
+    with np.errstate(over="ignore"):
+        z = _mix64(np.uint64(seed & 0xFFFFFFFFFFFFFFFF) + rows * _K_ROW + cols * _K_COL)
+    out = np.empty((n, D + 8), dtype=np.uint8)
+    out[:, :D] = ((z[:, :D] >> np.uint64(32)) & np.uint64(0xFF)).astype(np.uint8)
+    if kind == KIND_INT:
+        scale = np.ones(n, dtype=np.float32)
+    else:
+        a = (z[:, D] & np.uint64(0xFF)).astype(np.int64)
+        scale = (256 + a).astype(np.float32) * _QSCALE
+    bias = (np.float32(-128.0) * scale).astype(np.float32)
+    out[:, D:D + 4] = np.ascontiguousarray(scale).view(np.uint8).reshape(n, 4)
+    out[:, D + 4:D + 8] = np.ascontiguousarray(bias).view(np.uint8).reshape(n, 4)
+    return out
+
+
 def table_values_range(seed: int, first_row: int, nrows: int, D: int, dtype: str = "f32",
                        kind: int = KIND_NORMAL, chunk_rows: int = 1 << 16) -> np.ndarray:
     """Rows [first_row, first_row + nrows) of the arena, generated in chunks."""
-    out = np.empty((nrows, D), dtype={"f16": np.float16, "bf16": np.uint16}.get(dtype, np.float32))
+    if dtype == "u8row":
+        out = np.empty((nrows, D + 8), dtype=np.uint8)
+    else:
+        out = np.empty((nrows, D), dtype={"f16": np.float16, "bf16": np.uint16}.get(dtype, np.float32))
     for r0 in range(0, nrows, chunk_rows):
         r1 = min(nrows, r0 + chunk_rows)
         out[r0:r1] = table_values(seed, np.arange(first_row + r0, first_row + r1, dtype=np.uint64),
@@ -131,7 +161,7 @@ def fill_arena_device(dev_ptr: int, first_row: int, nrows: int, D: int, dtype: s
     """Fill arena rows [first_row, first_row+nrows) at device address `dev_ptr` (= address of
     row `first_row`) with `table_values`; asynchronous on `stream` (a hipStream_t as int)."""
     rc = load_lib().gen_fill_table(ctypes.c_void_p(dev_ptr), first_row, nrows, D,
-                                   {"f32": 0, "f16": 1, "bf16": 2}[dtype],
+                                   {"f32": 0, "f16": 1, "bf16": 2, "u8row": 3}[dtype],
                                    ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF), kind,
                                    ctypes.c_void_p(stream))
     if rc != 0:
@@ -146,12 +176,13 @@ class DeviceArena:
     been synchronised).  If the contiguous request is refused the arena falls back to an ordinary
     allocation and says so in `kind`."""
 
-    _TYPESTR = {"f32": "<f4", "f16": "<f2", "bf16": "<i2"}
+    _TYPESTR = {"f32": "<f4", "f16": "<f2", "bf16": "<i2", "u8row": "|u1"}
 
     def __init__(self, rows: int, D: int, dtype: str, contiguous: bool = True):
         import torch
         self.rows, self.D, self.dtype = int(rows), int(D), dtype
-        self.nbytes = self.rows * self.D * (4 if dtype == "f32" else 2)
+        width = self.D + 8 if dtype == "u8row" else self.D      # elements per row in the view
+        self.nbytes = self.rows * width * {"f32": 4, "u8row": 1}.get(dtype, 2)
         lib = load_lib()
         p = ctypes.c_void_p()
         self.kind = "hip-contiguous" if contiguous else "hip-default"
@@ -163,7 +194,7 @@ class DeviceArena:
         if rc != 0 or not p.value:
             raise MemoryError(f"gen_alloc_arena({self.nbytes}) failed with hipError {rc}")
         self.ptr = int(p.value)
-        self.__cuda_array_interface__ = {"shape": (self.rows, self.D), "typestr": self._TYPESTR[dtype],
+        self.__cuda_array_interface__ = {"shape": (self.rows, width), "typestr": self._TYPESTR[dtype],
                                          "data": (self.ptr, False), "version": 2, "strides": None}
         t = torch.as_tensor(self, device="cuda")
         self.tensor = t.view(torch.bfloat16) if dtype == "bf16" else t
@@ -207,7 +238,7 @@ class Workload:
     T: int                      # number of tables
     rows: Tuple[int, ...]       # rows per table (len T)
     D: int                      # embedding dimension (uniform over tables)
-    dtype: str                  # 'f32' | 'f16' | 'bf16' (table storage; output is always fp32)
+    dtype: str                  # 'f32' | 'f16' | 'bf16' | 'u8row' (table storage; output is fp32)
     B: int                      # batch (bags per table)
     pooling: Tuple              # ('fixed', L) | ('uniform', lo, hi) inclusive
     dists: Tuple[Tuple, ...]    # per table: ('uniform',) | ('zipf', alpha) | ('one_item',)
@@ -219,10 +250,12 @@ class Workload:
 
     @property
     def elem_bytes(self) -> int:
-        return 4 if self.dtype == "f32" else 2
+        return {"f32": 4, "u8row": 1}.get(self.dtype, 2)
 
     @property
     def row_bytes(self) -> int:
+        if self.dtype == "u8row":   # D one-byte codes + fp32 scale + fp32 bias
+            return self.D + 8
         return self.D * self.elem_bytes
 
     @property
@@ -313,6 +346,18 @@ def workload(name: str) -> Workload:
                         dtype="f32", B=131, pooling=("uniform", 0, 200),
                         dists=(("uniform",), ("zipf", 1.2), ("uniform",), ("uniform",)),
                         seed=0x5EED0012)
+    if name == "small_u8_d120":    # 128-byte quantised rows
+        return Workload(name="small_u8_d120", T=4, rows=(1200, 9, 2048, 77), D=120, dtype="u8row",
+                        B=83, pooling=("uniform", 0, 140),
+                        dists=(("uniform",), ("uniform",), ("zipf", 1.1), ("uniform",)),
+                        seed=0x5EED0015)
+    if name == "small_u8_d504":    # 512-byte quantised rows
+        return Workload(name="small_u8_d504", T=3, rows=(900, 65, 400), D=504, dtype="u8row",
+                        B=45, pooling=("uniform", 0, 130),
+                        dists=(("uniform",), ("zipf", 1.2), ("uniform",)), seed=0x5EED0016)
+    if name == "cfg3_u8":          # cfg3's shape with quantised rows (dim 120 -> 128-byte rows)
+        return _homog("cfg3_u8", 60, 4_000_000, 120, "u8row", 4096, ("fixed", 80), ("uniform",),
+                      seed_off=0x17)
     if name == "small_bf16_d256":  # 512-byte bfloat16 rows
         return Workload(name="small_bf16_d256", T=3, rows=(1500, 33, 700), D=256,
                         dtype="bf16", B=61, pooling=("uniform", 0, 130),

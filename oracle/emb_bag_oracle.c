@@ -21,8 +21,8 @@
  *   - per-sample weights are not in the paper: out = sum_j w_j * row_j, sum mode only.
  *   - summation order is not fixed by the paper: this oracle adds in index order, in fp64.
  *
- * Arithmetic: every table element is widened exactly (fp32, IEEE half or bfloat16 -> fp64) and
- * accumulated in fp64.  Alongside each output element the oracle returns bound = sum_j |w_j *
+ * Arithmetic: every table element is widened exactly (fp32, IEEE half or bfloat16 -> fp64; a
+ * quantised element is scale * code + bias evaluated in fp64) and accumulated in fp64.  Alongside each output element the oracle returns bound = sum_j |w_j *
  * x_j| (divided by the bag length in mean mode), the scale of the rounding-error tolerance.
  *
  * Parity pins (tests/test_oracle_pins.py): exact rational brute force on tiny inputs, index
@@ -67,10 +67,32 @@ static double bf16_bits_to_double(uint16_t h) {
   return (double)f;
 }
 
-static double table_elem(const void* tables, int dtype, int64_t arena_row, int64_t D, int64_t d) {
-  if (dtype == 1) return half_bits_to_double(((const uint16_t*)tables)[arena_row * D + d]);
-  if (dtype == 2) return bf16_bits_to_double(((const uint16_t*)tables)[arena_row * D + d]);
-  return (double)((const float*)tables)[arena_row * D + d];
+/*
+ * Element d of an arena row as a double, and the magnitude the error bound charges for it.
+ * dtype 3 is a row-wise quantised table: a row is D unsigned 8-bit codes followed by an fp32
+ * scale and an fp32 bias (row stride D + 8 bytes), and element d is scale * code_d + bias; its
+ * magnitude for the bound is |scale * code_d| + |bias|, the two terms an implementation adds.
+ */
+static double table_elem(const void* tables, int dtype, int64_t arena_row, int64_t D, int64_t d,
+                         double* magnitude) {
+  double x;
+  if (dtype == 3) {
+    const uint8_t* row = (const uint8_t*)tables + arena_row * (D + 8);
+    float scale, bias;
+    memcpy(&scale, row + D, sizeof scale);
+    memcpy(&bias, row + D + 4, sizeof bias);
+    const double sc = (double)scale * (double)row[d];
+    *magnitude = fabs(sc) + fabs((double)bias);
+    return sc + (double)bias;
+  }
+  if (dtype == 1)
+    x = half_bits_to_double(((const uint16_t*)tables)[arena_row * D + d]);
+  else if (dtype == 2)
+    x = bf16_bits_to_double(((const uint16_t*)tables)[arena_row * D + d]);
+  else
+    x = (double)((const float*)tables)[arena_row * D + d];
+  *magnitude = fabs(x);
+  return x;
 }
 
 int oracle_num_threads(void) {
@@ -93,9 +115,10 @@ void oracle_set_num_threads(int n) {
  * All pointers are HOST pointers.
  *   T, B, D        tables, batch, embedding dimension
  *   dtype          0 = fp32 tables, 1 = fp16 tables (raw half bit patterns),
- *                  2 = bfloat16 tables (raw bit patterns)
+ *                  2 = bfloat16 tables (raw bit patterns),
+ *                  3 = row-wise quantised tables: D uint8 codes + fp32 scale + fp32 bias per row
  *   mode           0 = sum, 1 = mean
- *   tables         arena [sum_t R_t, D], row-major
+ *   tables         arena [sum_t R_t, D], row-major ([sum_t R_t, D + 8] bytes for dtype 3)
  *   table_offsets  [T+1] first arena row of each table (so R_t = table_offsets[t+1]-table_offsets[t])
  *   indices        [NL] table-local row ids
  *   offsets        [T*B+1] CSR over bags in (t, b) order
@@ -108,7 +131,7 @@ int oracle_emb_bag(int32_t T, int64_t B, int32_t D, int32_t dtype, int32_t mode,
                    const void* tables, const int64_t* table_offsets, const int64_t* indices,
                    const int64_t* offsets, const float* weights, int64_t out_ld, double* ref,
                    double* bound) {
-  if (T < 1 || B < 0 || D < 1 || (dtype < 0 || dtype > 2) || (mode != 0 && mode != 1))
+  if (T < 1 || B < 0 || D < 1 || (dtype < 0 || dtype > 3) || (mode != 0 && mode != 1))
     return ORACLE_ERR_ARG;
   if (out_ld < (int64_t)T * D) return ORACLE_ERR_ARG;
   if (weights && mode != 0) return ORACLE_ERR_ARG;
@@ -141,10 +164,11 @@ int oracle_emb_bag(int32_t T, int64_t B, int32_t D, int32_t dtype, int32_t mode,
       double acc = 0.0;
       double mag = 0.0;
       for (int64_t j = s; j < e; ++j) {
-        const double x = table_elem(tables, dtype, table_offsets[t] + indices[j], D, d);
+        double ax;
+        const double x = table_elem(tables, dtype, table_offsets[t] + indices[j], D, d, &ax);
         const double w = weights ? (double)weights[j] : 1.0;
         acc += w * x;
-        mag += fabs(w * x);
+        mag += fabs(w) * ax;
       }
       if (mode == 1) {
         if (e > s) {

@@ -62,7 +62,8 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
             out_ld: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     """Reference output and error-bound scale, both fp64 [B, out_ld].
 
-    tables: [sum R_t, D] float32, float16 or uint16 (= bfloat16 bits) host array; table_offsets int64 [T+1];
+    tables: [sum R_t, D] float32, float16 or uint16 (= bfloat16 bits) host array, or uint8
+    [sum R_t, D + 8] (D codes, fp32 scale, fp32 bias per row: element = scale * code + bias); table_offsets int64 [T+1];
     indices int64 [NL]; offsets int64 [T*B+1]; weights float32 [NL] or None.
     Raises ValueError on the error codes of the C function.
     """
@@ -74,8 +75,13 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
         dtype = 1
     elif tables.dtype == np.uint16:   # numpy has no bfloat16: raw bit patterns
         dtype = 2
+    elif tables.dtype == np.uint8:    # row-wise quantised: D codes + fp32 scale + fp32 bias
+        dtype = 3
+        if tables.shape[1] <= 8:
+            raise ValueError("quantised rows need D + 8 bytes")
     else:
-        raise ValueError("tables must be float32, float16 or uint16 (bfloat16 bit patterns)")
+        raise ValueError("tables must be float32, float16, uint16 (bfloat16 bits) or uint8 "
+                         "(quantised rows)")
     tables = np.ascontiguousarray(tables)
     table_offsets = np.ascontiguousarray(table_offsets, dtype=np.int64)
     indices = np.ascontiguousarray(indices, dtype=np.int64)
@@ -85,7 +91,7 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
         if len(weights) != len(indices):
             raise ValueError("weights and indices differ in length")
     T = len(table_offsets) - 1
-    D = tables.shape[1]
+    D = tables.shape[1] - 8 if dtype == 3 else tables.shape[1]
     if len(offsets) != T * B + 1:
         raise ValueError("offsets must have T*B+1 entries")
     if int(offsets[-1]) != len(indices):

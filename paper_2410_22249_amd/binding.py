@@ -15,7 +15,7 @@ import torch  # imported before the library so that the HIP runtime torch ships 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libembbag.so")
 
-EMB_F32, EMB_F16, EMB_BF16 = 0, 1, 2
+EMB_F32, EMB_F16, EMB_BF16, EMB_U8ROW = 0, 1, 2, 3
 EMB_SUM, EMB_MEAN = 0, 1
 EMB_OK = 0
 

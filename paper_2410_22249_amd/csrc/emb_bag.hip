@@ -79,11 +79,38 @@ __device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
 
 __device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
 
-// acc += w * (one 16-byte segment of a row): 4 fp32 elements, or 8 fp16 / bf16 elements widened
-// exactly to fp32.
+// fp32 accumulators a lane keeps for its 16-byte segment of the row: 4 fp32 elements, 8 fp16 /
+// bf16 elements, or 16 one-byte codes plus one accumulator for the sum of the row biases.
+template <int ELEM>
+struct AccCount {
+  static constexpr int value = ELEM == EMB_F32 ? 4 : (ELEM == EMB_U8ROW ? 17 : 8);
+};
+
+// acc += w * (one 16-byte segment of a row): 4 fp32 elements, 8 fp16 / bf16 elements widened
+// exactly to fp32, or 16 codes of a row-wise quantised row.  For the latter the row's scale and
+// bias sit in the last 8 bytes of the row, i.e. in words z and w of lane `meta_lane`'s segment;
+// acc[i] collects w * scale * code_i and acc[16] collects w * bias, added to every element at the
+// end of the bag (a lookup that fetched nothing has scale = bias = 0).
 template <int ELEM, bool WEIGHTED>
-__device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w) {
-  if constexpr (ELEM != EMB_F32) {
+__device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int meta_lane) {
+  if constexpr (ELEM == EMB_U8ROW) {
+    float scale = as_float((uint32_t)__shfl((int)r.z, meta_lane));
+    float bias = as_float((uint32_t)__shfl((int)r.w, meta_lane));
+    if constexpr (WEIGHTED) {
+      scale *= w;
+      bias *= w;
+    }
+    const uint32_t u[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float code = (float)((u[i] >> (8 * k)) & 0xFFu);
+        acc[4 * i + k] = __builtin_fmaf(scale, code, acc[4 * i + k]);
+      }
+    }
+    acc[16] += bias;
+  } else if constexpr (ELEM != EMB_F32) {
     const uint32_t u[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -125,7 +152,8 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
                                            const float* __restrict__ weights, int64_t s,
                                            int64_t e, int64_t R, uint32_t row_bytes,
                                            const char* tbase, __amdgpu_buffer_rsrc_t rsrc,
-                                           int lane, int g, uint32_t col, bool lane_ok) {
+                                           int lane, int g, uint32_t col, bool lane_ok,
+                                           int meta_lane) {
   constexpr int G = kWaveSize / LPR;
   constexpr int kAux = NT ? 2 : 0;  // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
   for (int64_t c = s; c < e; c += kWaveSize) {
@@ -175,7 +203,7 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
         }
       }
 #pragma unroll
-      for (int d = 0; d < DEPTH; ++d) accumulate<ELEM, WEIGHTED>(acc, r[d], wj[d]);
+      for (int d = 0; d < DEPTH; ++d) accumulate<ELEM, WEIGHTED>(acc, r[d], wj[d], meta_lane);
     }
   }
 
@@ -188,8 +216,10 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
                     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
                     const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
                     float* __restrict__ out, KParams p) {
-  constexpr bool HALF = ELEM != EMB_F32;  // 2-byte elements
-  constexpr int NACC = HALF ? 8 : 4;      // fp32 accumulators per lane
+  constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;  // 2-byte elements
+  constexpr bool QUANT = ELEM == EMB_U8ROW;                   // 1-byte codes + scale, bias
+  constexpr int NACC = AccCount<ELEM>::value;                 // fp32 accumulators per lane
+  constexpr int NOUT = QUANT ? 16 : NACC;                     // output elements per lane
 
   const int lane = threadIdx.x & (kWaveSize - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -240,20 +270,29 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
   float acc[NACC];
 #pragma unroll
   for (int i = 0; i < NACC; ++i) acc[i] = 0.0f;
+  // quantised rows: the lane of this lane's group whose segment ends with the row's scale and bias
+  const int meta_lane = (lane & ~(LPR - 1)) + (int)(p.D >> 4);
 
   const bool streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
   if (streaming)
     gather_bag<LPR, ELEM, DEPTH, WEIGHTED, BUF, true>(acc, indices, weights, s, e, R, p.row_bytes,
-                                                     tbase, rsrc, lane, g, col, lane_ok);
+                                                     tbase, rsrc, lane, g, col, lane_ok,
+                                                     meta_lane);
   else
     gather_bag<LPR, ELEM, DEPTH, WEIGHTED, BUF, false>(acc, indices, weights, s, e, R, p.row_bytes,
-                                                      tbase, rsrc, lane, g, col, lane_ok);
+                                                      tbase, rsrc, lane, g, col, lane_ok,
+                                                      meta_lane);
+
+  if constexpr (QUANT) {
+#pragma unroll
+    for (int i = 0; i < NOUT; ++i) acc[i] += acc[16];
+  }
 
   // combine the G row groups (fixed butterfly: every lane ends with the same bits)
 #pragma unroll
   for (int m = kWaveSize / 2; m >= LPR; m >>= 1) {
 #pragma unroll
-    for (int i = 0; i < NACC; ++i) acc[i] += __shfl_xor(acc[i], m);
+    for (int i = 0; i < NOUT; ++i) acc[i] += __shfl_xor(acc[i], m);
   }
 
   if (p.mean) {
@@ -261,19 +300,21 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
     if (len > 0) {
       const float fl = (float)len;
 #pragma unroll
-      for (int i = 0; i < NACC; ++i) acc[i] = acc[i] / fl;
+      for (int i = 0; i < NOUT; ++i) acc[i] = acc[i] / fl;
     }
   }
 
   if (lane < LPR && lane_ok) {
-    // col counts bytes of the table row; the output is fp32
-    const uint32_t elem0 = HALF ? col / 2 : col / 4;
+    // col counts bytes of the table row; the output is fp32.  A quantised row ends with 8 codes
+    // and 8 bytes of scale and bias, so its last lane stores 8 elements instead of 16.
+    const uint32_t elem0 = QUANT ? col : (HALF ? col / 2 : col / 4);
     f32x4* dst = reinterpret_cast<f32x4*>(out + (int64_t)b * p.out_ld + (int64_t)t * p.D + elem0);
-    const f32x4 v0 = {acc[0], acc[1], acc[2], acc[3]};
-    __builtin_nontemporal_store(v0, dst);
-    if constexpr (HALF) {
-      const f32x4 v1 = {acc[4], acc[5], acc[6], acc[7]};
-      __builtin_nontemporal_store(v1, dst + 1);
+#pragma unroll
+    for (int q = 0; q < NOUT / 4; ++q) {
+      if (!QUANT || elem0 + 4 * q < p.D) {
+        const f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        __builtin_nontemporal_store(v, dst + q);
+      }
     }
   }
 }
@@ -407,6 +448,7 @@ KernelFn pick_dtype(int elem, int depth, bool weighted, bool buf) {
     case EMB_F32: return pick_depth<LPR, EMB_F32>(depth, weighted, buf);
     case EMB_F16: return pick_depth<LPR, EMB_F16>(depth, weighted, buf);
     case EMB_BF16: return pick_depth<LPR, EMB_BF16>(depth, weighted, buf);
+    case EMB_U8ROW: return pick_depth<LPR, EMB_U8ROW>(depth, weighted, buf);
     default: return nullptr;
   }
 }
@@ -424,11 +466,16 @@ KernelFn pick_kernel(int lpr, int elem, int depth, bool weighted, bool buf) {
 
 int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
   if (!d) return EMB_ERR_NULL_PTR;
-  if (d->table_dtype != EMB_F32 && d->table_dtype != EMB_F16 && d->table_dtype != EMB_BF16)
+  if (d->table_dtype != EMB_F32 && d->table_dtype != EMB_F16 && d->table_dtype != EMB_BF16 &&
+      d->table_dtype != EMB_U8ROW)
     return EMB_ERR_BAD_DTYPE;
   if (d->mode != EMB_SUM && d->mode != EMB_MEAN) return EMB_ERR_BAD_MODE;
   if (d->num_tables < 1 || d->dim < 1) return EMB_ERR_BAD_DIM;
-  const int64_t row_bytes = (int64_t)d->dim * (d->table_dtype == EMB_F32 ? 4 : 2);
+  int64_t row_bytes = (int64_t)d->dim * (d->table_dtype == EMB_F32 ? 4 : 2);
+  if (d->table_dtype == EMB_U8ROW) {
+    row_bytes = (int64_t)d->dim + 8;  // one-byte codes, then fp32 scale and fp32 bias
+    if (row_bytes > kSlabBytes) return EMB_ERR_BAD_DIM;
+  }
   if (row_bytes % 16 != 0 || row_bytes > 65536) return EMB_ERR_BAD_DIM;
   if (d->batch < 0 || d->num_lookups < 0 || d->max_table_rows < 0) return EMB_ERR_BAD_SIZE;
   *row_bytes_out = (uint32_t)row_bytes;

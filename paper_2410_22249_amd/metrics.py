@@ -10,15 +10,16 @@ from __future__ import annotations
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth, GB/s (decimal)
 
 
-def gathered_bytes(num_lookups: int, dim: int, elem_bytes: int) -> int:
-    """Bytes of table rows gathered: one row of dim*elem_bytes per lookup."""
-    return int(num_lookups) * int(dim) * int(elem_bytes)
+def gathered_bytes(num_lookups: int, dim: int, elem_bytes: int, row_bytes: int = 0) -> int:
+    """Bytes of table rows gathered: one row of dim*elem_bytes per lookup (`row_bytes`, when given,
+    overrides the product: quantised rows carry 8 bytes of scale and bias)."""
+    return int(num_lookups) * (int(row_bytes) if row_bytes else int(dim) * int(elem_bytes))
 
 
 def algorithmic_bytes(num_lookups: int, num_tables: int, batch: int, dim: int, elem_bytes: int,
-                      weighted: bool = False) -> int:
+                      weighted: bool = False, row_bytes: int = 0) -> int:
     """Gathered rows + int64 indices + int64 CSR offsets + fp32 output (+ fp32 weights)."""
-    total = gathered_bytes(num_lookups, dim, elem_bytes)
+    total = gathered_bytes(num_lookups, dim, elem_bytes, row_bytes)
     total += 8 * int(num_lookups)
     total += 8 * (int(num_tables) * int(batch) + 1)
     total += 4 * int(batch) * int(num_tables) * int(dim)

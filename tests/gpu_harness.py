@@ -31,8 +31,15 @@ def upload_arena(arena: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(arena).to(DEV)
 
 
-TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
-EMB_DTYPE = {torch.float32: emb.EMB_F32, torch.float16: emb.EMB_F16, torch.bfloat16: emb.EMB_BF16}
+TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16,
+               "u8row": torch.uint8}
+EMB_DTYPE = {torch.float32: emb.EMB_F32, torch.float16: emb.EMB_F16, torch.bfloat16: emb.EMB_BF16,
+             torch.uint8: emb.EMB_U8ROW}
+
+
+def arena_dim(arena: torch.Tensor) -> int:
+    """Logical embedding dimension: quantised (uint8) rows carry 8 bytes of scale and bias."""
+    return arena.shape[1] - 8 if arena.dtype == torch.uint8 else arena.shape[1]
 
 
 def arena_bytes(arena: torch.Tensor) -> np.ndarray:
@@ -42,7 +49,8 @@ def arena_bytes(arena: torch.Tensor) -> np.ndarray:
 
 def device_arena(wl: gen.Workload) -> torch.Tensor:
     """Allocate the arena on the device and fill it with the generator's kernel."""
-    arena = torch.empty((wl.total_rows, wl.D), dtype=TORCH_DTYPE[wl.dtype], device=DEV)
+    width = wl.D + 8 if wl.dtype == "u8row" else wl.D
+    arena = torch.empty((wl.total_rows, width), dtype=TORCH_DTYPE[wl.dtype], device=DEV)
     gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed, wl.kind,
                           torch.cuda.current_stream().cuda_stream)
     return arena
@@ -53,7 +61,7 @@ def forward(arena: torch.Tensor, table_offsets: np.ndarray, indices, offsets, B:
             out: Optional[torch.Tensor] = None, fill: float = float("nan")) -> torch.Tensor:
     """Run emb_bag_forward; numpy inputs are uploaded, torch inputs are used as they are."""
     T = len(table_offsets) - 1
-    D = arena.shape[1]
+    D = arena_dim(arena)
     toff_np = np.asarray(table_offsets, dtype=np.int64)
     if max_table_rows is None:
         max_table_rows = int(np.max(np.diff(toff_np))) if T else 0

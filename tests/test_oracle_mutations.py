@@ -17,8 +17,15 @@ WRAP = os.path.join(ROOT, "oracle", "emb_bag_oracle.py")
 
 MUTATIONS = {
     "weight dropped from the sum": ("acc += w * x;", "acc += x;"),
-    "bound without abs": ("mag += fabs(w * x);", "mag += w * x;"),
-    "table base ignored": ("table_offsets[t] + indices[j], D, d)", "indices[j], D, d)"),
+    "bound without abs": ("mag += fabs(w) * ax;", "mag += w * ax;"),
+    "bound of a float element without abs": ("  *magnitude = fabs(x);\n  return x;", "  *magnitude = x;\n  return x;"),
+    "quantised element without its bias": ("return sc + (double)bias;", "return sc;"),
+    "quantised scale and bias swapped": ("memcpy(&scale, row + D, sizeof scale);\n    memcpy(&bias, row + D + 4, sizeof bias);",
+                                         "memcpy(&bias, row + D, sizeof scale);\n    memcpy(&scale, row + D + 4, sizeof bias);"),
+    "quantised row stride without the scale and bias": ("(const uint8_t*)tables + arena_row * (D + 8);", "(const uint8_t*)tables + arena_row * D;"),
+    "quantised code read as signed": ("(double)scale * (double)row[d];", "(double)scale * (double)(int8_t)row[d];"),
+    "quantised bound forgets the bias": ("*magnitude = fabs(sc) + fabs((double)bias);", "*magnitude = fabs(sc);"),
+    "table base ignored": ("table_offsets[t] + indices[j], D, d, &ax)", "indices[j], D, d, &ax)"),
     "first lookup of a bag skipped": ("for (int64_t j = s; j < e; ++j) {", "for (int64_t j = s + 1; j < e; ++j) {"),
     "last lookup of a bag skipped": ("for (int64_t j = s; j < e; ++j) {", "for (int64_t j = s; j < e - 1; ++j) {"),
     "bags taken in (b, t) order": ("const int64_t t = g / B;\n    const int64_t b = g % B;",
@@ -29,9 +36,10 @@ MUTATIONS = {
                                         "ref[b * out_ld + (T - 1 - t) * D + d] = acc;"),
     "mean divides by len + 1": ("acc /= (double)(e - s);", "acc /= (double)(e - s + 1);"),
     "mean of bound forgotten": ("mag /= (double)(e - s);", ""),
-    "columns reversed when reading a row": ("[arena_row * D + d]);\n  return (double)", "[arena_row * D + (D - 1 - d)]);\n  return (double)"),
-    "fp32 rows read with the wrong stride": ("return (double)((const float*)tables)[arena_row * D + d];",
-                                             "return (double)((const float*)tables)[arena_row * (D - 1) + d];"),
+    "columns reversed when reading a half row": ("x = half_bits_to_double(((const uint16_t*)tables)[arena_row * D + d]);",
+                                                 "x = half_bits_to_double(((const uint16_t*)tables)[arena_row * D + (D - 1 - d)]);"),
+    "fp32 rows read with the wrong stride": ("x = (double)((const float*)tables)[arena_row * D + d];",
+                                             "x = (double)((const float*)tables)[arena_row * (D - 1) + d];"),
     "half exponent bias off by one": ("expo - 25", "expo - 24"),
     "half subnormal scale off by one": ("ldexp((double)frac, -24)", "ldexp((double)frac, -25)"),
     "half sign dropped": ("return sign ? -v : v;", "return v;"),
@@ -54,6 +62,8 @@ PIN_FUNCS = [
     pins.test_bound_is_sum_of_abs_terms,
     pins.test_half_widening_is_exact,
     pins.test_bfloat16_widening_is_exact,
+    pins.test_quantised_rows_brute_force,
+    pins.test_quantised_rows_equal_their_dequantised_table,
 ]
 
 

@@ -340,6 +340,74 @@ def test_bfloat16_widening_is_exact(oracle):
     assert np.array_equal(ra, rb) and np.array_equal(ba, bb)
 
 
+def _quantised_table(rng, rows, D):
+    """uint8 [rows, D + 8]: D codes, then fp32 scale and fp32 bias (little endian)."""
+    t = np.zeros((rows, D + 8), dtype=np.uint8)
+    t[:, :D] = rng.integers(0, 256, size=(rows, D))
+    scale = rng.uniform(0.001, 0.01, size=rows).astype(np.float32)
+    bias = rng.uniform(-1.0, 1.0, size=rows).astype(np.float32)
+    t[:, D:D + 4] = scale.view(np.uint8).reshape(rows, 4)
+    t[:, D + 4:D + 8] = bias.view(np.uint8).reshape(rows, 4)
+    return t, scale, bias
+
+
+def test_quantised_rows_brute_force(oracle):
+    """Row-wise quantised rows: element = scale * code + bias, checked in exact rationals."""
+    rng = np.random.default_rng(31)
+    R, D, B = 9, 8, 4
+    table, scale, bias = _quantised_table(rng, R, D)
+    toff = np.array([0, 5, 9], dtype=np.int64)          # two tables of 5 and 4 rows
+    lengths = np.array([3, 0, 2, 4, 1, 0, 5, 2])
+    offsets = gen.lengths_to_offsets(lengths)
+    idx = np.concatenate([rng.integers(0, 5, size=lengths[:4].sum()),
+                          rng.integers(0, 4, size=lengths[4:].sum())]).astype(np.int64)
+    w = rng.uniform(-1, 1, size=len(idx)).astype(np.float32)
+    for mode, weights in (("sum", None), ("mean", None), ("sum", w)):
+        ref, bound = oracle.emb_bag(table, toff, idx, offsets, B, mode, weights=weights)
+        for t in range(2):
+            for b in range(B):
+                lo, hi = int(offsets[t * B + b]), int(offsets[t * B + b + 1])
+                for d in range(D):
+                    a = Fraction(0)
+                    m = Fraction(0)
+                    for j in range(lo, hi):
+                        r = int(toff[t]) + int(idx[j])
+                        ww = Fraction(float(weights[j])) if weights is not None else Fraction(1)
+                        sc = Fraction(float(scale[r])) * int(table[r, d])
+                        a += ww * (sc + Fraction(float(bias[r])))
+                        m += abs(ww) * (abs(sc) + abs(Fraction(float(bias[r]))))
+                    if mode == "mean" and hi > lo:
+                        a, m = a / (hi - lo), m / (hi - lo)
+                    tol = 16 * 2.0 ** -53 * float(m) + 1e-300
+                    assert abs(ref[b, t * D + d] - float(a)) <= tol
+                    assert abs(bound[b, t * D + d] - float(m)) <= tol
+
+
+def test_quantised_rows_equal_their_dequantised_table(oracle):
+    """Looking up quantised rows equals looking up the table dequantised in fp64 beforehand
+    (here: codes chosen so that scale * code + bias is exact in fp32)."""
+    rng = np.random.default_rng(32)
+    R, D, B = 40, 24, 6
+    table = np.zeros((R, D + 8), dtype=np.uint8)
+    table[:, :D] = rng.integers(0, 256, size=(R, D))
+    scale = (2.0 ** rng.integers(-6, 2, size=R)).astype(np.float32)      # powers of two
+    bias = (scale * rng.integers(-128, 128, size=R)).astype(np.float32)
+    table[:, D:D + 4] = scale.view(np.uint8).reshape(R, 4)
+    table[:, D + 4:] = bias.view(np.uint8).reshape(R, 4)
+    deq = (scale[:, None] * table[:, :D].astype(np.float32) + bias[:, None]).astype(np.float32)
+    toff = np.array([0, R], dtype=np.int64)
+    lengths = rng.integers(0, 12, size=B)
+    offsets = gen.lengths_to_offsets(lengths)
+    idx = rng.integers(0, R, size=int(offsets[-1])).astype(np.int64)
+    rq, bq = oracle.emb_bag(table, toff, idx, offsets, B, "sum")
+    rf, bf = oracle.emb_bag(deq, toff, idx, offsets, B, "sum")
+    assert np.array_equal(rq, rf)
+    assert np.all(bq >= bf)          # |scale*code| + |bias| >= |scale*code + bias|
+    # a single lookup returns the dequantised row itself
+    r1, _ = oracle.emb_bag(table, toff, np.array([7], np.int64), np.array([0, 1], np.int64), 1)
+    assert np.array_equal(r1[0], deq[7].astype(np.float64))
+
+
 def test_rejects_bad_inputs(oracle):
     table = np.ones((4, 4), np.float32)
     toff = np.array([0, 4], dtype=np.int64)

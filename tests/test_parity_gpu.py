@@ -25,7 +25,7 @@ def _problem(name, **over):
 
 
 @pytest.mark.parametrize("name", ["tiny", "small_f32_d64", "small_f32_d128", "small_f16_d256",
-                                  "small_bf16_d256"])
+                                  "small_bf16_d256", "small_u8_d120", "small_u8_d504"])
 @pytest.mark.parametrize("mode", ["sum", "mean"])
 @pytest.mark.parametrize("addressing", [0, 1])
 def test_small_workloads_match_oracle(oracle, name, mode, addressing):
@@ -39,7 +39,7 @@ def test_small_workloads_match_oracle(oracle, name, mode, addressing):
 
 @pytest.mark.parametrize("depth", [1, 2, 4, 8, 16])
 @pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
-                                  "small_bf16_d256"])
+                                  "small_bf16_d256", "small_u8_d120", "small_u8_d504"])
 def test_every_depth(oracle, name, depth):
     wl, batch, arena = _problem(name)
     ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
@@ -51,7 +51,7 @@ def test_every_depth(oracle, name, depth):
 
 
 @pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
-                                  "small_bf16_d256"])
+                                  "small_bf16_d256", "small_u8_d120", "small_u8_d504"])
 def test_integer_tables_are_bit_exact(oracle, name):
     """Integer-valued tables: every partial sum is exact in fp32, so any order gives the same bits."""
     wl, batch, arena = _problem(name, kind=gen.KIND_INT)
@@ -65,7 +65,7 @@ def test_integer_tables_are_bit_exact(oracle, name):
 
 
 @pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
-                                  "small_bf16_d256"])
+                                  "small_bf16_d256", "small_u8_d120", "small_u8_d504"])
 def test_per_sample_weights(oracle, name):
     wl, batch, arena = _problem(name, weighted=True)
     assert batch.weights is not None
@@ -83,7 +83,9 @@ def test_per_sample_weights(oracle, name):
 @pytest.mark.parametrize("D,dtype", [(4, "f32"), (12, "f32"), (32, "f32"), (96, "f32"),
                                      (256, "f32"), (320, "f32"), (1024, "f32"), (8, "f16"),
                                      (24, "f16"), (128, "f16"), (520, "f16"), (2048, "f16"),
-                                     (8, "bf16"), (72, "bf16"), (512, "bf16"), (1032, "bf16")])
+                                     (8, "bf16"), (72, "bf16"), (512, "bf16"), (1032, "bf16"),
+                                     (8, "u8row"), (24, "u8row"), (56, "u8row"), (88, "u8row"),
+                                     (248, "u8row"), (312, "u8row"), (1016, "u8row")])
 def test_general_row_widths(oracle, D, dtype):
     wl = gen.Workload(name=f"w{D}{dtype}", T=3, rows=(300, 17, 64), D=D, dtype=dtype, B=21,
                       pooling=("uniform", 0, 90), dists=(("uniform",),) * 3, seed=0x5EED0100 + D)
@@ -256,10 +258,11 @@ def test_rows_beyond_max_table_rows_read_as_zero(oracle):
     assert_close_to_oracle(got, ref, bound, False, "max_table_rows clamp")
 
 
-@pytest.mark.parametrize("dtype,kind", [("f32", 0), ("f16", 0), ("bf16", 0), ("f32", 1), ("f16", 1),
-                                        ("bf16", 1)])
+@pytest.mark.parametrize("dtype,kind", [("f32", 0), ("f16", 0), ("bf16", 0), ("u8row", 0), ("f32", 1),
+                                        ("f16", 1), ("bf16", 1), ("u8row", 1)])
 def test_device_fill_matches_host_values_bit_for_bit(dtype, kind):
-    wl = gen.Workload(name="fill", T=2, rows=(7001, 4099), D=128 if dtype == "f32" else 256,
+    wl = gen.Workload(name="fill", T=2, rows=(7001, 4099),
+                      D={"f32": 128, "u8row": 120}.get(dtype, 256),
                       dtype=dtype, B=1, pooling=("fixed", 1), dists=(("uniform",),) * 2,
                       seed=0x5EED0300, kind=kind)
     dev = device_arena(wl)
@@ -267,7 +270,7 @@ def test_device_fill_matches_host_values_bit_for_bit(dtype, kind):
     host = gen.host_arena(wl)
     assert np.array_equal(arena_bytes(dev), host.view(np.uint8))
     # a slab filled from a non-zero first row matches the same rows of the whole
-    part = torch.empty((1000, wl.D), dtype=dev.dtype, device=DEV)
+    part = torch.empty((1000, dev.shape[1]), dtype=dev.dtype, device=DEV)
     gen.fill_arena_device(part.data_ptr(), 5000, 1000, wl.D, dtype, wl.seed, kind,
                           torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
@@ -320,7 +323,8 @@ def test_forward_replays_correctly_from_a_hip_graph(oracle):
 def test_table_hints_change_speed_only(oracle):
     """Streaming hints switch the cache policy of the row loads; results must not move a bit."""
     import paper_2410_22249_amd as emb
-    for name in ("small_f32_d64", "small_f32_d128", "small_f16_d256", "small_bf16_d256"):
+    for name in ("small_f32_d64", "small_f32_d128", "small_f16_d256", "small_bf16_d256",
+                 "small_u8_d120"):
         wl = gen.workload(name)
         batch = gen.make_batches(wl, 1)[0]
         host = gen.host_arena(wl)
@@ -382,9 +386,11 @@ def test_randomised_shapes(oracle):
     dtypes, modes, weights, padded leading dimensions, addressing and launch knobs drawn at random."""
     rng = np.random.default_rng(0xE3B)
     for case in range(40):
-        dtype = ("f32", "f16", "bf16")[int(rng.integers(0, 3))]
+        dtype = ("f32", "f16", "bf16", "u8row")[int(rng.integers(0, 4))]
         unit = 4 if dtype == "f32" else 8
         D = int(unit * rng.integers(1, 80))                      # rows of 16 B .. 1264 B
+        if dtype == "u8row":
+            D = int(16 * rng.integers(0, 63) + 8)                # D + 8 a multiple of 16, <= 1024
         T = int(rng.integers(1, 12))
         rows = tuple(int(x) for x in rng.integers(1, 3000, size=T))
         B = int(rng.integers(1, 90))
@@ -459,11 +465,22 @@ def test_gpu_invariants_without_the_oracle():
     assert np.array_equal(a12, a1 + a2)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_quantised_rows_reject_bad_shapes():
+    import ctypes
+    import paper_2410_22249_amd as emb
+    fake = ctypes.c_void_p(0x1000)
+    for dim, want in ((120, None), (128, -2), (1016, None), (1032, -2), (4, -2)):
+        desc = emb.make_desc(2, 4, dim, emb.EMB_U8ROW, emb.EMB_SUM, 10)
+        rc = emb.lib().emb_bag_validate(ctypes.byref(desc), None, fake, fake, fake, None)
+        assert rc == (want if want is not None else -1), dim    # -1: shape accepted, NULL pointer
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "u8row"])
 def test_hip_allocated_arena_gives_the_same_result(oracle, dtype):
     """Arenas allocated by the generator straight from HIP (physically contiguous on request)
     are ordinary device memory: same fill, same forward result as a torch allocation."""
-    wl = gen.Workload(name="arena", T=3, rows=(900, 40, 333), D=128 if dtype == "f32" else 256,
+    wl = gen.Workload(name="arena", T=3, rows=(900, 40, 333),
+                      D={"f32": 128, "u8row": 248}.get(dtype, 256),
                       dtype=dtype, B=37, pooling=("uniform", 0, 70), dists=(("uniform",),) * 3,
                       seed=0x5EED0800)
     batch = gen.make_batches(wl, 1)[0]
