@@ -47,8 +47,10 @@ def _setup(name: str, n_batches: int):
 
     wl = gen.workload(name)
     dev = "cuda:0"
-    arena = torch.empty((wl.total_rows, wl.D),
-                        dtype={"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[wl.dtype], device=dev)
+    tdtype = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16,
+              "u8row": torch.uint8}[wl.dtype]
+    width = wl.D + 8 if wl.dtype == "u8row" else wl.D   # quantised rows end with scale and bias
+    arena = torch.empty((wl.total_rows, width), dtype=tdtype, device=dev)
     gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed, wl.kind,
                           torch.cuda.current_stream().cuda_stream)
     batches = gen.make_batches(wl, n_batches)
@@ -56,7 +58,8 @@ def _setup(name: str, n_batches: int):
     dev_batches = [(torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev),
                     None if b.weights is None else torch.from_numpy(b.weights).to(dev))
                    for b in batches]
-    edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16}[wl.dtype]
+    edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16,
+           "u8row": emb.EMB_U8ROW}[wl.dtype]
     emode = emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM
     hints = torch.zeros(wl.T, dtype=torch.uint8, device=dev)
     d0 = emb.make_desc(wl.T, wl.B, wl.D, edt, emode, batches[0].num_lookups, 0, max(wl.rows))
@@ -109,7 +112,7 @@ def main(argv: List[str] = None) -> int:
     state = _setup(a.workload, a.batches)
     wl, batches, hints = state[0], state[6], state[7]
     nl = float(np.mean([b.num_lookups for b in batches]))
-    gathered = metrics.gathered_bytes(nl, wl.D, wl.elem_bytes)
+    gathered = metrics.gathered_bytes(nl, wl.D, wl.elem_bytes, wl.row_bytes)
     print(f"# {a.workload}: {nl:.0f} lookups/launch, {gathered / 1e9:.3f} GB gathered, "
           f"{int(hints.sum().item())}/{wl.T} tables classified streaming")
     results = []

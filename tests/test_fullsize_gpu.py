@@ -21,7 +21,7 @@ pytestmark = pytest.mark.gpu
 def _run(wl, batch, arena, toff):
     idx, off = to_dev(batch.indices), to_dev(batch.offsets)
     out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
-    desc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16}[wl.dtype],
+    desc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16, "u8row": emb.EMB_U8ROW}[wl.dtype],
                          emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, batch.num_lookups, 0,
                          max(wl.rows))
     emb.emb_bag_forward(desc, arena, toff, idx, off, None, out)
@@ -83,7 +83,7 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     assert np.array_equal(hints.cpu().numpy(), rh)
     expect = np.array([1 if d[0] == "uniform" else 0 for d in wl.dists], dtype=np.uint8)
     assert np.array_equal(rh, expect), "uniform tables stream, skewed tables stay cached"
-    hdesc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16}[wl.dtype],
+    hdesc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16, "u8row": emb.EMB_U8ROW}[wl.dtype],
                           emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, batch.num_lookups,
                           0, max(wl.rows), hints)
     emb.emb_bag_forward(hdesc, arena, toff, idx, off, None, out2)
