@@ -20,6 +20,22 @@ TARGETS = {
 }
 
 
+C_DRIVER_SRC = "tests/c_abi/c_abi_driver.c"
+C_DRIVER_BIN = "tests/c_abi/c_abi_driver"
+
+
+def build_c_driver(verbose: bool = True) -> None:
+    """The plain-C caller of the ABI (gcc, HIP runtime API, no torch): proves the boundary is C."""
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+           "-I", os.path.join(ROOT, "include"), "-o", os.path.join(ROOT, C_DRIVER_BIN),
+           os.path.join(ROOT, C_DRIVER_SRC), "-L", PKG, "-lembbag", "-L/opt/rocm/lib",
+           "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN/../../paper_2410_22249_amd",
+           "-Wl,-rpath,/opt/rocm/lib"]
+    if verbose:
+        print("[build]", " ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+
+
 def build_all(verbose: bool = True) -> None:
     for out, srcs in TARGETS.items():
         cmd = [HIPCC] + HIP_FLAGS + ["-I", os.path.join(ROOT, "include"), "-o",
@@ -33,11 +49,12 @@ def build_all(verbose: bool = True) -> None:
             print(log, flush=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed for {out}")
+    build_c_driver(verbose)
 
 
 def ensure_built(verbose: bool = True) -> None:
     """Build only if a library is missing (tests, smoke() and bench.py load what is there)."""
-    if not all(os.path.exists(os.path.join(ROOT, out)) for out in TARGETS):
+    if not all(os.path.exists(os.path.join(ROOT, out)) for out in list(TARGETS) + [C_DRIVER_BIN]):
         build_all(verbose=verbose)
 
 

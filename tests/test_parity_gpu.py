@@ -502,3 +502,15 @@ def test_hip_allocated_arena_gives_the_same_result(oracle, dtype):
     host = gen.host_arena(wl)
     ref, bound = oracle.emb_bag(host, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
     assert_close_to_oracle(want, ref, bound, dtype != "f32", "hip arena")
+
+
+def test_plain_c_caller_of_the_abi():
+    """tests/c_abi/c_abi_driver.c links libembbag.so and the HIP runtime from C (no Python, no
+    torch in its process), runs sum and mean on a small problem and checks them itself."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = os.path.join(root, "tests", "c_abi", "c_abi_driver")
+    assert os.path.exists(exe), "build() compiles the C driver"
+    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=100)
+    assert r.returncode == 0 and "C ABI OK" in r.stdout, r.stdout
