@@ -514,3 +514,31 @@ def test_plain_c_caller_of_the_abi():
     assert os.path.exists(exe), "build() compiles the C driver"
     r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=100)
     assert r.returncode == 0 and "C ABI OK" in r.stdout, r.stdout
+
+
+def test_concurrent_calls_on_two_streams(oracle):
+    """The library keeps no state between calls (no scratch, no retained pointers): two calls
+    enqueued on different streams with different outputs do not disturb each other."""
+    import paper_2410_22249_amd as emb
+    wl = gen.Workload(name="streams", T=8, rows=(5000,) * 8, D=128, dtype="f32", B=512,
+                      pooling=("uniform", 0, 90), dists=(("uniform",),) * 8, seed=0x5EED0B00)
+    b0, b1 = gen.make_batches(wl, 2)
+    host = gen.host_arena(wl)
+    arena = upload_arena(host)
+    toff = to_dev(wl.table_offsets())
+    dev = [(to_dev(b.indices), to_dev(b.offsets)) for b in (b0, b1)]
+    outs = [torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
+            for _ in range(2)]
+    descs = [emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F32, emb.EMB_SUM, b.num_lookups, 0, max(wl.rows))
+             for b in (b0, b1)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for k in range(2):
+            emb.emb_bag_forward(descs[k], arena, toff, dev[k][0], dev[k][1], None, outs[k], streams[k])
+    torch.cuda.synchronize()
+    for k, b in enumerate((b0, b1)):
+        ref, bound = oracle.emb_bag(host, wl.table_offsets(), b.indices, b.offsets, wl.B)
+        assert_close_to_oracle(outs[k].cpu().numpy(), ref, bound, False, f"stream {k}")
+        alone = forward(arena, wl.table_offsets(), b.indices, b.offsets, wl.B).cpu().numpy()
+        assert np.array_equal(outs[k].cpu().numpy(), alone)
