@@ -32,6 +32,7 @@ DESCRIPTIONS = {
     "paper": "250 fp32 tables x 500,000 rows x dim 128, batch 2048, pooling 150 fixed, uniform "
              "indices, sum (the paper's model, random dataset)",
     "paper_one_item": "250 fp32 tables x 500,000 x dim 128, batch 2048, pooling 150, one item, sum",
+    "cfg3_weighted": "cfg3 with fp32 per-sample weights",
     "cfg3_u8": "cfg3's shape with row-wise quantised rows: 60 tables x 4,000,000 rows x dim 120 "
                "(uint8 codes + fp32 scale, bias = 128-byte rows), batch 4096, pooling 80, uniform, sum",
     "paper_high": "paper's model, Zipf(1.3396) stand-in for its high-hot trace (4.05 % unique)",
@@ -245,9 +246,9 @@ def main() -> int:
         nb = wl.num_bags
         bags = np.unique(np.concatenate([rng.integers(0, nb, size=args.check_bags),
                                          [0, wl.B - 1, nb - wl.B, nb - 1]]))
-        small, ix, off = gen.compact_rows(wl, batches[k], bags)
+        small, ix, off, wsmall = gen.compact_rows(wl, batches[k], bags)
         ref, bound = emb_bag_oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, off,
-                                            len(bags), wl.mode)
+                                            len(bags), wl.mode, weights=wsmall)
         got_all = out.view(wl.B, wl.T, wl.D)
         tb = torch.from_numpy(np.stack([bags % wl.B, bags // wl.B], 1)).to(dev)
         got = got_all[tb[:, 0], tb[:, 1]].cpu().numpy().astype(np.float64)

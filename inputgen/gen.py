@@ -355,6 +355,8 @@ def workload(name: str) -> Workload:
         return Workload(name="small_u8_d504", T=3, rows=(900, 65, 400), D=504, dtype="u8row",
                         B=45, pooling=("uniform", 0, 130),
                         dists=(("uniform",), ("zipf", 1.2), ("uniform",)), seed=0x5EED0016)
+    if name == "cfg3_weighted":    # cfg3 with per-sample weights
+        return with_overrides(workload("cfg3"), name="cfg3_weighted", weighted=True)
     if name == "cfg3_u8":          # cfg3's shape with quantised rows (dim 120 -> 128-byte rows)
         return _homog("cfg3_u8", 60, 4_000_000, 120, "u8row", 4096, ("fixed", 80), ("uniform",),
                       seed_off=0x17)
@@ -487,18 +489,24 @@ def host_arena(wl: Workload) -> np.ndarray:
 def compact_rows(wl: Workload, batch: Batch, bag_ids: Sequence[int]):
     """For a subset of bags, build a small self-contained problem (one 'table' holding only the
     rows those bags touch) so that a host-side checker can evaluate sampled bags of an arena
-    that does not fit in host memory.  Returns (arena_small, indices_small, offsets_small)
-    where bag i of the small problem equals bag bag_ids[i] of the full one."""
+    that does not fit in host memory.  Returns (arena_small, indices_small, offsets_small,
+    weights_small) where bag i of the small problem equals bag bag_ids[i] of the full one
+    (weights_small is None for an unweighted batch)."""
     toff = wl.table_offsets()
-    segs, lens = [], []
+    segs, lens, wsegs = [], [], []
     for g in bag_ids:
         t = int(g) // wl.B
         s, e = int(batch.offsets[g]), int(batch.offsets[g + 1])
         segs.append(batch.indices[s:e] + toff[t])
         lens.append(e - s)
+        if batch.weights is not None:
+            wsegs.append(batch.weights[s:e])
     arena_rows = np.concatenate(segs) if segs else np.zeros(0, dtype=np.int64)
     uniq, inv = np.unique(arena_rows, return_inverse=True)
     small = table_values(wl.seed, uniq, wl.D, wl.dtype, wl.kind)
     if len(uniq) == 0:
         small = np.zeros((1, wl.D), dtype=small.dtype)
-    return small, inv.astype(np.int64), lengths_to_offsets(np.asarray(lens, dtype=np.int64))
+    wsmall = None
+    if batch.weights is not None:
+        wsmall = np.concatenate(wsegs).astype(np.float32) if wsegs else np.zeros(0, np.float32)
+    return small, inv.astype(np.int64), lengths_to_offsets(np.asarray(lens, dtype=np.int64)), wsmall

@@ -20,16 +20,17 @@ pytestmark = pytest.mark.gpu
 
 def _run(wl, batch, arena, toff):
     idx, off = to_dev(batch.indices), to_dev(batch.offsets)
+    w = to_dev(batch.weights)
     out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
     desc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16, "u8row": emb.EMB_U8ROW}[wl.dtype],
                          emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, batch.num_lookups, 0,
                          max(wl.rows))
-    emb.emb_bag_forward(desc, arena, toff, idx, off, None, out)
+    emb.emb_bag_forward(desc, arena, toff, idx, off, w, out)
     bad = torch.zeros(1, dtype=torch.int64, device=DEV)
     emb.emb_bag_validate(desc, toff, idx, off, bad)
     torch.cuda.synchronize()
     assert int(bad.item()) == 0
-    return out, (desc, idx, off)
+    return out, (desc, idx, off, w)
 
 
 def _sample_bags(wl, n, seed=2024):
@@ -50,7 +51,8 @@ def test_cfg1_whole_output(oracle):
 
 
 @pytest.mark.parametrize("name,nsample", [("cfg2", 2000), ("cfg3", 600), ("cfg4", 600),
-                                          ("cfg5", 600), ("paper", 400)])
+                                          ("cfg5", 600), ("paper", 400), ("cfg3_weighted", 300),
+                                          ("cfg3_u8", 300)])
 def test_full_size_sampled_bags(oracle, name, nsample):
     print(f"\n[fullsize] {name}: generating", flush=True)
     wl = gen.workload(name)
@@ -58,16 +60,17 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     arena = device_arena(wl)
     toff = to_dev(wl.table_offsets())
     print(f"[fullsize] {name}: {batch.num_lookups} lookups, arena {wl.table_bytes / 1e9:.1f} GB", flush=True)
-    out, (desc, idx, off) = _run(wl, batch, arena, toff)
+    out, (desc, idx, off, w) = _run(wl, batch, arena, toff)
     assert bool(torch.isfinite(out).all())                    # every bag was written
     # run-to-run determinism over the whole output
     out2 = torch.full_like(out, float("nan"))
-    emb.emb_bag_forward(desc, arena, toff, idx, off, None, out2)
+    emb.emb_bag_forward(desc, arena, toff, idx, off, w, out2)
     torch.cuda.synchronize()
     assert torch.equal(out, out2)
     bags = _sample_bags(wl, nsample)
-    small, ix, soff = gen.compact_rows(wl, batch, bags)
-    ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, soff, len(bags), wl.mode)
+    small, ix, soff, wsmall = gen.compact_rows(wl, batch, bags)
+    ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, soff, len(bags),
+                                wl.mode, weights=wsmall)
     sel = torch.from_numpy(np.stack([bags % wl.B, bags // wl.B], 1)).to(DEV)
     got = out.view(wl.B, wl.T, wl.D)[sel[:, 0], sel[:, 1]].cpu().numpy()
     worst = assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"{name} sampled")
@@ -86,13 +89,13 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     hdesc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16, "u8row": emb.EMB_U8ROW}[wl.dtype],
                           emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, batch.num_lookups,
                           0, max(wl.rows), hints)
-    emb.emb_bag_forward(hdesc, arena, toff, idx, off, None, out2)
+    emb.emb_bag_forward(hdesc, arena, toff, idx, off, w, out2)
     torch.cuda.synchronize()
     assert torch.equal(out, out2), "hints must not change results"
     # the alternative launch shapes give the same bits at full size too
     for kw in (dict(xcd_remap=1), dict(addressing=1, depth=8)):
         with tuning(**kw):
-            emb.emb_bag_forward(desc, arena, toff, idx, off, None, out2)
+            emb.emb_bag_forward(desc, arena, toff, idx, off, w, out2)
             torch.cuda.synchronize()
         assert torch.equal(out, out2), kw
     print(f"[fullsize] {name}: {len(bags)} bags checked, max err/bound {worst:.3e}", flush=True)

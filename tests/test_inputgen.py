@@ -116,8 +116,23 @@ def test_compact_rows_reproduces_full_problem(oracle):
     arena = gen.host_arena(wl)
     ref, _ = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
     bags = [0, 5, wl.B, 2 * wl.B + 17, wl.T * wl.B - 1]
-    small, ix, off = gen.compact_rows(wl, batch, bags)
+    small, ix, off, wsmall = gen.compact_rows(wl, batch, bags)
+    assert wsmall is None
     r2, _ = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, off, len(bags))
+    for i, g in enumerate(bags):
+        t, b = divmod(g, wl.B)
+        assert np.array_equal(r2[i], ref[b, t * wl.D:(t + 1) * wl.D])
+
+
+def test_compact_rows_carries_weights(oracle):
+    wl = gen.with_overrides(gen.workload("small_f32_d64"), weighted=True)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    ref, _ = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                            weights=batch.weights)
+    bags = [1, wl.B + 3, wl.T * wl.B - 2]
+    small, ix, off, wsmall = gen.compact_rows(wl, batch, bags)
+    r2, _ = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, off, len(bags), weights=wsmall)
     for i, g in enumerate(bags):
         t, b = divmod(g, wl.B)
         assert np.array_equal(r2[i], ref[b, t * wl.D:(t + 1) * wl.D])
