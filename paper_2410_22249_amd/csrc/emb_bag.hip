@@ -22,6 +22,10 @@
 //     is below 3.5 GiB: the hardware range check turns an invalid row into zeros instead of a
 //     fault, and address arithmetic stays 32-bit.  Larger tables use 64-bit global addressing
 //     with an explicit check;
+//   * a table that the caller marks as streaming (rows not re-used within a batch; the outcome of
+//     the access-pattern profiling the paper does offline, Sec. 4.3 and Sec. 7) has its rows read
+//     with the non-temporal policy, a re-used table with the default policy;
+//   * rows may be fp32, fp16, bf16 (widened exactly) or row-wise quantised 8-bit codes;
 //   * partial sums of the G row groups are combined with a fixed xor butterfly (deterministic),
 //     the mean is one division per element per bag, and the result leaves with 16-byte
 //     non-temporal stores so that it does not displace table rows in L2 / MALL.
