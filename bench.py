@@ -312,7 +312,7 @@ def main() -> int:
                    "arena_allocation": arena_kind,
                    "streaming_tables": None if hints is None else int(hints.sum().item()),
                    "tuning": {k: emb.emb_bag_get_tuning(k) for k in
-                              ("depth", "addressing", "blocks_per_cu", "xcd_remap", "use_hints", "kernel")}},
+                              ("depth", "addressing", "blocks_per_cu", "xcd_remap", "use_hints")}},
         "gathered_GBps": gathered * args.steps / wall / 1e9,
         "gathered_frac_of_hbm_peak": gathered * args.steps / wall / 1e9 / metrics.HBM_PEAK_GBPS,
         "kernel_ms": {"avg": avg_kern_s * 1e3, "min": float(min(kern_ms)),

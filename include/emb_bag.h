@@ -162,7 +162,6 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
  *                   (the stand-in for the L2 pinning of Sec. 4.3); 0 = natural order;
  *                   -1 = automatic (on for large launches)
  *   "use_hints"     1 (default) = honour desc->table_hints, 0 = ignore them
- *   "kernel"        0 = automatic, 1 = one bag per wavefront
  * Not thread-safe against concurrent emb_bag_forward calls.
  */
 int emb_bag_set_tuning(const char* key, int64_t value);

@@ -417,7 +417,6 @@ struct Tuning {
   int64_t addressing = 0;
   int64_t blocks_per_cu = 0;
   int64_t xcd_remap = -1;
-  int64_t kernel = 0;
   int64_t use_hints = 1;
 };
 Tuning g_tuning;
@@ -636,9 +635,6 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
   } else if (!strcmp(key, "xcd_remap")) {
     if (value < -1 || value > 1) return EMB_ERR_BAD_TUNING;
     g_tuning.xcd_remap = value;
-  } else if (!strcmp(key, "kernel")) {
-    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
-    g_tuning.kernel = value;
   } else if (!strcmp(key, "use_hints")) {
     if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
     g_tuning.use_hints = value;
@@ -654,7 +650,6 @@ int emb_bag_get_tuning(const char* key, int64_t* value) {
   else if (!strcmp(key, "addressing")) *value = g_tuning.addressing;
   else if (!strcmp(key, "blocks_per_cu")) *value = g_tuning.blocks_per_cu;
   else if (!strcmp(key, "xcd_remap")) *value = g_tuning.xcd_remap;
-  else if (!strcmp(key, "kernel")) *value = g_tuning.kernel;
   else if (!strcmp(key, "use_hints")) *value = g_tuning.use_hints;
   else return EMB_ERR_BAD_TUNING;
   return EMB_OK;
