@@ -116,6 +116,46 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
                     const float* per_sample_weights, float* out, void* stream);
 
 /*
+ * emb_bag_forward_mixed - the same pooled lookup for tables of DIFFERENT widths D_t.
+ *
+ *   The paper's tables are homogeneous (Sec. 5); production models mix widths.  Table t holds
+ *   rows of D_t elements (row = D_t * sizeof(element) bytes, D_t + 8 for EMB_U8ROW; every row size
+ *   a multiple of 16 and at most 1024 bytes) stored contiguously from BYTE offset
+ *   table_byte_offsets[t] of the arena (R_t = (table_byte_offsets[t+1] - table_byte_offsets[t]) /
+ *   row bytes), and its result occupies output columns [out_offsets[t], out_offsets[t+1]) with
+ *   out_offsets[t+1] - out_offsets[t] = D_t.
+ *
+ *   desc                HOST    shape; desc->dims is a HOST array of the T widths, used to check
+ *                               the call; the kernel itself reads the widths from out_offsets
+ *   tables              DEVICE  arena bytes, 16-byte aligned; every table starts 16-byte aligned
+ *   table_byte_offsets  DEVICE  int64 [T+1], non-decreasing
+ *   out_offsets         DEVICE  int64 [T+1], out_offsets[0] >= 0, multiples of 4, last <= out_ld
+ *   indices, offsets, per_sample_weights, out, stream   as in emb_bag_forward
+ *
+ * table_byte_offsets and out_offsets describe the model, not the batch, and are trusted the way
+ * table_offsets is; a table whose entries contradict the rules above is skipped (nothing is
+ * written for it).  Index and bag-bound defects are neutralised as in emb_bag_forward.
+ */
+typedef struct emb_bag_mixed_desc {
+  int32_t num_tables;      /* T >= 1 */
+  int32_t table_dtype;     /* EMB_F32, EMB_F16, EMB_BF16 or EMB_U8ROW (one type for all tables) */
+  int32_t mode;            /* EMB_SUM or EMB_MEAN */
+  int32_t reserved;        /* 0 */
+  int64_t batch;           /* B >= 0 */
+  int64_t num_lookups;     /* NL = offsets[T*B] */
+  int64_t out_ld;          /* leading dimension of out in floats; 0 means sum_t D_t */
+  int64_t max_table_bytes; /* upper bound on the largest table in bytes, or 0 if unknown; a bound
+                              below 3.5 GiB selects 32-bit buffer addressing */
+  const int32_t* dims;     /* HOST, T widths D_t */
+  const uint8_t* table_hints; /* DEVICE, T bytes of EMB_HINT_*, or NULL */
+} emb_bag_mixed_desc;
+
+int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
+                          const int64_t* table_byte_offsets, const int64_t* out_offsets,
+                          const int64_t* indices, const int64_t* offsets,
+                          const float* per_sample_weights, float* out, void* stream);
+
+/*
  * emb_bag_validate - count the data-dependent defects emb_bag_forward neutralises.
  *
  *   Adds to *num_bad (DEVICE, one int64 that the caller has zeroed, on the same stream) one for

@@ -289,6 +289,81 @@ def expected_unique_fraction(R: int, alpha: float, n: int) -> float:
     return float(np.mean(-np.expm1(n * np.log1p(-p))))
 
 
+@dataclass(frozen=True)
+class MixedWorkload:
+    """Tables of different widths (one element type).  Same batch machinery as `Workload`."""
+    name: str
+    T: int
+    rows: Tuple[int, ...]
+    dims: Tuple[int, ...]       # embedding dimension of each table
+    dtype: str
+    B: int
+    pooling: Tuple
+    dists: Tuple[Tuple, ...]
+    mode: str = "sum"
+    weighted: bool = False
+    seed: int = 0x5EED0000
+    kind: int = KIND_NORMAL
+
+    @property
+    def num_bags(self) -> int:
+        return self.T * self.B
+
+    def row_bytes_of(self, t: int) -> int:
+        d = self.dims[t]
+        return d + 8 if self.dtype == "u8row" else d * (4 if self.dtype == "f32" else 2)
+
+    def table_byte_offsets(self) -> np.ndarray:
+        sizes = [self.rows[t] * self.row_bytes_of(t) for t in range(self.T)]
+        return np.concatenate([[0], np.cumsum(np.asarray(sizes, dtype=np.int64))]).astype(np.int64)
+
+    def out_offsets(self) -> np.ndarray:
+        return np.concatenate([[0], np.cumsum(np.asarray(self.dims, dtype=np.int64))]).astype(np.int64)
+
+    def row_bases(self) -> np.ndarray:
+        """First procedural row id of each table (rows are numbered across tables)."""
+        return np.concatenate([[0], np.cumsum(np.asarray(self.rows, dtype=np.int64))]).astype(np.int64)
+
+    @property
+    def table_bytes(self) -> int:
+        return int(self.table_byte_offsets()[-1])
+
+    def gathered_bytes(self, batch: "Batch") -> int:
+        per_table = np.diff(batch.offsets[::self.B])
+        return int(sum(int(per_table[t]) * self.row_bytes_of(t) for t in range(self.T)))
+
+
+def mixed_host_tables(wl: MixedWorkload) -> List[np.ndarray]:
+    """Per-table host arrays with the same procedural values the device fill produces."""
+    base = wl.row_bases()
+    return [table_values_range(wl.seed, int(base[t]), wl.rows[t], wl.dims[t], wl.dtype, wl.kind)
+            for t in range(wl.T)]
+
+
+def mixed_fill_device(wl: MixedWorkload, arena_ptr: int, stream: int = 0) -> None:
+    """Fill a device arena laid out by `table_byte_offsets` (one fill launch per table)."""
+    base, boff = wl.row_bases(), wl.table_byte_offsets()
+    for t in range(wl.T):
+        fill_arena_device(arena_ptr + int(boff[t]), int(base[t]), wl.rows[t], wl.dims[t], wl.dtype,
+                          wl.seed, wl.kind, stream)
+
+
+def mixed_workload(name: str) -> MixedWorkload:
+    if name == "mixed_small":
+        return MixedWorkload(name=name, T=7, rows=(500, 33, 1000, 1, 257, 64, 90),
+                             dims=(64, 4, 128, 256, 32, 96, 12), dtype="f32", B=53,
+                             pooling=("uniform", 0, 120),
+                             dists=(("uniform",), ("uniform",), ("zipf", 1.1), ("one_item",),
+                                    ("uniform",), ("uniform",), ("uniform",)), seed=0x5EED0C01)
+    if name == "mixed_cfg":   # 60 tables x 4 M rows, widths cycling 32 / 64 / 128 / 256 fp32 (108 GB)
+        T = 60
+        return MixedWorkload(name=name, T=T, rows=(4_000_000,) * T,
+                             dims=tuple((32, 64, 128, 256)[t % 4] for t in range(T)), dtype="f32",
+                             B=4096, pooling=("fixed", 80), dists=(("uniform",),) * T,
+                             seed=0x5EED0C02)
+    raise KeyError(name)
+
+
 def _homog(name, T, R, D, dtype, B, pooling, dist, mode="sum", seed_off=0, **kw) -> Workload:
     return Workload(name=name, T=T, rows=(R,) * T, D=D, dtype=dtype, B=B, pooling=pooling,
                     dists=(dist,) * T, mode=mode, seed=0x5EED0000 + seed_off, **kw)

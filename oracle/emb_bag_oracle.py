@@ -108,3 +108,31 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
         raise ValueError({-1: "bad argument", -2: "offsets not monotone from 0",
                           -3: "index out of range"}.get(rc, f"oracle error {rc}"))
     return ref, bound
+
+
+def emb_bag_mixed(tables, indices: np.ndarray, offsets: np.ndarray, B: int, mode: str = "sum",
+                  weights: Optional[np.ndarray] = None,
+                  out_ld: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """Tables of different widths: `tables` is a list of per-table host arrays ([R_t, D_t], or
+    uint8 [R_t, D_t + 8] for quantised rows).  The definition is unchanged - bag (t, b) pools rows
+    of table t - and table t's block starts at column sum of the widths before it; each table is
+    evaluated on its own by `emb_bag`."""
+    T = len(tables)
+    dims = [a.shape[1] - 8 if a.dtype == np.uint8 else a.shape[1] for a in tables]
+    total = int(sum(dims))
+    ld = out_ld if out_ld else total
+    if ld < total:
+        raise ValueError("out_ld smaller than the sum of the widths")
+    ref = np.zeros((B, ld), dtype=np.float64)
+    bound = np.zeros((B, ld), dtype=np.float64)
+    col = 0
+    for t in range(T):
+        o = np.asarray(offsets[t * B:(t + 1) * B + 1], dtype=np.int64)
+        s, e = int(o[0]), int(o[-1])
+        w = None if weights is None else weights[s:e]
+        r, b = emb_bag(tables[t], np.array([0, tables[t].shape[0]], np.int64), indices[s:e], o - s,
+                       B, mode, weights=w)
+        ref[:, col:col + dims[t]] = r
+        bound[:, col:col + dims[t]] = b
+        col += dims[t]
+    return ref, bound

@@ -21,7 +21,7 @@ EMB_OK = 0
 
 EMB_HINT_DEFAULT, EMB_HINT_STREAMING = 0, 1
 
-EXPORTS = ("emb_bag_forward", "emb_bag_validate", "emb_bag_profile_reuse", "emb_bag_set_tuning",
+EXPORTS = ("emb_bag_forward", "emb_bag_forward_mixed", "emb_bag_validate", "emb_bag_profile_reuse", "emb_bag_set_tuning",
            "emb_bag_get_tuning", "emb_bag_status_string", "emb_bag_version")
 
 
@@ -31,6 +31,14 @@ class emb_bag_desc(ctypes.Structure):
                 ("batch", ctypes.c_int64), ("num_lookups", ctypes.c_int64),
                 ("out_ld", ctypes.c_int64), ("max_table_rows", ctypes.c_int64),
                 ("table_hints", ctypes.c_void_p)]
+
+
+class emb_bag_mixed_desc(ctypes.Structure):
+    _fields_ = [("num_tables", ctypes.c_int32), ("table_dtype", ctypes.c_int32),
+                ("mode", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("batch", ctypes.c_int64), ("num_lookups", ctypes.c_int64),
+                ("out_ld", ctypes.c_int64), ("max_table_bytes", ctypes.c_int64),
+                ("dims", ctypes.POINTER(ctypes.c_int32)), ("table_hints", ctypes.c_void_p)]
 
 
 class EmbBagError(RuntimeError):
@@ -47,6 +55,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     P = ctypes.c_void_p
     lib.emb_bag_forward.restype = ctypes.c_int
     lib.emb_bag_forward.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, P, P, P, P, P]
+    lib.emb_bag_forward_mixed.restype = ctypes.c_int
+    lib.emb_bag_forward_mixed.argtypes = [ctypes.POINTER(emb_bag_mixed_desc), P, P, P, P, P, P, P, P]
     lib.emb_bag_validate.restype = ctypes.c_int
     lib.emb_bag_validate.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, P, P, P]
     lib.emb_bag_profile_reuse.restype = ctypes.c_int
@@ -107,6 +117,34 @@ def emb_bag_forward(desc: emb_bag_desc, tables: torch.Tensor, table_offsets: tor
                               _stream_handle(stream))
     if rc != EMB_OK:
         raise EmbBagError(rc, "emb_bag_forward")
+
+
+def make_mixed_desc(dims, batch: int, table_dtype: int, mode: int, num_lookups: int,
+                    out_ld: int = 0, max_table_bytes: int = 0,
+                    table_hints: Optional[torch.Tensor] = None) -> emb_bag_mixed_desc:
+    """Host descriptor for tables of different widths; `dims` is a sequence of the T widths (the
+    descriptor keeps its own host copy alive)."""
+    arr = (ctypes.c_int32 * len(dims))(*[int(d) for d in dims])
+    desc = emb_bag_mixed_desc(num_tables=len(dims), table_dtype=table_dtype, mode=mode, reserved=0,
+                              batch=batch, num_lookups=num_lookups, out_ld=out_ld,
+                              max_table_bytes=max_table_bytes,
+                              dims=ctypes.cast(arr, ctypes.POINTER(ctypes.c_int32)),
+                              table_hints=_ptr(table_hints))
+    desc._dims_keepalive = arr
+    return desc
+
+
+def emb_bag_forward_mixed(desc: emb_bag_mixed_desc, tables: torch.Tensor,
+                          table_byte_offsets: torch.Tensor, out_offsets: torch.Tensor,
+                          indices: torch.Tensor, offsets: torch.Tensor,
+                          per_sample_weights: Optional[torch.Tensor], out: torch.Tensor,
+                          stream=None) -> None:
+    """Enqueue the pooled lookup over tables of different widths (see include/emb_bag.h)."""
+    rc = _lib.emb_bag_forward_mixed(ctypes.byref(desc), _ptr(tables), _ptr(table_byte_offsets),
+                                    _ptr(out_offsets), _ptr(indices), _ptr(offsets),
+                                    _ptr(per_sample_weights), _ptr(out), _stream_handle(stream))
+    if rc != EMB_OK:
+        raise EmbBagError(rc, "emb_bag_forward_mixed")
 
 
 def emb_bag_validate(desc: emb_bag_desc, table_offsets: torch.Tensor, indices: torch.Tensor,

@@ -149,7 +149,8 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int met
 }
 
 // The gather of one bag (one column slab of it): walk the bag's lookups in chunks of 64 and add
-// the rows into acc.  NT selects the non-temporal cache policy for the row loads (tables whose
+// the rows into acc.  LPR is the number of lanes per row (0: decided per table at run time, then
+// 2^glog2 rows share a wave load).  NT selects the non-temporal cache policy for the row loads (tables whose
 // rows are not re-used within a batch), the default policy otherwise.
 template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool BUF, bool NT>
 __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict__ indices,
@@ -157,8 +158,9 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
                                            int64_t e, int64_t R, uint32_t row_bytes,
                                            const char* tbase, __amdgpu_buffer_rsrc_t rsrc,
                                            int lane, int g, uint32_t col, bool lane_ok,
-                                           int meta_lane) {
-  constexpr int G = kWaveSize / LPR;
+                                           int meta_lane, int glog2) {
+  // log2 of the rows per wave load: a constant for a fixed LPR, a wave-uniform value for LPR == 0
+  const int gl = LPR ? __builtin_ctz((unsigned)(kWaveSize / (LPR ? LPR : 1))) : glog2;
   constexpr int kAux = NT ? 2 : 0;  // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
   for (int64_t c = s; c < e; c += kWaveSize) {
     const int64_t left = e - c;
@@ -178,13 +180,13 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
       if (idx_ok) roff = idx * (int64_t)row_bytes;
     }
 
-    const int steps = (n + G - 1) / G;
+    const int steps = (n + (1 << gl) - 1) >> gl;
     for (int k0 = 0; k0 < steps; k0 += DEPTH) {
       u32x4 r[DEPTH];
       float wj[DEPTH];
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
-        const int j = (k0 + d) * G + g;  // lookup of this chunk served by this lane's group
+        const int j = ((k0 + d) << gl) + g;  // lookup of this chunk served by this lane's group
         const bool take = (j < n) && lane_ok;
         if constexpr (BUF) {
           uint32_t vo = (uint32_t)__shfl((int)voff, j & (kWaveSize - 1));
@@ -213,13 +215,17 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
 
 }
 
-// One wavefront per (bag, column slab).  LPR = lanes per row (power of two, 4..64).
+// One wavefront per (bag, column slab).  LPR = lanes per row (power of two, 4..64), or 0 for
+// tables of different widths: then table t is described by table_offsets[t] (its BYTE offset in
+// the arena) and out_offsets[t] (its first output column; its width is the difference to the next
+// entry), the lanes per row are chosen per wavefront, and rows are at most 1 KiB.
 template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool BUF>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
                     const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
-                    float* __restrict__ out, KParams p) {
+                    const int64_t* __restrict__ out_offsets, float* __restrict__ out, KParams p) {
+  constexpr bool MIXED = LPR == 0;
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;  // 2-byte elements
   constexpr bool QUANT = ELEM == EMB_U8ROW;                   // 1-byte codes + scale, bias
   constexpr int NACC = AccCount<ELEM>::value;                 // fp32 accumulators per lane
@@ -258,34 +264,61 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
   s = s < 0 ? 0 : (s > p.num_lookups ? p.num_lookups : s);
   e = e < s ? s : (e > p.num_lookups ? p.num_lookups : e);
 
-  const int64_t row0 = uniform64(table_offsets[t]);
-  int64_t R = uniform64(table_offsets[t + 1]) - row0;
-  if (R < 0) R = 0;
-  if (BUF && R > p.max_rows) R = p.max_rows;
+  // per-table geometry
+  uint32_t D_t = p.D, row_bytes = p.row_bytes;
+  int64_t out_col = (int64_t)t * p.D;
+  int lpr = LPR ? LPR : 4;
+  const char* tbase;
+  int64_t R;
+  if constexpr (MIXED) {
+    out_col = uniform64(out_offsets[t]);
+    const int64_t out_next = uniform64(out_offsets[t + 1]);
+    const int64_t d64 = out_next - out_col;
+    const int64_t rb64 = QUANT ? d64 + 8 : d64 * (HALF ? 2 : 4);
+    // a malformed table description writes nothing (the host checked its own copy of the widths)
+    if (d64 <= 0 || rb64 > kSlabBytes || (rb64 & 15) || out_col < 0 || (out_col & 3) ||
+        out_next > p.out_ld)
+      return;
+    D_t = (uint32_t)d64;
+    row_bytes = (uint32_t)rb64;
+    while ((uint32_t)lpr * 16u < row_bytes) lpr <<= 1;
+    const int64_t byte0 = uniform64(table_offsets[t]);
+    int64_t bytes = uniform64(table_offsets[t + 1]) - byte0;
+    if (bytes < 0) bytes = 0;
+    if (BUF && bytes > (int64_t)kBufMaxBytes) bytes = (int64_t)kBufMaxBytes;
+    R = bytes / row_bytes;
+    tbase = tables + byte0;
+  } else {
+    const int64_t row0 = uniform64(table_offsets[t]);
+    R = uniform64(table_offsets[t + 1]) - row0;
+    if (R < 0) R = 0;
+    if (BUF && R > p.max_rows) R = p.max_rows;
+    tbase = tables + row0 * (int64_t)p.row_bytes;
+  }
+  const int lpr_log2 = __builtin_ctz((unsigned)lpr);
 
-  const int g = lane / LPR;
-  const uint32_t col = slab * kSlabBytes + (uint32_t)(lane & (LPR - 1)) * 16u;
-  const bool lane_ok = col < p.row_bytes;
+  const int g = lane >> lpr_log2;
+  const uint32_t col = slab * kSlabBytes + (uint32_t)(lane & (lpr - 1)) * 16u;
+  const bool lane_ok = col < row_bytes;
 
-  const char* tbase = tables + row0 * (int64_t)p.row_bytes;
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<char*>(tbase), 0, BUF ? (uint32_t)((uint64_t)R * p.row_bytes) : 0u, kBufWord3);
+      const_cast<char*>(tbase), 0, BUF ? (uint32_t)((uint64_t)R * row_bytes) : 0u, kBufWord3);
 
   float acc[NACC];
 #pragma unroll
   for (int i = 0; i < NACC; ++i) acc[i] = 0.0f;
   // quantised rows: the lane of this lane's group whose segment ends with the row's scale and bias
-  const int meta_lane = (lane & ~(LPR - 1)) + (int)(p.D >> 4);
+  const int meta_lane = (lane & ~(lpr - 1)) + (int)(D_t >> 4);
 
   const bool streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
   if (streaming)
-    gather_bag<LPR, ELEM, DEPTH, WEIGHTED, BUF, true>(acc, indices, weights, s, e, R, p.row_bytes,
+    gather_bag<LPR, ELEM, DEPTH, WEIGHTED, BUF, true>(acc, indices, weights, s, e, R, row_bytes,
                                                      tbase, rsrc, lane, g, col, lane_ok,
-                                                     meta_lane);
+                                                     meta_lane, 6 - lpr_log2);
   else
-    gather_bag<LPR, ELEM, DEPTH, WEIGHTED, BUF, false>(acc, indices, weights, s, e, R, p.row_bytes,
+    gather_bag<LPR, ELEM, DEPTH, WEIGHTED, BUF, false>(acc, indices, weights, s, e, R, row_bytes,
                                                       tbase, rsrc, lane, g, col, lane_ok,
-                                                      meta_lane);
+                                                      meta_lane, 6 - lpr_log2);
 
   if constexpr (QUANT) {
 #pragma unroll
@@ -294,9 +327,11 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
 
   // combine the G row groups (fixed butterfly: every lane ends with the same bits)
 #pragma unroll
-  for (int m = kWaveSize / 2; m >= LPR; m >>= 1) {
+  for (int m = kWaveSize / 2; m >= 4; m >>= 1) {
+    if (m >= lpr) {  // wave-uniform; a compile-time constant unless LPR == 0
 #pragma unroll
-    for (int i = 0; i < NOUT; ++i) acc[i] += __shfl_xor(acc[i], m);
+      for (int i = 0; i < NOUT; ++i) acc[i] += __shfl_xor(acc[i], m);
+    }
   }
 
   if (p.mean) {
@@ -308,14 +343,14 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
     }
   }
 
-  if (lane < LPR && lane_ok) {
+  if (lane < lpr && lane_ok) {
     // col counts bytes of the table row; the output is fp32.  A quantised row ends with 8 codes
     // and 8 bytes of scale and bias, so its last lane stores 8 elements instead of 16.
     const uint32_t elem0 = QUANT ? col : (HALF ? col / 2 : col / 4);
-    f32x4* dst = reinterpret_cast<f32x4*>(out + (int64_t)b * p.out_ld + (int64_t)t * p.D + elem0);
+    f32x4* dst = reinterpret_cast<f32x4*>(out + (int64_t)b * p.out_ld + out_col + elem0);
 #pragma unroll
     for (int q = 0; q < NOUT / 4; ++q) {
-      if (!QUANT || elem0 + 4 * q < p.D) {
+      if (!QUANT || elem0 + 4 * q < D_t) {
         const f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
         __builtin_nontemporal_store(v, dst + q);
       }
@@ -422,7 +457,7 @@ struct Tuning {
 Tuning g_tuning;
 
 using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int64_t*,
-                          const float*, const uint8_t*, float*, KParams);
+                          const float*, const uint8_t*, const int64_t*, float*, KParams);
 
 template <int LPR, int ELEM, int DEPTH>
 KernelFn pick_wb(bool weighted, bool buf) {
@@ -435,6 +470,8 @@ KernelFn pick_wb(bool weighted, bool buf) {
 
 template <int LPR, int ELEM>
 KernelFn pick_depth(int depth, bool weighted, bool buf) {
+  if constexpr (LPR == 0)  // tables of different widths: two depths are enough
+    return depth <= 4 ? pick_wb<LPR, ELEM, 4>(weighted, buf) : pick_wb<LPR, ELEM, 8>(weighted, buf);
   switch (depth) {
     case 1: return pick_wb<LPR, ELEM, 1>(weighted, buf);
     case 2: return pick_wb<LPR, ELEM, 2>(weighted, buf);
@@ -458,6 +495,7 @@ KernelFn pick_dtype(int elem, int depth, bool weighted, bool buf) {
 
 KernelFn pick_kernel(int lpr, int elem, int depth, bool weighted, bool buf) {
   switch (lpr) {
+    case 0: return pick_dtype<0>(elem, depth, weighted, buf);
     case 4: return pick_dtype<4>(elem, depth, weighted, buf);
     case 8: return pick_dtype<8>(elem, depth, weighted, buf);
     case 16: return pick_dtype<16>(elem, depth, weighted, buf);
@@ -483,6 +521,59 @@ int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
   if (d->batch < 0 || d->num_lookups < 0 || d->max_table_rows < 0) return EMB_ERR_BAD_SIZE;
   *row_bytes_out = (uint32_t)row_bytes;
   return EMB_OK;
+}
+
+// Choose the kernel instantiation, lay out the grid (natural or XCD-affine order), apply the
+// occupancy cap, and launch.  `p` holds the shape; the XCD fields are filled here.
+int enqueue(int lpr, int elem, int depth, bool buf, int64_t T, KParams p, const void* tables,
+            const int64_t* table_offsets, const int64_t* indices, const int64_t* offsets,
+            const float* weights, const uint8_t* table_hints, const int64_t* out_offsets,
+            float* out, void* stream) {
+  KernelFn fn = pick_kernel(lpr, elem, depth, weights != nullptr, buf);
+  if (!fn) return EMB_ERR_BAD_TUNING;
+  const int64_t num_work = p.num_work;
+  const int64_t waves_per_table_i = num_work / T;
+  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = 0;
+
+  uint32_t blocks = (uint32_t)((num_work + kWavesPerBlock - 1) / kWavesPerBlock);
+  const bool remap = g_tuning.xcd_remap == 1 || (g_tuning.xcd_remap == -1 && blocks >= 4096);
+  if (remap && blocks >= 64) {
+    // pieces per table: the smallest power of two that makes T * pieces a multiple of 8, so
+    // that every XCD gets the same number of pieces and neighbouring XCDs share a table
+    uint32_t pshift = 0;
+    while (((uint64_t)T << pshift) % 8 != 0) ++pshift;
+    const uint64_t waves_per_table = (uint64_t)waves_per_table_i;
+    const uint64_t wpp = (waves_per_table + (1u << pshift) - 1) >> pshift;
+    const uint64_t bpp = (wpp + kWavesPerBlock - 1) / kWavesPerBlock;
+    const uint64_t grid = ((uint64_t)T << pshift) * bpp;
+    if (grid <= 0x7FFFFFFFull) {
+      p.xcd_bpp = (uint32_t)bpp;
+      p.xcd_wpp = (uint32_t)wpp;
+      p.xcd_pshift = pshift;
+      blocks = (uint32_t)grid;
+    }
+  }
+
+  // A cap on resident workgroups per CU is imposed through a dynamic LDS request that the
+  // kernel never touches: k workgroups fit when each asks for 1/k of the CU's LDS.
+  uint32_t lds = 0;
+  if (g_tuning.blocks_per_cu > 0) {
+    int dev = 0, lds_per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor,
+                              dev) != hipSuccess || lds_per_cu <= 0)
+      return EMB_ERR_LAUNCH;
+    lds = ((uint32_t)lds_per_cu / (uint32_t)g_tuning.blocks_per_cu) & ~1023u;
+    if (lds > 65536u &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return EMB_ERR_LAUNCH;
+  }
+
+  hipLaunchKernelGGL(fn, dim3(blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
+                     static_cast<const char*>(tables), table_offsets, indices, offsets, weights,
+                     table_hints, out_offsets, out, p);
+  return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
 }
 
 }  // namespace
@@ -521,10 +612,6 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   int depth = (int)g_tuning.depth;
   if (depth == 0) depth = (desc->table_dtype == EMB_F32 && row_bytes >= 512) ? 8 : 4;
 
-  KernelFn fn = pick_kernel(lpr, desc->table_dtype, depth,
-                            per_sample_weights != nullptr, buf);
-  if (!fn) return EMB_ERR_BAD_TUNING;
-
   KParams p;
   p.num_lookups = desc->num_lookups;
   p.out_ld = out_ld;
@@ -536,47 +623,62 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   p.D = (uint32_t)D;
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
-  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = 0;
+  return enqueue(lpr, desc->table_dtype, depth, buf, T, p, tables, table_offsets, indices, offsets,
+                 per_sample_weights, desc->table_hints, nullptr, out, stream);
+}
 
-  uint32_t blocks = (uint32_t)((num_work + kWavesPerBlock - 1) / kWavesPerBlock);
-  const bool remap = g_tuning.xcd_remap == 1 || (g_tuning.xcd_remap == -1 && blocks >= 4096);
-  if (remap && blocks >= 64) {
-    // pieces per table: the smallest power of two that makes T * pieces a multiple of 8, so
-    // that every XCD gets the same number of pieces and neighbouring XCDs share a table
-    uint32_t pshift = 0;
-    while (((uint64_t)T << pshift) % 8 != 0) ++pshift;
-    const uint64_t waves_per_table = (uint64_t)B * slabs;
-    const uint64_t wpp = (waves_per_table + (1u << pshift) - 1) >> pshift;
-    const uint64_t bpp = (wpp + kWavesPerBlock - 1) / kWavesPerBlock;
-    const uint64_t grid = ((uint64_t)T << pshift) * bpp;
-    if (grid <= 0x7FFFFFFFull) {
-      p.xcd_bpp = (uint32_t)bpp;
-      p.xcd_wpp = (uint32_t)wpp;
-      p.xcd_pshift = pshift;
-      blocks = (uint32_t)grid;
-    }
+int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
+                          const int64_t* table_byte_offsets, const int64_t* out_offsets,
+                          const int64_t* indices, const int64_t* offsets,
+                          const float* per_sample_weights, float* out, void* stream) {
+  if (!desc) return EMB_ERR_NULL_PTR;
+  if (desc->table_dtype != EMB_F32 && desc->table_dtype != EMB_F16 &&
+      desc->table_dtype != EMB_BF16 && desc->table_dtype != EMB_U8ROW)
+    return EMB_ERR_BAD_DTYPE;
+  if (desc->mode != EMB_SUM && desc->mode != EMB_MEAN) return EMB_ERR_BAD_MODE;
+  if (desc->num_tables < 1 || !desc->dims) return desc->dims ? EMB_ERR_BAD_DIM : EMB_ERR_NULL_PTR;
+  if (desc->batch < 0 || desc->num_lookups < 0 || desc->max_table_bytes < 0)
+    return EMB_ERR_BAD_SIZE;
+  const int64_t T = desc->num_tables, B = desc->batch;
+  int64_t total_dim = 0;
+  uint32_t max_row_bytes = 0;
+  for (int64_t t = 0; t < T; ++t) {
+    const int64_t d = desc->dims[t];
+    if (d < 1) return EMB_ERR_BAD_DIM;
+    const int64_t rb = desc->table_dtype == EMB_U8ROW ? d + 8
+                                                       : d * (desc->table_dtype == EMB_F32 ? 4 : 2);
+    if (rb % 16 != 0 || rb > kSlabBytes) return EMB_ERR_BAD_DIM;
+    if (rb > max_row_bytes) max_row_bytes = (uint32_t)rb;
+    total_dim += d;
   }
+  if (per_sample_weights && desc->mode == EMB_MEAN) return EMB_ERR_UNSUPPORTED;
+  const int64_t out_ld = desc->out_ld ? desc->out_ld : total_dim;
+  if (out_ld < total_dim || out_ld % 4 != 0) return EMB_ERR_BAD_DIM;
+  if (B == 0) return EMB_OK;
+  if (!tables || !table_byte_offsets || !out_offsets || !offsets || !out) return EMB_ERR_NULL_PTR;
+  if (desc->num_lookups > 0 && !indices) return EMB_ERR_NULL_PTR;
+  if ((reinterpret_cast<uintptr_t>(tables) | reinterpret_cast<uintptr_t>(out)) & 15)
+    return EMB_ERR_ALIGNMENT;
+  if (B > 0x7FFFFFFF || T * B > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
 
-  // A cap on resident workgroups per CU is imposed through a dynamic LDS request that the
-  // kernel never touches: k workgroups fit when each asks for 1/k of the CU's LDS.
-  uint32_t lds = 0;
-  if (g_tuning.blocks_per_cu > 0) {
-    int dev = 0, lds_per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor,
-                              dev) != hipSuccess || lds_per_cu <= 0)
-      return EMB_ERR_LAUNCH;
-    lds = ((uint32_t)lds_per_cu / (uint32_t)g_tuning.blocks_per_cu) & ~1023u;
-    if (lds > 65536u &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return EMB_ERR_LAUNCH;
-  }
+  bool buf = desc->max_table_bytes > 0 && (uint64_t)desc->max_table_bytes <= kBufMaxBytes;
+  if (g_tuning.addressing == 1) buf = false;
+  int depth = (int)g_tuning.depth;
+  if (depth == 0) depth = (desc->table_dtype == EMB_F32 && max_row_bytes >= 512) ? 8 : 4;
 
-  hipLaunchKernelGGL(fn, dim3(blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
-                     static_cast<const char*>(tables), table_offsets, indices, offsets,
-                     per_sample_weights, desc->table_hints, out, p);
-  return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
+  KParams p;
+  p.num_lookups = desc->num_lookups;
+  p.out_ld = out_ld;
+  p.max_rows = 0;
+  p.B = (uint32_t)B;
+  p.num_work = (uint32_t)(T * B);
+  p.slabs = 1;
+  p.row_bytes = max_row_bytes;
+  p.D = 0;
+  p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
+  p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
+  return enqueue(0, desc->table_dtype, depth, buf, T, p, tables, table_byte_offsets, indices,
+                 offsets, per_sample_weights, desc->table_hints, out_offsets, out, stream);
 }
 
 int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,

@@ -47,6 +47,34 @@ def test_desc_layout_matches_header():
     assert emb.emb_bag_desc.table_hints.offset == 48
 
 
+def test_mixed_desc_layout_and_host_errors():
+    import paper_2410_22249_amd as emb
+    assert ctypes.sizeof(emb.emb_bag_mixed_desc) == 4 * 4 + 4 * 8 + 2 * 8
+    assert emb.emb_bag_mixed_desc.dims.offset == 48
+    lib = emb.lib()
+    fake = ctypes.c_void_p(0x1000)
+
+    def call(desc, tables=fake, boff=fake, ooff=fake, idx=fake, off=fake, w=None, out=fake):
+        return lib.emb_bag_forward_mixed(ctypes.byref(desc) if desc is not None else None, tables,
+                                         boff, ooff, idx, off, w, out, None)
+
+    ok = dict(batch=4, table_dtype=emb.EMB_F32, mode=emb.EMB_SUM, num_lookups=10)
+    assert call(None) == -1
+    assert call(emb.make_mixed_desc([64, 6], **ok)) == -2                   # 24-byte rows
+    assert call(emb.make_mixed_desc([64, 512], **ok)) == -2                 # 2 KiB rows
+    assert call(emb.make_mixed_desc([64, 0], **ok)) == -2
+    assert call(emb.make_mixed_desc([64, 32], **{**ok, "table_dtype": 9})) == -3
+    assert call(emb.make_mixed_desc([64, 32], **{**ok, "mode": 5})) == -4
+    assert call(emb.make_mixed_desc([64, 32], **{**ok, "out_ld": 92})) == -2   # < 96
+    assert call(emb.make_mixed_desc([64, 32], **{**ok, "batch": -1})) == -7
+    assert call(emb.make_mixed_desc([64, 32], **{**ok, "mode": emb.EMB_MEAN}), w=fake) == -5
+    assert call(emb.make_mixed_desc([64, 32], **ok), ooff=None) == -1
+    assert call(emb.make_mixed_desc([64, 32], **ok), tables=ctypes.c_void_p(0x1004)) == -8
+    assert call(emb.make_mixed_desc([120, 56], **{**ok, "table_dtype": emb.EMB_U8ROW}), out=None) == -1
+    assert call(emb.make_mixed_desc([128], **{**ok, "table_dtype": emb.EMB_U8ROW})) == -2
+    assert call(emb.make_mixed_desc([64, 32], **{**ok, "batch": 0}), tables=None, out=None) == 0
+
+
 def test_generator_library_exports():
     from inputgen import gen
     lib = ctypes.CDLL(gen.LIB_PATH)

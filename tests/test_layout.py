@@ -22,6 +22,9 @@ def test_header_is_valid_c99(tmp_path):
                    "  emb_bag_desc d = {0};\n"
                    "  d.num_tables = 1; d.dim = 4; d.table_dtype = EMB_BF16; d.mode = EMB_MEAN;\n"
                    "  d.table_hints = 0;\n"
+                   "  emb_bag_mixed_desc m = {0};\n"
+                   "  m.num_tables = 2; m.dims = 0;\n"
+                   "  (void)emb_bag_forward_mixed(&m, 0, 0, 0, 0, 0, 0, 0, 0);\n"
                    "  return emb_bag_forward(&d, 0, 0, 0, 0, 0, 0, 0) + emb_bag_version() +\n"
                    "         emb_bag_profile_reuse(&d, 0, 0, 64, -1, 0, 0, 0, 0) + EMB_HINT_STREAMING;\n"
                    "}\n")

@@ -1,0 +1,145 @@
+"""GPU parity for tables of different widths (emb_bag_forward_mixed) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2410_22249_amd as emb
+from inputgen import gen
+from gpu_harness import DEV, assert_close_to_oracle, to_dev, tuning
+
+pytestmark = pytest.mark.gpu
+
+EDT = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16, "u8row": emb.EMB_U8ROW}
+
+
+def _device_arena(wl):
+    arena = torch.empty(wl.table_bytes, dtype=torch.uint8, device=DEV)
+    gen.mixed_fill_device(wl, arena.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return arena
+
+
+def _forward(wl, arena, batch, mode="sum", weights=None, out_ld=0, hints=None, fill=float("nan")):
+    total = int(sum(wl.dims))
+    ld = out_ld if out_ld else total
+    out = torch.full((wl.B, ld), fill, dtype=torch.float32, device=DEV)
+    desc = emb.make_mixed_desc(wl.dims, wl.B, EDT[wl.dtype],
+                               emb.EMB_MEAN if mode == "mean" else emb.EMB_SUM, batch.num_lookups,
+                               out_ld, int(np.diff(wl.table_byte_offsets()).max()), hints)
+    emb.emb_bag_forward_mixed(desc, arena, to_dev(wl.table_byte_offsets()), to_dev(wl.out_offsets()),
+                              to_dev(batch.indices) if batch.num_lookups else None,
+                              to_dev(batch.offsets), to_dev(weights), out)
+    torch.cuda.synchronize()
+    return out
+
+
+def _wl(dtype, **kw):
+    base = gen.mixed_workload("mixed_small")
+    dims = {"f32": base.dims, "f16": (64, 8, 128, 512, 32, 96, 24), "bf16": (64, 8, 128, 512, 32, 96, 24),
+            "u8row": (120, 8, 248, 1016, 56, 24, 504)}[dtype]
+    from dataclasses import replace
+    return replace(base, dtype=dtype, dims=dims, **kw)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "u8row"])
+def test_mixed_widths_match_oracle(oracle, dtype):
+    for mode, weighted in (("sum", False), ("mean", False), ("sum", True)):
+        wl = _wl(dtype, weighted=weighted)
+        batch = gen.make_batches(wl, 1)[0]
+        tabs = gen.mixed_host_tables(wl)
+        arena = _device_arena(wl)
+        # the device fill of every table equals the host values
+        boff = wl.table_byte_offsets()
+        host_bytes = np.concatenate([t.view(np.uint8).reshape(-1) for t in tabs])
+        assert np.array_equal(arena.cpu().numpy(), host_bytes)
+        ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, mode,
+                                          weights=batch.weights)
+        first = None
+        for kw in (dict(), dict(addressing=1), dict(depth=8), dict(depth=2, xcd_remap=1),
+                   dict(blocks_per_cu=3)):
+            with tuning(**kw):
+                got = _forward(wl, arena, batch, mode, batch.weights).cpu().numpy()
+            assert_close_to_oracle(got, ref, bound, dtype != "f32", f"mixed/{dtype}/{mode}/{kw}")
+            if first is None:
+                first = got
+            elif kw.get("depth") is None:
+                assert np.array_equal(got, first), kw       # addressing / launch shape: same bits
+
+
+def test_mixed_equals_uniform_when_widths_agree(oracle):
+    wl = gen.workload("small_f32_d128")
+    batch = gen.make_batches(wl, 1)[0]
+    host = gen.host_arena(wl)
+    from gpu_harness import forward, upload_arena
+    uni = forward(upload_arena(host), wl.table_offsets(), batch.indices, batch.offsets, wl.B, "mean")
+    mw = gen.MixedWorkload(name="same", T=wl.T, rows=wl.rows, dims=(wl.D,) * wl.T, dtype="f32",
+                           B=wl.B, pooling=wl.pooling, dists=wl.dists, seed=wl.seed)
+    arena = torch.from_numpy(host.view(np.uint8).reshape(-1)).to(DEV)
+    mix = _forward(mw, arena, batch, "mean")
+    assert torch.equal(uni, mix)
+
+
+def test_mixed_padding_hints_and_empty(oracle):
+    wl = _wl("f32")
+    batch = gen.make_batches(wl, 1)[0]
+    tabs = gen.mixed_host_tables(wl)
+    arena = _device_arena(wl)
+    total = int(sum(wl.dims))
+    ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, "sum", out_ld=total + 12)
+    hints = to_dev((np.arange(wl.T) % 2).astype(np.uint8))
+    got = _forward(wl, arena, batch, "sum", out_ld=total + 12, hints=hints, fill=-5.0).cpu().numpy()
+    assert np.all(got[:, total:] == -5.0)
+    assert_close_to_oracle(got[:, :total], ref[:, :total], bound[:, :total], False, "mixed/padded")
+    plain = _forward(wl, arena, batch, "sum").cpu().numpy()
+    assert np.array_equal(plain, got[:, :total])
+    # every bag empty
+    empty = gen.Batch(offsets=np.zeros(wl.T * wl.B + 1, np.int64), indices=np.zeros(0, np.int64))
+    z = _forward(wl, arena, empty, "mean").cpu().numpy()
+    assert np.all(z == 0) and not np.signbit(z).any()
+
+
+def test_mixed_malformed_table_description_is_skipped():
+    """out_offsets that contradict the rules (a width that is not a multiple of 4 floats here) make
+    the kernel skip that table instead of writing out of place; the others are unaffected."""
+    wl = _wl("f32")
+    batch = gen.make_batches(wl, 1)[0]
+    arena = _device_arena(wl)
+    good = _forward(wl, arena, batch, "sum")
+    total = int(sum(wl.dims))
+    out = torch.full((wl.B, total), -9.0, dtype=torch.float32, device=DEV)
+    ooff = wl.out_offsets().copy()
+    ooff[3] += 2                      # table 2 gets width 130, table 3 starts unaligned
+    desc = emb.make_mixed_desc(wl.dims, wl.B, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups, 0,
+                               int(np.diff(wl.table_byte_offsets()).max()))
+    emb.emb_bag_forward_mixed(desc, arena, to_dev(wl.table_byte_offsets()), to_dev(ooff),
+                              to_dev(batch.indices), to_dev(batch.offsets), None, out)
+    torch.cuda.synchronize()
+    o, g = out.cpu().numpy(), good.cpu().numpy()
+    c = wl.out_offsets()
+    assert np.all(o[:, c[2]:c[4]] == -9.0)                         # tables 2 and 3 skipped
+    assert np.array_equal(o[:, :c[2]], g[:, :c[2]]) and np.array_equal(o[:, c[4]:], g[:, c[4]:])
+
+
+def test_mixed_full_size_sampled(oracle):
+    """60 tables x 4 M rows with widths 32 / 64 / 128 / 256 (108 GB): sampled bags against the oracle."""
+    wl = gen.mixed_workload("mixed_cfg")
+    batch = gen.make_batches(wl, 1)[0]
+    arena = _device_arena(wl)
+    out = _forward(wl, arena, batch, "sum")
+    assert bool(torch.isfinite(out).all())
+    out2 = _forward(wl, arena, batch, "sum")
+    assert torch.equal(out, out2)
+    rng = np.random.default_rng(7)
+    base, cols = wl.row_bases(), wl.out_offsets()
+    worst = 0.0
+    for t in range(wl.T):
+        bs = np.unique(np.concatenate([rng.integers(0, wl.B, size=6), [0, wl.B - 1]]))
+        segs = [batch.indices[batch.offsets[t * wl.B + b]:batch.offsets[t * wl.B + b + 1]] for b in bs]
+        uniq, inv = np.unique(np.concatenate(segs), return_inverse=True)
+        small = gen.table_values(wl.seed, base[t] + uniq, wl.dims[t], wl.dtype, wl.kind)
+        soff = gen.lengths_to_offsets(np.array([len(x) for x in segs]))
+        ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), inv.astype(np.int64),
+                                    soff, len(bs), "sum")
+        got = out[torch.from_numpy(bs).to(DEV), cols[t]:cols[t + 1]].cpu().numpy()
+        worst = max(worst, assert_close_to_oracle(got, ref, bound, False, f"mixed_cfg table {t}"))
+    print(f"\n[mixed_cfg] max err/bound {worst:.3e}", flush=True)

@@ -464,3 +464,52 @@ def test_reuse_profile_closed_forms():
     # birthday problem: expected repeats of n uniform draws over R rows is about n^2 / (2R) = 1.1
     assert dup[2] == n - len(np.unique(uni)) and dup[2] < 12
     assert hints.tolist() == [1, 0, 1]
+
+
+# ---- tables of different widths: the same definition, table by table ---------------------------
+def test_mixed_widths_equal_the_uniform_oracle_when_widths_agree(oracle):
+    rng = np.random.default_rng(41)
+    T, rows, D, B = 3, [20, 7, 33], 8, 6
+    tables, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 9)
+    w = rng.uniform(-1, 1, len(idx)).astype(np.float32)
+    per_table = [tables[toff[t]:toff[t + 1]] for t in range(T)]
+    for mode, weights in (("sum", None), ("mean", None), ("sum", w)):
+        r0, b0 = oracle.emb_bag(tables, toff, idx, offsets, B, mode, weights=weights)
+        r1, b1 = oracle.emb_bag_mixed(per_table, idx, offsets, B, mode, weights=weights)
+        assert np.array_equal(r0, r1) and np.array_equal(b0, b1)
+
+
+def test_mixed_widths_hand_worked(oracle):
+    t0 = np.array([[1, 2], [10, 20], [100, 200]], dtype=np.float32)          # D = 2
+    t1 = np.array([[1, 2, 3, 4], [-1, -2, -3, -4]], dtype=np.float32)        # D = 4
+    B = 2
+    # bags (t,b): (0,0)=[2,0]  (0,1)=[1]  (1,0)=[]  (1,1)=[0,1,0]
+    idx = np.array([2, 0, 1, 0, 1, 0], dtype=np.int64)
+    offsets = np.array([0, 2, 3, 3, 6], dtype=np.int64)
+    ref, bound = oracle.emb_bag_mixed([t0, t1], idx, offsets, B, "sum")
+    assert ref.tolist() == [[101.0, 202.0, 0.0, 0.0, 0.0, 0.0], [10.0, 20.0, 1.0, 2.0, 3.0, 4.0]]
+    assert bound.tolist() == [[101.0, 202.0, 0.0, 0.0, 0.0, 0.0], [10.0, 20.0, 3.0, 6.0, 9.0, 12.0]]
+    ref, _ = oracle.emb_bag_mixed([t0, t1], idx, offsets, B, "mean", out_ld=8)
+    assert ref.tolist() == [[50.5, 101.0, 0, 0, 0, 0, 0, 0],
+                            [10.0, 20.0, 1 / 3, 2 / 3, 1.0, 4 / 3, 0, 0]]
+
+
+def test_mixed_widths_brute_force(oracle):
+    rng = np.random.default_rng(42)
+    dims, rows, B = [4, 12, 8], [6, 3, 9], 5
+    tables = [rng.normal(0, 0.1, size=(rows[t], dims[t])).astype(np.float32) for t in range(3)]
+    lengths = rng.integers(0, 6, size=3 * B)
+    offsets = gen.lengths_to_offsets(lengths)
+    idx = np.concatenate([rng.integers(0, rows[t], size=int(offsets[(t + 1) * B] - offsets[t * B]))
+                          for t in range(3)]).astype(np.int64)
+    ref, bound = oracle.emb_bag_mixed(tables, idx, offsets, B, "sum")
+    col = 0
+    for t in range(3):
+        for b in range(B):
+            lo, hi = int(offsets[t * B + b]), int(offsets[t * B + b + 1])
+            for d in range(dims[t]):
+                a = sum((Fraction(float(tables[t][int(idx[j]), d])) for j in range(lo, hi)), Fraction(0))
+                m = sum((abs(Fraction(float(tables[t][int(idx[j]), d]))) for j in range(lo, hi)), Fraction(0))
+                assert abs(ref[b, col + d] - float(a)) <= 8 * 2.0 ** -53 * float(m) + 1e-300
+                assert abs(bound[b, col + d] - float(m)) <= 8 * 2.0 ** -53 * float(m) + 1e-300
+        col += dims[t]
