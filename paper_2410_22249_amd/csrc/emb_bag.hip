@@ -67,6 +67,15 @@ struct KParams {
   uint32_t xcd_bpp;
   uint32_t xcd_wpp;
   uint32_t xcd_pshift;
+  uint32_t xcd_ordered;  // 1 = position q of the XCD-affine order holds table TableOrder::t[q]
+};
+
+// Tables of different widths load the XCDs unevenly when they are dealt out in their own order
+// (a wavefront's work grows with the row width).  The host then deals them by width instead and
+// hands the kernel the resulting order by value, in the kernel-argument segment.
+constexpr int kMaxOrdered = 1024;
+struct TableOrder {
+  uint16_t t[kMaxOrdered];
 };
 
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
@@ -224,7 +233,8 @@ __global__ void __launch_bounds__(kBlock)
 emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
                     const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
-                    const int64_t* __restrict__ out_offsets, float* __restrict__ out, KParams p) {
+                    const int64_t* __restrict__ out_offsets, float* __restrict__ out, KParams p,
+                    TableOrder order) {
   constexpr bool MIXED = LPR == 0;
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;  // 2-byte elements
   constexpr bool QUANT = ELEM == EMB_U8ROW;                   // 1-byte codes + scale, bias
@@ -243,7 +253,11 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
     const uint32_t waves_per_table = p.B * p.slabs;
     const uint32_t w_in_table = (unit & ((1u << p.xcd_pshift) - 1u)) * p.xcd_wpp + w_in_piece;
     if (w_in_piece >= p.xcd_wpp || w_in_table >= waves_per_table) return;
-    work = (unit >> p.xcd_pshift) * waves_per_table + w_in_table;
+    uint32_t tpos = unit >> p.xcd_pshift;
+    if constexpr (MIXED) {
+      if (p.xcd_ordered) tpos = order.t[tpos];
+    }
+    work = tpos * waves_per_table + w_in_table;
   } else {
     const uint64_t work64 = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
     if (work64 >= p.num_work) return;
@@ -457,7 +471,8 @@ struct Tuning {
 Tuning g_tuning;
 
 using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int64_t*,
-                          const float*, const uint8_t*, const int64_t*, float*, KParams);
+                          const float*, const uint8_t*, const int64_t*, float*, KParams,
+                          TableOrder);
 
 template <int LPR, int ELEM, int DEPTH>
 KernelFn pick_wb(bool weighted, bool buf) {
@@ -528,16 +543,17 @@ int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
 int enqueue(int lpr, int elem, int depth, bool buf, int64_t T, KParams p, const void* tables,
             const int64_t* table_offsets, const int64_t* indices, const int64_t* offsets,
             const float* weights, const uint8_t* table_hints, const int64_t* out_offsets,
-            float* out, void* stream) {
+            const uint16_t* row_units, bool natural_order, float* out, void* stream) {
   KernelFn fn = pick_kernel(lpr, elem, depth, weights != nullptr, buf);
   if (!fn) return EMB_ERR_BAD_TUNING;
   const int64_t num_work = p.num_work;
   const int64_t waves_per_table_i = num_work / T;
-  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = 0;
+  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = p.xcd_ordered = 0;
+  TableOrder order = {};  // only the first T entries are read, and only when xcd_ordered is set
 
   uint32_t blocks = (uint32_t)((num_work + kWavesPerBlock - 1) / kWavesPerBlock);
   const bool remap = g_tuning.xcd_remap == 1 || (g_tuning.xcd_remap == -1 && blocks >= 4096);
-  if (remap && blocks >= 64) {
+  if (remap && blocks >= 64 && !natural_order) {
     // pieces per table: the smallest power of two that makes T * pieces a multiple of 8, so
     // that every XCD gets the same number of pieces and neighbouring XCDs share a table
     uint32_t pshift = 0;
@@ -546,10 +562,38 @@ int enqueue(int lpr, int elem, int depth, bool buf, int64_t T, KParams p, const 
     const uint64_t wpp = (waves_per_table + (1u << pshift) - 1) >> pshift;
     const uint64_t bpp = (wpp + kWavesPerBlock - 1) / kWavesPerBlock;
     const uint64_t grid = ((uint64_t)T << pshift) * bpp;
-    if (grid <= 0x7FFFFFFFull) {
+    // Tables of different widths (row_units[t] = 16-byte segments per row, given only when they
+    // differ): position q of the order runs on the XCD set q % sets.  Deal the tables out widest
+    // first, each to the set with the least work so far, so that every XCD ends up with about
+    // the same number of bytes.
+    const uint32_t sets = 8u >> (pshift < 3 ? pshift : 3);
+    const bool ok = grid <= 0x7FFFFFFFull;
+    const bool ordered = ok && row_units && sets > 1;
+    if (ordered) {
+      uint32_t head[66];  // counting sort by width, widest first
+      for (int i = 0; i < 66; ++i) head[i] = 0;
+      for (int64_t t = 0; t < T; ++t) ++head[64 - row_units[t] + 1];
+      for (int i = 1; i < 66; ++i) head[i] += head[i - 1];
+      uint16_t by_width[kMaxOrdered];
+      for (int64_t t = 0; t < T; ++t) by_width[head[64 - row_units[t]]++] = (uint16_t)t;
+      uint64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      uint32_t taken[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      const uint32_t per_set = (uint32_t)(T / sets);  // exact: T * pieces is a multiple of 8
+      for (int64_t k = 0; k < T; ++k) {
+        const uint16_t t = by_width[k];
+        uint32_t best = sets;
+        for (uint32_t c = 0; c < sets; ++c)
+          if (taken[c] < per_set && (best == sets || load[c] < load[best])) best = c;
+        order.t[best + sets * taken[best]] = t;
+        ++taken[best];
+        load[best] += row_units[t];
+      }
+    }
+    if (ok) {
       p.xcd_bpp = (uint32_t)bpp;
       p.xcd_wpp = (uint32_t)wpp;
       p.xcd_pshift = pshift;
+      p.xcd_ordered = ordered ? 1u : 0u;
       blocks = (uint32_t)grid;
     }
   }
@@ -572,7 +616,7 @@ int enqueue(int lpr, int elem, int depth, bool buf, int64_t T, KParams p, const 
 
   hipLaunchKernelGGL(fn, dim3(blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
                      static_cast<const char*>(tables), table_offsets, indices, offsets, weights,
-                     table_hints, out_offsets, out, p);
+                     table_hints, out_offsets, out, p, order);
   return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
 }
 
@@ -624,7 +668,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
   return enqueue(lpr, desc->table_dtype, depth, buf, T, p, tables, table_offsets, indices, offsets,
-                 per_sample_weights, desc->table_hints, nullptr, out, stream);
+                 per_sample_weights, desc->table_hints, nullptr, nullptr, false, out, stream);
 }
 
 int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
@@ -642,6 +686,8 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   const int64_t T = desc->num_tables, B = desc->batch;
   int64_t total_dim = 0;
   uint32_t max_row_bytes = 0;
+  uint16_t row_units[kMaxOrdered];  // 16-byte segments per row, for the XCD-affine table order
+  bool widths_differ = false;
   for (int64_t t = 0; t < T; ++t) {
     const int64_t d = desc->dims[t];
     if (d < 1) return EMB_ERR_BAD_DIM;
@@ -649,8 +695,14 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
                                                        : d * (desc->table_dtype == EMB_F32 ? 4 : 2);
     if (rb % 16 != 0 || rb > kSlabBytes) return EMB_ERR_BAD_DIM;
     if (rb > max_row_bytes) max_row_bytes = (uint32_t)rb;
+    if (t < kMaxOrdered) row_units[t] = (uint16_t)(rb / 16);
+    if (rb != (desc->table_dtype == EMB_U8ROW ? desc->dims[0] + 8
+                                              : desc->dims[0] * (desc->table_dtype == EMB_F32 ? 4 : 2)))
+      widths_differ = true;
     total_dim += d;
   }
+  // more tables than the order holds: such a launch keeps the natural block order
+  const bool too_many = widths_differ && T > kMaxOrdered;
   if (per_sample_weights && desc->mode == EMB_MEAN) return EMB_ERR_UNSUPPORTED;
   const int64_t out_ld = desc->out_ld ? desc->out_ld : total_dim;
   if (out_ld < total_dim || out_ld % 4 != 0) return EMB_ERR_BAD_DIM;
@@ -678,7 +730,8 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
   return enqueue(0, desc->table_dtype, depth, buf, T, p, tables, table_byte_offsets, indices,
-                 offsets, per_sample_weights, desc->table_hints, out_offsets, out, stream);
+                 offsets, per_sample_weights, desc->table_hints, out_offsets,
+                 widths_differ && !too_many ? row_units : nullptr, too_many, out, stream);
 }
 
 int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,

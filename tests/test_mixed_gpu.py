@@ -143,3 +143,24 @@ def test_mixed_full_size_sampled(oracle):
         got = out[torch.from_numpy(bs).to(DEV), cols[t]:cols[t + 1]].cpu().numpy()
         worst = max(worst, assert_close_to_oracle(got, ref, bound, False, f"mixed_cfg table {t}"))
     print(f"\n[mixed_cfg] max err/bound {worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("T", [8, 10, 12, 16, 24])
+def test_mixed_width_balanced_xcd_order(oracle, T):
+    """With the XCD-affine block order forced on, tables of different widths are dealt to the XCDs
+    by width (2, 4 or 8 XCD sets depending on T); the result must not depend on the order."""
+    rng = np.random.default_rng(100 + T)
+    dims = tuple(int(d) for d in rng.choice([4, 8, 16, 32, 64, 96, 128, 192, 256], size=T))
+    rows = tuple(int(r) for r in rng.integers(1, 400, size=T))
+    wl = gen.MixedWorkload(name=f"order{T}", T=T, rows=rows, dims=dims, dtype="f32", B=37,
+                           pooling=("uniform", 0, 70), dists=(("uniform",),) * T, seed=0x5EED0D00 + T)
+    batch = gen.make_batches(wl, 1)[0]
+    tabs = gen.mixed_host_tables(wl)
+    arena = _device_arena(wl)
+    ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, "sum")
+    with tuning(xcd_remap=0):
+        natural = _forward(wl, arena, batch).cpu().numpy()
+    with tuning(xcd_remap=1):
+        ordered = _forward(wl, arena, batch).cpu().numpy()
+    assert_close_to_oracle(ordered, ref, bound, False, f"mixed order T={T}")
+    assert np.array_equal(natural, ordered)
