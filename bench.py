@@ -41,6 +41,8 @@ DESCRIPTIONS = {
     "paper_mix1": "paper's model, Mix1: 100 high / 75 med / 50 low / 25 random tables",
     "paper_mix2": "paper's model, Mix2: 62 / 63 / 63 / 62",
     "paper_mix3": "paper's model, Mix3: 25 / 50 / 75 / 100",
+    "mixed_cfg": "60 fp32 tables x 4,000,000 rows, widths cycling 32 / 64 / 128 / 256 (115.2 GB), "
+                 "batch 4096, pooling 80 fixed, uniform indices, sum, one emb_bag_forward_mixed launch",
 }
 
 
@@ -114,7 +116,8 @@ def main() -> int:
         k, v = kv.split("=")
         emb.emb_bag_set_tuning(k, int(v))
 
-    wl = gen.workload(args.workload)
+    mixed = args.workload.startswith("mixed")
+    wl = gen.mixed_workload(args.workload) if mixed else gen.workload(args.workload)
     stream = torch.cuda.Stream()           # default priority; the library launches on it
     sh = stream.cuda_stream
 
@@ -122,28 +125,35 @@ def main() -> int:
     t0 = time.time()
     tdtype = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16,
               "u8row": torch.uint8}[wl.dtype]
-    width = wl.D + 8 if wl.dtype == "u8row" else wl.D   # elements per stored row
+    width = 0 if mixed else (wl.D + 8 if wl.dtype == "u8row" else wl.D)  # elements per stored row
     # The arena is the caller's memory.  Where it lands physically moves cfg3 by about 5 %
     # between allocations of the same size; the contiguous flag itself makes no difference.
     owner = None
-    if args.arena == "contiguous":
+    if mixed:
+        arena, arena_kind = torch.empty(wl.table_bytes, dtype=torch.uint8, device=dev), "torch"
+    elif args.arena == "contiguous":
         owner = gen.DeviceArena(wl.total_rows, wl.D, wl.dtype, contiguous=True)
         arena, arena_kind = owner.tensor, owner.kind
     else:
         arena, arena_kind = torch.empty((wl.total_rows, width), dtype=tdtype, device=dev), "torch"
     with torch.cuda.stream(stream):
-        gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed,
-                              wl.kind, sh)
+        if mixed:
+            gen.mixed_fill_device(wl, arena.data_ptr(), sh)
+        else:
+            gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed,
+                                  wl.kind, sh)
     log(f"{wl.name}: arena {wl.table_bytes / 1e9:.2f} GB allocated ({arena_kind}), fill enqueued")
     batches = gen.make_batches(wl, args.batches)
     log(f"{len(batches)} index batches generated in {time.time() - t0:.1f} s "
         f"({batches[0].num_lookups} lookups in batch 0)")
-    toff = torch.from_numpy(wl.table_offsets()).to(dev)
+    toff = torch.from_numpy(wl.table_byte_offsets() if mixed else wl.table_offsets()).to(dev)
+    ooff = torch.from_numpy(wl.out_offsets()).to(dev) if mixed else None
+    total_dim = int(sum(wl.dims)) if mixed else wl.T * wl.D
     dbatches = []
     for b in batches:
         dbatches.append((torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev),
                          None if b.weights is None else torch.from_numpy(b.weights).to(dev)))
-    out = torch.empty((wl.B, wl.T * wl.D), dtype=torch.float32, device=dev)
+    out = torch.empty((wl.B, total_dim), dtype=torch.float32, device=dev)
     edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16,
            "u8row": emb.EMB_U8ROW}[wl.dtype]
     emode = emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM
@@ -152,19 +162,28 @@ def main() -> int:
     hints = None
     if not args.no_hints:
         hints = torch.zeros(wl.T, dtype=torch.uint8, device=dev)
-        d0 = emb.make_desc(wl.T, wl.B, wl.D, edt, emode, batches[0].num_lookups, 0, max(wl.rows))
+        d0 = emb.make_desc(wl.T, wl.B, 4 if mixed else wl.D, emb.EMB_F32 if mixed else edt, emode,
+                           batches[0].num_lookups, 0, max(wl.rows))   # the profile reads ids only
         emb.emb_bag_profile_reuse(d0, dbatches[0][0], dbatches[0][1], 4096, -1, None, None, hints,
                                   stream)
         stream.synchronize()
         log(f"table hints: {int(hints.sum().item())} of {wl.T} tables streaming")
-    descs = [emb.make_desc(wl.T, wl.B, wl.D, edt, emode, b.num_lookups, 0, max(wl.rows), hints)
-             for b in batches]
+    if mixed:
+        max_bytes = int(np.diff(wl.table_byte_offsets()).max())
+        descs = [emb.make_mixed_desc(wl.dims, wl.B, edt, emode, b.num_lookups, 0, max_bytes, hints)
+                 for b in batches]
+    else:
+        descs = [emb.make_desc(wl.T, wl.B, wl.D, edt, emode, b.num_lookups, 0, max(wl.rows), hints)
+                 for b in batches]
     torch.cuda.synchronize()
 
     def step(i: int) -> None:
         k = i % len(dbatches)
         idx, off, w = dbatches[k]
-        emb.emb_bag_forward(descs[k], arena, toff, idx, off, w, out, stream)
+        if mixed:
+            emb.emb_bag_forward_mixed(descs[k], arena, toff, ooff, idx, off, w, out, stream)
+        else:
+            emb.emb_bag_forward(descs[k], arena, toff, idx, off, w, out, stream)
 
     # a plain copy of known size on the same stream: the calibration kernel for HBM counters
     cal_bytes = 1 << 30
@@ -209,9 +228,15 @@ def main() -> int:
     avg_lookups = lookups_timed / args.steps
     avg_kern_s = float(np.mean(kern_ms)) / 1e3
     lookups_per_s = lookups_timed / wall
-    gathered = metrics.gathered_bytes(avg_lookups, wl.D, wl.elem_bytes, wl.row_bytes)
-    algo = metrics.algorithmic_bytes(avg_lookups, wl.T, wl.B, wl.D, wl.elem_bytes, wl.weighted,
-                                     wl.row_bytes)
+    if mixed:   # rows of each table's own width + indices + offsets + output (+ weights)
+        gathered = sum(wl.gathered_bytes(batches[(args.warmup + i) % len(batches)])
+                       for i in range(args.steps)) / args.steps
+        algo = (gathered + 8 * avg_lookups + 8 * (wl.num_bags + 1) + 4 * wl.B * total_dim
+                + (4 * avg_lookups if wl.weighted else 0))
+    else:
+        gathered = metrics.gathered_bytes(avg_lookups, wl.D, wl.elem_bytes, wl.row_bytes)
+        algo = metrics.algorithmic_bytes(avg_lookups, wl.T, wl.B, wl.D, wl.elem_bytes, wl.weighted,
+                                         wl.row_bytes)
     achieved = algo / avg_kern_s / 1e9
     log(f"wall {wall * 1e3 / args.steps:.3f} ms/step, kernel avg {avg_kern_s * 1e3:.3f} ms "
         f"(min {min(kern_ms):.3f}, max {max(kern_ms):.3f}); gathered "
@@ -246,12 +271,29 @@ def main() -> int:
         nb = wl.num_bags
         bags = np.unique(np.concatenate([rng.integers(0, nb, size=args.check_bags),
                                          [0, wl.B - 1, nb - wl.B, nb - 1]]))
-        small, ix, off, wsmall = gen.compact_rows(wl, batches[k], bags)
-        ref, bound = emb_bag_oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, off,
-                                            len(bags), wl.mode, weights=wsmall)
-        got_all = out.view(wl.B, wl.T, wl.D)
-        tb = torch.from_numpy(np.stack([bags % wl.B, bags // wl.B], 1)).to(dev)
-        got = got_all[tb[:, 0], tb[:, 1]].cpu().numpy().astype(np.float64)
+        if mixed:   # table by table: the sampled bags of one table share its width
+            base, cols = wl.row_bases(), wl.out_offsets()
+            refs, bounds, gots = [], [], []
+            for t in np.unique(bags // wl.B):
+                bs = bags[bags // wl.B == t]
+                segs = [batches[k].indices[batches[k].offsets[g]:batches[k].offsets[g + 1]]
+                        for g in bs]
+                uniq, inv = np.unique(np.concatenate(segs), return_inverse=True)
+                small = gen.table_values(wl.seed, base[t] + uniq, wl.dims[t], wl.dtype, wl.kind)
+                off = gen.lengths_to_offsets(np.array([len(x) for x in segs], dtype=np.int64))
+                r, bd = emb_bag_oracle.emb_bag(small, np.array([0, len(small)], np.int64),
+                                               inv.astype(np.int64), off, len(bs), wl.mode)
+                g = out[torch.from_numpy(bs % wl.B).to(dev), int(cols[t]):int(cols[t + 1])]
+                refs.append(r.ravel()), bounds.append(bd.ravel())
+                gots.append(g.cpu().numpy().astype(np.float64).ravel())
+            ref, bound, got = np.concatenate(refs), np.concatenate(bounds), np.concatenate(gots)
+        else:
+            small, ix, off, wsmall = gen.compact_rows(wl, batches[k], bags)
+            ref, bound = emb_bag_oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, off,
+                                                len(bags), wl.mode, weights=wsmall)
+            got_all = out.view(wl.B, wl.T, wl.D)
+            tb = torch.from_numpy(np.stack([bags % wl.B, bags // wl.B], 1)).to(dev)
+            got = got_all[tb[:, 0], tb[:, 1]].cpu().numpy().astype(np.float64)
         err = np.abs(got - ref)
         ok = err <= 1e-5 * bound
         if wl.dtype != "f32":
@@ -265,7 +307,35 @@ def main() -> int:
             return 1
 
     # ---- the oracle timed on this machine's host cores (a reported baseline, not the target) ---
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and mixed:
+        if wl.dtype in ("f16", "bf16"):
+            raise SystemExit("bench.py: the mixed-width cpu baseline covers f32 and u8row tables")
+        boff = wl.table_byte_offsets()
+        tsub = max(1, int(np.searchsorted(boff, 8e9, side="right")) - 1)   # <= 8 GB on the host
+        tabs = []
+        for t in range(tsub):
+            raw = arena[int(boff[t]):int(boff[t + 1])].cpu().numpy()
+            tabs.append(raw.view(np.float32 if wl.dtype == "f32" else
+                                 np.uint8 if wl.dtype == "u8row" else np.uint16)
+                        .reshape(wl.rows[t], -1))
+        b0 = batches[0]
+        e = int(b0.offsets[tsub * wl.B])
+        sub_off, sub_idx = b0.offsets[: tsub * wl.B + 1].copy(), b0.indices[:e]
+        emb_bag_oracle.emb_bag_mixed(tabs, sub_idx, sub_off, wl.B, wl.mode)   # warm
+        reps, t_cpu = 0, 0.0
+        while t_cpu < args.cpu_seconds and reps < 100000:
+            t1 = time.perf_counter()
+            emb_bag_oracle.emb_bag_mixed(tabs, sub_idx, sub_off, wl.B, wl.mode)
+            t_cpu += time.perf_counter() - t1
+            reps += 1
+        cpu_baseline = {"value": e * reps / t_cpu, "unit": "lookups/s",
+                        "cores": emb_bag_oracle.num_threads(), "kind": "oracle",
+                        "sample": f"first {tsub} of {wl.T} tables (widths {list(wl.dims[:tsub])}), "
+                                  f"all {wl.B} bags each ({e} lookups), {reps} passes in "
+                                  f"{t_cpu:.1f} s, tables copied to host RAM"}
+        log(f"cpu baseline: {cpu_baseline}")
+        del tabs
+    elif not args.no_cpu_baseline:
         per_table = wl.rows[0] * wl.row_bytes
         tsub = max(1, min(wl.T, int(8e9 // per_table)))      # <= 8 GB of tables on the host
         toff_np = wl.table_offsets()
@@ -306,7 +376,8 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {DESCRIPTIONS[wl.name]}",
-                   "tables": wl.T, "rows_per_table": wl.rows[0], "dim": wl.D,
+                   "tables": wl.T, "rows_per_table": wl.rows[0],
+                   "dim": list(wl.dims) if mixed else wl.D,
                    "table_dtype": wl.dtype, "batch": wl.B, "mode": wl.mode,
                    "lookups_per_step": avg_lookups, "index_batches_rotated": len(batches),
                    "arena_allocation": arena_kind,

@@ -355,7 +355,7 @@ def mixed_workload(name: str) -> MixedWorkload:
                              pooling=("uniform", 0, 120),
                              dists=(("uniform",), ("uniform",), ("zipf", 1.1), ("one_item",),
                                     ("uniform",), ("uniform",), ("uniform",)), seed=0x5EED0C01)
-    if name == "mixed_cfg":   # 60 tables x 4 M rows, widths cycling 32 / 64 / 128 / 256 fp32 (108 GB)
+    if name == "mixed_cfg":   # 60 tables x 4 M rows, widths cycling 32 / 64 / 128 / 256 fp32 (115 GB)
         T = 60
         return MixedWorkload(name=name, T=T, rows=(4_000_000,) * T,
                              dims=tuple((32, 64, 128, 256)[t % 4] for t in range(T)), dtype="f32",

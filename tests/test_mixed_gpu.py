@@ -121,7 +121,7 @@ def test_mixed_malformed_table_description_is_skipped():
 
 
 def test_mixed_full_size_sampled(oracle):
-    """60 tables x 4 M rows with widths 32 / 64 / 128 / 256 (108 GB): sampled bags against the oracle."""
+    """60 tables x 4 M rows with widths 32 / 64 / 128 / 256 (115 GB): sampled bags against the oracle."""
     wl = gen.mixed_workload("mixed_cfg")
     batch = gen.make_batches(wl, 1)[0]
     arena = _device_arena(wl)
