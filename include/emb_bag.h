@@ -202,6 +202,17 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
  *                   (the stand-in for the L2 pinning of Sec. 4.3); 0 = natural order;
  *                   -1 = automatic (on for large launches)
  *   "use_hints"     1 (default) = honour desc->table_hints, 0 = ignore them
+ *   "stream"        the kernel for short bags, in which a lane group streams several consecutive
+ *                   bags so that row loads stay in flight across bag boundaries (the prefetch of
+ *                   Sec. 4.2 carried over the bounds -> indices -> rows chain of Sec. 3.1):
+ *                   -1 = automatic (average bag length num_lookups / (T * batch) below three
+ *                   load instructions' worth of rows, i.e. 3 * 1024 / row bytes rounded to a
+ *                   power of two: 24 at 128-byte rows, 12 at 256, 6 at 512, 3 at 1 KiB; rows of
+ *                   at most 1 KiB, buffer addressing), 0 = never, 1 = whenever rows and
+ *                   addressing allow it.  It adds a bag's rows in the order of its lookups; the
+ *                   one-wavefront-per-bag kernel keeps several partial sums, so the two agree
+ *                   to rounding, not to the bit.
+ *   "bags_per_group" consecutive bags per lane group in that kernel, 1..63; 0 = automatic
  * Not thread-safe against concurrent emb_bag_forward calls.
  */
 int emb_bag_set_tuning(const char* key, int64_t value);

@@ -9,15 +9,17 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-Wall", "-Wno-unused-command-line-argument"]
 
 TARGETS = {
-    # output (relative to the repo root): sources
-    "paper_2410_22249_amd/libembbag.so": ["paper_2410_22249_amd/csrc/emb_bag.hip"],
+    # output (relative to the repo root): sources (compiled side by side, then linked)
+    "paper_2410_22249_amd/libembbag.so": ["paper_2410_22249_amd/csrc/emb_bag.hip",
+                                          "paper_2410_22249_amd/csrc/emb_bag_stream.hip"],
     "inputgen/libembgen.so": ["inputgen/csrc/embgen.hip"],
 }
+OBJ_DIR = os.path.join(ROOT, "_build")
 
 
 C_DRIVER_SRC = "tests/c_abi/c_abi_driver.c"
@@ -36,19 +38,38 @@ def build_c_driver(verbose: bool = True) -> None:
     subprocess.run(cmd, check=True)
 
 
+def _run(cmd, verbose: bool):
+    if verbose:
+        print("[build]", " ".join(cmd), flush=True)
+    return subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+
+
+def _finish(proc, what: str, verbose: bool) -> None:
+    out, _ = proc.communicate()
+    # the host pass does not know the packed-fp32 feature and says so: harmless noise
+    log = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+    if log.strip() and (verbose or proc.returncode):
+        print(log, flush=True)
+    if proc.returncode != 0:
+        raise RuntimeError(f"hipcc failed for {what}")
+
+
 def build_all(verbose: bool = True) -> None:
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include")]
+    # every source to an object, all at once; then one link per library
+    jobs = []
     for out, srcs in TARGETS.items():
-        cmd = [HIPCC] + HIP_FLAGS + ["-I", os.path.join(ROOT, "include"), "-o",
-                                      os.path.join(ROOT, out)] + [os.path.join(ROOT, s) for s in srcs]
-        if verbose:
-            print("[build]", " ".join(cmd), flush=True)
-        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-        # the host pass does not know the packed-fp32 feature and says so: harmless noise
-        log = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
-        if log.strip() and (verbose or r.returncode):
-            print(log, flush=True)
-        if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed for {out}")
+        for src in srcs:
+            obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+            jobs.append((src, _run([HIPCC] + HIP_FLAGS + inc + ["-c", "-o", obj,
+                                                               os.path.join(ROOT, src)], verbose)))
+    for src, proc in jobs:
+        _finish(proc, src, verbose)
+    for out, srcs in TARGETS.items():
+        objs = [os.path.join(OBJ_DIR, os.path.basename(src) + ".o") for src in srcs]
+        _finish(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o",
+                      os.path.join(ROOT, out)] + objs, verbose), out, verbose)
     build_c_driver(verbose)
 
 

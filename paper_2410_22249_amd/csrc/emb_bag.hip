@@ -36,193 +36,11 @@
 #include <string.h>
 
 #include "../../include/emb_bag.h"
+#include "emb_bag_device.h"
 
 namespace {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kWaveSize = 64;
-constexpr int kWavesPerBlock = 4;
-constexpr int kBlock = kWaveSize * kWavesPerBlock;
-constexpr int kSlabBytes = 1024;                   // bytes of one row a wavefront covers per pass
-constexpr uint32_t kBufSentinel = 0xF0000000u;     // offset that is out of range for any table
-constexpr uint64_t kBufMaxBytes = 0xE0000000ull;   // largest table addressed through a buffer
-constexpr uint32_t kBufWord3 = 0x00020000u;        // gfx9 buffer resource: 32-bit data format
-
-struct KParams {
-  int64_t num_lookups;   // NL
-  int64_t out_ld;        // floats
-  int64_t max_rows;      // clamp on R_t in buffer mode (host guarantees max_rows*row_bytes fits)
-  uint32_t B;            // bags per table
-  uint32_t num_work;     // T*B*slabs
-  uint32_t slabs;        // ceil(row_bytes / 1024)
-  uint32_t row_bytes;
-  uint32_t D;
-  uint32_t mean;         // 1 = divide by bag length
-  uint32_t has_hints;    // 1 = table_hints points to T bytes
-  // XCD-affine block order (xcd_bpp = 0: natural order).  Every table is cut into 2^xcd_pshift
-  // pieces of xcd_wpp wavefronts (xcd_bpp workgroups); piece u = t * 2^xcd_pshift + k runs on
-  // XCD u % 8, and an XCD takes its pieces in increasing u.
-  uint32_t xcd_bpp;
-  uint32_t xcd_wpp;
-  uint32_t xcd_pshift;
-  uint32_t xcd_ordered;  // 1 = position q of the XCD-affine order holds table TableOrder::t[q]
-};
-
-// Tables of different widths load the XCDs unevenly when they are dealt out in their own order
-// (a wavefront's work grows with the row width).  The host then deals them by width instead and
-// hands the kernel the resulting order by value, in the kernel-argument segment.
-constexpr int kMaxOrdered = 1024;
-struct TableOrder {
-  uint16_t t[kMaxOrdered];
-};
-
-__device__ __forceinline__ int64_t uniform64(int64_t v) {
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)v);
-  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
-  return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-
-__device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
-  const uint32_t lo = (uint32_t)__shfl((int)(uint32_t)(uint64_t)v, src);
-  const uint32_t hi = (uint32_t)__shfl((int)(uint32_t)((uint64_t)v >> 32), src);
-  return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-
-__device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
-
-// fp32 accumulators a lane keeps for its 16-byte segment of the row: 4 fp32 elements, 8 fp16 /
-// bf16 elements, or 16 one-byte codes plus one accumulator for the sum of the row biases.
-template <int ELEM>
-struct AccCount {
-  static constexpr int value = ELEM == EMB_F32 ? 4 : (ELEM == EMB_U8ROW ? 17 : 8);
-};
-
-// acc += w * (one 16-byte segment of a row): 4 fp32 elements, 8 fp16 / bf16 elements widened
-// exactly to fp32, or 16 codes of a row-wise quantised row.  For the latter the row's scale and
-// bias sit in the last 8 bytes of the row, i.e. in words z and w of lane `meta_lane`'s segment;
-// acc[i] collects w * scale * code_i and acc[16] collects w * bias, added to every element at the
-// end of the bag (a lookup that fetched nothing has scale = bias = 0).
-template <int ELEM, bool WEIGHTED>
-__device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int meta_lane) {
-  if constexpr (ELEM == EMB_U8ROW) {
-    float scale = as_float((uint32_t)__shfl((int)r.z, meta_lane));
-    float bias = as_float((uint32_t)__shfl((int)r.w, meta_lane));
-    if constexpr (WEIGHTED) {
-      scale *= w;
-      bias *= w;
-    }
-    const uint32_t u[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const float code = (float)((u[i] >> (8 * k)) & 0xFFu);
-        acc[4 * i + k] = __builtin_fmaf(scale, code, acc[4 * i + k]);
-      }
-    }
-    acc[16] += bias;
-  } else if constexpr (ELEM != EMB_F32) {
-    const uint32_t u[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float lo, hi;
-      if constexpr (ELEM == EMB_F16) {
-        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-        const h2 h = __builtin_bit_cast(h2, u[i]);
-        lo = (float)h.x;
-        hi = (float)h.y;
-      } else {  // bfloat16 is the upper half of a binary32: widening is a shift
-        lo = as_float(u[i] << 16);
-        hi = as_float(u[i] & 0xFFFF0000u);
-      }
-      if constexpr (WEIGHTED) {
-        acc[2 * i] = __builtin_fmaf(w, lo, acc[2 * i]);
-        acc[2 * i + 1] = __builtin_fmaf(w, hi, acc[2 * i + 1]);
-      } else {
-        acc[2 * i] += lo;
-        acc[2 * i + 1] += hi;
-      }
-    }
-  } else {
-    const float x[4] = {as_float(r.x), as_float(r.y), as_float(r.z), as_float(r.w)};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if constexpr (WEIGHTED)
-        acc[i] = __builtin_fmaf(w, x[i], acc[i]);
-      else
-        acc[i] += x[i];
-    }
-  }
-}
-
-// The gather of one bag (one column slab of it): walk the bag's lookups in chunks of 64 and add
-// the rows into acc.  LPR is the number of lanes per row (0: decided per table at run time, then
-// 2^glog2 rows share a wave load).  NT selects the non-temporal cache policy for the row loads (tables whose
-// rows are not re-used within a batch), the default policy otherwise.
-template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool BUF, bool NT>
-__device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict__ indices,
-                                           const float* __restrict__ weights, int64_t s,
-                                           int64_t e, int64_t R, uint32_t row_bytes,
-                                           const char* tbase, __amdgpu_buffer_rsrc_t rsrc,
-                                           int lane, int g, uint32_t col, bool lane_ok,
-                                           int meta_lane, int glog2) {
-  // log2 of the rows per wave load: a constant for a fixed LPR, a wave-uniform value for LPR == 0
-  const int gl = LPR ? __builtin_ctz((unsigned)(kWaveSize / (LPR ? LPR : 1))) : glog2;
-  constexpr int kAux = NT ? 2 : 0;  // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
-  for (int64_t c = s; c < e; c += kWaveSize) {
-    const int64_t left = e - c;
-    const int n = left < kWaveSize ? (int)left : kWaveSize;  // lookups in this chunk (uniform)
-    int64_t idx = -1;
-    float w = 0.0f;
-    if (lane < n) {
-      idx = __builtin_nontemporal_load(indices + c + lane);
-      if constexpr (WEIGHTED) w = __builtin_nontemporal_load(weights + c + lane);
-    }
-    const bool idx_ok = (uint64_t)idx < (uint64_t)R;
-    uint32_t voff = kBufSentinel;  // BUF: 32-bit byte offset of the row inside the table
-    int64_t roff = -1;             // !BUF: 64-bit byte offset, -1 = skip
-    if constexpr (BUF) {
-      if (idx_ok) voff = (uint32_t)idx * row_bytes;
-    } else {
-      if (idx_ok) roff = idx * (int64_t)row_bytes;
-    }
-
-    const int steps = (n + (1 << gl) - 1) >> gl;
-    for (int k0 = 0; k0 < steps; k0 += DEPTH) {
-      u32x4 r[DEPTH];
-      float wj[DEPTH];
-#pragma unroll
-      for (int d = 0; d < DEPTH; ++d) {
-        const int j = ((k0 + d) << gl) + g;  // lookup of this chunk served by this lane's group
-        const bool take = (j < n) && lane_ok;
-        if constexpr (BUF) {
-          uint32_t vo = (uint32_t)__shfl((int)voff, j & (kWaveSize - 1));
-          vo = take ? vo : kBufSentinel;
-          r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
-        } else {
-          const int64_t ro = shfl64(roff, j & (kWaveSize - 1));
-          u32x4 v = {0u, 0u, 0u, 0u};
-          if (take && ro >= 0) {
-            const u32x4* src = reinterpret_cast<const u32x4*>(tbase + ro + col);
-            v = NT ? __builtin_nontemporal_load(src) : *src;
-          }
-          r[d] = v;
-        }
-        if constexpr (WEIGHTED) {
-          const float ws = __shfl(w, j & (kWaveSize - 1));
-          wj[d] = (j < n) ? ws : 0.0f;
-        } else {
-          wj[d] = 1.0f;
-        }
-      }
-#pragma unroll
-      for (int d = 0; d < DEPTH; ++d) accumulate<ELEM, WEIGHTED>(acc, r[d], wj[d], meta_lane);
-    }
-  }
-
-}
+using namespace embbag;
 
 // One wavefront per (bag, column slab).  LPR = lanes per row (power of two, 4..64), or 0 for
 // tables of different widths: then table t is described by table_offsets[t] (its BYTE offset in
@@ -239,30 +57,11 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;  // 2-byte elements
   constexpr bool QUANT = ELEM == EMB_U8ROW;                   // 1-byte codes + scale, bias
   constexpr int NACC = AccCount<ELEM>::value;                 // fp32 accumulators per lane
-  constexpr int NOUT = QUANT ? 16 : NACC;                     // output elements per lane
 
   const int lane = threadIdx.x & (kWaveSize - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t work;
-  if (p.xcd_bpp) {
-    // workgroups are dealt round-robin to the 8 XCDs: blockIdx % 8 names the XCD (and its L2)
-    const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
-    const uint32_t ul = slot / p.xcd_bpp;
-    const uint32_t unit = ul * 8u + xcd;
-    const uint32_t w_in_piece = (slot - ul * p.xcd_bpp) * kWavesPerBlock + wave;
-    const uint32_t waves_per_table = p.B * p.slabs;
-    const uint32_t w_in_table = (unit & ((1u << p.xcd_pshift) - 1u)) * p.xcd_wpp + w_in_piece;
-    if (w_in_piece >= p.xcd_wpp || w_in_table >= waves_per_table) return;
-    uint32_t tpos = unit >> p.xcd_pshift;
-    if constexpr (MIXED) {
-      if (p.xcd_ordered) tpos = order.t[tpos];
-    }
-    work = tpos * waves_per_table + w_in_table;
-  } else {
-    const uint64_t work64 = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
-    if (work64 >= p.num_work) return;
-    work = (uint32_t)work64;
-  }
+  if (!decode_work(p, wave, MIXED, order, &work)) return;
 
   uint32_t bag = work, slab = 0;
   if (p.slabs > 1) {
@@ -334,42 +133,8 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
                                                       tbase, rsrc, lane, g, col, lane_ok,
                                                       meta_lane, 6 - lpr_log2);
 
-  if constexpr (QUANT) {
-#pragma unroll
-    for (int i = 0; i < NOUT; ++i) acc[i] += acc[16];
-  }
-
-  // combine the G row groups (fixed butterfly: every lane ends with the same bits)
-#pragma unroll
-  for (int m = kWaveSize / 2; m >= 4; m >>= 1) {
-    if (m >= lpr) {  // wave-uniform; a compile-time constant unless LPR == 0
-#pragma unroll
-      for (int i = 0; i < NOUT; ++i) acc[i] += __shfl_xor(acc[i], m);
-    }
-  }
-
-  if (p.mean) {
-    const int64_t len = e - s;
-    if (len > 0) {
-      const float fl = (float)len;
-#pragma unroll
-      for (int i = 0; i < NOUT; ++i) acc[i] = acc[i] / fl;
-    }
-  }
-
-  if (lane < lpr && lane_ok) {
-    // col counts bytes of the table row; the output is fp32.  A quantised row ends with 8 codes
-    // and 8 bytes of scale and bias, so its last lane stores 8 elements instead of 16.
-    const uint32_t elem0 = QUANT ? col : (HALF ? col / 2 : col / 4);
-    f32x4* dst = reinterpret_cast<f32x4*>(out + (int64_t)b * p.out_ld + out_col + elem0);
-#pragma unroll
-    for (int q = 0; q < NOUT / 4; ++q) {
-      if (!QUANT || elem0 + 4 * q < D_t) {
-        const f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-        __builtin_nontemporal_store(v, dst + q);
-      }
-    }
-  }
+  finish_bag<LPR, ELEM>(acc, lpr, lane, lane_ok, col, D_t, e - s, p.mean != 0, out, p.out_ld, b,
+                        out_col);
 }
 
 // One wavefront per bag: count bad bounds and bad indices.
@@ -467,12 +232,21 @@ struct Tuning {
   int64_t blocks_per_cu = 0;
   int64_t xcd_remap = -1;
   int64_t use_hints = 1;
+  int64_t stream = -1;          // short-bag kernel: -1 = by average bag length, 0 = never, 1 = when possible
+  int64_t bags_per_group = 0;   // its consecutive bags per lane group: 0 = automatic
 };
 Tuning g_tuning;
 
-using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int64_t*,
-                          const float*, const uint8_t*, const int64_t*, float*, KParams,
-                          TableOrder);
+// When the short-bag kernel is chosen (measured on MI355X over row widths 128 B .. 1 KiB and
+// pooling 1 .. 80): the wave kernel fetches G = 64/LPR rows of a bag per load instruction and
+// needs about three such instructions per bag to hide its per-bag chain, so the stream kernel
+// wins below an average of 3 * G lookups per bag (7x at 128-byte rows and one lookup per bag,
+// nothing above the threshold).  A group then takes about kStreamGroupLookups lookups' worth of
+// consecutive bags, fewer when the launch would drop below kStreamMinWaves wavefronts.
+constexpr double kStreamBelowRowLoads = 3.0;
+constexpr double kStreamGroupLookups = 4.0;
+constexpr int64_t kStreamMaxAutoBags = 4;
+constexpr int64_t kStreamMinWaves = 1024;
 
 template <int LPR, int ELEM, int DEPTH>
 KernelFn pick_wb(bool weighted, bool buf) {
@@ -540,14 +314,13 @@ int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
 
 // Choose the kernel instantiation, lay out the grid (natural or XCD-affine order), apply the
 // occupancy cap, and launch.  `p` holds the shape; the XCD fields are filled here.
-int enqueue(int lpr, int elem, int depth, bool buf, int64_t T, KParams p, const void* tables,
+int enqueue(KernelFn fn, int64_t T, KParams p, const void* tables,
             const int64_t* table_offsets, const int64_t* indices, const int64_t* offsets,
             const float* weights, const uint8_t* table_hints, const int64_t* out_offsets,
             const uint16_t* row_units, bool natural_order, float* out, void* stream) {
-  KernelFn fn = pick_kernel(lpr, elem, depth, weights != nullptr, buf);
   if (!fn) return EMB_ERR_BAD_TUNING;
   const int64_t num_work = p.num_work;
-  const int64_t waves_per_table_i = num_work / T;
+  const int64_t waves_per_table_i = p.wpt;
   p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = p.xcd_ordered = 0;
   TableOrder order = {};  // only the first T entries are read, and only when xcd_ordered is set
 
@@ -662,13 +435,42 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   p.max_rows = desc->max_table_rows;
   p.B = (uint32_t)B;
   p.num_work = (uint32_t)num_work;
+  p.wpt = (uint32_t)(B * slabs);
   p.slabs = (uint32_t)slabs;
   p.row_bytes = row_bytes;
   p.D = (uint32_t)D;
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
-  return enqueue(lpr, desc->table_dtype, depth, buf, T, p, tables, table_offsets, indices, offsets,
-                 per_sample_weights, desc->table_hints, nullptr, nullptr, false, out, stream);
+  p.bags_per_group = 0;
+  KernelFn fn = nullptr;
+
+  // Short bags: a lane group streams several consecutive bags (emb_bag_stream.hip).  The host
+  // knows the average bag length, NL / (T * B), and nothing else about the lengths.
+  const int groups = kWaveSize / lpr;
+  const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
+  if (g_tuning.stream != 0 && slabs == 1 && buf &&
+      (g_tuning.stream == 1 || avg_len < kStreamBelowRowLoads * groups)) {
+    int64_t m = g_tuning.bags_per_group;
+    if (m == 0) {
+      m = (int64_t)(kStreamGroupLookups / (avg_len < 1.0 ? 1.0 : avg_len) + 0.5);
+      if (m > kStreamMaxAutoBags) m = kStreamMaxAutoBags;
+      while (m > 1 && T * ((B + groups * m - 1) / (groups * m)) < kStreamMinWaves) m /= 2;
+    }
+    if (m > lpr - 1) m = lpr - 1;
+    if (m < 1) m = 1;
+    // the wavefront's output rows are addressed through one buffer with 32-bit offsets
+    if ((uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u <= kBufMaxBytes) {
+      fn = pick_stream_kernel(lpr, desc->table_dtype, depth, per_sample_weights != nullptr);
+      if (fn) {
+        p.bags_per_group = (uint32_t)m;
+        p.wpt = (uint32_t)((B + groups * m - 1) / (groups * m));
+        p.num_work = (uint32_t)(T * p.wpt);
+      }
+    }
+  }
+  if (!fn) fn = pick_kernel(lpr, desc->table_dtype, depth, per_sample_weights != nullptr, buf);
+  return enqueue(fn, T, p, tables, table_offsets, indices, offsets, per_sample_weights,
+                 desc->table_hints, nullptr, nullptr, false, out, stream);
 }
 
 int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
@@ -724,13 +526,16 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   p.max_rows = 0;
   p.B = (uint32_t)B;
   p.num_work = (uint32_t)(T * B);
+  p.wpt = (uint32_t)B;
+  p.bags_per_group = 0;
   p.slabs = 1;
   p.row_bytes = max_row_bytes;
   p.D = 0;
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
-  return enqueue(0, desc->table_dtype, depth, buf, T, p, tables, table_byte_offsets, indices,
-                 offsets, per_sample_weights, desc->table_hints, out_offsets,
+  return enqueue(pick_kernel(0, desc->table_dtype, depth, per_sample_weights != nullptr, buf), T, p,
+                 tables, table_byte_offsets, indices, offsets, per_sample_weights,
+                 desc->table_hints, out_offsets,
                  widths_differ && !too_many ? row_units : nullptr, too_many, out, stream);
 }
 
@@ -793,6 +598,12 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
   } else if (!strcmp(key, "use_hints")) {
     if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
     g_tuning.use_hints = value;
+  } else if (!strcmp(key, "stream")) {
+    if (value < -1 || value > 1) return EMB_ERR_BAD_TUNING;
+    g_tuning.stream = value;
+  } else if (!strcmp(key, "bags_per_group")) {
+    if (value < 0 || value > 63) return EMB_ERR_BAD_TUNING;
+    g_tuning.bags_per_group = value;
   } else {
     return EMB_ERR_BAD_TUNING;
   }
@@ -806,6 +617,8 @@ int emb_bag_get_tuning(const char* key, int64_t* value) {
   else if (!strcmp(key, "blocks_per_cu")) *value = g_tuning.blocks_per_cu;
   else if (!strcmp(key, "xcd_remap")) *value = g_tuning.xcd_remap;
   else if (!strcmp(key, "use_hints")) *value = g_tuning.use_hints;
+  else if (!strcmp(key, "stream")) *value = g_tuning.stream;
+  else if (!strcmp(key, "bags_per_group")) *value = g_tuning.bags_per_group;
   else return EMB_ERR_BAD_TUNING;
   return EMB_OK;
 }

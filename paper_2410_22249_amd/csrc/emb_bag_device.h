@@ -1,0 +1,278 @@
+// Device-side building blocks shared by the embedding-bag kernels (gfx950, wave64): constants,
+// launch parameters, cross-lane helpers, the per-segment accumulate and the gather of one bag.
+// Included by the kernel sources only; nothing here is part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/emb_bag.h"
+
+namespace embbag {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWaveSize = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWaveSize * kWavesPerBlock;
+constexpr int kSlabBytes = 1024;                   // bytes of one row a wavefront covers per pass
+constexpr uint32_t kBufSentinel = 0xF0000000u;     // offset that is out of range for any table
+constexpr uint64_t kBufMaxBytes = 0xE0000000ull;   // largest table addressed through a buffer
+constexpr uint32_t kBufWord3 = 0x00020000u;        // gfx9 buffer resource: 32-bit data format
+
+struct KParams {
+  int64_t num_lookups;   // NL
+  int64_t out_ld;        // floats
+  int64_t max_rows;      // clamp on R_t in buffer mode (host guarantees max_rows*row_bytes fits)
+  uint32_t B;            // bags per table
+  uint32_t num_work;     // wavefronts with work: T * wpt
+  uint32_t wpt;          // wavefronts per table
+  uint32_t slabs;        // ceil(row_bytes / 1024)
+  uint32_t row_bytes;
+  uint32_t D;
+  uint32_t mean;         // 1 = divide by bag length
+  uint32_t has_hints;    // 1 = table_hints points to T bytes
+  // XCD-affine block order (xcd_bpp = 0: natural order).  Every table is cut into 2^xcd_pshift
+  // pieces of xcd_wpp wavefronts (xcd_bpp workgroups); piece u = t * 2^xcd_pshift + k runs on
+  // XCD u % 8, and an XCD takes its pieces in increasing u.
+  uint32_t xcd_bpp;
+  uint32_t xcd_wpp;
+  uint32_t xcd_pshift;
+  uint32_t xcd_ordered;  // 1 = position q of the XCD-affine order holds table TableOrder::t[q]
+  uint32_t bags_per_group;  // stream kernel: consecutive bags owned by one lane group
+};
+
+// Tables of different widths load the XCDs unevenly when they are dealt out in their own order
+// (a wavefront's work grows with the row width).  The host then deals them by width instead and
+// hands the kernel the resulting order by value, in the kernel-argument segment.
+constexpr int kMaxOrdered = 1024;
+struct TableOrder {
+  uint16_t t[kMaxOrdered];
+};
+
+// Every forward kernel takes the same arguments: tables, table_offsets, indices, offsets,
+// weights, table_hints, out_offsets (different widths only), out, parameters, table order.
+using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int64_t*,
+                          const float*, const uint8_t*, const int64_t*, float*, KParams,
+                          TableOrder);
+
+// The kernel for short bags (emb_bag_stream.hip): lanes per row 4..64, rows of at most 1 KiB,
+// buffer addressing.  nullptr if there is no such instantiation.
+__attribute__((visibility("hidden"))) KernelFn pick_stream_kernel(int lpr, int elem, int depth,
+                                                                  bool weighted);
+
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
+  const uint32_t lo = (uint32_t)__shfl((int)(uint32_t)(uint64_t)v, src);
+  const uint32_t hi = (uint32_t)__shfl((int)(uint32_t)((uint64_t)v >> 32), src);
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// fp32 accumulators a lane keeps for its 16-byte segment of the row: 4 fp32 elements, 8 fp16 /
+// bf16 elements, or 16 one-byte codes plus one accumulator for the sum of the row biases.
+template <int ELEM>
+struct AccCount {
+  static constexpr int value = ELEM == EMB_F32 ? 4 : (ELEM == EMB_U8ROW ? 17 : 8);
+};
+
+// acc += w * (one 16-byte segment of a row): 4 fp32 elements, 8 fp16 / bf16 elements widened
+// exactly to fp32, or 16 codes of a row-wise quantised row.  For the latter the row's scale and
+// bias sit in the last 8 bytes of the row, i.e. in words z and w of lane `meta_lane`'s segment;
+// acc[i] collects w * scale * code_i and acc[16] collects w * bias, added to every element at the
+// end of the bag (a lookup that fetched nothing has scale = bias = 0).
+template <int ELEM, bool WEIGHTED>
+__device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int meta_lane) {
+  if constexpr (ELEM == EMB_U8ROW) {
+    float scale = as_float((uint32_t)__shfl((int)r.z, meta_lane));
+    float bias = as_float((uint32_t)__shfl((int)r.w, meta_lane));
+    if constexpr (WEIGHTED) {
+      scale *= w;
+      bias *= w;
+    }
+    const uint32_t u[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float code = (float)((u[i] >> (8 * k)) & 0xFFu);
+        acc[4 * i + k] = __builtin_fmaf(scale, code, acc[4 * i + k]);
+      }
+    }
+    acc[16] += bias;
+  } else if constexpr (ELEM != EMB_F32) {
+    const uint32_t u[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float lo, hi;
+      if constexpr (ELEM == EMB_F16) {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        const h2 h = __builtin_bit_cast(h2, u[i]);
+        lo = (float)h.x;
+        hi = (float)h.y;
+      } else {  // bfloat16 is the upper half of a binary32: widening is a shift
+        lo = as_float(u[i] << 16);
+        hi = as_float(u[i] & 0xFFFF0000u);
+      }
+      if constexpr (WEIGHTED) {
+        acc[2 * i] = __builtin_fmaf(w, lo, acc[2 * i]);
+        acc[2 * i + 1] = __builtin_fmaf(w, hi, acc[2 * i + 1]);
+      } else {
+        acc[2 * i] += lo;
+        acc[2 * i + 1] += hi;
+      }
+    }
+  } else {
+    const float x[4] = {as_float(r.x), as_float(r.y), as_float(r.z), as_float(r.w)};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (WEIGHTED)
+        acc[i] = __builtin_fmaf(w, x[i], acc[i]);
+      else
+        acc[i] += x[i];
+    }
+  }
+}
+
+// The gather of one bag (one column slab of it): walk the bag's lookups in chunks of 64 and add
+// the rows into acc.  LPR is the number of lanes per row (0: decided per table at run time, then
+// 2^glog2 rows share a wave load).  NT selects the non-temporal cache policy for the row loads (tables whose
+// rows are not re-used within a batch), the default policy otherwise.
+template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool BUF, bool NT>
+__device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict__ indices,
+                                           const float* __restrict__ weights, int64_t s,
+                                           int64_t e, int64_t R, uint32_t row_bytes,
+                                           const char* tbase, __amdgpu_buffer_rsrc_t rsrc,
+                                           int lane, int g, uint32_t col, bool lane_ok,
+                                           int meta_lane, int glog2) {
+  // log2 of the rows per wave load: a constant for a fixed LPR, a wave-uniform value for LPR == 0
+  const int gl = LPR ? __builtin_ctz((unsigned)(kWaveSize / (LPR ? LPR : 1))) : glog2;
+  constexpr int kAux = NT ? 2 : 0;  // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
+  for (int64_t c = s; c < e; c += kWaveSize) {
+    const int64_t left = e - c;
+    const int n = left < kWaveSize ? (int)left : kWaveSize;  // lookups in this chunk (uniform)
+    int64_t idx = -1;
+    float w = 0.0f;
+    if (lane < n) {
+      idx = __builtin_nontemporal_load(indices + c + lane);
+      if constexpr (WEIGHTED) w = __builtin_nontemporal_load(weights + c + lane);
+    }
+    const bool idx_ok = (uint64_t)idx < (uint64_t)R;
+    uint32_t voff = kBufSentinel;  // BUF: 32-bit byte offset of the row inside the table
+    int64_t roff = -1;             // !BUF: 64-bit byte offset, -1 = skip
+    if constexpr (BUF) {
+      if (idx_ok) voff = (uint32_t)idx * row_bytes;
+    } else {
+      if (idx_ok) roff = idx * (int64_t)row_bytes;
+    }
+
+    const int steps = (n + (1 << gl) - 1) >> gl;
+    for (int k0 = 0; k0 < steps; k0 += DEPTH) {
+      u32x4 r[DEPTH];
+      float wj[DEPTH];
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        const int j = ((k0 + d) << gl) + g;  // lookup of this chunk served by this lane's group
+        const bool take = (j < n) && lane_ok;
+        if constexpr (BUF) {
+          uint32_t vo = (uint32_t)__shfl((int)voff, j & (kWaveSize - 1));
+          vo = take ? vo : kBufSentinel;
+          r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
+        } else {
+          const int64_t ro = shfl64(roff, j & (kWaveSize - 1));
+          u32x4 v = {0u, 0u, 0u, 0u};
+          if (take && ro >= 0) {
+            const u32x4* src = reinterpret_cast<const u32x4*>(tbase + ro + col);
+            v = NT ? __builtin_nontemporal_load(src) : *src;
+          }
+          r[d] = v;
+        }
+        if constexpr (WEIGHTED) {
+          const float ws = __shfl(w, j & (kWaveSize - 1));
+          wj[d] = (j < n) ? ws : 0.0f;
+        } else {
+          wj[d] = 1.0f;
+        }
+      }
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) accumulate<ELEM, WEIGHTED>(acc, r[d], wj[d], meta_lane);
+    }
+  }
+
+}
+
+// Which piece of work this wavefront owns: its number in table-major order (table = work / wpt),
+// or false if it has none.  Workgroups are dealt round-robin to the 8 XCDs, so blockIdx % 8
+// names the XCD (and its L2); the XCD-affine order turns that into (table, piece) as described
+// at KParams.  `order` is read only by launches with tables of different widths.
+__device__ __forceinline__ bool decode_work(const KParams& p, uint32_t wave, bool use_order,
+                                            const TableOrder& order, uint32_t* work) {
+  if (p.xcd_bpp) {
+    const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+    const uint32_t ul = slot / p.xcd_bpp;
+    const uint32_t unit = ul * 8u + xcd;
+    const uint32_t w_in_piece = (slot - ul * p.xcd_bpp) * kWavesPerBlock + wave;
+    const uint32_t w_in_table = (unit & ((1u << p.xcd_pshift) - 1u)) * p.xcd_wpp + w_in_piece;
+    if (w_in_piece >= p.xcd_wpp || w_in_table >= p.wpt) return false;
+    uint32_t tpos = unit >> p.xcd_pshift;
+    if (use_order && p.xcd_ordered) tpos = order.t[tpos];
+    *work = tpos * p.wpt + w_in_table;
+    return true;
+  }
+  const uint64_t work64 = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (work64 >= p.num_work) return false;
+  *work = (uint32_t)work64;
+  return true;
+}
+
+// The end of a bag that all 64 lanes gathered together (gather_bag): combine the G = 64/lpr row
+// groups with a fixed xor butterfly (every lane ends with the same bits), add the summed biases
+// of quantised rows, divide by the bag length for the mean, and store the lane's elements of
+// bag row `b` at output column `out_col` with 16-byte non-temporal stores.
+template <int LPR, int ELEM>
+__device__ __forceinline__ void finish_bag(float* acc, int lpr, int lane, bool lane_ok,
+                                           uint32_t col, uint32_t D_t, int64_t len, bool mean,
+                                           float* __restrict__ out, int64_t out_ld, uint32_t b,
+                                           int64_t out_col) {
+  constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;
+  constexpr bool QUANT = ELEM == EMB_U8ROW;
+  constexpr int NOUT = QUANT ? 16 : AccCount<ELEM>::value;
+  if constexpr (QUANT) {
+#pragma unroll
+    for (int i = 0; i < NOUT; ++i) acc[i] += acc[16];
+  }
+#pragma unroll
+  for (int m = kWaveSize / 2; m >= 4; m >>= 1) {
+    if (m >= lpr) {  // wave-uniform; a compile-time constant unless LPR == 0
+#pragma unroll
+      for (int i = 0; i < NOUT; ++i) acc[i] += __shfl_xor(acc[i], m);
+    }
+  }
+  if (mean && len > 0) {
+    const float fl = (float)len;
+#pragma unroll
+    for (int i = 0; i < NOUT; ++i) acc[i] = acc[i] / fl;
+  }
+  if (lane < lpr && lane_ok) {
+    // col counts bytes of the table row; the output is fp32.  A quantised row ends with 8 codes
+    // and 8 bytes of scale and bias, so its last lane stores 8 elements instead of 16.
+    const uint32_t elem0 = QUANT ? col : (HALF ? col / 2 : col / 4);
+    f32x4* dst = reinterpret_cast<f32x4*>(out + (int64_t)b * out_ld + out_col + elem0);
+#pragma unroll
+    for (int q = 0; q < NOUT / 4; ++q) {
+      if (!QUANT || elem0 + 4 * q < D_t) {
+        const f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        __builtin_nontemporal_store(v, dst + q);
+      }
+    }
+  }
+}
+
+}  // namespace embbag
