@@ -35,6 +35,10 @@ DESCRIPTIONS = {
     "cfg3_weighted": "cfg3 with fp32 per-sample weights",
     "cfg3_u8": "cfg3's shape with row-wise quantised rows: 60 tables x 4,000,000 rows x dim 120 "
                "(uint8 codes + fp32 scale, bias = 128-byte rows), batch 4096, pooling 80, uniform, sum",
+    "onehot": "short bags: 26 fp32 tables x 1,000,000 rows x dim 64, batch 131072, ONE lookup per "
+              "bag, uniform indices, sum (stream kernel)",
+    "short": "short bags: 26 fp32 tables x 1,000,000 rows x dim 64, batch 32768, pooling U[0,8], "
+             "uniform indices, sum (stream kernel)",
     "paper_high": "paper's model, Zipf(1.3396) stand-in for its high-hot trace (4.05 % unique)",
     "paper_med": "paper's model, Zipf(1.0234) stand-in for its med-hot trace (20.5 % unique)",
     "paper_low": "paper's model, Zipf(0.6999) stand-in for its low-hot trace (46.21 % unique)",
@@ -383,7 +387,8 @@ def main() -> int:
                    "arena_allocation": arena_kind,
                    "streaming_tables": None if hints is None else int(hints.sum().item()),
                    "tuning": {k: emb.emb_bag_get_tuning(k) for k in
-                              ("depth", "addressing", "blocks_per_cu", "xcd_remap", "use_hints")}},
+                              ("depth", "addressing", "blocks_per_cu", "xcd_remap", "use_hints",
+                               "stream", "bags_per_group")}},
         "gathered_GBps": gathered * args.steps / wall / 1e9,
         "gathered_frac_of_hbm_peak": gathered * args.steps / wall / 1e9 / metrics.HBM_PEAK_GBPS,
         "kernel_ms": {"avg": avg_kern_s * 1e3, "min": float(min(kern_ms)),

@@ -430,6 +430,12 @@ def workload(name: str) -> Workload:
         return Workload(name="small_u8_d504", T=3, rows=(900, 65, 400), D=504, dtype="u8row",
                         B=45, pooling=("uniform", 0, 130),
                         dists=(("uniform",), ("zipf", 1.2), ("uniform",)), seed=0x5EED0016)
+    if name == "onehot":           # short bags: cfg2's tables, one lookup per bag, large batch
+        return _homog("onehot", 26, 1_000_000, 64, "f32", 131072, ("fixed", 1), ("uniform",),
+                      seed_off=0x18)
+    if name == "short":            # cfg2's tables, 0..8 lookups per bag (a ninth of the bags empty)
+        return _homog("short", 26, 1_000_000, 64, "f32", 32768, ("uniform", 0, 8), ("uniform",),
+                      seed_off=0x19)
     if name == "cfg3_weighted":    # cfg3 with per-sample weights
         return with_overrides(workload("cfg3"), name="cfg3_weighted", weighted=True)
     if name == "cfg3_u8":          # cfg3's shape with quantised rows (dim 120 -> 128-byte rows)

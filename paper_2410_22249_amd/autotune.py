@@ -30,7 +30,9 @@ DEFAULT_GRID = {
     "use_hints": [1, 0],
     "xcd_remap": [1, 0],
 }
-NEUTRAL = {"blocks_per_cu": 0, "depth": 0, "use_hints": 1, "xcd_remap": -1, "addressing": 0}
+# for short bags add e.g. --grid '{"stream":[0,1],"bags_per_group":[1,2,4,8],"depth":[4,8]}'
+NEUTRAL = {"blocks_per_cu": 0, "depth": 0, "use_hints": 1, "xcd_remap": -1, "addressing": 0,
+           "stream": -1, "bags_per_group": 0}
 
 
 def apply_tuning(settings: Dict[str, int]) -> None:
@@ -41,11 +43,15 @@ def apply_tuning(settings: Dict[str, int]) -> None:
 
 
 def _setup(name: str, n_batches: int):
+    from inputgen import gen
+    return _setup_wl(gen.workload(name), n_batches)
+
+
+def _setup_wl(wl, n_batches: int):
     import torch
     import paper_2410_22249_amd as emb
     from inputgen import gen
 
-    wl = gen.workload(name)
     dev = "cuda:0"
     tdtype = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16,
               "u8row": torch.uint8}[wl.dtype]

@@ -19,7 +19,7 @@ import statistics
 import sys
 from collections import defaultdict
 
-EMB = "emb_bag_wave_kernel"          # the forward kernel (all template variants)
+EMB = ("emb_bag_wave_kernel", "emb_bag_stream_kernel")   # the forward kernels (all variants)
 COPY = "(anonymous namespace)::copy_kernel("   # the generator's calibration copy, not torch's
 CAL_BYTES = 1 << 30
 
@@ -68,7 +68,7 @@ def main() -> int:
             continue
         data = per_kernel_counter(path)[counter]
         cal = [v for k, vs in data.items() if COPY in k for v in vs]
-        emb = [v for k, vs in data.items() if EMB in k for v in vs]
+        emb = [v for k, vs in data.items() if any(e in k for e in EMB) for v in vs]
         if not cal or not emb:
             print(f"\n## {counter}: calibration copy or embedding kernel not found in {path}")
             continue
@@ -86,7 +86,7 @@ def main() -> int:
         data = per_kernel_counter(path)
         print(f"\n## counters from {path.split('/')[-2] if '/' in path else path} (embedding kernel, median per dispatch)")
         for counter, per in sorted(data.items()):
-            emb = [v for k, vs in per.items() if EMB in k for v in vs]
+            emb = [v for k, vs in per.items() if any(e in k for e in EMB) for v in vs]
             if emb:
                 print(f"{counter:32s} {statistics.median(emb):18.3f}")
     return 0
