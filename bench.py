@@ -33,6 +33,7 @@ DESCRIPTIONS = {
              "indices, sum (the paper's model, random dataset)",
     "paper_one_item": "250 fp32 tables x 500,000 x dim 128, batch 2048, pooling 150, one item, sum",
     "cfg3_weighted": "cfg3 with fp32 per-sample weights",
+    "cfg3_max": "cfg3 with max pooling",
     "cfg3_u8": "cfg3's shape with row-wise quantised rows: 60 tables x 4,000,000 rows x dim 120 "
                "(uint8 codes + fp32 scale, bias = 128-byte rows), batch 4096, pooling 80, uniform, sum",
     "onehot": "short bags: 26 fp32 tables x 1,000,000 rows x dim 64, batch 131072, ONE lookup per "
@@ -160,7 +161,7 @@ def main() -> int:
     out = torch.empty((wl.B, total_dim), dtype=torch.float32, device=dev)
     edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16,
            "u8row": emb.EMB_U8ROW}[wl.dtype]
-    emode = emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM
+    emode = emb.MODES[wl.mode]
     # Set-up, untimed (the paper profiles table access patterns offline, Sec. 4.3): classify each
     # table as streaming or re-used from the first index batch, on the device.
     hints = None

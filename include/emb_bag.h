@@ -37,9 +37,14 @@ extern "C" {
                        an fp32 bias (row = D + 8 bytes, which must be a multiple of 16 and at most
                        1024); element d of a row is scale * code_d + bias, accumulated in fp32 */
 
-/* pooling modes (the two modes of the sum/mean kernel the paper studies, Sec. 3.1) */
+/* pooling modes: the two modes of the sum/mean kernel the paper studies (Sec. 3.1), and the
+   element-wise maximum, the third pooling an embedding-bag operator usually offers */
 #define EMB_SUM 0
 #define EMB_MEAN 1 /* sum divided by the bag length; an empty bag gives 0 */
+#define EMB_MAX 2  /* element-wise maximum over the bag's lookups that name an existing row; a bag
+                      with none (empty, or invalid ids only) gives 0.  No per-sample weights.  The
+                      result is an element of the table (exact) for fp32 / fp16 / bf16 rows; if a
+                      gathered element is NaN the result for that output element is unspecified */
 
 /* per-table access hints (one byte per table, see emb_bag_desc.table_hints) */
 #define EMB_HINT_DEFAULT 0   /* rows are re-used within a batch: read them with the default cache
@@ -52,8 +57,8 @@ extern "C" {
 #define EMB_ERR_NULL_PTR (-1)    /* a required pointer is NULL */
 #define EMB_ERR_BAD_DIM (-2)     /* dim <= 0, row not a multiple of 16 bytes, bad out_ld, ... */
 #define EMB_ERR_BAD_DTYPE (-3)   /* table_dtype is not one of the EMB_* element types */
-#define EMB_ERR_BAD_MODE (-4)    /* mode is neither EMB_SUM nor EMB_MEAN */
-#define EMB_ERR_UNSUPPORTED (-5) /* per-sample weights together with EMB_MEAN */
+#define EMB_ERR_BAD_MODE (-4)    /* mode is not EMB_SUM, EMB_MEAN or EMB_MAX */
+#define EMB_ERR_UNSUPPORTED (-5) /* per-sample weights together with EMB_MEAN or EMB_MAX */
 #define EMB_ERR_LAUNCH (-6)      /* the HIP runtime refused the launch */
 #define EMB_ERR_BAD_SIZE (-7)    /* negative count, or a size beyond the supported range */
 #define EMB_ERR_ALIGNMENT (-8)   /* tables / out not 16-byte aligned */
@@ -71,7 +76,7 @@ typedef struct emb_bag_desc {
   int32_t num_tables;     /* T >= 1 */
   int32_t dim;            /* D >= 1 */
   int32_t table_dtype;    /* EMB_F32, EMB_F16, EMB_BF16 or EMB_U8ROW */
-  int32_t mode;           /* EMB_SUM or EMB_MEAN */
+  int32_t mode;           /* EMB_SUM, EMB_MEAN or EMB_MAX */
   int64_t batch;          /* B >= 0; B == 0 is a no-op that returns EMB_OK */
   int64_t num_lookups;    /* NL = offsets[T*B]: entries in indices (and in per_sample_weights) */
   int64_t out_ld;         /* leading dimension of out, in floats; 0 means T*D; must be >= T*D
@@ -92,7 +97,8 @@ typedef struct emb_bag_desc {
  *
  *   out[b*out_ld + t*D + d] = sum over j in [offsets[t*B+b], offsets[t*B+b+1]) of
  *                               w_j * table_t[indices[j]][d]            (w_j = 1 without weights)
- *   and that sum divided by the bag length in EMB_MEAN mode (0 for an empty bag).
+ *   and that sum divided by the bag length in EMB_MEAN mode (0 for an empty bag); in EMB_MAX
+ *   mode the maximum over the same j of table_t[indices[j]][d] instead (see EMB_MAX).
  *   Accumulation is in fp32; fp16 and bf16 rows are widened exactly first.
  *
  *   desc                HOST    shape, see above
@@ -139,7 +145,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
 typedef struct emb_bag_mixed_desc {
   int32_t num_tables;      /* T >= 1 */
   int32_t table_dtype;     /* EMB_F32, EMB_F16, EMB_BF16 or EMB_U8ROW (one type for all tables) */
-  int32_t mode;            /* EMB_SUM or EMB_MEAN */
+  int32_t mode;            /* EMB_SUM, EMB_MEAN or EMB_MAX */
   int32_t reserved;        /* 0 */
   int64_t batch;           /* B >= 0 */
   int64_t num_lookups;     /* NL = offsets[T*B] */

@@ -242,7 +242,7 @@ class Workload:
     B: int                      # batch (bags per table)
     pooling: Tuple              # ('fixed', L) | ('uniform', lo, hi) inclusive
     dists: Tuple[Tuple, ...]    # per table: ('uniform',) | ('zipf', alpha) | ('one_item',)
-    mode: str = "sum"           # 'sum' | 'mean'
+    mode: str = "sum"           # 'sum' | 'mean' | 'max'
     weighted: bool = False
     seed: int = 0x5EED0000
     kind: int = KIND_NORMAL
@@ -436,6 +436,8 @@ def workload(name: str) -> Workload:
     if name == "short":            # cfg2's tables, 0..8 lookups per bag (a ninth of the bags empty)
         return _homog("short", 26, 1_000_000, 64, "f32", 32768, ("uniform", 0, 8), ("uniform",),
                       seed_off=0x19)
+    if name == "cfg3_max":         # cfg3 with max pooling
+        return with_overrides(workload("cfg3"), name="cfg3_max", mode="max")
     if name == "cfg3_weighted":    # cfg3 with per-sample weights
         return with_overrides(workload("cfg3"), name="cfg3_weighted", weighted=True)
     if name == "cfg3_u8":          # cfg3's shape with quantised rows (dim 120 -> 128-byte rows)

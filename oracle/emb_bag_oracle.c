@@ -19,6 +19,9 @@
  *   - "mean" appears only in the name of the kernel the paper studies: mean = sum / bag length,
  *     and an empty bag gives 0.
  *   - per-sample weights are not in the paper: out = sum_j w_j * row_j, sum mode only.
+ *   - max pooling is not in the paper either (its kernel is the sum/mean one): out = max_j row_j
+ *     element by element, 0 for an empty bag; the maximum is an element of the table, so no
+ *     rounding is involved except in the dequantisation of quantised rows.
  *   - summation order is not fixed by the paper: this oracle adds in index order, in fp64.
  *
  * Arithmetic: every table element is widened exactly (fp32, IEEE half or bfloat16 -> fp64; a
@@ -117,7 +120,7 @@ void oracle_set_num_threads(int n) {
  *   dtype          0 = fp32 tables, 1 = fp16 tables (raw half bit patterns),
  *                  2 = bfloat16 tables (raw bit patterns),
  *                  3 = row-wise quantised tables: D uint8 codes + fp32 scale + fp32 bias per row
- *   mode           0 = sum, 1 = mean
+ *   mode           0 = sum, 1 = mean, 2 = max (bound = magnitude of the element that is the max)
  *   tables         arena [sum_t R_t, D], row-major ([sum_t R_t, D + 8] bytes for dtype 3)
  *   table_offsets  [T+1] first arena row of each table (so R_t = table_offsets[t+1]-table_offsets[t])
  *   indices        [NL] table-local row ids
@@ -131,7 +134,7 @@ int oracle_emb_bag(int32_t T, int64_t B, int32_t D, int32_t dtype, int32_t mode,
                    const void* tables, const int64_t* table_offsets, const int64_t* indices,
                    const int64_t* offsets, const float* weights, int64_t out_ld, double* ref,
                    double* bound) {
-  if (T < 1 || B < 0 || D < 1 || (dtype < 0 || dtype > 3) || (mode != 0 && mode != 1))
+  if (T < 1 || B < 0 || D < 1 || (dtype < 0 || dtype > 3) || (mode < 0 || mode > 2))
     return ORACLE_ERR_ARG;
   if (out_ld < (int64_t)T * D) return ORACLE_ERR_ARG;
   if (weights && mode != 0) return ORACLE_ERR_ARG;
@@ -166,6 +169,13 @@ int oracle_emb_bag(int32_t T, int64_t B, int32_t D, int32_t dtype, int32_t mode,
       for (int64_t j = s; j < e; ++j) {
         double ax;
         const double x = table_elem(tables, dtype, table_offsets[t] + indices[j], D, d, &ax);
+        if (mode == 2) {
+          if (j == s || x > acc) {
+            acc = x;
+            mag = ax;
+          }
+          continue;
+        }
         const double w = weights ? (double)weights[j] : 1.0;
         acc += w * x;
         mag += fabs(w) * ax;

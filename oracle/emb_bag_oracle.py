@@ -101,7 +101,7 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
     ld = out_ld if out_ld else T * D
     ref = np.zeros((B, ld), dtype=np.float64)
     bound = np.zeros((B, ld), dtype=np.float64)
-    rc = _load().oracle_emb_bag(T, B, D, dtype, {"sum": 0, "mean": 1}[mode], _ptr(tables),
+    rc = _load().oracle_emb_bag(T, B, D, dtype, {"sum": 0, "mean": 1, "max": 2}[mode], _ptr(tables),
                                 _ptr(table_offsets), _ptr(indices), _ptr(offsets),
                                 _ptr(weights), ld, _ptr(ref), _ptr(bound))
     if rc != 0:

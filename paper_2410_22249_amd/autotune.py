@@ -66,7 +66,7 @@ def _setup_wl(wl, n_batches: int):
                    for b in batches]
     edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16,
            "u8row": emb.EMB_U8ROW}[wl.dtype]
-    emode = emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM
+    emode = emb.MODES[wl.mode]
     hints = torch.zeros(wl.T, dtype=torch.uint8, device=dev)
     d0 = emb.make_desc(wl.T, wl.B, wl.D, edt, emode, batches[0].num_lookups, 0, max(wl.rows))
     emb.emb_bag_profile_reuse(d0, dev_batches[0][0], dev_batches[0][1], 4096, -1, None, None, hints)

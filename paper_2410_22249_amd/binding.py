@@ -16,7 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libembbag.so")
 
 EMB_F32, EMB_F16, EMB_BF16, EMB_U8ROW = 0, 1, 2, 3
-EMB_SUM, EMB_MEAN = 0, 1
+EMB_SUM, EMB_MEAN, EMB_MAX = 0, 1, 2
+MODES = {"sum": EMB_SUM, "mean": EMB_MEAN, "max": EMB_MAX}
 EMB_OK = 0
 
 EMB_HINT_DEFAULT, EMB_HINT_STREAMING = 0, 1

@@ -46,7 +46,7 @@ using namespace embbag;
 // tables of different widths: then table t is described by table_offsets[t] (its BYTE offset in
 // the arena) and out_offsets[t] (its first output column; its width is the difference to the next
 // entry), the lanes per row are chosen per wavefront, and rows are at most 1 KiB.
-template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool BUF>
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
@@ -56,7 +56,7 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
   constexpr bool MIXED = LPR == 0;
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;  // 2-byte elements
   constexpr bool QUANT = ELEM == EMB_U8ROW;                   // 1-byte codes + scale, bias
-  constexpr int NACC = AccCount<ELEM>::value;                 // fp32 accumulators per lane
+  constexpr int NACC = AccCount<ELEM, OP>::value;             // fp32 accumulators per lane
 
   const int lane = threadIdx.x & (kWaveSize - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -118,22 +118,21 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
       const_cast<char*>(tbase), 0, BUF ? (uint32_t)((uint64_t)R * row_bytes) : 0u, kBufWord3);
 
   float acc[NACC];
-#pragma unroll
-  for (int i = 0; i < NACC; ++i) acc[i] = 0.0f;
+  init_acc<ELEM, OP>(acc);
   // quantised rows: the lane of this lane's group whose segment ends with the row's scale and bias
   const int meta_lane = (lane & ~(lpr - 1)) + (int)(D_t >> 4);
 
   const bool streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
   if (streaming)
-    gather_bag<LPR, ELEM, DEPTH, WEIGHTED, BUF, true>(acc, indices, weights, s, e, R, row_bytes,
+    gather_bag<LPR, ELEM, DEPTH, OP, BUF, true>(acc, indices, weights, s, e, R, row_bytes,
                                                      tbase, rsrc, lane, g, col, lane_ok,
                                                      meta_lane, 6 - lpr_log2);
   else
-    gather_bag<LPR, ELEM, DEPTH, WEIGHTED, BUF, false>(acc, indices, weights, s, e, R, row_bytes,
+    gather_bag<LPR, ELEM, DEPTH, OP, BUF, false>(acc, indices, weights, s, e, R, row_bytes,
                                                       tbase, rsrc, lane, g, col, lane_ok,
                                                       meta_lane, 6 - lpr_log2);
 
-  finish_bag<LPR, ELEM>(acc, lpr, lane, lane_ok, col, D_t, e - s, p.mean != 0, out, p.out_ld, b,
+  finish_bag<LPR, ELEM, OP>(acc, lpr, lane, lane_ok, col, D_t, e - s, p.mean != 0, out, p.out_ld, b,
                         out_col);
 }
 
@@ -249,49 +248,64 @@ constexpr int64_t kStreamMaxAutoBags = 4;
 constexpr int64_t kStreamMinWaves = 1024;
 
 template <int LPR, int ELEM, int DEPTH>
-KernelFn pick_wb(bool weighted, bool buf) {
-  if (weighted)
-    return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, true, true>
-               : emb_bag_wave_kernel<LPR, ELEM, DEPTH, true, false>;
-  return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, false, true>
-             : emb_bag_wave_kernel<LPR, ELEM, DEPTH, false, false>;
+KernelFn pick_op(int op, bool buf) {
+  if (op == kOpWeighted)
+    return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpWeighted, true>
+               : emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpWeighted, false>;
+  if (op == kOpMax) {
+    if constexpr (DEPTH == 4 || DEPTH == 8)  // max pooling: two depths are enough
+      return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpMax, true>
+                 : emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpMax, false>;
+    else
+      return nullptr;
+  }
+  return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpSum, true>
+             : emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpSum, false>;
 }
 
 template <int LPR, int ELEM>
-KernelFn pick_depth(int depth, bool weighted, bool buf) {
-  if constexpr (LPR == 0)  // tables of different widths: two depths are enough
-    return depth <= 4 ? pick_wb<LPR, ELEM, 4>(weighted, buf) : pick_wb<LPR, ELEM, 8>(weighted, buf);
-  switch (depth) {
-    case 1: return pick_wb<LPR, ELEM, 1>(weighted, buf);
-    case 2: return pick_wb<LPR, ELEM, 2>(weighted, buf);
-    case 4: return pick_wb<LPR, ELEM, 4>(weighted, buf);
-    case 8: return pick_wb<LPR, ELEM, 8>(weighted, buf);
-    case 16: return pick_wb<LPR, ELEM, 16>(weighted, buf);
-    default: return nullptr;
+KernelFn pick_depth(int depth, int op, bool buf) {
+  if (LPR == 0 || op == kOpMax)  // tables of different widths, max pooling: depth 4 or 8
+    return depth <= 4 ? pick_op<LPR, ELEM, 4>(op, buf) : pick_op<LPR, ELEM, 8>(op, buf);
+  if constexpr (LPR != 0) {
+    switch (depth) {
+      case 1: return pick_op<LPR, ELEM, 1>(op, buf);
+      case 2: return pick_op<LPR, ELEM, 2>(op, buf);
+      case 4: return pick_op<LPR, ELEM, 4>(op, buf);
+      case 8: return pick_op<LPR, ELEM, 8>(op, buf);
+      case 16: return pick_op<LPR, ELEM, 16>(op, buf);
+      default: return nullptr;
+    }
   }
+  return nullptr;
 }
 
 template <int LPR>
-KernelFn pick_dtype(int elem, int depth, bool weighted, bool buf) {
+KernelFn pick_dtype(int elem, int depth, int op, bool buf) {
   switch (elem) {
-    case EMB_F32: return pick_depth<LPR, EMB_F32>(depth, weighted, buf);
-    case EMB_F16: return pick_depth<LPR, EMB_F16>(depth, weighted, buf);
-    case EMB_BF16: return pick_depth<LPR, EMB_BF16>(depth, weighted, buf);
-    case EMB_U8ROW: return pick_depth<LPR, EMB_U8ROW>(depth, weighted, buf);
+    case EMB_F32: return pick_depth<LPR, EMB_F32>(depth, op, buf);
+    case EMB_F16: return pick_depth<LPR, EMB_F16>(depth, op, buf);
+    case EMB_BF16: return pick_depth<LPR, EMB_BF16>(depth, op, buf);
+    case EMB_U8ROW: return pick_depth<LPR, EMB_U8ROW>(depth, op, buf);
     default: return nullptr;
   }
 }
 
-KernelFn pick_kernel(int lpr, int elem, int depth, bool weighted, bool buf) {
+KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf) {
   switch (lpr) {
-    case 0: return pick_dtype<0>(elem, depth, weighted, buf);
-    case 4: return pick_dtype<4>(elem, depth, weighted, buf);
-    case 8: return pick_dtype<8>(elem, depth, weighted, buf);
-    case 16: return pick_dtype<16>(elem, depth, weighted, buf);
-    case 32: return pick_dtype<32>(elem, depth, weighted, buf);
-    case 64: return pick_dtype<64>(elem, depth, weighted, buf);
+    case 0: return pick_dtype<0>(elem, depth, op, buf);
+    case 4: return pick_dtype<4>(elem, depth, op, buf);
+    case 8: return pick_dtype<8>(elem, depth, op, buf);
+    case 16: return pick_dtype<16>(elem, depth, op, buf);
+    case 32: return pick_dtype<32>(elem, depth, op, buf);
+    case 64: return pick_dtype<64>(elem, depth, op, buf);
     default: return nullptr;
   }
+}
+
+// The accumulate operation of a call: max pooling, or a sum with or without weights.
+int op_of(int mode, const float* weights) {
+  return mode == EMB_MAX ? kOpMax : (weights ? kOpWeighted : kOpSum);
 }
 
 int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
@@ -299,7 +313,7 @@ int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
   if (d->table_dtype != EMB_F32 && d->table_dtype != EMB_F16 && d->table_dtype != EMB_BF16 &&
       d->table_dtype != EMB_U8ROW)
     return EMB_ERR_BAD_DTYPE;
-  if (d->mode != EMB_SUM && d->mode != EMB_MEAN) return EMB_ERR_BAD_MODE;
+  if (d->mode != EMB_SUM && d->mode != EMB_MEAN && d->mode != EMB_MAX) return EMB_ERR_BAD_MODE;
   if (d->num_tables < 1 || d->dim < 1) return EMB_ERR_BAD_DIM;
   int64_t row_bytes = (int64_t)d->dim * (d->table_dtype == EMB_F32 ? 4 : 2);
   if (d->table_dtype == EMB_U8ROW) {
@@ -404,7 +418,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   const int rc = check_desc(desc, &row_bytes);
   if (rc != EMB_OK) return rc;
   const int64_t T = desc->num_tables, B = desc->batch, D = desc->dim;
-  if (per_sample_weights && desc->mode == EMB_MEAN) return EMB_ERR_UNSUPPORTED;
+  if (per_sample_weights && desc->mode != EMB_SUM) return EMB_ERR_UNSUPPORTED;
   const int64_t out_ld = desc->out_ld ? desc->out_ld : T * D;
   if (out_ld < T * D || out_ld % 4 != 0) return EMB_ERR_BAD_DIM;
   if (B == 0) return EMB_OK;
@@ -448,7 +462,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   // knows the average bag length, NL / (T * B), and nothing else about the lengths.
   const int groups = kWaveSize / lpr;
   const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
-  if (g_tuning.stream != 0 && slabs == 1 && buf &&
+  if (g_tuning.stream != 0 && slabs == 1 && buf && desc->mode != EMB_MAX &&
       (g_tuning.stream == 1 || avg_len < kStreamBelowRowLoads * groups)) {
     int64_t m = g_tuning.bags_per_group;
     if (m == 0) {
@@ -468,7 +482,8 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
       }
     }
   }
-  if (!fn) fn = pick_kernel(lpr, desc->table_dtype, depth, per_sample_weights != nullptr, buf);
+  if (!fn)
+    fn = pick_kernel(lpr, desc->table_dtype, depth, op_of(desc->mode, per_sample_weights), buf);
   return enqueue(fn, T, p, tables, table_offsets, indices, offsets, per_sample_weights,
                  desc->table_hints, nullptr, nullptr, false, out, stream);
 }
@@ -481,7 +496,8 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   if (desc->table_dtype != EMB_F32 && desc->table_dtype != EMB_F16 &&
       desc->table_dtype != EMB_BF16 && desc->table_dtype != EMB_U8ROW)
     return EMB_ERR_BAD_DTYPE;
-  if (desc->mode != EMB_SUM && desc->mode != EMB_MEAN) return EMB_ERR_BAD_MODE;
+  if (desc->mode != EMB_SUM && desc->mode != EMB_MEAN && desc->mode != EMB_MAX)
+    return EMB_ERR_BAD_MODE;
   if (desc->num_tables < 1 || !desc->dims) return desc->dims ? EMB_ERR_BAD_DIM : EMB_ERR_NULL_PTR;
   if (desc->batch < 0 || desc->num_lookups < 0 || desc->max_table_bytes < 0)
     return EMB_ERR_BAD_SIZE;
@@ -505,7 +521,7 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   }
   // more tables than the order holds: such a launch keeps the natural block order
   const bool too_many = widths_differ && T > kMaxOrdered;
-  if (per_sample_weights && desc->mode == EMB_MEAN) return EMB_ERR_UNSUPPORTED;
+  if (per_sample_weights && desc->mode != EMB_SUM) return EMB_ERR_UNSUPPORTED;
   const int64_t out_ld = desc->out_ld ? desc->out_ld : total_dim;
   if (out_ld < total_dim || out_ld % 4 != 0) return EMB_ERR_BAD_DIM;
   if (B == 0) return EMB_OK;
@@ -533,7 +549,7 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   p.D = 0;
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
-  return enqueue(pick_kernel(0, desc->table_dtype, depth, per_sample_weights != nullptr, buf), T, p,
+  return enqueue(pick_kernel(0, desc->table_dtype, depth, op_of(desc->mode, per_sample_weights), buf), T, p,
                  tables, table_byte_offsets, indices, offsets, per_sample_weights,
                  desc->table_hints, out_offsets,
                  widths_differ && !too_many ? row_units : nullptr, too_many, out, stream);

@@ -76,20 +76,46 @@ __device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
 
 __device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
 
-// fp32 accumulators a lane keeps for its 16-byte segment of the row: 4 fp32 elements, 8 fp16 /
-// bf16 elements, or 16 one-byte codes plus one accumulator for the sum of the row biases.
+// What a lookup does to the accumulator: plain sum, sum with per-sample weights, or maximum.
+constexpr int kOpSum = 0, kOpWeighted = 1, kOpMax = 2;
+
+// Elements of the output a lane owns (its 16-byte segment of the row): 4 fp32 elements, 8 fp16 /
+// bf16 elements, or 16 one-byte codes.
 template <int ELEM>
-struct AccCount {
-  static constexpr int value = ELEM == EMB_F32 ? 4 : (ELEM == EMB_U8ROW ? 17 : 8);
+struct OutCount {
+  static constexpr int value = ELEM == EMB_F32 ? 4 : (ELEM == EMB_U8ROW ? 16 : 8);
 };
 
-// acc += w * (one 16-byte segment of a row): 4 fp32 elements, 8 fp16 / bf16 elements widened
-// exactly to fp32, or 16 codes of a row-wise quantised row.  For the latter the row's scale and
-// bias sit in the last 8 bytes of the row, i.e. in words z and w of lane `meta_lane`'s segment;
-// acc[i] collects w * scale * code_i and acc[16] collects w * bias, added to every element at the
-// end of the bag (a lookup that fetched nothing has scale = bias = 0).
-template <int ELEM, bool WEIGHTED>
+// fp32 accumulators a lane keeps: one per element, plus one more for quantised rows (the sum of
+// the row biases) or for max pooling (the number of valid lookups seen).
+template <int ELEM, int OP = kOpSum>
+struct AccCount {
+  static constexpr int value = OutCount<ELEM>::value + ((ELEM == EMB_U8ROW || OP == kOpMax) ? 1 : 0);
+};
+
+template <int ELEM, int OP>
+__device__ __forceinline__ void init_acc(float* acc) {
+  constexpr int NOUT = OutCount<ELEM>::value;
+#pragma unroll
+  for (int i = 0; i < AccCount<ELEM, OP>::value; ++i)
+    acc[i] = (OP == kOpMax && i < NOUT) ? -__builtin_inff() : 0.0f;
+}
+
+// One 16-byte segment of a row into the accumulators: 4 fp32 elements, 8 fp16 / bf16 elements
+// widened exactly to fp32, or 16 codes of a row-wise quantised row.  For the latter the row's
+// scale and bias sit in the last 8 bytes of the row, i.e. in words z and w of lane `meta_lane`'s
+// segment.
+//   kOpSum / kOpWeighted: acc += w * element; for quantised rows acc[i] collects w * scale *
+//     code_i and acc[16] collects w * bias, added to every element at the end of the bag (a
+//     lookup that fetched nothing has scale = bias = 0).
+//   kOpMax: acc = max(acc, element) where w != 0 marks a valid lookup (an invalid one fetched
+//     zeros, which must not take part); the last accumulator counts the valid lookups.
+template <int ELEM, int OP>
 __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int meta_lane) {
+  constexpr bool WEIGHTED = OP == kOpWeighted;
+  constexpr bool MAXP = OP == kOpMax;
+  constexpr int NOUT = OutCount<ELEM>::value;
+  const float skip = -__builtin_inff();
   if constexpr (ELEM == EMB_U8ROW) {
     float scale = as_float((uint32_t)__shfl((int)r.z, meta_lane));
     float bias = as_float((uint32_t)__shfl((int)r.w, meta_lane));
@@ -103,10 +129,15 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int met
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const float code = (float)((u[i] >> (8 * k)) & 0xFFu);
-        acc[4 * i + k] = __builtin_fmaf(scale, code, acc[4 * i + k]);
+        if constexpr (MAXP) {
+          const float v = __builtin_fmaf(scale, code, bias);
+          acc[4 * i + k] = __builtin_fmaxf(acc[4 * i + k], w != 0.0f ? v : skip);
+        } else {
+          acc[4 * i + k] = __builtin_fmaf(scale, code, acc[4 * i + k]);
+        }
       }
     }
-    acc[16] += bias;
+    acc[16] += MAXP ? w : bias;
   } else if constexpr (ELEM != EMB_F32) {
     const uint32_t u[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
@@ -121,7 +152,10 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int met
         lo = as_float(u[i] << 16);
         hi = as_float(u[i] & 0xFFFF0000u);
       }
-      if constexpr (WEIGHTED) {
+      if constexpr (MAXP) {
+        acc[2 * i] = __builtin_fmaxf(acc[2 * i], w != 0.0f ? lo : skip);
+        acc[2 * i + 1] = __builtin_fmaxf(acc[2 * i + 1], w != 0.0f ? hi : skip);
+      } else if constexpr (WEIGHTED) {
         acc[2 * i] = __builtin_fmaf(w, lo, acc[2 * i]);
         acc[2 * i + 1] = __builtin_fmaf(w, hi, acc[2 * i + 1]);
       } else {
@@ -129,15 +163,19 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int met
         acc[2 * i + 1] += hi;
       }
     }
+    if constexpr (MAXP) acc[NOUT] += w;
   } else {
     const float x[4] = {as_float(r.x), as_float(r.y), as_float(r.z), as_float(r.w)};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if constexpr (WEIGHTED)
+      if constexpr (MAXP)
+        acc[i] = __builtin_fmaxf(acc[i], w != 0.0f ? x[i] : skip);
+      else if constexpr (WEIGHTED)
         acc[i] = __builtin_fmaf(w, x[i], acc[i]);
       else
         acc[i] += x[i];
     }
+    if constexpr (MAXP) acc[NOUT] += w;
   }
 }
 
@@ -145,13 +183,14 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int met
 // the rows into acc.  LPR is the number of lanes per row (0: decided per table at run time, then
 // 2^glog2 rows share a wave load).  NT selects the non-temporal cache policy for the row loads (tables whose
 // rows are not re-used within a batch), the default policy otherwise.
-template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool BUF, bool NT>
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, bool NT>
 __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict__ indices,
                                            const float* __restrict__ weights, int64_t s,
                                            int64_t e, int64_t R, uint32_t row_bytes,
                                            const char* tbase, __amdgpu_buffer_rsrc_t rsrc,
                                            int lane, int g, uint32_t col, bool lane_ok,
                                            int meta_lane, int glog2) {
+  constexpr bool WEIGHTED = OP == kOpWeighted;
   // log2 of the rows per wave load: a constant for a fixed LPR, a wave-uniform value for LPR == 0
   const int gl = LPR ? __builtin_ctz((unsigned)(kWaveSize / (LPR ? LPR : 1))) : glog2;
   constexpr int kAux = NT ? 2 : 0;  // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
@@ -181,14 +220,17 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
       for (int d = 0; d < DEPTH; ++d) {
         const int j = ((k0 + d) << gl) + g;  // lookup of this chunk served by this lane's group
         const bool take = (j < n) && lane_ok;
+        bool valid;  // this lane fetches a segment of a row that exists
         if constexpr (BUF) {
           uint32_t vo = (uint32_t)__shfl((int)voff, j & (kWaveSize - 1));
           vo = take ? vo : kBufSentinel;
+          valid = vo != kBufSentinel;
           r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
         } else {
           const int64_t ro = shfl64(roff, j & (kWaveSize - 1));
           u32x4 v = {0u, 0u, 0u, 0u};
-          if (take && ro >= 0) {
+          valid = take && ro >= 0;
+          if (valid) {
             const u32x4* src = reinterpret_cast<const u32x4*>(tbase + ro + col);
             v = NT ? __builtin_nontemporal_load(src) : *src;
           }
@@ -197,12 +239,14 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
         if constexpr (WEIGHTED) {
           const float ws = __shfl(w, j & (kWaveSize - 1));
           wj[d] = (j < n) ? ws : 0.0f;
+        } else if constexpr (OP == kOpMax) {
+          wj[d] = valid ? 1.0f : 0.0f;
         } else {
           wj[d] = 1.0f;
         }
       }
 #pragma unroll
-      for (int d = 0; d < DEPTH; ++d) accumulate<ELEM, WEIGHTED>(acc, r[d], wj[d], meta_lane);
+      for (int d = 0; d < DEPTH; ++d) accumulate<ELEM, OP>(acc, r[d], wj[d], meta_lane);
     }
   }
 
@@ -234,17 +278,19 @@ __device__ __forceinline__ bool decode_work(const KParams& p, uint32_t wave, boo
 
 // The end of a bag that all 64 lanes gathered together (gather_bag): combine the G = 64/lpr row
 // groups with a fixed xor butterfly (every lane ends with the same bits), add the summed biases
-// of quantised rows, divide by the bag length for the mean, and store the lane's elements of
-// bag row `b` at output column `out_col` with 16-byte non-temporal stores.
-template <int LPR, int ELEM>
+// of quantised rows, divide by the bag length for the mean (or, for max pooling, give 0 to a bag
+// without a valid lookup), and store the lane's elements of bag row `b` at output column
+// `out_col` with 16-byte non-temporal stores.
+template <int LPR, int ELEM, int OP>
 __device__ __forceinline__ void finish_bag(float* acc, int lpr, int lane, bool lane_ok,
                                            uint32_t col, uint32_t D_t, int64_t len, bool mean,
                                            float* __restrict__ out, int64_t out_ld, uint32_t b,
                                            int64_t out_col) {
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;
   constexpr bool QUANT = ELEM == EMB_U8ROW;
-  constexpr int NOUT = QUANT ? 16 : AccCount<ELEM>::value;
-  if constexpr (QUANT) {
+  constexpr bool MAXP = OP == kOpMax;
+  constexpr int NOUT = OutCount<ELEM>::value;
+  if constexpr (QUANT && !MAXP) {
 #pragma unroll
     for (int i = 0; i < NOUT; ++i) acc[i] += acc[16];
   }
@@ -252,10 +298,18 @@ __device__ __forceinline__ void finish_bag(float* acc, int lpr, int lane, bool l
   for (int m = kWaveSize / 2; m >= 4; m >>= 1) {
     if (m >= lpr) {  // wave-uniform; a compile-time constant unless LPR == 0
 #pragma unroll
-      for (int i = 0; i < NOUT; ++i) acc[i] += __shfl_xor(acc[i], m);
+      for (int i = 0; i < NOUT; ++i) {
+        const float other = __shfl_xor(acc[i], m);
+        acc[i] = MAXP ? __builtin_fmaxf(acc[i], other) : acc[i] + other;
+      }
+      if constexpr (MAXP) acc[NOUT] += __shfl_xor(acc[NOUT], m);
     }
   }
-  if (mean && len > 0) {
+  if constexpr (MAXP) {
+    const bool none = acc[NOUT] == 0.0f;  // empty bag, or no lookup named an existing row
+#pragma unroll
+    for (int i = 0; i < NOUT; ++i) acc[i] = none ? 0.0f : acc[i];
+  } else if (mean && len > 0) {
     const float fl = (float)len;
 #pragma unroll
     for (int i = 0; i < NOUT; ++i) acc[i] = acc[i] / fl;

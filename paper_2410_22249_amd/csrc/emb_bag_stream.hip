@@ -104,7 +104,7 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
       }
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
-        accumulate<ELEM, WEIGHTED>(acc, r[d], wj[d], meta_lane);
+        accumulate<ELEM, WEIGHTED ? kOpWeighted : kOpSum>(acc, r[d], wj[d], meta_lane);
         const bool flush = qbase + (uint32_t)(k0 + d) + 1u == next_end;  // this lookup ends a bag
         float v[NOUT];
 #pragma unroll
@@ -141,7 +141,8 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
   }
 }
 
-// One wavefront per G * M consecutive bags of one table (see the head of this file).
+// One wavefront per G * M consecutive bags of one table (see the head of this file).  Sum and
+// mean pooling; max pooling always takes the wave kernel.
 template <int LPR, int ELEM, int DEPTH, bool WEIGHTED>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
@@ -209,10 +210,10 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
       float acc[NACC];
 #pragma unroll
       for (int k = 0; k < NACC; ++k) acc[k] = 0.0f;
-      gather_bag<LPR, ELEM, 2, WEIGHTED, true, false>(acc, indices, weights, s, e, R, row_bytes,
+      gather_bag<LPR, ELEM, 2, WEIGHTED ? kOpWeighted : kOpSum, true, false>(acc, indices, weights, s, e, R, row_bytes,
                                                       tbase, rsrc, lane, g, col, lane_ok,
                                                       meta_lane, GL);
-      finish_bag<LPR, ELEM>(acc, LPR, lane, lane_ok, col, p.D, e - s, p.mean != 0, out, p.out_ld,
+      finish_bag<LPR, ELEM, kOpSum>(acc, LPR, lane, lane_ok, col, p.D, e - s, p.mean != 0, out, p.out_ld,
                             b0 + i, (int64_t)t * p.D);
     }
     return;

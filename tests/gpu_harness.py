@@ -75,7 +75,7 @@ def forward(arena: torch.Tensor, table_offsets: np.ndarray, indices, offsets, B:
     if out is None:
         out = torch.full((B, ld), fill, dtype=torch.float32, device=DEV)
     desc = emb.make_desc(T, B, D, EMB_DTYPE[arena.dtype],
-                         emb.EMB_MEAN if mode == "mean" else emb.EMB_SUM, nl, out_ld,
+                         emb.MODES[mode], nl, out_ld,
                          max_table_rows)
     emb.emb_bag_forward(desc, arena, toff, idx if nl else None, off, w, out)
     torch.cuda.synchronize()

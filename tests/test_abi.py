@@ -97,7 +97,7 @@ def test_host_side_argument_errors():
               num_lookups=10)
     assert fwd(None) == -1
     assert fwd(emb.make_desc(**{**ok, "table_dtype": 7})) == -3
-    assert fwd(emb.make_desc(**{**ok, "mode": 2})) == -4
+    assert fwd(emb.make_desc(**{**ok, "mode": 3})) == -4
     assert fwd(emb.make_desc(**{**ok, "num_tables": 0})) == -2
     assert fwd(emb.make_desc(**{**ok, "dim": 0})) == -2
     assert fwd(emb.make_desc(**{**ok, "dim": 6})) == -2                       # 24-byte rows
@@ -109,6 +109,7 @@ def test_host_side_argument_errors():
     assert fwd(emb.make_desc(**{**ok, "out_ld": 100})) == -2                  # < T*D
     assert fwd(emb.make_desc(**{**ok, "out_ld": 130})) == -2                  # not a multiple of 4
     assert fwd(emb.make_desc(**{**ok, "mode": emb.EMB_MEAN}), w=fake) == -5
+    assert fwd(emb.make_desc(**{**ok, "mode": emb.EMB_MAX}), w=fake) == -5
     assert fwd(emb.make_desc(**ok), tables=None) == -1
     assert fwd(emb.make_desc(**ok), out=None) == -1
     assert fwd(emb.make_desc(**ok), idx=None) == -1

@@ -23,7 +23,7 @@ def _run(wl, batch, arena, toff):
     w = to_dev(batch.weights)
     out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
     desc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16, "u8row": emb.EMB_U8ROW}[wl.dtype],
-                         emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, batch.num_lookups, 0,
+                         emb.MODES[wl.mode], batch.num_lookups, 0,
                          max(wl.rows))
     emb.emb_bag_forward(desc, arena, toff, idx, off, w, out)
     bad = torch.zeros(1, dtype=torch.int64, device=DEV)
@@ -52,7 +52,8 @@ def test_cfg1_whole_output(oracle):
 
 @pytest.mark.parametrize("name,nsample", [("cfg2", 2000), ("cfg3", 600), ("cfg4", 600),
                                           ("cfg5", 600), ("paper", 400), ("cfg3_weighted", 300),
-                                          ("cfg3_u8", 300), ("onehot", 3000), ("short", 3000)])
+                                          ("cfg3_u8", 300), ("onehot", 3000), ("short", 3000),
+                                          ("cfg3_max", 300)])
 def test_full_size_sampled_bags(oracle, name, nsample):
     print(f"\n[fullsize] {name}: generating", flush=True)
     wl = gen.workload(name)
@@ -87,7 +88,7 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     expect = np.array([1 if d[0] == "uniform" else 0 for d in wl.dists], dtype=np.uint8)
     assert np.array_equal(rh, expect), "uniform tables stream, skewed tables stay cached"
     hdesc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16, "u8row": emb.EMB_U8ROW}[wl.dtype],
-                          emb.EMB_MEAN if wl.mode == "mean" else emb.EMB_SUM, batch.num_lookups,
+                          emb.MODES[wl.mode], batch.num_lookups,
                           0, max(wl.rows), hints)
     emb.emb_bag_forward(hdesc, arena, toff, idx, off, w, out2)
     torch.cuda.synchronize()

@@ -24,7 +24,7 @@ def _forward(wl, arena, batch, mode="sum", weights=None, out_ld=0, hints=None, f
     ld = out_ld if out_ld else total
     out = torch.full((wl.B, ld), fill, dtype=torch.float32, device=DEV)
     desc = emb.make_mixed_desc(wl.dims, wl.B, EDT[wl.dtype],
-                               emb.EMB_MEAN if mode == "mean" else emb.EMB_SUM, batch.num_lookups,
+                               emb.MODES[mode], batch.num_lookups,
                                out_ld, int(np.diff(wl.table_byte_offsets()).max()), hints)
     emb.emb_bag_forward_mixed(desc, arena, to_dev(wl.table_byte_offsets()), to_dev(wl.out_offsets()),
                               to_dev(batch.indices) if batch.num_lookups else None,

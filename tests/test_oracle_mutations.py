@@ -44,6 +44,9 @@ MUTATIONS = {
     "half subnormal scale off by one": ("ldexp((double)frac, -24)", "ldexp((double)frac, -25)"),
     "half sign dropped": ("return sign ? -v : v;", "return v;"),
     "bfloat16 shifted one bit short": ("const uint32_t u = (uint32_t)h << 16;", "const uint32_t u = (uint32_t)h << 15;"),
+    "max keeps the smaller element": ("if (j == s || x > acc) {", "if (j == s || x < acc) {"),
+    "max starts from zero instead of the first element": ("if (j == s || x > acc) {", "if (x > acc) {"),
+    "max bound not taken from the selected element": ("            acc = x;\n            mag = ax;", "            acc = x;\n            mag += ax;"),
     "weights applied in mean mode only": ("const double w = weights ? (double)weights[j] : 1.0;",
                                           "const double w = (weights && mode == 1) ? (double)weights[j] : 1.0;"),
 }
@@ -64,6 +67,9 @@ PIN_FUNCS = [
     pins.test_bfloat16_widening_is_exact,
     pins.test_quantised_rows_brute_force,
     pins.test_quantised_rows_equal_their_dequantised_table,
+    pins.test_max_hand_worked,
+    lambda o: pins.test_max_brute_force(o, np.float32),
+    pins.test_max_invariants,
 ]
 
 

@@ -513,3 +513,105 @@ def test_mixed_widths_brute_force(oracle):
                 assert abs(ref[b, col + d] - float(a)) <= 8 * 2.0 ** -53 * float(m) + 1e-300
                 assert abs(bound[b, col + d] - float(m)) <= 8 * 2.0 ** -53 * float(m) + 1e-300
         col += dims[t]
+
+
+# ------------------------------------------------------------------------------------------
+# max pooling (not in the paper: the usual third mode of an embedding-bag operator)
+# ------------------------------------------------------------------------------------------
+def test_max_hand_worked(oracle):
+    """Values typed in.  All-negative bags show that the maximum does not start from zero."""
+    tables = np.array([[1, -2], [10, -20], [-100, 200],      # table 0
+                       [-1, -5], [-3, -7]], dtype=np.float32)  # table 1
+    toff = np.array([0, 3, 5], dtype=np.int64)
+    # bags (t,b): (0,0)=[2,0,2]  (0,1)=[]  (1,0)=[1]  (1,1)=[0,1,1,0]
+    idx = np.array([2, 0, 2, 1, 0, 1, 1, 0], dtype=np.int64)
+    offsets = np.array([0, 3, 3, 4, 8], dtype=np.int64)
+    ref, bound = oracle.emb_bag(tables, toff, idx, offsets, 2, "max")
+    assert ref.tolist() == [[1.0, 200.0, -3.0, -7.0], [0.0, 0.0, -1.0, -5.0]]
+    assert bound.tolist() == [[1.0, 200.0, 3.0, 7.0], [0.0, 0.0, 1.0, 5.0]]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_max_brute_force(oracle, dtype):
+    rng = np.random.default_rng(21)
+    T, rows, D, B = 3, [8, 5, 7], 4, 6
+    tables, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 5, dtype)
+    ref, bound = oracle.emb_bag(tables, toff, idx, offsets, B, "max")
+    for t in range(T):
+        for b in range(B):
+            lo, hi = int(offsets[t * B + b]), int(offsets[t * B + b + 1])
+            for d in range(D):
+                vals = [Fraction(float(tables[int(toff[t]) + int(idx[j]), d])) for j in range(lo, hi)]
+                want = max(vals) if vals else Fraction(0)
+                assert Fraction(ref[b, t * D + d]) == want             # a table element: exact
+                assert Fraction(bound[b, t * D + d]) == abs(want)
+
+
+def test_max_invariants(oracle):
+    rng = np.random.default_rng(22)
+    T, rows, D, B = 2, [30, 9], 8, 10
+    tables, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 12)
+    mx, _ = oracle.emb_bag(tables, toff, idx, offsets, B, "max")
+    mean, _ = oracle.emb_bag(tables, toff, idx, offsets, B, "mean")
+    assert np.all(mx >= mean - 1e-12)                      # a maximum is at least the average
+    # order inside a bag does not matter; duplicating a bag's lookups does not either
+    idx2, off2 = [], [0]
+    for g in range(T * B):
+        seg = idx[offsets[g]:offsets[g + 1]]
+        seg = np.concatenate([seg[::-1], seg])
+        idx2.append(seg)
+        off2.append(off2[-1] + len(seg))
+    mx2, _ = oracle.emb_bag(tables, toff, np.concatenate(idx2).astype(np.int64),
+                            np.array(off2, np.int64), B, "max")
+    assert np.array_equal(mx, mx2)
+    # one lookup per bag: the row itself; negated table: max(-x) = -min(x)
+    one = np.arange(T * B, dtype=np.int64) % 9
+    r1, _ = oracle.emb_bag(tables, toff, one, np.arange(T * B + 1, dtype=np.int64), B, "max")
+    for t in range(T):
+        for b in range(B):
+            assert np.array_equal(r1[b, t * D:(t + 1) * D],
+                                  tables[toff[t] + one[t * B + b]].astype(np.float64))
+    neg, _ = oracle.emb_bag(-tables, toff, idx, offsets, B, "max")
+    mn = np.zeros_like(mx)
+    for t in range(T):
+        for b in range(B):
+            seg = idx[offsets[t * B + b]:offsets[t * B + b + 1]]
+            if len(seg):
+                mn[b, t * D:(t + 1) * D] = tables[toff[t] + seg].astype(np.float64).min(axis=0)
+    assert np.array_equal(neg, -mn)
+    with pytest.raises(ValueError):                        # no weights with max pooling
+        oracle.emb_bag(tables, toff, idx, offsets, B, "max", weights=np.ones(len(idx), np.float32))
+
+
+def test_max_second_opinion_torch_cpu(oracle):
+    import torch
+    import torch.nn.functional as F
+    wl = gen.workload("small_f32_d64")
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    toff = wl.table_offsets()
+    ref, _ = oracle.emb_bag(arena, toff, batch.indices, batch.offsets, wl.B, "max")
+    for t in range(wl.T):
+        o = batch.offsets[t * wl.B:(t + 1) * wl.B + 1]
+        ix = torch.from_numpy(batch.indices[o[0]:o[-1]])
+        W = torch.from_numpy(arena[toff[t]:toff[t + 1]].astype(np.float64))
+        want = F.embedding_bag(ix, W, torch.from_numpy(o[:-1] - o[0]), mode="max").numpy()
+        assert np.array_equal(ref[:, t * wl.D:(t + 1) * wl.D], want)
+
+
+def test_max_of_quantised_rows_is_the_max_of_the_dequantised_table(oracle):
+    wl = gen.workload("small_u8_d120")
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    D = wl.D
+    scale = arena[:, D:D + 4].copy().view(np.float32).astype(np.float64)
+    bias = arena[:, D + 4:D + 8].copy().view(np.float32).astype(np.float64)
+    deq = scale * arena[:, :D].astype(np.float64) + bias
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "max")
+    toff = wl.table_offsets()
+    for t in range(wl.T):
+        for b in range(0, wl.B, 7):
+            seg = batch.indices[batch.offsets[t * wl.B + b]:batch.offsets[t * wl.B + b + 1]]
+            want = deq[toff[t] + seg].max(axis=0) if len(seg) else np.zeros(D)
+            assert np.allclose(ref[b, t * D:(t + 1) * D], want, rtol=1e-15, atol=0)
+    assert np.all(bound >= np.abs(ref) - 1e-12)
