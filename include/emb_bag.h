@@ -196,6 +196,52 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
                           int32_t* dup_count, int32_t* window_used, uint8_t* hints, void* stream);
 
 /*
+ * emb_bag_plan_forward / emb_bag_plan_forward_mixed - what the corresponding forward call would
+ * launch for this descriptor under the current tuning, without launching anything: which kernel
+ * (the paper's recipe of Sec. 7 picks a scheme per workload; this is where a caller sees the
+ * pick), the prefetch depth, the grid and the block order.  Pure host code: no device pointer is
+ * read, no HIP call is made, so it works on a machine without a GPU.
+ *
+ *   desc         HOST   as for the forward call (table_hints is only tested against NULL)
+ *   has_weights  non-zero if the forward call would pass per_sample_weights
+ *   plan         HOST   filled in; all zero for batch == 0
+ *   table_order  HOST   uint16 [min(T, 1024)] or NULL: the table at each position of the
+ *                       XCD-affine order (the identity unless plan->xcd_ordered)
+ *   Returns the status the forward call would return for the descriptor alone.
+ *
+ * Block order, when xcd_pieces > 0: workgroup g runs on XCD g % 8; with slot = g / 8,
+ * unit = (slot / blocks_per_piece) * 8 + g % 8 is piece unit % xcd_pieces of the table at
+ * position unit / xcd_pieces, and wavefront w of workgroup (slot % blocks_per_piece) of that
+ * piece is wavefront (unit % xcd_pieces) * waves_per_piece + (slot % blocks_per_piece) * 4 + w
+ * of the table if that number is below waves_per_piece within the piece and below
+ * waves_per_table overall (otherwise it has no work).  With xcd_pieces == 0 wavefront
+ * 4 * g + w of the grid is wavefront number 4 * g + w in table-major order.
+ */
+#define EMB_KERNEL_WAVE 0   /* one wavefront per bag (per 1-KiB column slab of it) */
+#define EMB_KERNEL_STREAM 1 /* short bags: a lane group streams consecutive bags */
+
+typedef struct emb_bag_plan {
+  int32_t kernel;            /* EMB_KERNEL_WAVE or EMB_KERNEL_STREAM */
+  int32_t lanes_per_row;     /* 4..64; 0 = chosen per table (different widths) */
+  int32_t depth;             /* row loads in flight per wavefront (per lane group: stream) */
+  int32_t buffer_addressing; /* 1 = 32-bit buffer offsets with hardware range check, 0 = 64-bit */
+  int32_t bags_per_group;    /* stream kernel: consecutive bags per lane group; else 0 */
+  int32_t xcd_pieces;        /* pieces per table in XCD-affine order; 0 = natural order */
+  int32_t xcd_ordered;       /* 1 = tables dealt to XCDs by width (see table_order) */
+  int32_t reserved;
+  int64_t grid_blocks;       /* 256-thread workgroups launched */
+  int64_t wavefronts;        /* wavefronts that have work */
+  int64_t waves_per_table;
+  int64_t waves_per_piece;   /* XCD-affine order only */
+  int64_t blocks_per_piece;  /* XCD-affine order only */
+} emb_bag_plan;
+
+int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, emb_bag_plan* plan,
+                         uint16_t* table_order);
+int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights,
+                               emb_bag_plan* plan, uint16_t* table_order);
+
+/*
  * emb_bag_set_tuning / emb_bag_get_tuning - process-wide launch tuning (the occupancy x
  * prefetch-depth search of paper Sec. 3.3, Sec. 4.2 and the recipe of Sec. 7, made a runtime
  * knob).  Keys (HOST strings):

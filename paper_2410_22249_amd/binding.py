@@ -22,8 +22,10 @@ EMB_OK = 0
 
 EMB_HINT_DEFAULT, EMB_HINT_STREAMING = 0, 1
 
-EXPORTS = ("emb_bag_forward", "emb_bag_forward_mixed", "emb_bag_validate", "emb_bag_profile_reuse", "emb_bag_set_tuning",
-           "emb_bag_get_tuning", "emb_bag_status_string", "emb_bag_version")
+EMB_KERNEL_WAVE, EMB_KERNEL_STREAM = 0, 1
+EXPORTS = ("emb_bag_forward", "emb_bag_forward_mixed", "emb_bag_plan_forward",
+           "emb_bag_plan_forward_mixed", "emb_bag_validate", "emb_bag_profile_reuse",
+           "emb_bag_set_tuning", "emb_bag_get_tuning", "emb_bag_status_string", "emb_bag_version")
 
 
 class emb_bag_desc(ctypes.Structure):
@@ -42,6 +44,19 @@ class emb_bag_mixed_desc(ctypes.Structure):
                 ("dims", ctypes.POINTER(ctypes.c_int32)), ("table_hints", ctypes.c_void_p)]
 
 
+class emb_bag_plan(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("lanes_per_row", ctypes.c_int32),
+                ("depth", ctypes.c_int32), ("buffer_addressing", ctypes.c_int32),
+                ("bags_per_group", ctypes.c_int32), ("xcd_pieces", ctypes.c_int32),
+                ("xcd_ordered", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("grid_blocks", ctypes.c_int64), ("wavefronts", ctypes.c_int64),
+                ("waves_per_table", ctypes.c_int64), ("waves_per_piece", ctypes.c_int64),
+                ("blocks_per_piece", ctypes.c_int64)]
+
+    def as_dict(self) -> dict:
+        return {name: int(getattr(self, name)) for name, _ in self._fields_ if name != "reserved"}
+
+
 class EmbBagError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -58,6 +73,12 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.emb_bag_forward.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, P, P, P, P, P]
     lib.emb_bag_forward_mixed.restype = ctypes.c_int
     lib.emb_bag_forward_mixed.argtypes = [ctypes.POINTER(emb_bag_mixed_desc), P, P, P, P, P, P, P, P]
+    lib.emb_bag_plan_forward.restype = ctypes.c_int
+    lib.emb_bag_plan_forward.argtypes = [ctypes.POINTER(emb_bag_desc), ctypes.c_int,
+                                         ctypes.POINTER(emb_bag_plan), P]
+    lib.emb_bag_plan_forward_mixed.restype = ctypes.c_int
+    lib.emb_bag_plan_forward_mixed.argtypes = [ctypes.POINTER(emb_bag_mixed_desc), ctypes.c_int,
+                                               ctypes.POINTER(emb_bag_plan), P]
     lib.emb_bag_validate.restype = ctypes.c_int
     lib.emb_bag_validate.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, P, P, P]
     lib.emb_bag_profile_reuse.restype = ctypes.c_int
@@ -146,6 +167,29 @@ def emb_bag_forward_mixed(desc: emb_bag_mixed_desc, tables: torch.Tensor,
                                     _ptr(per_sample_weights), _ptr(out), _stream_handle(stream))
     if rc != EMB_OK:
         raise EmbBagError(rc, "emb_bag_forward_mixed")
+
+
+def _plan(fn, where: str, desc, has_weights: bool, with_order: bool):
+    plan = emb_bag_plan()
+    n = min(int(desc.num_tables), 1024)
+    order = (ctypes.c_uint16 * max(n, 1))() if with_order else None
+    rc = fn(ctypes.byref(desc), int(bool(has_weights)), ctypes.byref(plan), order)
+    if rc != EMB_OK:
+        raise EmbBagError(rc, where)
+    return (plan, list(order)[:n]) if with_order else plan
+
+
+def emb_bag_plan_forward(desc: emb_bag_desc, has_weights: bool = False, with_order: bool = False):
+    """What emb_bag_forward would launch for `desc` under the current tuning (host only, no GPU
+    needed).  Returns the plan, or (plan, table order) with `with_order`."""
+    return _plan(_lib.emb_bag_plan_forward, "emb_bag_plan_forward", desc, has_weights, with_order)
+
+
+def emb_bag_plan_forward_mixed(desc: emb_bag_mixed_desc, has_weights: bool = False,
+                               with_order: bool = False):
+    """What emb_bag_forward_mixed would launch for `desc` (host only, no GPU needed)."""
+    return _plan(_lib.emb_bag_plan_forward_mixed, "emb_bag_plan_forward_mixed", desc, has_weights,
+                 with_order)
 
 
 def emb_bag_validate(desc: emb_bag_desc, table_offsets: torch.Tensor, indices: torch.Tensor,

@@ -303,11 +303,6 @@ KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf) {
   }
 }
 
-// The accumulate operation of a call: max pooling, or a sum with or without weights.
-int op_of(int mode, const float* weights) {
-  return mode == EMB_MAX ? kOpMax : (weights ? kOpWeighted : kOpSum);
-}
-
 int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
   if (!d) return EMB_ERR_NULL_PTR;
   if (d->table_dtype != EMB_F32 && d->table_dtype != EMB_F16 && d->table_dtype != EMB_BF16 &&
@@ -326,33 +321,38 @@ int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
   return EMB_OK;
 }
 
-// Choose the kernel instantiation, lay out the grid (natural or XCD-affine order), apply the
-// occupancy cap, and launch.  `p` holds the shape; the XCD fields are filled here.
-int enqueue(KernelFn fn, int64_t T, KParams p, const void* tables,
-            const int64_t* table_offsets, const int64_t* indices, const int64_t* offsets,
-            const float* weights, const uint8_t* table_hints, const int64_t* out_offsets,
-            const uint16_t* row_units, bool natural_order, float* out, void* stream) {
-  if (!fn) return EMB_ERR_BAD_TUNING;
-  const int64_t num_work = p.num_work;
-  const int64_t waves_per_table_i = p.wpt;
-  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = p.xcd_ordered = 0;
-  TableOrder order = {};  // only the first T entries are read, and only when xcd_ordered is set
+// Everything a forward call decides on the host before it launches: the kernel instantiation,
+// its parameters, the grid and the table order.  Filled by plan_uniform / plan_mixed (no HIP
+// calls, no device pointers), launched by `launch`, reported by emb_bag_plan_forward*.
+struct Launch {
+  KernelFn fn = nullptr;
+  KParams p = {};
+  TableOrder order = {};  // only the first T entries are read, and only when p.xcd_ordered is set
+  uint32_t blocks = 0;
+  int kernel = EMB_KERNEL_WAVE;
+  int lpr = 0;
+  int depth = 0;
+  bool buf = false;
+};
 
-  uint32_t blocks = (uint32_t)((num_work + kWavesPerBlock - 1) / kWavesPerBlock);
+// Lay out the grid: natural order, or the XCD-affine order described at KParams.  row_units
+// (16-byte segments per row of each table) is given only when tables differ in width.
+void plan_grid(int64_t T, const uint16_t* row_units, bool natural_order, Launch* L) {
+  KParams& p = L->p;
+  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = p.xcd_ordered = 0;
+  uint32_t blocks = (uint32_t)(((uint64_t)p.num_work + kWavesPerBlock - 1) / kWavesPerBlock);
   const bool remap = g_tuning.xcd_remap == 1 || (g_tuning.xcd_remap == -1 && blocks >= 4096);
   if (remap && blocks >= 64 && !natural_order) {
     // pieces per table: the smallest power of two that makes T * pieces a multiple of 8, so
     // that every XCD gets the same number of pieces and neighbouring XCDs share a table
     uint32_t pshift = 0;
     while (((uint64_t)T << pshift) % 8 != 0) ++pshift;
-    const uint64_t waves_per_table = (uint64_t)waves_per_table_i;
-    const uint64_t wpp = (waves_per_table + (1u << pshift) - 1) >> pshift;
+    const uint64_t wpp = ((uint64_t)p.wpt + (1u << pshift) - 1) >> pshift;
     const uint64_t bpp = (wpp + kWavesPerBlock - 1) / kWavesPerBlock;
     const uint64_t grid = ((uint64_t)T << pshift) * bpp;
-    // Tables of different widths (row_units[t] = 16-byte segments per row, given only when they
-    // differ): position q of the order runs on the XCD set q % sets.  Deal the tables out widest
-    // first, each to the set with the least work so far, so that every XCD ends up with about
-    // the same number of bytes.
+    // Tables of different widths: position q of the order runs on the XCD set q % sets.  Deal
+    // the tables out widest first, each to the set with the least work so far, so that every
+    // XCD ends up with about the same number of bytes.
     const uint32_t sets = 8u >> (pshift < 3 ? pshift : 3);
     const bool ok = grid <= 0x7FFFFFFFull;
     const bool ordered = ok && row_units && sets > 1;
@@ -371,7 +371,7 @@ int enqueue(KernelFn fn, int64_t T, KParams p, const void* tables,
         uint32_t best = sets;
         for (uint32_t c = 0; c < sets; ++c)
           if (taken[c] < per_set && (best == sets || load[c] < load[best])) best = c;
-        order.t[best + sets * taken[best]] = t;
+        L->order.t[best + sets * taken[best]] = t;
         ++taken[best];
         load[best] += row_units[t];
       }
@@ -384,49 +384,25 @@ int enqueue(KernelFn fn, int64_t T, KParams p, const void* tables,
       blocks = (uint32_t)grid;
     }
   }
-
-  // A cap on resident workgroups per CU is imposed through a dynamic LDS request that the
-  // kernel never touches: k workgroups fit when each asks for 1/k of the CU's LDS.
-  uint32_t lds = 0;
-  if (g_tuning.blocks_per_cu > 0) {
-    int dev = 0, lds_per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor,
-                              dev) != hipSuccess || lds_per_cu <= 0)
-      return EMB_ERR_LAUNCH;
-    lds = ((uint32_t)lds_per_cu / (uint32_t)g_tuning.blocks_per_cu) & ~1023u;
-    if (lds > 65536u &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return EMB_ERR_LAUNCH;
-  }
-
-  hipLaunchKernelGGL(fn, dim3(blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
-                     static_cast<const char*>(tables), table_offsets, indices, offsets, weights,
-                     table_hints, out_offsets, out, p, order);
-  return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
+  L->blocks = blocks;
 }
 
-}  // namespace
-
-extern "C" {
-
-int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t* table_offsets,
-                    const int64_t* indices, const int64_t* offsets,
-                    const float* per_sample_weights, float* out, void* stream) {
-  uint32_t row_bytes = 0;
-  const int rc = check_desc(desc, &row_bytes);
+// Descriptor checks of emb_bag_forward that need no pointer: shape, mode, weights, out_ld.
+int precheck_uniform(const emb_bag_desc* desc, bool weighted, uint32_t* row_bytes,
+                     int64_t* out_ld) {
+  const int rc = check_desc(desc, row_bytes);
   if (rc != EMB_OK) return rc;
-  const int64_t T = desc->num_tables, B = desc->batch, D = desc->dim;
-  if (per_sample_weights && desc->mode != EMB_SUM) return EMB_ERR_UNSUPPORTED;
-  const int64_t out_ld = desc->out_ld ? desc->out_ld : T * D;
-  if (out_ld < T * D || out_ld % 4 != 0) return EMB_ERR_BAD_DIM;
-  if (B == 0) return EMB_OK;
-  if (!tables || !table_offsets || !offsets || !out) return EMB_ERR_NULL_PTR;
-  if (desc->num_lookups > 0 && !indices) return EMB_ERR_NULL_PTR;
-  if ((reinterpret_cast<uintptr_t>(tables) | reinterpret_cast<uintptr_t>(out)) & 15)
-    return EMB_ERR_ALIGNMENT;
+  const int64_t T = desc->num_tables, D = desc->dim;
+  if (weighted && desc->mode != EMB_SUM) return EMB_ERR_UNSUPPORTED;
+  *out_ld = desc->out_ld ? desc->out_ld : T * D;
+  if (*out_ld < T * D || *out_ld % 4 != 0) return EMB_ERR_BAD_DIM;
+  return EMB_OK;
+}
 
+// The host-side decisions of emb_bag_forward for a checked descriptor with batch > 0.
+int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, int64_t out_ld,
+                 Launch* L) {
+  const int64_t T = desc->num_tables, B = desc->batch, D = desc->dim;
   const int64_t slabs = (row_bytes + kSlabBytes - 1) / kSlabBytes;
   const int64_t num_work = T * B * slabs;
   if (B > 0x7FFFFFFF || num_work > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
@@ -443,7 +419,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   int depth = (int)g_tuning.depth;
   if (depth == 0) depth = (desc->table_dtype == EMB_F32 && row_bytes >= 512) ? 8 : 4;
 
-  KParams p;
+  KParams& p = L->p;
   p.num_lookups = desc->num_lookups;
   p.out_ld = out_ld;
   p.max_rows = desc->max_table_rows;
@@ -456,7 +432,11 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
   p.bags_per_group = 0;
-  KernelFn fn = nullptr;
+  L->fn = nullptr;
+  L->kernel = EMB_KERNEL_WAVE;
+  L->lpr = lpr;
+  L->depth = depth;
+  L->buf = buf;
 
   // Short bags: a lane group streams several consecutive bags (emb_bag_stream.hip).  The host
   // knows the average bag length, NL / (T * B), and nothing else about the lengths.
@@ -474,24 +454,30 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
     if (m < 1) m = 1;
     // the wavefront's output rows are addressed through one buffer with 32-bit offsets
     if ((uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u <= kBufMaxBytes) {
-      fn = pick_stream_kernel(lpr, desc->table_dtype, depth, per_sample_weights != nullptr);
-      if (fn) {
+      L->fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted);
+      if (L->fn) {
+        L->kernel = EMB_KERNEL_STREAM;
+        L->depth = depth <= 4 || lpr < 8 ? 4 : 8;  // the depths that kernel is built with
         p.bags_per_group = (uint32_t)m;
         p.wpt = (uint32_t)((B + groups * m - 1) / (groups * m));
         p.num_work = (uint32_t)(T * p.wpt);
       }
     }
   }
-  if (!fn)
-    fn = pick_kernel(lpr, desc->table_dtype, depth, op_of(desc->mode, per_sample_weights), buf);
-  return enqueue(fn, T, p, tables, table_offsets, indices, offsets, per_sample_weights,
-                 desc->table_hints, nullptr, nullptr, false, out, stream);
+  if (!L->fn) {
+    const int op = desc->mode == EMB_MAX ? kOpMax : (weighted ? kOpWeighted : kOpSum);
+    if (op == kOpMax) L->depth = depth <= 4 ? 4 : 8;
+    L->fn = pick_kernel(lpr, desc->table_dtype, depth, op, buf);
+  }
+  if (!L->fn) return EMB_ERR_BAD_TUNING;
+  plan_grid(T, nullptr, false, L);
+  return EMB_OK;
 }
 
-int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
-                          const int64_t* table_byte_offsets, const int64_t* out_offsets,
-                          const int64_t* indices, const int64_t* offsets,
-                          const float* per_sample_weights, float* out, void* stream) {
+// Descriptor checks of emb_bag_forward_mixed that need no device pointer; also the widest row
+// and the total width.
+int precheck_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t* max_row_bytes,
+                   int64_t* out_ld) {
   if (!desc) return EMB_ERR_NULL_PTR;
   if (desc->table_dtype != EMB_F32 && desc->table_dtype != EMB_F16 &&
       desc->table_dtype != EMB_BF16 && desc->table_dtype != EMB_U8ROW)
@@ -501,42 +487,46 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   if (desc->num_tables < 1 || !desc->dims) return desc->dims ? EMB_ERR_BAD_DIM : EMB_ERR_NULL_PTR;
   if (desc->batch < 0 || desc->num_lookups < 0 || desc->max_table_bytes < 0)
     return EMB_ERR_BAD_SIZE;
-  const int64_t T = desc->num_tables, B = desc->batch;
   int64_t total_dim = 0;
-  uint32_t max_row_bytes = 0;
-  uint16_t row_units[kMaxOrdered];  // 16-byte segments per row, for the XCD-affine table order
-  bool widths_differ = false;
-  for (int64_t t = 0; t < T; ++t) {
+  *max_row_bytes = 0;
+  for (int64_t t = 0; t < desc->num_tables; ++t) {
     const int64_t d = desc->dims[t];
     if (d < 1) return EMB_ERR_BAD_DIM;
     const int64_t rb = desc->table_dtype == EMB_U8ROW ? d + 8
                                                        : d * (desc->table_dtype == EMB_F32 ? 4 : 2);
     if (rb % 16 != 0 || rb > kSlabBytes) return EMB_ERR_BAD_DIM;
-    if (rb > max_row_bytes) max_row_bytes = (uint32_t)rb;
-    if (t < kMaxOrdered) row_units[t] = (uint16_t)(rb / 16);
-    if (rb != (desc->table_dtype == EMB_U8ROW ? desc->dims[0] + 8
-                                              : desc->dims[0] * (desc->table_dtype == EMB_F32 ? 4 : 2)))
-      widths_differ = true;
+    if (rb > *max_row_bytes) *max_row_bytes = (uint32_t)rb;
     total_dim += d;
+  }
+  if (weighted && desc->mode != EMB_SUM) return EMB_ERR_UNSUPPORTED;
+  *out_ld = desc->out_ld ? desc->out_ld : total_dim;
+  if (*out_ld < total_dim || *out_ld % 4 != 0) return EMB_ERR_BAD_DIM;
+  return EMB_OK;
+}
+
+// The host-side decisions of emb_bag_forward_mixed for a checked descriptor with batch > 0.
+int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_bytes,
+               int64_t out_ld, Launch* L) {
+  const int64_t T = desc->num_tables, B = desc->batch;
+  if (B > 0x7FFFFFFF || T * B > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
+  const int elem_bytes = desc->table_dtype == EMB_F32 ? 4 : 2;
+  uint16_t row_units[kMaxOrdered];  // 16-byte segments per row, for the XCD-affine table order
+  bool widths_differ = false;
+  for (int64_t t = 0; t < T; ++t) {
+    const int64_t d = desc->dims[t];
+    const int64_t rb = desc->table_dtype == EMB_U8ROW ? d + 8 : d * elem_bytes;
+    if (t < kMaxOrdered) row_units[t] = (uint16_t)(rb / 16);
+    if (d != desc->dims[0]) widths_differ = true;
   }
   // more tables than the order holds: such a launch keeps the natural block order
   const bool too_many = widths_differ && T > kMaxOrdered;
-  if (per_sample_weights && desc->mode != EMB_SUM) return EMB_ERR_UNSUPPORTED;
-  const int64_t out_ld = desc->out_ld ? desc->out_ld : total_dim;
-  if (out_ld < total_dim || out_ld % 4 != 0) return EMB_ERR_BAD_DIM;
-  if (B == 0) return EMB_OK;
-  if (!tables || !table_byte_offsets || !out_offsets || !offsets || !out) return EMB_ERR_NULL_PTR;
-  if (desc->num_lookups > 0 && !indices) return EMB_ERR_NULL_PTR;
-  if ((reinterpret_cast<uintptr_t>(tables) | reinterpret_cast<uintptr_t>(out)) & 15)
-    return EMB_ERR_ALIGNMENT;
-  if (B > 0x7FFFFFFF || T * B > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
 
   bool buf = desc->max_table_bytes > 0 && (uint64_t)desc->max_table_bytes <= kBufMaxBytes;
   if (g_tuning.addressing == 1) buf = false;
   int depth = (int)g_tuning.depth;
   if (depth == 0) depth = (desc->table_dtype == EMB_F32 && max_row_bytes >= 512) ? 8 : 4;
 
-  KParams p;
+  KParams& p = L->p;
   p.num_lookups = desc->num_lookups;
   p.out_ld = out_ld;
   p.max_rows = 0;
@@ -549,10 +539,135 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   p.D = 0;
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
-  return enqueue(pick_kernel(0, desc->table_dtype, depth, op_of(desc->mode, per_sample_weights), buf), T, p,
-                 tables, table_byte_offsets, indices, offsets, per_sample_weights,
-                 desc->table_hints, out_offsets,
-                 widths_differ && !too_many ? row_units : nullptr, too_many, out, stream);
+  L->kernel = EMB_KERNEL_WAVE;
+  L->lpr = 0;
+  L->depth = depth <= 4 ? 4 : 8;  // the depths the mixed-width kernels are built with
+  L->buf = buf;
+  const int op = desc->mode == EMB_MAX ? kOpMax : (weighted ? kOpWeighted : kOpSum);
+  L->fn = pick_kernel(0, desc->table_dtype, depth, op, buf);
+  if (!L->fn) return EMB_ERR_BAD_TUNING;
+  plan_grid(T, widths_differ && !too_many ? row_units : nullptr, too_many, L);
+  return EMB_OK;
+}
+
+// Apply the occupancy cap and launch what was planned.
+int launch(const Launch& L, const void* tables, const int64_t* table_offsets,
+           const int64_t* indices, const int64_t* offsets, const float* weights,
+           const uint8_t* table_hints, const int64_t* out_offsets, float* out, void* stream) {
+  // A cap on resident workgroups per CU is imposed through a dynamic LDS request that the
+  // kernel never touches: k workgroups fit when each asks for 1/k of the CU's LDS.
+  uint32_t lds = 0;
+  if (g_tuning.blocks_per_cu > 0) {
+    int dev = 0, lds_per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor,
+                              dev) != hipSuccess || lds_per_cu <= 0)
+      return EMB_ERR_LAUNCH;
+    lds = ((uint32_t)lds_per_cu / (uint32_t)g_tuning.blocks_per_cu) & ~1023u;
+    if (lds > 65536u &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(L.fn),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return EMB_ERR_LAUNCH;
+  }
+  hipLaunchKernelGGL(L.fn, dim3(L.blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
+                     static_cast<const char*>(tables), table_offsets, indices, offsets, weights,
+                     table_hints, out_offsets, out, L.p, L.order);
+  return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
+}
+
+// What emb_bag_plan_forward* report about a planned launch.
+void report(const Launch& L, int64_t T, emb_bag_plan* plan, uint16_t* table_order) {
+  plan->kernel = L.kernel;
+  plan->lanes_per_row = L.lpr;
+  plan->depth = L.depth;
+  plan->buffer_addressing = L.buf ? 1 : 0;
+  plan->bags_per_group = (int32_t)L.p.bags_per_group;
+  plan->xcd_pieces = L.p.xcd_bpp ? (int32_t)(1u << L.p.xcd_pshift) : 0;
+  plan->xcd_ordered = (int32_t)L.p.xcd_ordered;
+  plan->reserved = 0;
+  plan->grid_blocks = L.blocks;
+  plan->wavefronts = L.p.num_work;
+  plan->waves_per_table = L.p.wpt;
+  plan->waves_per_piece = L.p.xcd_wpp;
+  plan->blocks_per_piece = L.p.xcd_bpp;
+  if (table_order)
+    for (int64_t t = 0; t < T && t < kMaxOrdered; ++t)
+      table_order[t] = L.p.xcd_ordered ? L.order.t[t] : (uint16_t)t;
+}
+
+}  // namespace
+
+extern "C" {
+
+int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t* table_offsets,
+                    const int64_t* indices, const int64_t* offsets,
+                    const float* per_sample_weights, float* out, void* stream) {
+  uint32_t row_bytes = 0;
+  int64_t out_ld = 0;
+  int rc = precheck_uniform(desc, per_sample_weights != nullptr, &row_bytes, &out_ld);
+  if (rc != EMB_OK) return rc;
+  if (desc->batch == 0) return EMB_OK;
+  if (!tables || !table_offsets || !offsets || !out) return EMB_ERR_NULL_PTR;
+  if (desc->num_lookups > 0 && !indices) return EMB_ERR_NULL_PTR;
+  if ((reinterpret_cast<uintptr_t>(tables) | reinterpret_cast<uintptr_t>(out)) & 15)
+    return EMB_ERR_ALIGNMENT;
+  Launch L;
+  rc = plan_uniform(desc, per_sample_weights != nullptr, row_bytes, out_ld, &L);
+  if (rc != EMB_OK) return rc;
+  return launch(L, tables, table_offsets, indices, offsets, per_sample_weights, desc->table_hints,
+                nullptr, out, stream);
+}
+
+int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
+                          const int64_t* table_byte_offsets, const int64_t* out_offsets,
+                          const int64_t* indices, const int64_t* offsets,
+                          const float* per_sample_weights, float* out, void* stream) {
+  uint32_t max_row_bytes = 0;
+  int64_t out_ld = 0;
+  int rc = precheck_mixed(desc, per_sample_weights != nullptr, &max_row_bytes, &out_ld);
+  if (rc != EMB_OK) return rc;
+  if (desc->batch == 0) return EMB_OK;
+  if (!tables || !table_byte_offsets || !out_offsets || !offsets || !out) return EMB_ERR_NULL_PTR;
+  if (desc->num_lookups > 0 && !indices) return EMB_ERR_NULL_PTR;
+  if ((reinterpret_cast<uintptr_t>(tables) | reinterpret_cast<uintptr_t>(out)) & 15)
+    return EMB_ERR_ALIGNMENT;
+  Launch L;
+  rc = plan_mixed(desc, per_sample_weights != nullptr, max_row_bytes, out_ld, &L);
+  if (rc != EMB_OK) return rc;
+  return launch(L, tables, table_byte_offsets, indices, offsets, per_sample_weights,
+                desc->table_hints, out_offsets, out, stream);
+}
+
+int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, emb_bag_plan* plan,
+                         uint16_t* table_order) {
+  if (!plan) return EMB_ERR_NULL_PTR;
+  memset(plan, 0, sizeof *plan);
+  uint32_t row_bytes = 0;
+  int64_t out_ld = 0;
+  int rc = precheck_uniform(desc, has_weights != 0, &row_bytes, &out_ld);
+  if (rc != EMB_OK) return rc;
+  if (desc->batch == 0) return EMB_OK;
+  Launch L;
+  rc = plan_uniform(desc, has_weights != 0, row_bytes, out_ld, &L);
+  if (rc != EMB_OK) return rc;
+  report(L, desc->num_tables, plan, table_order);
+  return EMB_OK;
+}
+
+int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights,
+                               emb_bag_plan* plan, uint16_t* table_order) {
+  if (!plan) return EMB_ERR_NULL_PTR;
+  memset(plan, 0, sizeof *plan);
+  uint32_t max_row_bytes = 0;
+  int64_t out_ld = 0;
+  int rc = precheck_mixed(desc, has_weights != 0, &max_row_bytes, &out_ld);
+  if (rc != EMB_OK) return rc;
+  if (desc->batch == 0) return EMB_OK;
+  Launch L;
+  rc = plan_mixed(desc, has_weights != 0, max_row_bytes, out_ld, &L);
+  if (rc != EMB_OK) return rc;
+  report(L, desc->num_tables, plan, table_order);
+  return EMB_OK;
 }
 
 int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,

@@ -9,6 +9,7 @@ import torch
 
 import paper_2410_22249_amd as emb
 from inputgen import gen
+from tuning_ctx import tuning  # noqa: F401  (re-exported for the GPU tests)
 
 DEV = "cuda:0"
 
@@ -102,20 +103,3 @@ def assert_close_to_oracle(got: np.ndarray, ref: np.ndarray, bound: np.ndarray, 
     return float(np.max(err[nz] / bound[nz])) if nz.any() else 0.0
 
 
-class tuning:
-    """Context manager: set tuning keys, restore the previous values on exit."""
-
-    def __init__(self, **kw):
-        self.kw = kw
-        self.old = {}
-
-    def __enter__(self):
-        for k, v in self.kw.items():
-            self.old[k] = emb.emb_bag_get_tuning(k)
-            emb.emb_bag_set_tuning(k, v)
-        return self
-
-    def __exit__(self, *exc):
-        for k, v in self.old.items():
-            emb.emb_bag_set_tuning(k, v)
-        return False

@@ -1,0 +1,184 @@
+"""Host logic of the forward calls, observed through emb_bag_plan_forward* (no GPU needed): which
+kernel is chosen, with which depth and group size, and how the grid maps workgroups to (table,
+wavefront) - simulated here from the plan, following the description in include/emb_bag.h."""
+import numpy as np
+import pytest
+
+import paper_2410_22249_amd as emb
+from tuning_ctx import tuning
+
+
+def _plan(T, B, D, L, dtype=emb.EMB_F32, mode=emb.EMB_SUM, rows=1_000_000, weights=False, order=False):
+    desc = emb.make_desc(T, B, D, dtype, mode, int(T * B * L), 0, rows)
+    return emb.emb_bag_plan_forward(desc, weights, order)
+
+
+def test_plan_of_the_benchmark_configurations():
+    p = _plan(60, 4096, 128, 80, rows=4_000_000).as_dict()           # cfg3
+    assert p["kernel"] == emb.EMB_KERNEL_WAVE and p["lanes_per_row"] == 32 and p["depth"] == 8
+    assert p["buffer_addressing"] == 1 and p["wavefronts"] == 60 * 4096
+    assert p["xcd_pieces"] == 2 and p["grid_blocks"] == 60 * 2 * 512
+    p = _plan(26, 2048, 64, 20.5).as_dict()                          # cfg2: average 20.5 >= 12
+    assert p["kernel"] == emb.EMB_KERNEL_WAVE and p["lanes_per_row"] == 16 and p["depth"] == 4
+    p = _plan(8, 256, 64, 20, rows=100_000).as_dict()                # cfg1: small launch
+    assert p["xcd_pieces"] == 0 and p["grid_blocks"] == 8 * 256 // 4
+    p = _plan(100, 8192, 256, 50.5, dtype=emb.EMB_F16, rows=2_000_000).as_dict()   # cfg5
+    assert p["kernel"] == emb.EMB_KERNEL_WAVE and p["lanes_per_row"] == 32 and p["depth"] == 4
+
+
+@pytest.mark.parametrize("D,threshold", [(32, 24), (64, 12), (128, 6), (256, 3)])
+def test_stream_kernel_threshold_is_three_row_loads_per_bag(D, threshold):
+    B = 40_000
+    below = _plan(26, B, D, threshold - 0.01)
+    at = _plan(26, B, D, threshold)
+    assert below.kernel == emb.EMB_KERNEL_STREAM and at.kernel == emb.EMB_KERNEL_WAVE
+    assert below.bags_per_group >= 1 and at.bags_per_group == 0
+    # what rules the stream kernel out whatever the bag length
+    assert _plan(26, B, D, 1, mode=emb.EMB_MAX).kernel == emb.EMB_KERNEL_WAVE
+    assert _plan(26, B, D, 1, rows=0).kernel == emb.EMB_KERNEL_WAVE             # no row bound: 64-bit
+    assert _plan(26, B, D, 1, rows=1 << 40).buffer_addressing == 0
+    with tuning(addressing=1):
+        assert _plan(26, B, D, 1).kernel == emb.EMB_KERNEL_WAVE
+    with tuning(stream=0):
+        assert _plan(26, B, D, 1).kernel == emb.EMB_KERNEL_WAVE
+    with tuning(stream=1):
+        assert _plan(26, B, D, 500).kernel == emb.EMB_KERNEL_STREAM
+    assert _plan(26, B, 320, 1).kernel == emb.EMB_KERNEL_WAVE                   # rows above 1 KiB
+
+
+def test_bags_per_group_rule():
+    big = 200_000
+    assert _plan(26, big, 64, 1).bags_per_group == 4
+    assert _plan(26, big, 64, 2).bags_per_group == 2
+    assert _plan(26, big, 64, 3).bags_per_group == 1
+    assert _plan(26, big, 64, 8).bags_per_group == 1
+    assert _plan(26, big, 4, 1).bags_per_group == 3           # 4 lanes per row hold 4 bag bounds
+    # a launch that would fall below 1024 wavefronts halves the group instead
+    p = _plan(2, 3000, 64, 1)
+    assert p.bags_per_group in (1, 2) and p.wavefronts >= 2 * 3000 // (4 * 2)
+    with tuning(stream=1, bags_per_group=63):
+        assert _plan(26, big, 64, 30).bags_per_group == 15    # capped at lanes per row - 1
+        assert _plan(26, big, 256, 30).bags_per_group == 63
+    # waves: ceil(B / (groups * M)) per table
+    p = _plan(26, 1001, 64, 1)
+    g = 64 // p.lanes_per_row
+    assert p.waves_per_table == -(-1001 // (g * p.bags_per_group))
+    assert p.wavefronts == 26 * p.waves_per_table
+
+
+def test_depth_rules():
+    assert _plan(4, 5000, 128, 80).depth == 8                 # fp32 rows of 512 B and more
+    assert _plan(4, 5000, 64, 80).depth == 4
+    assert _plan(4, 5000, 256, 80, dtype=emb.EMB_F16).depth == 4
+    with tuning(depth=16):
+        assert _plan(4, 5000, 64, 80).depth == 16
+        assert _plan(4, 5000, 64, 80, mode=emb.EMB_MAX).depth == 8     # max pooling: 4 or 8
+        assert _plan(4, 5000, 64, 1).depth == 8                        # stream kernel: 4 or 8
+        assert _plan(4, 5000, 4, 1).depth == 4                         # ... and at most lanes per row
+    with tuning(depth=1):
+        assert _plan(4, 5000, 64, 80).depth == 1
+        assert _plan(4, 5000, 64, 80, mode=emb.EMB_MAX).depth == 4
+
+
+def test_plan_reports_descriptor_errors_like_forward():
+    def status(**kw):
+        base = dict(num_tables=2, batch=4, dim=64, table_dtype=emb.EMB_F32, mode=emb.EMB_SUM,
+                    num_lookups=10)
+        try:
+            emb.emb_bag_plan_forward(emb.make_desc(**{**base, **kw}), kw.pop("_w", False))
+        except emb.EmbBagError as ex:
+            return ex.status
+        return 0
+    assert status() == 0 and status(table_dtype=9) == -3 and status(mode=3) == -4
+    assert status(dim=6) == -2 and status(out_ld=100) == -2 and status(batch=-1) == -7
+    plan = emb.emb_bag_plan_forward(emb.make_desc(2, 0, 64, emb.EMB_F32, emb.EMB_SUM, 0))
+    assert all(v == 0 for v in plan.as_dict().values())                # batch 0: nothing to launch
+    with pytest.raises(emb.EmbBagError):
+        emb.emb_bag_plan_forward(emb.make_desc(2, 4, 64, emb.EMB_F32, emb.EMB_MEAN, 10), True)
+    with tuning(depth=16, stream=0):                                   # no such mixed kernel? mapped
+        m = emb.make_mixed_desc([64, 32], 4, emb.EMB_F32, emb.EMB_SUM, 10, 0, 1 << 20)
+        assert emb.emb_bag_plan_forward_mixed(m).depth == 8
+
+
+def _simulate(plan, T, order=None):
+    """(table, wavefront-in-table) of every wavefront of the grid that has work, and the XCD it
+    runs on, from the fields of the plan alone."""
+    p = plan.as_dict()
+    g = np.arange(p["grid_blocks"], dtype=np.int64)
+    w = np.arange(4, dtype=np.int64)
+    if p["xcd_pieces"] == 0:
+        n = (g[:, None] * 4 + w[None, :]).ravel()
+        keep = n < p["wavefronts"]
+        n = n[keep]
+        return n // p["waves_per_table"], n % p["waves_per_table"], np.repeat(g % 8, 4)[keep]
+    xcd, slot = g % 8, g // 8
+    unit = (slot // p["blocks_per_piece"]) * 8 + xcd
+    piece, pos = unit % p["xcd_pieces"], unit // p["xcd_pieces"]
+    in_piece = ((slot % p["blocks_per_piece"]) * 4)[:, None] + w[None, :]
+    in_table = piece[:, None] * p["waves_per_piece"] + in_piece
+    keep = (in_piece < p["waves_per_piece"]) & (in_table < p["waves_per_table"])
+    assert pos.max() < T
+    table = np.asarray(order, dtype=np.int64)[pos] if order is not None else pos
+    return (np.broadcast_to(table[:, None], keep.shape)[keep], in_table[keep],
+            np.broadcast_to(xcd[:, None], keep.shape)[keep])
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 4, 5, 7, 8, 12, 13, 16, 26, 60, 100, 250])
+@pytest.mark.parametrize("B,L", [(1000, 30), (4097, 30), (333, 1), (70_001, 1)])
+def test_every_wavefront_of_every_table_is_launched_exactly_once(T, B, L):
+    with tuning(xcd_remap=1):
+        plan = _plan(T, B, 64, L)
+    if -(-plan.wavefronts // 4) >= 64:      # smaller launches keep the natural order
+        assert plan.xcd_pieces in (1, 2, 4, 8) and (T * plan.xcd_pieces) % 8 == 0
+    else:
+        assert plan.xcd_pieces == 0
+    table, wave, xcd = _simulate(plan, T)
+    assert len(table) == plan.wavefronts == T * plan.waves_per_table
+    flat = table * plan.waves_per_table + wave
+    assert np.array_equal(np.sort(flat), np.arange(T * plan.waves_per_table))
+    # a table runs on exactly xcd_pieces XCDs, and every XCD gets the same number of pieces
+    for t in range(min(T, 9) if plan.xcd_pieces else 0):
+        assert len(np.unique(xcd[table == t])) == plan.xcd_pieces
+    with tuning(xcd_remap=0):
+        nat = _plan(T, B, 64, L)
+    table, wave, _ = _simulate(nat, T)
+    assert np.array_equal(table * nat.waves_per_table + wave, np.arange(T * nat.waves_per_table))
+
+
+def _mixed_plan(dims, B=4096, L=80, dtype=emb.EMB_F32):
+    desc = emb.make_mixed_desc(list(dims), B, dtype, emb.EMB_SUM, len(dims) * B * L, 0, 1 << 30)
+    return emb.emb_bag_plan_forward_mixed(desc, False, True)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_tables_of_different_widths_are_dealt_to_the_xcds_by_bytes(seed):
+    rng = np.random.default_rng(seed)
+    T = int(rng.choice([4, 10, 12, 20, 60, 100, 250, 1000]))
+    dims = rng.choice([4, 8, 16, 32, 64, 96, 128, 192, 256], size=T)
+    plan, order = _mixed_plan(dims)
+    assert sorted(order) == list(range(T))
+    if plan.xcd_pieces in (1, 2, 4):
+        assert plan.xcd_ordered == 1
+    table, wave, xcd = _simulate(plan, T, order)
+    flat = table * plan.waves_per_table + wave
+    assert np.array_equal(np.sort(flat), np.arange(T * plan.waves_per_table))
+    # bytes per XCD: within one widest table's piece of each other (greedy, widest first)
+    load = np.bincount(xcd, weights=dims[table].astype(np.float64), minlength=8)
+    assert load.max() - load.min() <= dims.max() * plan.waves_per_piece + 1e-9
+    # the caller's own order would have been worse or equal
+    naive = np.bincount(_simulate(plan, T)[2], weights=dims[_simulate(plan, T)[0]].astype(np.float64),
+                        minlength=8)
+    assert load.max() <= naive.max() + 1e-9
+
+
+def test_mixed_plan_special_cases():
+    plan, order = _mixed_plan([64] * 60)                       # equal widths: the caller's order
+    assert plan.xcd_ordered == 0 and order == list(range(60)) and plan.xcd_pieces == 2
+    plan, order = _mixed_plan([64, 32] * 600)                  # more tables than the order holds
+    assert plan.xcd_pieces == 0 and plan.xcd_ordered == 0      # natural order instead
+    plan, _ = _mixed_plan([64] * 1200)                         # ... which equal widths do not need
+    assert plan.xcd_pieces == 1                                # 1200 is a multiple of 8
+    plan, order = _mixed_plan([64, 32, 128] * 5)               # odd T: every table on all 8 XCDs
+    assert plan.xcd_pieces == 8 and plan.xcd_ordered == 0
+    plan, order = _mixed_plan([(32, 64, 128, 256)[t % 4] for t in range(60)])
+    assert order[:15] == list(range(3, 60, 4))                 # widest tables first
