@@ -387,6 +387,8 @@ def main() -> int:
                    "lookups_per_step": avg_lookups, "index_batches_rotated": len(batches),
                    "arena_allocation": arena_kind,
                    "streaming_tables": None if hints is None else int(hints.sum().item()),
+                   "launch_plan": (emb.emb_bag_plan_forward_mixed if mixed else
+                                   emb.emb_bag_plan_forward)(descs[0], wl.weighted).as_dict(),
                    "tuning": {k: emb.emb_bag_get_tuning(k) for k in
                               ("depth", "addressing", "blocks_per_cu", "xcd_remap", "use_hints",
                                "stream", "bags_per_group")}},

@@ -1,4 +1,6 @@
-// Multi-table EmbeddingBag forward for MI355X (gfx950, CDNA4): kernels + C ABI.
+// Multi-table EmbeddingBag forward for MI355X (gfx950, CDNA4): the one-wavefront-per-bag kernel,
+// the validator, the reuse profiler, and the C ABI with the host-side choice of kernel and grid.
+// (The kernel for short bags is in emb_bag_stream.hip, shared device code in emb_bag_device.h.)
 //
 // What is computed is the embedding stage of the paper (Sec. 3.1, Algorithm 1): per bag (t, b)
 // follow offsets -> indices -> table rows, add the rows, store one vector of length D.
@@ -770,6 +772,6 @@ const char* emb_bag_status_string(int status) {
   }
 }
 
-int emb_bag_version(void) { return 200; }
+int emb_bag_version(void) { return 300; }
 
 }  // extern "C"
