@@ -139,3 +139,62 @@ def test_widest_rows(oracle):
     host = gen.host_arena(wl16)
     ref, bound = oracle.emb_bag(host, wl16.table_offsets(), batch.indices, batch.offsets, wl16.B, "sum")
     assert_close_to_oracle(out.cpu().numpy(), ref, bound, True, "64 KiB f16 rows")
+
+
+def test_more_than_2_pow_32_lookups_in_one_call():
+    """Positions in `indices` beyond 2^32: 65,536 bags of 65,552 lookups (34 GB of indices).  The
+    table has two rows, +1 and -1 in every element, and position p names row (p mod 32 >= 16),
+    so every partial sum any lane group can form stays tiny and the result is exact: a bag that
+    starts on a multiple of 32 ends with an unpaired run of +1 (sum 16), the others start with an
+    unpaired run of -1 (sum -16)."""
+    B, L = 1 << 16, (1 << 16) + 16
+    n = B * L
+    assert n > 1 << 32
+    table = torch.tensor([[1.0] * 4, [-1.0] * 4], dtype=torch.float32, device=DEV)
+    idx = torch.empty(n, dtype=torch.int64, device=DEV)
+    step = 1 << 28
+    for lo in range(0, n, step):                          # in pieces: bounded temporaries
+        hi = min(n, lo + step)
+        idx[lo:hi] = (torch.arange(lo, hi, device=DEV) % 32) >= 16
+    off = to_dev(np.arange(B + 1, dtype=np.int64) * L)
+    toff = to_dev(np.array([0, 2], np.int64))
+    want_sum = np.where(np.arange(B) % 2 == 0, 16.0, -16.0).astype(np.float32)
+    for kw in (dict(), dict(addressing=1), dict(stream=1, bags_per_group=2)):
+        for mode in (emb.EMB_SUM, emb.EMB_MAX):
+            out = torch.full((B, 4), float("nan"), dtype=torch.float32, device=DEV)
+            desc = emb.make_desc(1, B, 4, emb.EMB_F32, mode, n, 0, 2)
+            with tuning(**kw):
+                emb.emb_bag_forward(desc, table, toff, idx, off, None, out)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            want = want_sum if mode == emb.EMB_SUM else np.ones(B, np.float32)
+            assert np.array_equal(got, np.repeat(want[:, None], 4, axis=1)), (kw, mode)
+    bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    emb.emb_bag_validate(desc, toff, idx, off, bad)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+    idx[n - 3] = 2                                         # one invalid id beyond position 2^32
+    emb.emb_bag_validate(desc, toff, idx, off, bad)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 1
+
+
+def test_table_of_more_than_2_pow_31_rows(oracle):
+    """Row ids beyond 2^31 and byte offsets beyond 2^35 inside ONE table (64-bit addressing; the
+    table is far above the 3.5 GiB that buffer addressing covers)."""
+    R = (1 << 31) + 1000
+    wl = gen.Workload(name="tall", T=2, rows=(R, 10), D=4, dtype="f32", B=64,
+                      pooling=("uniform", 0, 40), dists=(("uniform",), ("uniform",)), seed=0x5EED0A01)
+    batch = gen.make_batches(wl, 1)[0]
+    assert int(batch.indices.max()) > (1 << 31) - (1 << 27)     # lookups reach the far end
+    assert int(batch.offsets[wl.B]) >= 64                        # table 0 owns the first lookups
+    idx = batch.indices.copy()
+    idx[:64] = np.arange(R - 64, R, dtype=np.int64)              # ... and the very last rows
+    batch = gen.Batch(offsets=batch.offsets, indices=idx)
+    arena = device_arena(wl)
+    out, _ = _run(wl, batch, arena, to_dev(wl.table_offsets()))
+    bags = np.arange(wl.num_bags)
+    small, ix, soff, _ = gen.compact_rows(wl, batch, bags)
+    ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, soff, len(bags), "sum")
+    got = out.view(wl.B, wl.T, wl.D).permute(1, 0, 2).reshape(wl.num_bags, wl.D).cpu().numpy()
+    assert_close_to_oracle(got, ref, bound, False, "table of 2^31 + 1000 rows")
