@@ -34,6 +34,8 @@ DESCRIPTIONS = {
     "paper_one_item": "250 fp32 tables x 500,000 x dim 128, batch 2048, pooling 150, one item, sum",
     "cfg3_weighted": "cfg3 with fp32 per-sample weights",
     "cfg3_max": "cfg3 with max pooling",
+    "cfg3_fp8": "cfg3's shape with row-wise quantised rows of E4M3 codes: 60 tables x 4,000,000 "
+                "rows x dim 120 (128-byte rows), batch 4096, pooling 80, uniform, sum",
     "cfg3_u8": "cfg3's shape with row-wise quantised rows: 60 tables x 4,000,000 rows x dim 120 "
                "(uint8 codes + fp32 scale, bias = 128-byte rows), batch 4096, pooling 80, uniform, sum",
     "onehot": "short bags: 26 fp32 tables x 1,000,000 rows x dim 64, batch 131072, ONE lookup per "
@@ -129,8 +131,8 @@ def main() -> int:
     # ---- inputs, resident in HBM before anything is timed -------------------------------
     t0 = time.time()
     tdtype = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16,
-              "u8row": torch.uint8}[wl.dtype]
-    width = 0 if mixed else (wl.D + 8 if wl.dtype == "u8row" else wl.D)  # elements per stored row
+              "u8row": torch.uint8, "fp8row": torch.uint8}[wl.dtype]
+    width = 0 if mixed else (wl.D + 8 if wl.dtype in gen.QUANTISED else wl.D)  # elements per stored row
     # The arena is the caller's memory.  Where it lands physically moves cfg3 by about 5 %
     # between allocations of the same size; the contiguous flag itself makes no difference.
     owner = None
@@ -159,8 +161,7 @@ def main() -> int:
         dbatches.append((torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev),
                          None if b.weights is None else torch.from_numpy(b.weights).to(dev)))
     out = torch.empty((wl.B, total_dim), dtype=torch.float32, device=dev)
-    edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16,
-           "u8row": emb.EMB_U8ROW}[wl.dtype]
+    edt = emb.DTYPES[wl.dtype]
     emode = emb.MODES[wl.mode]
     # Set-up, untimed (the paper profiles table access patterns offline, Sec. 4.3): classify each
     # table as streaming or re-used from the first index batch, on the device.
@@ -287,7 +288,8 @@ def main() -> int:
                 small = gen.table_values(wl.seed, base[t] + uniq, wl.dims[t], wl.dtype, wl.kind)
                 off = gen.lengths_to_offsets(np.array([len(x) for x in segs], dtype=np.int64))
                 r, bd = emb_bag_oracle.emb_bag(small, np.array([0, len(small)], np.int64),
-                                               inv.astype(np.int64), off, len(bs), wl.mode)
+                                               inv.astype(np.int64), off, len(bs), wl.mode,
+                                               codes=wl.codes)
                 g = out[torch.from_numpy(bs % wl.B).to(dev), int(cols[t]):int(cols[t + 1])]
                 refs.append(r.ravel()), bounds.append(bd.ravel())
                 gots.append(g.cpu().numpy().astype(np.float64).ravel())
@@ -295,7 +297,7 @@ def main() -> int:
         else:
             small, ix, off, wsmall = gen.compact_rows(wl, batches[k], bags)
             ref, bound = emb_bag_oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, off,
-                                                len(bags), wl.mode, weights=wsmall)
+                                                len(bags), wl.mode, weights=wsmall, codes=wl.codes)
             got_all = out.view(wl.B, wl.T, wl.D)
             tb = torch.from_numpy(np.stack([bags % wl.B, bags // wl.B], 1)).to(dev)
             got = got_all[tb[:, 0], tb[:, 1]].cpu().numpy().astype(np.float64)
@@ -321,16 +323,16 @@ def main() -> int:
         for t in range(tsub):
             raw = arena[int(boff[t]):int(boff[t + 1])].cpu().numpy()
             tabs.append(raw.view(np.float32 if wl.dtype == "f32" else
-                                 np.uint8 if wl.dtype == "u8row" else np.uint16)
+                                 np.uint8 if wl.dtype in gen.QUANTISED else np.uint16)
                         .reshape(wl.rows[t], -1))
         b0 = batches[0]
         e = int(b0.offsets[tsub * wl.B])
         sub_off, sub_idx = b0.offsets[: tsub * wl.B + 1].copy(), b0.indices[:e]
-        emb_bag_oracle.emb_bag_mixed(tabs, sub_idx, sub_off, wl.B, wl.mode)   # warm
+        emb_bag_oracle.emb_bag_mixed(tabs, sub_idx, sub_off, wl.B, wl.mode, codes=wl.codes)   # warm
         reps, t_cpu = 0, 0.0
         while t_cpu < args.cpu_seconds and reps < 100000:
             t1 = time.perf_counter()
-            emb_bag_oracle.emb_bag_mixed(tabs, sub_idx, sub_off, wl.B, wl.mode)
+            emb_bag_oracle.emb_bag_mixed(tabs, sub_idx, sub_off, wl.B, wl.mode, codes=wl.codes)
             t_cpu += time.perf_counter() - t1
             reps += 1
         cpu_baseline = {"value": e * reps / t_cpu, "unit": "lookups/s",
@@ -350,11 +352,13 @@ def main() -> int:
         sub_off = b0.offsets[: tsub * wl.B + 1].copy()
         sub_idx = b0.indices[:e]
         n_sub = int(sub_off[-1])
-        emb_bag_oracle.emb_bag(host, toff_np[: tsub + 1], sub_idx, sub_off, wl.B, wl.mode)  # warm
+        emb_bag_oracle.emb_bag(host, toff_np[: tsub + 1], sub_idx, sub_off, wl.B, wl.mode,
+                                   codes=wl.codes)  # warm
         reps, t_cpu = 0, 0.0
         while t_cpu < args.cpu_seconds and reps < 100000:
             t1 = time.perf_counter()
-            emb_bag_oracle.emb_bag(host, toff_np[: tsub + 1], sub_idx, sub_off, wl.B, wl.mode)
+            emb_bag_oracle.emb_bag(host, toff_np[: tsub + 1], sub_idx, sub_off, wl.B, wl.mode,
+                                   codes=wl.codes)
             t_cpu += time.perf_counter() - t1
             reps += 1
         cpu_baseline = {"value": n_sub * reps / t_cpu, "unit": "lookups/s",

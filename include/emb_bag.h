@@ -36,6 +36,10 @@ extern "C" {
 #define EMB_U8ROW 3 /* row-wise quantised rows: D unsigned 8-bit codes followed by an fp32 scale and
                        an fp32 bias (row = D + 8 bytes, which must be a multiple of 16 and at most
                        1024); element d of a row is scale * code_d + bias, accumulated in fp32 */
+#define EMB_FP8ROW 4 /* the same row layout with 8-bit floating-point codes (OCP 8-bit floating
+                        point, E4M3: bias 7, 3 fraction bits, subnormals, largest finite 448, no
+                        infinities): element d is scale * e4m3(code_d) + bias.  The two NaN codes
+                        (0x7F, 0xFF) give an unspecified result */
 
 /* pooling modes: the two modes of the sum/mean kernel the paper studies (Sec. 3.1), and the
    element-wise maximum, the third pooling an embedding-bag operator usually offers */

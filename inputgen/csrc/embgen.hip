@@ -83,7 +83,10 @@ __global__ __launch_bounds__(256) void fill_kernel(void* __restrict__ dst, uint6
 }
 
 // Row-wise quantised rows: D one-byte codes, then an fp32 scale and an fp32 bias (D + 8 bytes per
-// row, a multiple of 16).  One thread writes one 16-byte vector of a row.
+// row, a multiple of 16).  One thread writes one 16-byte vector of a row.  FP8: the codes are
+// E4M3 numbers: the two NaN codes move to their neighbours, kind 1 clears the top exponent bit,
+// and scale / bias are (256 + a) * 2e-6 / -32 * scale (kind 0) or 1 / -1 (kind 1).
+template <bool FP8>
 __global__ __launch_bounds__(256) void fill_quantised_kernel(uint4* __restrict__ dst,
                                                              uint64_t first_row, uint64_t nvec,
                                                              uint32_t D, uint64_t seed, int kind) {
@@ -97,17 +100,23 @@ __global__ __launch_bounds__(256) void fill_quantised_kernel(uint4* __restrict__
 #pragma unroll
     for (uint32_t k = 0; k < 16; ++k) {
       const uint32_t col = c0 + k;
-      pk.b[k] = col < D ? (uint8_t)((mix64(seed + arow * K_ROW + (uint64_t)col * K_COL) >> 32) & 0xFF)
-                        : 0;
+      uint8_t code =
+          col < D ? (uint8_t)((mix64(seed + arow * K_ROW + (uint64_t)col * K_COL) >> 32) & 0xFF) : 0;
+      if constexpr (FP8) {
+        if ((code & 0x7F) == 0x7F) code &= 0xFE;
+        if (kind == 1) code &= 0xBF;
+      }
+      pk.b[k] = code;
     }
     if (c0 + 16 > D) {  // this vector holds the row's last 8 codes, then scale and bias
       float scale = 1.0f;
       if (kind == 0) {
         const int a = (int)(mix64(seed + arow * K_ROW + (uint64_t)D * K_COL) & 0xFF);
-        scale = __fmul_rn((float)(256 + a), 3.5e-6f);
+        scale = __fmul_rn((float)(256 + a), FP8 ? 2.0e-6f : 3.5e-6f);
       }
+      const float bias_factor = FP8 ? (kind == 1 ? -1.0f : -32.0f) : -128.0f;
       pk.w[2] = __builtin_bit_cast(uint32_t, scale);
-      pk.w[3] = __builtin_bit_cast(uint32_t, __fmul_rn(-128.0f, scale));
+      pk.w[3] = __builtin_bit_cast(uint32_t, __fmul_rn(bias_factor, scale));
     }
     dst[v] = pk.u;
   }
@@ -167,21 +176,27 @@ unsigned grid_for(uint64_t nvec) {
 extern "C" {
 
 // dst: DEVICE pointer to the first element of arena row `first_row` ([nrows, D] row-major).
-// dtype: 0 = fp32, 1 = fp16, 2 = bfloat16, 3 = row-wise quantised ([nrows, D + 8] bytes).  kind: 0 = normal, 1 = int.  Returns 0, or a negative code for a
+// dtype: 0 = fp32, 1 = fp16, 2 = bfloat16, 3 / 4 = row-wise quantised with integer / E4M3 codes
+// ([nrows, D + 8] bytes).  kind: 0 = normal, 1 = int.  Returns 0, or a negative code for a
 // bad argument / a positive hipError_t for a failed launch.
 int gen_fill_table(void* dst, int64_t first_row, int64_t nrows, int32_t D, int32_t dtype,
                    uint64_t seed, int32_t kind, void* stream) {
   if (nrows == 0) return 0;
   if (!dst || nrows < 0 || first_row < 0 || D <= 0) return -1;
-  if (dtype < 0 || dtype > 3) return -2;
+  if (dtype < 0 || dtype > 4) return -2;
   if (kind != 0 && kind != 1) return -3;
-  if (dtype == 3) {  // quantised rows: D codes + 8 bytes, a whole number of 16-byte vectors
+  if (dtype >= 3) {  // quantised rows: D codes + 8 bytes, a whole number of 16-byte vectors
     if ((D + 8) % 16 != 0) return -4;
     if ((reinterpret_cast<uintptr_t>(dst) & 15) != 0) return -5;
     const uint64_t nv = (uint64_t)nrows * (uint64_t)((D + 8) / 16);
-    hipLaunchKernelGGL(fill_quantised_kernel, dim3(grid_for(nv)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), static_cast<uint4*>(dst),
-                       (uint64_t)first_row, nv, (uint32_t)D, seed, kind);
+    if (dtype == 4)
+      hipLaunchKernelGGL(fill_quantised_kernel<true>, dim3(grid_for(nv)), dim3(256), 0,
+                         static_cast<hipStream_t>(stream), static_cast<uint4*>(dst),
+                         (uint64_t)first_row, nv, (uint32_t)D, seed, kind);
+    else
+      hipLaunchKernelGGL(fill_quantised_kernel<false>, dim3(grid_for(nv)), dim3(256), 0,
+                         static_cast<hipStream_t>(stream), static_cast<uint4*>(dst),
+                         (uint64_t)first_row, nv, (uint32_t)D, seed, kind);
     return (int)hipGetLastError();
   }
   const uint32_t epv = dtype == 0 ? 4 : 8;

@@ -58,8 +58,8 @@ def table_values(seed: int, arena_rows: Sequence[int], D: int, dtype: str = "f32
     kind 1: integers in [-8, 7] (sums of these are exact in fp32 in any order).
     """
     rows = np.asarray(arena_rows, dtype=np.uint64).reshape(-1, 1)
-    if dtype == "u8row":
-        return _quantised_rows(seed, rows, D, kind)
+    if dtype in QUANTISED:
+        return _quantised_rows(seed, rows, D, kind, fp8=dtype == "fp8row")
     cols = np.arange(D, dtype=np.uint64).reshape(1, -1)
     with np.errstate(over="ignore"):
         z = _mix64(np.uint64(seed & 0xFFFFFFFFFFFFFFFF) + rows * _K_ROW + cols * _K_COL)
@@ -83,25 +83,40 @@ def table_values(seed: int, arena_rows: Sequence[int], D: int, dtype: str = "f32
 
 
 _QSCALE = np.float32(3.5e-6)
+_QSCALE_FP8 = np.float32(2.0e-6)
+QUANTISED = ("u8row", "fp8row")   # D one-byte codes + fp32 scale + fp32 bias per row
 
 
-def _quantised_rows(seed: int, rows: np.ndarray, D: int, kind: int) -> np.ndarray:
+def _quantised_rows(seed: int, rows: np.ndarray, D: int, kind: int, fp8: bool = False) -> np.ndarray:
     """Row-wise quantised rows, uint8 [n, D + 8]: D codes, fp32 scale, fp32 bias.
-    code = bits 32..39 of the hash of (row, col); the hash of (row, col = D) picks the scale:
-    kind 0: scale = (256 + a) * 3.5e-6 with a in [0, 255], bias = -128 * scale (elements roughly
-    uniform in +-0.17, sigma about 0.1); kind 1: scale = 1, bias = -128 (integers in [-128, 127])."""
+    code = bits 32..39 of the hash of (row, col); the hash of (row, col = D) picks the scale.
+    Integer codes: kind 0: scale = (256 + a) * 3.5e-6 with a in [0, 255], bias = -128 * scale
+    (elements roughly uniform in +-0.17, sigma about 0.1); kind 1: scale = 1, bias = -128
+    (integers in [-128, 127]).
+    E4M3 codes (fp8): the two NaN codes are moved to their neighbours (0x7F -> 0x7E, 0xFF -> 0xFE);
+    kind 0: scale = (256 + a) * 2e-6, bias = -32 * scale (elements within +-0.46); kind 1: the
+    top exponent bit is cleared (|value| < 2, a multiple of 2^-9), scale = 1, bias = -1, so sums
+    of a few hundred elements are exact in fp32."""
     n = rows.shape[0]
     cols = np.arange(D + 1, dtype=np.uint64).reshape(1, -1)
     with np.errstate(over="ignore"):
         z = _mix64(np.uint64(seed & 0xFFFFFFFFFFFFFFFF) + rows * _K_ROW + cols * _K_COL)
     out = np.empty((n, D + 8), dtype=np.uint8)
-    out[:, :D] = ((z[:, :D] >> np.uint64(32)) & np.uint64(0xFF)).astype(np.uint8)
+    codes = ((z[:, :D] >> np.uint64(32)) & np.uint64(0xFF)).astype(np.uint8)
+    if fp8:
+        codes = np.where((codes & 0x7F) == 0x7F, codes & 0xFE, codes).astype(np.uint8)
+        if kind == KIND_INT:
+            codes &= np.uint8(0xBF)
+    out[:, :D] = codes
     if kind == KIND_INT:
         scale = np.ones(n, dtype=np.float32)
     else:
         a = (z[:, D] & np.uint64(0xFF)).astype(np.int64)
-        scale = (256 + a).astype(np.float32) * _QSCALE
-    bias = (np.float32(-128.0) * scale).astype(np.float32)
+        scale = (256 + a).astype(np.float32) * (_QSCALE_FP8 if fp8 else _QSCALE)
+    if fp8:
+        bias = (np.float32(-1.0 if kind == KIND_INT else -32.0) * scale).astype(np.float32)
+    else:
+        bias = (np.float32(-128.0) * scale).astype(np.float32)
     out[:, D:D + 4] = np.ascontiguousarray(scale).view(np.uint8).reshape(n, 4)
     out[:, D + 4:D + 8] = np.ascontiguousarray(bias).view(np.uint8).reshape(n, 4)
     return out
@@ -110,7 +125,7 @@ def _quantised_rows(seed: int, rows: np.ndarray, D: int, kind: int) -> np.ndarra
 def table_values_range(seed: int, first_row: int, nrows: int, D: int, dtype: str = "f32",
                        kind: int = KIND_NORMAL, chunk_rows: int = 1 << 16) -> np.ndarray:
     """Rows [first_row, first_row + nrows) of the arena, generated in chunks."""
-    if dtype == "u8row":
+    if dtype in QUANTISED:
         out = np.empty((nrows, D + 8), dtype=np.uint8)
     else:
         out = np.empty((nrows, D), dtype={"f16": np.float16, "bf16": np.uint16}.get(dtype, np.float32))
@@ -161,7 +176,7 @@ def fill_arena_device(dev_ptr: int, first_row: int, nrows: int, D: int, dtype: s
     """Fill arena rows [first_row, first_row+nrows) at device address `dev_ptr` (= address of
     row `first_row`) with `table_values`; asynchronous on `stream` (a hipStream_t as int)."""
     rc = load_lib().gen_fill_table(ctypes.c_void_p(dev_ptr), first_row, nrows, D,
-                                   {"f32": 0, "f16": 1, "bf16": 2, "u8row": 3}[dtype],
+                                   {"f32": 0, "f16": 1, "bf16": 2, "u8row": 3, "fp8row": 4}[dtype],
                                    ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF), kind,
                                    ctypes.c_void_p(stream))
     if rc != 0:
@@ -176,13 +191,13 @@ class DeviceArena:
     been synchronised).  If the contiguous request is refused the arena falls back to an ordinary
     allocation and says so in `kind`."""
 
-    _TYPESTR = {"f32": "<f4", "f16": "<f2", "bf16": "<i2", "u8row": "|u1"}
+    _TYPESTR = {"f32": "<f4", "f16": "<f2", "bf16": "<i2", "u8row": "|u1", "fp8row": "|u1"}
 
     def __init__(self, rows: int, D: int, dtype: str, contiguous: bool = True):
         import torch
         self.rows, self.D, self.dtype = int(rows), int(D), dtype
-        width = self.D + 8 if dtype == "u8row" else self.D      # elements per row in the view
-        self.nbytes = self.rows * width * {"f32": 4, "u8row": 1}.get(dtype, 2)
+        width = self.D + 8 if dtype in QUANTISED else self.D    # elements per row in the view
+        self.nbytes = self.rows * width * {"f32": 4, "u8row": 1, "fp8row": 1}.get(dtype, 2)
         lib = load_lib()
         p = ctypes.c_void_p()
         self.kind = "hip-contiguous" if contiguous else "hip-default"
@@ -238,7 +253,7 @@ class Workload:
     T: int                      # number of tables
     rows: Tuple[int, ...]       # rows per table (len T)
     D: int                      # embedding dimension (uniform over tables)
-    dtype: str                  # 'f32' | 'f16' | 'bf16' | 'u8row' (table storage; output is fp32)
+    dtype: str                  # 'f32' | 'f16' | 'bf16' | 'u8row' | 'fp8row' (table storage; output is fp32)
     B: int                      # batch (bags per table)
     pooling: Tuple              # ('fixed', L) | ('uniform', lo, hi) inclusive
     dists: Tuple[Tuple, ...]    # per table: ('uniform',) | ('zipf', alpha) | ('one_item',)
@@ -250,11 +265,11 @@ class Workload:
 
     @property
     def elem_bytes(self) -> int:
-        return {"f32": 4, "u8row": 1}.get(self.dtype, 2)
+        return {"f32": 4, "u8row": 1, "fp8row": 1}.get(self.dtype, 2)
 
     @property
     def row_bytes(self) -> int:
-        if self.dtype == "u8row":   # D one-byte codes + fp32 scale + fp32 bias
+        if self.dtype in QUANTISED:   # D one-byte codes + fp32 scale + fp32 bias
             return self.D + 8
         return self.D * self.elem_bytes
 
@@ -265,6 +280,11 @@ class Workload:
     @property
     def table_bytes(self) -> int:
         return self.total_rows * self.row_bytes
+
+    @property
+    def codes(self) -> str:
+        """What the code bytes of quantised rows stand for: 'u8' integers or 'fp8' E4M3 numbers."""
+        return "fp8" if self.dtype == "fp8row" else "u8"
 
     @property
     def num_bags(self) -> int:
@@ -309,9 +329,14 @@ class MixedWorkload:
     def num_bags(self) -> int:
         return self.T * self.B
 
+    @property
+    def codes(self) -> str:
+        """What the code bytes of quantised rows stand for: 'u8' integers or 'fp8' E4M3 numbers."""
+        return "fp8" if self.dtype == "fp8row" else "u8"
+
     def row_bytes_of(self, t: int) -> int:
         d = self.dims[t]
-        return d + 8 if self.dtype == "u8row" else d * (4 if self.dtype == "f32" else 2)
+        return d + 8 if self.dtype in QUANTISED else d * (4 if self.dtype == "f32" else 2)
 
     def table_byte_offsets(self) -> np.ndarray:
         sizes = [self.rows[t] * self.row_bytes_of(t) for t in range(self.T)]
@@ -440,6 +465,15 @@ def workload(name: str) -> Workload:
         return with_overrides(workload("cfg3"), name="cfg3_max", mode="max")
     if name == "cfg3_weighted":    # cfg3 with per-sample weights
         return with_overrides(workload("cfg3"), name="cfg3_weighted", weighted=True)
+    if name == "small_fp8_d120":   # 128-byte rows of E4M3 codes
+        return with_overrides(workload("small_u8_d120"), name="small_fp8_d120", dtype="fp8row",
+                              seed=0x5EED001A)
+    if name == "small_fp8_d504":   # 512-byte rows of E4M3 codes
+        return with_overrides(workload("small_u8_d504"), name="small_fp8_d504", dtype="fp8row",
+                              seed=0x5EED001B)
+    if name == "cfg3_fp8":         # cfg3's shape with E4M3 rows (dim 120 -> 128-byte rows)
+        return _homog("cfg3_fp8", 60, 4_000_000, 120, "fp8row", 4096, ("fixed", 80), ("uniform",),
+                      seed_off=0x1C)
     if name == "cfg3_u8":          # cfg3's shape with quantised rows (dim 120 -> 128-byte rows)
         return _homog("cfg3_u8", 60, 4_000_000, 120, "u8row", 4096, ("fixed", 80), ("uniform",),
                       seed_off=0x17)

@@ -25,7 +25,8 @@
  *   - summation order is not fixed by the paper: this oracle adds in index order, in fp64.
  *
  * Arithmetic: every table element is widened exactly (fp32, IEEE half or bfloat16 -> fp64; a
- * quantised element is scale * code + bias evaluated in fp64) and accumulated in fp64.  Alongside each output element the oracle returns bound = sum_j |w_j *
+ * quantised element is scale * code + bias evaluated in fp64, the code being an unsigned byte or an
+ * E4M3 8-bit float) and accumulated in fp64.  Alongside each output element the oracle returns bound = sum_j |w_j *
  * x_j| (divided by the bag length in mean mode), the scale of the rounding-error tolerance.
  *
  * Parity pins (tests/test_oracle_pins.py): exact rational brute force on tiny inputs, index
@@ -71,20 +72,40 @@ static double bf16_bits_to_double(uint16_t h) {
 }
 
 /*
+ * OCP 8-bit floating point, format E4M3 (1 sign, 4 exponent bits with bias 7, 3 fraction bits; no
+ * infinities; S.1111.111 is NaN; largest finite value 448) -> double, exactly.
+ */
+static double e4m3_bits_to_double(uint8_t c) {
+  const int sign = (c >> 7) & 1;
+  const int expo = (c >> 3) & 0xF;
+  const int frac = c & 0x7;
+  double v;
+  if (expo == 0)
+    v = ldexp((double)frac, -9); /* subnormal: frac/8 * 2^-6 */
+  else if (expo == 15 && frac == 7)
+    v = NAN;
+  else
+    v = ldexp((double)(8 + frac), expo - 10); /* (1 + frac/8) * 2^(expo-7) */
+  return sign ? -v : v;
+}
+
+/*
  * Element d of an arena row as a double, and the magnitude the error bound charges for it.
- * dtype 3 is a row-wise quantised table: a row is D unsigned 8-bit codes followed by an fp32
- * scale and an fp32 bias (row stride D + 8 bytes), and element d is scale * code_d + bias; its
- * magnitude for the bound is |scale * code_d| + |bias|, the two terms an implementation adds.
+ * dtype 3 and 4 are row-wise quantised tables: a row is D 8-bit codes followed by an fp32 scale
+ * and an fp32 bias (row stride D + 8 bytes), and element d is scale * value(code_d) + bias, where
+ * value() is the unsigned integer (dtype 3) or the E4M3 number (dtype 4) the code stands for; its
+ * magnitude for the bound is |scale * value| + |bias|, the two terms an implementation adds.
  */
 static double table_elem(const void* tables, int dtype, int64_t arena_row, int64_t D, int64_t d,
                          double* magnitude) {
   double x;
-  if (dtype == 3) {
+  if (dtype == 3 || dtype == 4) {
     const uint8_t* row = (const uint8_t*)tables + arena_row * (D + 8);
     float scale, bias;
     memcpy(&scale, row + D, sizeof scale);
     memcpy(&bias, row + D + 4, sizeof bias);
-    const double sc = (double)scale * (double)row[d];
+    const double code = dtype == 3 ? (double)row[d] : e4m3_bits_to_double(row[d]);
+    const double sc = (double)scale * code;
     *magnitude = fabs(sc) + fabs((double)bias);
     return sc + (double)bias;
   }
@@ -120,6 +141,7 @@ void oracle_set_num_threads(int n) {
  *   dtype          0 = fp32 tables, 1 = fp16 tables (raw half bit patterns),
  *                  2 = bfloat16 tables (raw bit patterns),
  *                  3 = row-wise quantised tables: D uint8 codes + fp32 scale + fp32 bias per row
+ *                  4 = the same with E4M3 8-bit floating-point codes
  *   mode           0 = sum, 1 = mean, 2 = max (bound = magnitude of the element that is the max)
  *   tables         arena [sum_t R_t, D], row-major ([sum_t R_t, D + 8] bytes for dtype 3)
  *   table_offsets  [T+1] first arena row of each table (so R_t = table_offsets[t+1]-table_offsets[t])
@@ -134,7 +156,7 @@ int oracle_emb_bag(int32_t T, int64_t B, int32_t D, int32_t dtype, int32_t mode,
                    const void* tables, const int64_t* table_offsets, const int64_t* indices,
                    const int64_t* offsets, const float* weights, int64_t out_ld, double* ref,
                    double* bound) {
-  if (T < 1 || B < 0 || D < 1 || (dtype < 0 || dtype > 3) || (mode < 0 || mode > 2))
+  if (T < 1 || B < 0 || D < 1 || (dtype < 0 || dtype > 4) || (mode < 0 || mode > 2))
     return ORACLE_ERR_ARG;
   if (out_ld < (int64_t)T * D) return ORACLE_ERR_ARG;
   if (weights && mode != 0) return ORACLE_ERR_ARG;

@@ -59,8 +59,11 @@ def _ptr(a: Optional[np.ndarray]):
 def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
             offsets: np.ndarray, B: int, mode: str = "sum",
             weights: Optional[np.ndarray] = None,
-            out_ld: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+            out_ld: int = 0, codes: str = "u8") -> Tuple[np.ndarray, np.ndarray]:
     """Reference output and error-bound scale, both fp64 [B, out_ld].
+
+    `codes` says what the bytes of a quantised (uint8) table stand for: "u8" unsigned integers,
+    "fp8" OCP E4M3 8-bit floats.
 
     tables: [sum R_t, D] float32, float16 or uint16 (= bfloat16 bits) host array, or uint8
     [sum R_t, D + 8] (D codes, fp32 scale, fp32 bias per row: element = scale * code + bias); table_offsets int64 [T+1];
@@ -76,7 +79,7 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
     elif tables.dtype == np.uint16:   # numpy has no bfloat16: raw bit patterns
         dtype = 2
     elif tables.dtype == np.uint8:    # row-wise quantised: D codes + fp32 scale + fp32 bias
-        dtype = 3
+        dtype = {"u8": 3, "fp8": 4}[codes]
         if tables.shape[1] <= 8:
             raise ValueError("quantised rows need D + 8 bytes")
     else:
@@ -91,7 +94,7 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
         if len(weights) != len(indices):
             raise ValueError("weights and indices differ in length")
     T = len(table_offsets) - 1
-    D = tables.shape[1] - 8 if dtype == 3 else tables.shape[1]
+    D = tables.shape[1] - 8 if dtype >= 3 else tables.shape[1]
     if len(offsets) != T * B + 1:
         raise ValueError("offsets must have T*B+1 entries")
     if int(offsets[-1]) != len(indices):
@@ -112,7 +115,7 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
 
 def emb_bag_mixed(tables, indices: np.ndarray, offsets: np.ndarray, B: int, mode: str = "sum",
                   weights: Optional[np.ndarray] = None,
-                  out_ld: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+                  out_ld: int = 0, codes: str = "u8") -> Tuple[np.ndarray, np.ndarray]:
     """Tables of different widths: `tables` is a list of per-table host arrays ([R_t, D_t], or
     uint8 [R_t, D_t + 8] for quantised rows).  The definition is unchanged - bag (t, b) pools rows
     of table t - and table t's block starts at column sum of the widths before it; each table is
@@ -131,7 +134,7 @@ def emb_bag_mixed(tables, indices: np.ndarray, offsets: np.ndarray, B: int, mode
         s, e = int(o[0]), int(o[-1])
         w = None if weights is None else weights[s:e]
         r, b = emb_bag(tables[t], np.array([0, tables[t].shape[0]], np.int64), indices[s:e], o - s,
-                       B, mode, weights=w)
+                       B, mode, weights=w, codes=codes)
         ref[:, col:col + dims[t]] = r
         bound[:, col:col + dims[t]] = b
         col += dims[t]

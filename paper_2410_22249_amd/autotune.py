@@ -54,8 +54,8 @@ def _setup_wl(wl, n_batches: int):
 
     dev = "cuda:0"
     tdtype = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16,
-              "u8row": torch.uint8}[wl.dtype]
-    width = wl.D + 8 if wl.dtype == "u8row" else wl.D   # quantised rows end with scale and bias
+              "u8row": torch.uint8, "fp8row": torch.uint8}[wl.dtype]
+    width = wl.D + 8 if wl.dtype in gen.QUANTISED else wl.D   # quantised rows end with scale and bias
     arena = torch.empty((wl.total_rows, width), dtype=tdtype, device=dev)
     gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed, wl.kind,
                           torch.cuda.current_stream().cuda_stream)
@@ -64,8 +64,7 @@ def _setup_wl(wl, n_batches: int):
     dev_batches = [(torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev),
                     None if b.weights is None else torch.from_numpy(b.weights).to(dev))
                    for b in batches]
-    edt = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16,
-           "u8row": emb.EMB_U8ROW}[wl.dtype]
+    edt = emb.DTYPES[wl.dtype]
     emode = emb.MODES[wl.mode]
     hints = torch.zeros(wl.T, dtype=torch.uint8, device=dev)
     d0 = emb.make_desc(wl.T, wl.B, wl.D, edt, emode, batches[0].num_lookups, 0, max(wl.rows))

@@ -15,7 +15,9 @@ import torch  # imported before the library so that the HIP runtime torch ships 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libembbag.so")
 
-EMB_F32, EMB_F16, EMB_BF16, EMB_U8ROW = 0, 1, 2, 3
+EMB_F32, EMB_F16, EMB_BF16, EMB_U8ROW, EMB_FP8ROW = 0, 1, 2, 3, 4
+DTYPES = {"f32": EMB_F32, "f16": EMB_F16, "bf16": EMB_BF16, "u8row": EMB_U8ROW,
+          "fp8row": EMB_FP8ROW}
 EMB_SUM, EMB_MEAN, EMB_MAX = 0, 1, 2
 MODES = {"sum": EMB_SUM, "mean": EMB_MEAN, "max": EMB_MAX}
 EMB_OK = 0

@@ -57,7 +57,7 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
                     TableOrder order) {
   constexpr bool MIXED = LPR == 0;
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;  // 2-byte elements
-  constexpr bool QUANT = ELEM == EMB_U8ROW;                   // 1-byte codes + scale, bias
+  constexpr bool QUANT = IsQuant<ELEM>::value;                // 1-byte codes + scale, bias
   constexpr int NACC = AccCount<ELEM, OP>::value;             // fp32 accumulators per lane
 
   const int lane = threadIdx.x & (kWaveSize - 1);
@@ -289,6 +289,7 @@ KernelFn pick_dtype(int elem, int depth, int op, bool buf) {
     case EMB_F16: return pick_depth<LPR, EMB_F16>(depth, op, buf);
     case EMB_BF16: return pick_depth<LPR, EMB_BF16>(depth, op, buf);
     case EMB_U8ROW: return pick_depth<LPR, EMB_U8ROW>(depth, op, buf);
+    case EMB_FP8ROW: return pick_depth<LPR, EMB_FP8ROW>(depth, op, buf);
     default: return nullptr;
   }
 }
@@ -305,15 +306,15 @@ KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf) {
   }
 }
 
+bool is_quant(int table_dtype) { return table_dtype == EMB_U8ROW || table_dtype == EMB_FP8ROW; }
+
 int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
   if (!d) return EMB_ERR_NULL_PTR;
-  if (d->table_dtype != EMB_F32 && d->table_dtype != EMB_F16 && d->table_dtype != EMB_BF16 &&
-      d->table_dtype != EMB_U8ROW)
-    return EMB_ERR_BAD_DTYPE;
+  if (d->table_dtype < EMB_F32 || d->table_dtype > EMB_FP8ROW) return EMB_ERR_BAD_DTYPE;
   if (d->mode != EMB_SUM && d->mode != EMB_MEAN && d->mode != EMB_MAX) return EMB_ERR_BAD_MODE;
   if (d->num_tables < 1 || d->dim < 1) return EMB_ERR_BAD_DIM;
   int64_t row_bytes = (int64_t)d->dim * (d->table_dtype == EMB_F32 ? 4 : 2);
-  if (d->table_dtype == EMB_U8ROW) {
+  if (is_quant(d->table_dtype)) {
     row_bytes = (int64_t)d->dim + 8;  // one-byte codes, then fp32 scale and fp32 bias
     if (row_bytes > kSlabBytes) return EMB_ERR_BAD_DIM;
   }
@@ -481,9 +482,7 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
 int precheck_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t* max_row_bytes,
                    int64_t* out_ld) {
   if (!desc) return EMB_ERR_NULL_PTR;
-  if (desc->table_dtype != EMB_F32 && desc->table_dtype != EMB_F16 &&
-      desc->table_dtype != EMB_BF16 && desc->table_dtype != EMB_U8ROW)
-    return EMB_ERR_BAD_DTYPE;
+  if (desc->table_dtype < EMB_F32 || desc->table_dtype > EMB_FP8ROW) return EMB_ERR_BAD_DTYPE;
   if (desc->mode != EMB_SUM && desc->mode != EMB_MEAN && desc->mode != EMB_MAX)
     return EMB_ERR_BAD_MODE;
   if (desc->num_tables < 1 || !desc->dims) return desc->dims ? EMB_ERR_BAD_DIM : EMB_ERR_NULL_PTR;
@@ -494,8 +493,8 @@ int precheck_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t* max_
   for (int64_t t = 0; t < desc->num_tables; ++t) {
     const int64_t d = desc->dims[t];
     if (d < 1) return EMB_ERR_BAD_DIM;
-    const int64_t rb = desc->table_dtype == EMB_U8ROW ? d + 8
-                                                       : d * (desc->table_dtype == EMB_F32 ? 4 : 2);
+    const int64_t rb = is_quant(desc->table_dtype) ? d + 8
+                                                     : d * (desc->table_dtype == EMB_F32 ? 4 : 2);
     if (rb % 16 != 0 || rb > kSlabBytes) return EMB_ERR_BAD_DIM;
     if (rb > *max_row_bytes) *max_row_bytes = (uint32_t)rb;
     total_dim += d;
@@ -516,7 +515,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
   bool widths_differ = false;
   for (int64_t t = 0; t < T; ++t) {
     const int64_t d = desc->dims[t];
-    const int64_t rb = desc->table_dtype == EMB_U8ROW ? d + 8 : d * elem_bytes;
+    const int64_t rb = is_quant(desc->table_dtype) ? d + 8 : d * elem_bytes;
     if (t < kMaxOrdered) row_units[t] = (uint16_t)(rb / 16);
     if (d != desc->dims[0]) widths_differ = true;
   }

@@ -76,6 +76,12 @@ __device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
 
 __device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
 
+// Row-wise quantised element types: D one-byte codes, then an fp32 scale and an fp32 bias.
+template <int ELEM>
+struct IsQuant {
+  static constexpr bool value = ELEM == EMB_U8ROW || ELEM == EMB_FP8ROW;
+};
+
 // What a lookup does to the accumulator: plain sum, sum with per-sample weights, or maximum.
 constexpr int kOpSum = 0, kOpWeighted = 1, kOpMax = 2;
 
@@ -83,14 +89,14 @@ constexpr int kOpSum = 0, kOpWeighted = 1, kOpMax = 2;
 // bf16 elements, or 16 one-byte codes.
 template <int ELEM>
 struct OutCount {
-  static constexpr int value = ELEM == EMB_F32 ? 4 : (ELEM == EMB_U8ROW ? 16 : 8);
+  static constexpr int value = ELEM == EMB_F32 ? 4 : (IsQuant<ELEM>::value ? 16 : 8);
 };
 
 // fp32 accumulators a lane keeps: one per element, plus one more for quantised rows (the sum of
 // the row biases) or for max pooling (the number of valid lookups seen).
 template <int ELEM, int OP = kOpSum>
 struct AccCount {
-  static constexpr int value = OutCount<ELEM>::value + ((ELEM == EMB_U8ROW || OP == kOpMax) ? 1 : 0);
+  static constexpr int value = OutCount<ELEM>::value + ((IsQuant<ELEM>::value || OP == kOpMax) ? 1 : 0);
 };
 
 template <int ELEM, int OP>
@@ -102,7 +108,8 @@ __device__ __forceinline__ void init_acc(float* acc) {
 }
 
 // One 16-byte segment of a row into the accumulators: 4 fp32 elements, 8 fp16 / bf16 elements
-// widened exactly to fp32, or 16 codes of a row-wise quantised row.  For the latter the row's
+// widened exactly to fp32, or 16 codes (unsigned bytes or E4M3 numbers, both exact in fp32) of a
+// row-wise quantised row.  For the latter the row's
 // scale and bias sit in the last 8 bytes of the row, i.e. in words z and w of lane `meta_lane`'s
 // segment.
 //   kOpSum / kOpWeighted: acc += w * element; for quantised rows acc[i] collects w * scale *
@@ -116,7 +123,7 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int met
   constexpr bool MAXP = OP == kOpMax;
   constexpr int NOUT = OutCount<ELEM>::value;
   const float skip = -__builtin_inff();
-  if constexpr (ELEM == EMB_U8ROW) {
+  if constexpr (IsQuant<ELEM>::value) {
     float scale = as_float((uint32_t)__shfl((int)r.z, meta_lane));
     float bias = as_float((uint32_t)__shfl((int)r.w, meta_lane));
     if constexpr (WEIGHTED) {
@@ -126,9 +133,22 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int met
     const uint32_t u[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      float codes[4];
+      if constexpr (ELEM == EMB_FP8ROW) {  // two E4M3 codes per conversion instruction
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)u[i], false);
+        const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)u[i], true);
+        codes[0] = lo.x;
+        codes[1] = lo.y;
+        codes[2] = hi.x;
+        codes[3] = hi.y;
+      } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) codes[k] = (float)((u[i] >> (8 * k)) & 0xFFu);
+      }
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        const float code = (float)((u[i] >> (8 * k)) & 0xFFu);
+        const float code = codes[k];
         if constexpr (MAXP) {
           const float v = __builtin_fmaf(scale, code, bias);
           acc[4 * i + k] = __builtin_fmaxf(acc[4 * i + k], w != 0.0f ? v : skip);
@@ -287,7 +307,7 @@ __device__ __forceinline__ void finish_bag(float* acc, int lpr, int lane, bool l
                                            float* __restrict__ out, int64_t out_ld, uint32_t b,
                                            int64_t out_col) {
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;
-  constexpr bool QUANT = ELEM == EMB_U8ROW;
+  constexpr bool QUANT = IsQuant<ELEM>::value;
   constexpr bool MAXP = OP == kOpMax;
   constexpr int NOUT = OutCount<ELEM>::value;
   if constexpr (QUANT && !MAXP) {

@@ -51,7 +51,7 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
                                               int lane, uint32_t col, bool lane_ok,
                                               int meta_lane) {
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;
-  constexpr bool QUANT = ELEM == EMB_U8ROW;
+  constexpr bool QUANT = IsQuant<ELEM>::value;
   constexpr int NACC = AccCount<ELEM>::value;
   constexpr int NOUT = QUANT ? 16 : NACC;
   constexpr int kAux = NT ? 2 : 0;  // cache-policy bits of the row loads: 2 = nt
@@ -153,7 +153,7 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
   constexpr int G = kWaveSize / LPR;
   constexpr int GL = __builtin_ctz((unsigned)G);
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;
-  constexpr bool QUANT = ELEM == EMB_U8ROW;
+  constexpr bool QUANT = IsQuant<ELEM>::value;
   constexpr int NACC = AccCount<ELEM>::value;
   constexpr int NOUT = QUANT ? 16 : NACC;
 
@@ -285,6 +285,7 @@ KernelFn pick_e(int elem, int depth, bool weighted) {
     case EMB_F16: return pick_w<LPR, EMB_F16>(depth, weighted);
     case EMB_BF16: return pick_w<LPR, EMB_BF16>(depth, weighted);
     case EMB_U8ROW: return pick_w<LPR, EMB_U8ROW>(depth, weighted);
+    case EMB_FP8ROW: return pick_w<LPR, EMB_FP8ROW>(depth, weighted);
     default: return nullptr;
   }
 }

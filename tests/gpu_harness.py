@@ -33,7 +33,7 @@ def upload_arena(arena: np.ndarray) -> torch.Tensor:
 
 
 TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16,
-               "u8row": torch.uint8}
+               "u8row": torch.uint8, "fp8row": torch.uint8}
 EMB_DTYPE = {torch.float32: emb.EMB_F32, torch.float16: emb.EMB_F16, torch.bfloat16: emb.EMB_BF16,
              torch.uint8: emb.EMB_U8ROW}
 
@@ -50,7 +50,7 @@ def arena_bytes(arena: torch.Tensor) -> np.ndarray:
 
 def device_arena(wl: gen.Workload) -> torch.Tensor:
     """Allocate the arena on the device and fill it with the generator's kernel."""
-    width = wl.D + 8 if wl.dtype == "u8row" else wl.D
+    width = wl.D + 8 if wl.dtype in gen.QUANTISED else wl.D
     arena = torch.empty((wl.total_rows, width), dtype=TORCH_DTYPE[wl.dtype], device=DEV)
     gen.fill_arena_device(arena.data_ptr(), 0, wl.total_rows, wl.D, wl.dtype, wl.seed, wl.kind,
                           torch.cuda.current_stream().cuda_stream)
@@ -59,8 +59,11 @@ def device_arena(wl: gen.Workload) -> torch.Tensor:
 
 def forward(arena: torch.Tensor, table_offsets: np.ndarray, indices, offsets, B: int,
             mode: str = "sum", weights=None, out_ld: int = 0, max_table_rows: Optional[int] = None,
-            out: Optional[torch.Tensor] = None, fill: float = float("nan")) -> torch.Tensor:
-    """Run emb_bag_forward; numpy inputs are uploaded, torch inputs are used as they are."""
+            out: Optional[torch.Tensor] = None, fill: float = float("nan"),
+            table_dtype: Optional[int] = None) -> torch.Tensor:
+    """Run emb_bag_forward; numpy inputs are uploaded, torch inputs are used as they are.  The
+    element type follows from the arena's dtype unless `table_dtype` names it (uint8 arenas hold
+    integer codes by default, E4M3 codes with EMB_FP8ROW)."""
     T = len(table_offsets) - 1
     D = arena_dim(arena)
     toff_np = np.asarray(table_offsets, dtype=np.int64)
@@ -75,7 +78,7 @@ def forward(arena: torch.Tensor, table_offsets: np.ndarray, indices, offsets, B:
     ld = out_ld if out_ld else T * D
     if out is None:
         out = torch.full((B, ld), fill, dtype=torch.float32, device=DEV)
-    desc = emb.make_desc(T, B, D, EMB_DTYPE[arena.dtype],
+    desc = emb.make_desc(T, B, D, EMB_DTYPE[arena.dtype] if table_dtype is None else table_dtype,
                          emb.MODES[mode], nl, out_ld,
                          max_table_rows)
     emb.emb_bag_forward(desc, arena, toff, idx if nl else None, off, w, out)

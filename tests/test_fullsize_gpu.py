@@ -22,7 +22,7 @@ def _run(wl, batch, arena, toff):
     idx, off = to_dev(batch.indices), to_dev(batch.offsets)
     w = to_dev(batch.weights)
     out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
-    desc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16, "u8row": emb.EMB_U8ROW}[wl.dtype],
+    desc = emb.make_desc(wl.T, wl.B, wl.D, emb.DTYPES[wl.dtype],
                          emb.MODES[wl.mode], batch.num_lookups, 0,
                          max(wl.rows))
     emb.emb_bag_forward(desc, arena, toff, idx, off, w, out)
@@ -53,7 +53,7 @@ def test_cfg1_whole_output(oracle):
 @pytest.mark.parametrize("name,nsample", [("cfg2", 2000), ("cfg3", 600), ("cfg4", 600),
                                           ("cfg5", 600), ("paper", 400), ("cfg3_weighted", 300),
                                           ("cfg3_u8", 300), ("onehot", 3000), ("short", 3000),
-                                          ("cfg3_max", 300)])
+                                          ("cfg3_max", 300), ("cfg3_fp8", 300)])
 def test_full_size_sampled_bags(oracle, name, nsample):
     print(f"\n[fullsize] {name}: generating", flush=True)
     wl = gen.workload(name)
@@ -71,7 +71,7 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     bags = _sample_bags(wl, nsample)
     small, ix, soff, wsmall = gen.compact_rows(wl, batch, bags)
     ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, soff, len(bags),
-                                wl.mode, weights=wsmall)
+                                wl.mode, weights=wsmall, codes=wl.codes)
     sel = torch.from_numpy(np.stack([bags % wl.B, bags // wl.B], 1)).to(DEV)
     got = out.view(wl.B, wl.T, wl.D)[sel[:, 0], sel[:, 1]].cpu().numpy()
     worst = assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"{name} sampled")
@@ -87,7 +87,7 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     assert np.array_equal(hints.cpu().numpy(), rh)
     expect = np.array([1 if d[0] == "uniform" else 0 for d in wl.dists], dtype=np.uint8)
     assert np.array_equal(rh, expect), "uniform tables stream, skewed tables stay cached"
-    hdesc = emb.make_desc(wl.T, wl.B, wl.D, {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16, "u8row": emb.EMB_U8ROW}[wl.dtype],
+    hdesc = emb.make_desc(wl.T, wl.B, wl.D, emb.DTYPES[wl.dtype],
                           emb.MODES[wl.mode], batch.num_lookups,
                           0, max(wl.rows), hints)
     emb.emb_bag_forward(hdesc, arena, toff, idx, off, w, out2)

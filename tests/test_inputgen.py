@@ -165,3 +165,33 @@ def test_hotness_ladder_matches_the_papers_unique_access_table():
         wl = gen.workload(name)
         assert wl.T == sum(counts) == 250
         assert sum(d[0] == "uniform" for d in wl.dists) == counts[3]
+
+
+def test_quantised_row_generators():
+    """Row-wise quantised rows from the generator: layout, code ranges, scale and bias rules."""
+    rows = np.arange(5000, dtype=np.uint64)
+    for dtype in ("u8row", "fp8row"):
+        for kind in (gen.KIND_NORMAL, gen.KIND_INT):
+            t = gen.table_values(0x5EED, rows, 24, dtype, kind)
+            assert t.dtype == np.uint8 and t.shape == (5000, 32)
+            assert np.array_equal(t, gen.table_values(0x5EED, rows, 24, dtype, kind))
+            scale = t[:, 24:28].copy().view(np.float32).ravel()
+            bias = t[:, 28:32].copy().view(np.float32).ravel()
+            codes = t[:, :24]
+            if kind == gen.KIND_INT:
+                assert np.all(scale == 1.0)
+                assert np.all(bias == (-128.0 if dtype == "u8row" else -1.0))
+            else:
+                assert np.all(scale > 0) and len(np.unique(scale)) > 100
+                assert np.allclose(bias, scale * (-128.0 if dtype == "u8row" else -32.0), rtol=1e-6)
+            if dtype == "fp8row":
+                assert not np.any((codes & 0x7F) == 0x7F)            # the two NaN codes never occur
+                if kind == gen.KIND_INT:
+                    assert not np.any(codes & 0x40)                  # exponent below 8: |value| < 2
+                else:
+                    assert len(np.unique(codes)) == 254
+            else:
+                assert len(np.unique(codes)) == 256
+    # a different table seed gives different codes
+    assert not np.array_equal(gen.table_values(1, rows[:50], 24, "fp8row"),
+                              gen.table_values(2, rows[:50], 24, "fp8row"))

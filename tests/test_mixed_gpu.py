@@ -9,7 +9,7 @@ from gpu_harness import DEV, assert_close_to_oracle, to_dev, tuning
 
 pytestmark = pytest.mark.gpu
 
-EDT = {"f32": emb.EMB_F32, "f16": emb.EMB_F16, "bf16": emb.EMB_BF16, "u8row": emb.EMB_U8ROW}
+EDT = emb.DTYPES
 
 
 def _device_arena(wl):

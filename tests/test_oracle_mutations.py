@@ -23,7 +23,7 @@ MUTATIONS = {
     "quantised scale and bias swapped": ("memcpy(&scale, row + D, sizeof scale);\n    memcpy(&bias, row + D + 4, sizeof bias);",
                                          "memcpy(&bias, row + D, sizeof scale);\n    memcpy(&scale, row + D + 4, sizeof bias);"),
     "quantised row stride without the scale and bias": ("(const uint8_t*)tables + arena_row * (D + 8);", "(const uint8_t*)tables + arena_row * D;"),
-    "quantised code read as signed": ("(double)scale * (double)row[d];", "(double)scale * (double)(int8_t)row[d];"),
+    "quantised code read as signed": ("dtype == 3 ? (double)row[d] :", "dtype == 3 ? (double)(int8_t)row[d] :"),
     "quantised bound forgets the bias": ("*magnitude = fabs(sc) + fabs((double)bias);", "*magnitude = fabs(sc);"),
     "table base ignored": ("table_offsets[t] + indices[j], D, d, &ax)", "indices[j], D, d, &ax)"),
     "first lookup of a bag skipped": ("for (int64_t j = s; j < e; ++j) {", "for (int64_t j = s + 1; j < e; ++j) {"),
@@ -42,11 +42,16 @@ MUTATIONS = {
                                              "x = (double)((const float*)tables)[arena_row * (D - 1) + d];"),
     "half exponent bias off by one": ("expo - 25", "expo - 24"),
     "half subnormal scale off by one": ("ldexp((double)frac, -24)", "ldexp((double)frac, -25)"),
-    "half sign dropped": ("return sign ? -v : v;", "return v;"),
+    "half sign dropped": ("(1 + frac/1024) * 2^(expo-15) */\n  return sign ? -v : v;", "(1 + frac/1024) * 2^(expo-15) */\n  return v;"),
     "bfloat16 shifted one bit short": ("const uint32_t u = (uint32_t)h << 16;", "const uint32_t u = (uint32_t)h << 15;"),
     "max keeps the smaller element": ("if (j == s || x > acc) {", "if (j == s || x < acc) {"),
     "max starts from zero instead of the first element": ("if (j == s || x > acc) {", "if (x > acc) {"),
     "max bound not taken from the selected element": ("            acc = x;\n            mag = ax;", "            acc = x;\n            mag += ax;"),
+    "e4m3 exponent bias off by one": ("ldexp((double)(8 + frac), expo - 10)", "ldexp((double)(8 + frac), expo - 11)"),
+    "e4m3 subnormal scale off by one": ("ldexp((double)frac, -9)", "ldexp((double)frac, -10)"),
+    "e4m3 sign dropped": ("(1 + frac/8) * 2^(expo-7) */\n  return sign ? -v : v;", "(1 + frac/8) * 2^(expo-7) */\n  return v;"),
+    "e4m3 treats the whole top exponent as NaN": ("else if (expo == 15 && frac == 7)", "else if (expo == 15)"),
+    "e4m3 codes read as integers": ("const double code = dtype == 3 ? (double)row[d] : e4m3_bits_to_double(row[d]);", "const double code = (double)row[d];"),
     "weights applied in mean mode only": ("const double w = weights ? (double)weights[j] : 1.0;",
                                           "const double w = (weights && mode == 1) ? (double)weights[j] : 1.0;"),
 }
@@ -67,6 +72,9 @@ PIN_FUNCS = [
     pins.test_bfloat16_widening_is_exact,
     pins.test_quantised_rows_brute_force,
     pins.test_quantised_rows_equal_their_dequantised_table,
+    pins.test_e4m3_values_typed_in,
+    pins.test_e4m3_every_code_against_torch,
+    pins.test_e4m3_rows_brute_force,
     pins.test_max_hand_worked,
     lambda o: pins.test_max_brute_force(o, np.float32),
     pins.test_max_invariants,

@@ -615,3 +615,86 @@ def test_max_of_quantised_rows_is_the_max_of_the_dequantised_table(oracle):
             want = deq[toff[t] + seg].max(axis=0) if len(seg) else np.zeros(D)
             assert np.allclose(ref[b, t * D:(t + 1) * D], want, rtol=1e-15, atol=0)
     assert np.all(bound >= np.abs(ref) - 1e-12)
+
+
+# ------------------------------------------------------------------------------------------
+# quantised rows with E4M3 8-bit floating-point codes (OCP 8-bit floating point, E4M3 variant)
+# ------------------------------------------------------------------------------------------
+def _one_row_lookup(oracle, codes, scale=1.0, bias=0.0):
+    """Look up a single quantised row holding `codes` and return its elements."""
+    D = len(codes)
+    pad = (-(D + 8)) % 16
+    row = np.zeros((1, D + pad + 8), dtype=np.uint8)
+    row[0, :D] = codes
+    row[0, D + pad:D + pad + 4] = np.array([scale], np.float32).view(np.uint8)
+    row[0, D + pad + 4:] = np.array([bias], np.float32).view(np.uint8)
+    ref, bound = oracle.emb_bag(row, np.array([0, 1], np.int64), np.array([0], np.int64),
+                                np.array([0, 1], np.int64), 1, "sum", codes="fp8")
+    return ref[0, :D], bound[0, :D]
+
+
+def test_e4m3_values_typed_in(oracle):
+    """Bit patterns and values from the format's definition: bias 7, 3 fraction bits, subnormals
+    m * 2^-9, largest finite 448, no infinities."""
+    cases = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x38: 1.0,
+             0x3C: 1.5, 0x40: 2.0, 0x7E: 448.0, 0x77: 240.0, 0x78: 256.0, 0x81: -(2.0 ** -9),
+             0xB8: -1.0, 0xFE: -448.0, 0x30: 0.5, 0x3F: 1.875}
+    codes = np.array(sorted(cases), dtype=np.uint8)
+    vals, bound = _one_row_lookup(oracle, codes)
+    assert vals.tolist() == [cases[int(c)] for c in codes]
+    assert bound.tolist() == [abs(cases[int(c)]) for c in codes]
+    nan, _ = _one_row_lookup(oracle, np.array([0x7F, 0xFF], np.uint8))
+    assert np.isnan(nan).all()
+
+
+def test_e4m3_every_code_against_torch(oracle):
+    """Second opinion on all 256 codes: torch's float8_e4m3fn, widened on the CPU."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    want = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    vals, _ = _one_row_lookup(oracle, codes)
+    finite = ~np.isnan(want)
+    assert finite.sum() == 254 and np.array_equal(vals[finite], want[finite])
+    assert np.isnan(vals[~finite]).all()
+    # scale and bias apply as for integer codes: element = scale * value + bias, bound from both terms
+    vals, bound = _one_row_lookup(oracle, codes[finite], scale=0.25, bias=-3.0)
+    assert np.array_equal(vals, 0.25 * want[finite] - 3.0)
+    assert np.array_equal(bound, 0.25 * np.abs(want[finite]) + 3.0)
+
+
+def test_e4m3_rows_brute_force(oracle):
+    rng = np.random.default_rng(41)
+    R, D, B = 9, 8, 4
+    table, scale, bias = _quantised_table(rng, R, D)
+    table[:, :D][(table[:, :D] & 0x7F) == 0x7F] = 0x3A         # no NaN codes
+    toff = np.array([0, 5, 9], dtype=np.int64)
+    lengths = np.array([3, 0, 2, 4, 1, 0, 5, 2])
+    offsets = gen.lengths_to_offsets(lengths)
+    idx = np.concatenate([rng.integers(0, 5, size=lengths[:4].sum()),
+                          rng.integers(0, 4, size=lengths[4:].sum())]).astype(np.int64)
+
+    def value(c):                                             # straight from the definition
+        s, e, m = c >> 7, (c >> 3) & 15, c & 7
+        v = Fraction(m, 8) * Fraction(1, 64) if e == 0 else (1 + Fraction(m, 8)) * Fraction(2) ** (e - 7)
+        return -v if s else v
+
+    for mode in ("sum", "mean", "max"):
+        ref, bound = oracle.emb_bag(table, toff, idx, offsets, B, mode, codes="fp8")
+        for t in range(2):
+            for b in range(B):
+                lo, hi = int(offsets[t * B + b]), int(offsets[t * B + b + 1])
+                for d in range(D):
+                    terms = []
+                    for j in range(lo, hi):
+                        r = int(toff[t]) + int(idx[j])
+                        sc = Fraction(float(scale[r])) * value(int(table[r, d]))
+                        terms.append((sc + Fraction(float(bias[r])), abs(sc) + abs(Fraction(float(bias[r])))))
+                    if mode == "max":
+                        a, m = max(terms, key=lambda x: x[0]) if terms else (Fraction(0), Fraction(0))
+                    else:
+                        a, m = sum(x[0] for x in terms), sum(x[1] for x in terms)
+                        if mode == "mean" and terms:
+                            a, m = a / len(terms), m / len(terms)
+                    tol = 16 * 2.0 ** -53 * float(m) + 1e-300
+                    assert abs(ref[b, t * D + d] - float(a)) <= tol
+                    assert abs(bound[b, t * D + d] - float(m)) <= tol
