@@ -171,7 +171,10 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
  *   Adds to *num_bad (DEVICE, one int64 that the caller has zeroed, on the same stream) one for
  *   every bag whose bounds are decreasing or outside [0, NL], one if offsets[0] != 0 or
  *   offsets[T*B] != NL, and one for every lookup whose index is outside [0, R_t).
- *   Same pointer meanings as emb_bag_forward; asynchronous on `stream`.
+ *   Same pointer meanings as emb_bag_forward; asynchronous on `stream`.  Only table_offsets'
+ *   differences (the row counts R_t), num_tables, batch and num_lookups are used, so a batch for
+ *   emb_bag_forward_mixed is checked with a descriptor of any valid dim and the cumulative row
+ *   counts of its tables as table_offsets.
  */
 int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
                      const int64_t* indices, const int64_t* offsets, int64_t* num_bad,
@@ -190,7 +193,9 @@ int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
  *   uniform-random access (the paper's "random" dataset) shows practically no repeats, the
  *   power-law datasets show many.  threshold_permille < 0 selects the library default (20).
  *
- *   desc, indices, offsets   as in emb_bag_forward (desc->table_hints is ignored)
+ *   desc, indices, offsets   as in emb_bag_forward (desc->table_hints is ignored; only
+ *                            num_tables, batch and num_lookups matter, so any valid dim serves
+ *                            for tables of different widths)
  *   dup_count, window_used   DEVICE int32 [T] each, or NULL
  *   hints                    DEVICE uint8 [T], or NULL
  *   Asynchronous on `stream`; counts are exact and deterministic.

@@ -166,3 +166,48 @@ def test_mixed_width_balanced_xcd_order(oracle, T):
         ordered = _forward(wl, arena, batch).cpu().numpy()
     assert_close_to_oracle(ordered, ref, bound, False, f"mixed order T={T}")
     assert np.array_equal(natural, ordered)
+
+
+def test_mixed_batches_validate_profile_and_replay_from_a_graph(oracle):
+    """The checker and the reuse profiler read only ids and bag bounds, so a uniform descriptor of
+    any width and the cumulative row counts serve a mixed-width batch; and the mixed launch (its
+    table order travels by value in the kernel arguments) replays from a HIP graph."""
+    wl = gen.mixed_workload("mixed_small")
+    batch = gen.make_batches(wl, 1)[0]
+    tabs = gen.mixed_host_tables(wl)
+    arena = _device_arena(wl)
+    rows = to_dev(wl.row_bases())
+    idx, off = to_dev(batch.indices), to_dev(batch.offsets)
+    udesc = emb.make_desc(wl.T, wl.B, 4, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups, 0, max(wl.rows))
+    bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    emb.emb_bag_validate(udesc, rows, idx, off, bad)
+    hints = torch.zeros(wl.T, dtype=torch.uint8, device=DEV)
+    emb.emb_bag_profile_reuse(udesc, idx, off, 4096, -1, None, None, hints)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+    from oracle import reuse_oracle
+    assert np.array_equal(hints.cpu().numpy(),
+                          reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B, 4096, 20)[2])
+    bad_idx = idx.clone()
+    bad_idx[0] = wl.rows[0]                                 # one past the end of table 0
+    bad.zero_()
+    emb.emb_bag_validate(udesc, rows, bad_idx, off, bad)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 1
+
+    ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, "sum")
+    out = torch.empty((wl.B, int(sum(wl.dims))), dtype=torch.float32, device=DEV)
+    desc = emb.make_mixed_desc(wl.dims, wl.B, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups, 0,
+                               int(np.diff(wl.table_byte_offsets()).max()), hints)
+    boff, ooff = to_dev(wl.table_byte_offsets()), to_dev(wl.out_offsets())
+    with tuning(xcd_remap=1):
+        stream = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            emb.emb_bag_forward_mixed(desc, arena, boff, ooff, idx, off, None, out, stream)
+    for _ in range(3):
+        out.fill_(-1.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, "mixed graph replay")
