@@ -48,6 +48,9 @@ DESCRIPTIONS = {
     "paper_mix1": "paper's model, Mix1: 100 high / 75 med / 50 low / 25 random tables",
     "paper_mix2": "paper's model, Mix2: 62 / 63 / 63 / 62",
     "paper_mix3": "paper's model, Mix3: 25 / 50 / 75 / 100",
+    "mixed_onehot": "26 fp32 tables x 1,000,000 rows, widths cycling 16 / 32 / 64 / 128, batch 131072, "
+                    "ONE lookup per bag, uniform indices, sum: emb_bag_forward_mixed splits the call "
+                    "into one stream-kernel launch per lanes-per-row class",
     "mixed_cfg": "60 fp32 tables x 4,000,000 rows, widths cycling 32 / 64 / 128 / 256 (115.2 GB), "
                  "batch 4096, pooling 80 fixed, uniform indices, sum, one emb_bag_forward_mixed launch",
 }
@@ -402,6 +405,12 @@ def main() -> int:
         log(f"cpu baseline: {cpu_baseline}")
         del host
 
+    if mixed:   # a mixed-width call may make several launches
+        n_launch = emb.emb_bag_plan_forward_mixed(descs[0], wl.weighted).num_launches
+        launch_plan = [emb.emb_bag_plan_forward_mixed(descs[0], wl.weighted, which=w).as_dict()
+                       for w in range(n_launch)]
+    else:
+        launch_plan = emb.emb_bag_plan_forward(descs[0], wl.weighted).as_dict()
     traffic = read_traffic(wl.name)
     result = {
         "metric": "embedding lookups/sec and effective gathered HBM GB/s (% of peak), 1 MI355X",
@@ -423,8 +432,7 @@ def main() -> int:
                    "lookups_per_step": avg_lookups, "index_batches_rotated": len(batches),
                    "arena_allocation": arena_kind,
                    "streaming_tables": None if hints is None else int(hints.sum().item()),
-                   "launch_plan": (emb.emb_bag_plan_forward_mixed if mixed else
-                                   emb.emb_bag_plan_forward)(descs[0], wl.weighted).as_dict(),
+                   "launch_plan": launch_plan,
                    "tuning": {k: emb.emb_bag_get_tuning(k) for k in
                               ("depth", "addressing", "blocks_per_cu", "xcd_remap", "use_hints",
                                "stream", "bags_per_group")}},

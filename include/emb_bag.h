@@ -129,7 +129,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
  * emb_bag_forward_mixed - the same pooled lookup for tables of DIFFERENT widths D_t.
  *
  *   The paper's tables are homogeneous (Sec. 5); production models mix widths.  Table t holds
- *   rows of D_t elements (row = D_t * sizeof(element) bytes, D_t + 8 for EMB_U8ROW; every row size
+ *   rows of D_t elements (row = D_t * sizeof(element) bytes, D_t + 8 for quantised rows; every row size
  *   a multiple of 16 and at most 1024 bytes) stored contiguously from BYTE offset
  *   table_byte_offsets[t] of the arena (R_t = (table_byte_offsets[t+1] - table_byte_offsets[t]) /
  *   row bytes), and its result occupies output columns [out_offsets[t], out_offsets[t+1]) with
@@ -145,10 +145,16 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
  * table_byte_offsets and out_offsets describe the model, not the batch, and are trusted the way
  * table_offsets is; a table whose entries contradict the rules above is skipped (nothing is
  * written for it).  Index and bag-bound defects are neutralised as in emb_bag_forward.
+ *
+ * One call is one kernel launch unless bags are short (see the "stream" tuning key): then the
+ * tables are grouped by row size (64, 128, 256, 512, 1024 bytes and below), every group the
+ * short-bag kernel suits gets a launch of its own and the other tables share one; the launches
+ * write disjoint columns and are enqueued on `stream` one after the other
+ * (emb_bag_plan_forward_mixed lists them).  More than 65535 tables are refused in that case.
  */
 typedef struct emb_bag_mixed_desc {
   int32_t num_tables;      /* T >= 1 */
-  int32_t table_dtype;     /* EMB_F32, EMB_F16, EMB_BF16 or EMB_U8ROW (one type for all tables) */
+  int32_t table_dtype;     /* EMB_F32 ... EMB_FP8ROW (one type for all tables) */
   int32_t mode;            /* EMB_SUM, EMB_MEAN or EMB_MAX */
   int32_t reserved;        /* 0 */
   int64_t batch;           /* B >= 0 */
@@ -214,17 +220,22 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
  *   desc         HOST   as for the forward call (table_hints is only tested against NULL)
  *   has_weights  non-zero if the forward call would pass per_sample_weights
  *   plan         HOST   filled in; all zero for batch == 0
- *   table_order  HOST   uint16 [min(T, 1024)] or NULL: the table at each position of the
- *                       XCD-affine order (the identity unless plan->xcd_ordered)
- *   Returns the status the forward call would return for the descriptor alone.
+ *   which        (mixed only) which of the call's launches to describe, 0 .. num_launches - 1;
+ *                       emb_bag_forward always makes one launch, emb_bag_forward_mixed makes
+ *                       several when bags are short: one stream-kernel launch per lanes-per-row
+ *                       class that kernel suits, one wave-kernel launch for the other tables
+ *   table_order  HOST   uint16 [min(T, 1024)] or NULL: the table at each of the launch's
+ *                       plan->tables positions (the identity unless plan->listed)
+ *   Returns the status the forward call would return for the descriptor alone
+ *   (EMB_ERR_BAD_SIZE for a `which` beyond the last launch).
  *
  * Block order, when xcd_pieces > 0: workgroup g runs on XCD g % 8; with slot = g / 8,
  * unit = (slot / blocks_per_piece) * 8 + g % 8 is piece unit % xcd_pieces of the table at
- * position unit / xcd_pieces, and wavefront w of workgroup (slot % blocks_per_piece) of that
+ * position unit / xcd_pieces of the launch, and wavefront w of workgroup (slot % blocks_per_piece) of that
  * piece is wavefront (unit % xcd_pieces) * waves_per_piece + (slot % blocks_per_piece) * 4 + w
  * of the table if that number is below waves_per_piece within the piece and below
  * waves_per_table overall (otherwise it has no work).  With xcd_pieces == 0 wavefront
- * 4 * g + w of the grid is wavefront number 4 * g + w in table-major order.
+ * 4 * g + w of the grid is wavefront number 4 * g + w in position-major order.
  */
 #define EMB_KERNEL_WAVE 0   /* one wavefront per bag (per 1-KiB column slab of it) */
 #define EMB_KERNEL_STREAM 1 /* short bags: a lane group streams consecutive bags */
@@ -236,18 +247,21 @@ typedef struct emb_bag_plan {
   int32_t buffer_addressing; /* 1 = 32-bit buffer offsets with hardware range check, 0 = 64-bit */
   int32_t bags_per_group;    /* stream kernel: consecutive bags per lane group; else 0 */
   int32_t xcd_pieces;        /* pieces per table in XCD-affine order; 0 = natural order */
-  int32_t xcd_ordered;       /* 1 = tables dealt to XCDs by width (see table_order) */
-  int32_t reserved;
+  int32_t listed;            /* 1 = the launch takes its tables from a list (see table_order):
+                                a subset of the tables, or all of them dealt to XCDs by width */
+  int32_t num_launches;      /* launches the forward call makes (1 unless tables of different
+                                widths with short bags are split by lanes-per-row class) */
   int64_t grid_blocks;       /* 256-thread workgroups launched */
   int64_t wavefronts;        /* wavefronts that have work */
   int64_t waves_per_table;
   int64_t waves_per_piece;   /* XCD-affine order only */
   int64_t blocks_per_piece;  /* XCD-affine order only */
+  int64_t tables;            /* tables (positions) this launch covers */
 } emb_bag_plan;
 
 int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, emb_bag_plan* plan,
                          uint16_t* table_order);
-int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights,
+int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, int32_t which,
                                emb_bag_plan* plan, uint16_t* table_order);
 
 /*

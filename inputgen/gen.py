@@ -386,6 +386,12 @@ def mixed_workload(name: str) -> MixedWorkload:
                              dims=tuple((32, 64, 128, 256)[t % 4] for t in range(T)), dtype="f32",
                              B=4096, pooling=("fixed", 80), dists=(("uniform",),) * T,
                              seed=0x5EED0C02)
+    if name == "mixed_onehot":   # 26 tables x 1 M rows, widths cycling 16 / 32 / 64 / 128, one lookup per bag
+        T = 26
+        return MixedWorkload(name=name, T=T, rows=(1_000_000,) * T,
+                             dims=tuple((16, 32, 64, 128)[t % 4] for t in range(T)), dtype="f32",
+                             B=131072, pooling=("fixed", 1), dists=(("uniform",),) * T,
+                             seed=0x5EED0C03)
     raise KeyError(name)
 
 

@@ -50,13 +50,13 @@ class emb_bag_plan(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int32), ("lanes_per_row", ctypes.c_int32),
                 ("depth", ctypes.c_int32), ("buffer_addressing", ctypes.c_int32),
                 ("bags_per_group", ctypes.c_int32), ("xcd_pieces", ctypes.c_int32),
-                ("xcd_ordered", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("listed", ctypes.c_int32), ("num_launches", ctypes.c_int32),
                 ("grid_blocks", ctypes.c_int64), ("wavefronts", ctypes.c_int64),
                 ("waves_per_table", ctypes.c_int64), ("waves_per_piece", ctypes.c_int64),
-                ("blocks_per_piece", ctypes.c_int64)]
+                ("blocks_per_piece", ctypes.c_int64), ("tables", ctypes.c_int64)]
 
     def as_dict(self) -> dict:
-        return {name: int(getattr(self, name)) for name, _ in self._fields_ if name != "reserved"}
+        return {name: int(getattr(self, name)) for name, _ in self._fields_}
 
 
 class EmbBagError(RuntimeError):
@@ -80,7 +80,7 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
                                          ctypes.POINTER(emb_bag_plan), P]
     lib.emb_bag_plan_forward_mixed.restype = ctypes.c_int
     lib.emb_bag_plan_forward_mixed.argtypes = [ctypes.POINTER(emb_bag_mixed_desc), ctypes.c_int,
-                                               ctypes.POINTER(emb_bag_plan), P]
+                                               ctypes.c_int32, ctypes.POINTER(emb_bag_plan), P]
     lib.emb_bag_validate.restype = ctypes.c_int
     lib.emb_bag_validate.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, P, P, P]
     lib.emb_bag_profile_reuse.restype = ctypes.c_int
@@ -171,14 +171,14 @@ def emb_bag_forward_mixed(desc: emb_bag_mixed_desc, tables: torch.Tensor,
         raise EmbBagError(rc, "emb_bag_forward_mixed")
 
 
-def _plan(fn, where: str, desc, has_weights: bool, with_order: bool):
+def _plan(fn, where: str, desc, has_weights: bool, with_order: bool, *which):
     plan = emb_bag_plan()
     n = min(int(desc.num_tables), 1024)
     order = (ctypes.c_uint16 * max(n, 1))() if with_order else None
-    rc = fn(ctypes.byref(desc), int(bool(has_weights)), ctypes.byref(plan), order)
+    rc = fn(ctypes.byref(desc), int(bool(has_weights)), *which, ctypes.byref(plan), order)
     if rc != EMB_OK:
         raise EmbBagError(rc, where)
-    return (plan, list(order)[:n]) if with_order else plan
+    return (plan, list(order)[:int(plan.tables)]) if with_order else plan
 
 
 def emb_bag_plan_forward(desc: emb_bag_desc, has_weights: bool = False, with_order: bool = False):
@@ -188,10 +188,11 @@ def emb_bag_plan_forward(desc: emb_bag_desc, has_weights: bool = False, with_ord
 
 
 def emb_bag_plan_forward_mixed(desc: emb_bag_mixed_desc, has_weights: bool = False,
-                               with_order: bool = False):
-    """What emb_bag_forward_mixed would launch for `desc` (host only, no GPU needed)."""
+                               with_order: bool = False, which: int = 0):
+    """Launch number `which` of what emb_bag_forward_mixed would do for `desc` (host only, no GPU
+    needed); plan.num_launches says how many there are."""
     return _plan(_lib.emb_bag_plan_forward_mixed, "emb_bag_plan_forward_mixed", desc, has_weights,
-                 with_order)
+                 with_order, int(which))
 
 
 def emb_bag_validate(desc: emb_bag_desc, table_offsets: torch.Tensor, indices: torch.Tensor,

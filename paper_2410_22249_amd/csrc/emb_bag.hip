@@ -37,6 +37,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <vector>
+
 #include "../../include/emb_bag.h"
 #include "emb_bag_device.h"
 
@@ -62,16 +64,15 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
 
   const int lane = threadIdx.x & (kWaveSize - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  uint32_t work;
-  if (!decode_work(p, wave, MIXED, order, &work)) return;
-
-  uint32_t bag = work, slab = 0;
+  uint32_t tpos, w_in_table;
+  if (!decode_work(p, wave, &tpos, &w_in_table)) return;
+  const uint32_t t = (MIXED && p.listed) ? order.t[tpos] : tpos;
+  uint32_t b = w_in_table, slab = 0;
   if (p.slabs > 1) {
-    bag = work / p.slabs;
-    slab = work - bag * p.slabs;
+    b = w_in_table / p.slabs;
+    slab = w_in_table - b * p.slabs;
   }
-  const uint32_t t = bag / p.B;
-  const uint32_t b = bag - t * p.B;
+  const uint32_t bag = t * p.B + b;
 
   // bag bounds, clamped so that no index read can leave [0, NL)
   int64_t s = uniform64(offsets[bag]);
@@ -330,7 +331,8 @@ int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
 struct Launch {
   KernelFn fn = nullptr;
   KParams p = {};
-  TableOrder order = {};  // only the first T entries are read, and only when p.xcd_ordered is set
+  TableOrder order = {};  // table at each position of the launch; read only when p.listed is set
+  int64_t tables = 0;     // positions of the launch
   uint32_t blocks = 0;
   int kernel = EMB_KERNEL_WAVE;
   int lpr = 0;
@@ -338,56 +340,79 @@ struct Launch {
   bool buf = false;
 };
 
-// Lay out the grid: natural order, or the XCD-affine order described at KParams.  row_units
-// (16-byte segments per row of each table) is given only when tables differ in width.
-void plan_grid(int64_t T, const uint16_t* row_units, bool natural_order, Launch* L) {
+// Lay out the grid of a launch over n tables (p.wpt wavefronts each): natural order, or the
+// XCD-affine order described at KParams.  `ids` names the tables (nullptr: tables 0 .. n-1 in
+// their own order); `row_units` (16-byte segments per row, indexed like ids) is given only when
+// the tables of the launch differ in width, and then n <= kMaxOrdered unless natural_order.
+void plan_grid(int64_t n, const uint16_t* ids, const uint16_t* row_units, bool natural_order,
+               Launch* L) {
   KParams& p = L->p;
-  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = p.xcd_ordered = 0;
+  L->tables = n;
+  p.num_work = (uint32_t)(n * (int64_t)p.wpt);
+  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = p.listed = 0;
   uint32_t blocks = (uint32_t)(((uint64_t)p.num_work + kWavesPerBlock - 1) / kWavesPerBlock);
   const bool remap = g_tuning.xcd_remap == 1 || (g_tuning.xcd_remap == -1 && blocks >= 4096);
+  bool ordered = false;
   if (remap && blocks >= 64 && !natural_order) {
-    // pieces per table: the smallest power of two that makes T * pieces a multiple of 8, so
+    // pieces per table: the smallest power of two that makes n * pieces a multiple of 8, so
     // that every XCD gets the same number of pieces and neighbouring XCDs share a table
     uint32_t pshift = 0;
-    while (((uint64_t)T << pshift) % 8 != 0) ++pshift;
+    while (((uint64_t)n << pshift) % 8 != 0) ++pshift;
     const uint64_t wpp = ((uint64_t)p.wpt + (1u << pshift) - 1) >> pshift;
     const uint64_t bpp = (wpp + kWavesPerBlock - 1) / kWavesPerBlock;
-    const uint64_t grid = ((uint64_t)T << pshift) * bpp;
+    const uint64_t grid = ((uint64_t)n << pshift) * bpp;
     // Tables of different widths: position q of the order runs on the XCD set q % sets.  Deal
     // the tables out widest first, each to the set with the least work so far, so that every
     // XCD ends up with about the same number of bytes.
     const uint32_t sets = 8u >> (pshift < 3 ? pshift : 3);
     const bool ok = grid <= 0x7FFFFFFFull;
-    const bool ordered = ok && row_units && sets > 1;
+    ordered = ok && row_units && sets > 1;
     if (ordered) {
       uint32_t head[66];  // counting sort by width, widest first
       for (int i = 0; i < 66; ++i) head[i] = 0;
-      for (int64_t t = 0; t < T; ++t) ++head[64 - row_units[t] + 1];
+      for (int64_t t = 0; t < n; ++t) ++head[64 - row_units[t] + 1];
       for (int i = 1; i < 66; ++i) head[i] += head[i - 1];
       uint16_t by_width[kMaxOrdered];
-      for (int64_t t = 0; t < T; ++t) by_width[head[64 - row_units[t]]++] = (uint16_t)t;
+      for (int64_t t = 0; t < n; ++t) by_width[head[64 - row_units[t]]++] = (uint16_t)t;
       uint64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
       uint32_t taken[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-      const uint32_t per_set = (uint32_t)(T / sets);  // exact: T * pieces is a multiple of 8
-      for (int64_t k = 0; k < T; ++k) {
+      const uint32_t per_set = (uint32_t)(n / sets);  // exact: n * pieces is a multiple of 8
+      for (int64_t k = 0; k < n; ++k) {
         const uint16_t t = by_width[k];
         uint32_t best = sets;
         for (uint32_t c = 0; c < sets; ++c)
           if (taken[c] < per_set && (best == sets || load[c] < load[best])) best = c;
-        L->order.t[best + sets * taken[best]] = t;
+        L->order.t[best + sets * taken[best]] = ids ? ids[t] : t;
         ++taken[best];
         load[best] += row_units[t];
       }
+      p.listed = 1;
     }
     if (ok) {
       p.xcd_bpp = (uint32_t)bpp;
       p.xcd_wpp = (uint32_t)wpp;
       p.xcd_pshift = pshift;
-      p.xcd_ordered = ordered ? 1u : 0u;
       blocks = (uint32_t)grid;
     }
   }
+  if (ids && !ordered) {  // a subset of the tables, in the order given
+    for (int64_t t = 0; t < n; ++t) L->order.t[t] = ids[t];
+    p.listed = 1;
+  }
   L->blocks = blocks;
+}
+
+// Consecutive bags per lane group of the stream kernel for an average bag length.
+int64_t stream_bags_per_group(double avg_len, int lpr, int64_t tables, int64_t B) {
+  const int groups = kWaveSize / lpr;
+  int64_t m = g_tuning.bags_per_group;
+  if (m == 0) {
+    m = (int64_t)(kStreamGroupLookups / (avg_len < 1.0 ? 1.0 : avg_len) + 0.5);
+    if (m > kStreamMaxAutoBags) m = kStreamMaxAutoBags;
+    while (m > 1 && tables * ((B + groups * m - 1) / (groups * m)) < kStreamMinWaves) m /= 2;
+  }
+  if (m > lpr - 1) m = lpr - 1;
+  return m < 1 ? 1 : m;
 }
 
 // Descriptor checks of emb_bag_forward that need no pointer: shape, mode, weights, out_ld.
@@ -447,17 +472,10 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
   if (g_tuning.stream != 0 && slabs == 1 && buf && desc->mode != EMB_MAX &&
       (g_tuning.stream == 1 || avg_len < kStreamBelowRowLoads * groups)) {
-    int64_t m = g_tuning.bags_per_group;
-    if (m == 0) {
-      m = (int64_t)(kStreamGroupLookups / (avg_len < 1.0 ? 1.0 : avg_len) + 0.5);
-      if (m > kStreamMaxAutoBags) m = kStreamMaxAutoBags;
-      while (m > 1 && T * ((B + groups * m - 1) / (groups * m)) < kStreamMinWaves) m /= 2;
-    }
-    if (m > lpr - 1) m = lpr - 1;
-    if (m < 1) m = 1;
+    const int64_t m = stream_bags_per_group(avg_len, lpr, T, B);
     // the wavefront's output rows are addressed through one buffer with 32-bit offsets
     if ((uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u <= kBufMaxBytes) {
-      L->fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted);
+      L->fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted, false);
       if (L->fn) {
         L->kernel = EMB_KERNEL_STREAM;
         L->depth = depth <= 4 || lpr < 8 ? 4 : 8;  // the depths that kernel is built with
@@ -473,7 +491,7 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
     L->fn = pick_kernel(lpr, desc->table_dtype, depth, op, buf);
   }
   if (!L->fn) return EMB_ERR_BAD_TUNING;
-  plan_grid(T, nullptr, false, L);
+  plan_grid(T, nullptr, nullptr, false, L);
   return EMB_OK;
 }
 
@@ -505,34 +523,27 @@ int precheck_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t* max_
   return EMB_OK;
 }
 
-// The host-side decisions of emb_bag_forward_mixed for a checked descriptor with batch > 0.
+// The host-side decisions of emb_bag_forward_mixed for a checked descriptor with batch > 0: one
+// launch of the wave kernel over all tables, or - with short bags - one launch of the stream
+// kernel per lanes-per-row class whose tables it suits, and one of the wave kernel for the rest.
+// A launch that needs a table list takes at most kMaxOrdered tables.
 int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_bytes,
-               int64_t out_ld, Launch* L) {
+               int64_t out_ld, std::vector<Launch>* launches) {
   const int64_t T = desc->num_tables, B = desc->batch;
   if (B > 0x7FFFFFFF || T * B > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
   const int elem_bytes = desc->table_dtype == EMB_F32 ? 4 : 2;
-  uint16_t row_units[kMaxOrdered];  // 16-byte segments per row, for the XCD-affine table order
-  bool widths_differ = false;
-  for (int64_t t = 0; t < T; ++t) {
-    const int64_t d = desc->dims[t];
-    const int64_t rb = is_quant(desc->table_dtype) ? d + 8 : d * elem_bytes;
-    if (t < kMaxOrdered) row_units[t] = (uint16_t)(rb / 16);
-    if (d != desc->dims[0]) widths_differ = true;
-  }
-  // more tables than the order holds: such a launch keeps the natural block order
-  const bool too_many = widths_differ && T > kMaxOrdered;
-
   bool buf = desc->max_table_bytes > 0 && (uint64_t)desc->max_table_bytes <= kBufMaxBytes;
   if (g_tuning.addressing == 1) buf = false;
   int depth = (int)g_tuning.depth;
   if (depth == 0) depth = (desc->table_dtype == EMB_F32 && max_row_bytes >= 512) ? 8 : 4;
+  const int op = desc->mode == EMB_MAX ? kOpMax : (weighted ? kOpWeighted : kOpSum);
 
-  KParams& p = L->p;
+  Launch base;
+  KParams& p = base.p;
   p.num_lookups = desc->num_lookups;
   p.out_ld = out_ld;
   p.max_rows = 0;
   p.B = (uint32_t)B;
-  p.num_work = (uint32_t)(T * B);
   p.wpt = (uint32_t)B;
   p.bags_per_group = 0;
   p.slabs = 1;
@@ -540,14 +551,85 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
   p.D = 0;
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
-  L->kernel = EMB_KERNEL_WAVE;
-  L->lpr = 0;
-  L->depth = depth <= 4 ? 4 : 8;  // the depths the mixed-width kernels are built with
-  L->buf = buf;
-  const int op = desc->mode == EMB_MAX ? kOpMax : (weighted ? kOpWeighted : kOpSum);
-  L->fn = pick_kernel(0, desc->table_dtype, depth, op, buf);
-  if (!L->fn) return EMB_ERR_BAD_TUNING;
-  plan_grid(T, widths_differ && !too_many ? row_units : nullptr, too_many, L);
+  base.kernel = EMB_KERNEL_WAVE;
+  base.lpr = 0;
+  base.depth = depth <= 4 ? 4 : 8;  // the depths the mixed-width kernels are built with
+  base.buf = buf;
+  base.fn = pick_kernel(0, desc->table_dtype, depth, op, buf);
+  if (!base.fn) return EMB_ERR_BAD_TUNING;
+
+  // which lanes-per-row classes (4, 8, 16, 32, 64) go to the stream kernel
+  const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
+  bool streams[7] = {false, false, false, false, false, false, false};  // by log2(lanes per row)
+  bool any_stream = false;
+  if (g_tuning.stream != 0 && buf && desc->mode != EMB_MAX) {
+    for (int lg = 2; lg <= 6; ++lg) {
+      const int groups = kWaveSize >> lg;
+      const int64_t m = stream_bags_per_group(avg_len, 1 << lg, T, B);
+      streams[lg] = (g_tuning.stream == 1 || avg_len < kStreamBelowRowLoads * groups) &&
+                    (uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u <= kBufMaxBytes;
+    }
+  }
+  std::vector<uint16_t> units((size_t)T);
+  std::vector<uint8_t> cls((size_t)T);
+  bool widths_differ = false;
+  for (int64_t t = 0; t < T; ++t) {
+    const int64_t d = desc->dims[t];
+    const int64_t rb = is_quant(desc->table_dtype) ? d + 8 : d * elem_bytes;
+    units[(size_t)t] = (uint16_t)(rb / 16);
+    int lg = 2;
+    while ((16 << lg) < rb) ++lg;
+    cls[(size_t)t] = (uint8_t)lg;
+    if (d != desc->dims[0]) widths_differ = true;
+    if (streams[lg]) any_stream = true;
+  }
+
+  if (!any_stream) {  // one launch of the wave kernel over all tables
+    launches->push_back(base);
+    // more tables than the list holds: such a launch keeps the natural block order
+    const bool too_many = widths_differ && T > kMaxOrdered;
+    plan_grid(T, nullptr, widths_differ && !too_many ? units.data() : nullptr, too_many,
+              &launches->back());
+    return EMB_OK;
+  }
+
+  // one group of tables per streamed class, one for everything else; pieces of <= kMaxOrdered
+  for (int lg = 1; lg <= 6; ++lg) {  // lg == 1 stands for "the wave kernel's tables"
+    if (lg >= 2 && !streams[lg]) continue;
+    std::vector<uint16_t> ids, u;
+    for (int64_t t = 0; t < T; ++t) {
+      const bool streamed = streams[cls[(size_t)t]];
+      if (lg == 1 ? !streamed : (streamed && cls[(size_t)t] == lg)) {
+        // table numbers above 65535 cannot be listed: the descriptor is refused below
+        ids.push_back((uint16_t)t);
+        u.push_back(units[(size_t)t]);
+      }
+    }
+    if (ids.empty()) continue;
+    if (T > 65535) return EMB_ERR_BAD_SIZE;
+    for (size_t first = 0; first < ids.size(); first += kMaxOrdered) {
+      const int64_t n = (int64_t)(ids.size() - first < (size_t)kMaxOrdered ? ids.size() - first
+                                                                            : (size_t)kMaxOrdered);
+      launches->push_back(base);
+      Launch& L = launches->back();
+      bool differ = false;
+      for (int64_t i = 1; i < n && !differ; ++i) differ = u[first + (size_t)i] != u[first];
+      if (lg >= 2) {
+        const int lpr = 1 << lg;
+        const int groups = kWaveSize / lpr;
+        const int64_t m = stream_bags_per_group(avg_len, lpr, n, B);
+        L.fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted, true);
+        if (!L.fn) return EMB_ERR_BAD_TUNING;
+        L.kernel = EMB_KERNEL_STREAM;
+        L.lpr = lpr;
+        L.depth = depth <= 4 || lpr < 8 ? 4 : 8;
+        L.p.row_bytes = (uint32_t)lpr * 16u;
+        L.p.bags_per_group = (uint32_t)m;
+        L.p.wpt = (uint32_t)((B + groups * m - 1) / (groups * m));
+      }
+      plan_grid(n, ids.data() + first, differ ? u.data() + first : nullptr, false, &L);
+    }
+  }
   return EMB_OK;
 }
 
@@ -577,23 +659,24 @@ int launch(const Launch& L, const void* tables, const int64_t* table_offsets,
 }
 
 // What emb_bag_plan_forward* report about a planned launch.
-void report(const Launch& L, int64_t T, emb_bag_plan* plan, uint16_t* table_order) {
+void report(const Launch& L, int32_t num_launches, emb_bag_plan* plan, uint16_t* table_order) {
   plan->kernel = L.kernel;
   plan->lanes_per_row = L.lpr;
   plan->depth = L.depth;
   plan->buffer_addressing = L.buf ? 1 : 0;
   plan->bags_per_group = (int32_t)L.p.bags_per_group;
   plan->xcd_pieces = L.p.xcd_bpp ? (int32_t)(1u << L.p.xcd_pshift) : 0;
-  plan->xcd_ordered = (int32_t)L.p.xcd_ordered;
-  plan->reserved = 0;
+  plan->listed = (int32_t)L.p.listed;
+  plan->num_launches = num_launches;
   plan->grid_blocks = L.blocks;
   plan->wavefronts = L.p.num_work;
   plan->waves_per_table = L.p.wpt;
   plan->waves_per_piece = L.p.xcd_wpp;
   plan->blocks_per_piece = L.p.xcd_bpp;
+  plan->tables = L.tables;
   if (table_order)
-    for (int64_t t = 0; t < T && t < kMaxOrdered; ++t)
-      table_order[t] = L.p.xcd_ordered ? L.order.t[t] : (uint16_t)t;
+    for (int64_t t = 0; t < L.tables && t < kMaxOrdered; ++t)
+      table_order[t] = L.p.listed ? L.order.t[t] : (uint16_t)t;
 }
 
 }  // namespace
@@ -632,11 +715,15 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   if (desc->num_lookups > 0 && !indices) return EMB_ERR_NULL_PTR;
   if ((reinterpret_cast<uintptr_t>(tables) | reinterpret_cast<uintptr_t>(out)) & 15)
     return EMB_ERR_ALIGNMENT;
-  Launch L;
-  rc = plan_mixed(desc, per_sample_weights != nullptr, max_row_bytes, out_ld, &L);
+  std::vector<Launch> launches;
+  rc = plan_mixed(desc, per_sample_weights != nullptr, max_row_bytes, out_ld, &launches);
   if (rc != EMB_OK) return rc;
-  return launch(L, tables, table_byte_offsets, indices, offsets, per_sample_weights,
+  for (const Launch& L : launches) {  // disjoint tables: the launches are independent
+    rc = launch(L, tables, table_byte_offsets, indices, offsets, per_sample_weights,
                 desc->table_hints, out_offsets, out, stream);
+    if (rc != EMB_OK) return rc;
+  }
+  return EMB_OK;
 }
 
 int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, emb_bag_plan* plan,
@@ -651,11 +738,11 @@ int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, emb_bag_plan
   Launch L;
   rc = plan_uniform(desc, has_weights != 0, row_bytes, out_ld, &L);
   if (rc != EMB_OK) return rc;
-  report(L, desc->num_tables, plan, table_order);
+  report(L, 1, plan, table_order);
   return EMB_OK;
 }
 
-int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights,
+int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, int32_t which,
                                emb_bag_plan* plan, uint16_t* table_order) {
   if (!plan) return EMB_ERR_NULL_PTR;
   memset(plan, 0, sizeof *plan);
@@ -664,10 +751,11 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights,
   int rc = precheck_mixed(desc, has_weights != 0, &max_row_bytes, &out_ld);
   if (rc != EMB_OK) return rc;
   if (desc->batch == 0) return EMB_OK;
-  Launch L;
-  rc = plan_mixed(desc, has_weights != 0, max_row_bytes, out_ld, &L);
+  std::vector<Launch> launches;
+  rc = plan_mixed(desc, has_weights != 0, max_row_bytes, out_ld, &launches);
   if (rc != EMB_OK) return rc;
-  report(L, desc->num_tables, plan, table_order);
+  if (which < 0 || (size_t)which >= launches.size()) return EMB_ERR_BAD_SIZE;
+  report(launches[(size_t)which], (int32_t)launches.size(), plan, table_order);
   return EMB_OK;
 }
 

@@ -39,13 +39,15 @@ struct KParams {
   uint32_t xcd_bpp;
   uint32_t xcd_wpp;
   uint32_t xcd_pshift;
-  uint32_t xcd_ordered;  // 1 = position q of the XCD-affine order holds table TableOrder::t[q]
+  uint32_t listed;       // 1 = position q of the launch holds table TableOrder::t[q], 0 = table q
   uint32_t bags_per_group;  // stream kernel: consecutive bags owned by one lane group
 };
 
-// Tables of different widths load the XCDs unevenly when they are dealt out in their own order
-// (a wavefront's work grows with the row width).  The host then deals them by width instead and
-// hands the kernel the resulting order by value, in the kernel-argument segment.
+// A launch over tables of different widths may cover a subset of the tables (one lanes-per-row
+// class for the stream kernel) and may take them in another order than the caller's: dealt out
+// in their own order, tables of different widths load the XCDs unevenly (a wavefront's work
+// grows with the row width), so the host deals them by width.  Either way the kernel receives
+// the table at each position of the launch by value, in the kernel-argument segment.
 constexpr int kMaxOrdered = 1024;
 struct TableOrder {
   uint16_t t[kMaxOrdered];
@@ -58,9 +60,10 @@ using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int
                           TableOrder);
 
 // The kernel for short bags (emb_bag_stream.hip): lanes per row 4..64, rows of at most 1 KiB,
-// buffer addressing.  nullptr if there is no such instantiation.
+// buffer addressing; `mixed`: tables of different widths within one lanes-per-row class.
+// nullptr if there is no such instantiation.
 __attribute__((visibility("hidden"))) KernelFn pick_stream_kernel(int lpr, int elem, int depth,
-                                                                  bool weighted);
+                                                                  bool weighted, bool mixed);
 
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)v);
@@ -272,27 +275,28 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
 
 }
 
-// Which piece of work this wavefront owns: its number in table-major order (table = work / wpt),
-// or false if it has none.  Workgroups are dealt round-robin to the 8 XCDs, so blockIdx % 8
-// names the XCD (and its L2); the XCD-affine order turns that into (table, piece) as described
-// at KParams.  `order` is read only by launches with tables of different widths.
-__device__ __forceinline__ bool decode_work(const KParams& p, uint32_t wave, bool use_order,
-                                            const TableOrder& order, uint32_t* work) {
+// Which piece of work this wavefront owns: position `tpos` in the launch's table list and
+// wavefront `w_in_table` of that table (0 .. wpt-1), or false if it has none.  Workgroups are
+// dealt round-robin to the 8 XCDs, so blockIdx % 8 names the XCD (and its L2); the XCD-affine
+// order turns that into (position, piece) as described at KParams.
+__device__ __forceinline__ bool decode_work(const KParams& p, uint32_t wave, uint32_t* tpos,
+                                            uint32_t* w_in_table) {
   if (p.xcd_bpp) {
     const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
     const uint32_t ul = slot / p.xcd_bpp;
     const uint32_t unit = ul * 8u + xcd;
     const uint32_t w_in_piece = (slot - ul * p.xcd_bpp) * kWavesPerBlock + wave;
-    const uint32_t w_in_table = (unit & ((1u << p.xcd_pshift) - 1u)) * p.xcd_wpp + w_in_piece;
-    if (w_in_piece >= p.xcd_wpp || w_in_table >= p.wpt) return false;
-    uint32_t tpos = unit >> p.xcd_pshift;
-    if (use_order && p.xcd_ordered) tpos = order.t[tpos];
-    *work = tpos * p.wpt + w_in_table;
+    const uint32_t w = (unit & ((1u << p.xcd_pshift) - 1u)) * p.xcd_wpp + w_in_piece;
+    if (w_in_piece >= p.xcd_wpp || w >= p.wpt) return false;
+    *tpos = unit >> p.xcd_pshift;
+    *w_in_table = w;
     return true;
   }
   const uint64_t work64 = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
   if (work64 >= p.num_work) return false;
-  *work = (uint32_t)work64;
+  const uint32_t q = (uint32_t)work64 / p.wpt;
+  *tpos = q;
+  *w_in_table = (uint32_t)work64 - q * p.wpt;
   return true;
 }
 

@@ -142,13 +142,16 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
 }
 
 // One wavefront per G * M consecutive bags of one table (see the head of this file).  Sum and
-// mean pooling; max pooling always takes the wave kernel.
-template <int LPR, int ELEM, int DEPTH, bool WEIGHTED>
+// mean pooling; max pooling always takes the wave kernel.  MIXED: the launch covers tables of
+// different widths that share LPR lanes per row; table t is then described by table_offsets[t]
+// (its BYTE offset in the arena) and out_offsets[t] (its first output column; its width is the
+// difference to the next entry), as for the wave kernel.
+template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool MIXED>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                       const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
                       const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
-                      const int64_t* __restrict__ /*out_offsets*/, float* __restrict__ out,
+                      const int64_t* __restrict__ out_offsets, float* __restrict__ out,
                       KParams p, TableOrder order) {
   constexpr int G = kWaveSize / LPR;
   constexpr int GL = __builtin_ctz((unsigned)G);
@@ -159,11 +162,11 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
 
   const int lane = threadIdx.x & (kWaveSize - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  uint32_t work;
-  if (!decode_work(p, wave, false, order, &work)) return;
-  const uint32_t t = work / p.wpt;
+  uint32_t tpos, w_in_table;
+  if (!decode_work(p, wave, &tpos, &w_in_table)) return;
+  const uint32_t t = (MIXED && p.listed) ? order.t[tpos] : tpos;
   const uint32_t M = p.bags_per_group;                   // 1 .. LPR - 1
-  const uint32_t b0 = (work - t * p.wpt) * (uint32_t)G * M;  // first bag of the wavefront, < B
+  const uint32_t b0 = w_in_table * (uint32_t)G * M;      // first bag of the wavefront, < B
   const uint32_t nbw = p.B - b0 < (uint32_t)G * M ? p.B - b0 : (uint32_t)G * M;  // its bags
 
   const int g = lane >> __builtin_ctz((unsigned)LPR);
@@ -173,17 +176,40 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
   const uint32_t m = gb0 < nbw ? (nbw - gb0 < M ? nbw - gb0 : M) : 0u;  // group's bags
 
   // table geometry (buffer addressing only)
-  const int64_t row0 = uniform64(table_offsets[t]);
-  int64_t R = uniform64(table_offsets[t + 1]) - row0;
-  if (R < 0) R = 0;
-  if (R > p.max_rows) R = p.max_rows;
-  const uint32_t row_bytes = p.row_bytes;
-  const char* tbase = tables + row0 * (int64_t)row_bytes;
+  uint32_t D_t = p.D, row_bytes = p.row_bytes;
+  int64_t out_col = (int64_t)t * p.D;
+  const char* tbase;
+  int64_t R;
+  if constexpr (MIXED) {
+    out_col = uniform64(out_offsets[t]);
+    const int64_t out_next = uniform64(out_offsets[t + 1]);
+    const int64_t d64 = out_next - out_col;
+    const int64_t rb64 = QUANT ? d64 + 8 : d64 * (HALF ? 2 : 4);
+    // a table description that does not fit this launch writes nothing (the host chose LPR from
+    // its own copy of the widths)
+    if (d64 <= 0 || rb64 > (int64_t)LPR * 16 || (rb64 & 15) || out_col < 0 || (out_col & 3) ||
+        out_next > p.out_ld)
+      return;
+    D_t = (uint32_t)d64;
+    row_bytes = (uint32_t)rb64;
+    const int64_t byte0 = uniform64(table_offsets[t]);
+    int64_t bytes = uniform64(table_offsets[t + 1]) - byte0;
+    if (bytes < 0) bytes = 0;
+    if (bytes > (int64_t)kBufMaxBytes) bytes = (int64_t)kBufMaxBytes;
+    R = bytes / row_bytes;
+    tbase = tables + byte0;
+  } else {
+    const int64_t row0 = uniform64(table_offsets[t]);
+    R = uniform64(table_offsets[t + 1]) - row0;
+    if (R < 0) R = 0;
+    if (R > p.max_rows) R = p.max_rows;
+    tbase = tables + row0 * (int64_t)row_bytes;
+  }
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<char*>(tbase), 0, (uint32_t)((uint64_t)R * row_bytes), kBufWord3);
   const uint32_t col = (uint32_t)l * 16u;
   const bool lane_ok = col < row_bytes;
-  const int meta_lane = group_base + (int)(p.D >> 4);
+  const int meta_lane = group_base + (int)(D_t >> 4);
   const bool streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
 
   // bag bounds: lane l of a group holds bound min(l, m) of the group, clamped to [0, NL]
@@ -213,17 +239,17 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
       gather_bag<LPR, ELEM, 2, WEIGHTED ? kOpWeighted : kOpSum, true, false>(acc, indices, weights, s, e, R, row_bytes,
                                                       tbase, rsrc, lane, g, col, lane_ok,
                                                       meta_lane, GL);
-      finish_bag<LPR, ELEM, kOpSum>(acc, LPR, lane, lane_ok, col, p.D, e - s, p.mean != 0, out, p.out_ld,
-                            b0 + i, (int64_t)t * p.D);
+      finish_bag<LPR, ELEM, kOpSum>(acc, LPR, lane, lane_ok, col, D_t, e - s, p.mean != 0, out,
+                                    p.out_ld, b0 + i, out_col);
     }
     return;
   }
 
   // output rows of this wavefront as a buffer: a store with an out-of-range offset is dropped
   const uint32_t out_ld_bytes = (uint32_t)p.out_ld * 4u;
-  float* obuf = out + (int64_t)b0 * p.out_ld + (int64_t)t * p.D;
+  float* obuf = out + (int64_t)b0 * p.out_ld + out_col;
   const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      obuf, 0, (nbw - 1u) * out_ld_bytes + p.D * 4u, kBufWord3);
+      obuf, 0, (nbw - 1u) * out_ld_bytes + D_t * 4u, kBufWord3);
   const uint32_t elem0 = QUANT ? col : (HALF ? col / 2 : col / 4);
   const uint32_t store0 = gb0 * out_ld_bytes + elem0 * 4u;
 
@@ -236,7 +262,7 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
       const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (int q = 0; q < NOUT / 4; ++q) {
-        const bool in_row = !QUANT || elem0 + 4u * q < p.D;
+        const bool in_row = !QUANT || elem0 + 4u * q < D_t;
         __builtin_amdgcn_raw_buffer_store_b128(zero, out_rsrc,
                                                (int)(in_row ? so + 16u * q : kBufSentinel), 0, 2);
       }
@@ -260,32 +286,44 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
   const float* gw = WEIGHTED ? weights + S : nullptr;
   if (streaming)
     stream_groups<LPR, ELEM, DEPTH, WEIGHTED, true>(gi, gw, glen, pk, R, row_bytes, rsrc, out_rsrc,
-                                                    store0, out_ld_bytes, p.D, p.mean != 0, lane,
+                                                    store0, out_ld_bytes, D_t, p.mean != 0, lane,
                                                     col, lane_ok, meta_lane);
   else
     stream_groups<LPR, ELEM, DEPTH, WEIGHTED, false>(gi, gw, glen, pk, R, row_bytes, rsrc,
-                                                     out_rsrc, store0, out_ld_bytes, p.D,
+                                                     out_rsrc, store0, out_ld_bytes, D_t,
                                                      p.mean != 0, lane, col, lane_ok, meta_lane);
 }
 
-template <int LPR, int ELEM>
+template <int LPR, int ELEM, bool MIXED>
 KernelFn pick_w(int depth, bool weighted) {
   constexpr int D8 = LPR >= 8 ? 8 : 4;  // a group holds LPR lookups per chunk: DEPTH <= LPR
   if (depth <= 4)
-    return weighted ? emb_bag_stream_kernel<LPR, ELEM, 4, true>
-                    : emb_bag_stream_kernel<LPR, ELEM, 4, false>;
-  return weighted ? emb_bag_stream_kernel<LPR, ELEM, D8, true>
-                  : emb_bag_stream_kernel<LPR, ELEM, D8, false>;
+    return weighted ? emb_bag_stream_kernel<LPR, ELEM, 4, true, MIXED>
+                    : emb_bag_stream_kernel<LPR, ELEM, 4, false, MIXED>;
+  return weighted ? emb_bag_stream_kernel<LPR, ELEM, D8, true, MIXED>
+                  : emb_bag_stream_kernel<LPR, ELEM, D8, false, MIXED>;
 }
 
-template <int LPR>
+template <int LPR, bool MIXED>
 KernelFn pick_e(int elem, int depth, bool weighted) {
   switch (elem) {
-    case EMB_F32: return pick_w<LPR, EMB_F32>(depth, weighted);
-    case EMB_F16: return pick_w<LPR, EMB_F16>(depth, weighted);
-    case EMB_BF16: return pick_w<LPR, EMB_BF16>(depth, weighted);
-    case EMB_U8ROW: return pick_w<LPR, EMB_U8ROW>(depth, weighted);
-    case EMB_FP8ROW: return pick_w<LPR, EMB_FP8ROW>(depth, weighted);
+    case EMB_F32: return pick_w<LPR, EMB_F32, MIXED>(depth, weighted);
+    case EMB_F16: return pick_w<LPR, EMB_F16, MIXED>(depth, weighted);
+    case EMB_BF16: return pick_w<LPR, EMB_BF16, MIXED>(depth, weighted);
+    case EMB_U8ROW: return pick_w<LPR, EMB_U8ROW, MIXED>(depth, weighted);
+    case EMB_FP8ROW: return pick_w<LPR, EMB_FP8ROW, MIXED>(depth, weighted);
+    default: return nullptr;
+  }
+}
+
+template <bool MIXED>
+KernelFn pick_l(int lpr, int elem, int depth, bool weighted) {
+  switch (lpr) {
+    case 4: return pick_e<4, MIXED>(elem, depth, weighted);
+    case 8: return pick_e<8, MIXED>(elem, depth, weighted);
+    case 16: return pick_e<16, MIXED>(elem, depth, weighted);
+    case 32: return pick_e<32, MIXED>(elem, depth, weighted);
+    case 64: return pick_e<64, MIXED>(elem, depth, weighted);
     default: return nullptr;
   }
 }
@@ -294,15 +332,8 @@ KernelFn pick_e(int elem, int depth, bool weighted) {
 
 namespace embbag {
 
-KernelFn pick_stream_kernel(int lpr, int elem, int depth, bool weighted) {
-  switch (lpr) {
-    case 4: return pick_e<4>(elem, depth, weighted);
-    case 8: return pick_e<8>(elem, depth, weighted);
-    case 16: return pick_e<16>(elem, depth, weighted);
-    case 32: return pick_e<32>(elem, depth, weighted);
-    case 64: return pick_e<64>(elem, depth, weighted);
-    default: return nullptr;
-  }
+KernelFn pick_stream_kernel(int lpr, int elem, int depth, bool weighted, bool mixed) {
+  return mixed ? pick_l<true>(lpr, elem, depth, weighted) : pick_l<false>(lpr, elem, depth, weighted);
 }
 
 }  // namespace embbag

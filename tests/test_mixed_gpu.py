@@ -211,3 +211,64 @@ def test_mixed_batches_validate_profile_and_replay_from_a_graph(oracle):
         g.replay()
         torch.cuda.synchronize()
         assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, "mixed graph replay")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "u8row"])
+@pytest.mark.parametrize("pooling", [("fixed", 1), ("uniform", 0, 3), ("uniform", 0, 9)])
+def test_mixed_widths_with_short_bags_use_the_stream_kernel(oracle, dtype, pooling):
+    """Short bags split a mixed-width call into one stream-kernel launch per lanes-per-row class
+    and one wave-kernel launch for the remaining tables; every table is still written once."""
+    wl = _wl(dtype, pooling=pooling, B=211)
+    batch = gen.make_batches(wl, 1)[0]
+    tabs = gen.mixed_host_tables(wl)
+    arena = _device_arena(wl)
+    max_bytes = int(np.diff(wl.table_byte_offsets()).max())
+    desc = emb.make_mixed_desc(wl.dims, wl.B, EDT[dtype], emb.EMB_SUM, batch.num_lookups, 0, max_bytes)
+    plan = emb.emb_bag_plan_forward_mixed(desc)
+    assert plan.num_launches > 1
+    for mode in ("sum", "mean"):
+        ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, mode)
+        first = None
+        for kw in (dict(), dict(xcd_remap=1), dict(bags_per_group=3), dict(stream=1, depth=4)):
+            with tuning(**kw):
+                got = _forward(wl, arena, batch, mode).cpu().numpy()
+            assert_close_to_oracle(got, ref, bound, dtype != "f32", f"mixed short/{dtype}/{mode}/{kw}")
+            if first is None:
+                first = got
+            elif "stream" not in kw:
+                assert np.array_equal(got, first), kw
+        with tuning(stream=0):                              # the wave kernel alone, for comparison
+            wave = _forward(wl, arena, batch, mode).cpu().numpy()
+        assert_close_to_oracle(wave, ref, bound, dtype != "f32", "mixed short/wave only")
+
+
+def test_mixed_short_bags_weights_padding_and_hints(oracle):
+    wl = _wl("f32", pooling=("uniform", 0, 4), weighted=True, B=97)
+    batch = gen.make_batches(wl, 1)[0]
+    tabs = gen.mixed_host_tables(wl)
+    arena = _device_arena(wl)
+    total = int(sum(wl.dims))
+    ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, "sum",
+                                      weights=batch.weights, out_ld=total + 8)
+    hints = to_dev((np.arange(wl.T) % 2).astype(np.uint8))
+    got = _forward(wl, arena, batch, "sum", batch.weights, out_ld=total + 8, hints=hints,
+                   fill=-5.0).cpu().numpy()
+    assert np.all(got[:, total:] == -5.0)
+    assert_close_to_oracle(got[:, :total], ref[:, :total], bound[:, :total], False, "mixed short weighted")
+
+
+def test_mixed_onehot_full_size_sampled(oracle):
+    """26 tables x 1 M rows, widths 16 / 32 / 64 / 128, batch 131,072, one lookup per bag."""
+    wl = gen.mixed_workload("mixed_onehot")
+    batch = gen.make_batches(wl, 1)[0]
+    arena = _device_arena(wl)
+    out = _forward(wl, arena, batch, "sum")
+    assert bool(torch.isfinite(out).all())
+    rng = np.random.default_rng(9)
+    base, cols = wl.row_bases(), wl.out_offsets()
+    for t in range(wl.T):
+        bs = np.unique(np.concatenate([rng.integers(0, wl.B, size=40), [0, wl.B - 1]]))
+        rows = batch.indices[batch.offsets[t * wl.B + bs]]
+        want = gen.table_values(wl.seed, base[t] + rows, wl.dims[t], wl.dtype, wl.kind)
+        got = out[torch.from_numpy(bs).to(DEV), cols[t]:cols[t + 1]].cpu().numpy()
+        assert np.array_equal(got, want), t                  # one lookup per bag: the row itself

@@ -110,7 +110,9 @@ def _simulate(plan, T, order=None):
         n = (g[:, None] * 4 + w[None, :]).ravel()
         keep = n < p["wavefronts"]
         n = n[keep]
-        return n // p["waves_per_table"], n % p["waves_per_table"], np.repeat(g % 8, 4)[keep]
+        pos = n // p["waves_per_table"]
+        table = np.asarray(order, dtype=np.int64)[pos] if order is not None else pos
+        return table, n % p["waves_per_table"], np.repeat(g % 8, 4)[keep]
     xcd, slot = g % 8, g // 8
     unit = (slot // p["blocks_per_piece"]) * 8 + xcd
     piece, pos = unit % p["xcd_pieces"], unit // p["xcd_pieces"]
@@ -145,9 +147,9 @@ def test_every_wavefront_of_every_table_is_launched_exactly_once(T, B, L):
     assert np.array_equal(table * nat.waves_per_table + wave, np.arange(T * nat.waves_per_table))
 
 
-def _mixed_plan(dims, B=4096, L=80, dtype=emb.EMB_F32):
-    desc = emb.make_mixed_desc(list(dims), B, dtype, emb.EMB_SUM, len(dims) * B * L, 0, 1 << 30)
-    return emb.emb_bag_plan_forward_mixed(desc, False, True)
+def _mixed_plan(dims, B=4096, L=80, dtype=emb.EMB_F32, which=0, mode=emb.EMB_SUM):
+    desc = emb.make_mixed_desc(list(dims), B, dtype, mode, int(len(dims) * B * L), 0, 1 << 30)
+    return emb.emb_bag_plan_forward_mixed(desc, False, True, which)
 
 
 @pytest.mark.parametrize("seed", range(8))
@@ -156,9 +158,9 @@ def test_tables_of_different_widths_are_dealt_to_the_xcds_by_bytes(seed):
     T = int(rng.choice([4, 10, 12, 20, 60, 100, 250, 1000]))
     dims = rng.choice([4, 8, 16, 32, 64, 96, 128, 192, 256], size=T)
     plan, order = _mixed_plan(dims)
-    assert sorted(order) == list(range(T))
+    assert plan.num_launches == 1 and plan.tables == T and sorted(order) == list(range(T))
     if plan.xcd_pieces in (1, 2, 4):
-        assert plan.xcd_ordered == 1
+        assert plan.listed == 1
     table, wave, xcd = _simulate(plan, T, order)
     flat = table * plan.waves_per_table + wave
     assert np.array_equal(np.sort(flat), np.arange(T * plan.waves_per_table))
@@ -173,12 +175,70 @@ def test_tables_of_different_widths_are_dealt_to_the_xcds_by_bytes(seed):
 
 def test_mixed_plan_special_cases():
     plan, order = _mixed_plan([64] * 60)                       # equal widths: the caller's order
-    assert plan.xcd_ordered == 0 and order == list(range(60)) and plan.xcd_pieces == 2
+    assert plan.listed == 0 and order == list(range(60)) and plan.xcd_pieces == 2
     plan, order = _mixed_plan([64, 32] * 600)                  # more tables than the order holds
-    assert plan.xcd_pieces == 0 and plan.xcd_ordered == 0      # natural order instead
+    assert plan.xcd_pieces == 0 and plan.listed == 0      # natural order instead
     plan, _ = _mixed_plan([64] * 1200)                         # ... which equal widths do not need
     assert plan.xcd_pieces == 1                                # 1200 is a multiple of 8
     plan, order = _mixed_plan([64, 32, 128] * 5)               # odd T: every table on all 8 XCDs
-    assert plan.xcd_pieces == 8 and plan.xcd_ordered == 0
+    assert plan.xcd_pieces == 8 and plan.listed == 0
     plan, order = _mixed_plan([(32, 64, 128, 256)[t % 4] for t in range(60)])
     assert order[:15] == list(range(3, 60, 4))                 # widest tables first
+
+
+@pytest.mark.parametrize("L", [0.5, 1, 2, 5, 10, 20])
+@pytest.mark.parametrize("seed", range(3))
+def test_short_bags_split_a_mixed_call_into_one_launch_per_row_class(seed, L):
+    """Below three row loads per bag a lanes-per-row class goes to the stream kernel, the other
+    tables to one wave-kernel launch; together the launches cover every table exactly once."""
+    rng = np.random.default_rng(100 + seed)
+    T = int(rng.choice([7, 40, 333]))
+    dims = rng.choice([4, 8, 16, 32, 64, 96, 128, 192, 256], size=T)
+    B = 5000
+    first, _ = _mixed_plan(dims, B, L)
+    lanes = np.maximum(4, 2 ** np.ceil(np.log2(dims * 4 / 16)).astype(int))      # lanes per row
+    want_stream = L < 3 * (64 // lanes)
+    seen = np.zeros(T, dtype=int)
+    kinds = []
+    for w in range(first.num_launches):
+        plan, order = _mixed_plan(dims, B, L, which=w)
+        assert plan.num_launches == first.num_launches and plan.tables == len(order) > 0
+        kinds.append((plan.kernel, plan.lanes_per_row))
+        order = np.asarray(order)
+        seen[order] += 1
+        if plan.kernel == emb.EMB_KERNEL_STREAM:
+            assert np.all(lanes[order] == plan.lanes_per_row) and np.all(want_stream[order])
+            g = 64 // plan.lanes_per_row
+            assert 1 <= plan.bags_per_group <= plan.lanes_per_row - 1
+            assert plan.waves_per_table == -(-B // (g * plan.bags_per_group))
+        else:
+            assert plan.lanes_per_row == 0 and plan.waves_per_table == B
+            if first.num_launches > 1:
+                assert not np.any(want_stream[order])
+        table, wave, _ = _simulate(plan, plan.tables, order)
+        flat = table * plan.waves_per_table + wave
+        assert len(np.unique(flat)) == len(flat) == plan.tables * plan.waves_per_table
+        assert set(np.unique(table)) == set(order.tolist())
+    assert np.all(seen == 1)
+    assert len(set(kinds)) == len(kinds)                       # one launch per kernel and class
+    with pytest.raises(emb.EmbBagError):
+        _mixed_plan(dims, B, L, which=first.num_launches)
+
+
+def test_mixed_plan_never_streams_max_pooling_or_unbounded_tables():
+    dims = [32, 64, 128, 256] * 5
+    assert _mixed_plan(dims, 5000, 1, mode=emb.EMB_MAX)[0].num_launches == 1
+    with tuning(stream=0):
+        assert _mixed_plan(dims, 5000, 1)[0].num_launches == 1
+    with tuning(addressing=1):
+        assert _mixed_plan(dims, 5000, 1)[0].num_launches == 1
+    desc = emb.make_mixed_desc(dims, 5000, emb.EMB_F32, emb.EMB_SUM, 20 * 5000, 0, 0)   # no size bound
+    assert emb.emb_bag_plan_forward_mixed(desc).num_launches == 1
+    with tuning(stream=1):                                      # forced on: every class streams
+        first, _ = _mixed_plan(dims, 5000, 100)
+        assert first.num_launches == 4 and first.kernel == emb.EMB_KERNEL_STREAM
+    # more tables than a list holds: pieces of at most 1024 tables
+    first, _ = _mixed_plan([32, 64] * 1500, 2000, 1)
+    assert first.num_launches == 4
+    sizes = [_mixed_plan([32, 64] * 1500, 2000, 1, which=w)[0].tables for w in range(4)]
+    assert sorted(sizes) == [476, 476, 1024, 1024]
