@@ -4,6 +4,7 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+import time
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
@@ -13,12 +14,17 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-Wall", "-Wno-unused-command-line-argument"]
 
+CSRC = "paper_2410_22249_amd/csrc/"
 TARGETS = {
-    # output (relative to the repo root): sources (compiled side by side, then linked)
-    "paper_2410_22249_amd/libembbag.so": ["paper_2410_22249_amd/csrc/emb_bag.hip",
-                                          "paper_2410_22249_amd/csrc/emb_bag_stream.hip"],
-    "inputgen/libembgen.so": ["inputgen/csrc/embgen.hip"],
+    # output (relative to the repo root): (source, lanes-per-row class or None) pairs, compiled
+    # side by side, then linked.  The kernel sources are compiled once per class (-DEMB_LPR=n).
+    "paper_2410_22249_amd/libembbag.so":
+        [(CSRC + "emb_bag.hip", None)]
+        + [(CSRC + "emb_bag_wave.hip", n) for n in (0, 4, 8, 16, 32, 64)]
+        + [(CSRC + "emb_bag_stream.hip", n) for n in (4, 8, 16, 32, 64)],
+    "inputgen/libembgen.so": [("inputgen/csrc/embgen.hip", None)],
 }
+MAX_JOBS = max(1, min(int(os.environ.get("MAX_JOBS", "8")), os.cpu_count() or 1))
 OBJ_DIR = os.path.join(ROOT, "_build")
 
 
@@ -54,20 +60,32 @@ def _finish(proc, what: str, verbose: bool) -> None:
         raise RuntimeError(f"hipcc failed for {what}")
 
 
+def _obj(src: str, lpr) -> str:
+    tag = "" if lpr is None else f".lpr{lpr}"
+    return os.path.join(OBJ_DIR, os.path.basename(src) + tag + ".o")
+
+
 def build_all(verbose: bool = True) -> None:
     os.makedirs(OBJ_DIR, exist_ok=True)
     inc = ["-I", os.path.join(ROOT, "include")]
-    # every source to an object, all at once; then one link per library
-    jobs = []
+    # every (source, class) to an object, MAX_JOBS at a time; then one link per library
+    todo = [(src, lpr) for srcs in TARGETS.values() for src, lpr in srcs]
+    running = []
+    while todo or running:
+        while todo and len(running) < MAX_JOBS:
+            src, lpr = todo.pop(0)
+            defs = [] if lpr is None else [f"-DEMB_LPR={lpr}"]
+            cmd = [HIPCC] + HIP_FLAGS + inc + defs + ["-c", "-o", _obj(src, lpr),
+                                                      os.path.join(ROOT, src)]
+            running.append((f"{src} {' '.join(defs)}", _run(cmd, verbose)))
+        done = [i for i, (_, proc) in enumerate(running) if proc.poll() is not None]
+        if not done:
+            time.sleep(0.2)
+            continue
+        what, proc = running.pop(done[0])
+        _finish(proc, what, verbose)
     for out, srcs in TARGETS.items():
-        for src in srcs:
-            obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
-            jobs.append((src, _run([HIPCC] + HIP_FLAGS + inc + ["-c", "-o", obj,
-                                                               os.path.join(ROOT, src)], verbose)))
-    for src, proc in jobs:
-        _finish(proc, src, verbose)
-    for out, srcs in TARGETS.items():
-        objs = [os.path.join(OBJ_DIR, os.path.basename(src) + ".o") for src in srcs]
+        objs = [_obj(src, lpr) for src, lpr in srcs]
         _finish(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o",
                       os.path.join(ROOT, out)] + objs, verbose), out, verbose)
     build_c_driver(verbose)

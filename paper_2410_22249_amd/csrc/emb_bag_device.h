@@ -59,11 +59,25 @@ using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int
                           const float*, const uint8_t*, const int64_t*, float*, KParams,
                           TableOrder);
 
-// The kernel for short bags (emb_bag_stream.hip): lanes per row 4..64, rows of at most 1 KiB,
-// buffer addressing; `mixed`: tables of different widths within one lanes-per-row class.
-// nullptr if there is no such instantiation.
-__attribute__((visibility("hidden"))) KernelFn pick_stream_kernel(int lpr, int elem, int depth,
-                                                                  bool weighted, bool mixed);
+// The forward kernels are built one lanes-per-row class per translation unit; each unit exports
+// one function that picks an instantiation (nullptr if there is none):
+//   wave kernel (emb_bag_wave.hip):     lanes per row 0 (different widths), 4 .. 64
+//   stream kernel (emb_bag_stream.hip): lanes per row 4 .. 64, rows of at most 1 KiB, buffer
+//     addressing; `mixed`: tables of different widths within the class
+#define EMB_PASTE_(a, b) a##b
+#define EMB_PASTE(a, b) EMB_PASTE_(a, b)
+#define EMB_DECLARE_PICKERS(n)                                                                  \
+  __attribute__((visibility("hidden"))) KernelFn pick_wave_kernel_lpr##n(int elem, int depth,   \
+                                                                         int op, bool buf);     \
+  __attribute__((visibility("hidden"))) KernelFn pick_stream_kernel_lpr##n(                     \
+      int elem, int depth, bool weighted, bool mixed);
+EMB_DECLARE_PICKERS(0)  // (there is no stream kernel for class 0; the declaration is unused)
+EMB_DECLARE_PICKERS(4)
+EMB_DECLARE_PICKERS(8)
+EMB_DECLARE_PICKERS(16)
+EMB_DECLARE_PICKERS(32)
+EMB_DECLARE_PICKERS(64)
+#undef EMB_DECLARE_PICKERS
 
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)v);

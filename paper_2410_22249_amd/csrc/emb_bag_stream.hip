@@ -28,6 +28,12 @@
 #include "../../include/emb_bag.h"
 #include "emb_bag_device.h"
 
+// Compiled once per lanes-per-row class (-DEMB_LPR=4, 8, 16, 32, 64) so that the classes build
+// side by side; each build exports pick_stream_kernel_lpr<EMB_LPR>.
+#ifndef EMB_LPR
+#error "compile with -DEMB_LPR=<lanes per row: 4, 8, 16, 32 or 64>"
+#endif
+
 namespace {
 
 using namespace embbag;
@@ -87,7 +93,7 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
     // a lookup past the group's range has idx = -1: out of range like any invalid row id
     const uint32_t voff = (uint64_t)idx < (uint64_t)R ? (uint32_t)idx * row_bytes : kBufSentinel;
 
-#pragma unroll
+#pragma unroll 1
     for (int k0 = 0; k0 < LPR; k0 += DEPTH) {
       if (k0 > 0 && !any_lane(qbase + k0 < glen)) break;
       u32x4 r[DEPTH];
@@ -316,24 +322,14 @@ KernelFn pick_e(int elem, int depth, bool weighted) {
   }
 }
 
-template <bool MIXED>
-KernelFn pick_l(int lpr, int elem, int depth, bool weighted) {
-  switch (lpr) {
-    case 4: return pick_e<4, MIXED>(elem, depth, weighted);
-    case 8: return pick_e<8, MIXED>(elem, depth, weighted);
-    case 16: return pick_e<16, MIXED>(elem, depth, weighted);
-    case 32: return pick_e<32, MIXED>(elem, depth, weighted);
-    case 64: return pick_e<64, MIXED>(elem, depth, weighted);
-    default: return nullptr;
-  }
-}
-
 }  // namespace
 
 namespace embbag {
 
-KernelFn pick_stream_kernel(int lpr, int elem, int depth, bool weighted, bool mixed) {
-  return mixed ? pick_l<true>(lpr, elem, depth, weighted) : pick_l<false>(lpr, elem, depth, weighted);
+KernelFn EMB_PASTE(pick_stream_kernel_lpr, EMB_LPR)(int elem, int depth, bool weighted,
+                                                     bool mixed) {
+  return mixed ? pick_e<EMB_LPR, true>(elem, depth, weighted)
+               : pick_e<EMB_LPR, false>(elem, depth, weighted);
 }
 
 }  // namespace embbag
