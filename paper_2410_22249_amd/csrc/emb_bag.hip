@@ -1,38 +1,8 @@
 // Multi-table EmbeddingBag forward for MI355X (gfx950, CDNA4): the C ABI with the host-side choice
-// of kernel and grid, the validator and the reuse profiler.  The forward kernels live in
-// emb_bag_wave.hip (one wavefront per bag) and emb_bag_stream.hip (short bags), shared device
-// code in emb_bag_device.h; the description below is that of the wave kernel.
-//
-// What is computed is the embedding stage of the paper (Sec. 3.1, Algorithm 1): per bag (t, b)
-// follow offsets -> indices -> table rows, add the rows, store one vector of length D.
-//
-// How it is mapped to the machine (this is not the paper's A100 kernel, which gives one CUDA
-// thread to one output element and walks the bag with dependent loads, Sec. 3.1):
-//   * one 64-lane wavefront owns one bag (or one 1-KiB column slab of it when rows are longer
-//     than 1 KiB); all tables of the batch share one launch;
-//   * a row is read as 16-byte lane segments, so one load instruction of the wavefront moves
-//     1 KiB: G = 64/LPR different rows of the same bag at once, LPR lanes per row
-//     (512-byte rows: 2 rows per instruction, 256-byte rows: 4);
-//   * the bag's indices are contiguous: the wavefront fetches up to 64 of them with one
-//     coalesced load (lane i holds lookup i), turns them into row byte offsets once, and hands
-//     offset j to the lanes that need it with a cross-lane permute - no dependent index load
-//     in front of every row load as in the paper's base kernel;
-//   * DEPTH row loads are issued back to back before the first is consumed (the register
-//     prefetch of Sec. 4.2, with the distance as a tuning knob, Sec. 7 step vi), and the many
-//     resident wavefronts per SIMD (the kernels need few VGPRs) supply the rest of the
-//     memory-level parallelism (the multithreading fix of Sec. 3.3);
-//   * rows are addressed through a per-table buffer resource with 32-bit offsets when the table
-//     is below 3.5 GiB: the hardware range check turns an invalid row into zeros instead of a
-//     fault, and address arithmetic stays 32-bit.  Larger tables use 64-bit global addressing
-//     with an explicit check;
-//   * a table that the caller marks as streaming (rows not re-used within a batch; the outcome of
-//     the access-pattern profiling the paper does offline, Sec. 4.3 and Sec. 7) has its rows read
-//     with the non-temporal policy, a re-used table with the default policy;
-//   * rows may be fp32, fp16, bf16 (widened exactly) or row-wise quantised 8-bit codes;
-//   * partial sums of the G row groups are combined with a fixed xor butterfly (deterministic),
-//     the mean is one division per element per bag, and the result leaves with 16-byte
-//     non-temporal stores so that it does not displace table rows in L2 / MALL.
-// No MFMA: this is a gather-reduce, not a contraction; the bound is HBM bandwidth.
+// of kernel, prefetch depth, grid and block order (the decisions the paper's profiling recipe
+// makes per workload, Sec. 7), the validator and the reuse profiler (the offline profiling of
+// Sec. 4.3, on the device).  The forward kernels live in emb_bag_wave.hip (one wavefront per
+// bag) and emb_bag_stream.hip (short bags), shared device code in emb_bag_device.h.
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
