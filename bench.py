@@ -34,6 +34,9 @@ DESCRIPTIONS = {
     "paper_one_item": "250 fp32 tables x 500,000 x dim 128, batch 2048, pooling 150, one item, sum",
     "cfg3_weighted": "cfg3 with fp32 per-sample weights",
     "cfg3_max": "cfg3 with max pooling",
+    "hetero": "26 fp32 tables x 1,000,000 rows x dim 64, batch 32768; 20 tables with ONE lookup per "
+              "bag, 6 with 100 (average 23.8): per-table bag lengths split the call into a "
+              "stream-kernel launch and a wave-kernel launch",
     "cfg3_fp8": "cfg3's shape with row-wise quantised rows of E4M3 codes: 60 tables x 4,000,000 "
                 "rows x dim 120 (128-byte rows), batch 4096, pooling 80, uniform, sum",
     "cfg3_u8": "cfg3's shape with row-wise quantised rows: 60 tables x 4,000,000 rows x dim 120 "
@@ -97,6 +100,9 @@ def main() -> int:
                          "contiguous hipExtMallocWithFlags")
     ap.add_argument("--no-hints", action="store_true",
                     help="do not profile table reuse / pass per-table cache hints")
+    ap.add_argument("--no-table-lengths", action="store_true",
+                    help="do not pass per-table bag lengths (table_avg_len) for workloads whose "
+                         "tables differ in pooling")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="emb_bag_set_tuning override, e.g. --tune depth=8")
     args = ap.parse_args()
@@ -177,13 +183,18 @@ def main() -> int:
                                   stream)
         stream.synchronize()
         log(f"table hints: {int(hints.sum().item())} of {wl.T} tables streaming")
+    # per-table bag lengths (a property of the features, taken from the first batch) where the
+    # tables differ in pooling; --no-table-lengths shows the single-kernel choice
+    avg_len = None
+    if wl.pooling[0] == "per_table" and not args.no_table_lengths:
+        avg_len = gen.table_avg_len(wl, batches[0])
     if mixed:
         max_bytes = int(np.diff(wl.table_byte_offsets()).max())
-        descs = [emb.make_mixed_desc(wl.dims, wl.B, edt, emode, b.num_lookups, 0, max_bytes, hints)
-                 for b in batches]
+        descs = [emb.make_mixed_desc(wl.dims, wl.B, edt, emode, b.num_lookups, 0, max_bytes, hints,
+                                     avg_len) for b in batches]
     else:
-        descs = [emb.make_desc(wl.T, wl.B, wl.D, edt, emode, b.num_lookups, 0, max(wl.rows), hints)
-                 for b in batches]
+        descs = [emb.make_desc(wl.T, wl.B, wl.D, edt, emode, b.num_lookups, 0, max(wl.rows), hints,
+                               avg_len) for b in batches]
     torch.cuda.synchronize()
 
     def step(i: int) -> None:
@@ -410,7 +421,11 @@ def main() -> int:
         launch_plan = [emb.emb_bag_plan_forward_mixed(descs[0], wl.weighted, which=w).as_dict()
                        for w in range(n_launch)]
     else:
-        launch_plan = emb.emb_bag_plan_forward(descs[0], wl.weighted).as_dict()
+        n_launch = emb.emb_bag_plan_forward(descs[0], wl.weighted).num_launches
+        launch_plan = [emb.emb_bag_plan_forward(descs[0], wl.weighted, which=w).as_dict()
+                       for w in range(n_launch)]
+        if n_launch == 1:
+            launch_plan = launch_plan[0]
     traffic = read_traffic(wl.name)
     result = {
         "metric": "embedding lookups/sec and effective gathered HBM GB/s (% of peak), 1 MI355X",

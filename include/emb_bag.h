@@ -79,7 +79,7 @@ extern "C" {
 typedef struct emb_bag_desc {
   int32_t num_tables;     /* T >= 1 */
   int32_t dim;            /* D >= 1 */
-  int32_t table_dtype;    /* EMB_F32, EMB_F16, EMB_BF16 or EMB_U8ROW */
+  int32_t table_dtype;    /* EMB_F32, EMB_F16, EMB_BF16, EMB_U8ROW or EMB_FP8ROW */
   int32_t mode;           /* EMB_SUM, EMB_MEAN or EMB_MAX */
   int64_t batch;          /* B >= 0; B == 0 is a no-op that returns EMB_OK */
   int64_t num_lookups;    /* NL = offsets[T*B]: entries in indices (and in per_sample_weights) */
@@ -94,6 +94,13 @@ typedef struct emb_bag_desc {
                              cache treatment from it (Sec. 4.3, Sec. 7 steps v-vi); this is where
                              that choice enters.  Hints change speed only, never results.
                              emb_bag_profile_reuse can produce them from a sample batch. */
+  const float* table_avg_len; /* HOST, T floats, or NULL: the typical number of lookups per bag of
+                             each table (a property of the feature: one-hot, multi-hot ...; e.g.
+                             (offsets[(t+1)*B] - offsets[t*B]) / B of a sample batch).  Without
+                             it one kernel serves all tables, chosen by the call's average
+                             num_lookups / (T*B); with it, tables with short bags go to the
+                             short-bag kernel and the others to the one-wavefront-per-bag kernel,
+                             in two launches (see the "stream" tuning key).  Speed only. */
 } emb_bag_desc;
 
 /*
@@ -164,6 +171,8 @@ typedef struct emb_bag_mixed_desc {
                               below 3.5 GiB selects 32-bit buffer addressing */
   const int32_t* dims;     /* HOST, T widths D_t */
   const uint8_t* table_hints; /* DEVICE, T bytes of EMB_HINT_*, or NULL */
+  const float* table_avg_len; /* HOST, T floats, or NULL: as in emb_bag_desc; decides per table
+                              (instead of per call) which tables go to the short-bag kernel */
 } emb_bag_mixed_desc;
 
 int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
@@ -220,10 +229,11 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
  *   desc         HOST   as for the forward call (table_hints is only tested against NULL)
  *   has_weights  non-zero if the forward call would pass per_sample_weights
  *   plan         HOST   filled in; all zero for batch == 0
- *   which        (mixed only) which of the call's launches to describe, 0 .. num_launches - 1;
- *                       emb_bag_forward always makes one launch, emb_bag_forward_mixed makes
- *                       several when bags are short: one stream-kernel launch per lanes-per-row
- *                       class that kernel suits, one wave-kernel launch for the other tables
+ *   which        which of the call's launches to describe, 0 .. num_launches - 1.
+ *                       emb_bag_forward makes one launch, or two when desc->table_avg_len
+ *                       separates tables with short bags from the others; emb_bag_forward_mixed
+ *                       makes one stream-kernel launch per lanes-per-row class that kernel suits
+ *                       and one wave-kernel launch for the other tables
  *   table_order  HOST   uint16 [min(T, 1024)] or NULL: the table at each of the launch's
  *                       plan->tables positions (the identity unless plan->listed)
  *   Returns the status the forward call would return for the descriptor alone
@@ -259,8 +269,8 @@ typedef struct emb_bag_plan {
   int64_t tables;            /* tables (positions) this launch covers */
 } emb_bag_plan;
 
-int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, emb_bag_plan* plan,
-                         uint16_t* table_order);
+int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, int32_t which,
+                         emb_bag_plan* plan, uint16_t* table_order);
 int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, int32_t which,
                                emb_bag_plan* plan, uint16_t* table_order);
 
@@ -287,6 +297,7 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   addressing allow it.  It adds a bag's rows in the order of its lookups; the
  *                   one-wavefront-per-bag kernel keeps several partial sums, so the two agree
  *                   to rounding, not to the bit.
+ *                   With desc->table_avg_len the automatic choice is made per table.
  *   "bags_per_group" consecutive bags per lane group in that kernel, 1..63; 0 = automatic
  * Not thread-safe against concurrent emb_bag_forward calls.
  */

@@ -467,6 +467,10 @@ def workload(name: str) -> Workload:
     if name == "short":            # cfg2's tables, 0..8 lookups per bag (a ninth of the bags empty)
         return _homog("short", 26, 1_000_000, 64, "f32", 32768, ("uniform", 0, 8), ("uniform",),
                       seed_off=0x19)
+    if name == "hetero":           # cfg2's tables; 20 one-hot features, 6 multi-hot ones of 100
+        specs = tuple(("fixed", 100) if t % 4 == 3 and t < 24 else ("fixed", 1) for t in range(26))
+        return _homog("hetero", 26, 1_000_000, 64, "f32", 32768, ("per_table", specs), ("uniform",),
+                      seed_off=0x1D)
     if name == "cfg3_max":         # cfg3 with max pooling
         return with_overrides(workload("cfg3"), name="cfg3_max", mode="max")
     if name == "cfg3_weighted":    # cfg3 with per-sample weights
@@ -513,8 +517,22 @@ def _rng(seed: int, purpose: int, batch_id: int = 0, table: int = 0) -> np.rando
 
 
 def make_lengths(wl: Workload, batch_id: int = 0) -> np.ndarray:
-    """Bag lengths in (t, b) order, int64 [T*B]."""
+    """Bag lengths in (t, b) order, int64 [T*B].  pooling is ("fixed", L), ("uniform", lo, hi)
+    (inclusive), or ("per_table", (spec, spec, ...)) with one such spec per table, cycled."""
     n = wl.num_bags
+    if wl.pooling[0] == "per_table":
+        specs = wl.pooling[1]
+        out = np.empty(n, dtype=np.int64)
+        for t in range(wl.T):
+            spec = specs[t % len(specs)]
+            if spec[0] == "fixed":
+                out[t * wl.B:(t + 1) * wl.B] = int(spec[1])
+            elif spec[0] == "uniform":
+                out[t * wl.B:(t + 1) * wl.B] = _rng(wl.seed, _PURPOSE_LEN, batch_id, t).integers(
+                    int(spec[1]), int(spec[2]) + 1, size=wl.B, dtype=np.int64)
+            else:
+                raise ValueError(f"bad pooling spec {spec!r}")
+        return out
     if wl.pooling[0] == "fixed":
         return np.full(n, int(wl.pooling[1]), dtype=np.int64)
     if wl.pooling[0] == "uniform":
@@ -607,6 +625,13 @@ def make_batches(wl: Workload, n_batches: int = 1, first_batch: int = 0) -> List
 def host_arena(wl: Workload) -> np.ndarray:
     """The whole table arena on the host, [sum R_t, D] (only for shapes that fit in RAM)."""
     return table_values_range(wl.seed, 0, wl.total_rows, wl.D, wl.dtype, wl.kind)
+
+
+def table_avg_len(wl, batch: "Batch") -> np.ndarray:
+    """Average bag length of each table in a batch, float32 [T] (what a caller would pass as
+    table_avg_len)."""
+    per_table = np.diff(batch.offsets[::wl.B]).astype(np.float64)
+    return (per_table / wl.B).astype(np.float32)
 
 
 def compact_rows(wl: Workload, batch: Batch, bag_ids: Sequence[int]):

@@ -35,7 +35,8 @@ class emb_bag_desc(ctypes.Structure):
                 ("table_dtype", ctypes.c_int32), ("mode", ctypes.c_int32),
                 ("batch", ctypes.c_int64), ("num_lookups", ctypes.c_int64),
                 ("out_ld", ctypes.c_int64), ("max_table_rows", ctypes.c_int64),
-                ("table_hints", ctypes.c_void_p)]
+                ("table_hints", ctypes.c_void_p),
+                ("table_avg_len", ctypes.POINTER(ctypes.c_float))]
 
 
 class emb_bag_mixed_desc(ctypes.Structure):
@@ -43,7 +44,8 @@ class emb_bag_mixed_desc(ctypes.Structure):
                 ("mode", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("batch", ctypes.c_int64), ("num_lookups", ctypes.c_int64),
                 ("out_ld", ctypes.c_int64), ("max_table_bytes", ctypes.c_int64),
-                ("dims", ctypes.POINTER(ctypes.c_int32)), ("table_hints", ctypes.c_void_p)]
+                ("dims", ctypes.POINTER(ctypes.c_int32)), ("table_hints", ctypes.c_void_p),
+                ("table_avg_len", ctypes.POINTER(ctypes.c_float))]
 
 
 class emb_bag_plan(ctypes.Structure):
@@ -77,7 +79,7 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.emb_bag_forward_mixed.argtypes = [ctypes.POINTER(emb_bag_mixed_desc), P, P, P, P, P, P, P, P]
     lib.emb_bag_plan_forward.restype = ctypes.c_int
     lib.emb_bag_plan_forward.argtypes = [ctypes.POINTER(emb_bag_desc), ctypes.c_int,
-                                         ctypes.POINTER(emb_bag_plan), P]
+                                         ctypes.c_int32, ctypes.POINTER(emb_bag_plan), P]
     lib.emb_bag_plan_forward_mixed.restype = ctypes.c_int
     lib.emb_bag_plan_forward_mixed.argtypes = [ctypes.POINTER(emb_bag_mixed_desc), ctypes.c_int,
                                                ctypes.c_int32, ctypes.POINTER(emb_bag_plan), P]
@@ -119,15 +121,28 @@ def _stream_handle(stream) -> Optional[int]:
 
 def make_desc(num_tables: int, batch: int, dim: int, table_dtype: int, mode: int,
               num_lookups: int, out_ld: int = 0, max_table_rows: int = 0,
-              table_hints: Optional[torch.Tensor] = None) -> emb_bag_desc:
+              table_hints: Optional[torch.Tensor] = None, table_avg_len=None) -> emb_bag_desc:
     """Fill the host descriptor.  `table_hints` is a device uint8 tensor [T] (or None) that the
-    caller keeps alive for as long as the descriptor is used."""
+    caller keeps alive for as long as the descriptor is used; `table_avg_len` is a host sequence
+    of T floats (or None), of which the descriptor keeps its own copy."""
     if table_hints is not None:
         if table_hints.dtype != torch.uint8 or table_hints.numel() != num_tables:
             raise ValueError("table_hints must be a uint8 tensor with one entry per table")
-    return emb_bag_desc(num_tables=num_tables, dim=dim, table_dtype=table_dtype, mode=mode,
+    desc = emb_bag_desc(num_tables=num_tables, dim=dim, table_dtype=table_dtype, mode=mode,
                         batch=batch, num_lookups=num_lookups, out_ld=out_ld,
                         max_table_rows=max_table_rows, table_hints=_ptr(table_hints))
+    _attach_avg_len(desc, table_avg_len, num_tables)
+    return desc
+
+
+def _attach_avg_len(desc, table_avg_len, num_tables: int) -> None:
+    if table_avg_len is None:
+        return
+    if len(table_avg_len) != num_tables:
+        raise ValueError("table_avg_len must have one entry per table")
+    arr = (ctypes.c_float * num_tables)(*[float(x) for x in table_avg_len])
+    desc.table_avg_len = ctypes.cast(arr, ctypes.POINTER(ctypes.c_float))
+    desc._avg_len_keepalive = arr
 
 
 def emb_bag_forward(desc: emb_bag_desc, tables: torch.Tensor, table_offsets: torch.Tensor,
@@ -145,9 +160,10 @@ def emb_bag_forward(desc: emb_bag_desc, tables: torch.Tensor, table_offsets: tor
 
 def make_mixed_desc(dims, batch: int, table_dtype: int, mode: int, num_lookups: int,
                     out_ld: int = 0, max_table_bytes: int = 0,
-                    table_hints: Optional[torch.Tensor] = None) -> emb_bag_mixed_desc:
-    """Host descriptor for tables of different widths; `dims` is a sequence of the T widths (the
-    descriptor keeps its own host copy alive)."""
+                    table_hints: Optional[torch.Tensor] = None,
+                    table_avg_len=None) -> emb_bag_mixed_desc:
+    """Host descriptor for tables of different widths; `dims` is a sequence of the T widths and
+    `table_avg_len` an optional sequence of T floats (the descriptor keeps its own host copies)."""
     arr = (ctypes.c_int32 * len(dims))(*[int(d) for d in dims])
     desc = emb_bag_mixed_desc(num_tables=len(dims), table_dtype=table_dtype, mode=mode, reserved=0,
                               batch=batch, num_lookups=num_lookups, out_ld=out_ld,
@@ -155,6 +171,7 @@ def make_mixed_desc(dims, batch: int, table_dtype: int, mode: int, num_lookups: 
                               dims=ctypes.cast(arr, ctypes.POINTER(ctypes.c_int32)),
                               table_hints=_ptr(table_hints))
     desc._dims_keepalive = arr
+    _attach_avg_len(desc, table_avg_len, len(dims))
     return desc
 
 
@@ -181,10 +198,12 @@ def _plan(fn, where: str, desc, has_weights: bool, with_order: bool, *which):
     return (plan, list(order)[:int(plan.tables)]) if with_order else plan
 
 
-def emb_bag_plan_forward(desc: emb_bag_desc, has_weights: bool = False, with_order: bool = False):
-    """What emb_bag_forward would launch for `desc` under the current tuning (host only, no GPU
-    needed).  Returns the plan, or (plan, table order) with `with_order`."""
-    return _plan(_lib.emb_bag_plan_forward, "emb_bag_plan_forward", desc, has_weights, with_order)
+def emb_bag_plan_forward(desc: emb_bag_desc, has_weights: bool = False, with_order: bool = False,
+                         which: int = 0):
+    """Launch number `which` of what emb_bag_forward would do for `desc` under the current tuning
+    (host only, no GPU needed).  Returns the plan, or (plan, table order) with `with_order`."""
+    return _plan(_lib.emb_bag_plan_forward, "emb_bag_plan_forward", desc, has_weights, with_order,
+                 int(which))
 
 
 def emb_bag_plan_forward_mixed(desc: emb_bag_mixed_desc, has_weights: bool = False,

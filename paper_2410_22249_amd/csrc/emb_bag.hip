@@ -273,9 +273,51 @@ int precheck_uniform(const emb_bag_desc* desc, bool weighted, uint32_t* row_byte
   return EMB_OK;
 }
 
-// The host-side decisions of emb_bag_forward for a checked descriptor with batch > 0.
+// Append launches over the tables `ids` (all T tables in their own order if ids is empty) that
+// share everything in `proto` except the grid; a launch that needs a table list takes at most
+// kMaxOrdered tables.  `units` (16-byte segments per row, indexed like ids) may be empty.
+void add_launches(const Launch& proto, int64_t T, const std::vector<uint16_t>& ids,
+                  const std::vector<uint16_t>& units, std::vector<Launch>* launches) {
+  if (ids.empty()) {
+    launches->push_back(proto);
+    plan_grid(T, nullptr, nullptr, false, &launches->back());
+    return;
+  }
+  for (size_t first = 0; first < ids.size(); first += kMaxOrdered) {
+    const size_t left = ids.size() - first;
+    const int64_t n = (int64_t)(left < (size_t)kMaxOrdered ? left : (size_t)kMaxOrdered);
+    bool differ = false;
+    for (int64_t i = 1; i < n && !units.empty() && !differ; ++i)
+      differ = units[first + (size_t)i] != units[first];
+    launches->push_back(proto);
+    plan_grid(n, ids.data() + first, differ ? units.data() + first : nullptr, false,
+              &launches->back());
+  }
+}
+
+// Turn `proto` (a wave-kernel launch of a uniform call) into a stream-kernel launch over
+// `tables` tables of average bag length avg_len; false if the stream kernel cannot take it.
+bool make_stream(Launch* L, const emb_bag_desc* desc, bool weighted, int depth, double avg_len,
+                 int64_t tables, int64_t out_ld) {
+  const int lpr = L->lpr, groups = kWaveSize / lpr;
+  const int64_t B = desc->batch;
+  const int64_t m = stream_bags_per_group(avg_len, lpr, tables, B);
+  // the wavefront's output rows are addressed through one buffer with 32-bit offsets
+  if ((uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u > kBufMaxBytes) return false;
+  KernelFn fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted, false);
+  if (!fn) return false;
+  L->fn = fn;
+  L->kernel = EMB_KERNEL_STREAM;
+  L->depth = depth <= 4 || lpr < 8 ? 4 : 8;  // the depths that kernel is built with
+  L->p.bags_per_group = (uint32_t)m;
+  L->p.wpt = (uint32_t)((B + groups * m - 1) / (groups * m));
+  return true;
+}
+
+// The host-side decisions of emb_bag_forward for a checked descriptor with batch > 0: one launch,
+// or two when desc->table_avg_len separates tables with short bags from the others.
 int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, int64_t out_ld,
-                 Launch* L) {
+                 std::vector<Launch>* launches) {
   const int64_t T = desc->num_tables, B = desc->batch, D = desc->dim;
   const int64_t slabs = (row_bytes + kSlabBytes - 1) / kSlabBytes;
   const int64_t num_work = T * B * slabs;
@@ -293,12 +335,12 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   int depth = (int)g_tuning.depth;
   if (depth == 0) depth = (desc->table_dtype == EMB_F32 && row_bytes >= 512) ? 8 : 4;
 
-  KParams& p = L->p;
+  Launch wave;  // the one-wavefront-per-bag launch; the stream launch is derived from it
+  KParams& p = wave.p;
   p.num_lookups = desc->num_lookups;
   p.out_ld = out_ld;
   p.max_rows = desc->max_table_rows;
   p.B = (uint32_t)B;
-  p.num_work = (uint32_t)num_work;
   p.wpt = (uint32_t)(B * slabs);
   p.slabs = (uint32_t)slabs;
   p.row_bytes = row_bytes;
@@ -306,38 +348,55 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
   p.bags_per_group = 0;
-  L->fn = nullptr;
-  L->kernel = EMB_KERNEL_WAVE;
-  L->lpr = lpr;
-  L->depth = depth;
-  L->buf = buf;
+  wave.kernel = EMB_KERNEL_WAVE;
+  wave.lpr = lpr;
+  wave.depth = depth;
+  wave.buf = buf;
+  const int op = desc->mode == EMB_MAX ? kOpMax : (weighted ? kOpWeighted : kOpSum);
+  if (op == kOpMax) wave.depth = depth <= 4 ? 4 : 8;
+  wave.fn = pick_kernel(lpr, desc->table_dtype, depth, op, buf);
+  if (!wave.fn) return EMB_ERR_BAD_TUNING;
 
-  // Short bags: a lane group streams several consecutive bags (emb_bag_stream.hip).  The host
-  // knows the average bag length, NL / (T * B), and nothing else about the lengths.
+  // Short bags: a lane group streams several consecutive bags (emb_bag_stream.hip).  Without
+  // per-table lengths the host knows the call's average bag length, NL / (T * B), and nothing
+  // else; with them each table is judged by its own.
   const int groups = kWaveSize / lpr;
+  const double threshold = kStreamBelowRowLoads * groups;
   const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
-  if (g_tuning.stream != 0 && slabs == 1 && buf && desc->mode != EMB_MAX &&
-      (g_tuning.stream == 1 || avg_len < kStreamBelowRowLoads * groups)) {
-    const int64_t m = stream_bags_per_group(avg_len, lpr, T, B);
-    // the wavefront's output rows are addressed through one buffer with 32-bit offsets
-    if ((uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u <= kBufMaxBytes) {
-      L->fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted, false);
-      if (L->fn) {
-        L->kernel = EMB_KERNEL_STREAM;
-        L->depth = depth <= 4 || lpr < 8 ? 4 : 8;  // the depths that kernel is built with
-        p.bags_per_group = (uint32_t)m;
-        p.wpt = (uint32_t)((B + groups * m - 1) / (groups * m));
-        p.num_work = (uint32_t)(T * p.wpt);
+  const bool can_stream = g_tuning.stream != 0 && slabs == 1 && buf && desc->mode != EMB_MAX;
+  const std::vector<uint16_t> none;
+  if (can_stream && g_tuning.stream == -1 && desc->table_avg_len && T <= 65535) {
+    std::vector<uint16_t> short_ids, long_ids;
+    double short_sum = 0.0;
+    for (int64_t t = 0; t < T; ++t) {
+      if ((double)desc->table_avg_len[t] < threshold) {
+        short_ids.push_back((uint16_t)t);
+        short_sum += (double)desc->table_avg_len[t];
+      } else {
+        long_ids.push_back((uint16_t)t);
       }
     }
+    Launch stream = wave;
+    if (!short_ids.empty() && !long_ids.empty() &&
+        make_stream(&stream, desc, weighted, depth, short_sum / (double)short_ids.size(),
+                    (int64_t)short_ids.size(), out_ld)) {
+      add_launches(stream, T, short_ids, none, launches);
+      add_launches(wave, T, long_ids, none, launches);
+      return EMB_OK;
+    }
+    // all tables on one side: one launch without a list
+    if (long_ids.empty() && make_stream(&stream, desc, weighted, depth, avg_len, T, out_ld))
+      add_launches(stream, T, none, none, launches);
+    else
+      add_launches(wave, T, none, none, launches);
+    return EMB_OK;
   }
-  if (!L->fn) {
-    const int op = desc->mode == EMB_MAX ? kOpMax : (weighted ? kOpWeighted : kOpSum);
-    if (op == kOpMax) L->depth = depth <= 4 ? 4 : 8;
-    L->fn = pick_kernel(lpr, desc->table_dtype, depth, op, buf);
-  }
-  if (!L->fn) return EMB_ERR_BAD_TUNING;
-  plan_grid(T, nullptr, nullptr, false, L);
+  Launch stream = wave;
+  if (can_stream && (g_tuning.stream == 1 || avg_len < threshold) &&
+      make_stream(&stream, desc, weighted, depth, avg_len, T, out_ld))
+    add_launches(stream, T, none, none, launches);
+  else
+    add_launches(wave, T, none, none, launches);
   return EMB_OK;
 }
 
@@ -406,19 +465,22 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
 
   // which lanes-per-row classes (4, 8, 16, 32, 64) go to the stream kernel
   const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
-  bool streams[7] = {false, false, false, false, false, false, false};  // by log2(lanes per row)
-  bool any_stream = false;
-  if (g_tuning.stream != 0 && buf && desc->mode != EMB_MAX) {
-    for (int lg = 2; lg <= 6; ++lg) {
-      const int groups = kWaveSize >> lg;
-      const int64_t m = stream_bags_per_group(avg_len, 1 << lg, T, B);
-      streams[lg] = (g_tuning.stream == 1 || avg_len < kStreamBelowRowLoads * groups) &&
-                    (uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u <= kBufMaxBytes;
-    }
+  // (judged by the call's average bag length, or table by table with desc->table_avg_len)
+  const bool can_stream = g_tuning.stream != 0 && buf && desc->mode != EMB_MAX;
+  const bool per_table = g_tuning.stream == -1 && desc->table_avg_len != nullptr;
+  bool fits[7] = {false, false, false, false, false, false, false};  // by log2(lanes per row)
+  for (int lg = 2; lg <= 6 && can_stream; ++lg) {
+    // the wavefront's output rows are addressed through one buffer with 32-bit offsets: checked
+    // for the largest group size the class can get
+    const int groups = kWaveSize >> lg;
+    int64_t m = g_tuning.bags_per_group ? g_tuning.bags_per_group : kStreamMaxAutoBags;
+    if (m > (1 << lg) - 1) m = (1 << lg) - 1;
+    fits[lg] = (uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u <= kBufMaxBytes;
   }
   std::vector<uint16_t> units((size_t)T);
-  std::vector<uint8_t> cls((size_t)T);
-  bool widths_differ = false;
+  std::vector<uint8_t> cls((size_t)T);   // log2(lanes per row)
+  std::vector<uint8_t> streamed((size_t)T);
+  bool widths_differ = false, any_stream = false;
   for (int64_t t = 0; t < T; ++t) {
     const int64_t d = desc->dims[t];
     const int64_t rb = is_quant(desc->table_dtype) ? d + 8 : d * elem_bytes;
@@ -427,7 +489,10 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
     while ((16 << lg) < rb) ++lg;
     cls[(size_t)t] = (uint8_t)lg;
     if (d != desc->dims[0]) widths_differ = true;
-    if (streams[lg]) any_stream = true;
+    const double len_t = per_table ? (double)desc->table_avg_len[t] : avg_len;
+    streamed[(size_t)t] = fits[lg] && (g_tuning.stream == 1 ||
+                                       len_t < kStreamBelowRowLoads * (kWaveSize >> lg));
+    if (streamed[(size_t)t]) any_stream = true;
   }
 
   if (!any_stream) {  // one launch of the wave kernel over all tables
@@ -439,42 +504,35 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
     return EMB_OK;
   }
 
-  // one group of tables per streamed class, one for everything else; pieces of <= kMaxOrdered
+  // one group of tables per streamed class, one for everything else
+  if (T > 65535) return EMB_ERR_BAD_SIZE;  // table numbers above 65535 cannot be listed
   for (int lg = 1; lg <= 6; ++lg) {  // lg == 1 stands for "the wave kernel's tables"
-    if (lg >= 2 && !streams[lg]) continue;
     std::vector<uint16_t> ids, u;
+    double len_sum = 0.0;
     for (int64_t t = 0; t < T; ++t) {
-      const bool streamed = streams[cls[(size_t)t]];
-      if (lg == 1 ? !streamed : (streamed && cls[(size_t)t] == lg)) {
-        // table numbers above 65535 cannot be listed: the descriptor is refused below
+      if (lg == 1 ? !streamed[(size_t)t] : (streamed[(size_t)t] && cls[(size_t)t] == lg)) {
         ids.push_back((uint16_t)t);
         u.push_back(units[(size_t)t]);
+        len_sum += per_table ? (double)desc->table_avg_len[t] : avg_len;
       }
     }
     if (ids.empty()) continue;
-    if (T > 65535) return EMB_ERR_BAD_SIZE;
-    for (size_t first = 0; first < ids.size(); first += kMaxOrdered) {
-      const int64_t n = (int64_t)(ids.size() - first < (size_t)kMaxOrdered ? ids.size() - first
-                                                                            : (size_t)kMaxOrdered);
-      launches->push_back(base);
-      Launch& L = launches->back();
-      bool differ = false;
-      for (int64_t i = 1; i < n && !differ; ++i) differ = u[first + (size_t)i] != u[first];
-      if (lg >= 2) {
-        const int lpr = 1 << lg;
-        const int groups = kWaveSize / lpr;
-        const int64_t m = stream_bags_per_group(avg_len, lpr, n, B);
-        L.fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted, true);
-        if (!L.fn) return EMB_ERR_BAD_TUNING;
-        L.kernel = EMB_KERNEL_STREAM;
-        L.lpr = lpr;
-        L.depth = depth <= 4 || lpr < 8 ? 4 : 8;
-        L.p.row_bytes = (uint32_t)lpr * 16u;
-        L.p.bags_per_group = (uint32_t)m;
-        L.p.wpt = (uint32_t)((B + groups * m - 1) / (groups * m));
-      }
-      plan_grid(n, ids.data() + first, differ ? u.data() + first : nullptr, false, &L);
+    Launch L = base;
+    if (lg >= 2) {
+      const int lpr = 1 << lg;
+      const int groups = kWaveSize / lpr;
+      const int64_t m = stream_bags_per_group(len_sum / (double)ids.size(), lpr,
+                                              (int64_t)ids.size(), B);
+      L.fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted, true);
+      if (!L.fn) return EMB_ERR_BAD_TUNING;
+      L.kernel = EMB_KERNEL_STREAM;
+      L.lpr = lpr;
+      L.depth = depth <= 4 || lpr < 8 ? 4 : 8;
+      L.p.row_bytes = (uint32_t)lpr * 16u;
+      L.p.bags_per_group = (uint32_t)m;
+      L.p.wpt = (uint32_t)((B + groups * m - 1) / (groups * m));
     }
+    add_launches(L, T, ids, u, launches);
   }
   return EMB_OK;
 }
@@ -541,11 +599,15 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   if (desc->num_lookups > 0 && !indices) return EMB_ERR_NULL_PTR;
   if ((reinterpret_cast<uintptr_t>(tables) | reinterpret_cast<uintptr_t>(out)) & 15)
     return EMB_ERR_ALIGNMENT;
-  Launch L;
-  rc = plan_uniform(desc, per_sample_weights != nullptr, row_bytes, out_ld, &L);
+  std::vector<Launch> launches;
+  rc = plan_uniform(desc, per_sample_weights != nullptr, row_bytes, out_ld, &launches);
   if (rc != EMB_OK) return rc;
-  return launch(L, tables, table_offsets, indices, offsets, per_sample_weights, desc->table_hints,
+  for (const Launch& L : launches) {  // disjoint tables: the launches are independent
+    rc = launch(L, tables, table_offsets, indices, offsets, per_sample_weights, desc->table_hints,
                 nullptr, out, stream);
+    if (rc != EMB_OK) return rc;
+  }
+  return EMB_OK;
 }
 
 int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
@@ -572,8 +634,8 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   return EMB_OK;
 }
 
-int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, emb_bag_plan* plan,
-                         uint16_t* table_order) {
+int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, int32_t which,
+                         emb_bag_plan* plan, uint16_t* table_order) {
   if (!plan) return EMB_ERR_NULL_PTR;
   memset(plan, 0, sizeof *plan);
   uint32_t row_bytes = 0;
@@ -581,10 +643,11 @@ int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, emb_bag_plan
   int rc = precheck_uniform(desc, has_weights != 0, &row_bytes, &out_ld);
   if (rc != EMB_OK) return rc;
   if (desc->batch == 0) return EMB_OK;
-  Launch L;
-  rc = plan_uniform(desc, has_weights != 0, row_bytes, out_ld, &L);
+  std::vector<Launch> launches;
+  rc = plan_uniform(desc, has_weights != 0, row_bytes, out_ld, &launches);
   if (rc != EMB_OK) return rc;
-  report(L, 1, plan, table_order);
+  if (which < 0 || (size_t)which >= launches.size()) return EMB_ERR_BAD_SIZE;
+  report(launches[(size_t)which], (int32_t)launches.size(), plan, table_order);
   return EMB_OK;
 }
 

@@ -170,7 +170,7 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t tpos, w_in_table;
   if (!decode_work(p, wave, &tpos, &w_in_table)) return;
-  const uint32_t t = (MIXED && p.listed) ? order.t[tpos] : tpos;
+  const uint32_t t = p.listed ? order.t[tpos] : tpos;
   const uint32_t M = p.bags_per_group;                   // 1 .. LPR - 1
   const uint32_t b0 = w_in_table * (uint32_t)G * M;      // first bag of the wavefront, < B
   const uint32_t nbw = p.B - b0 < (uint32_t)G * M ? p.B - b0 : (uint32_t)G * M;  // its bags

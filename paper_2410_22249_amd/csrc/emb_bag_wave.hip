@@ -70,7 +70,7 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t tpos, w_in_table;
   if (!decode_work(p, wave, &tpos, &w_in_table)) return;
-  const uint32_t t = (MIXED && p.listed) ? order.t[tpos] : tpos;
+  const uint32_t t = p.listed ? order.t[tpos] : tpos;
   uint32_t b = w_in_table, slab = 0;
   if (p.slabs > 1) {
     b = w_in_table / p.slabs;

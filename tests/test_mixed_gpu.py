@@ -272,3 +272,27 @@ def test_mixed_onehot_full_size_sampled(oracle):
         want = gen.table_values(wl.seed, base[t] + rows, wl.dims[t], wl.dtype, wl.kind)
         got = out[torch.from_numpy(bs).to(DEV), cols[t]:cols[t + 1]].cpu().numpy()
         assert np.array_equal(got, want), t                  # one lookup per bag: the row itself
+
+
+def test_mixed_widths_with_per_table_bag_lengths(oracle):
+    """Short-bag and long-bag tables of several widths in one call: table_avg_len sends each
+    short-bag table to the stream launch of its row class and the others to the wave launch."""
+    specs = (("fixed", 1), ("uniform", 60, 140), ("uniform", 0, 2), ("fixed", 90), ("fixed", 2))
+    wl = _wl("f32", pooling=("per_table", specs), B=130)
+    batch = gen.make_batches(wl, 1)[0]
+    tabs = gen.mixed_host_tables(wl)
+    arena = _device_arena(wl)
+    avg = gen.table_avg_len(wl, batch)
+    total = int(sum(wl.dims))
+    ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, "mean")
+    desc = emb.make_mixed_desc(wl.dims, wl.B, emb.EMB_F32, emb.EMB_MEAN, batch.num_lookups, 0,
+                               int(np.diff(wl.table_byte_offsets()).max()), None, avg)
+    n = emb.emb_bag_plan_forward_mixed(desc).num_launches
+    assert n >= 3
+    kinds = {emb.emb_bag_plan_forward_mixed(desc, which=w).kernel for w in range(n)}
+    assert kinds == {emb.EMB_KERNEL_WAVE, emb.EMB_KERNEL_STREAM}
+    out = torch.full((wl.B, total), float("nan"), dtype=torch.float32, device=DEV)
+    emb.emb_bag_forward_mixed(desc, arena, to_dev(wl.table_byte_offsets()), to_dev(wl.out_offsets()),
+                              to_dev(batch.indices), to_dev(batch.offsets), None, out)
+    torch.cuda.synchronize()
+    assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, "mixed per-table lengths")

@@ -242,3 +242,59 @@ def test_mixed_plan_never_streams_max_pooling_or_unbounded_tables():
     assert first.num_launches == 4
     sizes = [_mixed_plan([32, 64] * 1500, 2000, 1, which=w)[0].tables for w in range(4)]
     assert sorted(sizes) == [476, 476, 1024, 1024]
+
+
+def test_per_table_bag_lengths_split_a_uniform_call_in_two():
+    """With table_avg_len the choice of kernel is made per table: short-bag tables in a stream
+    launch, the others in a wave launch, each with its table list."""
+    T, B = 26, 32768
+    lens = [100.0 if t % 4 == 3 and t < 24 else 1.0 for t in range(T)]
+    nl = int(sum(lens) * B)
+
+    def plans(avg=lens, **kw):
+        desc = emb.make_desc(T, B, 64, emb.EMB_F32, kw.pop("mode", emb.EMB_SUM), nl, 0, 1_000_000,
+                             table_avg_len=avg)
+        first = emb.emb_bag_plan_forward(desc)
+        return [emb.emb_bag_plan_forward(desc, False, True, w) for w in range(first.num_launches)]
+
+    assert len(plans(avg=None)) == 1 and plans(avg=None)[0][0].kernel == emb.EMB_KERNEL_WAVE  # average 23.8
+    both = plans()
+    assert [p.kernel for p, _ in both] == [emb.EMB_KERNEL_STREAM, emb.EMB_KERNEL_WAVE]
+    short = [t for t in range(T) if lens[t] == 1.0]
+    assert both[0][1] == short and both[1][1] == [t for t in range(T) if lens[t] == 100.0]
+    assert both[0][0].bags_per_group == 4 and both[0][0].listed == 1 and both[1][0].listed == 1
+    for plan, order in both:
+        table, wave, _ = _simulate(plan, plan.tables, order)
+        flat = table * plan.waves_per_table + wave
+        assert len(np.unique(flat)) == len(flat) == plan.tables * plan.waves_per_table
+    # everything on one side: one launch, no list
+    one = plans(avg=[1.0] * T)
+    assert len(one) == 1 and one[0][0].kernel == emb.EMB_KERNEL_STREAM and one[0][0].listed == 0
+    one = plans(avg=[50.0] * T)
+    assert len(one) == 1 and one[0][0].kernel == emb.EMB_KERNEL_WAVE and one[0][0].listed == 0
+    # the explicit settings and max pooling override the per-table choice
+    with tuning(stream=0):
+        assert len(plans()) == 1 and plans()[0][0].kernel == emb.EMB_KERNEL_WAVE
+    with tuning(stream=1):
+        assert len(plans()) == 1 and plans()[0][0].kernel == emb.EMB_KERNEL_STREAM
+    assert len(plans(mode=emb.EMB_MAX)) == 1
+    with pytest.raises(ValueError):
+        emb.make_desc(T, B, 64, emb.EMB_F32, emb.EMB_SUM, nl, 0, 0, table_avg_len=[1.0])
+
+
+def test_per_table_bag_lengths_in_a_mixed_call():
+    dims = [32, 64, 128, 256] * 3
+    lens = [1.0, 50.0, 1.0, 50.0, 2.0, 2.0, 50.0, 50.0, 1.0, 1.0, 1.0, 1.0]
+    desc = emb.make_mixed_desc(dims, 4096, emb.EMB_F32, emb.EMB_SUM, int(sum(lens) * 4096), 0, 1 << 30,
+                               table_avg_len=lens)
+    n = emb.emb_bag_plan_forward_mixed(desc).num_launches
+    got = {}
+    for w in range(n):
+        plan, order = emb.emb_bag_plan_forward_mixed(desc, False, True, w)
+        got[(plan.kernel, plan.lanes_per_row)] = sorted(order)   # (the wave launch orders by width)
+    # short tables by class: widths 32 -> 8 lanes, 64 -> 16, 128 -> 32, 256 -> 64
+    assert got == {(emb.EMB_KERNEL_WAVE, 0): [1, 3, 6, 7],
+                   (emb.EMB_KERNEL_STREAM, 8): [0, 4, 8],
+                   (emb.EMB_KERNEL_STREAM, 16): [5, 9],
+                   (emb.EMB_KERNEL_STREAM, 32): [2, 10],
+                   (emb.EMB_KERNEL_STREAM, 64): [11]}

@@ -207,3 +207,27 @@ def test_stream_kernel_replays_from_a_hip_graph(oracle):
         g.replay()
         torch.cuda.synchronize()
         assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, "stream graph replay")
+
+
+@pytest.mark.parametrize("name", ["small_f32_d64", "small_f16_d256", "small_u8_d120"])
+def test_per_table_bag_lengths_give_two_launches_and_the_same_result(oracle, name):
+    """Tables with one lookup per bag next to tables with long bags: with table_avg_len the call
+    is planned as a stream launch plus a wave launch; the result still matches the oracle."""
+    import paper_2410_22249_amd as emb
+    specs = (("fixed", 1), ("uniform", 60, 140), ("uniform", 0, 2), ("fixed", 90))
+    wl, batch, arena = _problem(name, pooling=("per_table", specs), B=150)
+    avg = gen.table_avg_len(wl, batch)
+    dev = upload_arena(arena)
+    toff, idx, off = to_dev(wl.table_offsets()), to_dev(batch.indices), to_dev(batch.offsets)
+    for mode in ("sum", "mean"):
+        ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, mode)
+        desc = emb.make_desc(wl.T, wl.B, wl.D, emb.DTYPES[wl.dtype], emb.MODES[mode],
+                             batch.num_lookups, 0, max(wl.rows), None, avg)
+        assert emb.emb_bag_plan_forward(desc).num_launches == 2
+        for kw in (dict(), dict(xcd_remap=1), dict(depth=8)):
+            out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
+            with tuning(**kw):
+                emb.emb_bag_forward(desc, dev, toff, idx, off, None, out)
+            torch.cuda.synchronize()
+            assert_close_to_oracle(out.cpu().numpy(), ref, bound, wl.dtype != "f32",
+                                   f"per-table lengths/{name}/{mode}/{kw}")
