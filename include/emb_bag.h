@@ -71,10 +71,11 @@ extern "C" {
 /*
  * Shape of one call (HOST struct, read during the call only).
  *
- *   T = num_tables, B = batch, D = dim.  Row size in bytes = D * sizeof(element) (D + 8 for
- *   EMB_U8ROW) must be a multiple of 16 and at most 65536 (1024 for EMB_U8ROW).  Table t holds R_t = table_offsets[t+1] - table_offsets[t]
- *   rows, stored contiguously in one arena starting at arena row table_offsets[t]; D and the
- *   element type are the same for every table (the paper's tables are homogeneous, Sec. 5).
+ *   T = num_tables, B = batch, D = dim.  Row size in bytes = D * sizeof(element) (D + 8 for the
+ *   quantised types) must be a multiple of 16 and at most 65536 (1024 for the quantised types).
+ *   Table t holds R_t = table_offsets[t+1] - table_offsets[t] rows, stored contiguously in one
+ *   arena starting at arena row table_offsets[t]; D and the element type are the same for every
+ *   table (the paper's tables are homogeneous, Sec. 5; see emb_bag_forward_mixed otherwise).
  */
 typedef struct emb_bag_desc {
   int32_t num_tables;     /* T >= 1 */
@@ -114,7 +115,7 @@ typedef struct emb_bag_desc {
  *
  *   desc                HOST    shape, see above
  *   tables              DEVICE  arena [sum_t R_t, D] row-major, 16-byte aligned, f32 / f16 / bf16,
- *                               or [sum_t R_t, D + 8] bytes for EMB_U8ROW
+ *                               or [sum_t R_t, D + 8] bytes for EMB_U8ROW / EMB_FP8ROW
  *   table_offsets       DEVICE  int64 [T+1], first arena row of each table, non-decreasing
  *   indices             DEVICE  int64 [NL], table-local row ids, bags stored in (t, b) order
  *   offsets             DEVICE  int64 [T*B+1], CSR over bags: offsets[0] = 0, offsets[T*B] = NL
@@ -127,6 +128,10 @@ typedef struct emb_bag_desc {
  * harmless: bag bounds are clamped to [0, NL] (a decreasing pair gives an empty bag) and a
  * lookup whose index is outside [0, R_t) contributes zero.  Use emb_bag_validate to count them.
  * Host-visible argument errors return a negative code and enqueue nothing.
+ *
+ * One call is one kernel launch; with desc->table_avg_len it may be two (tables with short bags,
+ * the other tables), enqueued on `stream` one after the other and writing disjoint columns
+ * (emb_bag_plan_forward lists them).  More than 65535 tables are then served by one kernel.
  */
 int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t* table_offsets,
                     const int64_t* indices, const int64_t* offsets,
