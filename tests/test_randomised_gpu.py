@@ -1,7 +1,8 @@
 """Seeded random problems over everything the forward calls accept: uniform and mixed widths, all
 element types, the three pooling modes, weights, short / long / per-table bag lengths (with and
 without table_avg_len), hints, padded outputs, and every tuning key.  Each case is checked against
-the CPU oracle; a failure names its case, which the seed reproduces."""
+the CPU oracle, and guard rows around the output show that no store leaves it; a failure names its
+case, which the seed reproduces."""
 import numpy as np
 import pytest
 import torch
@@ -75,7 +76,9 @@ def test_random_problems(oracle, block):
         print(what, flush=True)
         idx = to_dev(batch.indices) if batch.num_lookups else None
         off, w = to_dev(batch.offsets), to_dev(batch.weights)
-        out = torch.full((B, ld), -3.0, dtype=torch.float32, device=DEV)
+        guard = 3                        # rows before and after `out` that no store may touch
+        big = torch.full((B + 2 * guard, ld), -3.0, dtype=torch.float32, device=DEV)
+        out = big[guard:guard + B]
         if mixed:
             tabs = gen.mixed_host_tables(wl)
             ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, B, mode,
@@ -96,6 +99,8 @@ def test_random_problems(oracle, block):
             with tuning(**kw):
                 emb.emb_bag_forward(desc, arena, to_dev(wl.table_offsets()), idx, off, w, out)
         torch.cuda.synchronize()
-        got = out.cpu().numpy()
+        whole = big.cpu().numpy()
+        assert np.all(whole[:guard] == -3.0) and np.all(whole[guard + B:] == -3.0), what
+        got = whole[guard:guard + B]
         assert np.all(got[:, total:] == -3.0), what
         assert_close_to_oracle(got[:, :total], ref[:, :total], bound[:, :total], dtype != "f32", what)
