@@ -296,3 +296,28 @@ def test_mixed_widths_with_per_table_bag_lengths(oracle):
                               to_dev(batch.indices), to_dev(batch.offsets), None, out)
     torch.cuda.synchronize()
     assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, "mixed per-table lengths")
+
+
+@pytest.mark.parametrize("pooling", [("uniform", 0, 3), ("uniform", 20, 60), ("uniform", 60, 100)])
+def test_mixed_widths_with_more_tables_than_one_list_holds(oracle, pooling):
+    """2,600 tables of four widths (three lanes-per-row classes, the narrowest with 1,300 tables):
+    launches that take their tables from a list are cut into pieces of at most 1,024 tables
+    (short bags), and a single wave launch over more tables than that keeps the natural block
+    order (long bags)."""
+    T = 2600
+    dims = tuple((8, 16, 32, 64)[t % 4] for t in range(T))
+    wl = gen.MixedWorkload(name="many", T=T, rows=(7,) * T, dims=dims, dtype="f32", B=33,
+                           pooling=pooling, dists=(("uniform",),) * T, seed=0x5EED0C10)
+    batch = gen.make_batches(wl, 1)[0]
+    tabs = gen.mixed_host_tables(wl)
+    arena = _device_arena(wl)
+    desc = emb.make_mixed_desc(dims, wl.B, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups, 0,
+                               int(np.diff(wl.table_byte_offsets()).max()))
+    n = emb.emb_bag_plan_forward_mixed(desc).num_launches
+    # short bags: classes of 1300 + 650 + 650 tables -> 2 + 1 + 1 stream launches; mid-length bags:
+    # the narrowest class streams (2 launches), the other 1300 tables share 2 wave launches
+    assert n == (1 if pooling[1] == 60 else 4)
+    ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, "sum")
+    with tuning(xcd_remap=1):
+        got = _forward(wl, arena, batch, "sum").cpu().numpy()
+    assert_close_to_oracle(got, ref, bound, False, f"2600 tables/{pooling}")
