@@ -231,3 +231,28 @@ def test_per_table_bag_lengths_give_two_launches_and_the_same_result(oracle, nam
             torch.cuda.synchronize()
             assert_close_to_oracle(out.cpu().numpy(), ref, bound, wl.dtype != "f32",
                                    f"per-table lengths/{name}/{mode}/{kw}")
+
+
+def test_per_table_bag_lengths_with_more_tables_than_one_list_holds(oracle):
+    """2,600 tables, every other one with one-lookup bags: 1,300 tables per kernel, so each side is
+    cut into launches of at most 1,024 listed tables."""
+    import paper_2410_22249_amd as emb
+    T = 2600
+    specs = (("fixed", 1), ("uniform", 40, 80))
+    wl = gen.Workload(name="many", T=T, rows=(9,) * T, D=8, dtype="f32", B=21,
+                      pooling=("per_table", specs), dists=(("uniform",),) * T, seed=0x5EED0E50)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "sum")
+    desc = emb.make_desc(T, wl.B, wl.D, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups, 0, 9, None,
+                         gen.table_avg_len(wl, batch))
+    n = emb.emb_bag_plan_forward(desc).num_launches
+    assert n == 4
+    sizes = sorted(emb.emb_bag_plan_forward(desc, which=w).tables for w in range(n))
+    assert sizes == [276, 276, 1024, 1024]
+    out = torch.full((wl.B, T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
+    with tuning(xcd_remap=1):
+        emb.emb_bag_forward(desc, upload_arena(arena), to_dev(wl.table_offsets()),
+                            to_dev(batch.indices), to_dev(batch.offsets), None, out)
+    torch.cuda.synchronize()
+    assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, "2600 tables, per-table lengths")
