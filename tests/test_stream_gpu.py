@@ -231,6 +231,18 @@ def test_per_table_bag_lengths_give_two_launches_and_the_same_result(oracle, nam
             torch.cuda.synchronize()
             assert_close_to_oracle(out.cpu().numpy(), ref, bound, wl.dtype != "f32",
                                    f"per-table lengths/{name}/{mode}/{kw}")
+        # both launches of the call are captured into one HIP graph and replay correctly
+        stream = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            emb.emb_bag_forward(desc, dev, toff, idx, off, None, out, stream)
+        for _ in range(2):
+            out.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert_close_to_oracle(out.cpu().numpy(), ref, bound, wl.dtype != "f32",
+                                   f"per-table lengths/{name}/{mode}/graph")
 
 
 def test_per_table_bag_lengths_with_more_tables_than_one_list_holds(oracle):
