@@ -249,7 +249,7 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
  * position unit / xcd_pieces of the launch, and wavefront w of workgroup (slot % blocks_per_piece) of that
  * piece is wavefront (unit % xcd_pieces) * waves_per_piece + (slot % blocks_per_piece) * 4 + w
  * of the table if that number is below waves_per_piece within the piece and below
- * waves_per_table overall (otherwise it has no work).  With xcd_pieces == 0 wavefront
+ * waves_per_table overall, and unit is below tables * xcd_pieces (otherwise it has no work).  With xcd_pieces == 0 wavefront
  * 4 * g + w of the grid is wavefront number 4 * g + w in position-major order.
  */
 #define EMB_KERNEL_WAVE 0   /* one wavefront per bag (per 1-KiB column slab of it) */
@@ -291,6 +291,8 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   rows are fetched into one or two of the eight L2s instead of all eight
  *                   (the stand-in for the L2 pinning of Sec. 4.3); 0 = natural order;
  *                   -1 = automatic (on for large launches)
+ *   "xcd_pieces"    pieces per table in the XCD-affine order: 1, 2, 4 or 8; 0 = automatic (the
+ *                   smallest power of two that gives every XCD the same number of pieces)
  *   "use_hints"     1 (default) = honour desc->table_hints, 0 = ignore them
  *   "stream"        the kernel for short bags, in which a lane group streams several consecutive
  *                   bags so that row loads stay in flight across bag boundaries (the prefetch of

@@ -114,6 +114,7 @@ struct Tuning {
   int64_t use_hints = 1;
   int64_t stream = -1;          // short-bag kernel: -1 = by average bag length, 0 = never, 1 = when possible
   int64_t bags_per_group = 0;   // its consecutive bags per lane group: 0 = automatic
+  int64_t xcd_pieces = 0;       // pieces per table in XCD-affine order: 0 = automatic, 1, 2, 4, 8
 };
 Tuning g_tuning;
 
@@ -195,7 +196,7 @@ void plan_grid(int64_t n, const uint16_t* ids, const uint16_t* row_units, bool n
   KParams& p = L->p;
   L->tables = n;
   p.num_work = (uint32_t)(n * (int64_t)p.wpt);
-  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = p.listed = 0;
+  p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = p.xcd_units = p.listed = 0;
   uint32_t blocks = (uint32_t)(((uint64_t)p.num_work + kWavesPerBlock - 1) / kWavesPerBlock);
   const bool remap = g_tuning.xcd_remap == 1 || (g_tuning.xcd_remap == -1 && blocks >= 4096);
   bool ordered = false;
@@ -204,15 +205,20 @@ void plan_grid(int64_t n, const uint16_t* ids, const uint16_t* row_units, bool n
     // that every XCD gets the same number of pieces and neighbouring XCDs share a table
     uint32_t pshift = 0;
     while (((uint64_t)n << pshift) % 8 != 0) ++pshift;
+    if (g_tuning.xcd_pieces > 0) {  // forced: XCDs may then differ by one piece
+      pshift = 0;
+      while ((1 << pshift) < g_tuning.xcd_pieces) ++pshift;
+    }
     const uint64_t wpp = ((uint64_t)p.wpt + (1u << pshift) - 1) >> pshift;
     const uint64_t bpp = (wpp + kWavesPerBlock - 1) / kWavesPerBlock;
-    const uint64_t grid = ((uint64_t)n << pshift) * bpp;
+    const uint64_t units = (uint64_t)n << pshift;
+    const uint64_t grid = ((units + 7) / 8) * 8 * bpp;
     // Tables of different widths: position q of the order runs on the XCD set q % sets.  Deal
     // the tables out widest first, each to the set with the least work so far, so that every
     // XCD ends up with about the same number of bytes.
     const uint32_t sets = 8u >> (pshift < 3 ? pshift : 3);
     const bool ok = grid <= 0x7FFFFFFFull;
-    ordered = ok && row_units && sets > 1;
+    ordered = ok && row_units && sets > 1 && n % sets == 0;
     if (ordered) {
       uint32_t head[66];  // counting sort by width, widest first
       for (int i = 0; i < 66; ++i) head[i] = 0;
@@ -238,6 +244,7 @@ void plan_grid(int64_t n, const uint16_t* ids, const uint16_t* row_units, bool n
       p.xcd_bpp = (uint32_t)bpp;
       p.xcd_wpp = (uint32_t)wpp;
       p.xcd_pshift = pshift;
+      p.xcd_units = (uint32_t)units;
       blocks = (uint32_t)grid;
     }
   }
@@ -733,6 +740,10 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
   } else if (!strcmp(key, "bags_per_group")) {
     if (value < 0 || value > 63) return EMB_ERR_BAD_TUNING;
     g_tuning.bags_per_group = value;
+  } else if (!strcmp(key, "xcd_pieces")) {
+    if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+      return EMB_ERR_BAD_TUNING;
+    g_tuning.xcd_pieces = value;
   } else {
     return EMB_ERR_BAD_TUNING;
   }
@@ -748,6 +759,7 @@ int emb_bag_get_tuning(const char* key, int64_t* value) {
   else if (!strcmp(key, "use_hints")) *value = g_tuning.use_hints;
   else if (!strcmp(key, "stream")) *value = g_tuning.stream;
   else if (!strcmp(key, "bags_per_group")) *value = g_tuning.bags_per_group;
+  else if (!strcmp(key, "xcd_pieces")) *value = g_tuning.xcd_pieces;
   else return EMB_ERR_BAD_TUNING;
   return EMB_OK;
 }

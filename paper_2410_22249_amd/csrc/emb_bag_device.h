@@ -39,6 +39,7 @@ struct KParams {
   uint32_t xcd_bpp;
   uint32_t xcd_wpp;
   uint32_t xcd_pshift;
+  uint32_t xcd_units;    // positions * pieces: units at or beyond this have no work
   uint32_t listed;       // 1 = position q of the launch holds table TableOrder::t[q], 0 = table q
   uint32_t bags_per_group;  // stream kernel: consecutive bags owned by one lane group
 };
@@ -301,7 +302,7 @@ __device__ __forceinline__ bool decode_work(const KParams& p, uint32_t wave, uin
     const uint32_t unit = ul * 8u + xcd;
     const uint32_t w_in_piece = (slot - ul * p.xcd_bpp) * kWavesPerBlock + wave;
     const uint32_t w = (unit & ((1u << p.xcd_pshift) - 1u)) * p.xcd_wpp + w_in_piece;
-    if (w_in_piece >= p.xcd_wpp || w >= p.wpt) return false;
+    if (w_in_piece >= p.xcd_wpp || w >= p.wpt || unit >= p.xcd_units) return false;
     *tpos = unit >> p.xcd_pshift;
     *w_in_table = w;
     return true;

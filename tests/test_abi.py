@@ -127,7 +127,8 @@ def test_tuning_keys():
     import paper_2410_22249_amd as emb
     for key, good, bad in (("depth", 8, 3), ("addressing", 1, 5), ("blocks_per_cu", 2, 9),
                            ("xcd_remap", 1, 2), ("use_hints", 0, 2),
-                           ("stream", 0, 2), ("bags_per_group", 5, 64)):
+                           ("stream", 0, 2), ("bags_per_group", 5, 64),
+                           ("xcd_pieces", 4, 3)):
         old = emb.emb_bag_get_tuning(key)
         emb.emb_bag_set_tuning(key, good)
         assert emb.emb_bag_get_tuning(key) == good

@@ -199,6 +199,10 @@ def test_xcd_affine_order_covers_every_bag(oracle, T, B, D):
     with tuning(xcd_remap=1):
         aff = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
     assert np.array_equal(nat, aff)
+    for pieces in (1, 2, 4, 8):          # forced: the XCDs may then differ by one piece
+        with tuning(xcd_remap=1, xcd_pieces=pieces):
+            got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
+        assert np.array_equal(nat, got), pieces
 
 
 def test_bad_indices_and_offsets_are_neutralised_and_counted(oracle):

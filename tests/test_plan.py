@@ -118,8 +118,9 @@ def _simulate(plan, T, order=None):
     piece, pos = unit % p["xcd_pieces"], unit // p["xcd_pieces"]
     in_piece = ((slot % p["blocks_per_piece"]) * 4)[:, None] + w[None, :]
     in_table = piece[:, None] * p["waves_per_piece"] + in_piece
-    keep = (in_piece < p["waves_per_piece"]) & (in_table < p["waves_per_table"])
-    assert pos.max() < T
+    keep = ((in_piece < p["waves_per_piece"]) & (in_table < p["waves_per_table"])
+            & (unit < T * p["xcd_pieces"])[:, None])
+    pos = np.minimum(pos, T - 1)          # units beyond the last table have no work (masked above)
     table = np.asarray(order, dtype=np.int64)[pos] if order is not None else pos
     return (np.broadcast_to(table[:, None], keep.shape)[keep], in_table[keep],
             np.broadcast_to(xcd[:, None], keep.shape)[keep])
@@ -298,3 +299,16 @@ def test_per_table_bag_lengths_in_a_mixed_call():
                    (emb.EMB_KERNEL_STREAM, 16): [5, 9],
                    (emb.EMB_KERNEL_STREAM, 32): [2, 10],
                    (emb.EMB_KERNEL_STREAM, 64): [11]}
+
+
+@pytest.mark.parametrize("T,pieces", [(60, 1), (7, 2), (250, 1), (13, 4), (5, 8)])
+def test_forced_pieces_per_table_still_cover_every_wavefront_once(T, pieces):
+    """With "xcd_pieces" forced the XCDs may differ by one piece; nothing is lost or doubled."""
+    with tuning(xcd_remap=1, xcd_pieces=pieces):
+        plan = _plan(T, 4096, 64, 30)
+    assert plan.xcd_pieces == pieces and plan.grid_blocks == -(-T * pieces // 8) * 8 * plan.blocks_per_piece
+    table, wave, xcd = _simulate(plan, T)
+    flat = table * plan.waves_per_table + wave
+    assert np.array_equal(np.sort(flat), np.arange(T * plan.waves_per_table))
+    counts = np.bincount(xcd, minlength=8)
+    assert counts.max() - counts.min() <= plan.waves_per_piece
