@@ -293,6 +293,9 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   -1 = automatic (on for large launches)
  *   "xcd_pieces"    pieces per table in the XCD-affine order: 1, 2, 4 or 8; 0 = automatic (the
  *                   smallest power of two that gives every XCD the same number of pieces)
+ *   "per_table_launch" 1 = emb_bag_forward makes one launch per table, one after the other, the
+ *                   launch structure of the paper's system (Sec. 3.1); for comparisons only.
+ *                   0 (default) = all tables in one launch
  *   "use_hints"     1 (default) = honour desc->table_hints, 0 = ignore them
  *   "stream"        the kernel for short bags, in which a lane group streams several consecutive
  *                   bags so that row loads stay in flight across bag boundaries (the prefetch of

@@ -115,6 +115,7 @@ struct Tuning {
   int64_t stream = -1;          // short-bag kernel: -1 = by average bag length, 0 = never, 1 = when possible
   int64_t bags_per_group = 0;   // its consecutive bags per lane group: 0 = automatic
   int64_t xcd_pieces = 0;       // pieces per table in XCD-affine order: 0 = automatic, 1, 2, 4, 8
+  int64_t per_table_launch = 0; // 1 = one launch per table, as the paper's system does (Sec. 3.1)
 };
 Tuning g_tuning;
 
@@ -372,6 +373,15 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
   const bool can_stream = g_tuning.stream != 0 && slabs == 1 && buf && desc->mode != EMB_MAX;
   const std::vector<uint16_t> none;
+  if (g_tuning.per_table_launch == 1 && T <= 65535) {
+    // the paper's launch structure, for comparison: the tables one after the other
+    Launch stream = wave;
+    const bool s = can_stream && (g_tuning.stream == 1 || avg_len < threshold) &&
+                   make_stream(&stream, desc, weighted, depth, avg_len, 1, out_ld);
+    for (int64_t t = 0; t < T; ++t)
+      add_launches(s ? stream : wave, T, std::vector<uint16_t>(1, (uint16_t)t), none, launches);
+    return EMB_OK;
+  }
   if (can_stream && g_tuning.stream == -1 && desc->table_avg_len && T <= 65535) {
     std::vector<uint16_t> short_ids, long_ids;
     double short_sum = 0.0;
@@ -740,6 +750,9 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
   } else if (!strcmp(key, "bags_per_group")) {
     if (value < 0 || value > 63) return EMB_ERR_BAD_TUNING;
     g_tuning.bags_per_group = value;
+  } else if (!strcmp(key, "per_table_launch")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    g_tuning.per_table_launch = value;
   } else if (!strcmp(key, "xcd_pieces")) {
     if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
       return EMB_ERR_BAD_TUNING;
@@ -760,6 +773,7 @@ int emb_bag_get_tuning(const char* key, int64_t* value) {
   else if (!strcmp(key, "stream")) *value = g_tuning.stream;
   else if (!strcmp(key, "bags_per_group")) *value = g_tuning.bags_per_group;
   else if (!strcmp(key, "xcd_pieces")) *value = g_tuning.xcd_pieces;
+  else if (!strcmp(key, "per_table_launch")) *value = g_tuning.per_table_launch;
   else return EMB_ERR_BAD_TUNING;
   return EMB_OK;
 }

@@ -268,3 +268,15 @@ def test_per_table_bag_lengths_with_more_tables_than_one_list_holds(oracle):
                             to_dev(batch.indices), to_dev(batch.offsets), None, out)
     torch.cuda.synchronize()
     assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, "2600 tables, per-table lengths")
+
+
+def test_one_launch_per_table_gives_the_same_bits(oracle):
+    """"per_table_launch" reproduces the paper's launch structure (one kernel per table); the
+    result is that of the single launch, bit for bit."""
+    for name, pooling in (("small_f32_d128", None), ("small_f32_d64", ("uniform", 0, 4))):
+        wl, batch, arena = _problem(name, **({"pooling": pooling} if pooling else {}))
+        dev = upload_arena(arena)
+        one = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
+        with tuning(per_table_launch=1):
+            many = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
+        assert np.array_equal(one, many), name
