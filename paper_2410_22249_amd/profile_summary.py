@@ -1,9 +1,9 @@
 """Turn rocprofv3 CSV output into the short text summaries kept under profiles/.
 
     python -m paper_2410_22249_amd.profile_summary --workload cfg3 \
-        --kernel-stats gpurun_out/prof/kt/cfg3_kernel_stats.csv \
-        --fetch gpurun_out/prof/fetch/cfg3_counter_collection.csv \
-        --write gpurun_out/prof/write/cfg3_counter_collection.csv \
+        --kernel-stats out/kt/cfg3_kernel_stats.csv \
+        --fetch out/fetch/cfg3_counter_collection.csv \
+        --write out/write/cfg3_counter_collection.csv \
         [--counters some_other_counter_collection.csv ...] --command "<how it was collected>"
 
 HBM traffic: rocprofv3 reports FETCH_SIZE / WRITE_SIZE in KiB per dispatch.  Each is scaled by
