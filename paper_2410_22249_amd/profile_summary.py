@@ -32,6 +32,13 @@ def per_kernel_counter(path):
     return out
 
 
+def emb_kernels(per):
+    """{kernel name: values} of the forward kernels in one counter's per-kernel table.  A call that
+    splits into several launches (short-bag tables apart from the others, one launch per row
+    class) shows up as several names, each dispatched once per call."""
+    return {k: vs for k, vs in per.items() if any(e in k for e in EMB)}
+
+
 def short(name: str) -> str:
     name = name.replace("(anonymous namespace)::", "").replace("void ", "")
     return name.split("(")[0]
@@ -68,27 +75,33 @@ def main() -> int:
             continue
         data = per_kernel_counter(path)[counter]
         cal = [v for k, vs in data.items() if COPY in k for v in vs]
-        emb = [v for k, vs in data.items() if any(e in k for e in EMB) for v in vs]
+        emb = emb_kernels(data)
         if not cal or not emb:
             print(f"\n## {counter}: calibration copy or embedding kernel not found in {path}")
             continue
         scale = (CAL_BYTES / 1024.0) / statistics.mean(cal)
-        med = statistics.median(emb)
+        med = sum(statistics.median(vs) for vs in emb.values())
         traffic[label] = med * 1024.0 * scale
         print(f"\n## {counter} (KiB per dispatch as reported)")
         print(f"copy_kernel of {CAL_BYTES} bytes reads {statistics.mean(cal):.1f} -> scale factor {scale:.4f}")
-        print(f"embedding kernel: n={len(emb)} median {med:.1f} min {min(emb):.1f} max {max(emb):.1f}")
-        print(f"{label}_bytes_per_launch = {traffic[label]:.0f}")
+        for k, vs in emb.items():
+            print(f"{short(k)[:60]}: n={len(vs)} median {statistics.median(vs):.1f} "
+                  f"min {min(vs):.1f} max {max(vs):.1f}")
+        if len(emb) > 1:
+            print(f"one call = {len(emb)} launches; sum of their medians {med:.1f}")
+        print(f"{label}_bytes_per_{'call' if len(emb) > 1 else 'launch'} = {traffic[label]:.0f}")
     if len(traffic) == 2:
-        print(f"\nhbm_bytes_per_launch = {traffic['fetch'] + traffic['write']:.0f}")
+        print(f"\nhbm_bytes_per_launch = {traffic['fetch'] + traffic['write']:.0f}"
+              "   (all launches of one call)")
 
     for path in a.counters:
         data = per_kernel_counter(path)
         print(f"\n## counters from {path.split('/')[-2] if '/' in path else path} (embedding kernel, median per dispatch)")
         for counter, per in sorted(data.items()):
-            emb = [v for k, vs in per.items() if any(e in k for e in EMB) for v in vs]
-            if emb:
-                print(f"{counter:32s} {statistics.median(emb):18.3f}")
+            emb = emb_kernels(per)
+            for k, vs in emb.items():
+                tag = f"   {short(k)[:60]}" if len(emb) > 1 else ""
+                print(f"{counter:32s} {statistics.median(vs):18.3f}{tag}")
     return 0
 
 
