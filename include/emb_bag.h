@@ -129,6 +129,11 @@ typedef struct emb_bag_desc {
  * lookup whose index is outside [0, R_t) contributes zero.  Use emb_bag_validate to count them.
  * Host-visible argument errors return a negative code and enqueue nothing.
  *
+ * Size limits (EMB_ERR_BAD_SIZE beyond them): B < 2^31, and a launch holds at most 2^24 - 1
+ * workgroups of four wavefronts, i.e. T * B * ceil(row bytes / 1024) <= 67,108,860 when every bag
+ * has a wavefront of its own (fewer wavefronts are needed when the short-bag kernel serves the
+ * call).  Split a larger batch over several calls.
+ *
  * One call is one kernel launch; with desc->table_avg_len it may be two (tables with short bags,
  * the other tables), enqueued on `stream` one after the other and writing disjoint columns
  * (emb_bag_plan_forward lists them).  More than 65535 tables are then served by one kernel.

@@ -175,6 +175,10 @@ int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
 
 // Everything a forward call decides on the host before it launches: the kernel instantiation,
 // its parameters, the grid and the table order.  Filled by plan_uniform / plan_mixed (no HIP
+// A dispatch counts its work-items in 32 bits, so a launch of 256-thread workgroups holds at most
+// 2^24 - 1 of them (67,108,860 wavefronts).  Larger calls are refused, not split.
+constexpr uint64_t kMaxBlocks = 0xFFFFFFull;
+
 // calls, no device pointers), launched by `launch`, reported by emb_bag_plan_forward*.
 struct Launch {
   KernelFn fn = nullptr;
@@ -218,7 +222,7 @@ void plan_grid(int64_t n, const uint16_t* ids, const uint16_t* row_units, bool n
     // the tables out widest first, each to the set with the least work so far, so that every
     // XCD ends up with about the same number of bytes.
     const uint32_t sets = 8u >> (pshift < 3 ? pshift : 3);
-    const bool ok = grid <= 0x7FFFFFFFull;
+    const bool ok = grid <= kMaxBlocks;  // else: natural order, checked by the caller
     ordered = ok && row_units && sets > 1 && n % sets == 0;
     if (ordered) {
       uint32_t head[66];  // counting sort by width, widest first
@@ -600,6 +604,13 @@ void report(const Launch& L, int32_t num_launches, emb_bag_plan* plan, uint16_t*
       table_order[t] = L.p.listed ? L.order.t[t] : (uint16_t)t;
 }
 
+// EMB_ERR_BAD_SIZE if a launch of the plan is larger than a dispatch can be.
+int check_grids(const std::vector<Launch>& launches) {
+  for (const Launch& L : launches)
+    if (L.blocks > kMaxBlocks) return EMB_ERR_BAD_SIZE;
+  return EMB_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -618,6 +629,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
     return EMB_ERR_ALIGNMENT;
   std::vector<Launch> launches;
   rc = plan_uniform(desc, per_sample_weights != nullptr, row_bytes, out_ld, &launches);
+  if (rc == EMB_OK) rc = check_grids(launches);
   if (rc != EMB_OK) return rc;
   for (const Launch& L : launches) {  // disjoint tables: the launches are independent
     rc = launch(L, tables, table_offsets, indices, offsets, per_sample_weights, desc->table_hints,
@@ -642,6 +654,7 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
     return EMB_ERR_ALIGNMENT;
   std::vector<Launch> launches;
   rc = plan_mixed(desc, per_sample_weights != nullptr, max_row_bytes, out_ld, &launches);
+  if (rc == EMB_OK) rc = check_grids(launches);
   if (rc != EMB_OK) return rc;
   for (const Launch& L : launches) {  // disjoint tables: the launches are independent
     rc = launch(L, tables, table_byte_offsets, indices, offsets, per_sample_weights,
@@ -662,6 +675,7 @@ int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, int32_t whic
   if (desc->batch == 0) return EMB_OK;
   std::vector<Launch> launches;
   rc = plan_uniform(desc, has_weights != 0, row_bytes, out_ld, &launches);
+  if (rc == EMB_OK) rc = check_grids(launches);
   if (rc != EMB_OK) return rc;
   if (which < 0 || (size_t)which >= launches.size()) return EMB_ERR_BAD_SIZE;
   report(launches[(size_t)which], (int32_t)launches.size(), plan, table_order);
@@ -679,6 +693,7 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
   if (desc->batch == 0) return EMB_OK;
   std::vector<Launch> launches;
   rc = plan_mixed(desc, has_weights != 0, max_row_bytes, out_ld, &launches);
+  if (rc == EMB_OK) rc = check_grids(launches);
   if (rc != EMB_OK) return rc;
   if (which < 0 || (size_t)which >= launches.size()) return EMB_ERR_BAD_SIZE;
   report(launches[(size_t)which], (int32_t)launches.size(), plan, table_order);
@@ -698,6 +713,7 @@ int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
   if (B > 0x7FFFFFFF || T * B > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
   const uint32_t num_bags = (uint32_t)(T * B);
   const uint32_t blocks = (num_bags + kWavesPerBlock - 1) / kWavesPerBlock;
+  if (blocks > kMaxBlocks) return EMB_ERR_BAD_SIZE;
   hipLaunchKernelGGL(emb_bag_validate_kernel, dim3(blocks), dim3(kBlock), 0,
                      static_cast<hipStream_t>(stream), table_offsets, indices, offsets,
                      reinterpret_cast<unsigned long long*>(num_bad), desc->num_lookups,

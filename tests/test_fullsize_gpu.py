@@ -198,3 +198,64 @@ def test_table_of_more_than_2_pow_31_rows(oracle):
     ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, soff, len(bags), "sum")
     got = out.view(wl.B, wl.T, wl.D).permute(1, 0, 2).reshape(wl.num_bags, wl.D).cpu().numpy()
     assert_close_to_oracle(got, ref, bound, False, "table of 2^31 + 1000 rows")
+
+
+def test_the_largest_grid_a_launch_can_hold(oracle):
+    """67,108,800 bags with a wavefront each are 16,777,200 workgroups, the most one dispatch
+    takes (its work-items are counted in 32 bits); the XCD-affine order would pad that to 2^24
+    and steps back to the natural order.  Nearly all bags are empty; one in 4099 holds 1-3
+    lookups.  Integer-valued rows make every sum exact, so the result is compared bit for bit."""
+    T, D, R = 64, 4, 1000
+    B = ((1 << 24) - 1) * 4 // T
+    nb = T * B
+    rng = np.random.default_rng(77)
+    host = rng.integers(-8, 9, size=(T * R, D)).astype(np.float32)
+    arena = to_dev(host)
+    toff = np.arange(T + 1, dtype=np.int64) * R
+    lengths = torch.zeros(nb, dtype=torch.int64, device=DEV)
+    some = torch.arange(0, nb, 4099, device=DEV)
+    lengths[some] = some % 3 + 1
+    lengths[-1] = 3
+    off = torch.zeros(nb + 1, dtype=torch.int64, device=DEV)
+    torch.cumsum(lengths, 0, out=off[1:])
+    NL = int(off[-1].item())
+    idx_host = rng.integers(0, R, size=NL).astype(np.int64)
+    idx = to_dev(idx_host)
+    desc = emb.make_desc(T, B, D, emb.EMB_F32, emb.EMB_SUM, NL, 0, R)
+    out = torch.full((B, T * D), float("nan"), dtype=torch.float32, device=DEV)
+    print(f"\n[fullsize] largest grid: {nb} bags, {NL} lookups", flush=True)
+    with tuning(stream=0):
+        plan = emb.emb_bag_plan_forward(desc)
+        assert plan.kernel == emb.EMB_KERNEL_WAVE and plan.grid_blocks == nb // 4 == (1 << 24) - 16
+        assert plan.xcd_pieces == 0
+        emb.emb_bag_forward(desc, arena, to_dev(toff), idx, off, None, out)
+    bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    emb.emb_bag_validate(desc, to_dev(toff), idx, off, bad)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+    # the non-empty bags against the oracle (one table of all rows, global row ids)
+    bags_dev = lengths.nonzero().flatten()
+    bags = bags_dev.cpu().numpy()
+    lens = lengths[bags_dev].cpu().numpy()
+    soff = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    assert soff[-1] == NL
+    gidx = idx_host + np.repeat(toff[bags // B], lens)
+    ref, _ = oracle.emb_bag(host, np.array([0, T * R], np.int64), gidx, soff, len(bags), "sum")
+    sel_b, sel_t = torch.from_numpy(bags % B).to(DEV), torch.from_numpy(bags // B).to(DEV)
+    got = out.view(B, T, D)[sel_b, sel_t]
+    assert np.array_equal(got.cpu().numpy().astype(np.float64), ref)
+    # ... and exact zeros everywhere else (a bag left unwritten would still hold its NaN)
+    assert int(torch.count_nonzero(out).item()) == int(torch.count_nonzero(got).item())
+    # the automatic choice (short bags: the stream kernel, far fewer wavefronts) agrees
+    out2 = torch.full_like(out, float("nan"))
+    plan = emb.emb_bag_plan_forward(desc)
+    assert plan.kernel == emb.EMB_KERNEL_STREAM
+    emb.emb_bag_forward(desc, arena, to_dev(toff), idx, off, None, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    # one bag more per table is refused before anything is launched
+    big = emb.make_desc(T, B + 1, D, emb.EMB_F32, emb.EMB_SUM, NL, 0, R)
+    with tuning(stream=0):
+        with pytest.raises(emb.EmbBagError) as ex:
+            emb.emb_bag_forward(big, arena, to_dev(toff), idx, off, None, out)
+    assert ex.value.status == -7

@@ -312,3 +312,35 @@ def test_forced_pieces_per_table_still_cover_every_wavefront_once(T, pieces):
     assert np.array_equal(np.sort(flat), np.arange(T * plan.waves_per_table))
     counts = np.bincount(xcd, minlength=8)
     assert counts.max() - counts.min() <= plan.waves_per_piece
+
+
+def test_a_launch_holds_at_most_2_pow_24_minus_1_workgroups():
+    """A dispatch counts work-items in 32 bits: 2^24 - 1 workgroups of 256 threads.  Calls beyond
+    that are refused with EMB_ERR_BAD_SIZE; the XCD-affine order, whose grid is padded, steps back
+    to the natural order when only the padding would not fit."""
+    limit = (1 << 24) - 1
+    def status(T, B, D=4, L=30.0, **kw):
+        try:
+            return _plan(T, B, D, L, **kw)
+        except emb.EmbBagError as ex:
+            return ex.status
+    with tuning(stream=0):
+        ok = status(64, limit * 4 // 64)                      # 67,108,800 wavefronts
+        assert ok.grid_blocks <= limit and ok.wavefronts == 64 * (limit * 4 // 64)
+        assert status(64, limit * 4 // 64 + 1) == -7          # 67,108,864: one workgroup too many
+        assert status(1, 1 << 31) == -7 and status(3, 1 << 30) == -7
+        assert status(64, 600_000, D=512) == -7               # two slabs per row double the count
+        # 7 tables: 8 pieces each; the padding of the last workgroup of each piece tips it over
+        B = limit * 4 // 7
+        with tuning(xcd_remap=1):
+            p = status(7, B)
+        assert p.xcd_pieces in (0, 8) and p.grid_blocks <= limit and p.wavefronts == 7 * B
+    # the short-bag kernel needs fewer wavefronts for the same bags
+    p = status(64, 4_000_000, L=1.0)
+    assert p.kernel == emb.EMB_KERNEL_STREAM and p.grid_blocks <= limit
+    # tables of different widths
+    m = emb.make_mixed_desc([4, 8] * 32, limit * 4 // 64 + 1, emb.EMB_F32, emb.EMB_SUM, 10, 0, 1 << 20)
+    with tuning(stream=0):
+        with pytest.raises(emb.EmbBagError) as ex:
+            emb.emb_bag_plan_forward_mixed(m)
+        assert ex.value.status == -7
