@@ -1,0 +1,375 @@
+// The bodies of the forward kernels as device functions, so that a kernel per body
+// (emb_bag_wave.hip, emb_bag_stream.hip) and a fused kernel that runs several bodies over
+// consecutive block ranges of one launch (emb_bag_fused.hip) share them.  `block` is the
+// workgroup's index within its launch or block range; `order_base` is where the tables of that
+// range start in the table list.  Included by the kernel sources only.
+#pragma once
+
+#include "emb_bag_device.h"
+
+namespace embbag {
+
+// ---------------------------------------------------------------------------------------------
+// wave body
+// ---------------------------------------------------------------------------------------------
+
+// One wavefront per (bag, column slab).  LPR = lanes per row (power of two, 4..64), or 0 for
+// tables of different widths: then table t is described by table_offsets[t] (its BYTE offset in
+// the arena) and out_offsets[t] (its first output column; its width is the difference to the next
+// entry), the lanes per row are chosen per wavefront, and rows are at most 1 KiB.
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF>
+__device__ __forceinline__ void wave_body(
+    const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
+    const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
+    const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
+    const int64_t* __restrict__ out_offsets, float* __restrict__ out, const KParams& p,
+    const TableOrder& order, uint32_t order_base, uint32_t block) {
+  constexpr bool MIXED = LPR == 0;
+  constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;  // 2-byte elements
+  constexpr bool QUANT = IsQuant<ELEM>::value;                // 1-byte codes + scale, bias
+  constexpr int NACC = AccCount<ELEM, OP>::value;             // fp32 accumulators per lane
+
+  const int lane = threadIdx.x & (kWaveSize - 1);
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint32_t tpos, w_in_table;
+  if (!decode_work(p, block, wave, &tpos, &w_in_table)) return;
+  const uint32_t t = p.listed ? order.t[order_base + tpos] : tpos;
+  uint32_t b = w_in_table, slab = 0;
+  if (p.slabs > 1) {
+    b = w_in_table / p.slabs;
+    slab = w_in_table - b * p.slabs;
+  }
+  const uint32_t bag = t * p.B + b;
+
+  // bag bounds, clamped so that no index read can leave [0, NL)
+  int64_t s = uniform64(offsets[bag]);
+  int64_t e = uniform64(offsets[bag + 1]);
+  s = s < 0 ? 0 : (s > p.num_lookups ? p.num_lookups : s);
+  e = e < s ? s : (e > p.num_lookups ? p.num_lookups : e);
+
+  // per-table geometry
+  uint32_t D_t = p.D, row_bytes = p.row_bytes;
+  int64_t out_col = (int64_t)t * p.D;
+  int lpr = LPR ? LPR : 4;
+  const char* tbase;
+  int64_t R;
+  if constexpr (MIXED) {
+    out_col = uniform64(out_offsets[t]);
+    const int64_t out_next = uniform64(out_offsets[t + 1]);
+    const int64_t d64 = out_next - out_col;
+    const int64_t rb64 = QUANT ? d64 + 8 : d64 * (HALF ? 2 : 4);
+    // a malformed table description writes nothing (the host checked its own copy of the widths)
+    if (d64 <= 0 || rb64 > kSlabBytes || (rb64 & 15) || out_col < 0 || (out_col & 3) ||
+        out_next > p.out_ld)
+      return;
+    D_t = (uint32_t)d64;
+    row_bytes = (uint32_t)rb64;
+    while ((uint32_t)lpr * 16u < row_bytes) lpr <<= 1;
+    const int64_t byte0 = uniform64(table_offsets[t]);
+    int64_t bytes = uniform64(table_offsets[t + 1]) - byte0;
+    if (bytes < 0) bytes = 0;
+    if (BUF && bytes > (int64_t)kBufMaxBytes) bytes = (int64_t)kBufMaxBytes;
+    R = bytes / row_bytes;
+    tbase = tables + byte0;
+  } else {
+    const int64_t row0 = uniform64(table_offsets[t]);
+    R = uniform64(table_offsets[t + 1]) - row0;
+    if (R < 0) R = 0;
+    if (BUF && R > p.max_rows) R = p.max_rows;
+    tbase = tables + row0 * (int64_t)p.row_bytes;
+  }
+  const int lpr_log2 = __builtin_ctz((unsigned)lpr);
+
+  const int g = lane >> lpr_log2;
+  const uint32_t col = slab * kSlabBytes + (uint32_t)(lane & (lpr - 1)) * 16u;
+  const bool lane_ok = col < row_bytes;
+
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(tbase), 0, BUF ? (uint32_t)((uint64_t)R * row_bytes) : 0u, kBufWord3);
+
+  float acc[NACC];
+  init_acc<ELEM, OP>(acc);
+  // quantised rows: the lane of this lane's group whose segment ends with the row's scale and bias
+  const int meta_lane = (lane & ~(lpr - 1)) + (int)(D_t >> 4);
+
+  const bool streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
+  if (streaming)
+    gather_bag<LPR, ELEM, DEPTH, OP, BUF, true>(acc, indices, weights, s, e, R, row_bytes,
+                                                     tbase, rsrc, lane, g, col, lane_ok,
+                                                     meta_lane, 6 - lpr_log2);
+  else
+    gather_bag<LPR, ELEM, DEPTH, OP, BUF, false>(acc, indices, weights, s, e, R, row_bytes,
+                                                      tbase, rsrc, lane, g, col, lane_ok,
+                                                      meta_lane, 6 - lpr_log2);
+
+  finish_bag<LPR, ELEM, OP>(acc, lpr, lane, lane_ok, col, D_t, e - s, p.mean != 0, out, p.out_ld, b,
+                        out_col);
+}
+
+// ---------------------------------------------------------------------------------------------
+// stream body
+// ---------------------------------------------------------------------------------------------
+
+constexpr uint32_t kNoBag = 0xFFFFFFFFu;       // packed (end, bag) of "no further bag"
+constexpr uint32_t kMaxGroupLookups = 1u << 25;  // a group's range must stay below this
+
+__device__ __forceinline__ bool any_lane(bool c) { return __builtin_amdgcn_ballot_w64(c) != 0; }
+
+// The stream of one wavefront.  Per lane: `glen` lookups of its group start at gi (indices) and
+// gw (weights); `pk` holds, in lane r of the group, (relative end << 6 | bag number within the
+// group) of the group's r-th non-empty bag, kNoBag beyond; out_rsrc covers the wavefront's
+// output rows and `store0` is the byte offset of this lane's elements in its group's first bag.
+template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool NT>
+__device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
+                                              const float* __restrict__ gw, uint32_t glen,
+                                              uint32_t pk, int64_t R, uint32_t row_bytes,
+                                              __amdgpu_buffer_rsrc_t rsrc,
+                                              __amdgpu_buffer_rsrc_t out_rsrc, uint32_t store0,
+                                              uint32_t out_ld_bytes, uint32_t D, bool mean,
+                                              int lane, uint32_t col, bool lane_ok,
+                                              int meta_lane) {
+  constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;
+  constexpr bool QUANT = IsQuant<ELEM>::value;
+  constexpr int NACC = AccCount<ELEM>::value;
+  constexpr int NOUT = QUANT ? 16 : NACC;
+  constexpr int kAux = NT ? 2 : 0;  // cache-policy bits of the row loads: 2 = nt
+  const int l = lane & (LPR - 1);
+  const int group_base = lane & ~(LPR - 1);
+  const uint32_t elem0 = QUANT ? col : (HALF ? col / 2 : col / 4);
+
+  float acc[NACC];
+#pragma unroll
+  for (int i = 0; i < NACC; ++i) acc[i] = 0.0f;
+
+  // the group's current (non-empty) bag: rank among the non-empty ones, relative bounds, number
+  uint32_t rank = 0, bag_start = 0;
+  uint32_t cur = (uint32_t)__shfl((int)pk, group_base);
+  uint32_t next_end = cur >> 6, bag_local = cur & 63u;
+
+  int64_t idx = -1;
+  float wt = 0.0f;
+  if ((uint32_t)l < glen) {
+    idx = __builtin_nontemporal_load(gi + l);
+    if constexpr (WEIGHTED) wt = __builtin_nontemporal_load(gw + l);
+  }
+
+  for (uint32_t qbase = 0; any_lane(qbase < glen); qbase += LPR) {
+    // the next chunk of indices is on its way while this chunk's rows are gathered
+    int64_t idx_next = -1;
+    float wt_next = 0.0f;
+    const uint32_t qn = qbase + LPR + (uint32_t)l;
+    if (qn < glen) {
+      idx_next = __builtin_nontemporal_load(gi + qn);
+      if constexpr (WEIGHTED) wt_next = __builtin_nontemporal_load(gw + qn);
+    }
+    // a lookup past the group's range has idx = -1: out of range like any invalid row id
+    const uint32_t voff = (uint64_t)idx < (uint64_t)R ? (uint32_t)idx * row_bytes : kBufSentinel;
+
+#pragma unroll 1
+    for (int k0 = 0; k0 < LPR; k0 += DEPTH) {
+      if (k0 > 0 && !any_lane(qbase + k0 < glen)) break;
+      u32x4 r[DEPTH];
+      float wj[DEPTH];
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        uint32_t vo = (uint32_t)__shfl((int)voff, group_base + k0 + d);
+        vo = lane_ok ? vo : kBufSentinel;
+        r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
+        if constexpr (WEIGHTED)
+          wj[d] = __shfl(wt, group_base + k0 + d);
+        else
+          wj[d] = 1.0f;
+      }
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        accumulate<ELEM, WEIGHTED ? kOpWeighted : kOpSum>(acc, r[d], wj[d], meta_lane);
+        const bool flush = qbase + (uint32_t)(k0 + d) + 1u == next_end;  // this lookup ends a bag
+        float v[NOUT];
+#pragma unroll
+        for (int i = 0; i < NOUT; ++i) v[i] = QUANT ? acc[i] + acc[16] : acc[i];
+        if (mean && any_lane(flush)) {
+          const float fl = (float)(next_end - bag_start);  // > 0: the bag is not empty
+#pragma unroll
+          for (int i = 0; i < NOUT; ++i) v[i] = v[i] / fl;
+        }
+        const uint32_t so = (flush && lane_ok) ? store0 + bag_local * out_ld_bytes : kBufSentinel;
+#pragma unroll
+        for (int q = 0; q < NOUT / 4; ++q) {
+          const bool in_row = !QUANT || elem0 + 4u * q < D;
+          const u32x4 bits = {__builtin_bit_cast(uint32_t, v[4 * q]),
+                              __builtin_bit_cast(uint32_t, v[4 * q + 1]),
+                              __builtin_bit_cast(uint32_t, v[4 * q + 2]),
+                              __builtin_bit_cast(uint32_t, v[4 * q + 3])};
+          __builtin_amdgcn_raw_buffer_store_b128(bits, out_rsrc,
+                                                 (int)(in_row ? so + 16u * q : kBufSentinel), 0, 2);
+        }
+#pragma unroll
+        for (int i = 0; i < NACC; ++i) acc[i] = flush ? 0.0f : acc[i];
+        if (any_lane(flush)) {  // move the groups that stored to their next non-empty bag
+          rank += flush ? 1u : 0u;
+          bag_start = flush ? next_end : bag_start;
+          cur = (uint32_t)__shfl((int)pk, group_base + (int)rank);
+          next_end = cur >> 6;
+          bag_local = cur & 63u;
+        }
+      }
+    }
+    idx = idx_next;
+    wt = wt_next;
+  }
+}
+
+// One wavefront per G * M consecutive bags of one table (see the head of this file).  Sum and
+// mean pooling; max pooling always takes the wave kernel.  MIXED: the launch covers tables of
+// different widths that share LPR lanes per row; table t is then described by table_offsets[t]
+// (its BYTE offset in the arena) and out_offsets[t] (its first output column; its width is the
+// difference to the next entry), as for the wave kernel.
+template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool MIXED>
+__device__ __forceinline__ void stream_body(
+    const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
+    const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
+    const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
+    const int64_t* __restrict__ out_offsets, float* __restrict__ out, const KParams& p,
+    const TableOrder& order, uint32_t order_base, uint32_t block) {
+  constexpr int G = kWaveSize / LPR;
+  constexpr int GL = __builtin_ctz((unsigned)G);
+  constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;
+  constexpr bool QUANT = IsQuant<ELEM>::value;
+  constexpr int NACC = AccCount<ELEM>::value;
+  constexpr int NOUT = QUANT ? 16 : NACC;
+
+  const int lane = threadIdx.x & (kWaveSize - 1);
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint32_t tpos, w_in_table;
+  if (!decode_work(p, block, wave, &tpos, &w_in_table)) return;
+  const uint32_t t = p.listed ? order.t[order_base + tpos] : tpos;
+  const uint32_t M = p.bags_per_group;                   // 1 .. LPR - 1
+  const uint32_t b0 = w_in_table * (uint32_t)G * M;      // first bag of the wavefront, < B
+  const uint32_t nbw = p.B - b0 < (uint32_t)G * M ? p.B - b0 : (uint32_t)G * M;  // its bags
+
+  const int g = lane >> __builtin_ctz((unsigned)LPR);
+  const int l = lane & (LPR - 1);
+  const int group_base = lane & ~(LPR - 1);
+  const uint32_t gb0 = (uint32_t)g * M;                            // group's first bag, wave-relative
+  const uint32_t m = gb0 < nbw ? (nbw - gb0 < M ? nbw - gb0 : M) : 0u;  // group's bags
+
+  // table geometry (buffer addressing only)
+  uint32_t D_t = p.D, row_bytes = p.row_bytes;
+  int64_t out_col = (int64_t)t * p.D;
+  const char* tbase;
+  int64_t R;
+  if constexpr (MIXED) {
+    out_col = uniform64(out_offsets[t]);
+    const int64_t out_next = uniform64(out_offsets[t + 1]);
+    const int64_t d64 = out_next - out_col;
+    const int64_t rb64 = QUANT ? d64 + 8 : d64 * (HALF ? 2 : 4);
+    // a table description that does not fit this launch writes nothing (the host chose LPR from
+    // its own copy of the widths)
+    if (d64 <= 0 || rb64 > (int64_t)LPR * 16 || (rb64 & 15) || out_col < 0 || (out_col & 3) ||
+        out_next > p.out_ld)
+      return;
+    D_t = (uint32_t)d64;
+    row_bytes = (uint32_t)rb64;
+    const int64_t byte0 = uniform64(table_offsets[t]);
+    int64_t bytes = uniform64(table_offsets[t + 1]) - byte0;
+    if (bytes < 0) bytes = 0;
+    if (bytes > (int64_t)kBufMaxBytes) bytes = (int64_t)kBufMaxBytes;
+    R = bytes / row_bytes;
+    tbase = tables + byte0;
+  } else {
+    const int64_t row0 = uniform64(table_offsets[t]);
+    R = uniform64(table_offsets[t + 1]) - row0;
+    if (R < 0) R = 0;
+    if (R > p.max_rows) R = p.max_rows;
+    tbase = tables + row0 * (int64_t)row_bytes;
+  }
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(tbase), 0, (uint32_t)((uint64_t)R * row_bytes), kBufWord3);
+  const uint32_t col = (uint32_t)l * 16u;
+  const bool lane_ok = col < row_bytes;
+  const int meta_lane = group_base + (int)(D_t >> 4);
+  const bool streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
+
+  // bag bounds: lane l of a group holds bound min(l, m) of the group, clamped to [0, NL]
+  const int64_t* obase = offsets + (uint64_t)t * p.B + b0;
+  int64_t o = 0;
+  if (m > 0) {
+    o = obase[gb0 + ((uint32_t)l < m ? (uint32_t)l : m)];
+    o = o < 0 ? 0 : (o > p.num_lookups ? p.num_lookups : o);
+  }
+  const int64_t o_next = shfl64(o, lane + 1 < kWaveSize ? lane + 1 : lane);
+  const bool mine = (uint32_t)l < m;                     // this lane stands for bag l of its group
+  const int64_t len = mine ? o_next - o : 0;
+  const int64_t S = shfl64(o, group_base);               // the group's first lookup
+  const int64_t E = shfl64(o, group_base + (int)m);      // one past its last
+  const bool malformed = (mine && len < 0) || E - S >= (int64_t)kMaxGroupLookups;
+
+  if (any_lane(malformed)) {
+    // bag by bag with the whole wavefront, exactly as the wave kernel treats a bag
+    for (uint32_t i = 0; i < nbw; ++i) {
+      int64_t s = uniform64(obase[i]);
+      int64_t e = uniform64(obase[i + 1]);
+      s = s < 0 ? 0 : (s > p.num_lookups ? p.num_lookups : s);
+      e = e < s ? s : (e > p.num_lookups ? p.num_lookups : e);
+      float acc[NACC];
+#pragma unroll
+      for (int k = 0; k < NACC; ++k) acc[k] = 0.0f;
+      gather_bag<LPR, ELEM, 2, WEIGHTED ? kOpWeighted : kOpSum, true, false>(acc, indices, weights, s, e, R, row_bytes,
+                                                      tbase, rsrc, lane, g, col, lane_ok,
+                                                      meta_lane, GL);
+      finish_bag<LPR, ELEM, kOpSum>(acc, LPR, lane, lane_ok, col, D_t, e - s, p.mean != 0, out,
+                                    p.out_ld, b0 + i, out_col);
+    }
+    return;
+  }
+
+  // output rows of this wavefront as a buffer: a store with an out-of-range offset is dropped
+  const uint32_t out_ld_bytes = (uint32_t)p.out_ld * 4u;
+  float* obuf = out + (int64_t)b0 * p.out_ld + out_col;
+  const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      obuf, 0, (nbw - 1u) * out_ld_bytes + D_t * 4u, kBufWord3);
+  const uint32_t elem0 = QUANT ? col : (HALF ? col / 2 : col / 4);
+  const uint32_t store0 = gb0 * out_ld_bytes + elem0 * 4u;
+
+  // empty bags get zeros now: the stream only ever stores bags that end at a lookup
+  const bool empty = mine && len == 0;
+  if (any_lane(empty)) {
+    for (uint32_t i = 0; i < M; ++i) {
+      const bool e_i = __shfl((int)empty, group_base + (int)i) != 0;
+      const uint32_t so = (e_i && lane_ok) ? store0 + i * out_ld_bytes : kBufSentinel;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int q = 0; q < NOUT / 4; ++q) {
+        const bool in_row = !QUANT || elem0 + 4u * q < D_t;
+        __builtin_amdgcn_raw_buffer_store_b128(zero, out_rsrc,
+                                               (int)(in_row ? so + 16u * q : kBufSentinel), 0, 2);
+      }
+    }
+  }
+
+  // Lane r of a group gets (relative end << 6 | bag) of the group's r-th non-empty bag: a stable
+  // partition of the group's lanes, non-empty bags first, sent with one forward permute.
+  const uint64_t ballot = __builtin_amdgcn_ballot_w64(mine && len > 0);
+  const uint64_t gmask = LPR == 64 ? ballot : (ballot >> group_base) & ((1ull << (LPR & 63)) - 1ull);
+  const uint32_t before = (uint32_t)__builtin_popcountll(gmask & ((1ull << l) - 1ull));
+  const uint32_t total = (uint32_t)__builtin_popcountll(gmask);
+  const bool nonempty = mine && len > 0;
+  const uint32_t dest = nonempty ? before : total + ((uint32_t)l - before);
+  const uint32_t send = nonempty ? ((uint32_t)(o_next - S) << 6) | (uint32_t)l : kNoBag;
+  const uint32_t pk =
+      (uint32_t)__builtin_amdgcn_ds_permute((group_base + (int)dest) << 2, (int)send);
+
+  const uint32_t glen = (uint32_t)(E - S);
+  const int64_t* gi = indices + S;
+  const float* gw = WEIGHTED ? weights + S : nullptr;
+  if (streaming)
+    stream_groups<LPR, ELEM, DEPTH, WEIGHTED, true>(gi, gw, glen, pk, R, row_bytes, rsrc, out_rsrc,
+                                                    store0, out_ld_bytes, D_t, p.mean != 0, lane,
+                                                    col, lane_ok, meta_lane);
+  else
+    stream_groups<LPR, ELEM, DEPTH, WEIGHTED, false>(gi, gw, glen, pk, R, row_bytes, rsrc,
+                                                     out_rsrc, store0, out_ld_bytes, D_t,
+                                                     p.mean != 0, lane, col, lane_ok, meta_lane);
+}
+
+}  // namespace embbag

@@ -293,11 +293,13 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
 // Which piece of work this wavefront owns: position `tpos` in the launch's table list and
 // wavefront `w_in_table` of that table (0 .. wpt-1), or false if it has none.  Workgroups are
 // dealt round-robin to the 8 XCDs, so blockIdx % 8 names the XCD (and its L2); the XCD-affine
-// order turns that into (position, piece) as described at KParams.
-__device__ __forceinline__ bool decode_work(const KParams& p, uint32_t wave, uint32_t* tpos,
-                                            uint32_t* w_in_table) {
+// order turns that into (position, piece) as described at KParams.  `block` is the workgroup's
+// index within the launch (or within its block range of a fused launch, which starts at a
+// multiple of 8 so that block % 8 still names the XCD).
+__device__ __forceinline__ bool decode_work(const KParams& p, uint32_t block, uint32_t wave,
+                                            uint32_t* tpos, uint32_t* w_in_table) {
   if (p.xcd_bpp) {
-    const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+    const uint32_t xcd = block & 7u, slot = block >> 3;
     const uint32_t ul = slot / p.xcd_bpp;
     const uint32_t unit = ul * 8u + xcd;
     const uint32_t w_in_piece = (slot - ul * p.xcd_bpp) * kWavesPerBlock + wave;
@@ -307,7 +309,7 @@ __device__ __forceinline__ bool decode_work(const KParams& p, uint32_t wave, uin
     *w_in_table = w;
     return true;
   }
-  const uint64_t work64 = (uint64_t)blockIdx.x * kWavesPerBlock + wave;
+  const uint64_t work64 = (uint64_t)block * kWavesPerBlock + wave;
   if (work64 >= p.num_work) return false;
   const uint32_t q = (uint32_t)work64 / p.wpt;
   *tpos = q;

@@ -41,6 +41,7 @@
 
 #include "../../include/emb_bag.h"
 #include "emb_bag_device.h"
+#include "emb_bag_bodies.h"
 
 #ifndef EMB_LPR
 #error "compile with -DEMB_LPR=<lanes per row: 0, 4, 8, 16, 32 or 64>"
@@ -50,10 +51,7 @@ namespace {
 
 using namespace embbag;
 
-// One wavefront per (bag, column slab).  LPR = lanes per row (power of two, 4..64), or 0 for
-// tables of different widths: then table t is described by table_offsets[t] (its BYTE offset in
-// the arena) and out_offsets[t] (its first output column; its width is the difference to the next
-// entry), the lanes per row are chosen per wavefront, and rows are at most 1 KiB.
+// The kernel proper is embbag::wave_body (emb_bag_bodies.h), shared with the fused launch.
 template <int LPR, int ELEM, int DEPTH, int OP, bool BUF>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
@@ -61,86 +59,8 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
                     const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
                     const int64_t* __restrict__ out_offsets, float* __restrict__ out, KParams p,
                     TableOrder order) {
-  constexpr bool MIXED = LPR == 0;
-  constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;  // 2-byte elements
-  constexpr bool QUANT = IsQuant<ELEM>::value;                // 1-byte codes + scale, bias
-  constexpr int NACC = AccCount<ELEM, OP>::value;             // fp32 accumulators per lane
-
-  const int lane = threadIdx.x & (kWaveSize - 1);
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  uint32_t tpos, w_in_table;
-  if (!decode_work(p, wave, &tpos, &w_in_table)) return;
-  const uint32_t t = p.listed ? order.t[tpos] : tpos;
-  uint32_t b = w_in_table, slab = 0;
-  if (p.slabs > 1) {
-    b = w_in_table / p.slabs;
-    slab = w_in_table - b * p.slabs;
-  }
-  const uint32_t bag = t * p.B + b;
-
-  // bag bounds, clamped so that no index read can leave [0, NL)
-  int64_t s = uniform64(offsets[bag]);
-  int64_t e = uniform64(offsets[bag + 1]);
-  s = s < 0 ? 0 : (s > p.num_lookups ? p.num_lookups : s);
-  e = e < s ? s : (e > p.num_lookups ? p.num_lookups : e);
-
-  // per-table geometry
-  uint32_t D_t = p.D, row_bytes = p.row_bytes;
-  int64_t out_col = (int64_t)t * p.D;
-  int lpr = LPR ? LPR : 4;
-  const char* tbase;
-  int64_t R;
-  if constexpr (MIXED) {
-    out_col = uniform64(out_offsets[t]);
-    const int64_t out_next = uniform64(out_offsets[t + 1]);
-    const int64_t d64 = out_next - out_col;
-    const int64_t rb64 = QUANT ? d64 + 8 : d64 * (HALF ? 2 : 4);
-    // a malformed table description writes nothing (the host checked its own copy of the widths)
-    if (d64 <= 0 || rb64 > kSlabBytes || (rb64 & 15) || out_col < 0 || (out_col & 3) ||
-        out_next > p.out_ld)
-      return;
-    D_t = (uint32_t)d64;
-    row_bytes = (uint32_t)rb64;
-    while ((uint32_t)lpr * 16u < row_bytes) lpr <<= 1;
-    const int64_t byte0 = uniform64(table_offsets[t]);
-    int64_t bytes = uniform64(table_offsets[t + 1]) - byte0;
-    if (bytes < 0) bytes = 0;
-    if (BUF && bytes > (int64_t)kBufMaxBytes) bytes = (int64_t)kBufMaxBytes;
-    R = bytes / row_bytes;
-    tbase = tables + byte0;
-  } else {
-    const int64_t row0 = uniform64(table_offsets[t]);
-    R = uniform64(table_offsets[t + 1]) - row0;
-    if (R < 0) R = 0;
-    if (BUF && R > p.max_rows) R = p.max_rows;
-    tbase = tables + row0 * (int64_t)p.row_bytes;
-  }
-  const int lpr_log2 = __builtin_ctz((unsigned)lpr);
-
-  const int g = lane >> lpr_log2;
-  const uint32_t col = slab * kSlabBytes + (uint32_t)(lane & (lpr - 1)) * 16u;
-  const bool lane_ok = col < row_bytes;
-
-  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<char*>(tbase), 0, BUF ? (uint32_t)((uint64_t)R * row_bytes) : 0u, kBufWord3);
-
-  float acc[NACC];
-  init_acc<ELEM, OP>(acc);
-  // quantised rows: the lane of this lane's group whose segment ends with the row's scale and bias
-  const int meta_lane = (lane & ~(lpr - 1)) + (int)(D_t >> 4);
-
-  const bool streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
-  if (streaming)
-    gather_bag<LPR, ELEM, DEPTH, OP, BUF, true>(acc, indices, weights, s, e, R, row_bytes,
-                                                     tbase, rsrc, lane, g, col, lane_ok,
-                                                     meta_lane, 6 - lpr_log2);
-  else
-    gather_bag<LPR, ELEM, DEPTH, OP, BUF, false>(acc, indices, weights, s, e, R, row_bytes,
-                                                      tbase, rsrc, lane, g, col, lane_ok,
-                                                      meta_lane, 6 - lpr_log2);
-
-  finish_bag<LPR, ELEM, OP>(acc, lpr, lane, lane_ok, col, D_t, e - s, p.mean != 0, out, p.out_ld, b,
-                        out_col);
+  wave_body<LPR, ELEM, DEPTH, OP, BUF>(tables, table_offsets, indices, offsets, weights,
+                                       table_hints, out_offsets, out, p, order, 0u, blockIdx.x);
 }
 
 template <int LPR, int ELEM, int DEPTH>
