@@ -452,7 +452,7 @@ def main() -> int:
                    "launch_plan": launch_plan,
                    "tuning": {k: emb.emb_bag_get_tuning(k) for k in
                               ("depth", "addressing", "blocks_per_cu", "xcd_remap", "use_hints",
-                               "stream", "bags_per_group", "xcd_pieces", "per_table_launch")}},
+                               "stream", "bags_per_group", "xcd_pieces", "per_table_launch", "fuse")}},
         "gathered_GBps": gathered * args.steps / wall / 1e9,
         "gathered_frac_of_hbm_peak": gathered * args.steps / wall / 1e9 / metrics.HBM_PEAK_GBPS,
         "kernel_ms": {"avg": avg_kern_s * 1e3, "min": float(min(kern_ms)),

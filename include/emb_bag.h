@@ -163,11 +163,13 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
  * table_offsets is; a table whose entries contradict the rules above is skipped (nothing is
  * written for it).  Index and bag-bound defects are neutralised as in emb_bag_forward.
  *
- * One call is one kernel launch unless bags are short (see the "stream" tuning key): then the
- * tables are grouped by row size (64, 128, 256, 512, 1024 bytes and below), every group the
- * short-bag kernel suits gets a launch of its own and the other tables share one; the launches
- * write disjoint columns and are enqueued on `stream` one after the other
- * (emb_bag_plan_forward_mixed lists them).  More than 65535 tables are refused in that case.
+ * One call is one kernel launch.  With short bags (see the "stream" tuning key) the tables are
+ * grouped by row size (64, 128, 256, 512, 1024 bytes and below); every group the short-bag kernel
+ * suits is served by that kernel and the other tables by the one-wavefront-per-bag kernel, as
+ * consecutive workgroup ranges of one fused launch (see the "fuse" tuning key), or - with more
+ * than 1024 tables, or "fuse" off - as launches of their own that write disjoint columns and are
+ * enqueued on `stream` one after the other (emb_bag_plan_forward_mixed lists them).  More than
+ * 65535 tables are refused in that case.
  */
 typedef struct emb_bag_mixed_desc {
   int32_t num_tables;      /* T >= 1 */
@@ -243,7 +245,8 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
  *                       emb_bag_forward makes one launch, or two when desc->table_avg_len
  *                       separates tables with short bags from the others; emb_bag_forward_mixed
  *                       makes one stream-kernel launch per lanes-per-row class that kernel suits
- *                       and one wave-kernel launch for the other tables
+ *                       and one wave-kernel launch for the other tables (as parts of one fused
+ *                       launch when plan->fused is set)
  *   table_order  HOST   uint16 [min(T, 1024)] or NULL: the table at each of the launch's
  *                       plan->tables positions (the identity unless plan->listed)
  *   Returns the status the forward call would return for the descriptor alone
@@ -277,6 +280,10 @@ typedef struct emb_bag_plan {
   int64_t waves_per_piece;   /* XCD-affine order only */
   int64_t blocks_per_piece;  /* XCD-affine order only */
   int64_t tables;            /* tables (positions) this launch covers */
+  int64_t fused;             /* 1 = the num_launches launches listed run as ONE kernel launch: they
+                                are consecutive ranges of its workgroups, in the order listed,
+                                each range padded to a multiple of 8 workgroups (see "fuse") */
+  int64_t fused_grid_blocks; /* workgroups of that one launch; 0 unless fused */
 } emb_bag_plan;
 
 int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, int32_t which,
@@ -314,6 +321,11 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   to rounding, not to the bit.
  *                   With desc->table_avg_len the automatic choice is made per table.
  *   "bags_per_group" consecutive bags per lane group in that kernel, 1..63; 0 = automatic
+ *   "fuse"          1 (default) = when emb_bag_forward_mixed would make several launches, they
+ *                   become consecutive workgroup ranges of one launch (same results, bit for
+ *                   bit; no ramp and drain per launch, which dominates at inference batch
+ *                   sizes); possible when the launches' table lists hold at most 1024 tables
+ *                   together.  0 = separate launches
  * Not thread-safe against concurrent emb_bag_forward calls.
  */
 int emb_bag_set_tuning(const char* key, int64_t value);

@@ -32,7 +32,7 @@ DEFAULT_GRID = {
 }
 # for short bags add e.g. --grid '{"stream":[0,1],"bags_per_group":[1,2,4,8],"depth":[4,8]}'
 NEUTRAL = {"blocks_per_cu": 0, "depth": 0, "use_hints": 1, "xcd_remap": -1, "addressing": 0,
-           "stream": -1, "bags_per_group": 0, "xcd_pieces": 0, "per_table_launch": 0}
+           "stream": -1, "bags_per_group": 0, "xcd_pieces": 0, "per_table_launch": 0, "fuse": 1}
 
 
 def apply_tuning(settings: Dict[str, int]) -> None:

@@ -55,7 +55,8 @@ class emb_bag_plan(ctypes.Structure):
                 ("listed", ctypes.c_int32), ("num_launches", ctypes.c_int32),
                 ("grid_blocks", ctypes.c_int64), ("wavefronts", ctypes.c_int64),
                 ("waves_per_table", ctypes.c_int64), ("waves_per_piece", ctypes.c_int64),
-                ("blocks_per_piece", ctypes.c_int64), ("tables", ctypes.c_int64)]
+                ("blocks_per_piece", ctypes.c_int64), ("tables", ctypes.c_int64),
+                ("fused", ctypes.c_int64), ("fused_grid_blocks", ctypes.c_int64)]
 
     def as_dict(self) -> dict:
         return {name: int(getattr(self, name)) for name, _ in self._fields_}

@@ -16,12 +16,14 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 
 CSRC = "paper_2410_22249_amd/csrc/"
 TARGETS = {
-    # output (relative to the repo root): (source, lanes-per-row class or None) pairs, compiled
-    # side by side, then linked.  The kernel sources are compiled once per class (-DEMB_LPR=n).
+    # output (relative to the repo root): (source, variant or None) pairs, compiled side by side,
+    # then linked.  The wave and stream kernel sources are compiled once per lanes-per-row class
+    # (-DEMB_LPR=n), the fused kernel once per element type (-DEMB_ELEM=n).
     "paper_2410_22249_amd/libembbag.so":
         [(CSRC + "emb_bag.hip", None)]
         + [(CSRC + "emb_bag_wave.hip", n) for n in (0, 4, 8, 16, 32, 64)]
-        + [(CSRC + "emb_bag_stream.hip", n) for n in (4, 8, 16, 32, 64)],
+        + [(CSRC + "emb_bag_stream.hip", n) for n in (4, 8, 16, 32, 64)]
+        + [(CSRC + "emb_bag_fused.hip", n) for n in (0, 1, 2, 3, 4)],
     "inputgen/libembgen.so": [("inputgen/csrc/embgen.hip", None)],
 }
 MAX_JOBS = max(1, min(int(os.environ.get("MAX_JOBS", "8")), os.cpu_count() or 1))
@@ -60,8 +62,12 @@ def _finish(proc, what: str, verbose: bool) -> None:
         raise RuntimeError(f"hipcc failed for {what}")
 
 
-def _obj(src: str, lpr) -> str:
-    tag = "" if lpr is None else f".lpr{lpr}"
+def _define(src: str) -> str:
+    return "EMB_ELEM" if src.endswith("emb_bag_fused.hip") else "EMB_LPR"
+
+
+def _obj(src: str, variant) -> str:
+    tag = "" if variant is None else f".{_define(src)[4:].lower()}{variant}"
     return os.path.join(OBJ_DIR, os.path.basename(src) + tag + ".o")
 
 
@@ -74,7 +80,7 @@ def build_all(verbose: bool = True) -> None:
     while todo or running:
         while todo and len(running) < MAX_JOBS:
             src, lpr = todo.pop(0)
-            defs = [] if lpr is None else [f"-DEMB_LPR={lpr}"]
+            defs = [] if lpr is None else [f"-D{_define(src)}={lpr}"]
             cmd = [HIPCC] + HIP_FLAGS + inc + defs + ["-c", "-o", _obj(src, lpr),
                                                       os.path.join(ROOT, src)]
             running.append((f"{src} {' '.join(defs)}", _run(cmd, verbose)))

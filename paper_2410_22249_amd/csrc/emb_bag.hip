@@ -116,6 +116,7 @@ struct Tuning {
   int64_t bags_per_group = 0;   // its consecutive bags per lane group: 0 = automatic
   int64_t xcd_pieces = 0;       // pieces per table in XCD-affine order: 0 = automatic, 1, 2, 4, 8
   int64_t per_table_launch = 0; // 1 = one launch per table, as the paper's system does (Sec. 3.1)
+  int64_t fuse = 1;             // 1 = the launches of a split mixed-width call become one launch
 };
 Tuning g_tuning;
 
@@ -151,6 +152,17 @@ KernelFn pick_stream_kernel(int lpr, int elem, int depth, bool weighted, bool mi
     case 16: return pick_stream_kernel_lpr16(elem, depth, weighted, mixed);
     case 32: return pick_stream_kernel_lpr32(elem, depth, weighted, mixed);
     case 64: return pick_stream_kernel_lpr64(elem, depth, weighted, mixed);
+    default: return nullptr;
+  }
+}
+
+FusedFn pick_fused_kernel(int elem, int depth, bool weighted) {
+  switch (elem) {
+    case EMB_F32: return pick_fused_kernel_elem0(depth, weighted);
+    case EMB_F16: return pick_fused_kernel_elem1(depth, weighted);
+    case EMB_BF16: return pick_fused_kernel_elem2(depth, weighted);
+    case EMB_U8ROW: return pick_fused_kernel_elem3(depth, weighted);
+    case EMB_FP8ROW: return pick_fused_kernel_elem4(depth, weighted);
     default: return nullptr;
   }
 }
@@ -558,28 +570,102 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
   return EMB_OK;
 }
 
+// A cap on resident workgroups per CU is imposed through a dynamic LDS request that the kernel
+// never touches: k workgroups fit when each asks for 1/k of the CU's LDS.
+int occupancy_cap_lds(const void* fn, uint32_t* lds) {
+  *lds = 0;
+  if (g_tuning.blocks_per_cu <= 0) return EMB_OK;
+  int dev = 0, lds_per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor,
+                            dev) != hipSuccess || lds_per_cu <= 0)
+    return EMB_ERR_LAUNCH;
+  *lds = ((uint32_t)lds_per_cu / (uint32_t)g_tuning.blocks_per_cu) & ~1023u;
+  if (*lds > 65536u &&
+      hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)*lds) != hipSuccess)
+    return EMB_ERR_LAUNCH;
+  return EMB_OK;
+}
+
 // Apply the occupancy cap and launch what was planned.
 int launch(const Launch& L, const void* tables, const int64_t* table_offsets,
            const int64_t* indices, const int64_t* offsets, const float* weights,
            const uint8_t* table_hints, const int64_t* out_offsets, float* out, void* stream) {
-  // A cap on resident workgroups per CU is imposed through a dynamic LDS request that the
-  // kernel never touches: k workgroups fit when each asks for 1/k of the CU's LDS.
   uint32_t lds = 0;
-  if (g_tuning.blocks_per_cu > 0) {
-    int dev = 0, lds_per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor,
-                              dev) != hipSuccess || lds_per_cu <= 0)
-      return EMB_ERR_LAUNCH;
-    lds = ((uint32_t)lds_per_cu / (uint32_t)g_tuning.blocks_per_cu) & ~1023u;
-    if (lds > 65536u &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(L.fn),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return EMB_ERR_LAUNCH;
-  }
+  const int rc = occupancy_cap_lds(reinterpret_cast<const void*>(L.fn), &lds);
+  if (rc != EMB_OK) return rc;
   hipLaunchKernelGGL(L.fn, dim3(L.blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
                      static_cast<const char*>(tables), table_offsets, indices, offsets, weights,
                      table_hints, out_offsets, out, L.p, L.order);
+  return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
+}
+
+// The launches of a split mixed-width call as ONE launch: consecutive ranges of its workgroups
+// run what would have been the separate launches (emb_bag_fused.hip).
+struct FusedLaunch {
+  FusedFn fn = nullptr;
+  FusedParams f;
+  TableOrder order;
+  uint32_t blocks = 0;
+};
+
+// Fuse `segs` (the launches plan_mixed made for one call) if there are several, each body occurs
+// at most once, their table lists fit one list, and the grid fits one dispatch.
+bool plan_fused(const std::vector<Launch>& segs, int table_dtype, bool weighted,
+                FusedLaunch* F) {
+  if (g_tuning.fuse == 0 || segs.size() < 2 || segs.size() > (size_t)kFusedSegments) return false;
+  const Launch* by_slot[kFusedSegments] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  int64_t tables = 0;
+  int depth = 4;
+  for (const Launch& L : segs) {
+    int slot;
+    if (L.kernel == EMB_KERNEL_WAVE) {
+      if (L.lpr != 0 || !L.buf) return false;
+      slot = 0;
+    } else {
+      slot = 0;
+      while ((2 << slot) < L.lpr) ++slot;  // 4 -> 1, 8 -> 2, ... 64 -> 5
+    }
+    if (slot >= kFusedSegments || by_slot[slot] || !L.p.listed) return false;
+    by_slot[slot] = &L;
+    tables += L.tables;
+    // one depth for the launch: the bodies with 8 or more lanes per row share it
+    if ((slot == 0 || L.lpr >= 8) && L.depth > depth) depth = L.depth;
+  }
+  if (tables > kMaxOrdered) return false;
+  for (const Launch& L : segs)
+    if ((L.kernel == EMB_KERNEL_WAVE || L.lpr >= 8) && L.depth != depth) return false;
+  F->fn = pick_fused_kernel(table_dtype, depth, weighted);
+  if (!F->fn) return false;
+  uint64_t end = 0;
+  uint32_t base = 0;
+  for (int k = 0; k < kFusedSegments; ++k) {
+    F->f.order_base[k] = base;
+    if (const Launch* L = by_slot[k]) {
+      F->f.seg[k] = L->p;
+      for (int64_t t = 0; t < L->tables; ++t) F->order.t[base + t] = L->order.t[t];
+      base += (uint32_t)L->tables;
+      end += ((uint64_t)L->blocks + 7u) & ~7ull;  // padding workgroups find no work
+    } else {
+      F->f.seg[k] = KParams{};
+    }
+    if (end > kMaxBlocks) return false;
+    F->f.end_block[k] = (uint32_t)end;
+  }
+  F->blocks = (uint32_t)end;
+  return true;
+}
+
+int launch_fused(const FusedLaunch& F, const void* tables, const int64_t* table_offsets,
+                 const int64_t* indices, const int64_t* offsets, const float* weights,
+                 const uint8_t* table_hints, const int64_t* out_offsets, float* out,
+                 void* stream) {
+  uint32_t lds = 0;
+  const int rc = occupancy_cap_lds(reinterpret_cast<const void*>(F.fn), &lds);
+  if (rc != EMB_OK) return rc;
+  hipLaunchKernelGGL(F.fn, dim3(F.blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
+                     static_cast<const char*>(tables), table_offsets, indices, offsets, weights,
+                     table_hints, out_offsets, out, F.f, F.order);
   return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
 }
 
@@ -656,6 +742,10 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   rc = plan_mixed(desc, per_sample_weights != nullptr, max_row_bytes, out_ld, &launches);
   if (rc == EMB_OK) rc = check_grids(launches);
   if (rc != EMB_OK) return rc;
+  FusedLaunch fused;
+  if (plan_fused(launches, desc->table_dtype, per_sample_weights != nullptr, &fused))
+    return launch_fused(fused, tables, table_byte_offsets, indices, offsets, per_sample_weights,
+                        desc->table_hints, out_offsets, out, stream);
   for (const Launch& L : launches) {  // disjoint tables: the launches are independent
     rc = launch(L, tables, table_byte_offsets, indices, offsets, per_sample_weights,
                 desc->table_hints, out_offsets, out, stream);
@@ -697,6 +787,11 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
   if (rc != EMB_OK) return rc;
   if (which < 0 || (size_t)which >= launches.size()) return EMB_ERR_BAD_SIZE;
   report(launches[(size_t)which], (int32_t)launches.size(), plan, table_order);
+  FusedLaunch fused;
+  if (plan_fused(launches, desc->table_dtype, has_weights != 0, &fused)) {
+    plan->fused = 1;
+    plan->fused_grid_blocks = fused.blocks;
+  }
   return EMB_OK;
 }
 
@@ -769,6 +864,9 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
   } else if (!strcmp(key, "per_table_launch")) {
     if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
     g_tuning.per_table_launch = value;
+  } else if (!strcmp(key, "fuse")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    g_tuning.fuse = value;
   } else if (!strcmp(key, "xcd_pieces")) {
     if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
       return EMB_ERR_BAD_TUNING;
@@ -790,6 +888,7 @@ int emb_bag_get_tuning(const char* key, int64_t* value) {
   else if (!strcmp(key, "bags_per_group")) *value = g_tuning.bags_per_group;
   else if (!strcmp(key, "xcd_pieces")) *value = g_tuning.xcd_pieces;
   else if (!strcmp(key, "per_table_launch")) *value = g_tuning.per_table_launch;
+  else if (!strcmp(key, "fuse")) *value = g_tuning.fuse;
   else return EMB_ERR_BAD_TUNING;
   return EMB_OK;
 }
@@ -810,6 +909,6 @@ const char* emb_bag_status_string(int status) {
   }
 }
 
-int emb_bag_version(void) { return 300; }
+int emb_bag_version(void) { return 400; }
 
 }  // extern "C"

@@ -60,6 +60,30 @@ using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int
                           const float*, const uint8_t*, const int64_t*, float*, KParams,
                           TableOrder);
 
+// A fused launch runs several bodies over consecutive ranges of its workgroups: segment 0 is the
+// wave body for tables of different widths, segments 1 .. 5 the stream body with 4, 8, 16, 32, 64
+// lanes per row.  Segment k owns workgroups [end_block[k-1], end_block[k]) (from 0 for k = 0; an
+// unused segment is empty), every boundary a multiple of 8 so that a workgroup's index within
+// its segment still names its XCD; its tables are TableOrder::t[order_base[k] ...].
+constexpr int kFusedSegments = 6;
+struct FusedParams {
+  uint32_t end_block[kFusedSegments];
+  uint32_t order_base[kFusedSegments];
+  KParams seg[kFusedSegments];
+};
+using FusedFn = void (*)(const char*, const int64_t*, const int64_t*, const int64_t*,
+                         const float*, const uint8_t*, const int64_t*, float*, FusedParams,
+                         TableOrder);
+// emb_bag_fused.hip, one translation unit per element type; depth 4 or 8
+#define EMB_DECLARE_FUSED(n) \
+  __attribute__((visibility("hidden"))) FusedFn pick_fused_kernel_elem##n(int depth, bool weighted);
+EMB_DECLARE_FUSED(0)
+EMB_DECLARE_FUSED(1)
+EMB_DECLARE_FUSED(2)
+EMB_DECLARE_FUSED(3)
+EMB_DECLARE_FUSED(4)
+#undef EMB_DECLARE_FUSED
+
 // The forward kernels are built one lanes-per-row class per translation unit; each unit exports
 // one function that picks an instantiation (nullptr if there is none):
 //   wave kernel (emb_bag_wave.hip):     lanes per row 0 (different widths), 4 .. 64

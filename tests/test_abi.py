@@ -128,7 +128,7 @@ def test_tuning_keys():
     for key, good, bad in (("depth", 8, 3), ("addressing", 1, 5), ("blocks_per_cu", 2, 9),
                            ("xcd_remap", 1, 2), ("use_hints", 0, 2),
                            ("stream", 0, 2), ("bags_per_group", 5, 64),
-                           ("xcd_pieces", 4, 3), ("per_table_launch", 1, 2)):
+                           ("xcd_pieces", 4, 3), ("per_table_launch", 1, 2), ("fuse", 0, 2)):
         old = emb.emb_bag_get_tuning(key)
         emb.emb_bag_set_tuning(key, good)
         assert emb.emb_bag_get_tuning(key) == good

@@ -321,3 +321,81 @@ def test_mixed_widths_with_more_tables_than_one_list_holds(oracle, pooling):
     with tuning(xcd_remap=1):
         got = _forward(wl, arena, batch, "sum").cpu().numpy()
     assert_close_to_oracle(got, ref, bound, False, f"2600 tables/{pooling}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "u8row"])
+@pytest.mark.parametrize("pooling", [("fixed", 1), ("uniform", 0, 5),
+                                     ("per_table", (("fixed", 1), ("uniform", 50, 90), ("uniform", 0, 2)))])
+def test_fused_launch_equals_the_separate_launches(oracle, dtype, pooling):
+    """A split mixed-width call runs as one fused launch (consecutive workgroup ranges run what
+    the separate launches would): same bits as the separate launches, in every mode, with and
+    without weights, hints and the XCD-affine order, and within tolerance of the oracle."""
+    for weighted in (False, True):
+        wl = _wl(dtype, pooling=pooling, weighted=weighted, B=389)
+        batch = gen.make_batches(wl, 1)[0]
+        tabs = gen.mixed_host_tables(wl)
+        arena = _device_arena(wl)
+        avg = gen.table_avg_len(wl, batch) if pooling[0] == "per_table" else None
+        total = int(sum(wl.dims))
+        hints = to_dev((np.arange(wl.T) % 2).astype(np.uint8))
+        boff, ooff = to_dev(wl.table_byte_offsets()), to_dev(wl.out_offsets())
+        idx, off, w = to_dev(batch.indices), to_dev(batch.offsets), to_dev(batch.weights)
+        for mode in (("sum",) if weighted else ("sum", "mean")):
+            desc = emb.make_mixed_desc(wl.dims, wl.B, EDT[dtype], emb.MODES[mode], batch.num_lookups, 0,
+                                       int(np.diff(wl.table_byte_offsets()).max()), hints, avg)
+            ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, mode,
+                                              weights=batch.weights)
+
+            def run():
+                out = torch.full((wl.B, total), float("nan"), dtype=torch.float32, device=DEV)
+                emb.emb_bag_forward_mixed(desc, arena, boff, ooff, idx, off, w, out)
+                torch.cuda.synchronize()
+                return out.cpu().numpy()
+
+            for kw in (dict(), dict(xcd_remap=1), dict(depth=8), dict(depth=4, bags_per_group=2)):
+                with tuning(fuse=1, **kw):
+                    plan = emb.emb_bag_plan_forward_mixed(desc, weighted)
+                    assert plan.num_launches >= 2 and plan.fused == 1
+                    blocks = [emb.emb_bag_plan_forward_mixed(desc, weighted, which=k).grid_blocks
+                              for k in range(plan.num_launches)]
+                    assert plan.fused_grid_blocks == sum(-(-b // 8) * 8 for b in blocks)
+                    fused = run()
+                with tuning(fuse=0, **kw):
+                    assert emb.emb_bag_plan_forward_mixed(desc, weighted).fused == 0
+                    separate = run()
+                what = f"fused/{dtype}/{pooling[0]}/{mode}/w{int(weighted)}/{kw}"
+                assert np.array_equal(fused.view(np.uint32), separate.view(np.uint32)), what
+                assert_close_to_oracle(fused, ref, bound, dtype != "f32", what)
+
+
+def test_fused_launch_replays_from_a_graph_and_respects_the_occupancy_cap(oracle):
+    wl = _wl("f32", pooling=("uniform", 0, 4), B=300)
+    batch = gen.make_batches(wl, 1)[0]
+    tabs = gen.mixed_host_tables(wl)
+    arena = _device_arena(wl)
+    ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, "sum")
+    with tuning(blocks_per_cu=2):
+        got = _forward(wl, arena, batch, "sum").cpu().numpy()
+    assert_close_to_oracle(got, ref, bound, False, "fused, 2 workgroups per CU")
+    total = int(sum(wl.dims))
+    desc = emb.make_mixed_desc(wl.dims, wl.B, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups, 0,
+                               int(np.diff(wl.table_byte_offsets()).max()))
+    assert emb.emb_bag_plan_forward_mixed(desc).fused == 1
+    boff, ooff = to_dev(wl.table_byte_offsets()), to_dev(wl.out_offsets())
+    idx, off = to_dev(batch.indices), to_dev(batch.offsets)
+    out = torch.zeros((wl.B, total), dtype=torch.float32, device=DEV)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        emb.emb_bag_forward_mixed(desc, arena, boff, ooff, idx, off, None, out, stream.cuda_stream)
+    stream.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        emb.emb_bag_forward_mixed(desc, arena, boff, ooff, idx, off, None, out,
+                                  torch.cuda.current_stream().cuda_stream)
+    for _ in range(3):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), got.view(np.uint32))

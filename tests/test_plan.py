@@ -344,3 +344,33 @@ def test_a_launch_holds_at_most_2_pow_24_minus_1_workgroups():
         with pytest.raises(emb.EmbBagError) as ex:
             emb.emb_bag_plan_forward_mixed(m)
         assert ex.value.status == -7
+
+
+def test_split_mixed_calls_are_fused_into_one_launch():
+    """The launches of a split mixed-width call become consecutive workgroup ranges of one launch
+    when every body occurs once and the table lists fit one list of 1024."""
+    dims = [(16, 32, 64, 128)[t % 4] for t in range(26)]
+    first, _ = _mixed_plan(dims, 2048, 1)
+    assert first.num_launches == 4 and first.fused == 1
+    parts = [_mixed_plan(dims, 2048, 1, which=w)[0] for w in range(4)]
+    assert all(p.fused == 1 and p.fused_grid_blocks == first.fused_grid_blocks for p in parts)
+    assert first.fused_grid_blocks == sum(-(-p.grid_blocks // 8) * 8 for p in parts)
+    with tuning(fuse=0):
+        assert _mixed_plan(dims, 2048, 1)[0].fused == 0
+    assert _mixed_plan(dims, 2048, 80)[0].fused == 0                    # one launch: nothing to fuse
+    # a wave launch and stream launches together (per-table lengths)
+    lens = [1.0 if t % 2 else 80.0 for t in range(26)]
+    desc = emb.make_mixed_desc(dims, 2048, emb.EMB_F32, emb.EMB_MEAN, int(sum(lens) * 2048), 0, 1 << 30,
+                               table_avg_len=lens)
+    plans = [emb.emb_bag_plan_forward_mixed(desc, False, False, w)
+             for w in range(emb.emb_bag_plan_forward_mixed(desc).num_launches)]
+    assert {p.kernel for p in plans} == {emb.EMB_KERNEL_WAVE, emb.EMB_KERNEL_STREAM}
+    assert all(p.fused == 1 for p in plans)
+    # more tables than one list holds: separate launches
+    assert _mixed_plan([32, 64] * 1500, 2000, 1)[0].fused == 0
+    assert _mixed_plan([32, 64] * 600, 2000, 1)[0].fused == 0           # 1200 tables in two lists
+    assert _mixed_plan([32, 64] * 500, 2000, 1)[0].fused == 1           # 1000 tables
+    # the uniform-width call is never fused (its two launches are separate kernels)
+    d = emb.make_desc(26, 32768, 64, emb.EMB_F32, emb.EMB_SUM, 26 * 32768 * 10, 0, 1_000_000,
+                      table_avg_len=[1.0] * 13 + [100.0] * 13)
+    assert emb.emb_bag_plan_forward(d).num_launches == 2 and emb.emb_bag_plan_forward(d).fused == 0
