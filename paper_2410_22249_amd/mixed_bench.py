@@ -2,11 +2,18 @@
 width, on one MI355X.
 
     python -m paper_2410_22249_amd.mixed_bench [--steps 20]
+    python -m paper_2410_22249_amd.mixed_bench --split-sweep
 
 Workload "mixed_cfg": 60 fp32 tables x 4,000,000 rows, widths cycling 32 / 64 / 128 / 256, batch
 4096, pooling 80, uniform indices (the paper's model has one width, Sec. 5; production models mix
 them).  The comparison runs the same 15 tables of each width through `emb_bag_forward`, four
 launches, and adds their times.  Prints a markdown table.
+
+`--split-sweep`: workload "mixed_onehot" (26 fp32 tables x 1,000,000 rows, widths cycling 16 / 32 /
+64 / 128, short bags) at batch sizes from inference (512, 2048: the paper's, Sec. 5) to 131,072.
+Short bags split the call by row class; the table compares the fused launch (the classes as
+workgroup ranges of one kernel), the separate launches ("fuse" 0) and the one-wavefront-per-bag
+kernel alone ("stream" 0).
 """
 from __future__ import annotations
 
@@ -33,14 +40,74 @@ def _events(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps / 1e3
 
 
+def split_sweep(steps: int, warmup: int) -> int:
+    from dataclasses import replace
+
+    import numpy as np
+    import torch
+    import paper_2410_22249_amd as emb
+    from inputgen import gen
+
+    dev = "cuda:0"
+    print("| pooling | batch | parts | fused us | separate launches us | wave kernel alone us | "
+          "algorithmic GB/s (fused) |")
+    print("|---|---|---|---|---|---|---|")
+    for pool, label in ((("fixed", 1), "1"), (("uniform", 0, 4), "U[0,4]")):
+        for B in (512, 2048, 8192, 32768, 131072):
+            wl = replace(gen.mixed_workload("mixed_onehot"), B=B, pooling=pool)
+            arena = torch.empty(wl.table_bytes, dtype=torch.uint8, device=dev)
+            gen.mixed_fill_device(wl, arena.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            batches = gen.make_batches(wl, 2)
+            boff = torch.from_numpy(wl.table_byte_offsets()).to(dev)
+            ooff = torch.from_numpy(wl.out_offsets()).to(dev)
+            dbat = [(torch.from_numpy(b.indices).to(dev), torch.from_numpy(b.offsets).to(dev))
+                    for b in batches]
+            hints = torch.ones(wl.T, dtype=torch.uint8, device=dev)
+            max_bytes = int(np.diff(wl.table_byte_offsets()).max())
+            descs = [emb.make_mixed_desc(wl.dims, wl.B, emb.EMB_F32, emb.EMB_SUM, b.num_lookups, 0,
+                                         max_bytes, hints) for b in batches]
+            out = torch.empty((wl.B, int(sum(wl.dims))), dtype=torch.float32, device=dev)
+            torch.cuda.synchronize()
+
+            def call(i):
+                k = i % len(dbat)
+                emb.emb_bag_forward_mixed(descs[k], arena, boff, ooff, dbat[k][0], dbat[k][1], None, out)
+
+            times = {}
+            try:
+                plan = emb.emb_bag_plan_forward_mixed(descs[0])
+                times["fused"] = _events(call, steps, warmup)
+                emb.emb_bag_set_tuning("fuse", 0)
+                times["separate"] = _events(call, steps, warmup)
+                emb.emb_bag_set_tuning("fuse", 1)
+                emb.emb_bag_set_tuning("stream", 0)
+                times["wave"] = _events(call, steps, warmup)
+            finally:
+                emb.emb_bag_set_tuning("fuse", 1)
+                emb.emb_bag_set_tuning("stream", -1)
+            nl = float(np.mean([b.num_lookups for b in batches]))
+            algo = (float(np.mean([wl.gathered_bytes(b) for b in batches])) + 8 * nl
+                    + 8 * (wl.T * B + 1) + 4 * B * sum(wl.dims))
+            print(f"| {label} | {B} | {plan.num_launches}{'' if plan.fused else ' (not fused)'} | "
+                  f"{times['fused'] * 1e6:.1f} | {times['separate'] * 1e6:.1f} | "
+                  f"{times['wave'] * 1e6:.1f} | {algo / times['fused'] / 1e9:.0f} |", flush=True)
+            del arena, out
+            torch.cuda.empty_cache()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
+    ap.add_argument("--split-sweep", action="store_true",
+                    help="fused launch against separate launches over batch sizes (mixed_onehot)")
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batches", type=int, default=4)
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="emb_bag_set_tuning override, e.g. --tune xcd_remap=0")
     a = ap.parse_args()
+    if a.split_sweep:
+        return split_sweep(max(a.steps, 50), max(a.warmup, 5))
 
     import numpy as np
     import torch
