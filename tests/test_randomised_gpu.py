@@ -1,6 +1,7 @@
 """Seeded random problems over everything the forward calls accept: uniform and mixed widths, all
 element types, the three pooling modes, weights, short / long / per-table bag lengths (with and
-without table_avg_len), hints, padded outputs, and every tuning key.  Each case is checked against
+without table_avg_len), hints, padded outputs, and every tuning key (fused and separate launches
+of split mixed-width calls alternate).  Each case is checked against
 the CPU oracle, and guard rows around the output show that no store leaves it; a failure names its
 case, which the seed reproduces."""
 import numpy as np
@@ -55,7 +56,7 @@ def test_random_problems(oracle, block):
         kw = dict(addressing=int(rng.choice([0, 0, 1])), depth=int(rng.choice([0, 1, 2, 4, 8, 16])),
                   xcd_remap=int(rng.integers(-1, 2)), blocks_per_cu=int(rng.choice([0, 0, 0, 3])),
                   stream=int(rng.integers(-1, 2)), bags_per_group=int(rng.choice([0, 0, 1, 2, 3, 7])),
-                  use_hints=int(rng.integers(0, 2)))
+                  use_hints=int(rng.integers(0, 2)), fuse=case % 2)
         hints = to_dev(rng.integers(0, 2, size=T).astype(np.uint8)) if rng.random() < 0.5 else None
         pad = int(rng.choice([0, 0, 4, 64]))
         if mixed:
