@@ -134,9 +134,12 @@ typedef struct emb_bag_desc {
  * has a wavefront of its own (fewer wavefronts are needed when the short-bag kernel serves the
  * call).  Split a larger batch over several calls.
  *
- * One call is one kernel launch; with desc->table_avg_len it may be two (tables with short bags,
- * the other tables), enqueued on `stream` one after the other and writing disjoint columns
- * (emb_bag_plan_forward lists them).  More than 65535 tables are then served by one kernel.
+ * One call is one kernel launch.  With desc->table_avg_len the tables with short bags may be
+ * served by the short-bag kernel and the others by the one-wavefront-per-bag kernel: as two
+ * workgroup ranges of one fused launch (see the "fuse" tuning key), or - with more than 1024
+ * tables, a prefetch depth other than 4 or 8, or "fuse" off - as two launches that write disjoint
+ * columns and are enqueued on `stream` one after the other (emb_bag_plan_forward lists them).
+ * More than 65535 tables are then served by one kernel.
  */
 int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t* table_offsets,
                     const int64_t* indices, const int64_t* offsets,
@@ -243,7 +246,8 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
  *   plan         HOST   filled in; all zero for batch == 0
  *   which        which of the call's launches to describe, 0 .. num_launches - 1.
  *                       emb_bag_forward makes one launch, or two when desc->table_avg_len
- *                       separates tables with short bags from the others; emb_bag_forward_mixed
+ *                       separates tables with short bags from the others (the others are
+ *                       listed first); emb_bag_forward_mixed
  *                       makes one stream-kernel launch per lanes-per-row class that kernel suits
  *                       and one wave-kernel launch for the other tables (as parts of one fused
  *                       launch when plan->fused is set)
@@ -321,11 +325,12 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   to rounding, not to the bit.
  *                   With desc->table_avg_len the automatic choice is made per table.
  *   "bags_per_group" consecutive bags per lane group in that kernel, 1..63; 0 = automatic
- *   "fuse"          1 (default) = when emb_bag_forward_mixed would make several launches, they
+ *   "fuse"          1 (default) = when a forward call would make several launches, they
  *                   become consecutive workgroup ranges of one launch (same results, bit for
  *                   bit; no ramp and drain per launch, which dominates at inference batch
  *                   sizes); possible when the launches' table lists hold at most 1024 tables
- *                   together.  0 = separate launches
+ *                   together (and, for emb_bag_forward, the depth is 4 or 8).  0 = separate
+ *                   launches
  * Not thread-safe against concurrent emb_bag_forward calls.
  */
 int emb_bag_set_tuning(const char* key, int64_t value);

@@ -18,12 +18,14 @@ CSRC = "paper_2410_22249_amd/csrc/"
 TARGETS = {
     # output (relative to the repo root): (source, variant or None) pairs, compiled side by side,
     # then linked.  The wave and stream kernel sources are compiled once per lanes-per-row class
-    # (-DEMB_LPR=n), the fused kernel once per element type (-DEMB_ELEM=n).
+    # (-DEMB_LPR=n), as is the fused kernel for one width; the fused kernel for different widths
+    # once per element type (-DEMB_ELEM=n).
     "paper_2410_22249_amd/libembbag.so":
         [(CSRC + "emb_bag.hip", None)]
         + [(CSRC + "emb_bag_wave.hip", n) for n in (0, 4, 8, 16, 32, 64)]
         + [(CSRC + "emb_bag_stream.hip", n) for n in (4, 8, 16, 32, 64)]
-        + [(CSRC + "emb_bag_fused.hip", n) for n in (0, 1, 2, 3, 4)],
+        + [(CSRC + "emb_bag_fused.hip", n) for n in (0, 1, 2, 3, 4)]
+        + [(CSRC + "emb_bag_fused_uniform.hip", n) for n in (4, 8, 16, 32, 64)],
     "inputgen/libembgen.so": [("inputgen/csrc/embgen.hip", None)],
 }
 MAX_JOBS = max(1, min(int(os.environ.get("MAX_JOBS", "8")), os.cpu_count() or 1))

@@ -116,7 +116,7 @@ struct Tuning {
   int64_t bags_per_group = 0;   // its consecutive bags per lane group: 0 = automatic
   int64_t xcd_pieces = 0;       // pieces per table in XCD-affine order: 0 = automatic, 1, 2, 4, 8
   int64_t per_table_launch = 0; // 1 = one launch per table, as the paper's system does (Sec. 3.1)
-  int64_t fuse = 1;             // 1 = the launches of a split mixed-width call become one launch
+  int64_t fuse = 1;             // 1 = the launches of a split call become one launch
 };
 Tuning g_tuning;
 
@@ -163,6 +163,17 @@ FusedFn pick_fused_kernel(int elem, int depth, bool weighted) {
     case EMB_BF16: return pick_fused_kernel_elem2(depth, weighted);
     case EMB_U8ROW: return pick_fused_kernel_elem3(depth, weighted);
     case EMB_FP8ROW: return pick_fused_kernel_elem4(depth, weighted);
+    default: return nullptr;
+  }
+}
+
+FusedFn pick_fused_uniform_kernel(int lpr, int elem, int depth, bool weighted) {
+  switch (lpr) {
+    case 4: return pick_fused_uniform_kernel_lpr4(elem, depth, weighted);
+    case 8: return pick_fused_uniform_kernel_lpr8(elem, depth, weighted);
+    case 16: return pick_fused_uniform_kernel_lpr16(elem, depth, weighted);
+    case 32: return pick_fused_uniform_kernel_lpr32(elem, depth, weighted);
+    case 64: return pick_fused_uniform_kernel_lpr64(elem, depth, weighted);
     default: return nullptr;
   }
 }
@@ -413,8 +424,8 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
     if (!short_ids.empty() && !long_ids.empty() &&
         make_stream(&stream, desc, weighted, depth, short_sum / (double)short_ids.size(),
                     (int64_t)short_ids.size(), out_ld)) {
-      add_launches(stream, T, short_ids, none, launches);
-      add_launches(wave, T, long_ids, none, launches);
+      add_launches(wave, T, long_ids, none, launches);  // listed in the order a fused launch
+      add_launches(stream, T, short_ids, none, launches);  // runs them: long bags first
       return EMB_OK;
     }
     // all tables on one side: one launch without a list
@@ -609,33 +620,44 @@ struct FusedLaunch {
   uint32_t blocks = 0;
 };
 
-// Fuse `segs` (the launches plan_mixed made for one call) if there are several, each body occurs
-// at most once, their table lists fit one list, and the grid fits one dispatch.
-bool plan_fused(const std::vector<Launch>& segs, int table_dtype, bool weighted,
+// Fuse `segs` (the launches planned for one call) if there are several, each body occurs at most
+// once, their table lists fit one list, and the grid fits one dispatch.  `mixed`: the call is for
+// tables of different widths (segment 0 the wave body, 1 .. 5 the stream body by lanes per row);
+// otherwise one width (segment 0 the wave body, 1 the stream body, both with lanes per row lpr).
+bool plan_fused(const std::vector<Launch>& segs, bool mixed, int table_dtype, bool weighted,
                 FusedLaunch* F) {
   if (g_tuning.fuse == 0 || segs.size() < 2 || segs.size() > (size_t)kFusedSegments) return false;
   const Launch* by_slot[kFusedSegments] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   int64_t tables = 0;
-  int depth = 4;
+  int depth = 0, lpr = 0;
   for (const Launch& L : segs) {
-    int slot;
+    int slot = 0;
     if (L.kernel == EMB_KERNEL_WAVE) {
-      if (L.lpr != 0 || !L.buf) return false;
-      slot = 0;
-    } else {
-      slot = 0;
+      if ((L.lpr == 0) != mixed || !L.buf) return false;
+      depth = L.depth;
+    } else if (mixed) {
       while ((2 << slot) < L.lpr) ++slot;  // 4 -> 1, 8 -> 2, ... 64 -> 5
+    } else {
+      slot = 1;
     }
     if (slot >= kFusedSegments || by_slot[slot] || !L.p.listed) return false;
+    if (!mixed && lpr != 0 && L.lpr != lpr) return false;
+    lpr = L.lpr;
     by_slot[slot] = &L;
     tables += L.tables;
-    // one depth for the launch: the bodies with 8 or more lanes per row share it
-    if ((slot == 0 || L.lpr >= 8) && L.depth > depth) depth = L.depth;
   }
   if (tables > kMaxOrdered) return false;
+  // one depth for the launch, the wave body's (4 or 8); a stream body takes the depth its own
+  // launch would: 4 if that is 4 or it has 4 lanes per row, else 8
+  if (depth == 0)
+    for (const Launch& L : segs)
+      if (L.depth > depth) depth = L.depth;
+  if (depth != 4 && depth != 8) return false;
   for (const Launch& L : segs)
-    if ((L.kernel == EMB_KERNEL_WAVE || L.lpr >= 8) && L.depth != depth) return false;
-  F->fn = pick_fused_kernel(table_dtype, depth, weighted);
+    if (L.kernel == EMB_KERNEL_STREAM && L.depth != ((depth == 4 || L.lpr < 8) ? 4 : 8))
+      return false;
+  F->fn = mixed ? pick_fused_kernel(table_dtype, depth, weighted)
+                : pick_fused_uniform_kernel(lpr, table_dtype, depth, weighted);
   if (!F->fn) return false;
   uint64_t end = 0;
   uint32_t base = 0;
@@ -717,6 +739,10 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
   rc = plan_uniform(desc, per_sample_weights != nullptr, row_bytes, out_ld, &launches);
   if (rc == EMB_OK) rc = check_grids(launches);
   if (rc != EMB_OK) return rc;
+  FusedLaunch fused;
+  if (plan_fused(launches, false, desc->table_dtype, per_sample_weights != nullptr, &fused))
+    return launch_fused(fused, tables, table_offsets, indices, offsets, per_sample_weights,
+                        desc->table_hints, nullptr, out, stream);
   for (const Launch& L : launches) {  // disjoint tables: the launches are independent
     rc = launch(L, tables, table_offsets, indices, offsets, per_sample_weights, desc->table_hints,
                 nullptr, out, stream);
@@ -743,7 +769,7 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
   if (rc == EMB_OK) rc = check_grids(launches);
   if (rc != EMB_OK) return rc;
   FusedLaunch fused;
-  if (plan_fused(launches, desc->table_dtype, per_sample_weights != nullptr, &fused))
+  if (plan_fused(launches, true, desc->table_dtype, per_sample_weights != nullptr, &fused))
     return launch_fused(fused, tables, table_byte_offsets, indices, offsets, per_sample_weights,
                         desc->table_hints, out_offsets, out, stream);
   for (const Launch& L : launches) {  // disjoint tables: the launches are independent
@@ -769,6 +795,11 @@ int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, int32_t whic
   if (rc != EMB_OK) return rc;
   if (which < 0 || (size_t)which >= launches.size()) return EMB_ERR_BAD_SIZE;
   report(launches[(size_t)which], (int32_t)launches.size(), plan, table_order);
+  FusedLaunch fused;
+  if (plan_fused(launches, false, desc->table_dtype, has_weights != 0, &fused)) {
+    plan->fused = 1;
+    plan->fused_grid_blocks = fused.blocks;
+  }
   return EMB_OK;
 }
 
@@ -788,7 +819,7 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
   if (which < 0 || (size_t)which >= launches.size()) return EMB_ERR_BAD_SIZE;
   report(launches[(size_t)which], (int32_t)launches.size(), plan, table_order);
   FusedLaunch fused;
-  if (plan_fused(launches, desc->table_dtype, has_weights != 0, &fused)) {
+  if (plan_fused(launches, true, desc->table_dtype, has_weights != 0, &fused)) {
     plan->fused = 1;
     plan->fused_grid_blocks = fused.blocks;
   }

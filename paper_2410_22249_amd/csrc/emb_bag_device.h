@@ -60,9 +60,9 @@ using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int
                           const float*, const uint8_t*, const int64_t*, float*, KParams,
                           TableOrder);
 
-// A fused launch runs several bodies over consecutive ranges of its workgroups: segment 0 is the
-// wave body for tables of different widths, segments 1 .. 5 the stream body with 4, 8, 16, 32, 64
-// lanes per row.  Segment k owns workgroups [end_block[k-1], end_block[k]) (from 0 for k = 0; an
+// A fused launch runs several bodies over consecutive ranges of its workgroups.  Tables of
+// different widths: segment 0 is the wave body, segments 1 .. 5 the stream body with 4, 8, 16,
+// 32, 64 lanes per row.  Tables of one width: segment 0 the wave body, segment 1 the stream body.  Segment k owns workgroups [end_block[k-1], end_block[k]) (from 0 for k = 0; an
 // unused segment is empty), every boundary a multiple of 8 so that a workgroup's index within
 // its segment still names its XCD; its tables are TableOrder::t[order_base[k] ...].
 constexpr int kFusedSegments = 6;
@@ -83,6 +83,19 @@ EMB_DECLARE_FUSED(2)
 EMB_DECLARE_FUSED(3)
 EMB_DECLARE_FUSED(4)
 #undef EMB_DECLARE_FUSED
+
+// emb_bag_fused_uniform.hip (tables of one width: segment 0 the wave body, segment 1 the stream
+// body, both with the call's lanes per row), one translation unit per class; depth 4 or 8
+#define EMB_DECLARE_FUSED_UNIFORM(n)                                                    \
+  __attribute__((visibility("hidden"))) FusedFn pick_fused_uniform_kernel_lpr##n(int elem, \
+                                                                                int depth, \
+                                                                                bool weighted);
+EMB_DECLARE_FUSED_UNIFORM(4)
+EMB_DECLARE_FUSED_UNIFORM(8)
+EMB_DECLARE_FUSED_UNIFORM(16)
+EMB_DECLARE_FUSED_UNIFORM(32)
+EMB_DECLARE_FUSED_UNIFORM(64)
+#undef EMB_DECLARE_FUSED_UNIFORM
 
 // The forward kernels are built one lanes-per-row class per translation unit; each unit exports
 // one function that picks an instantiation (nullptr if there is none):

@@ -19,7 +19,8 @@ import statistics
 import sys
 from collections import defaultdict
 
-EMB = ("emb_bag_wave_kernel", "emb_bag_stream_kernel", "emb_bag_fused_kernel")   # the forward kernels
+EMB = ("emb_bag_wave_kernel", "emb_bag_stream_kernel", "emb_bag_fused_kernel",
+       "emb_bag_fused_uniform_kernel")   # the forward kernels
 COPY = "(anonymous namespace)::copy_kernel("   # the generator's calibration copy, not torch's
 CAL_BYTES = 1 << 30
 

@@ -260,10 +260,19 @@ def test_per_table_bag_lengths_split_a_uniform_call_in_two():
 
     assert len(plans(avg=None)) == 1 and plans(avg=None)[0][0].kernel == emb.EMB_KERNEL_WAVE  # average 23.8
     both = plans()
-    assert [p.kernel for p, _ in both] == [emb.EMB_KERNEL_STREAM, emb.EMB_KERNEL_WAVE]
+    assert [p.kernel for p, _ in both] == [emb.EMB_KERNEL_WAVE, emb.EMB_KERNEL_STREAM]
     short = [t for t in range(T) if lens[t] == 1.0]
-    assert both[0][1] == short and both[1][1] == [t for t in range(T) if lens[t] == 100.0]
-    assert both[0][0].bags_per_group == 4 and both[0][0].listed == 1 and both[1][0].listed == 1
+    assert both[1][1] == short and both[0][1] == [t for t in range(T) if lens[t] == 100.0]
+    assert both[1][0].bags_per_group == 4 and both[0][0].listed == 1 and both[1][0].listed == 1
+    # ... as the two workgroup ranges of one fused launch (depth 4 or 8, at most 1024 tables)
+    assert all(p.fused == 1 for p, _ in both)
+    assert both[0][0].fused_grid_blocks == sum(-(-p.grid_blocks // 8) * 8 for p, _ in both)
+    with tuning(fuse=0):
+        assert all(p.fused == 0 for p, _ in plans())
+    with tuning(depth=2):
+        assert all(p.fused == 0 for p, _ in plans()) and len(plans()) == 2
+    with tuning(depth=8):
+        assert all(p.fused == 1 for p, _ in plans())
     for plan, order in both:
         table, wave, _ = _simulate(plan, plan.tables, order)
         flat = table * plan.waves_per_table + wave
@@ -370,7 +379,7 @@ def test_split_mixed_calls_are_fused_into_one_launch():
     assert _mixed_plan([32, 64] * 1500, 2000, 1)[0].fused == 0
     assert _mixed_plan([32, 64] * 600, 2000, 1)[0].fused == 0           # 1200 tables in two lists
     assert _mixed_plan([32, 64] * 500, 2000, 1)[0].fused == 1           # 1000 tables
-    # the uniform-width call is never fused (its two launches are separate kernels)
-    d = emb.make_desc(26, 32768, 64, emb.EMB_F32, emb.EMB_SUM, 26 * 32768 * 10, 0, 1_000_000,
-                      table_avg_len=[1.0] * 13 + [100.0] * 13)
+    # a uniform-width call with more than 1024 tables keeps its two launches
+    d = emb.make_desc(1100, 512, 64, emb.EMB_F32, emb.EMB_SUM, 1100 * 512 * 10, 0, 1000,
+                      table_avg_len=[1.0] * 550 + [100.0] * 550)
     assert emb.emb_bag_plan_forward(d).num_launches == 2 and emb.emb_bag_plan_forward(d).fused == 0

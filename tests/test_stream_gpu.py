@@ -280,3 +280,45 @@ def test_one_launch_per_table_gives_the_same_bits(oracle):
         with tuning(per_table_launch=1):
             many = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B).cpu().numpy()
         assert np.array_equal(one, many), name
+
+
+@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
+                                  "small_bf16_d256", "small_u8_d120", "small_fp8_d120"])
+def test_fused_launch_of_a_uniform_call_equals_its_two_launches(oracle, name):
+    """With table_avg_len a call with short-bag and long-bag tables is one fused launch (wave
+    body, then stream body); it gives the bits of the two separate launches."""
+    import paper_2410_22249_amd as emb
+    specs = (("fixed", 1), ("uniform", 60, 140), ("uniform", 0, 2), ("fixed", 90), ("fixed", 2))
+    for weighted in (False, True):
+        wl, batch, arena = _problem(name, pooling=("per_table", specs), B=333, weighted=weighted)
+        avg = gen.table_avg_len(wl, batch)
+        dev = upload_arena(arena)
+        hints = to_dev((np.arange(wl.T) % 2).astype(np.uint8))
+        toff, idx, off = to_dev(wl.table_offsets()), to_dev(batch.indices), to_dev(batch.offsets)
+        w = to_dev(batch.weights)
+        for mode in (("sum",) if weighted else ("sum", "mean")):
+            ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets,
+                                        wl.B, mode, weights=batch.weights, codes=wl.codes)
+            desc = emb.make_desc(wl.T, wl.B, wl.D, emb.DTYPES[wl.dtype], emb.MODES[mode],
+                                 batch.num_lookups, 0, max(wl.rows), hints, avg)
+
+            def run():
+                out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
+                emb.emb_bag_forward(desc, dev, toff, idx, off, w, out)
+                torch.cuda.synchronize()
+                return out.cpu().numpy()
+
+            for kw in (dict(), dict(xcd_remap=1), dict(depth=8), dict(depth=4, bags_per_group=2)):
+                with tuning(fuse=1, **kw):
+                    plan = emb.emb_bag_plan_forward(desc, weighted)
+                    assert plan.num_launches == 2 and plan.fused == 1
+                    fused = run()
+                with tuning(fuse=0, **kw):
+                    assert emb.emb_bag_plan_forward(desc, weighted).fused == 0
+                    separate = run()
+                what = f"fused uniform/{name}/{mode}/w{int(weighted)}/{kw}"
+                assert np.array_equal(fused.view(np.uint32), separate.view(np.uint32)), what
+                assert_close_to_oracle(fused, ref, bound, wl.dtype != "f32", what)
+            with tuning(depth=2):           # no fused kernel at this depth: two launches
+                assert emb.emb_bag_plan_forward(desc, weighted).fused == 0
+                assert_close_to_oracle(run(), ref, bound, wl.dtype != "f32", "depth 2")
