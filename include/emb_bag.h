@@ -102,6 +102,21 @@ typedef struct emb_bag_desc {
                              num_lookups / (T*B); with it, tables with short bags go to the
                              short-bag kernel and the others to the one-wavefront-per-bag kernel,
                              in two launches (see the "stream" tuning key).  Speed only. */
+  const int64_t* hot_rows; /* DEVICE, int64 [T], or NULL: hot_rows[t] leading rows of table t are
+                             its hot head, the rows a profile found to be looked up most often
+                             (the paper finds the top 60K indices per table offline and keeps
+                             their rows in L2, Sec. 4.3; emb_bag_profile_hot_rows finds them from
+                             a sample batch).  The caller lays the table out with those rows
+                             first and renumbers its row ids to match, once, offline.  Lookups
+                             of rows [0, hot_rows[t]) are then read with the default cache policy
+                             and gathered first, all other rows non-temporally, so that the
+                             stream of cold rows does not push the head out of L2; gfx950 has no
+                             residency control to pin them with.  When given, hot_rows replaces
+                             table_hints: 0 = a streaming table, >= R_t = a table re-used as a
+                             whole.  Speed only: results change by summation order (rounding)
+                             at most.  Honoured by the one-wavefront-per-bag kernel with 32-bit
+                             buffer addressing and a prefetch depth of 4 or 8 (plan->hot_split
+                             says whether); ignored otherwise. */
 } emb_bag_desc;
 
 /*
@@ -263,6 +278,8 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
  * of the table if that number is below waves_per_piece within the piece and below
  * waves_per_table overall, and unit is below tables * xcd_pieces (otherwise it has no work).  With xcd_pieces == 0 wavefront
  * 4 * g + w of the grid is wavefront number 4 * g + w in position-major order.
+ * In the wave kernel wavefront w of a table owns bags w * bags_per_wave .. (w + 1) * bags_per_wave
+ * - 1 of it (one column slab of bag w / slabs when rows are longer than 1 KiB).
  */
 #define EMB_KERNEL_WAVE 0   /* one wavefront per bag (per 1-KiB column slab of it) */
 #define EMB_KERNEL_STREAM 1 /* short bags: a lane group streams consecutive bags */
@@ -288,6 +305,9 @@ typedef struct emb_bag_plan {
                                 are consecutive ranges of its workgroups, in the order listed,
                                 each range padded to a multiple of 8 workgroups (see "fuse") */
   int64_t fused_grid_blocks; /* workgroups of that one launch; 0 unless fused */
+  int32_t bags_per_wave;     /* wave kernel: consecutive bags of a table per wavefront (wavefront w
+                                of a table owns bags w * bags_per_wave ...); else 0 */
+  int32_t hot_split;         /* 1 = the launch honours desc->hot_rows */
 } emb_bag_plan;
 
 int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, int32_t which,
@@ -331,6 +351,12 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   sizes); possible when the launches' table lists hold at most 1024 tables
  *                   together (and, for emb_bag_forward, the depth is 4 or 8).  0 = separate
  *                   launches
+ *   "bags_per_wave" consecutive bags of a table that one wavefront of the one-wavefront-per-bag
+ *                   kernel takes, 1..32; 0 = automatic (more for short bags, 1 for rows beyond
+ *                   1 KiB).  The bounds of a wavefront's bags come with one load and the next
+ *                   bag's row ids are requested while the current bag's rows are gathered (the
+ *                   index prefetch of Sec. 4.2, run across bags).  Same results, bit for bit
+ *   "hot_split"     1 (default) = honour desc->hot_rows, 0 = ignore it
  * Not thread-safe against concurrent emb_bag_forward calls.
  */
 int emb_bag_set_tuning(const char* key, int64_t value);

@@ -36,7 +36,8 @@ class emb_bag_desc(ctypes.Structure):
                 ("batch", ctypes.c_int64), ("num_lookups", ctypes.c_int64),
                 ("out_ld", ctypes.c_int64), ("max_table_rows", ctypes.c_int64),
                 ("table_hints", ctypes.c_void_p),
-                ("table_avg_len", ctypes.POINTER(ctypes.c_float))]
+                ("table_avg_len", ctypes.POINTER(ctypes.c_float)),
+                ("hot_rows", ctypes.c_void_p)]
 
 
 class emb_bag_mixed_desc(ctypes.Structure):
@@ -56,7 +57,8 @@ class emb_bag_plan(ctypes.Structure):
                 ("grid_blocks", ctypes.c_int64), ("wavefronts", ctypes.c_int64),
                 ("waves_per_table", ctypes.c_int64), ("waves_per_piece", ctypes.c_int64),
                 ("blocks_per_piece", ctypes.c_int64), ("tables", ctypes.c_int64),
-                ("fused", ctypes.c_int64), ("fused_grid_blocks", ctypes.c_int64)]
+                ("fused", ctypes.c_int64), ("fused_grid_blocks", ctypes.c_int64),
+                ("bags_per_wave", ctypes.c_int32), ("hot_split", ctypes.c_int32)]
 
     def as_dict(self) -> dict:
         return {name: int(getattr(self, name)) for name, _ in self._fields_}
@@ -122,16 +124,22 @@ def _stream_handle(stream) -> Optional[int]:
 
 def make_desc(num_tables: int, batch: int, dim: int, table_dtype: int, mode: int,
               num_lookups: int, out_ld: int = 0, max_table_rows: int = 0,
-              table_hints: Optional[torch.Tensor] = None, table_avg_len=None) -> emb_bag_desc:
-    """Fill the host descriptor.  `table_hints` is a device uint8 tensor [T] (or None) that the
-    caller keeps alive for as long as the descriptor is used; `table_avg_len` is a host sequence
-    of T floats (or None), of which the descriptor keeps its own copy."""
+              table_hints: Optional[torch.Tensor] = None, table_avg_len=None,
+              hot_rows: Optional[torch.Tensor] = None) -> emb_bag_desc:
+    """Fill the host descriptor.  `table_hints` (device uint8 [T]) and `hot_rows` (device int64
+    [T]) are tensors, or None, that the caller keeps alive for as long as the descriptor is used;
+    `table_avg_len` is a host sequence of T floats (or None), of which the descriptor keeps its
+    own copy."""
     if table_hints is not None:
         if table_hints.dtype != torch.uint8 or table_hints.numel() != num_tables:
             raise ValueError("table_hints must be a uint8 tensor with one entry per table")
+    if hot_rows is not None:
+        if hot_rows.dtype != torch.int64 or hot_rows.numel() != num_tables:
+            raise ValueError("hot_rows must be an int64 tensor with one entry per table")
     desc = emb_bag_desc(num_tables=num_tables, dim=dim, table_dtype=table_dtype, mode=mode,
                         batch=batch, num_lookups=num_lookups, out_ld=out_ld,
-                        max_table_rows=max_table_rows, table_hints=_ptr(table_hints))
+                        max_table_rows=max_table_rows, table_hints=_ptr(table_hints),
+                        hot_rows=_ptr(hot_rows))
     _attach_avg_len(desc, table_avg_len, num_tables)
     return desc
 

@@ -34,18 +34,21 @@ OBJ_DIR = os.path.join(ROOT, "_build")
 
 C_DRIVER_SRC = "tests/c_abi/c_abi_driver.c"
 C_DRIVER_BIN = "tests/c_abi/c_abi_driver"
+# plain-C programs over the ABI: the parity check, and the host-path timing bench.py reports
+C_PROGRAMS = {C_DRIVER_BIN: C_DRIVER_SRC, "tests/c_abi/c_abi_latency": "tests/c_abi/c_abi_latency.c"}
 
 
 def build_c_driver(verbose: bool = True) -> None:
-    """The plain-C caller of the ABI (gcc, HIP runtime API, no torch): proves the boundary is C."""
-    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
-           "-I", os.path.join(ROOT, "include"), "-o", os.path.join(ROOT, C_DRIVER_BIN),
-           os.path.join(ROOT, C_DRIVER_SRC), "-L", PKG, "-lembbag", "-L/opt/rocm/lib",
-           "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN/../../paper_2410_22249_amd",
-           "-Wl,-rpath,/opt/rocm/lib"]
-    if verbose:
-        print("[build]", " ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    """The plain-C callers of the ABI (gcc, HIP runtime API, no torch): prove the boundary is C."""
+    for out, src in C_PROGRAMS.items():
+        cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+               "-I", os.path.join(ROOT, "include"), "-o", os.path.join(ROOT, out),
+               os.path.join(ROOT, src), "-L", PKG, "-lembbag", "-L/opt/rocm/lib",
+               "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN/../../paper_2410_22249_amd",
+               "-Wl,-rpath,/opt/rocm/lib"]
+        if verbose:
+            print("[build]", " ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
 
 
 def _run(cmd, verbose: bool):

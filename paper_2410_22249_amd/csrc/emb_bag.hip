@@ -117,6 +117,8 @@ struct Tuning {
   int64_t xcd_pieces = 0;       // pieces per table in XCD-affine order: 0 = automatic, 1, 2, 4, 8
   int64_t per_table_launch = 0; // 1 = one launch per table, as the paper's system does (Sec. 3.1)
   int64_t fuse = 1;             // 1 = the launches of a split call become one launch
+  int64_t bags_per_wave = 0;    // wave kernel: consecutive bags per wavefront, 0 = automatic
+  int64_t hot_split = 1;        // 1 = honour desc->hot_rows, 0 = ignore it
 };
 Tuning g_tuning;
 
@@ -133,14 +135,14 @@ constexpr int64_t kStreamMinWaves = 1024;
 
 // The kernels are built one lanes-per-row class per translation unit (emb_bag_wave.hip and
 // emb_bag_stream.hip, compiled once per class); here the classes are put back together.
-KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf) {
+KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf, bool hot = false) {
   switch (lpr) {
-    case 0: return pick_wave_kernel_lpr0(elem, depth, op, buf);
-    case 4: return pick_wave_kernel_lpr4(elem, depth, op, buf);
-    case 8: return pick_wave_kernel_lpr8(elem, depth, op, buf);
-    case 16: return pick_wave_kernel_lpr16(elem, depth, op, buf);
-    case 32: return pick_wave_kernel_lpr32(elem, depth, op, buf);
-    case 64: return pick_wave_kernel_lpr64(elem, depth, op, buf);
+    case 0: return pick_wave_kernel_lpr0(elem, depth, op, buf, hot);
+    case 4: return pick_wave_kernel_lpr4(elem, depth, op, buf, hot);
+    case 8: return pick_wave_kernel_lpr8(elem, depth, op, buf, hot);
+    case 16: return pick_wave_kernel_lpr16(elem, depth, op, buf, hot);
+    case 32: return pick_wave_kernel_lpr32(elem, depth, op, buf, hot);
+    case 64: return pick_wave_kernel_lpr64(elem, depth, op, buf, hot);
     default: return nullptr;
   }
 }
@@ -196,12 +198,12 @@ int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out) {
   return EMB_OK;
 }
 
-// Everything a forward call decides on the host before it launches: the kernel instantiation,
-// its parameters, the grid and the table order.  Filled by plan_uniform / plan_mixed (no HIP
 // A dispatch counts its work-items in 32 bits, so a launch of 256-thread workgroups holds at most
 // 2^24 - 1 of them (67,108,860 wavefronts).  Larger calls are refused, not split.
 constexpr uint64_t kMaxBlocks = 0xFFFFFFull;
 
+// Everything a forward call decides on the host before it launches: the kernel instantiation,
+// its parameters, the grid and the table order.  Filled by plan_uniform / plan_mixed (no HIP
 // calls, no device pointers), launched by `launch`, reported by emb_bag_plan_forward*.
 struct Launch {
   KernelFn fn = nullptr;
@@ -213,6 +215,7 @@ struct Launch {
   int lpr = 0;
   int depth = 0;
   bool buf = false;
+  bool hot = false;       // the kernel splits a table's lookups into hot-head and other rows
 };
 
 // Lay out the grid of a launch over n tables (p.wpt wavefronts each): natural order, or the
@@ -296,6 +299,30 @@ int64_t stream_bags_per_group(double avg_len, int lpr, int64_t tables, int64_t B
   return m < 1 ? 1 : m;
 }
 
+// Consecutive bags per wavefront of the wave kernel.  A bag costs its wavefront a fixed chain
+// of memory round trips (bounds, row ids, first rows, store) besides its row loads; with several
+// bags per wavefront the bounds come with one load and the next bag's row ids are requested
+// while the current bag's rows are gathered.  Automatic: enough bags to give a wavefront about
+// kWaveLoadsTarget load instructions (rows_per_load rows each), at most kWaveMaxAutoBags, and
+// fewer when the launch would drop below kWaveMinWaves wavefronts.
+constexpr double kWaveLoadsTarget = 16.0;
+constexpr int64_t kWaveMaxAutoBags = 4;
+constexpr int64_t kWaveMinWaves = 32768;
+constexpr int64_t kWaveMaxBags = 32;
+int64_t wave_bags_per_wave(double avg_len, int rows_per_load, int64_t tables, int64_t B,
+                           int64_t slabs) {
+  if (slabs > 1) return 1;
+  int64_t m = g_tuning.bags_per_wave;
+  if (m == 0) {
+    const double loads = (avg_len < 1.0 ? 1.0 : avg_len) / rows_per_load;
+    m = (int64_t)(kWaveLoadsTarget / loads + 0.5);
+    if (m > kWaveMaxAutoBags) m = kWaveMaxAutoBags;
+    while (m > 1 && tables * ((B + m - 1) / m) < kWaveMinWaves) --m;
+  }
+  if (m > kWaveMaxBags) m = kWaveMaxBags;
+  return m < 1 ? 1 : m;
+}
+
 // Descriptor checks of emb_bag_forward that need no pointer: shape, mode, weights, out_ld.
 int precheck_uniform(const emb_bag_desc* desc, bool weighted, uint32_t* row_bytes,
                      int64_t* out_ld) {
@@ -343,8 +370,10 @@ bool make_stream(Launch* L, const emb_bag_desc* desc, bool weighted, int depth, 
   if (!fn) return false;
   L->fn = fn;
   L->kernel = EMB_KERNEL_STREAM;
+  L->hot = false;  // the short-bag kernel reads every row of a table with the table's policy
   L->depth = depth <= 4 || lpr < 8 ? 4 : 8;  // the depths that kernel is built with
   L->p.bags_per_group = (uint32_t)m;
+  L->p.bags_per_wave = 1;
   L->p.wpt = (uint32_t)((B + groups * m - 1) / (groups * m));
   return true;
 }
@@ -383,21 +412,27 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
   p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
   p.bags_per_group = 0;
+  const int groups = kWaveSize / lpr;
+  const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
+  p.bags_per_wave = (uint32_t)wave_bags_per_wave(avg_len, groups, T, B, slabs);
+  if (slabs == 1) p.wpt = (uint32_t)((B + p.bags_per_wave - 1) / p.bags_per_wave);
   wave.kernel = EMB_KERNEL_WAVE;
   wave.lpr = lpr;
   wave.depth = depth;
   wave.buf = buf;
   const int op = desc->mode == EMB_MAX ? kOpMax : (weighted ? kOpWeighted : kOpSum);
   if (op == kOpMax) wave.depth = depth <= 4 ? 4 : 8;
-  wave.fn = pick_kernel(lpr, desc->table_dtype, depth, op, buf);
+  // tables with a hot head: the kernel that reads hot and other rows with different cache
+  // policies, where it is built (buffer addressing, depth 4 or 8); otherwise the head is ignored
+  wave.hot = desc->hot_rows != nullptr && g_tuning.hot_split != 0 && buf &&
+             pick_kernel(lpr, desc->table_dtype, depth, op, buf, true) != nullptr;
+  wave.fn = pick_kernel(lpr, desc->table_dtype, depth, op, buf, wave.hot);
   if (!wave.fn) return EMB_ERR_BAD_TUNING;
 
   // Short bags: a lane group streams several consecutive bags (emb_bag_stream.hip).  Without
   // per-table lengths the host knows the call's average bag length, NL / (T * B), and nothing
   // else; with them each table is judged by its own.
-  const int groups = kWaveSize / lpr;
   const double threshold = kStreamBelowRowLoads * groups;
-  const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
   const bool can_stream = g_tuning.stream != 0 && slabs == 1 && buf && desc->mode != EMB_MAX;
   const std::vector<uint16_t> none;
   if (g_tuning.per_table_launch == 1 && T <= 65535) {
@@ -411,19 +446,24 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   }
   if (can_stream && g_tuning.stream == -1 && desc->table_avg_len && T <= 65535) {
     std::vector<uint16_t> short_ids, long_ids;
-    double short_sum = 0.0;
+    double short_sum = 0.0, long_sum = 0.0;
     for (int64_t t = 0; t < T; ++t) {
       if ((double)desc->table_avg_len[t] < threshold) {
         short_ids.push_back((uint16_t)t);
         short_sum += (double)desc->table_avg_len[t];
       } else {
         long_ids.push_back((uint16_t)t);
+        long_sum += (double)desc->table_avg_len[t];
       }
     }
     Launch stream = wave;
     if (!short_ids.empty() && !long_ids.empty() &&
         make_stream(&stream, desc, weighted, depth, short_sum / (double)short_ids.size(),
                     (int64_t)short_ids.size(), out_ld)) {
+      // the wave part's bags per wavefront follow its own tables
+      p.bags_per_wave = (uint32_t)wave_bags_per_wave(long_sum / (double)long_ids.size(), groups,
+                                                     (int64_t)long_ids.size(), B, slabs);
+      p.wpt = (uint32_t)((B + p.bags_per_wave - 1) / p.bags_per_wave);
       add_launches(wave, T, long_ids, none, launches);  // listed in the order a fused launch
       add_launches(stream, T, short_ids, none, launches);  // runs them: long bags first
       return EMB_OK;
@@ -493,7 +533,6 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
   p.out_ld = out_ld;
   p.max_rows = 0;
   p.B = (uint32_t)B;
-  p.wpt = (uint32_t)B;
   p.bags_per_group = 0;
   p.slabs = 1;
   p.row_bytes = max_row_bytes;
@@ -509,6 +548,12 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
 
   // which lanes-per-row classes (4, 8, 16, 32, 64) go to the stream kernel
   const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
+  {
+    int wide_lpr = 4;  // bags per wavefront: judged by the widest row (the fewest rows per load)
+    while ((uint32_t)wide_lpr * 16u < max_row_bytes) wide_lpr *= 2;
+    p.bags_per_wave = (uint32_t)wave_bags_per_wave(avg_len, kWaveSize / wide_lpr, T, B, 1);
+    p.wpt = (uint32_t)((B + p.bags_per_wave - 1) / p.bags_per_wave);
+  }
   // (judged by the call's average bag length, or table by table with desc->table_avg_len)
   const bool can_stream = g_tuning.stream != 0 && buf && desc->mode != EMB_MAX;
   const bool per_table = g_tuning.stream == -1 && desc->table_avg_len != nullptr;
@@ -574,6 +619,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
       L.depth = depth <= 4 || lpr < 8 ? 4 : 8;
       L.p.row_bytes = (uint32_t)lpr * 16u;
       L.p.bags_per_group = (uint32_t)m;
+      L.p.bags_per_wave = 1;
       L.p.wpt = (uint32_t)((B + groups * m - 1) / (groups * m));
     }
     add_launches(L, T, ids, u, launches);
@@ -601,13 +647,14 @@ int occupancy_cap_lds(const void* fn, uint32_t* lds) {
 // Apply the occupancy cap and launch what was planned.
 int launch(const Launch& L, const void* tables, const int64_t* table_offsets,
            const int64_t* indices, const int64_t* offsets, const float* weights,
-           const uint8_t* table_hints, const int64_t* out_offsets, float* out, void* stream) {
+           const uint8_t* table_hints, const int64_t* hot_rows, const int64_t* out_offsets,
+           float* out, void* stream) {
   uint32_t lds = 0;
   const int rc = occupancy_cap_lds(reinterpret_cast<const void*>(L.fn), &lds);
   if (rc != EMB_OK) return rc;
   hipLaunchKernelGGL(L.fn, dim3(L.blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
                      static_cast<const char*>(tables), table_offsets, indices, offsets, weights,
-                     table_hints, out_offsets, out, L.p, L.order);
+                     table_hints, L.hot ? hot_rows : nullptr, out_offsets, out, L.p, L.order);
   return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
 }
 
@@ -687,7 +734,8 @@ int launch_fused(const FusedLaunch& F, const void* tables, const int64_t* table_
   if (rc != EMB_OK) return rc;
   hipLaunchKernelGGL(F.fn, dim3(F.blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
                      static_cast<const char*>(tables), table_offsets, indices, offsets, weights,
-                     table_hints, out_offsets, out, F.f, F.order);
+                     table_hints, static_cast<const int64_t*>(nullptr), out_offsets, out, F.f,
+                     F.order);
   return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
 }
 
@@ -707,6 +755,8 @@ void report(const Launch& L, int32_t num_launches, emb_bag_plan* plan, uint16_t*
   plan->waves_per_piece = L.p.xcd_wpp;
   plan->blocks_per_piece = L.p.xcd_bpp;
   plan->tables = L.tables;
+  plan->bags_per_wave = L.kernel == EMB_KERNEL_WAVE ? (int32_t)L.p.bags_per_wave : 0;
+  plan->hot_split = L.hot ? 1 : 0;
   if (table_order)
     for (int64_t t = 0; t < L.tables && t < kMaxOrdered; ++t)
       table_order[t] = L.p.listed ? L.order.t[t] : (uint16_t)t;
@@ -745,7 +795,7 @@ int emb_bag_forward(const emb_bag_desc* desc, const void* tables, const int64_t*
                         desc->table_hints, nullptr, out, stream);
   for (const Launch& L : launches) {  // disjoint tables: the launches are independent
     rc = launch(L, tables, table_offsets, indices, offsets, per_sample_weights, desc->table_hints,
-                nullptr, out, stream);
+                desc->hot_rows, nullptr, out, stream);
     if (rc != EMB_OK) return rc;
   }
   return EMB_OK;
@@ -774,7 +824,7 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
                         desc->table_hints, out_offsets, out, stream);
   for (const Launch& L : launches) {  // disjoint tables: the launches are independent
     rc = launch(L, tables, table_byte_offsets, indices, offsets, per_sample_weights,
-                desc->table_hints, out_offsets, out, stream);
+                desc->table_hints, nullptr, out_offsets, out, stream);
     if (rc != EMB_OK) return rc;
   }
   return EMB_OK;
@@ -799,6 +849,7 @@ int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, int32_t whic
   if (plan_fused(launches, false, desc->table_dtype, has_weights != 0, &fused)) {
     plan->fused = 1;
     plan->fused_grid_blocks = fused.blocks;
+    plan->hot_split = 0;  // the fused kernel has no hot / cold split
   }
   return EMB_OK;
 }
@@ -902,6 +953,12 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
     if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
       return EMB_ERR_BAD_TUNING;
     g_tuning.xcd_pieces = value;
+  } else if (!strcmp(key, "bags_per_wave")) {
+    if (value < 0 || value > kWaveMaxBags) return EMB_ERR_BAD_TUNING;
+    g_tuning.bags_per_wave = value;
+  } else if (!strcmp(key, "hot_split")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    g_tuning.hot_split = value;
   } else {
     return EMB_ERR_BAD_TUNING;
   }
@@ -920,6 +977,8 @@ int emb_bag_get_tuning(const char* key, int64_t* value) {
   else if (!strcmp(key, "xcd_pieces")) *value = g_tuning.xcd_pieces;
   else if (!strcmp(key, "per_table_launch")) *value = g_tuning.per_table_launch;
   else if (!strcmp(key, "fuse")) *value = g_tuning.fuse;
+  else if (!strcmp(key, "bags_per_wave")) *value = g_tuning.bags_per_wave;
+  else if (!strcmp(key, "hot_split")) *value = g_tuning.hot_split;
   else return EMB_ERR_BAD_TUNING;
   return EMB_OK;
 }
@@ -940,6 +999,6 @@ const char* emb_bag_status_string(int status) {
   }
 }
 
-int emb_bag_version(void) { return 400; }
+int emb_bag_version(void) { return 500; }
 
 }  // extern "C"

@@ -13,20 +13,34 @@ namespace embbag {
 // wave body
 // ---------------------------------------------------------------------------------------------
 
-// One wavefront per (bag, column slab).  LPR = lanes per row (power of two, 4..64), or 0 for
-// tables of different widths: then table t is described by table_offsets[t] (its BYTE offset in
-// the arena) and out_offsets[t] (its first output column; its width is the difference to the next
-// entry), the lanes per row are chosen per wavefront, and rows are at most 1 KiB.
-template <int LPR, int ELEM, int DEPTH, int OP, bool BUF>
+// One wavefront per (bag, column slab), or per p.bags_per_wave consecutive bags of one table when
+// rows fit one slab.  LPR = lanes per row (power of two, 4..64), or 0 for tables of different
+// widths: then table t is described by table_offsets[t] (its BYTE offset in the arena) and
+// out_offsets[t] (its first output column; its width is the difference to the next entry), the
+// lanes per row are chosen per wavefront, and rows are at most 1 KiB.
+//
+// The per-bag chain bounds -> row ids -> rows (paper Sec. 3.1) is taken apart across the bags of
+// a wavefront: the bounds of all its bags arrive with one load (lane l holds bound l), and the
+// row ids of the next bag's first chunk are requested before the rows of the current bag, so
+// that they are there when the current bag has been stored (the index prefetch of Sec. 4.2,
+// which is always accurate because the ids are known ahead; here it runs across bags).
+//
+// HOT (buffer addressing only): hot_rows[t] leading rows of table t are its hot head; lookups
+// are regrouped per chunk and the two kinds read with different cache policies
+// (gather_hot_cold).  The hot head replaces the per-table hint: 0 rows = a streaming table.
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, bool HOT = false>
 __device__ __forceinline__ void wave_body(
     const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
     const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
-    const int64_t* __restrict__ out_offsets, float* __restrict__ out, const KParams& p,
-    const TableOrder& order, uint32_t order_base, uint32_t block) {
+    const int64_t* __restrict__ hot_rows, const int64_t* __restrict__ out_offsets,
+    float* __restrict__ out, const KParams& p, const TableOrder& order, uint32_t order_base,
+    uint32_t block) {
+  static_assert(!HOT || BUF, "the hot / cold split is built for buffer addressing");
   constexpr bool MIXED = LPR == 0;
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;  // 2-byte elements
   constexpr bool QUANT = IsQuant<ELEM>::value;                // 1-byte codes + scale, bias
+  constexpr bool WEIGHTED = OP == kOpWeighted;
   constexpr int NACC = AccCount<ELEM, OP>::value;             // fp32 accumulators per lane
 
   const int lane = threadIdx.x & (kWaveSize - 1);
@@ -34,18 +48,22 @@ __device__ __forceinline__ void wave_body(
   uint32_t tpos, w_in_table;
   if (!decode_work(p, block, wave, &tpos, &w_in_table)) return;
   const uint32_t t = p.listed ? order.t[order_base + tpos] : tpos;
-  uint32_t b = w_in_table, slab = 0;
+  // the wavefront's bags b0 .. b0 + nb - 1 (one bag, one slab of it, when rows span slabs)
+  uint32_t b0 = w_in_table * p.bags_per_wave, slab = 0, nb = p.bags_per_wave;
   if (p.slabs > 1) {
-    b = w_in_table / p.slabs;
-    slab = w_in_table - b * p.slabs;
+    b0 = w_in_table / p.slabs;
+    slab = w_in_table - b0 * p.slabs;
+    nb = 1;
   }
-  const uint32_t bag = t * p.B + b;
+  if (nb > p.B - b0) nb = p.B - b0;  // b0 < B: the grid holds ceil(B / bags_per_wave) per table
 
-  // bag bounds, clamped so that no index read can leave [0, NL)
-  int64_t s = uniform64(offsets[bag]);
-  int64_t e = uniform64(offsets[bag + 1]);
-  s = s < 0 ? 0 : (s > p.num_lookups ? p.num_lookups : s);
-  e = e < s ? s : (e > p.num_lookups ? p.num_lookups : e);
+  // bag bounds: lane l holds bound l of the wavefront's bags, clamped to [0, NL] so that no
+  // index read can leave [0, NL); a decreasing pair makes an empty bag
+  int64_t o = 0;
+  if ((uint32_t)lane <= nb) {
+    o = offsets[(uint64_t)t * p.B + b0 + (uint32_t)lane];
+    o = o < 0 ? 0 : (o > p.num_lookups ? p.num_lookups : o);
+  }
 
   // per-table geometry
   uint32_t D_t = p.D, row_bytes = p.row_bytes;
@@ -79,6 +97,7 @@ __device__ __forceinline__ void wave_body(
     tbase = tables + row0 * (int64_t)p.row_bytes;
   }
   const int lpr_log2 = __builtin_ctz((unsigned)lpr);
+  const int gl = 6 - lpr_log2;  // log2 of the rows per load instruction
 
   const int g = lane >> lpr_log2;
   const uint32_t col = slab * kSlabBytes + (uint32_t)(lane & (lpr - 1)) * 16u;
@@ -87,23 +106,79 @@ __device__ __forceinline__ void wave_body(
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<char*>(tbase), 0, BUF ? (uint32_t)((uint64_t)R * row_bytes) : 0u, kBufWord3);
 
-  float acc[NACC];
-  init_acc<ELEM, OP>(acc);
   // quantised rows: the lane of this lane's group whose segment ends with the row's scale and bias
   const int meta_lane = (lane & ~(lpr - 1)) + (int)(D_t >> 4);
 
-  const bool streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
-  if (streaming)
-    gather_bag<LPR, ELEM, DEPTH, OP, BUF, true>(acc, indices, weights, s, e, R, row_bytes,
-                                                     tbase, rsrc, lane, g, col, lane_ok,
-                                                     meta_lane, 6 - lpr_log2);
+  bool streaming = false;
+  int64_t hot = 0;
+  if constexpr (HOT)
+    hot = uniform64(hot_rows[t]);
   else
-    gather_bag<LPR, ELEM, DEPTH, OP, BUF, false>(acc, indices, weights, s, e, R, row_bytes,
-                                                      tbase, rsrc, lane, g, col, lane_ok,
-                                                      meta_lane, 6 - lpr_log2);
+    streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
 
-  finish_bag<LPR, ELEM, OP>(acc, lpr, lane, lane_ok, col, D_t, e - s, p.mean != 0, out, p.out_ld, b,
-                        out_col);
+  // the first bag's first chunk; from then on a bag's first chunk is requested one bag ahead
+  int64_t s = uniform64(o), e = uniform64(shfl64(o, 1));
+  e = e < s ? s : e;
+  int n = e - s < kWaveSize ? (int)(e - s) : kWaveSize;
+  int64_t idx;
+  float w;
+  load_chunk<WEIGHTED>(indices, weights, s, n, lane, &idx, &w);
+  ChunkLookups<BUF> q = chunk_offsets<BUF>(idx, w, R, row_bytes);
+  uint64_t hot_mask = HOT ? __builtin_amdgcn_ballot_w64((uint64_t)idx < (uint64_t)hot &&
+                                                        q.voff != kBufSentinel) : 0ull;
+
+  for (uint32_t i = 0; i < nb; ++i) {
+    // the next bag's first chunk is on its way while this bag's rows are gathered (bag i spans
+    // [bound i, max(bound i + 1, bound i)): a decreasing pair makes an empty bag)
+    int64_t s2 = 0, e2 = 0;
+    if (i + 1 < nb) {
+      s2 = uniform64(shfl64(o, (int)i + 1));
+      e2 = uniform64(shfl64(o, (int)i + 2));
+      e2 = e2 < s2 ? s2 : e2;
+    }
+    const int n2 = e2 - s2 < kWaveSize ? (int)(e2 - s2) : kWaveSize;
+    int64_t idx2;
+    float w2;
+    load_chunk<WEIGHTED>(indices, weights, s2, n2, lane, &idx2, &w2);
+
+    float acc[NACC];
+    init_acc<ELEM, OP>(acc);
+    for (int64_t c = s; c < e; c += kWaveSize) {
+      if (c != s) {  // chunks after the first are requested here
+        const int64_t left = e - c;
+        n = left < kWaveSize ? (int)left : kWaveSize;
+        load_chunk<WEIGHTED>(indices, weights, c, n, lane, &idx, &w);
+        q = chunk_offsets<BUF>(idx, w, R, row_bytes);
+        if constexpr (HOT)
+          hot_mask = __builtin_amdgcn_ballot_w64((uint64_t)idx < (uint64_t)hot &&
+                                                 q.voff != kBufSentinel);
+      }
+      if constexpr (HOT) {
+        gather_hot_cold<LPR, ELEM, DEPTH, OP>(acc, n, hot_mask, q, tbase, rsrc, lane, g, col,
+                                              lane_ok, meta_lane, gl);
+      } else if (streaming) {
+        gather_slots<LPR, ELEM, DEPTH, OP, BUF, true>(acc, 0, n, q, tbase, rsrc, g, col, lane_ok,
+                                                      meta_lane, gl);
+      } else {
+        gather_slots<LPR, ELEM, DEPTH, OP, BUF, false>(acc, 0, n, q, tbase, rsrc, g, col, lane_ok,
+                                                       meta_lane, gl);
+      }
+    }
+    // the next bag's row offsets before this bag's stores: its ids arrived ahead of the rows
+    // just consumed, so nothing is waited for here, and the stores are not waited for there
+    const ChunkLookups<BUF> q2 = chunk_offsets<BUF>(idx2, w2, R, row_bytes);
+    uint64_t hot_mask2 = 0ull;
+    if constexpr (HOT)
+      hot_mask2 = __builtin_amdgcn_ballot_w64((uint64_t)idx2 < (uint64_t)hot &&
+                                              q2.voff != kBufSentinel);
+    finish_bag<LPR, ELEM, OP>(acc, lpr, lane, lane_ok, col, D_t, e - s, p.mean != 0, out,
+                              p.out_ld, b0 + i, out_col);
+    q = q2;
+    hot_mask = hot_mask2;
+    s = s2;
+    e = e2;
+    n = n2;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -229,8 +304,9 @@ __device__ __forceinline__ void stream_body(
     const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
     const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
-    const int64_t* __restrict__ out_offsets, float* __restrict__ out, const KParams& p,
-    const TableOrder& order, uint32_t order_base, uint32_t block) {
+    const int64_t* __restrict__ /*hot_rows*/, const int64_t* __restrict__ out_offsets,
+    float* __restrict__ out, const KParams& p, const TableOrder& order, uint32_t order_base,
+    uint32_t block) {
   constexpr int G = kWaveSize / LPR;
   constexpr int GL = __builtin_ctz((unsigned)G);
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;

@@ -42,6 +42,7 @@ struct KParams {
   uint32_t xcd_units;    // positions * pieces: units at or beyond this have no work
   uint32_t listed;       // 1 = position q of the launch holds table TableOrder::t[q], 0 = table q
   uint32_t bags_per_group;  // stream kernel: consecutive bags owned by one lane group
+  uint32_t bags_per_wave;   // wave kernel: consecutive bags owned by one wavefront (1 if slabs > 1)
 };
 
 // A launch over tables of different widths may cover a subset of the tables (one lanes-per-row
@@ -55,10 +56,11 @@ struct TableOrder {
 };
 
 // Every forward kernel takes the same arguments: tables, table_offsets, indices, offsets,
-// weights, table_hints, out_offsets (different widths only), out, parameters, table order.
+// weights, table_hints, hot_rows (kernels with the hot / cold split only), out_offsets
+// (different widths only), out, parameters, table order.
 using KernelFn = void (*)(const char*, const int64_t*, const int64_t*, const int64_t*,
-                          const float*, const uint8_t*, const int64_t*, float*, KParams,
-                          TableOrder);
+                          const float*, const uint8_t*, const int64_t*, const int64_t*, float*,
+                          KParams, TableOrder);
 
 // A fused launch runs several bodies over consecutive ranges of its workgroups.  Tables of
 // different widths: segment 0 is the wave body, segments 1 .. 5 the stream body with 4, 8, 16,
@@ -72,8 +74,8 @@ struct FusedParams {
   KParams seg[kFusedSegments];
 };
 using FusedFn = void (*)(const char*, const int64_t*, const int64_t*, const int64_t*,
-                         const float*, const uint8_t*, const int64_t*, float*, FusedParams,
-                         TableOrder);
+                         const float*, const uint8_t*, const int64_t*, const int64_t*, float*,
+                         FusedParams, TableOrder);
 // emb_bag_fused.hip, one translation unit per element type; depth 4 or 8
 #define EMB_DECLARE_FUSED(n) \
   __attribute__((visibility("hidden"))) FusedFn pick_fused_kernel_elem##n(int depth, bool weighted);
@@ -105,8 +107,8 @@ EMB_DECLARE_FUSED_UNIFORM(64)
 #define EMB_PASTE_(a, b) a##b
 #define EMB_PASTE(a, b) EMB_PASTE_(a, b)
 #define EMB_DECLARE_PICKERS(n)                                                                  \
-  __attribute__((visibility("hidden"))) KernelFn pick_wave_kernel_lpr##n(int elem, int depth,   \
-                                                                         int op, bool buf);     \
+  __attribute__((visibility("hidden"))) KernelFn pick_wave_kernel_lpr##n(                       \
+      int elem, int depth, int op, bool buf, bool hot);                                         \
   __attribute__((visibility("hidden"))) KernelFn pick_stream_kernel_lpr##n(                     \
       int elem, int depth, bool weighted, bool mixed);
 EMB_DECLARE_PICKERS(0)  // (there is no stream kernel for class 0; the declaration is unused)
@@ -254,10 +256,139 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int met
   }
 }
 
-// The gather of one bag (one column slab of it): walk the bag's lookups in chunks of 64 and add
-// the rows into acc.  LPR is the number of lanes per row (0: decided per table at run time, then
-// 2^glog2 rows share a wave load).  NT selects the non-temporal cache policy for the row loads (tables whose
-// rows are not re-used within a batch), the default policy otherwise.
+// What lane i holds for lookup i of a chunk of up to 64 lookups: where the row starts inside its
+// table (a 32-bit byte offset for buffer addressing, kBufSentinel = no row; or a 64-bit byte
+// offset, -1 = no row) and the lookup's weight.
+template <bool BUF>
+struct ChunkLookups {
+  uint32_t voff;
+  int64_t roff;
+  float w;
+};
+
+// Request lookup `lane` of the chunk that starts at position c of `indices` (n lookups, n <= 64):
+// one coalesced non-temporal load of the row ids (and one of the weights).
+template <bool WEIGHTED>
+__device__ __forceinline__ void load_chunk(const int64_t* __restrict__ indices,
+                                           const float* __restrict__ weights, int64_t c, int n,
+                                           int lane, int64_t* idx, float* w) {
+  *idx = -1;
+  *w = 0.0f;
+  if (lane < n) {
+    *idx = __builtin_nontemporal_load(indices + c + lane);
+    if constexpr (WEIGHTED) *w = __builtin_nontemporal_load(weights + c + lane);
+  }
+}
+
+// Row id -> byte offset of the row, once per lookup.  A row id outside [0, R) names no row.
+template <bool BUF>
+__device__ __forceinline__ ChunkLookups<BUF> chunk_offsets(int64_t idx, float w, int64_t R,
+                                                           uint32_t row_bytes) {
+  ChunkLookups<BUF> q;
+  const bool idx_ok = (uint64_t)idx < (uint64_t)R;
+  q.voff = kBufSentinel;
+  q.roff = -1;
+  q.w = w;
+  if constexpr (BUF) {
+    if (idx_ok) q.voff = (uint32_t)idx * row_bytes;
+  } else {
+    if (idx_ok) q.roff = idx * (int64_t)row_bytes;
+  }
+  return q;
+}
+
+// Gather the lookups that sit in slots [j_lo, j_hi) of a chunk (slot = lane that holds the
+// lookup) and add their rows into acc.  LPR is the number of lanes per row (0: decided per table
+// at run time); 2^gl rows share one load instruction, group g of the wavefront taking slot
+// (step << gl) + g; DEPTH load instructions are issued back to back before the first is
+// consumed.  NT selects the non-temporal cache policy for the row loads (rows that are not
+// re-used within a batch), the default policy otherwise.  A slot outside the range, a lane
+// beyond the row's end and a lookup without a row fetch nothing: their offset fails the
+// buffer's range check (zeros, no memory traffic), or the load is skipped (64-bit addressing).
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, bool NT>
+__device__ __forceinline__ void gather_slots(float* acc, int j_lo, int j_hi,
+                                             const ChunkLookups<BUF>& q, const char* tbase,
+                                             __amdgpu_buffer_rsrc_t rsrc, int g, uint32_t col,
+                                             bool lane_ok, int meta_lane, int gl) {
+  constexpr bool WEIGHTED = OP == kOpWeighted;
+  constexpr int kAux = NT ? 2 : 0;  // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
+  const int k_lo = j_lo >> gl;
+  const int k_hi = (j_hi + (1 << gl) - 1) >> gl;
+  for (int k0 = k_lo; k0 < k_hi; k0 += DEPTH) {
+    u32x4 r[DEPTH];
+    float wj[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const int j = ((k0 + d) << gl) + g;  // slot served by this lane's group in this step
+      const bool in = j >= j_lo && j < j_hi;
+      const bool take = in && lane_ok;
+      bool valid;  // this lane fetches a segment of a row that exists
+      if constexpr (BUF) {
+        uint32_t vo = (uint32_t)__shfl((int)q.voff, j & (kWaveSize - 1));
+        vo = take ? vo : kBufSentinel;
+        valid = vo != kBufSentinel;
+        r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
+      } else {
+        const int64_t ro = shfl64(q.roff, j & (kWaveSize - 1));
+        u32x4 v = {0u, 0u, 0u, 0u};
+        valid = take && ro >= 0;
+        if (valid) {
+          const u32x4* src = reinterpret_cast<const u32x4*>(tbase + ro + col);
+          v = NT ? __builtin_nontemporal_load(src) : *src;
+        }
+        r[d] = v;
+      }
+      if constexpr (WEIGHTED) {
+        const float ws = __shfl(q.w, j & (kWaveSize - 1));
+        wj[d] = in ? ws : 0.0f;
+      } else if constexpr (OP == kOpMax) {
+        wj[d] = valid ? 1.0f : 0.0f;
+      } else {
+        wj[d] = 1.0f;
+      }
+    }
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) accumulate<ELEM, OP>(acc, r[d], wj[d], meta_lane);
+  }
+}
+
+// A chunk whose table has a hot head (rows [0, hot) of the table are the frequently looked-up
+// ones, the outcome of the offline profiling of paper Sec. 4.3): the lookups are regrouped, hot
+// ones to the low slots and the others to the high slots, each kind keeping its order, and the
+// two kinds are gathered one after the other - the hot rows with the default cache policy, so
+// that they stay in L2, the others non-temporally, so that they do not push hot rows out.
+// `hot_mask` has bit i set if lookup i names a hot row, `n` is the number of lookups.
+template <int LPR, int ELEM, int DEPTH, int OP>
+__device__ __forceinline__ void gather_hot_cold(float* acc, int n, uint64_t hot_mask,
+                                                const ChunkLookups<true>& q, const char* tbase,
+                                                __amdgpu_buffer_rsrc_t rsrc, int lane, int g,
+                                                uint32_t col, bool lane_ok, int meta_lane,
+                                                int gl) {
+  const uint64_t present = n >= kWaveSize ? ~0ull : ((1ull << n) - 1ull);
+  const uint64_t cold_mask = present & ~hot_mask;
+  const uint64_t below = (1ull << lane) - 1ull;
+  const int nh = __builtin_popcountll(hot_mask), nc = __builtin_popcountll(cold_mask);
+  const bool is_hot = (hot_mask >> lane) & 1ull, is_cold = (cold_mask >> lane) & 1ull;
+  // a bijection of the 64 slots: hot lookups to [0, nh), lanes without a lookup to the middle,
+  // other lookups to [64 - nc, 64)
+  const int dest = is_hot ? __builtin_popcountll(hot_mask & below)
+                          : (is_cold ? kWaveSize - nc + __builtin_popcountll(cold_mask & below)
+                                     : nh + __builtin_popcountll(~present & below));
+  ChunkLookups<true> s;
+  s.voff = (uint32_t)__builtin_amdgcn_ds_permute(dest << 2, (int)q.voff);
+  s.roff = -1;
+  s.w = q.w;
+  if constexpr (OP == kOpWeighted)
+    s.w = __builtin_bit_cast(float, __builtin_amdgcn_ds_permute(
+                                        dest << 2, __builtin_bit_cast(int, q.w)));
+  gather_slots<LPR, ELEM, DEPTH, OP, true, false>(acc, 0, nh, s, tbase, rsrc, g, col, lane_ok,
+                                                  meta_lane, gl);
+  gather_slots<LPR, ELEM, DEPTH, OP, true, true>(acc, kWaveSize - nc, kWaveSize, s, tbase, rsrc,
+                                                 g, col, lane_ok, meta_lane, gl);
+}
+
+// The gather of one bag (one column slab of it) by a whole wavefront: walk the bag's lookups
+// [s, e) in chunks of 64 and add the rows into acc.
 template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, bool NT>
 __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict__ indices,
                                            const float* __restrict__ weights, int64_t s,
@@ -265,66 +396,18 @@ __device__ __forceinline__ void gather_bag(float* acc, const int64_t* __restrict
                                            const char* tbase, __amdgpu_buffer_rsrc_t rsrc,
                                            int lane, int g, uint32_t col, bool lane_ok,
                                            int meta_lane, int glog2) {
-  constexpr bool WEIGHTED = OP == kOpWeighted;
   // log2 of the rows per wave load: a constant for a fixed LPR, a wave-uniform value for LPR == 0
   const int gl = LPR ? __builtin_ctz((unsigned)(kWaveSize / (LPR ? LPR : 1))) : glog2;
-  constexpr int kAux = NT ? 2 : 0;  // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
   for (int64_t c = s; c < e; c += kWaveSize) {
     const int64_t left = e - c;
     const int n = left < kWaveSize ? (int)left : kWaveSize;  // lookups in this chunk (uniform)
-    int64_t idx = -1;
-    float w = 0.0f;
-    if (lane < n) {
-      idx = __builtin_nontemporal_load(indices + c + lane);
-      if constexpr (WEIGHTED) w = __builtin_nontemporal_load(weights + c + lane);
-    }
-    const bool idx_ok = (uint64_t)idx < (uint64_t)R;
-    uint32_t voff = kBufSentinel;  // BUF: 32-bit byte offset of the row inside the table
-    int64_t roff = -1;             // !BUF: 64-bit byte offset, -1 = skip
-    if constexpr (BUF) {
-      if (idx_ok) voff = (uint32_t)idx * row_bytes;
-    } else {
-      if (idx_ok) roff = idx * (int64_t)row_bytes;
-    }
-
-    const int steps = (n + (1 << gl) - 1) >> gl;
-    for (int k0 = 0; k0 < steps; k0 += DEPTH) {
-      u32x4 r[DEPTH];
-      float wj[DEPTH];
-#pragma unroll
-      for (int d = 0; d < DEPTH; ++d) {
-        const int j = ((k0 + d) << gl) + g;  // lookup of this chunk served by this lane's group
-        const bool take = (j < n) && lane_ok;
-        bool valid;  // this lane fetches a segment of a row that exists
-        if constexpr (BUF) {
-          uint32_t vo = (uint32_t)__shfl((int)voff, j & (kWaveSize - 1));
-          vo = take ? vo : kBufSentinel;
-          valid = vo != kBufSentinel;
-          r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
-        } else {
-          const int64_t ro = shfl64(roff, j & (kWaveSize - 1));
-          u32x4 v = {0u, 0u, 0u, 0u};
-          valid = take && ro >= 0;
-          if (valid) {
-            const u32x4* src = reinterpret_cast<const u32x4*>(tbase + ro + col);
-            v = NT ? __builtin_nontemporal_load(src) : *src;
-          }
-          r[d] = v;
-        }
-        if constexpr (WEIGHTED) {
-          const float ws = __shfl(w, j & (kWaveSize - 1));
-          wj[d] = (j < n) ? ws : 0.0f;
-        } else if constexpr (OP == kOpMax) {
-          wj[d] = valid ? 1.0f : 0.0f;
-        } else {
-          wj[d] = 1.0f;
-        }
-      }
-#pragma unroll
-      for (int d = 0; d < DEPTH; ++d) accumulate<ELEM, OP>(acc, r[d], wj[d], meta_lane);
-    }
+    int64_t idx;
+    float w;
+    load_chunk<OP == kOpWeighted>(indices, weights, c, n, lane, &idx, &w);
+    const ChunkLookups<BUF> q = chunk_offsets<BUF>(idx, w, R, row_bytes);
+    gather_slots<LPR, ELEM, DEPTH, OP, BUF, NT>(acc, 0, n, q, tbase, rsrc, g, col, lane_ok,
+                                                meta_lane, gl);
   }
-
 }
 
 // Which piece of work this wavefront owns: position `tpos` in the launch's table list and

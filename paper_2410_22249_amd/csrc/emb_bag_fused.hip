@@ -36,11 +36,12 @@ __global__ void __launch_bounds__(kBlock)
 emb_bag_fused_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                      const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
                      const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
+                     const int64_t* __restrict__ hot_rows,
                      const int64_t* __restrict__ out_offsets, float* __restrict__ out,
                      FusedParams f, TableOrder order) {
   constexpr int OP = WEIGHTED ? kOpWeighted : kOpSum;
   const uint32_t blk = blockIdx.x;
-#define EMB_ARGS tables, table_offsets, indices, offsets, weights, table_hints, out_offsets, out
+#define EMB_ARGS tables, table_offsets, indices, offsets, weights, table_hints, hot_rows, out_offsets, out
   if (blk < f.end_block[0])
     wave_body<0, ELEM, DEPTH, OP, true>(EMB_ARGS, f.seg[0], order, f.order_base[0], blk);
   else if (blk < f.end_block[1])

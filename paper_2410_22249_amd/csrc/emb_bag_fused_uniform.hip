@@ -31,6 +31,7 @@ emb_bag_fused_uniform_kernel(const char* __restrict__ tables,
                              const int64_t* __restrict__ offsets,
                              const float* __restrict__ weights,
                              const uint8_t* __restrict__ table_hints,
+                             const int64_t* __restrict__ hot_rows,
                              const int64_t* __restrict__ out_offsets, float* __restrict__ out,
                              FusedParams f, TableOrder order) {
   constexpr int OP = WEIGHTED ? kOpWeighted : kOpSum;
@@ -38,11 +39,11 @@ emb_bag_fused_uniform_kernel(const char* __restrict__ tables,
   const uint32_t blk = blockIdx.x;
   if (blk < f.end_block[0])
     wave_body<LPR, ELEM, DEPTH, OP, true>(tables, table_offsets, indices, offsets, weights,
-                                          table_hints, out_offsets, out, f.seg[0], order,
+                                          table_hints, hot_rows, out_offsets, out, f.seg[0], order,
                                           f.order_base[0], blk);
   else if (blk < f.end_block[1])
     stream_body<LPR, ELEM, STREAM_DEPTH, WEIGHTED, false>(tables, table_offsets, indices, offsets,
-                                                          weights, table_hints, out_offsets, out,
+                                                          weights, table_hints, hot_rows, out_offsets, out,
                                                           f.seg[1], order, f.order_base[1],
                                                           blk - f.end_block[0]);
 }

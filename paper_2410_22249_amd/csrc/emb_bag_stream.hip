@@ -45,10 +45,11 @@ __global__ void __launch_bounds__(kBlock)
 emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                       const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
                       const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
+                      const int64_t* __restrict__ hot_rows,
                       const int64_t* __restrict__ out_offsets, float* __restrict__ out,
                       KParams p, TableOrder order) {
   stream_body<LPR, ELEM, DEPTH, WEIGHTED, MIXED>(tables, table_offsets, indices, offsets, weights,
-                                                 table_hints, out_offsets, out, p, order, 0u,
+                                                 table_hints, hot_rows, out_offsets, out, p, order, 0u,
                                                  blockIdx.x);
 }
 

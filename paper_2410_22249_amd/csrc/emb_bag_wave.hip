@@ -52,44 +52,56 @@ namespace {
 using namespace embbag;
 
 // The kernel proper is embbag::wave_body (emb_bag_bodies.h), shared with the fused launch.
-template <int LPR, int ELEM, int DEPTH, int OP, bool BUF>
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, bool HOT>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
                     const float* __restrict__ weights, const uint8_t* __restrict__ table_hints,
+                    const int64_t* __restrict__ hot_rows,
                     const int64_t* __restrict__ out_offsets, float* __restrict__ out, KParams p,
                     TableOrder order) {
-  wave_body<LPR, ELEM, DEPTH, OP, BUF>(tables, table_offsets, indices, offsets, weights,
-                                       table_hints, out_offsets, out, p, order, 0u, blockIdx.x);
+  wave_body<LPR, ELEM, DEPTH, OP, BUF, HOT>(tables, table_offsets, indices, offsets, weights,
+                                            table_hints, hot_rows, out_offsets, out, p, order, 0u,
+                                            blockIdx.x);
 }
 
-template <int LPR, int ELEM, int DEPTH>
-KernelFn pick_op(int op, bool buf) {
-  if (op == kOpWeighted)
-    return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpWeighted, true>
-               : emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpWeighted, false>;
-  if (op == kOpMax) {
-    if constexpr (DEPTH == 4 || DEPTH == 8)  // max pooling: two depths are enough
-      return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpMax, true>
-                 : emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpMax, false>;
+// buffer or 64-bit addressing; the hot / cold split (tables with a hot head) exists for buffer
+// addressing, tables of one width and depths 4 and 8
+template <int LPR, int ELEM, int DEPTH, int OP>
+KernelFn pick_addr(bool buf, bool hot) {
+  if (hot) {
+    if constexpr (LPR != 0 && (DEPTH == 4 || DEPTH == 8))
+      return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, true> : nullptr;
     else
       return nullptr;
   }
-  return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpSum, true>
-             : emb_bag_wave_kernel<LPR, ELEM, DEPTH, kOpSum, false>;
+  return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, false>
+             : emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, false, false>;
+}
+
+template <int LPR, int ELEM, int DEPTH>
+KernelFn pick_op(int op, bool buf, bool hot) {
+  if (op == kOpWeighted) return pick_addr<LPR, ELEM, DEPTH, kOpWeighted>(buf, hot);
+  if (op == kOpMax) {
+    if constexpr (DEPTH == 4 || DEPTH == 8)  // max pooling: two depths are enough
+      return pick_addr<LPR, ELEM, DEPTH, kOpMax>(buf, hot);
+    else
+      return nullptr;
+  }
+  return pick_addr<LPR, ELEM, DEPTH, kOpSum>(buf, hot);
 }
 
 template <int LPR, int ELEM>
-KernelFn pick_depth(int depth, int op, bool buf) {
+KernelFn pick_depth(int depth, int op, bool buf, bool hot) {
   if (LPR == 0 || op == kOpMax)  // tables of different widths, max pooling: depth 4 or 8
-    return depth <= 4 ? pick_op<LPR, ELEM, 4>(op, buf) : pick_op<LPR, ELEM, 8>(op, buf);
+    return depth <= 4 ? pick_op<LPR, ELEM, 4>(op, buf, hot) : pick_op<LPR, ELEM, 8>(op, buf, hot);
   if constexpr (LPR != 0) {
     switch (depth) {
-      case 1: return pick_op<LPR, ELEM, 1>(op, buf);
-      case 2: return pick_op<LPR, ELEM, 2>(op, buf);
-      case 4: return pick_op<LPR, ELEM, 4>(op, buf);
-      case 8: return pick_op<LPR, ELEM, 8>(op, buf);
-      case 16: return pick_op<LPR, ELEM, 16>(op, buf);
+      case 1: return pick_op<LPR, ELEM, 1>(op, buf, hot);
+      case 2: return pick_op<LPR, ELEM, 2>(op, buf, hot);
+      case 4: return pick_op<LPR, ELEM, 4>(op, buf, hot);
+      case 8: return pick_op<LPR, ELEM, 8>(op, buf, hot);
+      case 16: return pick_op<LPR, ELEM, 16>(op, buf, hot);
       default: return nullptr;
     }
   }
@@ -97,13 +109,13 @@ KernelFn pick_depth(int depth, int op, bool buf) {
 }
 
 template <int LPR>
-KernelFn pick_dtype(int elem, int depth, int op, bool buf) {
+KernelFn pick_dtype(int elem, int depth, int op, bool buf, bool hot) {
   switch (elem) {
-    case EMB_F32: return pick_depth<LPR, EMB_F32>(depth, op, buf);
-    case EMB_F16: return pick_depth<LPR, EMB_F16>(depth, op, buf);
-    case EMB_BF16: return pick_depth<LPR, EMB_BF16>(depth, op, buf);
-    case EMB_U8ROW: return pick_depth<LPR, EMB_U8ROW>(depth, op, buf);
-    case EMB_FP8ROW: return pick_depth<LPR, EMB_FP8ROW>(depth, op, buf);
+    case EMB_F32: return pick_depth<LPR, EMB_F32>(depth, op, buf, hot);
+    case EMB_F16: return pick_depth<LPR, EMB_F16>(depth, op, buf, hot);
+    case EMB_BF16: return pick_depth<LPR, EMB_BF16>(depth, op, buf, hot);
+    case EMB_U8ROW: return pick_depth<LPR, EMB_U8ROW>(depth, op, buf, hot);
+    case EMB_FP8ROW: return pick_depth<LPR, EMB_FP8ROW>(depth, op, buf, hot);
     default: return nullptr;
   }
 }
@@ -112,8 +124,10 @@ KernelFn pick_dtype(int elem, int depth, int op, bool buf) {
 
 namespace embbag {
 
-KernelFn EMB_PASTE(pick_wave_kernel_lpr, EMB_LPR)(int elem, int depth, int op, bool buf) {
-  return pick_dtype<EMB_LPR>(elem, depth, op, buf);
+// nullptr if there is no such instantiation
+KernelFn EMB_PASTE(pick_wave_kernel_lpr, EMB_LPR)(int elem, int depth, int op, bool buf,
+                                                  bool hot) {
+  return pick_dtype<EMB_LPR>(elem, depth, op, buf, hot);
 }
 
 }  // namespace embbag

@@ -224,7 +224,7 @@ def test_the_largest_grid_a_launch_can_hold(oracle):
     desc = emb.make_desc(T, B, D, emb.EMB_F32, emb.EMB_SUM, NL, 0, R)
     out = torch.full((B, T * D), float("nan"), dtype=torch.float32, device=DEV)
     print(f"\n[fullsize] largest grid: {nb} bags, {NL} lookups", flush=True)
-    with tuning(stream=0):
+    with tuning(stream=0, bags_per_wave=1):
         plan = emb.emb_bag_plan_forward(desc)
         assert plan.kernel == emb.EMB_KERNEL_WAVE and plan.grid_blocks == nb // 4 == (1 << 24) - 16
         assert plan.xcd_pieces == 0
@@ -255,7 +255,7 @@ def test_the_largest_grid_a_launch_can_hold(oracle):
     assert torch.equal(out, out2)
     # one bag more per table is refused before anything is launched
     big = emb.make_desc(T, B + 1, D, emb.EMB_F32, emb.EMB_SUM, NL, 0, R)
-    with tuning(stream=0):
+    with tuning(stream=0, bags_per_wave=1):
         with pytest.raises(emb.EmbBagError) as ex:
             emb.emb_bag_forward(big, arena, to_dev(toff), idx, off, None, out)
     assert ex.value.status == -7

@@ -546,3 +546,28 @@ def test_concurrent_calls_on_two_streams(oracle):
         assert_close_to_oracle(outs[k].cpu().numpy(), ref, bound, False, f"stream {k}")
         alone = forward(arena, wl.table_offsets(), b.indices, b.offsets, wl.B).cpu().numpy()
         assert np.array_equal(outs[k].cpu().numpy(), alone)
+
+
+@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
+                                  "small_u8_d120"])
+@pytest.mark.parametrize("mode", ["sum", "mean", "max"])
+def test_bags_per_wave_gives_the_same_bits(oracle, name, mode):
+    """A wavefront that takes several consecutive bags (bounds with one load, the next bag's row
+    ids requested ahead) adds every bag exactly as a wavefront with one bag does."""
+    wl, batch, arena = _problem(name)
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, mode)
+    dev = upload_arena(arena)
+    weights = None
+    for addressing in (0, 1):
+        base = None
+        for bpw in (1, 2, 3, 5, 8, 32):
+            with tuning(bags_per_wave=bpw, addressing=addressing, stream=0):
+                got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B, mode,
+                              weights=weights).cpu().numpy()
+            if base is None:
+                base = got
+                if mode == "max" and wl.dtype not in gen.QUANTISED:
+                    assert np.array_equal(got.astype(np.float64), ref)
+                else:
+                    assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"{name}/{mode}")
+            assert np.array_equal(got.view(np.uint32), base.view(np.uint32)), (bpw, addressing)

@@ -213,7 +213,8 @@ def test_short_bags_split_a_mixed_call_into_one_launch_per_row_class(seed, L):
             assert 1 <= plan.bags_per_group <= plan.lanes_per_row - 1
             assert plan.waves_per_table == -(-B // (g * plan.bags_per_group))
         else:
-            assert plan.lanes_per_row == 0 and plan.waves_per_table == B
+            assert plan.lanes_per_row == 0 and plan.bags_per_wave >= 1
+            assert plan.waves_per_table == -(-B // plan.bags_per_wave)
             if first.num_launches > 1:
                 assert not np.any(want_stream[order])
         table, wave, _ = _simulate(plan, plan.tables, order)
@@ -333,7 +334,7 @@ def test_a_launch_holds_at_most_2_pow_24_minus_1_workgroups():
             return _plan(T, B, D, L, **kw)
         except emb.EmbBagError as ex:
             return ex.status
-    with tuning(stream=0):
+    with tuning(stream=0, bags_per_wave=1):                   # a wavefront per bag
         ok = status(64, limit * 4 // 64)                      # 67,108,800 wavefronts
         assert ok.grid_blocks <= limit and ok.wavefronts == 64 * (limit * 4 // 64)
         assert status(64, limit * 4 // 64 + 1) == -7          # 67,108,864: one workgroup too many
@@ -349,10 +350,14 @@ def test_a_launch_holds_at_most_2_pow_24_minus_1_workgroups():
     assert p.kernel == emb.EMB_KERNEL_STREAM and p.grid_blocks <= limit
     # tables of different widths
     m = emb.make_mixed_desc([4, 8] * 32, limit * 4 // 64 + 1, emb.EMB_F32, emb.EMB_SUM, 10, 0, 1 << 20)
-    with tuning(stream=0):
+    with tuning(stream=0, bags_per_wave=1):
         with pytest.raises(emb.EmbBagError) as ex:
             emb.emb_bag_plan_forward_mixed(m)
         assert ex.value.status == -7
+    # several bags per wavefront (the automatic choice for short bags) make room for more bags
+    with tuning(stream=0):
+        p = status(64, limit * 4 // 64 + 1)
+        assert p.bags_per_wave > 1 and p.waves_per_table == -(-(limit * 4 // 64 + 1) // p.bags_per_wave)
 
 
 def test_split_mixed_calls_are_fused_into_one_launch():
