@@ -51,6 +51,12 @@ DESCRIPTIONS = {
     "paper_mix1": "paper's model, Mix1: 100 high / 75 med / 50 low / 25 random tables",
     "paper_mix2": "paper's model, Mix2: 62 / 63 / 63 / 62",
     "paper_mix3": "paper's model, Mix3: 25 / 50 / 75 / 100",
+    "cfg4_hot": "cfg4 with every table laid out hot rows first (the 8,192 most popular rows of a "
+                "table occupy its first 4 MB, the state after offline profiling and relayout) and "
+                "desc.hot_rows naming that head",
+    "cfg5_hot": "cfg5 with its 50 Zipf tables laid out hot rows first (8,192 rows) and desc.hot_rows",
+    "paper_high_hot": "paper_high with every table laid out hot rows first (8,192 rows) and desc.hot_rows",
+    "paper_med_hot": "paper_med with every table laid out hot rows first (8,192 rows) and desc.hot_rows",
     "mixed_onehot": "26 fp32 tables x 1,000,000 rows, widths cycling 16 / 32 / 64 / 128, batch 131072, "
                     "ONE lookup per bag, uniform indices, sum: emb_bag_forward_mixed splits the call "
                     "into one stream-kernel launch per lanes-per-row class",
@@ -103,6 +109,9 @@ def main() -> int:
     ap.add_argument("--no-table-lengths", action="store_true",
                     help="do not pass per-table bag lengths (table_avg_len) for workloads whose "
                          "tables differ in pooling")
+    ap.add_argument("--no-hot-rows", action="store_true",
+                    help="do not pass desc.hot_rows for workloads laid out hot rows first (the "
+                         "reuse hints are passed instead)")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="emb_bag_set_tuning override, e.g. --tune depth=8")
     args = ap.parse_args()
@@ -188,13 +197,17 @@ def main() -> int:
     avg_len = None
     if wl.pooling[0] == "per_table" and not args.no_table_lengths:
         avg_len = gen.table_avg_len(wl, batches[0])
+    # tables laid out hot rows first: the size of each table's head (replaces the hints)
+    hot_rows = None
+    if not mixed and wl.hot_head > 0 and not args.no_hot_rows:
+        hot_rows = torch.from_numpy(gen.hot_rows(wl)).to(dev)
     if mixed:
         max_bytes = int(np.diff(wl.table_byte_offsets()).max())
         descs = [emb.make_mixed_desc(wl.dims, wl.B, edt, emode, b.num_lookups, 0, max_bytes, hints,
                                      avg_len) for b in batches]
     else:
         descs = [emb.make_desc(wl.T, wl.B, wl.D, edt, emode, b.num_lookups, 0, max(wl.rows), hints,
-                               avg_len) for b in batches]
+                               avg_len, hot_rows) for b in batches]
     torch.cuda.synchronize()
 
     def step(i: int) -> None:
@@ -306,6 +319,8 @@ def main() -> int:
         from oracle import emb_bag_oracle
     if args.check_bags > 0:
         k = (args.warmup + args.steps - 1) % len(batches)
+        step(k)                      # the output of this batch, whatever ran after the timed region
+        torch.cuda.synchronize()
         rng = np.random.default_rng(12345)
         nb = wl.num_bags
         bags = np.unique(np.concatenate([rng.integers(0, nb, size=args.check_bags),
@@ -449,10 +464,12 @@ def main() -> int:
                    "lookups_per_step": avg_lookups, "index_batches_rotated": len(batches),
                    "arena_allocation": arena_kind,
                    "streaming_tables": None if hints is None else int(hints.sum().item()),
+                   "hot_rows": None if hot_rows is None else int(hot_rows.max().item()),
                    "launch_plan": launch_plan,
                    "tuning": {k: emb.emb_bag_get_tuning(k) for k in
                               ("depth", "addressing", "blocks_per_cu", "xcd_remap", "use_hints",
-                               "stream", "bags_per_group", "xcd_pieces", "per_table_launch", "fuse")}},
+                               "stream", "bags_per_group", "xcd_pieces", "per_table_launch", "fuse",
+                               "bags_per_wave", "hot_split")}},
         "gathered_GBps": gathered * args.steps / wall / 1e9,
         "gathered_frac_of_hbm_peak": gathered * args.steps / wall / 1e9 / metrics.HBM_PEAK_GBPS,
         "kernel_ms": {"avg": avg_kern_s * 1e3, "min": float(min(kern_ms)),

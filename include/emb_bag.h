@@ -232,11 +232,19 @@ int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
  *   receives fewer; window is clamped to [1, 4096]) are examined:
  *     window_used[t] = number of lookups examined,
  *     dup_count[t]   = window_used[t] - (number of distinct row ids among them),
- *     hints[t]       = EMB_HINT_STREAMING if dup_count[t] * 1000 < threshold_permille *
- *                      window_used[t] (also when window_used[t] == 0), else EMB_HINT_DEFAULT.
+ *     hints[t]       = EMB_HINT_STREAMING if window_used[t] == 0, or if both
+ *                        dup_count[t] * 1000 < threshold_permille * window_used[t]  (few repeats
+ *                        inside the window) and
+ *                        n_t * dup_count[t] * 4 < window_used[t]^2  (few repeats expected over
+ *                        all n_t lookups the batch sends to table t: d repeats among w draws put
+ *                        the rows in use at about w^2 / 2d, so about n_t * d / w^2 of n_t draws
+ *                        repeat; the table counts as re-used from a quarter on);
+ *                      else EMB_HINT_DEFAULT.
  *   This is the device-side counterpart of the offline hot-index profiling of paper Sec. 4.3:
- *   uniform-random access (the paper's "random" dataset) shows practically no repeats, the
- *   power-law datasets show many.  threshold_permille < 0 selects the library default (20).
+ *   uniform-random access (the paper's "random" dataset) over a table much larger than the batch
+ *   shows practically no repeats, the power-law datasets show many, and so does a batch that
+ *   draws a sizeable part of a small table.  threshold_permille < 0 selects the library
+ *   default (20).
  *
  *   desc, indices, offsets   as in emb_bag_forward (desc->table_hints is ignored; only
  *                            num_tables, batch and num_lookups matter, so any valid dim serves

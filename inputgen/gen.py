@@ -262,6 +262,8 @@ class Workload:
     seed: int = 0x5EED0000
     kind: int = KIND_NORMAL
     note: str = ""
+    hot_head: int = 0           # Zipf tables only: ranks 1..hot_head sit in rows 0..hot_head-1 (the
+                                # table after the offline hot-row relayout of paper Sec. 4.3)
 
     @property
     def elem_bytes(self) -> int:
@@ -471,6 +473,15 @@ def workload(name: str) -> Workload:
         specs = tuple(("fixed", 100) if t % 4 == 3 and t < 24 else ("fixed", 1) for t in range(26))
         return _homog("hetero", 26, 1_000_000, 64, "f32", 32768, ("per_table", specs), ("uniform",),
                       seed_off=0x1D)
+    if name in ("cfg4_hot", "cfg5_hot", "paper_high_hot", "paper_med_hot"):
+        # the same tables, bags and popularity ranks as the base workload, with each Zipf table
+        # laid out hot rows first (8,192 rows of 512 bytes are one XCD's 4 MB of L2)
+        return with_overrides(workload(name[:-4]), name=name, hot_head=8192)
+    if name == "small_hot":        # small Zipf tables with a hot head, ragged bags, several chunks
+        return Workload(name="small_hot", T=5, rows=(3000, 200, 4096, 64, 900), D=128,
+                        dtype="f32", B=71, pooling=("uniform", 0, 200),
+                        dists=(("zipf", 1.05), ("zipf", 1.2), ("uniform",), ("one_item",),
+                               ("zipf", 0.8)), seed=0x5EED001E, hot_head=100)
     if name == "cfg3_max":         # cfg3 with max pooling
         return with_overrides(workload("cfg3"), name="cfg3_max", mode="max")
     if name == "cfg3_weighted":    # cfg3 with per-sample weights
@@ -572,8 +583,29 @@ def zipf_ranks(rng: np.random.Generator, R: int, alpha: float, n: int) -> np.nda
 
 
 def table_permutation(wl: Workload, t: int) -> np.ndarray:
-    """Seeded bijection rank -> row for table t (fixed across batches)."""
-    return _rng(wl.seed, _PURPOSE_PERM, 0, t).permutation(wl.rows[t]).astype(np.int64)
+    """Seeded bijection rank -> row for table t (fixed across batches).  With `hot_head` = K the K
+    most popular ranks occupy rows 0..K-1 in order of popularity and the other ranks are scattered
+    over the remaining rows: the layout a caller produces by profiling its lookups offline and
+    moving the hot rows to the front."""
+    R = wl.rows[t]
+    K = min(int(getattr(wl, "hot_head", 0)), R)
+    rng = _rng(wl.seed, _PURPOSE_PERM, 0, t)
+    if K <= 0:
+        return rng.permutation(R).astype(np.int64)
+    return np.concatenate([np.arange(K, dtype=np.int64),
+                           K + rng.permutation(R - K).astype(np.int64)])
+
+
+def hot_rows(wl: Workload) -> np.ndarray:
+    """What a caller passes as `hot_rows` for this workload, int64 [T]: the hot head of the Zipf
+    tables, 0 (a streaming table) for uniform tables, the whole table for a one-item table."""
+    out = np.zeros(wl.T, dtype=np.int64)
+    for t, dist in enumerate(wl.dists):
+        if dist[0] == "zipf":
+            out[t] = min(int(wl.hot_head), wl.rows[t])
+        elif dist[0] == "one_item":
+            out[t] = wl.rows[t]
+    return out
 
 
 def one_item_row(wl: Workload, t: int) -> int:

@@ -3,8 +3,11 @@
 Definition (the device-side stand-in for the offline hot-index profiling of paper Sec. 4.3): for
 table t take the first `window` lookups of the batch that go to t; `dup_count` is how many of
 them name a row that an earlier one of them already named, i.e. (lookups examined) - (distinct
-row ids); the hint is "streaming" (1) when fewer than threshold_permille/1000 of them are
-repeats, or when none was examined, else "default" (0).  Integer work: parity is bit-exact.
+row ids); the hint is "streaming" (1) when none was examined, or when fewer than
+threshold_permille/1000 of them are repeats AND the share of repeats expected over all n_t
+lookups the batch sends to the table, n_t * dup / examined^2 (the birthday estimate: dup repeats
+among w draws put the rows in use at w^2 / (2 dup)), is below a quarter; else "default" (0).
+Integer work: parity is bit-exact.
 
 Pins (tests/test_oracle_pins.py): hand-worked cases typed in, the all-distinct and all-equal
 closed forms, and the birthday-problem expectation for uniform draws.
@@ -27,5 +30,7 @@ def profile_reuse(indices: np.ndarray, offsets: np.ndarray, T: int, B: int, wind
         seg = [int(x) for x in indices[s:e][:window]]
         used[t] = len(seg)
         dup[t] = len(seg) - len(set(seg))
-        hints[t] = 1 if (int(dup[t]) * 1000 < threshold_permille * len(seg) or not seg) else 0
+        few_in_window = int(dup[t]) * 1000 < threshold_permille * len(seg)
+        few_in_batch = (e - s) * int(dup[t]) * 4 < len(seg) * len(seg)
+        hints[t] = 1 if (not seg or (few_in_window and few_in_batch)) else 0
     return dup, used, hints

@@ -55,6 +55,7 @@ emb_bag_validate_kernel(const int64_t* __restrict__ table_offsets,
 constexpr int kProfileThreads = 1024;
 constexpr int kProfileMaxWindow = 4096;
 constexpr uint32_t kProfileSlots = 6144;  // load factor <= 2/3: every probe sequence ends
+constexpr int64_t kProfileBatchShare = 4;  // re-used: an estimated 1/4 of the batch's lookups repeat
 
 __global__ void __launch_bounds__(kProfileThreads)
 emb_bag_profile_kernel(const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
@@ -97,8 +98,12 @@ emb_bag_profile_kernel(const int64_t* __restrict__ indices, const int64_t* __res
     const int d = dups;
     if (dup_count) dup_count[t] = d;
     if (window_used) window_used[t] = n;
+    // few repeats inside the window, and few expected over the table's n64 lookups of the
+    // whole batch: n64 * d / n^2 estimates their share (d repeats among n draws put the number
+    // of rows in use at about n^2 / 2d; n64 draws over those repeat in n64 / (2 n^2 / 2d) of cases)
     if (hints)
-      hints[t] = ((int64_t)d * 1000 < (int64_t)threshold_permille * n || n == 0)
+      hints[t] = (((int64_t)d * 1000 < (int64_t)threshold_permille * n &&
+                   n64 * d * kProfileBatchShare < (int64_t)n * n) || n == 0)
                      ? EMB_HINT_STREAMING : EMB_HINT_DEFAULT;
   }
 }

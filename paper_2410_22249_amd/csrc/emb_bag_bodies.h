@@ -9,6 +9,14 @@
 
 namespace embbag {
 
+// Position q of a launch's table list.  The list arrives in the kernel-argument segment; read as
+// an aligned 32-bit word at a wave-uniform position it is a scalar load, not a vector one.
+__device__ __forceinline__ uint32_t listed_table(const TableOrder& order, uint32_t q) {
+  q = __builtin_amdgcn_readfirstlane(q);
+  const uint32_t word = reinterpret_cast<const uint32_t*>(order.t)[q >> 1];
+  return (word >> ((q & 1u) * 16u)) & 0xFFFFu;
+}
+
 // ---------------------------------------------------------------------------------------------
 // wave body
 // ---------------------------------------------------------------------------------------------
@@ -47,7 +55,7 @@ __device__ __forceinline__ void wave_body(
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t tpos, w_in_table;
   if (!decode_work(p, block, wave, &tpos, &w_in_table)) return;
-  const uint32_t t = p.listed ? order.t[order_base + tpos] : tpos;
+  const uint32_t t = p.listed ? listed_table(order, order_base + tpos) : tpos;
   // the wavefront's bags b0 .. b0 + nb - 1 (one bag, one slab of it, when rows span slabs)
   uint32_t b0 = w_in_table * p.bags_per_wave, slab = 0, nb = p.bags_per_wave;
   if (p.slabs > 1) {
@@ -57,12 +65,17 @@ __device__ __forceinline__ void wave_body(
   }
   if (nb > p.B - b0) nb = p.B - b0;  // b0 < B: the grid holds ceil(B / bags_per_wave) per table
 
-  // bag bounds: lane l holds bound l of the wavefront's bags, clamped to [0, NL] so that no
-  // index read can leave [0, NL); a decreasing pair makes an empty bag
+  // Everything the wavefront needs to know before it can ask for row ids is requested at once
+  // and waited for once: the bag bounds (lane l holds bound l of the wavefront's bags), the
+  // table's cache hint or hot-head size, and the table's geometry.
   int64_t o = 0;
-  if ((uint32_t)lane <= nb) {
-    o = offsets[(uint64_t)t * p.B + b0 + (uint32_t)lane];
-    o = o < 0 ? 0 : (o > p.num_lookups ? p.num_lookups : o);
+  if ((uint32_t)lane <= nb) o = offsets[(uint64_t)t * p.B + b0 + (uint32_t)lane];
+  int hint_raw = 0;
+  int64_t hot_raw = 0;
+  if constexpr (HOT) {
+    hot_raw = hot_rows[t];
+  } else {
+    if (p.has_hints) hint_raw = table_hints[t];
   }
 
   // per-table geometry
@@ -74,6 +87,8 @@ __device__ __forceinline__ void wave_body(
   if constexpr (MIXED) {
     out_col = uniform64(out_offsets[t]);
     const int64_t out_next = uniform64(out_offsets[t + 1]);
+    const int64_t byte0 = uniform64(table_offsets[t]);
+    int64_t bytes = uniform64(table_offsets[t + 1]) - byte0;
     const int64_t d64 = out_next - out_col;
     const int64_t rb64 = QUANT ? d64 + 8 : d64 * (HALF ? 2 : 4);
     // a malformed table description writes nothing (the host checked its own copy of the widths)
@@ -83,8 +98,6 @@ __device__ __forceinline__ void wave_body(
     D_t = (uint32_t)d64;
     row_bytes = (uint32_t)rb64;
     while ((uint32_t)lpr * 16u < row_bytes) lpr <<= 1;
-    const int64_t byte0 = uniform64(table_offsets[t]);
-    int64_t bytes = uniform64(table_offsets[t + 1]) - byte0;
     if (bytes < 0) bytes = 0;
     if (BUF && bytes > (int64_t)kBufMaxBytes) bytes = (int64_t)kBufMaxBytes;
     R = bytes / row_bytes;
@@ -109,12 +122,11 @@ __device__ __forceinline__ void wave_body(
   // quantised rows: the lane of this lane's group whose segment ends with the row's scale and bias
   const int meta_lane = (lane & ~(lpr - 1)) + (int)(D_t >> 4);
 
-  bool streaming = false;
-  int64_t hot = 0;
-  if constexpr (HOT)
-    hot = uniform64(hot_rows[t]);
-  else
-    streaming = p.has_hints && (__builtin_amdgcn_readfirstlane((int)table_hints[t]) & 1);
+  // bag bounds are clamped to [0, NL] so that no index read can leave [0, NL); a decreasing pair
+  // makes an empty bag
+  o = o < 0 ? 0 : (o > p.num_lookups ? p.num_lookups : o);
+  const bool streaming = !HOT && (__builtin_amdgcn_readfirstlane(hint_raw) & 1);
+  const int64_t hot = HOT ? uniform64(hot_raw) : 0;
 
   // the first bag's first chunk; from then on a bag's first chunk is requested one bag ahead
   int64_t s = uniform64(o), e = uniform64(shfl64(o, 1));
@@ -318,7 +330,7 @@ __device__ __forceinline__ void stream_body(
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t tpos, w_in_table;
   if (!decode_work(p, block, wave, &tpos, &w_in_table)) return;
-  const uint32_t t = p.listed ? order.t[order_base + tpos] : tpos;
+  const uint32_t t = p.listed ? listed_table(order, order_base + tpos) : tpos;
   const uint32_t M = p.bags_per_group;                   // 1 .. LPR - 1
   const uint32_t b0 = w_in_table * (uint32_t)G * M;      // first bag of the wavefront, < B
   const uint32_t nbw = p.B - b0 < (uint32_t)G * M ? p.B - b0 : (uint32_t)G * M;  // its bags

@@ -51,7 +51,7 @@ struct KParams {
 // grows with the row width), so the host deals them by width.  Either way the kernel receives
 // the table at each position of the launch by value, in the kernel-argument segment.
 constexpr int kMaxOrdered = 1024;
-struct TableOrder {
+struct alignas(8) TableOrder {  // (aligned: the kernels read it in 32-bit words)
   uint16_t t[kMaxOrdered];
 };
 

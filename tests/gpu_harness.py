@@ -60,7 +60,7 @@ def device_arena(wl: gen.Workload) -> torch.Tensor:
 def forward(arena: torch.Tensor, table_offsets: np.ndarray, indices, offsets, B: int,
             mode: str = "sum", weights=None, out_ld: int = 0, max_table_rows: Optional[int] = None,
             out: Optional[torch.Tensor] = None, fill: float = float("nan"),
-            table_dtype: Optional[int] = None) -> torch.Tensor:
+            table_dtype: Optional[int] = None, hot_rows=None) -> torch.Tensor:
     """Run emb_bag_forward; numpy inputs are uploaded, torch inputs are used as they are.  The
     element type follows from the arena's dtype unless `table_dtype` names it (uint8 arenas hold
     integer codes by default, E4M3 codes with EMB_FP8ROW)."""
@@ -78,9 +78,10 @@ def forward(arena: torch.Tensor, table_offsets: np.ndarray, indices, offsets, B:
     ld = out_ld if out_ld else T * D
     if out is None:
         out = torch.full((B, ld), fill, dtype=torch.float32, device=DEV)
+    hot = None if hot_rows is None else to_dev(np.asarray(hot_rows, np.int64))
     desc = emb.make_desc(T, B, D, EMB_DTYPE[arena.dtype] if table_dtype is None else table_dtype,
                          emb.MODES[mode], nl, out_ld,
-                         max_table_rows)
+                         max_table_rows, hot_rows=hot)
     emb.emb_bag_forward(desc, arena, toff, idx if nl else None, off, w, out)
     torch.cuda.synchronize()
     return out

@@ -445,7 +445,10 @@ def test_reuse_profile_hand_worked():
     dup, used, hints = reuse_oracle.profile_reuse(idx, off, 2, 2, 2, 20)     # window of 2
     assert dup.tolist() == [1, 0] and used.tolist() == [2, 2] and hints.tolist() == [0, 1]
     dup, used, hints = reuse_oracle.profile_reuse(idx, off, 2, 2, 4096, 500)  # 50 % threshold
-    assert hints.tolist() == [1, 1]                                          # 2/5 < 50 %
+    assert hints.tolist() == [0, 1]      # 2/5 < 50 %, but 2 of the table's 5 lookups repeat: >= 1/4
+    idx9 = np.array([5, 5, 7, 6, 9, 4, 3, 2, 1, 1, 2, 3], dtype=np.int64)    # table 0: 1 repeat in 9
+    off9 = np.array([0, 8, 9, 9, 12], dtype=np.int64)
+    assert reuse_oracle.profile_reuse(idx9, off9, 2, 2, 4096, 500)[2].tolist() == [1, 1]  # 9*1*4 < 81
     # a table that receives nothing is "streaming"
     dup, used, hints = reuse_oracle.profile_reuse(np.zeros(0, np.int64), np.zeros(3, np.int64), 2, 1, 8)
     assert used.tolist() == [0, 0] and hints.tolist() == [1, 1]
@@ -464,6 +467,27 @@ def test_reuse_profile_closed_forms():
     # birthday problem: expected repeats of n uniform draws over R rows is about n^2 / (2R) = 1.1
     assert dup[2] == n - len(np.unique(uni)) and dup[2] < 12
     assert hints.tolist() == [1, 0, 1]
+
+
+def test_reuse_profile_counts_the_whole_batch():
+    """A table whose window shows few repeats is still re-used when the batch sends it many more
+    lookups than the window holds: with d repeats among w examined draws, about n * d / w^2 of
+    the table's n lookups repeat, and from a quarter on the table is not streaming."""
+    from oracle import reuse_oracle
+    w = 4096
+    # table 0: its first w lookups hold 8 repeats (ids 0..7 twice), then nothing new is examined;
+    # n = 3 w^2 / (4 * 8 * 4) lookups keep n * d * 4 below w^2, one more bag of them does not
+    head = np.concatenate([np.arange(8), np.arange(w - 8)]).astype(np.int64)
+    n_small, n_large = w * w // 32 - 1, w * w // 32
+    for n, want in ((n_small, 1), (n_large, 0)):
+        idx = np.concatenate([head, np.arange(n - w, dtype=np.int64) + 10_000_000])
+        off = np.array([0, n], dtype=np.int64)
+        dup, used, hints = reuse_oracle.profile_reuse(idx, off, 1, 1, w, 20)
+        assert dup.tolist() == [8] and used.tolist() == [w] and hints.tolist() == [want], n
+    # the window rule alone still decides when the window covers the table's lookups:
+    # 3 repeats in 200 draws is 1.5 % (< 2 %) and 200 * 3 * 4 < 200^2
+    idx = np.concatenate([np.arange(3), np.arange(197)]).astype(np.int64)
+    assert reuse_oracle.profile_reuse(idx, np.array([0, 200], np.int64), 1, 1, w, 20)[2].tolist() == [1]
 
 
 # ---- tables of different widths: the same definition, table by table ---------------------------
