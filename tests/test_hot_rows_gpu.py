@@ -55,7 +55,8 @@ def test_hot_split_is_exact_on_integer_tables_for_any_head(oracle, dtype):
     """Integer-valued rows: every order of summation gives the same bits, so the split must equal
     the oracle and the unsplit kernel exactly, whatever the head sizes are (none, a few rows,
     the whole table, more than the table)."""
-    wl, batch, arena = _problem(dtype, kind=gen.KIND_INT, weighted=False)
+    wl, batch, arena = _problem(dtype, kind=gen.KIND_INT, weighted=False,
+                                D=120 if dtype == "u8row" else 128)
     ref, _ = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "sum",
                             codes=wl.codes)
     dev = upload_arena(arena)
