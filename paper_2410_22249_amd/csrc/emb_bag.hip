@@ -140,7 +140,7 @@ constexpr int64_t kStreamMinWaves = 1024;
 
 // The kernels are built one lanes-per-row class per translation unit (emb_bag_wave.hip and
 // emb_bag_stream.hip, compiled once per class); here the classes are put back together.
-KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf, bool hot = false) {
+KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf, int hot = 0) {
   switch (lpr) {
     case 0: return pick_wave_kernel_lpr0(elem, depth, op, buf, hot);
     case 4: return pick_wave_kernel_lpr4(elem, depth, op, buf, hot);
@@ -430,8 +430,9 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   // tables with a hot head: the kernel that reads hot and other rows with different cache
   // policies, where it is built (buffer addressing, depth 4 or 8); otherwise the head is ignored
   wave.hot = desc->hot_rows != nullptr && g_tuning.hot_split != 0 && buf &&
-             pick_kernel(lpr, desc->table_dtype, depth, op, buf, true) != nullptr;
-  wave.fn = pick_kernel(lpr, desc->table_dtype, depth, op, buf, wave.hot);
+             pick_kernel(lpr, desc->table_dtype, depth, op, buf, (int)g_tuning.hot_split) != nullptr;
+  wave.fn = pick_kernel(lpr, desc->table_dtype, depth, op, buf,
+                        wave.hot ? (int)g_tuning.hot_split : 0);
   if (!wave.fn) return EMB_ERR_BAD_TUNING;
 
   // Short bags: a lane group streams several consecutive bags (emb_bag_stream.hip).  Without
@@ -962,7 +963,7 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
     if (value < 0 || value > kWaveMaxBags) return EMB_ERR_BAD_TUNING;
     g_tuning.bags_per_wave = value;
   } else if (!strcmp(key, "hot_split")) {
-    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    if (value < 0 || value > 2) return EMB_ERR_BAD_TUNING;
     g_tuning.hot_split = value;
   } else {
     return EMB_ERR_BAD_TUNING;

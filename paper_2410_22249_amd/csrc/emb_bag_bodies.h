@@ -34,9 +34,10 @@ __device__ __forceinline__ uint32_t listed_table(const TableOrder& order, uint32
 // which is always accurate because the ids are known ahead; here it runs across bags).
 //
 // HOT (buffer addressing only): hot_rows[t] leading rows of table t are its hot head; lookups
-// are regrouped per chunk and the two kinds read with different cache policies
-// (gather_hot_cold).  The hot head replaces the per-table hint: 0 rows = a streaming table.
-template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, bool HOT = false>
+// are regrouped per chunk, hot ones first (gather_hot_cold).  HOT == 1: the other rows are read
+// non-temporally, and the hot head replaces the per-table hint (0 rows = a streaming table);
+// HOT == 2: both kinds are read with the default policy.
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, int HOT = 0>
 __device__ __forceinline__ void wave_body(
     const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
@@ -128,6 +129,11 @@ __device__ __forceinline__ void wave_body(
   const bool streaming = !HOT && (__builtin_amdgcn_readfirstlane(hint_raw) & 1);
   const int64_t hot = HOT ? uniform64(hot_raw) : 0;
 
+  // Rows that fill their lane groups exactly (every benchmark shape) with a batch of DEPTH
+  // steps inside the 64 slots of a chunk need neither of gather_slots' per-load tests.
+  constexpr bool kNoWrap = LPR != 0 && DEPTH <= (LPR ? LPR : 1);
+  const bool lean = row_bytes % ((uint32_t)lpr * 16u) == 0;
+
   // the first bag's first chunk; from then on a bag's first chunk is requested one bag ahead
   int64_t s = uniform64(o), e = uniform64(shfl64(o, 1));
   e = e < s ? s : e;
@@ -165,15 +171,29 @@ __device__ __forceinline__ void wave_body(
           hot_mask = __builtin_amdgcn_ballot_w64((uint64_t)idx < (uint64_t)hot &&
                                                  q.voff != kBufSentinel);
       }
+      bool gathered = false;
       if constexpr (HOT) {
-        gather_hot_cold<LPR, ELEM, DEPTH, OP>(acc, n, hot_mask, q, tbase, rsrc, lane, g, col,
-                                              lane_ok, meta_lane, gl);
-      } else if (streaming) {
-        gather_slots<LPR, ELEM, DEPTH, OP, BUF, true>(acc, 0, n, q, tbase, rsrc, g, col, lane_ok,
-                                                      meta_lane, gl);
-      } else {
-        gather_slots<LPR, ELEM, DEPTH, OP, BUF, false>(acc, 0, n, q, tbase, rsrc, g, col, lane_ok,
-                                                       meta_lane, gl);
+        gather_hot_cold<LPR, ELEM, DEPTH, OP, HOT == 1>(acc, n, hot_mask, q, tbase, rsrc, lane, g,
+                                                        col, lane_ok, meta_lane, gl);
+        gathered = true;
+      } else if constexpr (kNoWrap && BUF) {
+        if (lean) {  // no per-load tests: see gather_slots
+          if (streaming)
+            gather_slots<LPR, ELEM, DEPTH, OP, true, true, false, false>(
+                acc, 0, n, q, tbase, rsrc, g, col, lane_ok, meta_lane, gl);
+          else
+            gather_slots<LPR, ELEM, DEPTH, OP, true, false, false, false>(
+                acc, 0, n, q, tbase, rsrc, g, col, lane_ok, meta_lane, gl);
+          gathered = true;
+        }
+      }
+      if (!gathered) {
+        if (streaming)
+          gather_slots<LPR, ELEM, DEPTH, OP, BUF, true>(acc, 0, n, q, tbase, rsrc, g, col,
+                                                        lane_ok, meta_lane, gl);
+        else
+          gather_slots<LPR, ELEM, DEPTH, OP, BUF, false>(acc, 0, n, q, tbase, rsrc, g, col,
+                                                         lane_ok, meta_lane, gl);
       }
     }
     // the next bag's row offsets before this bag's stores: its ids arrived ahead of the rows

@@ -108,7 +108,7 @@ EMB_DECLARE_FUSED_UNIFORM(64)
 #define EMB_PASTE(a, b) EMB_PASTE_(a, b)
 #define EMB_DECLARE_PICKERS(n)                                                                  \
   __attribute__((visibility("hidden"))) KernelFn pick_wave_kernel_lpr##n(                       \
-      int elem, int depth, int op, bool buf, bool hot);                                         \
+      int elem, int depth, int op, bool buf, int hot);                                          \
   __attribute__((visibility("hidden"))) KernelFn pick_stream_kernel_lpr##n(                     \
       int elem, int depth, bool weighted, bool mixed);
 EMB_DECLARE_PICKERS(0)  // (there is no stream kernel for class 0; the declaration is unused)
@@ -215,6 +215,25 @@ __device__ __forceinline__ void accumulate(float* acc, u32x4 r, float w, int met
       }
     }
     acc[16] += MAXP ? w : bias;
+  } else if constexpr (ELEM == EMB_F16 && !MAXP) {
+    // acc += w * half, one instruction per element: the mixed-precision FMA reads the half
+    // straight from its half of the register (the product of a half and a float is exact in
+    // the FMA, so the result equals widening first and adding, or multiplying, afterwards)
+    const uint32_t u[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (WEIGHTED) {
+        asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,0,0] op_sel_hi:[1,0,0]"
+            : "+v"(acc[2 * i]) : "v"(u[i]), "v"(w));
+        asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]"
+            : "+v"(acc[2 * i + 1]) : "v"(u[i]), "v"(w));
+      } else {
+        asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[0,0,0] op_sel_hi:[1,0,0]"
+            : "+v"(acc[2 * i]) : "v"(u[i]));
+        asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]"
+            : "+v"(acc[2 * i + 1]) : "v"(u[i]));
+      }
+    }
   } else if constexpr (ELEM != EMB_F32) {
     const uint32_t u[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
@@ -305,14 +324,21 @@ __device__ __forceinline__ ChunkLookups<BUF> chunk_offsets(int64_t idx, float w,
 // re-used within a batch), the default policy otherwise.  A slot outside the range, a lane
 // beyond the row's end and a lookup without a row fetch nothing: their offset fails the
 // buffer's range check (zeros, no memory traffic), or the load is skipped (64-bit addressing).
-template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, bool NT>
+//
+// The two per-load tests are compiled in only where they can fire.  RANGE: slots outside
+// [j_lo, j_hi) may hold a lookup (the hot / cold split), or a batch of DEPTH steps can run past
+// slot 63 and wrap (DEPTH steps cover more than 64 slots); without it j_lo is 0 and the slots
+// from j_hi on hold "no row" already, as load_chunk and chunk_offsets leave them.  PARTIAL:
+// the row does not fill its lane group (lane_ok is false for some lanes).
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, bool NT, bool RANGE = true,
+          bool PARTIAL = true>
 __device__ __forceinline__ void gather_slots(float* acc, int j_lo, int j_hi,
                                              const ChunkLookups<BUF>& q, const char* tbase,
                                              __amdgpu_buffer_rsrc_t rsrc, int g, uint32_t col,
                                              bool lane_ok, int meta_lane, int gl) {
   constexpr bool WEIGHTED = OP == kOpWeighted;
   constexpr int kAux = NT ? 2 : 0;  // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
-  const int k_lo = j_lo >> gl;
+  const int k_lo = RANGE ? j_lo >> gl : 0;
   const int k_hi = (j_hi + (1 << gl) - 1) >> gl;
   for (int k0 = k_lo; k0 < k_hi; k0 += DEPTH) {
     u32x4 r[DEPTH];
@@ -320,26 +346,29 @@ __device__ __forceinline__ void gather_slots(float* acc, int j_lo, int j_hi,
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
       const int j = ((k0 + d) << gl) + g;  // slot served by this lane's group in this step
-      const bool in = j >= j_lo && j < j_hi;
-      const bool take = in && lane_ok;
+      const int src = RANGE ? (j & (kWaveSize - 1)) : j;  // (no wrap without RANGE)
+      const bool in = !RANGE || (j >= j_lo && j < j_hi);
+      const bool take = in && (!PARTIAL || lane_ok);
       bool valid;  // this lane fetches a segment of a row that exists
       if constexpr (BUF) {
-        uint32_t vo = (uint32_t)__shfl((int)q.voff, j & (kWaveSize - 1));
-        vo = take ? vo : kBufSentinel;
+        uint32_t vo = (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)q.voff);
+        if constexpr (RANGE || PARTIAL) vo = take ? vo : kBufSentinel;
         valid = vo != kBufSentinel;
         r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
       } else {
-        const int64_t ro = shfl64(q.roff, j & (kWaveSize - 1));
+        const int64_t ro = shfl64(q.roff, src);
         u32x4 v = {0u, 0u, 0u, 0u};
         valid = take && ro >= 0;
         if (valid) {
-          const u32x4* src = reinterpret_cast<const u32x4*>(tbase + ro + col);
-          v = NT ? __builtin_nontemporal_load(src) : *src;
+          const u32x4* srcp = reinterpret_cast<const u32x4*>(tbase + ro + col);
+          v = NT ? __builtin_nontemporal_load(srcp) : *srcp;
         }
         r[d] = v;
       }
       if constexpr (WEIGHTED) {
-        const float ws = __shfl(q.w, j & (kWaveSize - 1));
+        // (a slot without a lookup holds weight 0 and fetched zeros)
+        const float ws = __builtin_bit_cast(
+            float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, q.w)));
         wj[d] = in ? ws : 0.0f;
       } else if constexpr (OP == kOpMax) {
         wj[d] = valid ? 1.0f : 0.0f;
@@ -358,7 +387,7 @@ __device__ __forceinline__ void gather_slots(float* acc, int j_lo, int j_hi,
 // two kinds are gathered one after the other - the hot rows with the default cache policy, so
 // that they stay in L2, the others non-temporally, so that they do not push hot rows out.
 // `hot_mask` has bit i set if lookup i names a hot row, `n` is the number of lookups.
-template <int LPR, int ELEM, int DEPTH, int OP>
+template <int LPR, int ELEM, int DEPTH, int OP, bool COLD_NT>
 __device__ __forceinline__ void gather_hot_cold(float* acc, int n, uint64_t hot_mask,
                                                 const ChunkLookups<true>& q, const char* tbase,
                                                 __amdgpu_buffer_rsrc_t rsrc, int lane, int g,
@@ -383,8 +412,8 @@ __device__ __forceinline__ void gather_hot_cold(float* acc, int n, uint64_t hot_
                                         dest << 2, __builtin_bit_cast(int, q.w)));
   gather_slots<LPR, ELEM, DEPTH, OP, true, false>(acc, 0, nh, s, tbase, rsrc, g, col, lane_ok,
                                                   meta_lane, gl);
-  gather_slots<LPR, ELEM, DEPTH, OP, true, true>(acc, kWaveSize - nc, kWaveSize, s, tbase, rsrc,
-                                                 g, col, lane_ok, meta_lane, gl);
+  gather_slots<LPR, ELEM, DEPTH, OP, true, COLD_NT>(acc, kWaveSize - nc, kWaveSize, s, tbase,
+                                                    rsrc, g, col, lane_ok, meta_lane, gl);
 }
 
 // The gather of one bag (one column slab of it) by a whole wavefront: walk the bag's lookups

@@ -52,7 +52,7 @@ namespace {
 using namespace embbag;
 
 // The kernel proper is embbag::wave_body (emb_bag_bodies.h), shared with the fused launch.
-template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, bool HOT>
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, int HOT>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
@@ -68,19 +68,22 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
 // buffer or 64-bit addressing; the hot / cold split (tables with a hot head) exists for buffer
 // addressing, tables of one width and depths 4 and 8
 template <int LPR, int ELEM, int DEPTH, int OP>
-KernelFn pick_addr(bool buf, bool hot) {
+KernelFn pick_addr(bool buf, int hot) {
   if (hot) {
-    if constexpr (LPR != 0 && (DEPTH == 4 || DEPTH == 8))
-      return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, true> : nullptr;
-    else
+    if constexpr (LPR != 0 && (DEPTH == 4 || DEPTH == 8)) {
+      if (!buf) return nullptr;
+      return hot == 1 ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, 1>
+                      : emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, 2>;
+    } else {
       return nullptr;
+    }
   }
-  return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, false>
-             : emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, false, false>;
+  return buf ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, 0>
+             : emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, false, 0>;
 }
 
 template <int LPR, int ELEM, int DEPTH>
-KernelFn pick_op(int op, bool buf, bool hot) {
+KernelFn pick_op(int op, bool buf, int hot) {
   if (op == kOpWeighted) return pick_addr<LPR, ELEM, DEPTH, kOpWeighted>(buf, hot);
   if (op == kOpMax) {
     if constexpr (DEPTH == 4 || DEPTH == 8)  // max pooling: two depths are enough
@@ -92,7 +95,7 @@ KernelFn pick_op(int op, bool buf, bool hot) {
 }
 
 template <int LPR, int ELEM>
-KernelFn pick_depth(int depth, int op, bool buf, bool hot) {
+KernelFn pick_depth(int depth, int op, bool buf, int hot) {
   if (LPR == 0 || op == kOpMax)  // tables of different widths, max pooling: depth 4 or 8
     return depth <= 4 ? pick_op<LPR, ELEM, 4>(op, buf, hot) : pick_op<LPR, ELEM, 8>(op, buf, hot);
   if constexpr (LPR != 0) {
@@ -109,7 +112,7 @@ KernelFn pick_depth(int depth, int op, bool buf, bool hot) {
 }
 
 template <int LPR>
-KernelFn pick_dtype(int elem, int depth, int op, bool buf, bool hot) {
+KernelFn pick_dtype(int elem, int depth, int op, bool buf, int hot) {
   switch (elem) {
     case EMB_F32: return pick_depth<LPR, EMB_F32>(depth, op, buf, hot);
     case EMB_F16: return pick_depth<LPR, EMB_F16>(depth, op, buf, hot);
@@ -126,7 +129,7 @@ namespace embbag {
 
 // nullptr if there is no such instantiation
 KernelFn EMB_PASTE(pick_wave_kernel_lpr, EMB_LPR)(int elem, int depth, int op, bool buf,
-                                                  bool hot) {
+                                                  int hot) {
   return pick_dtype<EMB_LPR>(elem, depth, op, buf, hot);
 }
 

@@ -571,3 +571,33 @@ def test_bags_per_wave_gives_the_same_bits(oracle, name, mode):
                 else:
                     assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"{name}/{mode}")
             assert np.array_equal(got.view(np.uint32), base.view(np.uint32)), (bpw, addressing)
+
+
+@pytest.mark.parametrize("kernel", ["wave", "stream"])
+def test_every_finite_half_is_widened_exactly(kernel):
+    """A table that holds every finite binary16 bit pattern (subnormals included), one lookup per
+    bag: the output is the exact widening of the element, bit for bit, also through the
+    mixed-precision FMA the kernels use for fp16 rows, in sum, mean and weighted form."""
+    bits = np.arange(1 << 16, dtype=np.uint16)
+    bits = bits[(bits & 0x7C00) != 0x7C00]                      # no infinities, no NaNs
+    D = 8
+    pad = (-len(bits)) % D
+    table = np.concatenate([bits, np.zeros(pad, np.uint16)]).view(np.float16).reshape(-1, D)
+    R = len(table)
+    dev = torch.from_numpy(table).to(DEV)
+    want = table.astype(np.float32) + np.float32(0.0)           # numpy widens exactly; the sum
+    idx = np.arange(R, dtype=np.int64)                          # starts at +0, so -0 comes out +0
+    off = np.arange(R + 1, dtype=np.int64)
+    toff = np.array([0, R], np.int64)
+    with tuning(stream=1 if kernel == "stream" else 0):
+        for mode, weights in (("sum", None), ("mean", None), ("sum", np.ones(R, np.float32))):
+            got = forward(dev, toff, idx, off, R, mode, weights=weights).cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), (mode, weights is None)
+        # a weight of 0.5 halves every element exactly (subnormal halves widen to normal floats)
+        got = forward(dev, toff, idx, off, R, "sum", weights=np.full(R, 0.5, np.float32)).cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), (want * np.float32(0.5)).view(np.uint32))
+        # two lookups per bag: x + (-0.0 or +0.0) keeps x; and x + x doubles it
+        idx2 = np.stack([idx, idx], 1).ravel()
+        off2 = np.arange(R + 1, dtype=np.int64) * 2
+        got = forward(dev, toff, idx2, off2, R, "sum").cpu().numpy()
+        assert np.array_equal(got, want * np.float32(2.0))
