@@ -104,6 +104,10 @@ def main() -> int:
     ap.add_argument("--arena", default="torch", choices=["torch", "contiguous"],
                     help="table memory: torch's caching allocator (default) or physically "
                          "contiguous hipExtMallocWithFlags")
+    ap.add_argument("--arena-decoy", action="store_true",
+                    help="allocate (and afterwards free) a block of the arena's size first, so that "
+                         "the arena lands in the next physical region the driver hands out; the "
+                         "speed of random gathers differs by region (see DESIGN.md)")
     ap.add_argument("--no-hints", action="store_true",
                     help="do not profile table reuse / pass per-table cache hints")
     ap.add_argument("--no-table-lengths", action="store_true",
@@ -154,6 +158,9 @@ def main() -> int:
     # The arena is the caller's memory.  Where it lands physically moves cfg3 by about 5 %
     # between allocations of the same size; the contiguous flag itself makes no difference.
     owner = None
+    decoy = None
+    if args.arena_decoy:
+        decoy = torch.empty(wl.table_bytes, dtype=torch.uint8, device=dev)
     if mixed:
         arena, arena_kind = torch.empty(wl.table_bytes, dtype=torch.uint8, device=dev), "torch"
     elif args.arena == "contiguous":
@@ -161,6 +168,10 @@ def main() -> int:
         arena, arena_kind = owner.tensor, owner.kind
     else:
         arena, arena_kind = torch.empty((wl.total_rows, width), dtype=tdtype, device=dev), "torch"
+    if decoy is not None:
+        arena_kind += ", allocated after a decoy of the same size"
+        del decoy
+        torch.cuda.empty_cache()
     with torch.cuda.stream(stream):
         if mixed:
             gen.mixed_fill_device(wl, arena.data_ptr(), sh)
@@ -462,7 +473,7 @@ def main() -> int:
                    "dim": list(wl.dims) if mixed else wl.D,
                    "table_dtype": wl.dtype, "batch": wl.B, "mode": wl.mode,
                    "lookups_per_step": avg_lookups, "index_batches_rotated": len(batches),
-                   "arena_allocation": arena_kind,
+                   "arena_allocation": arena_kind, "arena_address": hex(arena.data_ptr()),
                    "streaming_tables": None if hints is None else int(hints.sum().item()),
                    "hot_rows": None if hot_rows is None else int(hot_rows.max().item()),
                    "launch_plan": launch_plan,

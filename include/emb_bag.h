@@ -258,6 +258,46 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
                           int32_t* dup_count, int32_t* window_used, uint8_t* hints, void* stream);
 
 /*
+ * emb_bag_profile_hot_rows - the k most frequently looked-up rows of every table in a sample batch.
+ *
+ *   The paper profiles offline to find "the top 60K hot indices" of each table and keeps their
+ *   rows in L2 (Sec. 4.3); this is that profiling step on the device.  For every table t the
+ *   first `window` lookups of the batch that go to t are examined (fewer if the table receives
+ *   fewer); ids outside [0, 2^40 - 1) are not counted.  The distinct ids are ordered by
+ *   (occurrences descending, id ascending) and the first k of them reported:
+ *     num_hot[t]            = min(k, number of distinct ids examined),
+ *     hot_ids[t*k + r]      = the r-th id of that order for r < num_hot[t], -1 beyond,
+ *     hot_counts[t*k + r]   = its number of occurrences, 0 beyond.
+ *   The result is unique (no two ids tie), exact and deterministic.  A caller that moves these
+ *   rows to the front of table t, in this order, and renumbers its row ids accordingly can pass
+ *   num_hot (widened to int64) as emb_bag_desc.hot_rows.
+ *
+ *   desc, indices, offsets   as in emb_bag_forward (only num_tables, batch and num_lookups
+ *                            matter, so any valid dim serves)
+ *   window                   1 .. 2^24 - 1 lookups examined per table
+ *   k                        1 .. 65536
+ *   hot_ids                  DEVICE int64 [T*k]
+ *   hot_counts               DEVICE int32 [T*k]
+ *   num_hot                  DEVICE int32 [T], or NULL
+ *   workspace                DEVICE, 8-byte aligned, at least
+ *                            emb_bag_profile_hot_rows_workspace(T, window, k) bytes: per table a
+ *                            hash table of 2^ceil(log2(2*window)) 8-byte slots (at least 64) and a
+ *                            sort buffer of 2^ceil(log2(k)) 8-byte keys (at least 2).  Its
+ *                            contents on entry do not matter (the kernel clears what it uses) and
+ *                            mean nothing afterwards; calls that share a workspace must not overlap
+ *   workspace_bytes          size of the workspace; EMB_ERR_BAD_SIZE if too small
+ *   Asynchronous on `stream`; one kernel launch, no allocation.
+ *
+ * emb_bag_profile_hot_rows_workspace returns the bytes needed, or EMB_ERR_BAD_SIZE (negative)
+ * for arguments outside the ranges above.
+ */
+int64_t emb_bag_profile_hot_rows_workspace(int32_t num_tables, int64_t window, int64_t k);
+int emb_bag_profile_hot_rows(const emb_bag_desc* desc, const int64_t* indices,
+                             const int64_t* offsets, int64_t window, int64_t k, int64_t* hot_ids,
+                             int32_t* hot_counts, int32_t* num_hot, void* workspace,
+                             int64_t workspace_bytes, void* stream);
+
+/*
  * emb_bag_plan_forward / emb_bag_plan_forward_mixed - what the corresponding forward call would
  * launch for this descriptor under the current tuning, without launching anything: which kernel
  * (the paper's recipe of Sec. 7 picks a scheme per workload; this is where a caller sees the

@@ -27,6 +27,7 @@ EMB_HINT_DEFAULT, EMB_HINT_STREAMING = 0, 1
 EMB_KERNEL_WAVE, EMB_KERNEL_STREAM = 0, 1
 EXPORTS = ("emb_bag_forward", "emb_bag_forward_mixed", "emb_bag_plan_forward",
            "emb_bag_plan_forward_mixed", "emb_bag_validate", "emb_bag_profile_reuse",
+           "emb_bag_profile_hot_rows", "emb_bag_profile_hot_rows_workspace",
            "emb_bag_set_tuning", "emb_bag_get_tuning", "emb_bag_status_string", "emb_bag_version")
 
 
@@ -91,6 +92,11 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.emb_bag_profile_reuse.restype = ctypes.c_int
     lib.emb_bag_profile_reuse.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, ctypes.c_int32,
                                           ctypes.c_int32, P, P, P, P]
+    lib.emb_bag_profile_hot_rows_workspace.restype = ctypes.c_int64
+    lib.emb_bag_profile_hot_rows_workspace.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64]
+    lib.emb_bag_profile_hot_rows.restype = ctypes.c_int
+    lib.emb_bag_profile_hot_rows.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, ctypes.c_int64,
+                                             ctypes.c_int64, P, P, P, P, ctypes.c_int64, P]
     lib.emb_bag_set_tuning.restype = ctypes.c_int
     lib.emb_bag_set_tuning.argtypes = [ctypes.c_char_p, ctypes.c_int64]
     lib.emb_bag_get_tuning.restype = ctypes.c_int
@@ -242,6 +248,29 @@ def emb_bag_profile_reuse(desc: emb_bag_desc, indices: torch.Tensor, offsets: to
                                     _ptr(hints), _stream_handle(stream))
     if rc != EMB_OK:
         raise EmbBagError(rc, "emb_bag_profile_reuse")
+
+
+def emb_bag_profile_hot_rows_workspace(num_tables: int, window: int, k: int) -> int:
+    """Bytes of workspace emb_bag_profile_hot_rows needs (raises for arguments out of range)."""
+    n = int(_lib.emb_bag_profile_hot_rows_workspace(int(num_tables), int(window), int(k)))
+    if n < 0:
+        raise EmbBagError(n, "emb_bag_profile_hot_rows_workspace")
+    return n
+
+
+def emb_bag_profile_hot_rows(desc: emb_bag_desc, indices: torch.Tensor, offsets: torch.Tensor,
+                             window: int, k: int, hot_ids: torch.Tensor, hot_counts: torch.Tensor,
+                             num_hot: Optional[torch.Tensor], workspace: torch.Tensor,
+                             stream=None) -> None:
+    """Enqueue the per-table top-k row profile (device int64 [T*k], int32 [T*k], int32 [T]);
+    `workspace` is a device tensor of at least emb_bag_profile_hot_rows_workspace(...) bytes."""
+    rc = _lib.emb_bag_profile_hot_rows(ctypes.byref(desc), _ptr(indices), _ptr(offsets),
+                                       int(window), int(k), _ptr(hot_ids), _ptr(hot_counts),
+                                       _ptr(num_hot), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(),
+                                       _stream_handle(stream))
+    if rc != EMB_OK:
+        raise EmbBagError(rc, "emb_bag_profile_hot_rows")
 
 
 def emb_bag_set_tuning(key: str, value: int) -> None:

@@ -490,6 +490,53 @@ def test_reuse_profile_counts_the_whole_batch():
     assert reuse_oracle.profile_reuse(idx, np.array([0, 200], np.int64), 1, 1, w, 20)[2].tolist() == [1]
 
 
+# ---- the hot-row profile oracle (integer work) -------------------------------------------------
+def test_hot_rows_hand_worked():
+    from oracle import hot_rows_oracle
+    # T = 2, B = 2.  table 0 lookups: [5,5,7,5 | 9,7]   table 1 lookups: [ | 3,1,2]
+    idx = np.array([5, 5, 7, 5, 9, 7, 3, 1, 2], dtype=np.int64)
+    off = np.array([0, 4, 6, 6, 9], dtype=np.int64)
+    ids, counts, num = hot_rows_oracle.profile_hot_rows(idx, off, 2, 2, 100, 3)
+    assert ids.tolist() == [[5, 7, 9], [1, 2, 3]]            # 5 x3, 7 x2, 9 x1; ties: smaller id first
+    assert counts.tolist() == [[3, 2, 1], [1, 1, 1]] and num.tolist() == [3, 3]
+    ids, counts, num = hot_rows_oracle.profile_hot_rows(idx, off, 2, 2, 100, 2)   # k cuts the list
+    assert ids.tolist() == [[5, 7], [1, 2]] and counts.tolist() == [[3, 2], [1, 1]]
+    ids, counts, num = hot_rows_oracle.profile_hot_rows(idx, off, 2, 2, 100, 5)   # k beyond the ids
+    assert ids.tolist() == [[5, 7, 9, -1, -1], [1, 2, 3, -1, -1]] and num.tolist() == [3, 3]
+    assert counts.tolist() == [[3, 2, 1, 0, 0], [1, 1, 1, 0, 0]]
+    ids, counts, num = hot_rows_oracle.profile_hot_rows(idx, off, 2, 2, 3, 2)     # window of 3: [5,5,7]
+    assert ids.tolist() == [[5, 7], [1, 2]] and counts.tolist() == [[2, 1], [1, 1]]
+    # ids that are no row ids are not counted; a table without lookups has no hot rows
+    idx = np.array([-1, 4, 1 << 40, 4, (1 << 40) - 1, (1 << 40) - 2], dtype=np.int64)
+    ids, counts, num = hot_rows_oracle.profile_hot_rows(idx, np.array([0, 6, 6]), 2, 1, 100, 3)
+    assert ids.tolist() == [[4, (1 << 40) - 2, -1], [-1, -1, -1]] and num.tolist() == [2, 0]
+    assert counts.tolist() == [[2, 1, 0], [0, 0, 0]]
+
+
+def test_hot_rows_closed_forms_and_second_route():
+    import collections
+    from oracle import hot_rows_oracle
+    n = 500
+    # table 0: all distinct -> the k smallest ids, once each; table 1: one item -> one hot row;
+    # table 2: id i occurs i + 1 times -> ids in descending order with counts id + 1
+    tri = np.repeat(np.arange(40), np.arange(40) + 1)
+    rng = np.random.default_rng(17)
+    rng.shuffle(tri)
+    idx = np.concatenate([rng.permutation(n) + 1000, np.full(n, 77), tri]).astype(np.int64)
+    off = np.array([0, n, 2 * n, 2 * n + len(tri)], dtype=np.int64)
+    ids, counts, num = hot_rows_oracle.profile_hot_rows(idx, off, 3, 1, 1 << 20, 8)
+    assert ids[0].tolist() == list(range(1000, 1008)) and counts[0].tolist() == [1] * 8
+    assert ids[1].tolist() == [77] + [-1] * 7 and counts[1].tolist() == [n] + [0] * 7
+    assert ids[2].tolist() == list(range(39, 31, -1)) and counts[2].tolist() == list(range(40, 32, -1))
+    assert num.tolist() == [8, 1, 8]
+    # a Zipf sample: the same answer through collections.Counter
+    zipf = np.minimum(rng.zipf(1.3, size=5000), 3000).astype(np.int64)
+    ids, counts, num = hot_rows_oracle.profile_hot_rows(zipf, np.array([0, 5000]), 1, 1, 4000, 50)
+    want = sorted(collections.Counter(zipf[:4000].tolist()).items(), key=lambda kv: (-kv[1], kv[0]))[:50]
+    assert ids[0].tolist() == [kv[0] for kv in want] and counts[0].tolist() == [kv[1] for kv in want]
+    assert ids[0, 0] == 1                                     # rank 1 is the most frequent
+
+
 # ---- tables of different widths: the same definition, table by table ---------------------------
 def test_mixed_widths_equal_the_uniform_oracle_when_widths_agree(oracle):
     rng = np.random.default_rng(41)
