@@ -298,6 +298,25 @@ int emb_bag_profile_hot_rows(const emb_bag_desc* desc, const int64_t* indices,
                              int64_t workspace_bytes, void* stream);
 
 /*
+ * emb_bag_profile_hot_rows_noalloc - emb_bag_profile_hot_rows for callers that cannot allocate
+ * device memory and have no workspace to pass: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, results and errors, without the
+ * workspace: the scratch memory is a fixed 16 MiB array in device memory that belongs to the
+ * library (every GPU the library is used on holds it until the process ends).  The call
+ * allocates and frees nothing; num_tables * (2^ceil(log2(2*window)) + 2^ceil(log2(k))) * 8
+ * bytes (see emb_bag_profile_hot_rows_workspace) must not exceed 16,777,216, else
+ * EMB_ERR_BAD_SIZE and nothing is enqueued.  All calls on one GPU share that array, which keeps
+ * the previous call's contents (the kernel clears what it uses): calls that overlap in time on
+ * one GPU, on different streams, race and give wrong results; calls on one stream are ordered.
+ * The first call on a device looks the array's address up (hipGetSymbolAddress): make it
+ * outside a graph capture.
+ */
+int emb_bag_profile_hot_rows_noalloc(const emb_bag_desc* desc, const int64_t* indices,
+                                     const int64_t* offsets, int64_t window, int64_t k,
+                                     int64_t* hot_ids, int32_t* hot_counts, int32_t* num_hot,
+                                     void* stream);
+
+/*
  * emb_bag_plan_forward / emb_bag_plan_forward_mixed - what the corresponding forward call would
  * launch for this descriptor under the current tuning, without launching anything: which kernel
  * (the paper's recipe of Sec. 7 picks a scheme per workload; this is where a caller sees the

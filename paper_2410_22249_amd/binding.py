@@ -28,6 +28,7 @@ EMB_KERNEL_WAVE, EMB_KERNEL_STREAM = 0, 1
 EXPORTS = ("emb_bag_forward", "emb_bag_forward_mixed", "emb_bag_plan_forward",
            "emb_bag_plan_forward_mixed", "emb_bag_validate", "emb_bag_profile_reuse",
            "emb_bag_profile_hot_rows", "emb_bag_profile_hot_rows_workspace",
+           "emb_bag_profile_hot_rows_noalloc",
            "emb_bag_set_tuning", "emb_bag_get_tuning", "emb_bag_status_string", "emb_bag_version")
 
 
@@ -97,6 +98,9 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.emb_bag_profile_hot_rows.restype = ctypes.c_int
     lib.emb_bag_profile_hot_rows.argtypes = [ctypes.POINTER(emb_bag_desc), P, P, ctypes.c_int64,
                                              ctypes.c_int64, P, P, P, P, ctypes.c_int64, P]
+    lib.emb_bag_profile_hot_rows_noalloc.restype = ctypes.c_int
+    lib.emb_bag_profile_hot_rows_noalloc.argtypes = [ctypes.POINTER(emb_bag_desc), P, P,
+                                                     ctypes.c_int64, ctypes.c_int64, P, P, P, P]
     lib.emb_bag_set_tuning.restype = ctypes.c_int
     lib.emb_bag_set_tuning.argtypes = [ctypes.c_char_p, ctypes.c_int64]
     lib.emb_bag_get_tuning.restype = ctypes.c_int
@@ -271,6 +275,19 @@ def emb_bag_profile_hot_rows(desc: emb_bag_desc, indices: torch.Tensor, offsets:
                                        _stream_handle(stream))
     if rc != EMB_OK:
         raise EmbBagError(rc, "emb_bag_profile_hot_rows")
+
+
+def emb_bag_profile_hot_rows_noalloc(desc: emb_bag_desc, indices: torch.Tensor,
+                                     offsets: torch.Tensor, window: int, k: int,
+                                     hot_ids: torch.Tensor, hot_counts: torch.Tensor,
+                                     num_hot: Optional[torch.Tensor], stream=None) -> None:
+    """emb_bag_profile_hot_rows without a workspace (the library's own 16 MiB scratch array)."""
+    rc = _lib.emb_bag_profile_hot_rows_noalloc(ctypes.byref(desc), _ptr(indices), _ptr(offsets),
+                                               int(window), int(k), _ptr(hot_ids),
+                                               _ptr(hot_counts), _ptr(num_hot),
+                                               _stream_handle(stream))
+    if rc != EMB_OK:
+        raise EmbBagError(rc, "emb_bag_profile_hot_rows_noalloc")
 
 
 def emb_bag_set_tuning(key: str, value: int) -> None:

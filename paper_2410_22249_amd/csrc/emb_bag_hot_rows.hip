@@ -17,12 +17,20 @@
 //      and written out as ids and counts.
 // All keys are distinct, so the result is unique and can be checked bit for bit.
 //
-// The scratch buffer is the caller's workspace.
+// The scratch buffer is either the caller's workspace or, for callers that cannot allocate, a
+// fixed array in device memory that belongs to the library (emb_bag_profile_hot_rows_noalloc).
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "../../include/emb_bag.h"
+
+// Scratch memory of emb_bag_profile_hot_rows_noalloc: 16 MiB of device memory that every GPU the
+// library runs on holds from the moment the library is loaded until the process ends.  In host
+// code this name is only a handle; the array's device address comes from hipGetSymbolAddress
+// (once per device, see scratch_on_current_device) and is what kernels and copies are given.
+constexpr uint64_t kScratchWords = 2ull << 20;
+static __device__ __align__(256) unsigned long long scratch[kScratchWords];
 
 namespace {
 
@@ -208,9 +216,40 @@ int check_and_launch(const emb_bag_desc* desc, const int64_t* indices, const int
   return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
 }
 
+// The device address of `scratch` on the current device: asked for once per device, then kept
+// (every GPU has its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+uint64_t* g_scratch_ptr[kMaxDevices];
+
+int scratch_on_current_device(uint64_t** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return EMB_ERR_LAUNCH;
+  uint64_t* p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym)
+      return EMB_ERR_LAUNCH;
+    p = static_cast<uint64_t*>(sym);
+    __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);  // (a racing thread stores the same)
+  }
+  *ptr = p;
+  return EMB_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+int emb_bag_profile_hot_rows_noalloc(const emb_bag_desc* desc, const int64_t* indices,
+                                     const int64_t* offsets, int64_t window, int64_t k,
+                                     int64_t* hot_ids, int32_t* hot_counts, int32_t* num_hot,
+                                     void* stream) {
+  uint64_t* ptr = nullptr;
+  const int rc = scratch_on_current_device(&ptr);
+  if (rc != EMB_OK) return rc;
+  return check_and_launch(desc, indices, offsets, window, k, hot_ids, hot_counts, num_hot, ptr,
+                          kScratchWords, stream);
+}
 
 int64_t emb_bag_profile_hot_rows_workspace(int32_t num_tables, int64_t window, int64_t k) {
   Layout L;
