@@ -107,16 +107,19 @@ typedef struct emb_bag_desc {
                              (the paper finds the top 60K indices per table offline and keeps
                              their rows in L2, Sec. 4.3; emb_bag_profile_hot_rows finds them from
                              a sample batch).  The caller lays the table out with those rows
-                             first and renumbers its row ids to match, once, offline.  Lookups
-                             of rows [0, hot_rows[t]) are then read with the default cache policy
-                             and gathered first, all other rows non-temporally, so that the
-                             stream of cold rows does not push the head out of L2; gfx950 has no
-                             residency control to pin them with.  When given, hot_rows replaces
-                             table_hints: 0 = a streaming table, >= R_t = a table re-used as a
-                             whole.  Speed only: results change by summation order (rounding)
-                             at most.  Honoured by the one-wavefront-per-bag kernel with 32-bit
-                             buffer addressing and a prefetch depth of 4 or 8 (plan->hot_split
-                             says whether); ignored otherwise. */
+                             first and renumbers its row ids to match, once, offline.  gfx950
+                             has no residency control to pin rows with; what the kernels can do
+                             with the head is selected by the "hot_split" tuning key: regroup a
+                             bag's lookups hot rows first, and read the hot rows with the
+                             default cache policy and all others non-temporally so that the
+                             stream of cold rows does not push the head out of L2 (hot_rows then
+                             replaces table_hints: 0 = a streaming table, >= R_t = a table
+                             re-used as a whole).  Measured on MI355X this lowers L2 misses but
+                             not the time, so by default ("hot_split" 0) the field is not used.
+                             Speed only: results change by summation order (rounding) at most.
+                             Honoured by the one-wavefront-per-bag kernel with 32-bit buffer
+                             addressing and a prefetch depth of 4 or 8 (plan->hot_split says
+                             whether); ignored otherwise. */
 } emb_bag_desc;
 
 /*
@@ -423,7 +426,9 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   1 KiB).  The bounds of a wavefront's bags come with one load and the next
  *                   bag's row ids are requested while the current bag's rows are gathered (the
  *                   index prefetch of Sec. 4.2, run across bags).  Same results, bit for bit
- *   "hot_split"     1 (default) = honour desc->hot_rows, 0 = ignore it
+ *   "hot_split"     what the kernels do with desc->hot_rows: 0 (default) = nothing; 1 = a bag's
+ *                   lookups are regrouped hot rows first, hot rows read with the default cache
+ *                   policy, all others non-temporally; 2 = regrouped only, one policy
  * Not thread-safe against concurrent emb_bag_forward calls.
  */
 int emb_bag_set_tuning(const char* key, int64_t value);

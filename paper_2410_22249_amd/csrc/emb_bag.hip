@@ -123,7 +123,7 @@ struct Tuning {
   int64_t per_table_launch = 0; // 1 = one launch per table, as the paper's system does (Sec. 3.1)
   int64_t fuse = 1;             // 1 = the launches of a split call become one launch
   int64_t bags_per_wave = 0;    // wave kernel: consecutive bags per wavefront, 0 = automatic
-  int64_t hot_split = 1;        // 1 = honour desc->hot_rows, 0 = ignore it
+  int64_t hot_split = 0;        // desc->hot_rows: 0 = not used, 1 = regroup + cold rows nt, 2 = regroup
 };
 Tuning g_tuning;
 

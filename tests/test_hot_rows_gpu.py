@@ -14,6 +14,13 @@ from gpu_harness import (DEV, assert_close_to_oracle, device_arena, forward, to_
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True)
+def _split_on():
+    """The split is opt-in (tuning key hot_split, default 0): switched on for these tests."""
+    with tuning(hot_split=1):
+        yield
+
+
 def _problem(dtype="f32", kind=gen.KIND_NORMAL, weighted=False, **over):
     wl = gen.with_overrides(gen.workload("small_hot"), dtype=dtype, kind=kind, weighted=weighted,
                             **over)
@@ -38,9 +45,9 @@ def test_hot_split_matches_oracle(oracle, dtype, D, mode):
     tdt = emb.DTYPES[dtype]
     hot = gen.hot_rows(wl)
     assert _plan_says_hot(wl, batch, hot) == 1
-    for depth in (4, 8):
+    for depth, split in ((4, 1), (8, 1), (8, 2)):
         for bpw in (1, 3):
-            with tuning(depth=depth, bags_per_wave=bpw, stream=0):
+            with tuning(depth=depth, bags_per_wave=bpw, stream=0, hot_split=split):
                 got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B, mode,
                               table_dtype=tdt, hot_rows=hot).cpu().numpy()
             if mode == "max" and dtype not in gen.QUANTISED:
@@ -106,6 +113,8 @@ def test_where_the_hot_split_applies():
     wl, batch, _ = _problem("f32")
     hot = gen.hot_rows(wl)
     assert _plan_says_hot(wl, batch, hot) == 1
+    with tuning(hot_split=2):
+        assert _plan_says_hot(wl, batch, hot) == 1
     for kw in (dict(hot_split=0), dict(addressing=1), dict(depth=2), dict(depth=16)):
         with tuning(**kw):
             assert _plan_says_hot(wl, batch, hot) == 0, kw

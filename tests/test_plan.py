@@ -388,3 +388,36 @@ def test_split_mixed_calls_are_fused_into_one_launch():
     d = emb.make_desc(1100, 512, 64, emb.EMB_F32, emb.EMB_SUM, 1100 * 512 * 10, 0, 1000,
                       table_avg_len=[1.0] * 550 + [100.0] * 550)
     assert emb.emb_bag_plan_forward(d).num_launches == 2 and emb.emb_bag_plan_forward(d).fused == 0
+
+
+def test_the_hot_head_is_opt_in():
+    """desc.hot_rows is used only when the hot_split tuning key asks for it (measured: no gain),
+    and only by the wave kernel with buffer addressing and a depth of 4 or 8."""
+    import torch
+    hot = torch.zeros(60, dtype=torch.int64)                 # (the plan only tests the pointer)
+    desc = emb.make_desc(60, 4096, 128, emb.EMB_F32, emb.EMB_MEAN, 60 * 4096 * 80, 0, 4_000_000,
+                         hot_rows=hot)
+    assert emb.emb_bag_plan_forward(desc).hot_split == 0
+    for mode in (1, 2):
+        with tuning(hot_split=mode):
+            assert emb.emb_bag_plan_forward(desc).hot_split == 1
+            with tuning(depth=2):
+                assert emb.emb_bag_plan_forward(desc).hot_split == 0
+            with tuning(addressing=1):
+                assert emb.emb_bag_plan_forward(desc).hot_split == 0
+    plain = emb.make_desc(60, 4096, 128, emb.EMB_F32, emb.EMB_MEAN, 60 * 4096 * 80, 0, 4_000_000)
+    with tuning(hot_split=1):
+        assert emb.emb_bag_plan_forward(plain).hot_split == 0
+
+
+def test_bags_per_wave_rule():
+    """Automatic bags per wavefront: more for short bags, one for long bags, for rows beyond one
+    slab, and whenever the launch would drop below 32,768 wavefronts."""
+    assert _plan(60, 16384, 64, 20).bags_per_wave == 3        # 5 row loads per bag -> 16 / 5
+    assert _plan(60, 4096, 128, 80).bags_per_wave == 1        # 40 row loads per bag
+    assert _plan(26, 2048, 64, 20.5).bags_per_wave == 1       # 53,248 bags: too few wavefronts
+    assert _plan(8, 256, 64, 20).bags_per_wave == 1
+    assert _plan(4, 100_000, 512, 4).bags_per_wave == 1       # 2 KiB rows: one slab per wavefront
+    with tuning(bags_per_wave=5):
+        p = _plan(8, 256, 64, 20)
+        assert p.bags_per_wave == 5 and p.waves_per_table == -(-256 // 5)
