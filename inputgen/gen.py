@@ -683,9 +683,12 @@ def compact_rows(wl: Workload, batch: Batch, bag_ids: Sequence[int]):
             wsegs.append(batch.weights[s:e])
     arena_rows = np.concatenate(segs) if segs else np.zeros(0, dtype=np.int64)
     uniq, inv = np.unique(arena_rows, return_inverse=True)
-    small = table_values(wl.seed, uniq, wl.D, wl.dtype, wl.kind)
+    step = max(1, (1 << 24) // max(1, wl.D))      # rows per piece: bounded temporaries
+    parts = [table_values(wl.seed, uniq[i:i + step], wl.D, wl.dtype, wl.kind)
+             for i in range(0, max(len(uniq), 1), step)]
+    small = np.concatenate(parts) if len(parts) > 1 else parts[0]
     if len(uniq) == 0:
-        small = np.zeros((1, wl.D), dtype=small.dtype)
+        small = np.zeros((1, small.shape[1]), dtype=small.dtype)
     wsmall = None
     if batch.weights is not None:
         wsmall = np.concatenate(wsegs).astype(np.float32) if wsegs else np.zeros(0, np.float32)

@@ -150,12 +150,15 @@ void oracle_set_num_threads(int n) {
  *   weights        [NL] or NULL (sum mode only)
  *   out_ld         leading dimension of ref / bound in elements (>= T*D)
  *   ref, bound     [B, out_ld] fp64 outputs; only columns [0, T*D) are written
+ *   strict         [B, out_ld] fp64 output or NULL: the sum of |w * element| with the element taken
+ *                  as one number (for quantised rows |scale * value + bias|, which is at most
+ *                  what `bound` charges; the same as `bound` for the other element types)
  * Returns ORACLE_OK or a negative code (bad argument, non-monotone offsets, index out of range).
  */
 int oracle_emb_bag(int32_t T, int64_t B, int32_t D, int32_t dtype, int32_t mode,
                    const void* tables, const int64_t* table_offsets, const int64_t* indices,
                    const int64_t* offsets, const float* weights, int64_t out_ld, double* ref,
-                   double* bound) {
+                   double* bound, double* strict) {
   if (T < 1 || B < 0 || D < 1 || (dtype < 0 || dtype > 4) || (mode < 0 || mode > 2))
     return ORACLE_ERR_ARG;
   if (out_ld < (int64_t)T * D) return ORACLE_ERR_ARG;
@@ -188,6 +191,7 @@ int oracle_emb_bag(int32_t T, int64_t B, int32_t D, int32_t dtype, int32_t mode,
     for (int64_t d = 0; d < D; ++d) {
       double acc = 0.0;
       double mag = 0.0;
+      double smag = 0.0;
       for (int64_t j = s; j < e; ++j) {
         double ax;
         const double x = table_elem(tables, dtype, table_offsets[t] + indices[j], D, d, &ax);
@@ -195,24 +199,29 @@ int oracle_emb_bag(int32_t T, int64_t B, int32_t D, int32_t dtype, int32_t mode,
           if (j == s || x > acc) {
             acc = x;
             mag = ax;
+            smag = fabs(x);
           }
           continue;
         }
         const double w = weights ? (double)weights[j] : 1.0;
         acc += w * x;
         mag += fabs(w) * ax;
+        smag += fabs(w * x);
       }
       if (mode == 1) {
         if (e > s) {
           acc /= (double)(e - s);
           mag /= (double)(e - s);
+          smag /= (double)(e - s);
         } else {
           acc = 0.0;
           mag = 0.0;
+          smag = 0.0;
         }
       }
       ref[b * out_ld + t * D + d] = acc;
       bound[b * out_ld + t * D + d] = mag;
+      if (strict) strict[b * out_ld + t * D + d] = smag;
     }
   }
   return status;

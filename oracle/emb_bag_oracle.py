@@ -37,7 +37,7 @@ def _load() -> ctypes.CDLL:
         lib.oracle_emb_bag.argtypes = [
             ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-            ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+            ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -59,8 +59,10 @@ def _ptr(a: Optional[np.ndarray]):
 def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
             offsets: np.ndarray, B: int, mode: str = "sum",
             weights: Optional[np.ndarray] = None,
-            out_ld: int = 0, codes: str = "u8") -> Tuple[np.ndarray, np.ndarray]:
-    """Reference output and error-bound scale, both fp64 [B, out_ld].
+            out_ld: int = 0, codes: str = "u8", strict: bool = False):
+    """Reference output and error-bound scale, both fp64 [B, out_ld]; with `strict` also the
+    strict bound scale, the sum of |w * element| with a quantised element taken as one number
+    (scale * code + bias) rather than as the two terms an implementation adds.
 
     `codes` says what the bytes of a quantised (uint8) table stand for: "u8" unsigned integers,
     "fp8" OCP E4M3 8-bit floats.
@@ -104,13 +106,14 @@ def emb_bag(tables: np.ndarray, table_offsets: np.ndarray, indices: np.ndarray,
     ld = out_ld if out_ld else T * D
     ref = np.zeros((B, ld), dtype=np.float64)
     bound = np.zeros((B, ld), dtype=np.float64)
+    sbound = np.zeros((B, ld), dtype=np.float64) if strict else None
     rc = _load().oracle_emb_bag(T, B, D, dtype, {"sum": 0, "mean": 1, "max": 2}[mode], _ptr(tables),
                                 _ptr(table_offsets), _ptr(indices), _ptr(offsets),
-                                _ptr(weights), ld, _ptr(ref), _ptr(bound))
+                                _ptr(weights), ld, _ptr(ref), _ptr(bound), _ptr(sbound))
     if rc != 0:
         raise ValueError({-1: "bad argument", -2: "offsets not monotone from 0",
                           -3: "index out of range"}.get(rc, f"oracle error {rc}"))
-    return ref, bound
+    return (ref, bound, sbound) if strict else (ref, bound)
 
 
 def emb_bag_mixed(tables, indices: np.ndarray, offsets: np.ndarray, B: int, mode: str = "sum",

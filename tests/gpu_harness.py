@@ -87,23 +87,42 @@ def forward(arena: torch.Tensor, table_offsets: np.ndarray, indices, offsets, B:
     return out
 
 
+REL_FALLBACK_USED = 0   # elements that only the relative fp16 rule accepted, over the whole run
+
+
 def assert_close_to_oracle(got: np.ndarray, ref: np.ndarray, bound: np.ndarray, f16: bool,
-                           what: str = "") -> float:
-    """Element-by-element check; returns max(err / bound) over elements with bound > 0."""
+                           what: str = "", strict: Optional[np.ndarray] = None,
+                           max_rel_fallback: int = 0) -> float:
+    """Element-by-element check; returns max(err / bound) over elements with bound > 0.
+
+    Every element type is held to |gpu - ref| <= 1e-5 * sum|terms| (accumulation is fp32 whatever
+    the rows are).  The stated rule for fp16 tables, 1e-3 * |ref|, is kept as a fallback for at
+    most `max_rel_fallback` elements (none by default) and the elements that needed it are
+    counted in REL_FALLBACK_USED.  `strict`, where given (quantised rows), is the bound scale with
+    an element taken as one term, |w * (scale * code + bias)|: the same tolerance must hold
+    against it."""
+    global REL_FALLBACK_USED
     got = got.astype(np.float64)
     err = np.abs(got - ref)
     ok = err <= F32_TOL * bound
     if f16:
-        ok |= err <= F16_REL * np.abs(ref)
+        rel = ~ok & (err <= F16_REL * np.abs(ref))
+        used = int(rel.sum())
+        REL_FALLBACK_USED += used
+        assert used <= max_rel_fallback, (f"{what}: {used} elements are within 1e-3 * |ref| but "
+                                          f"not within 1e-5 * sum|terms|")
+        ok |= rel
     if not ok.all():
         bad = np.argwhere(~ok)[0]
         raise AssertionError(f"{what}: {int((~ok).sum())} of {ok.size} elements out of tolerance; "
                              f"first at {tuple(bad)}: got {got[tuple(bad)]!r} ref {ref[tuple(bad)]!r} "
                              f"bound {bound[tuple(bad)]!r}")
+    if strict is not None:
+        worse = err > F32_TOL * strict
+        assert not worse.any(), (f"{what}: {int(worse.sum())} elements exceed 1e-5 * sum|w * x| "
+                                 f"(strict bound); worst ratio {float(np.max(err[worse] / strict[worse]))}")
     zero = bound == 0
     if zero.any():  # empty bags (and all-zero terms) must be exactly +0.0
         assert np.all(got[zero] == 0.0) and not np.signbit(got[zero]).any(), f"{what}: empty bag not +0"
     nz = bound > 0
     return float(np.max(err[nz] / bound[nz])) if nz.any() else 0.0
-
-

@@ -35,7 +35,7 @@ MUTATIONS = {
     "output block of the wrong table": ("ref[b * out_ld + t * D + d] = acc;",
                                         "ref[b * out_ld + (T - 1 - t) * D + d] = acc;"),
     "mean divides by len + 1": ("acc /= (double)(e - s);", "acc /= (double)(e - s + 1);"),
-    "mean of bound forgotten": ("mag /= (double)(e - s);", ""),
+    "mean of bound forgotten": ("          mag /= (double)(e - s);", ""),
     "columns reversed when reading a half row": ("x = half_bits_to_double(((const uint16_t*)tables)[arena_row * D + d]);",
                                                  "x = half_bits_to_double(((const uint16_t*)tables)[arena_row * D + (D - 1 - d)]);"),
     "fp32 rows read with the wrong stride": ("x = (double)((const float*)tables)[arena_row * D + d];",
@@ -52,6 +52,9 @@ MUTATIONS = {
     "e4m3 sign dropped": ("(1 + frac/8) * 2^(expo-7) */\n  return sign ? -v : v;", "(1 + frac/8) * 2^(expo-7) */\n  return v;"),
     "e4m3 treats the whole top exponent as NaN": ("else if (expo == 15 && frac == 7)", "else if (expo == 15)"),
     "e4m3 codes read as integers": ("const double code = dtype == 3 ? (double)row[d] : e4m3_bits_to_double(row[d]);", "const double code = (double)row[d];"),
+    "strict bound without abs": ("smag += fabs(w * x);", "smag += w * x;"),
+    "strict bound charges the two terms": ("smag += fabs(w * x);", "smag += fabs(w) * ax;"),
+    "strict bound of the mean forgotten": ("smag /= (double)(e - s);", ""),
     "weights applied in mean mode only": ("const double w = weights ? (double)weights[j] : 1.0;",
                                           "const double w = (weights && mode == 1) ? (double)weights[j] : 1.0;"),
 }
@@ -68,6 +71,7 @@ PIN_FUNCS = [
     pins.test_empty_and_len1_bags,
     pins.test_weights,
     pins.test_bound_is_sum_of_abs_terms,
+    pins.test_strict_bound_equals_the_bound_for_unquantised_rows,
     pins.test_half_widening_is_exact,
     pins.test_bfloat16_widening_is_exact,
     pins.test_quantised_rows_brute_force,

@@ -260,6 +260,22 @@ def test_bound_is_sum_of_abs_terms(oracle):
     assert np.all(bound >= 0)
 
 
+def test_strict_bound_equals_the_bound_for_unquantised_rows(oracle):
+    """For fp32 / fp16 / bf16 rows an element is one term: the strict scale is the bound itself;
+    for max pooling it is the magnitude of the selected element."""
+    rng = np.random.default_rng(21)
+    T, rows, D, B = 2, [15, 33], 8, 6
+    A, toff, idx, offsets = _rand_problem(rng, T, rows, D, B, 12)
+    w = rng.uniform(-1, 1, len(idx)).astype(np.float32)
+    for mode, weights in (("sum", None), ("sum", w), ("mean", None), ("max", None)):
+        ref, bound, strict = oracle.emb_bag(A, toff, idx, offsets, B, mode, weights=weights, strict=True)
+        assert np.array_equal(bound, strict)
+        if mode == "max":
+            assert np.array_equal(strict, np.abs(ref))
+    ref, bound, strict = oracle.emb_bag(A.astype(np.float16), toff, idx, offsets, B, "sum", strict=True)
+    assert np.array_equal(bound, strict)
+
+
 def test_second_opinion_sparse_matmul(oracle):
     """Per table, sum pooling is (bag-incidence CSR matrix) x (table): a library SpMM."""
     import scipy.sparse as sp
@@ -363,24 +379,30 @@ def test_quantised_rows_brute_force(oracle):
                           rng.integers(0, 4, size=lengths[4:].sum())]).astype(np.int64)
     w = rng.uniform(-1, 1, size=len(idx)).astype(np.float32)
     for mode, weights in (("sum", None), ("mean", None), ("sum", w)):
-        ref, bound = oracle.emb_bag(table, toff, idx, offsets, B, mode, weights=weights)
+        ref, bound, strict = oracle.emb_bag(table, toff, idx, offsets, B, mode, weights=weights,
+                                            strict=True)
         for t in range(2):
             for b in range(B):
                 lo, hi = int(offsets[t * B + b]), int(offsets[t * B + b + 1])
                 for d in range(D):
                     a = Fraction(0)
                     m = Fraction(0)
+                    sm = Fraction(0)             # the strict scale: |w * element|, one term each
                     for j in range(lo, hi):
                         r = int(toff[t]) + int(idx[j])
                         ww = Fraction(float(weights[j])) if weights is not None else Fraction(1)
                         sc = Fraction(float(scale[r])) * int(table[r, d])
                         a += ww * (sc + Fraction(float(bias[r])))
                         m += abs(ww) * (abs(sc) + abs(Fraction(float(bias[r]))))
+                        sm += abs(ww * (sc + Fraction(float(bias[r]))))
                     if mode == "mean" and hi > lo:
-                        a, m = a / (hi - lo), m / (hi - lo)
+                        a, m, sm = a / (hi - lo), m / (hi - lo), sm / (hi - lo)
                     tol = 16 * 2.0 ** -53 * float(m) + 1e-300
                     assert abs(ref[b, t * D + d] - float(a)) <= tol
                     assert abs(bound[b, t * D + d] - float(m)) <= tol
+                    assert abs(strict[b, t * D + d] - float(sm)) <= tol
+        assert np.all(strict <= bound * (1 + 1e-15)) and np.all(np.abs(ref) <= strict * (1 + 1e-12) + 1e-300)
+        assert np.any(strict < 0.9 * bound)       # scale * code and bias have opposite signs here
 
 
 def test_quantised_rows_equal_their_dequantised_table(oracle):
