@@ -21,7 +21,8 @@ TARGETS = {
     # (-DEMB_LPR=n), as is the fused kernel for one width; the fused kernel for different widths
     # once per element type (-DEMB_ELEM=n).
     "paper_2410_22249_amd/libembbag.so":
-        [(CSRC + "emb_bag.hip", None), (CSRC + "emb_bag_hot_rows.hip", None)]
+        [(CSRC + "emb_bag.hip", None), (CSRC + "emb_bag_plan.cpp", None),
+         (CSRC + "emb_bag_hot_rows.hip", None)]
         + [(CSRC + "emb_bag_wave.hip", n) for n in (0, 4, 8, 16, 32, 64)]
         + [(CSRC + "emb_bag_stream.hip", n) for n in (4, 8, 16, 32, 64)]
         + [(CSRC + "emb_bag_fused.hip", n) for n in (0, 1, 2, 3, 4)]
