@@ -216,6 +216,10 @@ int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
 /*
  * emb_bag_validate - count the data-dependent defects emb_bag_forward neutralises.
  *
+ *   No passage of the paper defines this call: its inputs are traces that are well-formed by
+ *   construction (Sec. 3.2, Sec. 5).  It checks the two arrays of the pointer chase of Sec. 3.1
+ *   (offsets -> indices -> table) against the properties the forward call assumes.
+ *
  *   Adds to *num_bad (DEVICE, one int64 that the caller has zeroed, on the same stream) one for
  *   every bag whose bounds are decreasing or outside [0, NL], one if offsets[0] != 0 or
  *   offsets[T*B] != NL, and one for every lookup whose index is outside [0, R_t).
@@ -390,8 +394,8 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  * prefetch-depth search of paper Sec. 3.3, Sec. 4.2 and the recipe of Sec. 7, made a runtime
  * knob).  Keys (HOST strings):
  *   "depth"         row loads a wavefront keeps in flight: 1, 2, 4, 8 or 16; 0 = automatic
- *   "addressing"    0 = automatic, 1 = force 64-bit global addressing, 2 = force buffer
- *                   addressing where the sizes allow it
+ *   "addressing"    0 = automatic (32-bit buffer addressing whenever the descriptor bounds the
+ *                   largest table below 3.5 GiB, else 64-bit), 1 = force 64-bit global addressing
  *   "blocks_per_cu" cap on resident 256-thread workgroups per compute unit, 1..8; 0 = no cap
  *   "xcd_remap"     1 = XCD-affine order: a table's bags are dealt to one or two XCDs, so its hot
  *                   rows are fetched into one or two of the eight L2s instead of all eight
@@ -434,10 +438,33 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
 int emb_bag_set_tuning(const char* key, int64_t value);
 int emb_bag_get_tuning(const char* key, int64_t* value);
 
-/* Static, NUL-terminated description of a status code (never NULL). */
+/*
+ * emb_bag_set_tuning_table - per-shape tuning found by a sweep (the outcome of the paper's
+ * profiling recipe, Sec. 7 steps ii-vii: multithreading level, prefetch distance and scheme per
+ * workload; python -m paper_2410_22249_amd.autotune --table writes one).  Entry i covers calls
+ * whose rows are at most max_row_bytes bytes (the widest row of emb_bag_forward_mixed) and whose
+ * average bag length num_lookups / (T * batch) is at most max_avg_len; the FIRST entry that
+ * covers a call supplies the keys that emb_bag_set_tuning has left at their automatic value
+ * (depth 0, bags_per_wave 0, stream -1, bags_per_group 0); a key set there explicitly wins.
+ * The library keeps its own copy of at most 64 entries; n = 0 clears the table.  HOST pointer.
+ * Results never depend on the table (speed only; the short-bag kernel rounds differently from the
+ * one-wavefront-per-bag kernel, see "stream").  Not thread-safe against concurrent forward calls.
+ */
+typedef struct emb_bag_tuning_entry {
+  int32_t max_row_bytes;  /* >= 16 */
+  float max_avg_len;      /* >= 0 */
+  int32_t depth;          /* 0 (automatic), 1, 2, 4, 8 or 16 */
+  int32_t bags_per_wave;  /* 0 (automatic) .. 32 */
+  int32_t stream;         /* -1 (automatic), 0 or 1 */
+  int32_t bags_per_group; /* 0 (automatic) .. 63 */
+} emb_bag_tuning_entry;
+int emb_bag_set_tuning_table(const emb_bag_tuning_entry* entries, int32_t n);
+
+/* Static, NUL-terminated description of a status code (never NULL).  Library plumbing: no
+   passage of the paper stands behind it. */
 const char* emb_bag_status_string(int status);
 
-/* Library version: major*10000 + minor*100 + patch. */
+/* Library version: major*10000 + minor*100 + patch.  Library plumbing, as above. */
 int emb_bag_version(void);
 
 #ifdef __cplusplus

@@ -7,6 +7,7 @@ from .binding import (EMB_BF16, EMB_F16, EMB_F32, EMB_HINT_DEFAULT, EMB_HINT_STR
                       emb_bag_plan_forward, emb_bag_plan_forward_mixed, EMB_KERNEL_WAVE,
                       EMB_KERNEL_STREAM,
                       emb_bag_mixed_desc, make_mixed_desc, emb_bag_get_tuning, emb_bag_set_tuning,
+                      emb_bag_set_tuning_table, emb_bag_tuning_entry,
                       emb_bag_status_string, emb_bag_validate, emb_bag_version, lib, make_desc)
 from . import metrics
 
@@ -15,6 +16,7 @@ __all__ = ["EMB_U8ROW", "EMB_FP8ROW", "DTYPES", "EMB_BF16", "EMB_F16", "EMB_F32"
            "emb_bag_desc", "emb_bag_forward", "emb_bag_forward_mixed", "emb_bag_mixed_desc",
            "emb_bag_plan", "emb_bag_plan_forward", "emb_bag_plan_forward_mixed", "EMB_KERNEL_WAVE",
            "EMB_KERNEL_STREAM",
-           "make_mixed_desc", "emb_bag_get_tuning", "emb_bag_set_tuning",
+           "make_mixed_desc", "emb_bag_get_tuning", "emb_bag_set_tuning", "emb_bag_set_tuning_table",
+           "emb_bag_tuning_entry",
            "emb_bag_status_string", "emb_bag_validate", "emb_bag_version", "lib", "make_desc",
            "metrics"]

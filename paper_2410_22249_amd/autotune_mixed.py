@@ -1,8 +1,8 @@
 """Tables of different widths in one launch (`emb_bag_forward_mixed`) against one uniform launch per
 width, on one MI355X.
 
-    python -m paper_2410_22249_amd.mixed_bench [--steps 20]
-    python -m paper_2410_22249_amd.mixed_bench --split-sweep
+    python -m paper_2410_22249_amd.autotune mixed [--steps 20]
+    python -m paper_2410_22249_amd.autotune mixed --split-sweep
 
 Workload "mixed_cfg": 60 fp32 tables x 4,000,000 rows, widths cycling 32 / 64 / 128 / 256, batch
 4096, pooling 80, uniform indices (the paper's model has one width, Sec. 5; production models mix
@@ -96,7 +96,7 @@ def split_sweep(steps: int, warmup: int) -> int:
     return 0
 
 
-def main() -> int:
+def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--split-sweep", action="store_true",
                     help="fused launch against separate launches over batch sizes (mixed_onehot)")
@@ -105,7 +105,7 @@ def main() -> int:
     ap.add_argument("--batches", type=int, default=4)
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="emb_bag_set_tuning override, e.g. --tune xcd_remap=0")
-    a = ap.parse_args()
+    a = ap.parse_args(argv)
     if a.split_sweep:
         return split_sweep(max(a.steps, 50), max(a.warmup, 5))
 

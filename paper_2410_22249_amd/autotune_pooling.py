@@ -1,6 +1,6 @@
 """The two forward kernels over the pooling factor (lookups per bag) and the row width, one MI355X.
 
-    python -m paper_2410_22249_amd.pooling_sweep [--lookups 4000000] [--steps 15]
+    python -m paper_2410_22249_amd.autotune pooling [--lookups 4000000] [--steps 15]
 
 The paper fixes the pooling factor at 150 and studies it only for L2 pinning (Sec. 4.3, the
 figure of speedup against pooling factor): short bags are where the per-bag chain bag bounds ->
@@ -22,14 +22,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-def main() -> int:
+def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--lookups", type=int, default=4_000_000)
     ap.add_argument("--steps", type=int, default=15)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--dims", default="32,64,128,256")
     ap.add_argument("--pooling", default="1,2,4,8,16,32,64")
-    a = ap.parse_args()
+    a = ap.parse_args(argv)
 
     import numpy as np
     import torch

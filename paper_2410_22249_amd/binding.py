@@ -29,7 +29,7 @@ EXPORTS = ("emb_bag_forward", "emb_bag_forward_mixed", "emb_bag_plan_forward",
            "emb_bag_plan_forward_mixed", "emb_bag_validate", "emb_bag_profile_reuse",
            "emb_bag_profile_hot_rows", "emb_bag_profile_hot_rows_workspace",
            "emb_bag_profile_hot_rows_noalloc",
-           "emb_bag_set_tuning", "emb_bag_get_tuning", "emb_bag_status_string", "emb_bag_version")
+           "emb_bag_set_tuning", "emb_bag_get_tuning", "emb_bag_set_tuning_table", "emb_bag_status_string", "emb_bag_version")
 
 
 class emb_bag_desc(ctypes.Structure):
@@ -64,6 +64,12 @@ class emb_bag_plan(ctypes.Structure):
 
     def as_dict(self) -> dict:
         return {name: int(getattr(self, name)) for name, _ in self._fields_}
+
+
+class emb_bag_tuning_entry(ctypes.Structure):
+    _fields_ = [("max_row_bytes", ctypes.c_int32), ("max_avg_len", ctypes.c_float),
+                ("depth", ctypes.c_int32), ("bags_per_wave", ctypes.c_int32),
+                ("stream", ctypes.c_int32), ("bags_per_group", ctypes.c_int32)]
 
 
 class EmbBagError(RuntimeError):
@@ -103,6 +109,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
                                                      ctypes.c_int64, ctypes.c_int64, P, P, P, P]
     lib.emb_bag_set_tuning.restype = ctypes.c_int
     lib.emb_bag_set_tuning.argtypes = [ctypes.c_char_p, ctypes.c_int64]
+    lib.emb_bag_set_tuning_table.restype = ctypes.c_int
+    lib.emb_bag_set_tuning_table.argtypes = [ctypes.POINTER(emb_bag_tuning_entry), ctypes.c_int32]
     lib.emb_bag_get_tuning.restype = ctypes.c_int
     lib.emb_bag_get_tuning.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64)]
     lib.emb_bag_status_string.restype = ctypes.c_char_p
@@ -294,6 +302,19 @@ def emb_bag_set_tuning(key: str, value: int) -> None:
     rc = _lib.emb_bag_set_tuning(key.encode(), int(value))
     if rc != EMB_OK:
         raise EmbBagError(rc, f"emb_bag_set_tuning({key!r}, {value})")
+
+
+def emb_bag_set_tuning_table(entries) -> None:
+    """Load a tuning table: a sequence of dicts with the fields of emb_bag_tuning_entry (missing
+    fields mean "automatic"); an empty sequence clears it."""
+    auto = {"depth": 0, "bags_per_wave": 0, "stream": -1, "bags_per_group": 0}
+    arr = (emb_bag_tuning_entry * max(len(entries), 1))()
+    for i, e in enumerate(entries):
+        arr[i] = emb_bag_tuning_entry(int(e["max_row_bytes"]), float(e["max_avg_len"]),
+                                      *[int(e.get(k, v)) for k, v in auto.items()])
+    rc = _lib.emb_bag_set_tuning_table(arr, len(entries))
+    if rc != EMB_OK:
+        raise EmbBagError(rc, "emb_bag_set_tuning_table")
 
 
 def emb_bag_get_tuning(key: str) -> int:

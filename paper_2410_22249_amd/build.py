@@ -1,9 +1,12 @@
 """Build the in-tree HIP shared libraries for gfx950 with hipcc (no JIT, no torch extension)."""
 from __future__ import annotations
 
+import hashlib
+import json
 import os
 import subprocess
 import sys
+import tempfile
 import time
 
 PKG = os.path.dirname(os.path.abspath(__file__))
@@ -53,13 +56,21 @@ def build_c_driver(verbose: bool = True) -> None:
 
 
 def _run(cmd, verbose: bool):
+    """Start a compiler; its output goes to a temporary file (a pipe that nobody reads while the
+    process runs would stall a compile that prints more than the pipe holds)."""
     if verbose:
         print("[build]", " ".join(cmd), flush=True)
-    return subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    log = tempfile.TemporaryFile(mode="w+")
+    proc = subprocess.Popen(cmd, stdout=log, stderr=subprocess.STDOUT, text=True)
+    proc.log = log
+    return proc
 
 
 def _finish(proc, what: str, verbose: bool) -> None:
-    out, _ = proc.communicate()
+    proc.wait()
+    proc.log.seek(0)
+    out = proc.log.read()
+    proc.log.close()
     # the host pass does not know the packed-fp32 feature and says so: harmless noise
     log = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
     if log.strip() and (verbose or proc.returncode):
@@ -101,12 +112,60 @@ def build_all(verbose: bool = True) -> None:
         _finish(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o",
                       os.path.join(ROOT, out)] + objs, verbose), out, verbose)
     build_c_driver(verbose)
+    with open(MANIFEST, "w") as fh:
+        json.dump(_hashes(), fh, indent=0)
+
+
+def _sources():
+    """Every file a library is built from: the listed sources, the headers beside them and the
+    C-ABI header."""
+    files = {os.path.join(ROOT, "include", "emb_bag.h")}
+    for srcs in TARGETS.values():
+        for src, _ in srcs:
+            files.add(os.path.join(ROOT, src))
+            d = os.path.dirname(os.path.join(ROOT, src))
+            files.update(os.path.join(d, f) for f in os.listdir(d) if f.endswith(".h"))
+    files.update(os.path.join(ROOT, src) for src in C_PROGRAMS.values())
+    return files
+
+
+MANIFEST = os.path.join(PKG, "build_manifest.json")   # content hashes of the sources last built
+
+
+def _hashes() -> dict:
+    out = {}
+    for f in sorted(_sources()):
+        with open(f, "rb") as fh:
+            out[os.path.relpath(f, ROOT)] = hashlib.sha256(fh.read()).hexdigest()
+    return out
+
+
+def stale() -> list:
+    """Sources whose content differs from what the libraries were built from (by content hash,
+    so that copying the tree to another machine does not make them look old or new)."""
+    outs = [os.path.join(ROOT, out) for out in list(TARGETS) + list(C_PROGRAMS)]
+    if not all(os.path.exists(o) for o in outs) or not os.path.exists(MANIFEST):
+        return ["(a library is missing)"]
+    with open(MANIFEST) as fh:
+        built = json.load(fh)
+    now = _hashes()
+    return sorted(f for f in set(now) | set(built) if now.get(f) != built.get(f))
 
 
 def ensure_built(verbose: bool = True) -> None:
-    """Build only if a library is missing (tests, smoke() and bench.py load what is there)."""
-    if not all(os.path.exists(os.path.join(ROOT, out)) for out in list(TARGETS) + [C_DRIVER_BIN]):
+    """Tests, smoke() and bench.py load what is built.  Nothing built: build.  Built from older
+    sources than those on disk: build again where a compiler is at hand, otherwise refuse to run
+    an out-of-date binary silently."""
+    old = stale()
+    if not old:
+        return
+    if os.path.exists(HIPCC):
+        if verbose or old != ["(a library is missing)"]:
+            print(f"[build] rebuilding: changed since the last build: {', '.join(old[:6])}", flush=True)
         build_all(verbose=verbose)
+    else:
+        raise RuntimeError("the built libraries do not match " + ", ".join(old[:6]) +
+                           " and there is no hipcc here: run __graft_entry__.build()")
 
 
 if __name__ == "__main__":

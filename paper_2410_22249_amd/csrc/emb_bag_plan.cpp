@@ -13,6 +13,27 @@ namespace host {
 
 Tuning g_tuning;
 
+// The tuning table (emb_bag_set_tuning_table): what a sweep found best per shape.  An entry covers
+// rows of at most max_row_bytes bytes and calls whose average bag length is at most max_avg_len;
+// the first entry that covers a call supplies the keys that emb_bag_set_tuning has left automatic.
+constexpr int kMaxTableEntries = 64;
+emb_bag_tuning_entry g_table[kMaxTableEntries];
+int g_table_entries = 0;
+
+Tuning effective_tuning(uint32_t row_bytes, double avg_len) {
+  Tuning tu = g_tuning;
+  for (int i = 0; i < g_table_entries; ++i) {
+    const emb_bag_tuning_entry& e = g_table[i];
+    if ((int64_t)row_bytes > (int64_t)e.max_row_bytes || avg_len > (double)e.max_avg_len) continue;
+    if (tu.depth == 0 && e.depth != 0) tu.depth = e.depth;
+    if (tu.bags_per_wave == 0 && e.bags_per_wave != 0) tu.bags_per_wave = e.bags_per_wave;
+    if (tu.stream == -1 && e.stream != -1) tu.stream = e.stream;
+    if (tu.bags_per_group == 0 && e.bags_per_group != 0) tu.bags_per_group = e.bags_per_group;
+    break;
+  }
+  return tu;
+}
+
 // When the short-bag kernel is chosen (measured on MI355X over row widths 128 B .. 1 KiB and
 // pooling 1 .. 80): the wave kernel fetches G = 64/LPR rows of a bag per load instruction and
 // needs about three such instructions per bag to hide its per-bag chain, so the stream kernel
@@ -158,9 +179,10 @@ void plan_grid(int64_t n, const uint16_t* ids, const uint16_t* row_units, bool n
 }
 
 // Consecutive bags per lane group of the stream kernel for an average bag length.
-int64_t stream_bags_per_group(double avg_len, int lpr, int64_t tables, int64_t B) {
+int64_t stream_bags_per_group(const Tuning& tu, double avg_len, int lpr, int64_t tables,
+                              int64_t B) {
   const int groups = kWaveSize / lpr;
-  int64_t m = g_tuning.bags_per_group;
+  int64_t m = tu.bags_per_group;
   if (m == 0) {
     m = (int64_t)(kStreamGroupLookups / (avg_len < 1.0 ? 1.0 : avg_len) + 0.5);
     if (m > kStreamMaxAutoBags) m = kStreamMaxAutoBags;
@@ -180,10 +202,10 @@ constexpr double kWaveLoadsTarget = 16.0;
 constexpr int64_t kWaveMaxAutoBags = 4;
 constexpr int64_t kWaveMinWaves = 32768;
 constexpr int64_t kWaveMaxBags = 32;
-int64_t wave_bags_per_wave(double avg_len, int rows_per_load, int64_t tables, int64_t B,
-                           int64_t slabs) {
+int64_t wave_bags_per_wave(const Tuning& tu, double avg_len, int rows_per_load, int64_t tables,
+                           int64_t B, int64_t slabs) {
   if (slabs > 1) return 1;
-  int64_t m = g_tuning.bags_per_wave;
+  int64_t m = tu.bags_per_wave;
   if (m == 0) {
     const double loads = (avg_len < 1.0 ? 1.0 : avg_len) / rows_per_load;
     m = (int64_t)(kWaveLoadsTarget / loads + 0.5);
@@ -230,11 +252,11 @@ void add_launches(const Launch& proto, int64_t T, const std::vector<uint16_t>& i
 
 // Turn `proto` (a wave-kernel launch of a uniform call) into a stream-kernel launch over
 // `tables` tables of average bag length avg_len; false if the stream kernel cannot take it.
-bool make_stream(Launch* L, const emb_bag_desc* desc, bool weighted, int depth, double avg_len,
-                 int64_t tables, int64_t out_ld) {
+bool make_stream(const Tuning& tu, Launch* L, const emb_bag_desc* desc, bool weighted, int depth,
+                 double avg_len, int64_t tables, int64_t out_ld) {
   const int lpr = L->lpr, groups = kWaveSize / lpr;
   const int64_t B = desc->batch;
-  const int64_t m = stream_bags_per_group(avg_len, lpr, tables, B);
+  const int64_t m = stream_bags_per_group(tu, avg_len, lpr, tables, B);
   // the wavefront's output rows are addressed through one buffer with 32-bit offsets
   if ((uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u > kBufMaxBytes) return false;
   KernelFn fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted, false);
@@ -267,7 +289,9 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
              (uint64_t)desc->max_table_rows * row_bytes <= kBufMaxBytes;
   if (g_tuning.addressing == 1) buf = false;
 
-  int depth = (int)g_tuning.depth;
+  // the tuning keys, with the keys left automatic filled in from the tuning table
+  const Tuning tu = effective_tuning(row_bytes, (double)desc->num_lookups / ((double)T * (double)B));
+  int depth = (int)tu.depth;
   if (depth == 0) depth = (desc->table_dtype == EMB_F32 && row_bytes >= 512) ? 8 : 4;
 
   Launch wave;  // the one-wavefront-per-bag launch; the stream launch is derived from it
@@ -285,7 +309,7 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   p.bags_per_group = 0;
   const int groups = kWaveSize / lpr;
   const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
-  p.bags_per_wave = (uint32_t)wave_bags_per_wave(avg_len, groups, T, B, slabs);
+  p.bags_per_wave = (uint32_t)wave_bags_per_wave(tu, avg_len, groups, T, B, slabs);
   if (slabs == 1) p.wpt = (uint32_t)((B + p.bags_per_wave - 1) / p.bags_per_wave);
   wave.kernel = EMB_KERNEL_WAVE;
   wave.lpr = lpr;
@@ -305,18 +329,18 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   // per-table lengths the host knows the call's average bag length, NL / (T * B), and nothing
   // else; with them each table is judged by its own.
   const double threshold = kStreamBelowRowLoads * groups;
-  const bool can_stream = g_tuning.stream != 0 && slabs == 1 && buf && desc->mode != EMB_MAX;
+  const bool can_stream = tu.stream != 0 && slabs == 1 && buf && desc->mode != EMB_MAX;
   const std::vector<uint16_t> none;
   if (g_tuning.per_table_launch == 1 && T <= 65535) {
     // the paper's launch structure, for comparison: the tables one after the other
     Launch stream = wave;
-    const bool s = can_stream && (g_tuning.stream == 1 || avg_len < threshold) &&
-                   make_stream(&stream, desc, weighted, depth, avg_len, 1, out_ld);
+    const bool s = can_stream && (tu.stream == 1 || avg_len < threshold) &&
+                   make_stream(tu, &stream, desc, weighted, depth, avg_len, 1, out_ld);
     for (int64_t t = 0; t < T; ++t)
       add_launches(s ? stream : wave, T, std::vector<uint16_t>(1, (uint16_t)t), none, launches);
     return EMB_OK;
   }
-  if (can_stream && g_tuning.stream == -1 && desc->table_avg_len && T <= 65535) {
+  if (can_stream && tu.stream == -1 && desc->table_avg_len && T <= 65535) {
     std::vector<uint16_t> short_ids, long_ids;
     double short_sum = 0.0, long_sum = 0.0;
     for (int64_t t = 0; t < T; ++t) {
@@ -330,10 +354,10 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
     }
     Launch stream = wave;
     if (!short_ids.empty() && !long_ids.empty() &&
-        make_stream(&stream, desc, weighted, depth, short_sum / (double)short_ids.size(),
+        make_stream(tu, &stream, desc, weighted, depth, short_sum / (double)short_ids.size(),
                     (int64_t)short_ids.size(), out_ld)) {
       // the wave part's bags per wavefront follow its own tables
-      p.bags_per_wave = (uint32_t)wave_bags_per_wave(long_sum / (double)long_ids.size(), groups,
+      p.bags_per_wave = (uint32_t)wave_bags_per_wave(tu, long_sum / (double)long_ids.size(), groups,
                                                      (int64_t)long_ids.size(), B, slabs);
       p.wpt = (uint32_t)((B + p.bags_per_wave - 1) / p.bags_per_wave);
       add_launches(wave, T, long_ids, none, launches);  // listed in the order a fused launch
@@ -341,15 +365,15 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
       return EMB_OK;
     }
     // all tables on one side: one launch without a list
-    if (long_ids.empty() && make_stream(&stream, desc, weighted, depth, avg_len, T, out_ld))
+    if (long_ids.empty() && make_stream(tu, &stream, desc, weighted, depth, avg_len, T, out_ld))
       add_launches(stream, T, none, none, launches);
     else
       add_launches(wave, T, none, none, launches);
     return EMB_OK;
   }
   Launch stream = wave;
-  if (can_stream && (g_tuning.stream == 1 || avg_len < threshold) &&
-      make_stream(&stream, desc, weighted, depth, avg_len, T, out_ld))
+  if (can_stream && (tu.stream == 1 || avg_len < threshold) &&
+      make_stream(tu, &stream, desc, weighted, depth, avg_len, T, out_ld))
     add_launches(stream, T, none, none, launches);
   else
     add_launches(wave, T, none, none, launches);
@@ -395,7 +419,9 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
   const int elem_bytes = desc->table_dtype == EMB_F32 ? 4 : 2;
   bool buf = desc->max_table_bytes > 0 && (uint64_t)desc->max_table_bytes <= kBufMaxBytes;
   if (g_tuning.addressing == 1) buf = false;
-  int depth = (int)g_tuning.depth;
+  const Tuning tu = effective_tuning(max_row_bytes,
+                                     (double)desc->num_lookups / ((double)T * (double)B));
+  int depth = (int)tu.depth;
   if (depth == 0) depth = (desc->table_dtype == EMB_F32 && max_row_bytes >= 512) ? 8 : 4;
   const int op = desc->mode == EMB_MAX ? kOpMax : (weighted ? kOpWeighted : kOpSum);
 
@@ -423,18 +449,18 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
   {
     int wide_lpr = 4;  // bags per wavefront: judged by the widest row (the fewest rows per load)
     while ((uint32_t)wide_lpr * 16u < max_row_bytes) wide_lpr *= 2;
-    p.bags_per_wave = (uint32_t)wave_bags_per_wave(avg_len, kWaveSize / wide_lpr, T, B, 1);
+    p.bags_per_wave = (uint32_t)wave_bags_per_wave(tu, avg_len, kWaveSize / wide_lpr, T, B, 1);
     p.wpt = (uint32_t)((B + p.bags_per_wave - 1) / p.bags_per_wave);
   }
   // (judged by the call's average bag length, or table by table with desc->table_avg_len)
-  const bool can_stream = g_tuning.stream != 0 && buf && desc->mode != EMB_MAX;
-  const bool per_table = g_tuning.stream == -1 && desc->table_avg_len != nullptr;
+  const bool can_stream = tu.stream != 0 && buf && desc->mode != EMB_MAX;
+  const bool per_table = tu.stream == -1 && desc->table_avg_len != nullptr;
   bool fits[7] = {false, false, false, false, false, false, false};  // by log2(lanes per row)
   for (int lg = 2; lg <= 6 && can_stream; ++lg) {
     // the wavefront's output rows are addressed through one buffer with 32-bit offsets: checked
     // for the largest group size the class can get
     const int groups = kWaveSize >> lg;
-    int64_t m = g_tuning.bags_per_group ? g_tuning.bags_per_group : kStreamMaxAutoBags;
+    int64_t m = tu.bags_per_group ? tu.bags_per_group : kStreamMaxAutoBags;
     if (m > (1 << lg) - 1) m = (1 << lg) - 1;
     fits[lg] = (uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u <= kBufMaxBytes;
   }
@@ -451,7 +477,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
     cls[(size_t)t] = (uint8_t)lg;
     if (d != desc->dims[0]) widths_differ = true;
     const double len_t = per_table ? (double)desc->table_avg_len[t] : avg_len;
-    streamed[(size_t)t] = fits[lg] && (g_tuning.stream == 1 ||
+    streamed[(size_t)t] = fits[lg] && (tu.stream == 1 ||
                                        len_t < kStreamBelowRowLoads * (kWaveSize >> lg));
     if (streamed[(size_t)t]) any_stream = true;
   }
@@ -482,7 +508,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
     if (lg >= 2) {
       const int lpr = 1 << lg;
       const int groups = kWaveSize / lpr;
-      const int64_t m = stream_bags_per_group(len_sum / (double)ids.size(), lpr,
+      const int64_t m = stream_bags_per_group(tu, len_sum / (double)ids.size(), lpr,
                                               (int64_t)ids.size(), B);
       L.fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted, true);
       if (!L.fn) return EMB_ERR_BAD_TUNING;
@@ -649,7 +675,7 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
       return EMB_ERR_BAD_TUNING;
     g_tuning.depth = value;
   } else if (!strcmp(key, "addressing")) {
-    if (value < 0 || value > 2) return EMB_ERR_BAD_TUNING;
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
     g_tuning.addressing = value;
   } else if (!strcmp(key, "blocks_per_cu")) {
     if (value < 0 || value > 8) return EMB_ERR_BAD_TUNING;
@@ -685,6 +711,23 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
   } else {
     return EMB_ERR_BAD_TUNING;
   }
+  return EMB_OK;
+}
+
+int emb_bag_set_tuning_table(const emb_bag_tuning_entry* entries, int32_t n) {
+  if (n < 0 || n > kMaxTableEntries) return EMB_ERR_BAD_SIZE;
+  if (n > 0 && !entries) return EMB_ERR_NULL_PTR;
+  for (int32_t i = 0; i < n; ++i) {
+    const emb_bag_tuning_entry& e = entries[i];
+    const bool depth_ok = e.depth == 0 || e.depth == 1 || e.depth == 2 || e.depth == 4 ||
+                          e.depth == 8 || e.depth == 16;
+    if (e.max_row_bytes < 16 || !(e.max_avg_len >= 0.0f) || !depth_ok || e.bags_per_wave < 0 ||
+        e.bags_per_wave > kWaveMaxBags || e.stream < -1 || e.stream > 1 || e.bags_per_group < 0 ||
+        e.bags_per_group > 63)
+      return EMB_ERR_BAD_TUNING;
+  }
+  for (int32_t i = 0; i < n; ++i) g_table[i] = entries[i];
+  g_table_entries = n;
   return EMB_OK;
 }
 
