@@ -49,6 +49,10 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", required=True)
     ap.add_argument("--kernel-stats")
+    ap.add_argument("--kernel-trace", help="the per-dispatch trace of the same run")
+    ap.add_argument("--last", type=int, default=40,
+                    help="dispatches of the forward kernel, counted from the end of the trace, that "
+                         "were bench.py's timed steps (warm-up and arena-pick probes come before)")
     ap.add_argument("--fetch")
     ap.add_argument("--write")
     ap.add_argument("--counters", action="append", default=[])
@@ -69,6 +73,17 @@ def main() -> int:
             print(f"{short(r['Name'])[:70]:70s} {int(r['Calls']):6d} {float(r['AverageNs']) / 1e3:10.1f} "
                   f"{float(r['MinNs']) / 1e3:10.1f} {float(r['MaxNs']) / 1e3:10.1f} "
                   f"{float(r['Percentage']):6.2f}")
+
+    if a.kernel_trace:
+        per = defaultdict(list)
+        for r in csv.DictReader(open(a.kernel_trace)):
+            if any(e in r["Kernel_Name"] for e in EMB):
+                per[r["Kernel_Name"]].append((int(r["Start_Timestamp"]), int(r["End_Timestamp"])))
+        print(f"\n## the last {a.last} dispatches of each forward kernel (bench.py's timed steps)")
+        for k, spans in per.items():
+            d = [(e - s) / 1e3 for s, e in sorted(spans)[-a.last:]]
+            print(f"{short(k)[:70]:70s} {len(d):6d} {statistics.mean(d):10.1f} {min(d):10.1f} "
+                  f"{max(d):10.1f}   (avg_us min_us max_us)")
 
     traffic = {}
     for label, path, counter in (("fetch", a.fetch, "FETCH_SIZE"), ("write", a.write, "WRITE_SIZE")):
