@@ -191,9 +191,12 @@ def run_workload(args, name: str, steps: int, warmup: int, headline: bool):
     hints = None
     if not args.no_hints:
         hints = torch.zeros(wl.T, dtype=torch.uint8, device=dev)
-        d0 = emb.make_desc(wl.T, wl.B, 4 if mixed else wl.D, emb.EMB_F32 if mixed else edt, emode,
-                           batches[0].num_lookups, 0, max(wl.rows))   # the profile reads ids only
-        emb.emb_bag_profile_reuse(d0, dbatches[0][0], dbatches[0][1], 4096, -1, None, None, hints,
+        # the profile reads ids and the row size (tables of different widths: the narrowest,
+        # which streams the fewest tables)
+        d0 = emb.make_desc(wl.T, wl.B, min(wl.row_bytes_of(t) for t in range(wl.T)) // 4 if mixed
+                           else wl.D, emb.EMB_F32 if mixed else edt, emode,
+                           batches[0].num_lookups, 0, max(wl.rows))
+        emb.emb_bag_profile_reuse(d0, dbatches[0][0], dbatches[0][1], 16384, -1, None, None, hints,
                                   stream)
         stream.synchronize()
         log(f"table hints: {int(hints.sum().item())} of {wl.T} tables streaming")

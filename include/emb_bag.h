@@ -236,26 +236,36 @@ int emb_bag_validate(const emb_bag_desc* desc, const int64_t* table_offsets,
  * emb_bag_profile_reuse - measure how often each table's lookups repeat, and derive hints.
  *
  *   For every table t the first `window` lookups of the batch that go to t (fewer if the table
- *   receives fewer; window is clamped to [1, 4096]) are examined:
+ *   receives fewer; window is clamped to [1, 16384]) are examined.  With n_t the number of
+ *   lookups the whole batch sends to table t, w = window_used[t] and d = dup_count[t]:
  *     window_used[t] = number of lookups examined,
  *     dup_count[t]   = window_used[t] - (number of distinct row ids among them),
- *     hints[t]       = EMB_HINT_STREAMING if window_used[t] == 0, or if both
- *                        dup_count[t] * 1000 < threshold_permille * window_used[t]  (few repeats
- *                        inside the window) and
- *                        n_t * dup_count[t] * 4 < window_used[t]^2  (few repeats expected over
- *                        all n_t lookups the batch sends to table t: d repeats among w draws put
- *                        the rows in use at about w^2 / 2d, so about n_t * d / w^2 of n_t draws
- *                        repeat; the table counts as re-used from a quarter on);
+ *     hints[t]       = EMB_HINT_STREAMING if w == 0, or
+ *                        w^2 * row_bytes * min(row_bytes, 128) > d * 2^36  (d repeats among w
+ *                        draws put the rows in use at about w^2 / 2d; rows of 128 bytes or more
+ *                        then exceed the 256 MiB memory-side cache, so a repeated row has left
+ *                        it before it is asked for again; narrower rows share a 128-byte line
+ *                        with 128 / row_bytes others and must exceed that many times the cache),
+ *                        or
+ *                        n_t * d * 1000 * 128 < threshold_permille * w^2 * min(row_bytes, 128)
+ *                        (few of the table's lookups find their 128-byte cache line already
+ *                        fetched: n_t draws over w^2 / 2d rows repeat a row in about
+ *                        n_t * d / w^2 of cases, which for n_t <= window is the measured share
+ *                        d / n_t itself, and a line holds 128 / row_bytes rows);
  *                      else EMB_HINT_DEFAULT.
- *   This is the device-side counterpart of the offline hot-index profiling of paper Sec. 4.3:
- *   uniform-random access (the paper's "random" dataset) over a table much larger than the batch
- *   shows practically no repeats, the power-law datasets show many, and so does a batch that
- *   draws a sizeable part of a small table.  threshold_permille < 0 selects the library
- *   default (20).
+ *   row_bytes follows from desc->dim and desc->table_dtype; all comparisons are exact integer
+ *   arithmetic.  This is the device-side counterpart of the offline hot-index profiling of paper
+ *   Sec. 4.3: uniform-random access (the paper's "random" dataset) over a table much larger
+ *   than the batch shows practically no repeats, the power-law datasets show many, and so does
+ *   a batch that draws a sizeable part of a small table.  Both constants are measured on MI355X
+ *   (uniform tables, the hint forced either way): the streaming policy stops paying where about
+ *   7.5 % of a table's lookups repeat a row, unless the rows in use outgrow the cache.
+ *   threshold_permille < 0 selects the library default (75); values above 1,000,000 are taken
+ *   as 1,000,000.
  *
- *   desc, indices, offsets   as in emb_bag_forward (desc->table_hints is ignored; only
- *                            num_tables, batch and num_lookups matter, so any valid dim serves
- *                            for tables of different widths)
+ *   desc, indices, offsets   as in emb_bag_forward (desc->table_hints is ignored; num_tables,
+ *                            batch, num_lookups and the row size matter; for tables of different
+ *                            widths call once per width, or pass a typical dim)
  *   dup_count, window_used   DEVICE int32 [T] each, or NULL
  *   hints                    DEVICE uint8 [T], or NULL
  *   Asynchronous on `stream`; counts are exact and deterministic.

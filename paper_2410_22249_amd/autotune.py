@@ -20,6 +20,7 @@ kernel) on fp32 tables of that shape - and writes the per-shape table that `load
 
     python -m paper_2410_22249_amd.autotune pooling ...   (the two kernels over pooling factor x row width)
     python -m paper_2410_22249_amd.autotune mixed ...     (tables of different widths; fused against separate launches)
+    python -m paper_2410_22249_amd.autotune hints ...     (where the streaming hint stops paying: the reuse profiler's constants)
 """
 from __future__ import annotations
 
@@ -169,7 +170,7 @@ def _setup_wl(wl, n_batches: int):
     emode = emb.MODES[wl.mode]
     hints = torch.zeros(wl.T, dtype=torch.uint8, device=dev)
     d0 = emb.make_desc(wl.T, wl.B, wl.D, edt, emode, batches[0].num_lookups, 0, max(wl.rows))
-    emb.emb_bag_profile_reuse(d0, dev_batches[0][0], dev_batches[0][1], 4096, -1, None, None, hints)
+    emb.emb_bag_profile_reuse(d0, dev_batches[0][0], dev_batches[0][1], 16384, -1, None, None, hints)
     descs = [emb.make_desc(wl.T, wl.B, wl.D, edt, emode, b.num_lookups, 0, max(wl.rows), hints)
              for b in batches]
     out = torch.empty((wl.B, wl.T * wl.D), dtype=torch.float32, device=dev)
@@ -207,6 +208,9 @@ def main(argv: List[str] = None) -> int:
     if argv and argv[0] == "mixed":
         from . import autotune_mixed
         return autotune_mixed.main(argv[1:])
+    if argv and argv[0] == "hints":
+        from . import autotune_hints
+        return autotune_hints.main(argv[1:])
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--steps", type=int, default=20)

@@ -53,23 +53,36 @@ emb_bag_validate_kernel(const int64_t* __restrict__ table_offsets,
 }
 
 // One workgroup per table: insert the first `window` lookups of the table into an open-addressing
-// hash set in LDS (64-bit compare-and-swap, linear probing) and count the inserts that find their
-// key already present.  The count does not depend on the order of the inserts.
+// hash set in LDS (32-bit compare-and-swap, linear probing) and count the inserts that find their
+// row id already present.  A slot holds the position of a lookup inside the window, not its row
+// id (the id is read back from `indices` to compare), so 16,384 lookups fit in 96 KiB.  The count
+// does not depend on the order of the inserts.
 constexpr int kProfileThreads = 1024;
-constexpr int kProfileMaxWindow = 4096;
-constexpr uint32_t kProfileSlots = 6144;  // load factor <= 2/3: every probe sequence ends
-constexpr int64_t kProfileBatchShare = 4;  // re-used: an estimated 1/4 of the batch's lookups repeat
+constexpr int kProfileMaxWindow = 16384;
+constexpr int kProfileDefaultPermille = 75;
+constexpr int kProfileMaxPermille = 1000000;  // keeps threshold * window^2 * 128 inside 64 bits
+// d repeats among n draws put the rows in use at n^2 / 2d; they outgrow the last-level
+// (memory-side) cache of 256 MiB = 2^28 bytes when n^2 * row_bytes > d * 2^29.  Rows narrower
+// than a 128-byte line share it with 128 / row_bytes others, which makes a line that much more
+// likely to be asked for again before it leaves, and the bar that much higher:
+// n^2 * row_bytes * min(row_bytes, 128) > d * 2^36.
+constexpr int kProfileCacheShift = 36;
+
+inline uint32_t profile_slots(int32_t window) {  // load factor <= 2/3: every probe sequence ends
+  return (uint32_t)window + (uint32_t)window / 2u + 2u;
+}
 
 __global__ void __launch_bounds__(kProfileThreads)
 emb_bag_profile_kernel(const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
                        int32_t* __restrict__ dup_count, int32_t* __restrict__ window_used,
                        uint8_t* __restrict__ hints, int64_t num_lookups, uint32_t B,
-                       int32_t window, int32_t threshold_permille) {
-  __shared__ unsigned long long slots[kProfileSlots];
+                       int32_t window, int32_t threshold_permille, uint32_t row_bytes,
+                       uint32_t num_slots) {
+  extern __shared__ uint32_t slots[];
   __shared__ int dups;
-  constexpr unsigned long long kEmpty = ~0ull;
+  constexpr uint32_t kEmpty = ~0u;
   const uint32_t t = blockIdx.x;
-  for (uint32_t i = threadIdx.x; i < kProfileSlots; i += kProfileThreads) slots[i] = kEmpty;
+  for (uint32_t i = threadIdx.x; i < num_slots; i += kProfileThreads) slots[i] = kEmpty;
   if (threadIdx.x == 0) dups = 0;
   __syncthreads();
 
@@ -83,31 +96,36 @@ emb_bag_profile_kernel(const int64_t* __restrict__ indices, const int64_t* __res
   int mine = 0;
   for (int i = threadIdx.x; i < n; i += kProfileThreads) {
     const unsigned long long key = (unsigned long long)indices[s + i];
-    if (key == kEmpty) continue;  // the id -1 is never valid; it is counted as distinct
-    uint32_t slot = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> 40) % kProfileSlots;
-    for (uint32_t probe = 0; probe < kProfileSlots; ++probe) {
-      const unsigned long long old = atomicCAS(&slots[slot], kEmpty, key);
+    uint32_t slot = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> 40) % num_slots;
+    for (uint32_t probe = 0; probe < num_slots; ++probe) {
+      const uint32_t old = atomicCAS(&slots[slot], kEmpty, (uint32_t)i);
       if (old == kEmpty) break;
-      if (old == key) {
+      if ((unsigned long long)indices[s + old] == key) {
         ++mine;
         break;
       }
-      slot = slot + 1 == kProfileSlots ? 0 : slot + 1;
+      slot = slot + 1 == num_slots ? 0 : slot + 1;
     }
   }
   if (mine) atomicAdd(&dups, mine);
   __syncthreads();
   if (threadIdx.x == 0) {
-    const int d = dups;
-    if (dup_count) dup_count[t] = d;
+    const int64_t d = dups;
+    if (dup_count) dup_count[t] = (int32_t)d;
     if (window_used) window_used[t] = n;
-    // few repeats inside the window, and few expected over the table's n64 lookups of the
-    // whole batch: n64 * d / n^2 estimates their share (d repeats among n draws put the number
-    // of rows in use at about n^2 / 2d; n64 draws over those repeat in n64 / (2 n^2 / 2d) of cases)
-    if (hints)
-      hints[t] = (((int64_t)d * 1000 < (int64_t)threshold_permille * n &&
-                   n64 * d * kProfileBatchShare < (int64_t)n * n) || n == 0)
-                     ? EMB_HINT_STREAMING : EMB_HINT_DEFAULT;
+    // d repeats among n draws put the rows in use at about n^2 / 2d.  Streaming: those rows do
+    // not fit the last-level cache, or few of the table's n64 lookups of the whole batch find
+    // their cache line already fetched (n64 draws over n^2 / 2d rows repeat a row in about
+    // n64 * d / n^2 of cases, and a 128-byte line holds 128 / row_bytes rows), or nothing was
+    // examined.  The share test is n64 * d * 1000 * 128 < threshold * n^2 * min(row_bytes, 128),
+    // taken without overflow.
+    const int64_t n2 = (int64_t)n * n;
+    const int64_t line_rows = row_bytes < 128u ? row_bytes : 128u;  // 128 / rows per line
+    const int64_t bar = (int64_t)threshold_permille * n2 * line_rows;
+    const bool beyond_cache = n2 * (int64_t)row_bytes * line_rows > (d << kProfileCacheShift);
+    const bool few_repeats = bar > 0 && n64 * d <= ((bar - 1) / 1000) / 128;
+    if (hints) hints[t] = (n == 0 || beyond_cache || few_repeats) ? EMB_HINT_STREAMING
+                                                                  : EMB_HINT_DEFAULT;
   }
 }
 
@@ -253,10 +271,18 @@ int emb_bag_profile_reuse(const emb_bag_desc* desc, const int64_t* indices,
   if (B > 0x7FFFFFFF || T * B > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
   if (window < 1) window = 1;
   if (window > kProfileMaxWindow) window = kProfileMaxWindow;
-  if (threshold_permille < 0) threshold_permille = 20;
-  hipLaunchKernelGGL(emb_bag_profile_kernel, dim3((uint32_t)T), dim3(kProfileThreads), 0,
+  if (threshold_permille < 0) threshold_permille = kProfileDefaultPermille;
+  if (threshold_permille > kProfileMaxPermille) threshold_permille = kProfileMaxPermille;
+  const uint32_t num_slots = profile_slots(window);
+  const uint32_t lds = num_slots * 4u;
+  if (lds > 65536u &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(emb_bag_profile_kernel),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    return EMB_ERR_LAUNCH;
+  hipLaunchKernelGGL(emb_bag_profile_kernel, dim3((uint32_t)T), dim3(kProfileThreads), lds,
                      static_cast<hipStream_t>(stream), indices, offsets, dup_count, window_used,
-                     hints, desc->num_lookups, (uint32_t)B, window, threshold_permille);
+                     hints, desc->num_lookups, (uint32_t)B, window, threshold_permille, row_bytes,
+                     num_slots);
   return hipGetLastError() == hipSuccess ? EMB_OK : EMB_ERR_LAUNCH;
 }
 }  // extern "C"

@@ -13,7 +13,7 @@ import torch
 
 import paper_2410_22249_amd as emb
 from inputgen import gen
-from gpu_harness import DEV, assert_close_to_oracle, device_arena, to_dev, tuning
+from gpu_harness import DEV, assert_close_to_oracle, device_arena, forward, to_dev, tuning
 
 pytestmark = pytest.mark.gpu
 
@@ -96,21 +96,25 @@ def test_full_size_sampled_bags(oracle, name, nsample):
     hints = torch.zeros(wl.T, dtype=torch.uint8, device=DEV)
     dup = torch.zeros(wl.T, dtype=torch.int32, device=DEV)
     used = torch.zeros(wl.T, dtype=torch.int32, device=DEV)
-    emb.emb_bag_profile_reuse(desc, idx, off, 4096, -1, dup, used, hints)
+    emb.emb_bag_profile_reuse(desc, idx, off, 16384, -1, dup, used, hints)
     torch.cuda.synchronize()
-    rd, ru, rh = reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B, 4096, 20)
+    rd, ru, rh = reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B, 16384, 75,
+                                            row_bytes=wl.row_bytes)
     assert np.array_equal(dup.cpu().numpy(), rd) and np.array_equal(used.cpu().numpy(), ru)
     assert np.array_equal(hints.cpu().numpy(), rh)
-    # skewed tables stay cached; uniform tables stream when the batch draws a small part of the
-    # table (draws * 2 = rows is where the rule's estimate of repeated lookups reaches a quarter;
-    # tables within a factor of four of that may fall on either side)
+    # skewed tables stay cached; a uniform table streams when its rows outgrow the 256 MiB
+    # memory-side cache or the batch draws a small part of it (the estimated share of repeated
+    # lookups, draws / 2 rows, reaches the 7.5 % threshold at draws = 0.15 rows), and stays
+    # cached when neither holds; tables within a factor of two of a threshold may fall on
+    # either side
     per_table = np.diff(batch.offsets[::wl.B])
     for t, d in enumerate(wl.dists):
+        table_bytes = wl.rows[t] * wl.row_bytes
         if d[0] != "uniform":
             assert rh[t] == 0, t
-        elif per_table[t] * 8 < wl.rows[t]:
+        elif table_bytes > (2 << 28) or per_table[t] < 0.075 * wl.rows[t]:
             assert rh[t] == 1, t
-        elif per_table[t] > wl.rows[t] * 2:
+        elif table_bytes < (1 << 27) and per_table[t] > 0.3 * wl.rows[t]:
             assert rh[t] == 0, t
     hdesc = emb.make_desc(wl.T, wl.B, wl.D, emb.DTYPES[wl.dtype],
                           emb.MODES[wl.mode], batch.num_lookups,
@@ -227,6 +231,45 @@ def test_table_of_more_than_2_pow_31_rows(oracle):
     ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, soff, len(bags), "sum")
     got = out.view(wl.B, wl.T, wl.D).permute(1, 0, 2).reshape(wl.num_bags, wl.D).cpu().numpy()
     assert_close_to_oracle(got, ref, bound, False, "table of 2^31 + 1000 rows")
+
+
+@pytest.mark.parametrize("dtype,D,R", [("f32", 128, 7_000_000), ("f16", 64, 28_000_011)])
+def test_buffer_addressing_beyond_2_pow_31_bytes(oracle, dtype, D, R):
+    """One table between 2 GiB and 3.5 GiB under buffer addressing: 32-bit row offsets at and
+    above 2^31 (as unsigned), the very last row, and ids at or beyond R (neutralised by the
+    buffer's range check); the same input through 64-bit addressing must give the same bits."""
+    wl = gen.Workload(name="buf3g", T=2, rows=(R, 1000), D=D, dtype=dtype, B=512,
+                      pooling=("uniform", 1, 150), dists=(("uniform",), ("uniform",)), seed=0x5EED0B0F)
+    row_bytes = D * (4 if dtype == "f32" else 2)
+    assert (1 << 31) + (1 << 29) < R * row_bytes <= 0xE0000000
+    batch = gen.make_batches(wl, 1)[0]
+    idx = batch.indices.copy()
+    n0 = int(batch.offsets[wl.B])                                # lookups of table 0
+    assert n0 > 2000
+    first_high = -(-(1 << 31) // row_bytes)                      # first row at byte offset >= 2^31
+    idx[:32] = np.arange(R - 32, R)                              # the last rows
+    idx[32:64] = np.arange(first_high - 16, first_high + 16)     # across 2^31
+    bad = np.array([64, 100, n0 - 1])
+    idx[bad] = [R, R + 7, (1 << 40) + 3]                         # at and beyond R: contribute nothing
+    assert int((idx[:n0] * row_bytes >= (3 << 30)).sum()) > 100  # the uniform draw reaches past 3 GiB
+    arena = device_arena(wl)
+    toff = wl.table_offsets()
+    with tuning(addressing=0):
+        plan = emb.emb_bag_plan_forward(emb.make_desc(wl.T, wl.B, wl.D, emb.DTYPES[dtype],
+                                                      emb.MODES["sum"], len(idx), 0, R))
+        assert plan.buffer_addressing == 1
+        got_buf = forward(arena, toff, idx, batch.offsets, wl.B, max_table_rows=R)
+    with tuning(addressing=1):
+        got_flat = forward(arena, toff, idx, batch.offsets, wl.B, max_table_rows=R)
+    assert torch.equal(got_buf.view(torch.int32), got_flat.view(torch.int32))
+    clean, w = idx.copy(), np.ones(len(idx), np.float32)
+    clean[bad], w[bad] = 0, 0.0
+    bags = np.arange(wl.num_bags)
+    small, ix, soff, ws = gen.compact_rows(wl, gen.Batch(offsets=batch.offsets, indices=clean, weights=w), bags)
+    ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, soff, len(bags), "sum",
+                                weights=ws)
+    got = got_buf.view(wl.B, wl.T, wl.D).permute(1, 0, 2).reshape(wl.num_bags, wl.D).cpu().numpy()
+    assert_close_to_oracle(got, ref, bound, dtype == "f16", f"buffer addressing, {dtype} table of {R * row_bytes} bytes")
 
 
 def test_the_largest_grid_a_launch_can_hold(oracle):

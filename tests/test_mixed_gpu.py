@@ -182,12 +182,13 @@ def test_mixed_batches_validate_profile_and_replay_from_a_graph(oracle):
     bad = torch.zeros(1, dtype=torch.int64, device=DEV)
     emb.emb_bag_validate(udesc, rows, idx, off, bad)
     hints = torch.zeros(wl.T, dtype=torch.uint8, device=DEV)
-    emb.emb_bag_profile_reuse(udesc, idx, off, 4096, -1, None, None, hints)
+    emb.emb_bag_profile_reuse(udesc, idx, off, 16384, -1, None, None, hints)
     torch.cuda.synchronize()
     assert int(bad.item()) == 0
     from oracle import reuse_oracle
     assert np.array_equal(hints.cpu().numpy(),
-                          reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B, 4096, 20)[2])
+                          reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B, 16384, 75,
+                                                     row_bytes=16)[2])
     bad_idx = idx.clone()
     bad_idx[0] = wl.rows[0]                                 # one past the end of table 0
     bad.zero_()

@@ -459,20 +459,24 @@ def test_thread_count_does_not_change_result(oracle):
 # ---- the reuse-profile oracle (integer work) -------------------------------------------------
 def test_reuse_profile_hand_worked():
     from oracle import reuse_oracle
-    # T = 2, B = 2.  table 0 lookups: [5,5,7,5 | 9]  table 1 lookups: [ | 1,2,3]
+    # T = 2, B = 2.  table 0 lookups: [5,5,7,5 | 9]  table 1 lookups: [ | 1,2,3]; 128-byte rows
     idx = np.array([5, 5, 7, 5, 9, 1, 2, 3], dtype=np.int64)
     off = np.array([0, 4, 5, 5, 8], dtype=np.int64)
-    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 2, 2, 4096, 20)
+    # table 0: w = 5, d = 2, n_t = 5: 5 * 2 * 1000 = 10000 against 75 * 25 = 1875; 25 * 128 < 2 * 2^29
+    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 2, 2, 4096, 75, row_bytes=128)
     assert dup.tolist() == [2, 0] and used.tolist() == [5, 3] and hints.tolist() == [0, 1]
-    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 2, 2, 2, 20)     # window of 2
+    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 2, 2, 2, 75, row_bytes=128)   # window of 2
     assert dup.tolist() == [1, 0] and used.tolist() == [2, 2] and hints.tolist() == [0, 1]
-    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 2, 2, 4096, 500)  # 50 % threshold
-    assert hints.tolist() == [0, 1]      # 2/5 < 50 %, but 2 of the table's 5 lookups repeat: >= 1/4
+    # the threshold is a strict bound on the share of repeats: 2 of 5 is 400 permille
+    assert reuse_oracle.profile_reuse(idx, off, 2, 2, 4096, 400, row_bytes=128)[2].tolist() == [0, 1]
+    assert reuse_oracle.profile_reuse(idx, off, 2, 2, 4096, 401, row_bytes=128)[2].tolist() == [1, 1]
     idx9 = np.array([5, 5, 7, 6, 9, 4, 3, 2, 1, 1, 2, 3], dtype=np.int64)    # table 0: 1 repeat in 9
     off9 = np.array([0, 8, 9, 9, 12], dtype=np.int64)
-    assert reuse_oracle.profile_reuse(idx9, off9, 2, 2, 4096, 500)[2].tolist() == [1, 1]  # 9*1*4 < 81
+    assert reuse_oracle.profile_reuse(idx9, off9, 2, 2, 4096, 111, row_bytes=128)[2].tolist() == [0, 1]
+    assert reuse_oracle.profile_reuse(idx9, off9, 2, 2, 4096, 112, row_bytes=128)[2].tolist() == [1, 1]
     # a table that receives nothing is "streaming"
-    dup, used, hints = reuse_oracle.profile_reuse(np.zeros(0, np.int64), np.zeros(3, np.int64), 2, 1, 8)
+    dup, used, hints = reuse_oracle.profile_reuse(np.zeros(0, np.int64), np.zeros(3, np.int64), 2, 1, 8,
+                                                  row_bytes=128)
     assert used.tolist() == [0, 0] and hints.tolist() == [1, 1]
 
 
@@ -483,7 +487,7 @@ def test_reuse_profile_closed_forms():
     rng = np.random.default_rng(3)
     uni = rng.integers(0, 4_000_000, size=n)
     idx = np.concatenate([np.arange(n), np.full(n, 42), uni]).astype(np.int64)
-    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 3, 1, 4096)
+    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 3, 1, 4096, row_bytes=512)
     assert used.tolist() == [n, n, n]
     assert dup[0] == 0 and dup[1] == n - 1
     # birthday problem: expected repeats of n uniform draws over R rows is about n^2 / (2R) = 1.1
@@ -491,25 +495,93 @@ def test_reuse_profile_closed_forms():
     assert hints.tolist() == [1, 0, 1]
 
 
+def _one_table_with_repeats(w, d, n):
+    """n lookups of one table: the first w hold exactly d repeats, the rest are all new."""
+    head = np.concatenate([np.arange(d), np.arange(w - d)]).astype(np.int64)
+    idx = np.concatenate([head, np.arange(n - w, dtype=np.int64) + 10_000_000])
+    return idx, np.array([0, n], dtype=np.int64)
+
+
 def test_reuse_profile_counts_the_whole_batch():
     """A table whose window shows few repeats is still re-used when the batch sends it many more
     lookups than the window holds: with d repeats among w examined draws, about n * d / w^2 of
-    the table's n lookups repeat, and from a quarter on the table is not streaming."""
+    the table's n lookups repeat, and from the threshold (75 permille) on the table is not
+    streaming."""
     from oracle import reuse_oracle
     w = 4096
-    # table 0: its first w lookups hold 8 repeats (ids 0..7 twice), then nothing new is examined;
-    # n = 3 w^2 / (4 * 8 * 4) lookups keep n * d * 4 below w^2, one more bag of them does not
-    head = np.concatenate([np.arange(8), np.arange(w - 8)]).astype(np.int64)
-    n_small, n_large = w * w // 32 - 1, w * w // 32
-    for n, want in ((n_small, 1), (n_large, 0)):
-        idx = np.concatenate([head, np.arange(n - w, dtype=np.int64) + 10_000_000])
-        off = np.array([0, n], dtype=np.int64)
-        dup, used, hints = reuse_oracle.profile_reuse(idx, off, 1, 1, w, 20)
+    # d = 8: n * 8 * 1000 < 75 * 2^24 holds up to n = 157286 (128-byte rows: the cache rule asks for d < 4)
+    for n, want in ((157286, 1), (157287, 0)):
+        idx, off = _one_table_with_repeats(w, 8, n)
+        dup, used, hints = reuse_oracle.profile_reuse(idx, off, 1, 1, w, 75, row_bytes=128)
         assert dup.tolist() == [8] and used.tolist() == [w] and hints.tolist() == [want], n
-    # the window rule alone still decides when the window covers the table's lookups:
-    # 3 repeats in 200 draws is 1.5 % (< 2 %) and 200 * 3 * 4 < 200^2
-    idx = np.concatenate([np.arange(3), np.arange(197)]).astype(np.int64)
-    assert reuse_oracle.profile_reuse(idx, np.array([0, 200], np.int64), 1, 1, w, 20)[2].tolist() == [1]
+    # when the window covers the table's lookups the share is the measured one: 14 repeats in 200
+    # draws are 70 permille, 15 are 75
+    for d, want in ((14, 1), (15, 0)):
+        idx = np.concatenate([np.arange(d), np.arange(200 - d)]).astype(np.int64)
+        assert reuse_oracle.profile_reuse(idx, np.array([0, 200], np.int64), 1, 1, w, 75,
+                                          row_bytes=128)[2].tolist() == [want]
+    # rows narrower than a 128-byte line share it: 64-byte rows double the share, 32-byte rows
+    # quadruple it (7 repeats in 200 are 35 permille, 3 are 15)
+    for d, row_bytes, want in ((7, 64, 1), (8, 64, 0), (3, 32, 1), (4, 32, 0), (14, 256, 1), (15, 256, 0)):
+        idx = np.concatenate([np.arange(d), np.arange(200 - d)]).astype(np.int64)
+        assert reuse_oracle.profile_reuse(idx, np.array([0, 200], np.int64), 1, 1, w, 75,
+                                          row_bytes=row_bytes)[2].tolist() == [want], (d, row_bytes)
+    # all 200 draws equal, 16-byte rows: 199 / 200 of the draws repeat and a line holds 8 rows,
+    # a share of 7960 permille
+    idx, off = np.zeros(200, np.int64), np.array([0, 200], np.int64)
+    assert reuse_oracle.profile_reuse(idx, off, 1, 1, w, 7960, row_bytes=16)[2].tolist() == [0]
+    assert reuse_oracle.profile_reuse(idx, off, 1, 1, w, 7961, row_bytes=16)[2].tolist() == [1]
+    # a threshold beyond 1,000,000 permille counts as 1,000,000: 100,000 lookups whose first 200
+    # are all equal give an estimated share of 100000 * 199 / 200^2 = 497.5, i.e. 497,500 permille
+    # of 128-byte rows and 995,000 of 64-byte rows
+    idx = np.concatenate([np.zeros(200, np.int64), np.arange(99_800, dtype=np.int64) + 5])
+    off = np.array([0, 100_000], np.int64)
+    assert reuse_oracle.profile_reuse(idx, off, 1, 1, 200, 497_500, row_bytes=128)[2].tolist() == [0]
+    assert reuse_oracle.profile_reuse(idx, off, 1, 1, 200, 497_501, row_bytes=128)[2].tolist() == [1]
+    assert reuse_oracle.profile_reuse(idx, off, 1, 1, 200, 1_000_000, row_bytes=64)[2].tolist() == [1]
+    assert reuse_oracle.profile_reuse(idx, off, 1, 1, 200, 2_000_000_000, row_bytes=32)[2].tolist() == [0]
+
+
+def test_reuse_profile_rows_in_use_beyond_the_cache():
+    """d repeats among w draws put the rows in use at w^2 / 2d.  With w = 4096 and 512-byte rows
+    that is 2^33 / 2d bytes: above 256 MiB = 2^28 for d < 16, whatever the batch sends; 256-byte
+    rows halve it (d < 8)."""
+    from oracle import reuse_oracle
+    w, n = 4096, 3_000_000      # n * d / w^2 is far above the share threshold for every d here
+    for d, row_bytes, want in ((15, 512, 1), (16, 512, 0), (7, 256, 1), (8, 256, 0), (15, 256, 0),
+                               (1, 32, 0), (0, 16, 1)):
+        idx, off = _one_table_with_repeats(w, d, n)
+        dup, used, hints = reuse_oracle.profile_reuse(idx, off, 1, 1, w, 75, row_bytes=row_bytes)
+        assert dup.tolist() == [d] and hints.tolist() == [want], (d, row_bytes)
+    # rows narrower than a line: 64-byte rows need twice the cache, 2^28 * 64 > d * 2^30 for d < 16
+    for d, row_bytes, want in ((15, 64, 1), (16, 64, 0), (3, 32, 1), (4, 32, 0), (63, 128, 1), (64, 128, 0)):
+        idx, off = _one_table_with_repeats(16384, d, n)
+        assert reuse_oracle.profile_reuse(idx, off, 1, 1, 16384, 75, row_bytes=row_bytes)[2].tolist() == [want]
+    # the largest window: 16384 draws, 1024-byte rows: 2^38 > d * 2^29 for d < 512
+    idx, off = _one_table_with_repeats(16384, 511, n)
+    assert reuse_oracle.profile_reuse(idx, off, 1, 1, 1 << 20, 75, row_bytes=1024)[2].tolist() == [1]
+    idx, off = _one_table_with_repeats(16384, 512, n)
+    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 1, 1, 1 << 20, 75, row_bytes=1024)
+    assert used.tolist() == [16384] and dup.tolist() == [512] and hints.tolist() == [0]
+
+
+@pytest.mark.parametrize("name,seeds,want", [
+    ("cfg1", 6, "1" * 8), ("cfg2", 4, "1" * 26), ("cfg3", 2, "1" * 60), ("cfg4", 1, "0" * 60),
+    ("cfg5", 1, "1" * 50 + "0" * 50)])
+def test_reuse_classification_of_the_benchmark_configurations(name, seeds, want):
+    """The hints of the five benchmark configurations do not depend on the seed: uniform tables
+    far larger than what a batch draws stream (cfg1-cfg3, the first half of cfg5), power-law
+    tables do not (cfg4, the second half of cfg5).  For each, the repeat count of the window sits
+    well away from the two thresholds."""
+    import dataclasses
+    from oracle import reuse_oracle
+    base = gen.workload(name)
+    for k in range(seeds):
+        wl = dataclasses.replace(base, seed=base.seed + 977 * k)
+        batch = gen.make_batches(wl, 1)[0]
+        dup, used, hints = reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B, 16384,
+                                                      row_bytes=wl.row_bytes)
+        assert "".join(map(str, hints)) == want, (name, k, dup.tolist())
 
 
 # ---- the hot-row profile oracle (integer work) -------------------------------------------------

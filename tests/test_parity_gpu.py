@@ -359,25 +359,29 @@ def test_reuse_profile_matches_oracle_bit_for_bit():
     from oracle import reuse_oracle
     cases = [gen.workload("small_f32_d64"), gen.workload("small_f32_d128"),
              gen.Workload(name="prof", T=9, rows=(4_000_000, 50, 1, 100_000, 7, 4_000_000, 300, 9, 2),
-                          D=64, dtype="f32", B=40, pooling=("uniform", 0, 300),
+                          D=64, dtype="f32", B=160, pooling=("uniform", 0, 300),
                           dists=(("uniform",), ("uniform",), ("one_item",), ("zipf", 1.05),
                                  ("uniform",), ("zipf", 1.2), ("zipf", 0.7), ("uniform",),
                                  ("one_item",)), seed=0x5EED0500)]
     for wl in cases:
         batch = gen.make_batches(wl, 1)[0]
         idx, off = to_dev(batch.indices), to_dev(batch.offsets)
-        desc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups)
-        for window, thr in ((4096, 20), (100, 20), (1, 20), (5000, 500), (333, -1)):
-            dup = torch.full((wl.T,), -1, dtype=torch.int32, device=DEV)
-            used = torch.full((wl.T,), -1, dtype=torch.int32, device=DEV)
-            hints = torch.full((wl.T,), 9, dtype=torch.uint8, device=DEV)
-            emb.emb_bag_profile_reuse(desc, idx, off, window, thr, dup, used, hints)
-            torch.cuda.synchronize()
-            rd, ru, rh = reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B,
-                                                    window, 20 if thr < 0 else thr)
-            assert np.array_equal(dup.cpu().numpy(), rd), (wl.name, window)
-            assert np.array_equal(used.cpu().numpy(), ru)
-            assert np.array_equal(hints.cpu().numpy(), rh)
+        # the row size enters the rule only: the same ids are profiled as rows of 16 B .. 4 KiB
+        for D in (wl.D, 4, 16, 1024):
+            desc = emb.make_desc(wl.T, wl.B, D, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups)
+            for window, thr in ((4096, 20), (100, 75), (1, 20), (5000, 500), (333, -1), (16384, -1),
+                                (1 << 30, 75), (64, 2_000_000_000), (16384, 0)):
+                dup = torch.full((wl.T,), -1, dtype=torch.int32, device=DEV)
+                used = torch.full((wl.T,), -1, dtype=torch.int32, device=DEV)
+                hints = torch.full((wl.T,), 9, dtype=torch.uint8, device=DEV)
+                emb.emb_bag_profile_reuse(desc, idx, off, window, thr, dup, used, hints)
+                torch.cuda.synchronize()
+                rd, ru, rh = reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B,
+                                                        window, 75 if thr < 0 else thr,
+                                                        row_bytes=D * 4)
+                assert np.array_equal(dup.cpu().numpy(), rd), (wl.name, window)
+                assert np.array_equal(used.cpu().numpy(), ru)
+                assert np.array_equal(hints.cpu().numpy(), rh), (wl.name, D, window, thr)
     # no lookups at all
     desc = emb.make_desc(3, 4, 64, emb.EMB_F32, emb.EMB_SUM, 0)
     hints = torch.full((3,), 9, dtype=torch.uint8, device=DEV)
