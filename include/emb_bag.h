@@ -392,6 +392,8 @@ typedef struct emb_bag_plan {
   int32_t bags_per_wave;     /* wave kernel: consecutive bags of a table per wavefront (wavefront w
                                 of a table owns bags w * bags_per_wave ...); else 0 */
   int32_t hot_split;         /* 1 = the launch honours desc->hot_rows */
+  int32_t station;           /* 1 = row loads land in LDS (see "station"), 0 = in registers */
+  int32_t reserved;          /* 0 */
 } emb_bag_plan;
 
 int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, int32_t which,
@@ -443,6 +445,14 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *   "hot_split"     what the kernels do with desc->hot_rows: 0 (default) = nothing; 1 = a bag's
  *                   lookups are regrouped hot rows first, hot rows read with the default cache
  *                   policy, all others non-temporally; 2 = regrouped only, one policy
+ *   "station"       where the rows a wavefront has in flight land (the prefetch station of
+ *                   Sec. 4.2): 0 (default) = in registers; 1 = in LDS (the paper's shared-memory
+ *                   prefetch: `depth` slots of 1 KiB per wavefront, read back when the load has
+ *                   landed), for the one-wavefront-per-bag kernel with buffer addressing, sum or
+ *                   mean pooling without weights, depth 4 or 8 and no hot / cold split;
+ *                   elsewhere, and in fused launches, the key is ignored (plan->station says
+ *                   what a launch does).  Same results, bit for bit.  Measured on MI355X it is
+ *                   never faster (a CU's registers hold more rows in flight than its LDS)
  * Not thread-safe against concurrent emb_bag_forward calls.
  */
 int emb_bag_set_tuning(const char* key, int64_t value);

@@ -38,13 +38,14 @@ if ROOT not in sys.path:
 DEFAULT_GRID = {
     "blocks_per_cu": [0, 4, 2],        # waves per SIMD: 8 (no cap), 4, 2
     "depth": [1, 2, 4, 8, 16],
+    "station": [0, 1],                 # rows in flight land in registers / in LDS (depth 4 and 8)
     "use_hints": [1, 0],
     "xcd_remap": [1, 0],
 }
 # for short bags add e.g. --grid '{"stream":[0,1],"bags_per_group":[1,2,4,8],"depth":[4,8]}'
 NEUTRAL = {"blocks_per_cu": 0, "depth": 0, "use_hints": 1, "xcd_remap": -1, "addressing": 0,
            "stream": -1, "bags_per_group": 0, "xcd_pieces": 0, "per_table_launch": 0, "fuse": 1,
-           "bags_per_wave": 0, "hot_split": 0}
+           "bags_per_wave": 0, "hot_split": 0, "station": 0}
 
 # per-shape sweep (--table): rows of 64 B .. 1 KiB, pooling factors from one-hot to the paper's 150
 TABLE_ROW_BYTES = [64, 128, 256, 512, 1024]

@@ -60,7 +60,8 @@ class emb_bag_plan(ctypes.Structure):
                 ("waves_per_table", ctypes.c_int64), ("waves_per_piece", ctypes.c_int64),
                 ("blocks_per_piece", ctypes.c_int64), ("tables", ctypes.c_int64),
                 ("fused", ctypes.c_int64), ("fused_grid_blocks", ctypes.c_int64),
-                ("bags_per_wave", ctypes.c_int32), ("hot_split", ctypes.c_int32)]
+                ("bags_per_wave", ctypes.c_int32), ("hot_split", ctypes.c_int32),
+                ("station", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
     def as_dict(self) -> dict:
         return {name: int(getattr(self, name)) for name, _ in self._fields_}

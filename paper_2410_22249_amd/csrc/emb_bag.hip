@@ -154,6 +154,7 @@ int launch(const Launch& L, const void* tables, const int64_t* table_offsets,
   uint32_t lds = 0;
   const int rc = occupancy_cap_lds(reinterpret_cast<const void*>(L.fn), &lds);
   if (rc != EMB_OK) return rc;
+  if (lds < L.lds_bytes) lds = L.lds_bytes;  // the LDS station's slots (at most 32 KiB)
   hipLaunchKernelGGL(L.fn, dim3(L.blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
                      static_cast<const char*>(tables), table_offsets, indices, offsets, weights,
                      table_hints, L.hot ? hot_rows : nullptr, out_offsets, out, L.p, L.order);

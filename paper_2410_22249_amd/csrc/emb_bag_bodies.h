@@ -37,7 +37,9 @@ __device__ __forceinline__ uint32_t listed_table(const TableOrder& order, uint32
 // are regrouped per chunk, hot ones first (gather_hot_cold).  HOT == 1: the other rows are read
 // non-temporally, and the hot head replaces the per-table hint (0 rows = a streaming table);
 // HOT == 2: both kinds are read with the default policy.
-template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, int HOT = 0>
+// LDS (buffer addressing, sum pooling, no hot / cold split): the row loads go through the LDS
+// station of gather_slots; the launch then provides kWavesPerBlock * DEPTH KiB of dynamic LDS.
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, int HOT = 0, bool LDS = false>
 __device__ __forceinline__ void wave_body(
     const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
@@ -46,6 +48,7 @@ __device__ __forceinline__ void wave_body(
     float* __restrict__ out, const KParams& p, const TableOrder& order, uint32_t order_base,
     uint32_t block) {
   static_assert(!HOT || BUF, "the hot / cold split is built for buffer addressing");
+  static_assert(!LDS || (BUF && !HOT), "the LDS station is built for buffer addressing");
   constexpr bool MIXED = LPR == 0;
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;  // 2-byte elements
   constexpr bool QUANT = IsQuant<ELEM>::value;                // 1-byte codes + scale, bias
@@ -179,21 +182,21 @@ __device__ __forceinline__ void wave_body(
       } else if constexpr (kNoWrap && BUF) {
         if (lean) {  // no per-load tests: see gather_slots
           if (streaming)
-            gather_slots<LPR, ELEM, DEPTH, OP, true, true, false, false>(
+            gather_slots<LPR, ELEM, DEPTH, OP, true, true, false, false, LDS>(
                 acc, 0, n, q, tbase, rsrc, g, col, lane_ok, meta_lane, gl);
           else
-            gather_slots<LPR, ELEM, DEPTH, OP, true, false, false, false>(
+            gather_slots<LPR, ELEM, DEPTH, OP, true, false, false, false, LDS>(
                 acc, 0, n, q, tbase, rsrc, g, col, lane_ok, meta_lane, gl);
           gathered = true;
         }
       }
       if (!gathered) {
         if (streaming)
-          gather_slots<LPR, ELEM, DEPTH, OP, BUF, true>(acc, 0, n, q, tbase, rsrc, g, col,
-                                                        lane_ok, meta_lane, gl);
+          gather_slots<LPR, ELEM, DEPTH, OP, BUF, true, true, true, LDS>(
+              acc, 0, n, q, tbase, rsrc, g, col, lane_ok, meta_lane, gl);
         else
-          gather_slots<LPR, ELEM, DEPTH, OP, BUF, false>(acc, 0, n, q, tbase, rsrc, g, col,
-                                                         lane_ok, meta_lane, gl);
+          gather_slots<LPR, ELEM, DEPTH, OP, BUF, false, true, true, LDS>(
+              acc, 0, n, q, tbase, rsrc, g, col, lane_ok, meta_lane, gl);
       }
     }
     // the next bag's row offsets before this bag's stores: its ids arrived ahead of the rows

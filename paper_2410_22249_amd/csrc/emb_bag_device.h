@@ -222,8 +222,27 @@ __device__ __forceinline__ ChunkLookups<BUF> chunk_offsets(int64_t idx, float w,
 // slot 63 and wrap (DEPTH steps cover more than 64 slots); without it j_lo is 0 and the slots
 // from j_hi on hold "no row" already, as load_chunk and chunk_offsets leave them.  PARTIAL:
 // the row does not fill its lane group (lane_ok is false for some lanes).
+// The LDS station (LDS = true; buffer addressing, sum pooling): the DEPTH row loads of a batch
+// bypass the registers (buffer load to LDS, 16 bytes per lane: load d of the wavefront fills the
+// d-th 1-KiB slot of the wavefront's DEPTH KiB of dynamic LDS) and each lane reads its segment
+// back when the load has landed.  This is the shared-memory prefetch station of paper Sec. 4.2.
+// The compiler does not track such a load in its wait-count insertion, so the wait is placed
+// here: loads complete in the order issued, stores (of an earlier bag) in theirs, so once at
+// most DEPTH - 1 - d vector memory operations are outstanding, load d and everything issued
+// before the batch have completed, whatever else is in flight.
+template <int D, int DEPTH, int ELEM, int OP>
+__device__ __forceinline__ void consume_lds_slots(float* acc, const u32x4* mine, int meta_lane) {
+  if constexpr (D < DEPTH) {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (DEPTH - 1 - D));  // vmcnt alone; the others at their maximum
+    asm volatile("" ::: "memory");
+    const u32x4 v = *(const volatile u32x4*)(mine + D * kWaveSize);
+    accumulate<ELEM, OP>(acc, v, 1.0f, meta_lane);
+    consume_lds_slots<D + 1, DEPTH, ELEM, OP>(acc, mine, meta_lane);
+  }
+}
+
 template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, bool NT, bool RANGE = true,
-          bool PARTIAL = true>
+          bool PARTIAL = true, bool LDS = false>
 __device__ __forceinline__ void gather_slots(float* acc, int j_lo, int j_hi,
                                              const ChunkLookups<BUF>& q, const char* tbase,
                                              __amdgpu_buffer_rsrc_t rsrc, int g, uint32_t col,
@@ -232,6 +251,28 @@ __device__ __forceinline__ void gather_slots(float* acc, int j_lo, int j_hi,
   constexpr int kAux = NT ? 2 : 0;  // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
   const int k_lo = RANGE ? j_lo >> gl : 0;
   const int k_hi = (j_hi + (1 << gl) - 1) >> gl;
+  if constexpr (LDS) {
+    static_assert(BUF && OP == kOpSum && DEPTH <= 8, "the LDS station: buffer addressing, sum");
+    extern __shared__ u32x4 emb_stage[];  // kWavesPerBlock * DEPTH slots of 64 segments
+    u32x4* slots = emb_stage + (threadIdx.x >> 6) * (DEPTH * kWaveSize);
+    for (int k0 = k_lo; k0 < k_hi; k0 += DEPTH) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        const int j = ((k0 + d) << gl) + g;
+        const int src = RANGE ? (j & (kWaveSize - 1)) : j;
+        const bool take = (!RANGE || (j >= j_lo && j < j_hi)) && (!PARTIAL || lane_ok);
+        uint32_t vo = (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)q.voff);
+        if constexpr (RANGE || PARTIAL) vo = take ? vo : kBufSentinel;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrc, (__attribute__((address_space(3))) void*)(slots + d * kWaveSize), 16,
+            (int)(vo + col), 0, 0, kAux);
+      }
+      consume_lds_slots<0, DEPTH, ELEM, OP>(acc, slots + (threadIdx.x & (kWaveSize - 1)),
+                                            meta_lane);
+      asm volatile("" ::: "memory");  // the slots are refilled only after they have been read
+    }
+    return;
+  }
   for (int k0 = k_lo; k0 < k_hi; k0 += DEPTH) {
     u32x4 r[DEPTH];
     float wj[DEPTH];

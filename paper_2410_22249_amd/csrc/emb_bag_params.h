@@ -19,6 +19,10 @@ constexpr uint32_t kBufWord3 = 0x00020000u;        // gfx9 buffer resource: 32-b
 
 // What a lookup does to the accumulator: plain sum, sum with per-sample weights, or maximum.
 constexpr int kOpSum = 0, kOpWeighted = 1, kOpMax = 2;
+// variants of the wave kernel (buffer addressing, tables of one width, depth 4 or 8): the hot /
+// cold split with the other rows read non-temporally or with the default policy, and the LDS
+// station (sum pooling)
+constexpr int kVariantPlain = 0, kVariantHotNt = 1, kVariantHot = 2, kVariantLds = 3;
 
 struct KParams {
   int64_t num_lookups;   // NL

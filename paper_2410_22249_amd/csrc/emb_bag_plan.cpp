@@ -47,14 +47,14 @@ constexpr int64_t kStreamMinWaves = 1024;
 
 // The kernels are built one lanes-per-row class per translation unit (emb_bag_wave.hip and
 // emb_bag_stream.hip, compiled once per class); here the classes are put back together.
-KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf, int hot = 0) {
+KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf, int variant = kVariantPlain) {
   switch (lpr) {
-    case 0: return pick_wave_kernel_lpr0(elem, depth, op, buf, hot);
-    case 4: return pick_wave_kernel_lpr4(elem, depth, op, buf, hot);
-    case 8: return pick_wave_kernel_lpr8(elem, depth, op, buf, hot);
-    case 16: return pick_wave_kernel_lpr16(elem, depth, op, buf, hot);
-    case 32: return pick_wave_kernel_lpr32(elem, depth, op, buf, hot);
-    case 64: return pick_wave_kernel_lpr64(elem, depth, op, buf, hot);
+    case 0: return pick_wave_kernel_lpr0(elem, depth, op, buf, variant);
+    case 4: return pick_wave_kernel_lpr4(elem, depth, op, buf, variant);
+    case 8: return pick_wave_kernel_lpr8(elem, depth, op, buf, variant);
+    case 16: return pick_wave_kernel_lpr16(elem, depth, op, buf, variant);
+    case 32: return pick_wave_kernel_lpr32(elem, depth, op, buf, variant);
+    case 64: return pick_wave_kernel_lpr64(elem, depth, op, buf, variant);
     default: return nullptr;
   }
 }
@@ -264,6 +264,7 @@ bool make_stream(const Tuning& tu, Launch* L, const emb_bag_desc* desc, bool wei
   L->fn = fn;
   L->kernel = EMB_KERNEL_STREAM;
   L->hot = false;  // the short-bag kernel reads every row of a table with the table's policy
+  L->lds_bytes = 0;  // ... into registers
   L->depth = depth <= 4 || lpr < 8 ? 4 : 8;  // the depths that kernel is built with
   L->p.bags_per_group = (uint32_t)m;
   L->p.bags_per_wave = 1;
@@ -321,8 +322,15 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   // policies, where it is built (buffer addressing, depth 4 or 8); otherwise the head is ignored
   wave.hot = desc->hot_rows != nullptr && g_tuning.hot_split != 0 && buf &&
              pick_kernel(lpr, desc->table_dtype, depth, op, buf, (int)g_tuning.hot_split) != nullptr;
-  wave.fn = pick_kernel(lpr, desc->table_dtype, depth, op, buf,
-                        wave.hot ? (int)g_tuning.hot_split : 0);
+  int variant = wave.hot ? (int)g_tuning.hot_split : kVariantPlain;
+  // the LDS station, where it is built (buffer addressing, sum pooling, depth 4 or 8, no hot /
+  // cold split); otherwise the key is ignored
+  if (g_tuning.station == 1 && !wave.hot &&
+      pick_kernel(lpr, desc->table_dtype, depth, op, buf, kVariantLds) != nullptr) {
+    variant = kVariantLds;
+    wave.lds_bytes = (uint32_t)(kWavesPerBlock * depth * kWaveSize * 16);
+  }
+  wave.fn = pick_kernel(lpr, desc->table_dtype, depth, op, buf, variant);
   if (!wave.fn) return EMB_ERR_BAD_TUNING;
 
   // Short bags: a lane group streams several consecutive bags (emb_bag_stream.hip).  Without
@@ -601,6 +609,7 @@ void report(const Launch& L, int32_t num_launches, emb_bag_plan* plan, uint16_t*
   plan->tables = L.tables;
   plan->bags_per_wave = L.kernel == EMB_KERNEL_WAVE ? (int32_t)L.p.bags_per_wave : 0;
   plan->hot_split = L.hot ? 1 : 0;
+  plan->station = L.lds_bytes ? 1 : 0;
   if (table_order)
     for (int64_t t = 0; t < L.tables && t < kMaxOrdered; ++t)
       table_order[t] = L.p.listed ? L.order.t[t] : (uint16_t)t;
@@ -641,6 +650,7 @@ int emb_bag_plan_forward(const emb_bag_desc* desc, int has_weights, int32_t whic
     plan->fused = 1;
     plan->fused_grid_blocks = fused.blocks;
     plan->hot_split = 0;  // the fused kernel has no hot / cold split
+    plan->station = 0;    // ... and keeps its rows in registers
   }
   return EMB_OK;
 }
@@ -708,6 +718,9 @@ int emb_bag_set_tuning(const char* key, int64_t value) {
   } else if (!strcmp(key, "hot_split")) {
     if (value < 0 || value > 2) return EMB_ERR_BAD_TUNING;
     g_tuning.hot_split = value;
+  } else if (!strcmp(key, "station")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    g_tuning.station = value;
   } else {
     return EMB_ERR_BAD_TUNING;
   }
@@ -745,6 +758,7 @@ int emb_bag_get_tuning(const char* key, int64_t* value) {
   else if (!strcmp(key, "fuse")) *value = g_tuning.fuse;
   else if (!strcmp(key, "bags_per_wave")) *value = g_tuning.bags_per_wave;
   else if (!strcmp(key, "hot_split")) *value = g_tuning.hot_split;
+  else if (!strcmp(key, "station")) *value = g_tuning.station;
   else return EMB_ERR_BAD_TUNING;
   return EMB_OK;
 }

@@ -27,6 +27,7 @@ struct Tuning {
   int64_t fuse = 1;             // 1 = the launches of a split call become one launch
   int64_t bags_per_wave = 0;    // wave kernel: consecutive bags per wavefront, 0 = automatic
   int64_t hot_split = 0;        // desc->hot_rows: 0 = not used, 1 = regroup + cold rows nt, 2 = regroup
+  int64_t station = 0;          // where row loads land: 0 = registers, 1 = LDS (paper Sec. 4.2)
 };
 extern Tuning g_tuning;
 
@@ -48,6 +49,7 @@ struct Launch {
   int depth = 0;
   bool buf = false;
   bool hot = false;       // the kernel splits a table's lookups into hot-head and other rows
+  uint32_t lds_bytes = 0; // dynamic LDS the kernel uses (the LDS station), else 0
 };
 
 // The launches of a split call as ONE launch: consecutive ranges of its workgroups run what

@@ -18,7 +18,14 @@
 //   * DEPTH row loads are issued back to back before the first is consumed (the register
 //     prefetch of Sec. 4.2, with the distance as a tuning knob, Sec. 7 step vi), and the many
 //     resident wavefronts per SIMD (the kernels need few VGPRs) supply the rest of the
-//     memory-level parallelism (the multithreading fix of Sec. 3.3);
+//     memory-level parallelism (the multithreading fix of Sec. 3.3); a variant lets the loads
+//     land in LDS instead (the shared-memory station of Sec. 4.2; opt-in, never faster here);
+//   * a wavefront may own several consecutive bags of a table: their bounds arrive with one
+//     load and the next bag's row ids are requested before the current bag's rows, so the
+//     offsets -> indices -> rows chain of Sec. 3.1 is paid once per wavefront, not per bag;
+//   * tables laid out with their most frequently used rows first (the offline hot-index
+//     profiling of Sec. 4.3) can have a bag's lookups regrouped hot rows first, the hot head
+//     read with the default cache policy and the rest non-temporally (opt-in);
 //   * rows are addressed through a per-table buffer resource with 32-bit offsets when the table
 //     is below 3.5 GiB: the hardware range check turns an invalid row into zeros instead of a
 //     fault, and address arithmetic stays 32-bit.  Larger tables use 64-bit global addressing
@@ -52,7 +59,7 @@ namespace {
 using namespace embbag;
 
 // The kernel proper is embbag::wave_body (emb_bag_bodies.h), shared with the fused launch.
-template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, int HOT>
+template <int LPR, int ELEM, int DEPTH, int OP, bool BUF, int HOT, bool LDS = false>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
@@ -60,20 +67,27 @@ emb_bag_wave_kernel(const char* __restrict__ tables, const int64_t* __restrict__
                     const int64_t* __restrict__ hot_rows,
                     const int64_t* __restrict__ out_offsets, float* __restrict__ out, KParams p,
                     TableOrder order) {
-  wave_body<LPR, ELEM, DEPTH, OP, BUF, HOT>(tables, table_offsets, indices, offsets, weights,
-                                            table_hints, hot_rows, out_offsets, out, p, order, 0u,
-                                            blockIdx.x);
+  wave_body<LPR, ELEM, DEPTH, OP, BUF, HOT, LDS>(tables, table_offsets, indices, offsets,
+                                                 weights, table_hints, hot_rows, out_offsets, out,
+                                                 p, order, 0u, blockIdx.x);
 }
 
-// buffer or 64-bit addressing; the hot / cold split (tables with a hot head) exists for buffer
-// addressing, tables of one width and depths 4 and 8
+// buffer or 64-bit addressing.  `variant` selects among the kernels built for buffer addressing,
+// tables of one width and depths 4 and 8: kVariantHotNt / kVariantHot = the hot / cold split
+// (tables with a hot head), kVariantLds = row loads through the LDS station (sum pooling).
 template <int LPR, int ELEM, int DEPTH, int OP>
-KernelFn pick_addr(bool buf, int hot) {
-  if (hot) {
+KernelFn pick_addr(bool buf, int variant) {
+  if (variant != kVariantPlain) {
     if constexpr (LPR != 0 && (DEPTH == 4 || DEPTH == 8)) {
       if (!buf) return nullptr;
-      return hot == 1 ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, 1>
-                      : emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, 2>;
+      if (variant == kVariantLds) {
+        if constexpr (OP == kOpSum)
+          return emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, 0, true>;
+        else
+          return nullptr;
+      }
+      return variant == kVariantHotNt ? emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, 1>
+                                      : emb_bag_wave_kernel<LPR, ELEM, DEPTH, OP, true, 2>;
     } else {
       return nullptr;
     }

@@ -96,7 +96,7 @@ int main(void) {
                                   {"stream", "0"}, {"xcd_remap", "1"}, {"xcd_pieces", "8"},
                                   {"bags_per_group", "63"}, {"bags_per_wave", "32"},
                                   {"per_table_launch", "1"}, {"fuse", "0"}, {"addressing", "1"},
-                                  {"hot_split", "1"}};
+                                  {"hot_split", "1"}, {"station", "1"}};
   const int nkeys = (int)(sizeof keys / sizeof keys[0]);
   float* lens = (float*)malloc(70000 * sizeof(float));
   int32_t* dims = (int32_t*)malloc(70000 * sizeof(int32_t));
@@ -137,7 +137,8 @@ int main(void) {
       static const char* defaults[][2] = {{"depth", "0"}, {"stream", "-1"}, {"xcd_remap", "-1"},
                                           {"xcd_pieces", "0"}, {"bags_per_group", "0"},
                                           {"bags_per_wave", "0"}, {"per_table_launch", "0"},
-                                          {"fuse", "1"}, {"addressing", "0"}, {"hot_split", "0"}};
+                                          {"fuse", "1"}, {"addressing", "0"}, {"hot_split", "0"},
+                                          {"station", "0"}};
       for (size_t i = 0; i < sizeof defaults / sizeof defaults[0]; ++i)
         if (emb_bag_set_tuning(defaults[i][0], atoll(defaults[i][1])) != EMB_OK) return 7;
     }

@@ -130,7 +130,7 @@ def test_full_size_sampled_bags(oracle, name, nsample):
         alts = (dict(xcd_remap=1), dict(fuse=0))
     else:
         alts = (dict(xcd_remap=1), dict(bags_per_group=3, depth=8) if name == "short"
-                else dict(addressing=1, depth=8))
+                else dict(addressing=1, depth=8), dict(station=1))   # (rows through LDS)
     for kw in alts:
         with tuning(**kw):
             emb.emb_bag_forward(desc, arena, toff, idx, off, w, out2)

@@ -579,6 +579,31 @@ def test_bags_per_wave_gives_the_same_bits(oracle, name, mode):
             assert np.array_equal(got.view(np.uint32), base.view(np.uint32)), (bpw, addressing)
 
 
+@pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
+                                  "small_u8_d120"])
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+def test_the_lds_station_gives_the_same_bits(oracle, name, mode):
+    """Row loads that land in LDS instead of registers (the shared-memory prefetch station of
+    paper Sec. 4.2) feed the same additions in the same order."""
+    import paper_2410_22249_amd as emb
+    wl, batch, arena = _problem(name)
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, mode)
+    dev = upload_arena(arena)
+    desc = emb.make_desc(wl.T, wl.B, wl.D, emb.DTYPES[wl.dtype], emb.MODES[mode], batch.num_lookups,
+                         0, max(wl.rows))
+    for depth in (4, 8):
+        for bpw in (1, 3):
+            with tuning(depth=depth, bags_per_wave=bpw, stream=0):
+                base = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                               mode).cpu().numpy()
+                with tuning(station=1):
+                    assert emb.emb_bag_plan_forward(desc).station == 1
+                    got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                                  mode).cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), base.view(np.uint32)), (depth, bpw)
+    assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"{name}/{mode} LDS station")
+
+
 @pytest.mark.parametrize("kernel", ["wave", "stream"])
 def test_every_finite_half_is_widened_exactly(kernel):
     """A table that holds every finite binary16 bit pattern (subnormals included), one lookup per

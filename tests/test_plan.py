@@ -410,6 +410,53 @@ def test_the_hot_head_is_opt_in():
         assert emb.emb_bag_plan_forward(plain).hot_split == 0
 
 
+def test_the_lds_station_is_opt_in():
+    """Row loads land in LDS only when the station tuning key asks for it (measured: never
+    faster), and only in the wave kernel with buffer addressing, unweighted sum or mean pooling,
+    a depth of 4 or 8, tables of one width, no hot / cold split and no fused launch."""
+    import torch
+
+    def station(mode=emb.EMB_SUM, rows=4_000_000, weights=False, dtype=emb.EMB_F32, D=128, L=80, **kw):
+        desc = emb.make_desc(60, 4096, D, dtype, mode, 60 * 4096 * L, 0, rows, **kw)
+        return emb.emb_bag_plan_forward(desc, weights).station
+
+    assert station() == 0
+    with tuning(station=1):
+        assert station() == 1 and station(emb.EMB_MEAN) == 1
+        for dtype, D in ((emb.EMB_F16, 128), (emb.EMB_BF16, 64), (emb.EMB_U8ROW, 120),
+                         (emb.EMB_FP8ROW, 56), (emb.EMB_F32, 4), (emb.EMB_F32, 1024)):
+            assert station(dtype=dtype, D=D, rows=500_000) == 1, (dtype, D)
+        assert station(emb.EMB_MAX) == 0
+        assert station(weights=True) == 0
+        assert station(rows=1 << 40) == 0                      # 64-bit addressing
+        assert station(L=1) == 0                               # the stream kernel
+        with tuning(stream=0):
+            assert station(L=1) == 1
+        for depth, want in ((1, 0), (2, 0), (4, 1), (8, 1), (16, 0)):
+            with tuning(depth=depth):
+                assert station() == want, depth
+        with tuning(addressing=1):
+            assert station() == 0
+        hot = torch.zeros(60, dtype=torch.int64)
+        assert station(hot_rows=hot) == 1                      # the head is ignored by default
+        with tuning(hot_split=1):
+            assert station(hot_rows=hot) == 0
+        # a split call that is fused keeps its rows in registers; taken apart, the wave part
+        # of it uses the station
+        lens = [1.0] * 30 + [100.0] * 30
+        d = emb.make_desc(60, 4096, 128, emb.EMB_F32, emb.EMB_SUM, 60 * 4096 * 50, 0, 4_000_000,
+                          table_avg_len=lens)
+        assert emb.emb_bag_plan_forward(d).fused == 1 and emb.emb_bag_plan_forward(d).station == 0
+        with tuning(fuse=0):
+            plans = [emb.emb_bag_plan_forward(d, which=k) for k in range(2)]
+            assert sorted(pl.station for pl in plans) == [0, 1]
+        mixed = emb.make_mixed_desc([32, 64] * 4, 2048, emb.EMB_F32, emb.EMB_SUM, 8 * 2048 * 40, 0,
+                                    1 << 30)
+        assert emb.emb_bag_plan_forward_mixed(mixed).station == 0
+    with pytest.raises(emb.EmbBagError):
+        emb.emb_bag_set_tuning("station", 2)
+
+
 def test_bags_per_wave_rule():
     """Automatic bags per wavefront: more for short bags, one for long bags, for rows beyond one
     slab, and whenever the launch would drop below 32,768 wavefronts."""
