@@ -69,6 +69,37 @@ extern "C" {
 #define EMB_ERR_BAD_TUNING (-9)  /* unknown tuning key or value out of range */
 
 /*
+ * Launch tuning of one descriptor (HOST struct, read during the call only): the keys of
+ * emb_bag_set_tuning as fields, with the same values and meanings (see there).  A descriptor
+ * whose `tuning` pointer is set is planned from this struct and from nothing process-wide except
+ * the tuning table (emb_bag_set_tuning_table, which fills the keys left automatic); one whose
+ * pointer is NULL uses the process-wide keys.  Two models served by one process can so hold
+ * different settings, and calls that carry their own tuning do not race with emb_bag_set_tuning.
+ * A value out of range makes the call return EMB_ERR_BAD_TUNING.  Fill it with
+ * emb_bag_tuning_defaults and change what differs.  No passage of the paper defines this struct;
+ * the knobs are those of its Sec. 3.3, Sec. 4.2 and Sec. 7.
+ */
+typedef struct emb_bag_tuning {
+  int32_t depth;            /* default 0 */
+  int32_t addressing;       /* 0 */
+  int32_t blocks_per_cu;    /* 0 */
+  int32_t xcd_remap;        /* -1 */
+  int32_t use_hints;        /* 1 */
+  int32_t stream;           /* -1 */
+  int32_t bags_per_group;   /* 0 */
+  int32_t xcd_pieces;       /* 0 */
+  int32_t per_table_launch; /* 0 */
+  int32_t fuse;             /* 1 */
+  int32_t bags_per_wave;    /* 0 */
+  int32_t hot_split;        /* 0 */
+  int32_t station;          /* 0 */
+  int32_t reserved[3];      /* 0 */
+} emb_bag_tuning;
+
+/* Writes the defaults listed above (the settings of a fresh process); EMB_ERR_NULL_PTR for NULL. */
+int emb_bag_tuning_defaults(emb_bag_tuning* tuning);
+
+/*
  * Shape of one call (HOST struct, read during the call only).
  *
  *   T = num_tables, B = batch, D = dim.  Row size in bytes = D * sizeof(element) (D + 8 for the
@@ -120,6 +151,8 @@ typedef struct emb_bag_desc {
                              Honoured by the one-wavefront-per-bag kernel with 32-bit buffer
                              addressing and a prefetch depth of 4 or 8 (plan->hot_split says
                              whether); ignored otherwise. */
+  const emb_bag_tuning* tuning; /* HOST, or NULL (= the process-wide keys of emb_bag_set_tuning):
+                             the launch tuning of this descriptor, see emb_bag_tuning */
 } emb_bag_desc;
 
 /*
@@ -206,6 +239,7 @@ typedef struct emb_bag_mixed_desc {
   const uint8_t* table_hints; /* DEVICE, T bytes of EMB_HINT_*, or NULL */
   const float* table_avg_len; /* HOST, T floats, or NULL: as in emb_bag_desc; decides per table
                               (instead of per call) which tables go to the short-bag kernel */
+  const emb_bag_tuning* tuning; /* HOST, or NULL: as in emb_bag_desc */
 } emb_bag_mixed_desc;
 
 int emb_bag_forward_mixed(const emb_bag_mixed_desc* desc, const void* tables,
@@ -453,7 +487,8 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   elsewhere, and in fused launches, the key is ignored (plan->station says
  *                   what a launch does).  Same results, bit for bit.  Measured on MI355X it is
  *                   never faster (a CU's registers hold more rows in flight than its LDS)
- * Not thread-safe against concurrent emb_bag_forward calls.
+ * Not thread-safe against concurrent emb_bag_forward calls whose descriptor has no tuning of its
+ * own (emb_bag_desc.tuning).
  */
 int emb_bag_set_tuning(const char* key, int64_t value);
 int emb_bag_get_tuning(const char* key, int64_t* value);

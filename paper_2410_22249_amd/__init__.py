@@ -7,7 +7,8 @@ from .binding import (EMB_BF16, EMB_F16, EMB_F32, EMB_HINT_DEFAULT, EMB_HINT_STR
                       emb_bag_plan_forward, emb_bag_plan_forward_mixed, EMB_KERNEL_WAVE,
                       EMB_KERNEL_STREAM,
                       emb_bag_mixed_desc, make_mixed_desc, emb_bag_get_tuning, emb_bag_set_tuning,
-                      emb_bag_set_tuning_table, emb_bag_tuning_entry,
+                      emb_bag_set_tuning_table, emb_bag_tuning_entry, emb_bag_tuning,
+                      emb_bag_tuning_defaults,
                       emb_bag_status_string, emb_bag_validate, emb_bag_version, lib, make_desc)
 from . import metrics
 
@@ -17,6 +18,6 @@ __all__ = ["EMB_U8ROW", "EMB_FP8ROW", "DTYPES", "EMB_BF16", "EMB_F16", "EMB_F32"
            "emb_bag_plan", "emb_bag_plan_forward", "emb_bag_plan_forward_mixed", "EMB_KERNEL_WAVE",
            "EMB_KERNEL_STREAM",
            "make_mixed_desc", "emb_bag_get_tuning", "emb_bag_set_tuning", "emb_bag_set_tuning_table",
-           "emb_bag_tuning_entry",
+           "emb_bag_tuning_entry", "emb_bag_tuning", "emb_bag_tuning_defaults",
            "emb_bag_status_string", "emb_bag_validate", "emb_bag_version", "lib", "make_desc",
            "metrics"]

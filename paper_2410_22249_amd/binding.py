@@ -29,7 +29,15 @@ EXPORTS = ("emb_bag_forward", "emb_bag_forward_mixed", "emb_bag_plan_forward",
            "emb_bag_plan_forward_mixed", "emb_bag_validate", "emb_bag_profile_reuse",
            "emb_bag_profile_hot_rows", "emb_bag_profile_hot_rows_workspace",
            "emb_bag_profile_hot_rows_noalloc",
-           "emb_bag_set_tuning", "emb_bag_get_tuning", "emb_bag_set_tuning_table", "emb_bag_status_string", "emb_bag_version")
+           "emb_bag_set_tuning", "emb_bag_get_tuning", "emb_bag_set_tuning_table",
+           "emb_bag_tuning_defaults", "emb_bag_status_string", "emb_bag_version")
+
+
+class emb_bag_tuning(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int32) for k in (
+        "depth", "addressing", "blocks_per_cu", "xcd_remap", "use_hints", "stream",
+        "bags_per_group", "xcd_pieces", "per_table_launch", "fuse", "bags_per_wave", "hot_split",
+        "station")] + [("reserved", ctypes.c_int32 * 3)]
 
 
 class emb_bag_desc(ctypes.Structure):
@@ -39,7 +47,7 @@ class emb_bag_desc(ctypes.Structure):
                 ("out_ld", ctypes.c_int64), ("max_table_rows", ctypes.c_int64),
                 ("table_hints", ctypes.c_void_p),
                 ("table_avg_len", ctypes.POINTER(ctypes.c_float)),
-                ("hot_rows", ctypes.c_void_p)]
+                ("hot_rows", ctypes.c_void_p), ("tuning", ctypes.POINTER(emb_bag_tuning))]
 
 
 class emb_bag_mixed_desc(ctypes.Structure):
@@ -48,7 +56,8 @@ class emb_bag_mixed_desc(ctypes.Structure):
                 ("batch", ctypes.c_int64), ("num_lookups", ctypes.c_int64),
                 ("out_ld", ctypes.c_int64), ("max_table_bytes", ctypes.c_int64),
                 ("dims", ctypes.POINTER(ctypes.c_int32)), ("table_hints", ctypes.c_void_p),
-                ("table_avg_len", ctypes.POINTER(ctypes.c_float))]
+                ("table_avg_len", ctypes.POINTER(ctypes.c_float)),
+                ("tuning", ctypes.POINTER(emb_bag_tuning))]
 
 
 class emb_bag_plan(ctypes.Structure):
@@ -112,6 +121,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.emb_bag_set_tuning.argtypes = [ctypes.c_char_p, ctypes.c_int64]
     lib.emb_bag_set_tuning_table.restype = ctypes.c_int
     lib.emb_bag_set_tuning_table.argtypes = [ctypes.POINTER(emb_bag_tuning_entry), ctypes.c_int32]
+    lib.emb_bag_tuning_defaults.restype = ctypes.c_int
+    lib.emb_bag_tuning_defaults.argtypes = [ctypes.POINTER(emb_bag_tuning)]
     lib.emb_bag_get_tuning.restype = ctypes.c_int
     lib.emb_bag_get_tuning.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64)]
     lib.emb_bag_status_string.restype = ctypes.c_char_p
@@ -144,11 +155,12 @@ def _stream_handle(stream) -> Optional[int]:
 def make_desc(num_tables: int, batch: int, dim: int, table_dtype: int, mode: int,
               num_lookups: int, out_ld: int = 0, max_table_rows: int = 0,
               table_hints: Optional[torch.Tensor] = None, table_avg_len=None,
-              hot_rows: Optional[torch.Tensor] = None) -> emb_bag_desc:
+              hot_rows: Optional[torch.Tensor] = None, tuning=None) -> emb_bag_desc:
     """Fill the host descriptor.  `table_hints` (device uint8 [T]) and `hot_rows` (device int64
     [T]) are tensors, or None, that the caller keeps alive for as long as the descriptor is used;
     `table_avg_len` is a host sequence of T floats (or None), of which the descriptor keeps its
-    own copy."""
+    own copy; `tuning` is a dict of tuning keys (the others at their defaults) that this
+    descriptor is planned from instead of the process-wide keys, or None."""
     if table_hints is not None:
         if table_hints.dtype != torch.uint8 or table_hints.numel() != num_tables:
             raise ValueError("table_hints must be a uint8 tensor with one entry per table")
@@ -160,7 +172,29 @@ def make_desc(num_tables: int, batch: int, dim: int, table_dtype: int, mode: int
                         max_table_rows=max_table_rows, table_hints=_ptr(table_hints),
                         hot_rows=_ptr(hot_rows))
     _attach_avg_len(desc, table_avg_len, num_tables)
+    _attach_tuning(desc, tuning)
     return desc
+
+
+def emb_bag_tuning_defaults() -> emb_bag_tuning:
+    """The tuning struct with the settings of a fresh process."""
+    t = emb_bag_tuning()
+    rc = _lib.emb_bag_tuning_defaults(ctypes.byref(t))
+    if rc != EMB_OK:
+        raise EmbBagError(rc, "emb_bag_tuning_defaults")
+    return t
+
+
+def _attach_tuning(desc, tuning) -> None:
+    if tuning is None:
+        return
+    t = emb_bag_tuning_defaults()
+    for k, v in tuning.items():
+        if k not in dict(emb_bag_tuning._fields_) or k == "reserved":
+            raise ValueError(f"unknown tuning key {k!r}")
+        setattr(t, k, int(v))
+    desc.tuning = ctypes.pointer(t)
+    desc._tuning_keepalive = t
 
 
 def _attach_avg_len(desc, table_avg_len, num_tables: int) -> None:
@@ -189,7 +223,7 @@ def emb_bag_forward(desc: emb_bag_desc, tables: torch.Tensor, table_offsets: tor
 def make_mixed_desc(dims, batch: int, table_dtype: int, mode: int, num_lookups: int,
                     out_ld: int = 0, max_table_bytes: int = 0,
                     table_hints: Optional[torch.Tensor] = None,
-                    table_avg_len=None) -> emb_bag_mixed_desc:
+                    table_avg_len=None, tuning=None) -> emb_bag_mixed_desc:
     """Host descriptor for tables of different widths; `dims` is a sequence of the T widths and
     `table_avg_len` an optional sequence of T floats (the descriptor keeps its own host copies)."""
     arr = (ctypes.c_int32 * len(dims))(*[int(d) for d in dims])
@@ -200,6 +234,7 @@ def make_mixed_desc(dims, batch: int, table_dtype: int, mode: int, num_lookups: 
                               table_hints=_ptr(table_hints))
     desc._dims_keepalive = arr
     _attach_avg_len(desc, table_avg_len, len(dims))
+    _attach_tuning(desc, tuning)
     return desc
 
 

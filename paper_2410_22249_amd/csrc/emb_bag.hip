@@ -131,15 +131,15 @@ emb_bag_profile_kernel(const int64_t* __restrict__ indices, const int64_t* __res
 
 // A cap on resident workgroups per CU is imposed through a dynamic LDS request that the kernel
 // never touches: k workgroups fit when each asks for 1/k of the CU's LDS.
-int occupancy_cap_lds(const void* fn, uint32_t* lds) {
+int occupancy_cap_lds(const void* fn, int64_t blocks_per_cu, uint32_t* lds) {
   *lds = 0;
-  if (g_tuning.blocks_per_cu <= 0) return EMB_OK;
+  if (blocks_per_cu <= 0) return EMB_OK;
   int dev = 0, lds_per_cu = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor,
                             dev) != hipSuccess || lds_per_cu <= 0)
     return EMB_ERR_LAUNCH;
-  *lds = ((uint32_t)lds_per_cu / (uint32_t)g_tuning.blocks_per_cu) & ~1023u;
+  *lds = ((uint32_t)lds_per_cu / (uint32_t)blocks_per_cu) & ~1023u;
   if (*lds > 65536u &&
       hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)*lds) != hipSuccess)
     return EMB_ERR_LAUNCH;
@@ -152,7 +152,8 @@ int launch(const Launch& L, const void* tables, const int64_t* table_offsets,
            const uint8_t* table_hints, const int64_t* hot_rows, const int64_t* out_offsets,
            float* out, void* stream) {
   uint32_t lds = 0;
-  const int rc = occupancy_cap_lds(reinterpret_cast<const void*>(L.fn), &lds);
+  const int rc = occupancy_cap_lds(reinterpret_cast<const void*>(L.fn), L.tuning.blocks_per_cu,
+                                   &lds);
   if (rc != EMB_OK) return rc;
   if (lds < L.lds_bytes) lds = L.lds_bytes;  // the LDS station's slots (at most 32 KiB)
   hipLaunchKernelGGL(L.fn, dim3(L.blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
@@ -166,7 +167,7 @@ int launch_fused(const FusedLaunch& F, const void* tables, const int64_t* table_
                  const uint8_t* table_hints, const int64_t* out_offsets, float* out,
                  void* stream) {
   uint32_t lds = 0;
-  const int rc = occupancy_cap_lds(reinterpret_cast<const void*>(F.fn), &lds);
+  const int rc = occupancy_cap_lds(reinterpret_cast<const void*>(F.fn), F.blocks_per_cu, &lds);
   if (rc != EMB_OK) return rc;
   hipLaunchKernelGGL(F.fn, dim3(F.blocks), dim3(kBlock), lds, static_cast<hipStream_t>(stream),
                      static_cast<const char*>(tables), table_offsets, indices, offsets, weights,

@@ -20,8 +20,8 @@ constexpr int kMaxTableEntries = 64;
 emb_bag_tuning_entry g_table[kMaxTableEntries];
 int g_table_entries = 0;
 
-Tuning effective_tuning(uint32_t row_bytes, double avg_len) {
-  Tuning tu = g_tuning;
+Tuning effective_tuning(const Tuning& base, uint32_t row_bytes, double avg_len) {
+  Tuning tu = base;
   for (int i = 0; i < g_table_entries; ++i) {
     const emb_bag_tuning_entry& e = g_table[i];
     if ((int64_t)row_bytes > (int64_t)e.max_row_bytes || avg_len > (double)e.max_avg_len) continue;
@@ -121,16 +121,17 @@ void plan_grid(int64_t n, const uint16_t* ids, const uint16_t* row_units, bool n
   p.num_work = (uint32_t)(n * (int64_t)p.wpt);
   p.xcd_bpp = p.xcd_wpp = p.xcd_pshift = p.xcd_units = p.listed = 0;
   uint32_t blocks = (uint32_t)(((uint64_t)p.num_work + kWavesPerBlock - 1) / kWavesPerBlock);
-  const bool remap = g_tuning.xcd_remap == 1 || (g_tuning.xcd_remap == -1 && blocks >= 4096);
+  const Tuning& base = L->tuning;
+  const bool remap = base.xcd_remap == 1 || (base.xcd_remap == -1 && blocks >= 4096);
   bool ordered = false;
   if (remap && blocks >= 64 && !natural_order) {
     // pieces per table: the smallest power of two that makes n * pieces a multiple of 8, so
     // that every XCD gets the same number of pieces and neighbouring XCDs share a table
     uint32_t pshift = 0;
     while (((uint64_t)n << pshift) % 8 != 0) ++pshift;
-    if (g_tuning.xcd_pieces > 0) {  // forced: XCDs may then differ by one piece
+    if (base.xcd_pieces > 0) {  // forced: XCDs may then differ by one piece
       pshift = 0;
-      while ((1 << pshift) < g_tuning.xcd_pieces) ++pshift;
+      while ((1 << pshift) < base.xcd_pieces) ++pshift;
     }
     const uint64_t wpp = ((uint64_t)p.wpt + (1u << pshift) - 1) >> pshift;
     const uint64_t bpp = (wpp + kWavesPerBlock - 1) / kWavesPerBlock;
@@ -272,6 +273,75 @@ bool make_stream(const Tuning& tu, Launch* L, const emb_bag_desc* desc, bool wei
   return true;
 }
 
+// One tuning key, checked (the values emb_bag_set_tuning documents).
+int set_key(Tuning* tu, const char* key, int64_t value) {
+  if (!strcmp(key, "depth")) {
+    if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
+      return EMB_ERR_BAD_TUNING;
+    tu->depth = value;
+  } else if (!strcmp(key, "addressing")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    tu->addressing = value;
+  } else if (!strcmp(key, "blocks_per_cu")) {
+    if (value < 0 || value > 8) return EMB_ERR_BAD_TUNING;
+    tu->blocks_per_cu = value;
+  } else if (!strcmp(key, "xcd_remap")) {
+    if (value < -1 || value > 1) return EMB_ERR_BAD_TUNING;
+    tu->xcd_remap = value;
+  } else if (!strcmp(key, "use_hints")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    tu->use_hints = value;
+  } else if (!strcmp(key, "stream")) {
+    if (value < -1 || value > 1) return EMB_ERR_BAD_TUNING;
+    tu->stream = value;
+  } else if (!strcmp(key, "bags_per_group")) {
+    if (value < 0 || value > 63) return EMB_ERR_BAD_TUNING;
+    tu->bags_per_group = value;
+  } else if (!strcmp(key, "per_table_launch")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    tu->per_table_launch = value;
+  } else if (!strcmp(key, "fuse")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    tu->fuse = value;
+  } else if (!strcmp(key, "xcd_pieces")) {
+    if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+      return EMB_ERR_BAD_TUNING;
+    tu->xcd_pieces = value;
+  } else if (!strcmp(key, "bags_per_wave")) {
+    if (value < 0 || value > kWaveMaxBags) return EMB_ERR_BAD_TUNING;
+    tu->bags_per_wave = value;
+  } else if (!strcmp(key, "hot_split")) {
+    if (value < 0 || value > 2) return EMB_ERR_BAD_TUNING;
+    tu->hot_split = value;
+  } else if (!strcmp(key, "station")) {
+    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
+    tu->station = value;
+  } else {
+    return EMB_ERR_BAD_TUNING;
+  }
+  return EMB_OK;
+}
+
+// The tuning a call is planned from: the descriptor's own, checked, or the process-wide keys.
+int base_tuning(const emb_bag_tuning* t, Tuning* out) {
+  if (!t) {
+    *out = g_tuning;
+    return EMB_OK;
+  }
+  *out = Tuning();
+  const struct { const char* key; int32_t value; } fields[] = {
+      {"depth", t->depth}, {"addressing", t->addressing}, {"blocks_per_cu", t->blocks_per_cu},
+      {"xcd_remap", t->xcd_remap}, {"use_hints", t->use_hints}, {"stream", t->stream},
+      {"bags_per_group", t->bags_per_group}, {"xcd_pieces", t->xcd_pieces},
+      {"per_table_launch", t->per_table_launch}, {"fuse", t->fuse},
+      {"bags_per_wave", t->bags_per_wave}, {"hot_split", t->hot_split}, {"station", t->station}};
+  for (const auto& f : fields) {
+    const int rc = set_key(out, f.key, f.value);
+    if (rc != EMB_OK) return rc;
+  }
+  return EMB_OK;
+}
+
 // The host-side decisions of emb_bag_forward for a checked descriptor with batch > 0: one launch,
 // or two when desc->table_avg_len separates tables with short bags from the others.
 int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, int64_t out_ld,
@@ -286,16 +356,21 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   const uint32_t span = row_bytes < (uint32_t)kSlabBytes ? row_bytes : (uint32_t)kSlabBytes;
   while ((uint32_t)lpr * 16u < span) lpr *= 2;
 
+  Tuning base;  // the descriptor's tuning, or the process-wide keys
+  const int trc = base_tuning(desc->tuning, &base);
+  if (trc != EMB_OK) return trc;
   bool buf = desc->max_table_rows > 0 &&
              (uint64_t)desc->max_table_rows * row_bytes <= kBufMaxBytes;
-  if (g_tuning.addressing == 1) buf = false;
+  if (base.addressing == 1) buf = false;
 
-  // the tuning keys, with the keys left automatic filled in from the tuning table
-  const Tuning tu = effective_tuning(row_bytes, (double)desc->num_lookups / ((double)T * (double)B));
+  // ... with the keys left automatic filled in from the tuning table
+  const Tuning tu = effective_tuning(base, row_bytes,
+                                     (double)desc->num_lookups / ((double)T * (double)B));
   int depth = (int)tu.depth;
   if (depth == 0) depth = (desc->table_dtype == EMB_F32 && row_bytes >= 512) ? 8 : 4;
 
   Launch wave;  // the one-wavefront-per-bag launch; the stream launch is derived from it
+  wave.tuning = base;
   KParams& p = wave.p;
   p.num_lookups = desc->num_lookups;
   p.out_ld = out_ld;
@@ -306,7 +381,7 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   p.row_bytes = row_bytes;
   p.D = (uint32_t)D;
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
-  p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
+  p.has_hints = (desc->table_hints != nullptr && base.use_hints != 0) ? 1u : 0u;
   p.bags_per_group = 0;
   const int groups = kWaveSize / lpr;
   const double avg_len = (double)desc->num_lookups / ((double)T * (double)B);
@@ -320,12 +395,12 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   if (op == kOpMax) wave.depth = depth <= 4 ? 4 : 8;
   // tables with a hot head: the kernel that reads hot and other rows with different cache
   // policies, where it is built (buffer addressing, depth 4 or 8); otherwise the head is ignored
-  wave.hot = desc->hot_rows != nullptr && g_tuning.hot_split != 0 && buf &&
-             pick_kernel(lpr, desc->table_dtype, depth, op, buf, (int)g_tuning.hot_split) != nullptr;
-  int variant = wave.hot ? (int)g_tuning.hot_split : kVariantPlain;
+  wave.hot = desc->hot_rows != nullptr && base.hot_split != 0 && buf &&
+             pick_kernel(lpr, desc->table_dtype, depth, op, buf, (int)base.hot_split) != nullptr;
+  int variant = wave.hot ? (int)base.hot_split : kVariantPlain;
   // the LDS station, where it is built (buffer addressing, sum pooling, depth 4 or 8, no hot /
   // cold split); otherwise the key is ignored
-  if (g_tuning.station == 1 && !wave.hot &&
+  if (base.station == 1 && !wave.hot &&
       pick_kernel(lpr, desc->table_dtype, depth, op, buf, kVariantLds) != nullptr) {
     variant = kVariantLds;
     wave.lds_bytes = (uint32_t)(kWavesPerBlock * depth * kWaveSize * 16);
@@ -339,7 +414,7 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   const double threshold = kStreamBelowRowLoads * groups;
   const bool can_stream = tu.stream != 0 && slabs == 1 && buf && desc->mode != EMB_MAX;
   const std::vector<uint16_t> none;
-  if (g_tuning.per_table_launch == 1 && T <= 65535) {
+  if (base.per_table_launch == 1 && T <= 65535) {
     // the paper's launch structure, for comparison: the tables one after the other
     Launch stream = wave;
     const bool s = can_stream && (tu.stream == 1 || avg_len < threshold) &&
@@ -425,15 +500,19 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
   const int64_t T = desc->num_tables, B = desc->batch;
   if (B > 0x7FFFFFFF || T * B > 0x7FFFFFFF) return EMB_ERR_BAD_SIZE;
   const int elem_bytes = desc->table_dtype == EMB_F32 ? 4 : 2;
+  Tuning tu0;  // the descriptor's tuning, or the process-wide keys
+  const int trc = base_tuning(desc->tuning, &tu0);
+  if (trc != EMB_OK) return trc;
   bool buf = desc->max_table_bytes > 0 && (uint64_t)desc->max_table_bytes <= kBufMaxBytes;
-  if (g_tuning.addressing == 1) buf = false;
-  const Tuning tu = effective_tuning(max_row_bytes,
+  if (tu0.addressing == 1) buf = false;
+  const Tuning tu = effective_tuning(tu0, max_row_bytes,
                                      (double)desc->num_lookups / ((double)T * (double)B));
   int depth = (int)tu.depth;
   if (depth == 0) depth = (desc->table_dtype == EMB_F32 && max_row_bytes >= 512) ? 8 : 4;
   const int op = desc->mode == EMB_MAX ? kOpMax : (weighted ? kOpWeighted : kOpSum);
 
   Launch base;
+  base.tuning = tu0;
   KParams& p = base.p;
   p.num_lookups = desc->num_lookups;
   p.out_ld = out_ld;
@@ -444,7 +523,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
   p.row_bytes = max_row_bytes;
   p.D = 0;
   p.mean = desc->mode == EMB_MEAN ? 1u : 0u;
-  p.has_hints = (desc->table_hints != nullptr && g_tuning.use_hints != 0) ? 1u : 0u;
+  p.has_hints = (desc->table_hints != nullptr && tu0.use_hints != 0) ? 1u : 0u;
   base.kernel = EMB_KERNEL_WAVE;
   base.lpr = 0;
   base.depth = depth <= 4 ? 4 : 8;  // the depths the mixed-width kernels are built with
@@ -539,7 +618,8 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
 // otherwise one width (segment 0 the wave body, 1 the stream body, both with lanes per row lpr).
 bool plan_fused(const std::vector<Launch>& segs, bool mixed, int table_dtype, bool weighted,
                 FusedLaunch* F) {
-  if (g_tuning.fuse == 0 || segs.size() < 2 || segs.size() > (size_t)kFusedSegments) return false;
+  if (segs.size() < 2 || segs.size() > (size_t)kFusedSegments || segs[0].tuning.fuse == 0)
+    return false;
   const Launch* by_slot[kFusedSegments] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   int64_t tables = 0;
   int depth = 0, lpr = 0;
@@ -588,6 +668,7 @@ bool plan_fused(const std::vector<Launch>& segs, bool mixed, int table_dtype, bo
     F->f.end_block[k] = (uint32_t)end;
   }
   F->blocks = (uint32_t)end;
+  F->blocks_per_cu = segs[0].tuning.blocks_per_cu;
   return true;
 }
 
@@ -680,50 +761,26 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
 
 int emb_bag_set_tuning(const char* key, int64_t value) {
   if (!key) return EMB_ERR_NULL_PTR;
-  if (!strcmp(key, "depth")) {
-    if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
-      return EMB_ERR_BAD_TUNING;
-    g_tuning.depth = value;
-  } else if (!strcmp(key, "addressing")) {
-    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
-    g_tuning.addressing = value;
-  } else if (!strcmp(key, "blocks_per_cu")) {
-    if (value < 0 || value > 8) return EMB_ERR_BAD_TUNING;
-    g_tuning.blocks_per_cu = value;
-  } else if (!strcmp(key, "xcd_remap")) {
-    if (value < -1 || value > 1) return EMB_ERR_BAD_TUNING;
-    g_tuning.xcd_remap = value;
-  } else if (!strcmp(key, "use_hints")) {
-    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
-    g_tuning.use_hints = value;
-  } else if (!strcmp(key, "stream")) {
-    if (value < -1 || value > 1) return EMB_ERR_BAD_TUNING;
-    g_tuning.stream = value;
-  } else if (!strcmp(key, "bags_per_group")) {
-    if (value < 0 || value > 63) return EMB_ERR_BAD_TUNING;
-    g_tuning.bags_per_group = value;
-  } else if (!strcmp(key, "per_table_launch")) {
-    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
-    g_tuning.per_table_launch = value;
-  } else if (!strcmp(key, "fuse")) {
-    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
-    g_tuning.fuse = value;
-  } else if (!strcmp(key, "xcd_pieces")) {
-    if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
-      return EMB_ERR_BAD_TUNING;
-    g_tuning.xcd_pieces = value;
-  } else if (!strcmp(key, "bags_per_wave")) {
-    if (value < 0 || value > kWaveMaxBags) return EMB_ERR_BAD_TUNING;
-    g_tuning.bags_per_wave = value;
-  } else if (!strcmp(key, "hot_split")) {
-    if (value < 0 || value > 2) return EMB_ERR_BAD_TUNING;
-    g_tuning.hot_split = value;
-  } else if (!strcmp(key, "station")) {
-    if (value < 0 || value > 1) return EMB_ERR_BAD_TUNING;
-    g_tuning.station = value;
-  } else {
-    return EMB_ERR_BAD_TUNING;
-  }
+  return set_key(&g_tuning, key, value);
+}
+
+int emb_bag_tuning_defaults(emb_bag_tuning* t) {
+  if (!t) return EMB_ERR_NULL_PTR;
+  const Tuning d;
+  memset(t, 0, sizeof *t);
+  t->depth = (int32_t)d.depth;
+  t->addressing = (int32_t)d.addressing;
+  t->blocks_per_cu = (int32_t)d.blocks_per_cu;
+  t->xcd_remap = (int32_t)d.xcd_remap;
+  t->use_hints = (int32_t)d.use_hints;
+  t->stream = (int32_t)d.stream;
+  t->bags_per_group = (int32_t)d.bags_per_group;
+  t->xcd_pieces = (int32_t)d.xcd_pieces;
+  t->per_table_launch = (int32_t)d.per_table_launch;
+  t->fuse = (int32_t)d.fuse;
+  t->bags_per_wave = (int32_t)d.bags_per_wave;
+  t->hot_split = (int32_t)d.hot_split;
+  t->station = (int32_t)d.station;
   return EMB_OK;
 }
 
@@ -779,5 +836,5 @@ const char* emb_bag_status_string(int status) {
   }
 }
 
-int emb_bag_version(void) { return 500; }
+int emb_bag_version(void) { return 600; }
 }  // extern "C"

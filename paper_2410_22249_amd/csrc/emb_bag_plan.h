@@ -50,6 +50,7 @@ struct Launch {
   bool buf = false;
   bool hot = false;       // the kernel splits a table's lookups into hot-head and other rows
   uint32_t lds_bytes = 0; // dynamic LDS the kernel uses (the LDS station), else 0
+  Tuning tuning;          // what the call was planned from (the descriptor's, or process-wide)
 };
 
 // The launches of a split call as ONE launch: consecutive ranges of its workgroups run what
@@ -59,6 +60,7 @@ struct FusedLaunch {
   FusedParams f;
   TableOrder order;
   uint32_t blocks = 0;
+  int64_t blocks_per_cu = 0;  // occupancy cap of the call (tuning key), 0 = none
 };
 
 int check_desc(const emb_bag_desc* d, uint32_t* row_bytes_out);

@@ -21,6 +21,7 @@ static uint32_t rnd(void) {
 }
 
 static long calls = 0, ok_calls = 0;
+static const emb_bag_tuning* desc_tuning = NULL; /* what the descriptors of a pass carry */
 
 static void plan_uniform(int32_t T, int64_t B, int32_t D, int dtype, int mode, double avg,
                          const float* lens, int weights, int64_t max_rows, const void* hot) {
@@ -35,6 +36,7 @@ static void plan_uniform(int32_t T, int64_t B, int32_t D, int dtype, int mode, d
   d.max_table_rows = max_rows;
   d.table_avg_len = lens;
   d.hot_rows = (const int64_t*)hot;
+  d.tuning = desc_tuning;
   /* exactly min(T, 1024) entries: a write beyond them is an overflow the sanitizer sees */
   const int n = T < 1024 ? T : 1024;
   uint16_t* order = (uint16_t*)malloc((size_t)n * sizeof(uint16_t));
@@ -70,6 +72,7 @@ static void plan_mixed(int32_t T, int64_t B, const int32_t* dims, int dtype, int
   d.max_table_bytes = max_bytes;
   d.dims = dims;
   d.table_avg_len = lens;
+  d.tuning = desc_tuning;
   const int n = T < 1024 ? T : 1024;
   uint16_t* order = (uint16_t*)malloc((size_t)n * sizeof(uint16_t));
   emb_bag_plan p;
@@ -101,13 +104,25 @@ int main(void) {
   float* lens = (float*)malloc(70000 * sizeof(float));
   int32_t* dims = (int32_t*)malloc(70000 * sizeof(int32_t));
   int64_t fake_hot = 0; /* the plan only tests the pointer */
-  for (int k = -1; k < nkeys; ++k) {
-    if (k >= 0 && emb_bag_set_tuning(keys[k][0], atoll(keys[k][1])) != EMB_OK) return 6;
+  /* the last pass: descriptors that carry their own tuning, in a heap block of its exact size */
+  emb_bag_tuning* own = (emb_bag_tuning*)malloc(sizeof(emb_bag_tuning));
+  if (emb_bag_tuning_defaults(own) != EMB_OK || emb_bag_tuning_defaults(NULL) != EMB_ERR_NULL_PTR)
+    return 11;
+  own->depth = 4;
+  own->station = 1;
+  own->xcd_pieces = 8;
+  own->bags_per_wave = 32;
+  own->blocks_per_cu = 2;
+  for (int k = -1; k <= nkeys; ++k) {
+    if (k == nkeys) desc_tuning = own;
+    if (k >= 0 && k < nkeys && emb_bag_set_tuning(keys[k][0], atoll(keys[k][1])) != EMB_OK)
+      return 6;
     for (size_t ti = 0; ti < sizeof tables / sizeof tables[0]; ++ti) {
       const int32_t T = tables[ti];
       /* one launch per table makes T launches of 2 KB each: the table counts around the list
          limit are enough for it, and the key sweeps stay below the 16-bit limit */
-      if (k >= 0 && (T > 2600 || (!strcmp(keys[k][0], "per_table_launch") && T > 1025))) continue;
+      if (k >= 0 && (T > 2600 || (k < nkeys && !strcmp(keys[k][0], "per_table_launch") && T > 1025)))
+        continue;
       for (int i = 0; i < T; ++i) lens[i] = (rnd() % 4 == 0) ? (float)(rnd() % 200) : (float)(rnd() % 5);
       for (size_t bi = 0; bi < sizeof batches / sizeof batches[0]; ++bi) {
         const int64_t B = batches[bi];
@@ -133,7 +148,7 @@ int main(void) {
         }
       }
     }
-    if (k >= 0) {  /* back to the default */
+    if (k >= 0 && k < nkeys) {  /* back to the default */
       static const char* defaults[][2] = {{"depth", "0"}, {"stream", "-1"}, {"xcd_remap", "-1"},
                                           {"xcd_pieces", "0"}, {"bags_per_group", "0"},
                                           {"bags_per_wave", "0"}, {"per_table_launch", "0"},
@@ -146,6 +161,22 @@ int main(void) {
   /* argument errors come back as codes */
   emb_bag_plan p;
   if (emb_bag_plan_forward(NULL, 0, 0, &p, NULL) != EMB_ERR_NULL_PTR) return 8;
+  {
+    emb_bag_desc d;
+    memset(&d, 0, sizeof d);
+    d.num_tables = 8;
+    d.dim = 64;
+    d.batch = 128;
+    d.num_lookups = 8 * 128 * 100;
+    d.max_table_rows = 100000; /* buffer addressing, which the LDS station needs */
+    d.tuning = own;
+    own->depth = 3; /* not a depth */
+    if (emb_bag_plan_forward(&d, 0, 0, &p, NULL) != EMB_ERR_BAD_TUNING) return 12;
+    own->depth = 8;
+    if (emb_bag_plan_forward(&d, 0, 0, &p, NULL) != EMB_OK || p.depth != 8 || p.station != 1)
+      return 13;
+  }
+  free(own);
   if (emb_bag_set_tuning("no such key", 1) != EMB_ERR_BAD_TUNING) return 9;
   printf("sanitized planning: %ld calls, %ld accepted\n", calls, ok_calls);
   free(lens);

@@ -42,16 +42,18 @@ def test_status_codes_and_strings_match_header():
 
 def test_desc_layout_matches_header():
     import paper_2410_22249_amd as emb
-    assert ctypes.sizeof(emb.emb_bag_desc) == 4 * 4 + 4 * 8 + 3 * 8
+    assert ctypes.sizeof(emb.emb_bag_desc) == 4 * 4 + 4 * 8 + 4 * 8
     assert emb.emb_bag_desc.batch.offset == 16 and emb.emb_bag_desc.max_table_rows.offset == 40
     assert emb.emb_bag_desc.table_hints.offset == 48 and emb.emb_bag_desc.table_avg_len.offset == 56
-    assert emb.emb_bag_desc.hot_rows.offset == 64
+    assert emb.emb_bag_desc.hot_rows.offset == 64 and emb.emb_bag_desc.tuning.offset == 72
+    assert ctypes.sizeof(emb.emb_bag_tuning) == 64
 
 
 def test_mixed_desc_layout_and_host_errors():
     import paper_2410_22249_amd as emb
-    assert ctypes.sizeof(emb.emb_bag_mixed_desc) == 4 * 4 + 4 * 8 + 3 * 8
+    assert ctypes.sizeof(emb.emb_bag_mixed_desc) == 4 * 4 + 4 * 8 + 4 * 8
     assert emb.emb_bag_mixed_desc.dims.offset == 48 and emb.emb_bag_mixed_desc.table_avg_len.offset == 64
+    assert emb.emb_bag_mixed_desc.tuning.offset == 72
     lib = emb.lib()
     fake = ctypes.c_void_p(0x1000)
 

@@ -41,7 +41,8 @@ def test_binding_structs_match_the_header_as_the_c_compiler_lays_it_out(tmp_path
     import ctypes
     import paper_2410_22249_amd as emb
     structs = {"emb_bag_desc": emb.emb_bag_desc, "emb_bag_mixed_desc": emb.emb_bag_mixed_desc,
-               "emb_bag_plan": emb.emb_bag_plan}
+               "emb_bag_plan": emb.emb_bag_plan, "emb_bag_tuning": emb.emb_bag_tuning,
+               "emb_bag_tuning_entry": emb.emb_bag_tuning_entry}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "emb_bag.h"', "int main(void) {"]
     for cname, cls in structs.items():
         lines.append(f'  printf("{cname} %zu\\n", sizeof({cname}));')

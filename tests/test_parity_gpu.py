@@ -579,6 +579,35 @@ def test_bags_per_wave_gives_the_same_bits(oracle, name, mode):
             assert np.array_equal(got.view(np.uint32), base.view(np.uint32)), (bpw, addressing)
 
 
+def test_a_descriptor_with_its_own_tuning_runs_as_planned(oracle):
+    """emb_bag_desc.tuning: the call runs what the process-wide keys with the same values would
+    run (same bits), whatever the process-wide keys say meanwhile."""
+    import paper_2410_22249_amd as emb
+    wl, batch, arena = _problem("small_f32_d128")
+    ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "sum")
+    dev, toff = upload_arena(arena), to_dev(wl.table_offsets())
+    idx, off = to_dev(batch.indices), to_dev(batch.offsets)
+    for own in (dict(depth=2, bags_per_wave=3, stream=0), dict(station=1, depth=4, stream=0, xcd_remap=1),
+                dict(stream=1, bags_per_group=5), dict(blocks_per_cu=2, addressing=1)):
+        with tuning(**own):
+            want = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B)
+            plan_want = emb.emb_bag_plan_forward(emb.make_desc(
+                wl.T, wl.B, wl.D, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups, 0, max(wl.rows))).as_dict()
+        desc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups, 0,
+                             max(wl.rows), tuning=own)
+        with tuning(depth=16, stream=-1, bags_per_wave=7):     # must not matter
+            assert emb.emb_bag_plan_forward(desc).as_dict() == plan_want
+            out = torch.full((wl.B, wl.T * wl.D), float("nan"), dtype=torch.float32, device=DEV)
+            emb.emb_bag_forward(desc, dev, toff, idx, off, None, out)
+            torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int32), want.view(torch.int32)), own
+        assert_close_to_oracle(out.cpu().numpy(), ref, bound, False, f"desc tuning {own}")
+    bad = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F32, emb.EMB_SUM, batch.num_lookups, 0,
+                        max(wl.rows), tuning=dict(depth=5))
+    with pytest.raises(emb.EmbBagError):
+        emb.emb_bag_forward(bad, dev, toff, idx, off, None, out)
+
+
 @pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
                                   "small_u8_d120"])
 @pytest.mark.parametrize("mode", ["sum", "mean"])

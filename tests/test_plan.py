@@ -410,6 +410,47 @@ def test_the_hot_head_is_opt_in():
         assert emb.emb_bag_plan_forward(plain).hot_split == 0
 
 
+def test_a_descriptor_can_carry_its_own_tuning():
+    """emb_bag_desc.tuning replaces the process-wide keys for that descriptor (two models in one
+    process can hold different settings); a value out of range is an error of the call."""
+    shape = (60, 4096, 128, emb.EMB_F32, emb.EMB_SUM, 60 * 4096 * 80, 0, 4_000_000)
+    plain = emb.make_desc(*shape)
+    own = emb.make_desc(*shape, tuning=dict(depth=2, bags_per_wave=3, xcd_remap=0))
+    other = emb.make_desc(*shape, tuning=dict(station=1, depth=4))
+    with tuning(depth=16, bags_per_wave=1):
+        a, b, c = (emb.emb_bag_plan_forward(d) for d in (plain, own, other))
+        assert (a.depth, a.bags_per_wave, a.station) == (16, 1, 0) and a.xcd_pieces > 0
+        assert (b.depth, b.bags_per_wave, b.station, b.xcd_pieces) == (2, 3, 0, 0)
+        assert (c.depth, c.station) == (4, 1) and c.bags_per_wave == 1 and c.xcd_pieces > 0
+        assert emb.emb_bag_get_tuning("depth") == 16          # nothing process-wide was touched
+    # the defaults are those of a fresh process
+    t = emb.emb_bag_tuning_defaults()
+    for key, _ in emb.emb_bag_tuning._fields_:
+        if key != "reserved":
+            assert getattr(t, key) == emb.emb_bag_get_tuning(key), key
+    with tuning(depth=8, stream=0):
+        assert emb.emb_bag_plan_forward(emb.make_desc(*shape, tuning={})).depth == 8   # automatic: 8
+        short = (60, 4096, 128, emb.EMB_F32, emb.EMB_SUM, 60 * 4096, 0, 4_000_000)
+        assert emb.emb_bag_plan_forward(emb.make_desc(*short)).kernel == emb.EMB_KERNEL_WAVE
+        assert emb.emb_bag_plan_forward(emb.make_desc(*short, tuning={})).kernel == emb.EMB_KERNEL_STREAM
+    for bad in (dict(depth=3), dict(station=2), dict(bags_per_wave=33), dict(xcd_pieces=3),
+                dict(stream=-2), dict(blocks_per_cu=9)):
+        with pytest.raises(emb.EmbBagError) as e:
+            emb.emb_bag_plan_forward(emb.make_desc(*shape, tuning=bad))
+        assert e.value.status == -9, bad
+    with pytest.raises(ValueError):
+        emb.make_desc(*shape, tuning=dict(no_such_key=1))
+    # tables of different widths: the same field
+    lens = [1.0] * 4 + [60.0] * 4
+    mshape = ([32, 64] * 4, 2048, emb.EMB_F32, emb.EMB_SUM, 8 * 2048 * 30, 0, 1 << 30)
+    fused = emb.make_mixed_desc(*mshape, table_avg_len=lens)
+    apart = emb.make_mixed_desc(*mshape, table_avg_len=lens, tuning=dict(fuse=0))
+    assert emb.emb_bag_plan_forward_mixed(fused).fused == 1
+    assert emb.emb_bag_plan_forward_mixed(apart).fused == 0
+    with pytest.raises(emb.EmbBagError):
+        emb.emb_bag_plan_forward_mixed(emb.make_mixed_desc(*mshape, tuning=dict(depth=5)))
+
+
 def test_the_lds_station_is_opt_in():
     """Row loads land in LDS only when the station tuning key asks for it (measured: never
     faster), and only in the wave kernel with buffer addressing, unweighted sum or mean pooling,
