@@ -459,8 +459,8 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   -1 = automatic (average bag length num_lookups / (T * batch) below three
  *                   load instructions' worth of rows, i.e. 3 * 1024 / row bytes rounded to a
  *                   power of two: 24 at 128-byte rows, 12 at 256, 6 at 512, 3 at 1 KiB; rows of
- *                   at most 1 KiB, buffer addressing), 0 = never, 1 = whenever rows and
- *                   addressing allow it.  It adds a bag's rows in the order of its lookups; the
+ *                   at most 1 KiB, buffer addressing; every pooling mode), 0 = never, 1 =
+ *                   whenever rows and addressing allow it.  It adds a bag's rows in the order of its lookups; the
  *                   one-wavefront-per-bag kernel keeps several partial sums, so the two agree
  *                   to rounding, not to the bit.
  *                   With desc->table_avg_len the automatic choice is made per table.
@@ -469,8 +469,9 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   become consecutive workgroup ranges of one launch (same results, bit for
  *                   bit; no ramp and drain per launch, which dominates at inference batch
  *                   sizes); possible when the launches' table lists hold at most 1024 tables
- *                   together (and, for emb_bag_forward, the depth is 4 or 8).  0 = separate
- *                   launches
+ *                   together (and, for emb_bag_forward, the depth is 4 or 8), for sum and mean
+ *                   pooling (with or without weights); EMB_MAX calls keep their launches.
+ *                   0 = separate launches
  *   "bags_per_wave" consecutive bags of a table that one wavefront of the one-wavefront-per-bag
  *                   kernel takes, 1..32; 0 = automatic (more for short bags, 1 for rows beyond
  *                   1 KiB).  The bounds of a wavefront's bags come with one load and the next

@@ -229,7 +229,7 @@ __device__ __forceinline__ bool any_lane(bool c) { return __builtin_amdgcn_ballo
 // gw (weights); `pk` holds, in lane r of the group, (relative end << 6 | bag number within the
 // group) of the group's r-th non-empty bag, kNoBag beyond; out_rsrc covers the wavefront's
 // output rows and `store0` is the byte offset of this lane's elements in its group's first bag.
-template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool NT>
+template <int LPR, int ELEM, int DEPTH, int OP, bool NT>
 __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
                                               const float* __restrict__ gw, uint32_t glen,
                                               uint32_t pk, int64_t R, uint32_t row_bytes,
@@ -238,18 +238,21 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
                                               uint32_t out_ld_bytes, uint32_t D, bool mean,
                                               int lane, uint32_t col, bool lane_ok,
                                               int meta_lane) {
+  constexpr bool WEIGHTED = OP == kOpWeighted;
+  constexpr bool MAXP = OP == kOpMax;
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;
   constexpr bool QUANT = IsQuant<ELEM>::value;
-  constexpr int NACC = AccCount<ELEM>::value;
-  constexpr int NOUT = QUANT ? 16 : NACC;
+  constexpr int NACC = AccCount<ELEM, OP>::value;
+  constexpr int NOUT = OutCount<ELEM>::value;
   constexpr int kAux = NT ? 2 : 0;  // cache-policy bits of the row loads: 2 = nt
   const int l = lane & (LPR - 1);
   const int group_base = lane & ~(LPR - 1);
   const uint32_t elem0 = QUANT ? col : (HALF ? col / 2 : col / 4);
 
-  float acc[NACC];
+  float acc[NACC], acc0[NACC];  // (acc0: what a bag starts from)
+  init_acc<ELEM, OP>(acc0);
 #pragma unroll
-  for (int i = 0; i < NACC; ++i) acc[i] = 0.0f;
+  for (int i = 0; i < NACC; ++i) acc[i] = acc0[i];
 
   // the group's current (non-empty) bag: rank among the non-empty ones, relative bounds, number
   uint32_t rank = 0, bag_start = 0;
@@ -283,21 +286,28 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
         uint32_t vo = (uint32_t)__shfl((int)voff, group_base + k0 + d);
-        vo = lane_ok ? vo : kBufSentinel;
-        r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
         if constexpr (WEIGHTED)
           wj[d] = __shfl(wt, group_base + k0 + d);
+        else if constexpr (MAXP)
+          wj[d] = vo != kBufSentinel ? 1.0f : 0.0f;  // marks a lookup of a row that exists
         else
           wj[d] = 1.0f;
+        vo = lane_ok ? vo : kBufSentinel;
+        r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
       }
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
-        accumulate<ELEM, WEIGHTED ? kOpWeighted : kOpSum>(acc, r[d], wj[d], meta_lane);
+        accumulate<ELEM, OP>(acc, r[d], wj[d], meta_lane);
         const bool flush = qbase + (uint32_t)(k0 + d) + 1u == next_end;  // this lookup ends a bag
         float v[NOUT];
 #pragma unroll
-        for (int i = 0; i < NOUT; ++i) v[i] = QUANT ? acc[i] + acc[16] : acc[i];
-        if (mean && any_lane(flush)) {
+        for (int i = 0; i < NOUT; ++i) {
+          if constexpr (MAXP)  // the last accumulator counts the bag's valid lookups
+            v[i] = acc[NOUT] > 0.0f ? acc[i] : 0.0f;
+          else
+            v[i] = QUANT ? acc[i] + acc[16] : acc[i];
+        }
+        if (!MAXP && mean && any_lane(flush)) {
           const float fl = (float)(next_end - bag_start);  // > 0: the bag is not empty
 #pragma unroll
           for (int i = 0; i < NOUT; ++i) v[i] = v[i] / fl;
@@ -314,7 +324,7 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
                                                  (int)(in_row ? so + 16u * q : kBufSentinel), 0, 2);
         }
 #pragma unroll
-        for (int i = 0; i < NACC; ++i) acc[i] = flush ? 0.0f : acc[i];
+        for (int i = 0; i < NACC; ++i) acc[i] = flush ? acc0[i] : acc[i];
         if (any_lane(flush)) {  // move the groups that stored to their next non-empty bag
           rank += flush ? 1u : 0u;
           bag_start = flush ? next_end : bag_start;
@@ -329,12 +339,11 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
   }
 }
 
-// One wavefront per G * M consecutive bags of one table (see the head of this file).  Sum and
-// mean pooling; max pooling always takes the wave kernel.  MIXED: the launch covers tables of
+// One wavefront per G * M consecutive bags of one table (see the head of this file).  MIXED: the launch covers tables of
 // different widths that share LPR lanes per row; table t is then described by table_offsets[t]
 // (its BYTE offset in the arena) and out_offsets[t] (its first output column; its width is the
 // difference to the next entry), as for the wave kernel.
-template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool MIXED>
+template <int LPR, int ELEM, int DEPTH, int OP, bool MIXED>
 __device__ __forceinline__ void stream_body(
     const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
@@ -346,8 +355,9 @@ __device__ __forceinline__ void stream_body(
   constexpr int GL = __builtin_ctz((unsigned)G);
   constexpr bool HALF = ELEM == EMB_F16 || ELEM == EMB_BF16;
   constexpr bool QUANT = IsQuant<ELEM>::value;
-  constexpr int NACC = AccCount<ELEM>::value;
-  constexpr int NOUT = QUANT ? 16 : NACC;
+  constexpr bool WEIGHTED = OP == kOpWeighted;
+  constexpr int NACC = AccCount<ELEM, OP>::value;
+  constexpr int NOUT = OutCount<ELEM>::value;
 
   const int lane = threadIdx.x & (kWaveSize - 1);
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -423,13 +433,11 @@ __device__ __forceinline__ void stream_body(
       s = s < 0 ? 0 : (s > p.num_lookups ? p.num_lookups : s);
       e = e < s ? s : (e > p.num_lookups ? p.num_lookups : e);
       float acc[NACC];
-#pragma unroll
-      for (int k = 0; k < NACC; ++k) acc[k] = 0.0f;
-      gather_bag<LPR, ELEM, 2, WEIGHTED ? kOpWeighted : kOpSum, true, false>(acc, indices, weights, s, e, R, row_bytes,
-                                                      tbase, rsrc, lane, g, col, lane_ok,
-                                                      meta_lane, GL);
-      finish_bag<LPR, ELEM, kOpSum>(acc, LPR, lane, lane_ok, col, D_t, e - s, p.mean != 0, out,
-                                    p.out_ld, b0 + i, out_col);
+      init_acc<ELEM, OP>(acc);
+      gather_bag<LPR, ELEM, 2, OP, true, false>(acc, indices, weights, s, e, R, row_bytes, tbase,
+                                                rsrc, lane, g, col, lane_ok, meta_lane, GL);
+      finish_bag<LPR, ELEM, OP>(acc, LPR, lane, lane_ok, col, D_t, e - s, p.mean != 0, out,
+                                p.out_ld, b0 + i, out_col);
     }
     return;
   }
@@ -474,13 +482,13 @@ __device__ __forceinline__ void stream_body(
   const int64_t* gi = indices + S;
   const float* gw = WEIGHTED ? weights + S : nullptr;
   if (streaming)
-    stream_groups<LPR, ELEM, DEPTH, WEIGHTED, true>(gi, gw, glen, pk, R, row_bytes, rsrc, out_rsrc,
-                                                    store0, out_ld_bytes, D_t, p.mean != 0, lane,
-                                                    col, lane_ok, meta_lane);
+    stream_groups<LPR, ELEM, DEPTH, OP, true>(gi, gw, glen, pk, R, row_bytes, rsrc, out_rsrc,
+                                              store0, out_ld_bytes, D_t, p.mean != 0, lane, col,
+                                              lane_ok, meta_lane);
   else
-    stream_groups<LPR, ELEM, DEPTH, WEIGHTED, false>(gi, gw, glen, pk, R, row_bytes, rsrc,
-                                                     out_rsrc, store0, out_ld_bytes, D_t,
-                                                     p.mean != 0, lane, col, lane_ok, meta_lane);
+    stream_groups<LPR, ELEM, DEPTH, OP, false>(gi, gw, glen, pk, R, row_bytes, rsrc, out_rsrc,
+                                               store0, out_ld_bytes, D_t, p.mean != 0, lane, col,
+                                               lane_ok, meta_lane);
 }
 
 }  // namespace embbag

@@ -45,19 +45,19 @@ emb_bag_fused_kernel(const char* __restrict__ tables, const int64_t* __restrict_
   if (blk < f.end_block[0])
     wave_body<0, ELEM, DEPTH, OP, true>(EMB_ARGS, f.seg[0], order, f.order_base[0], blk);
   else if (blk < f.end_block[1])
-    stream_body<4, ELEM, 4, WEIGHTED, true>(EMB_ARGS, f.seg[1], order, f.order_base[1],
+    stream_body<4, ELEM, 4, OP, true>(EMB_ARGS, f.seg[1], order, f.order_base[1],
                                             blk - f.end_block[0]);
   else if (blk < f.end_block[2])
-    stream_body<8, ELEM, DEPTH, WEIGHTED, true>(EMB_ARGS, f.seg[2], order, f.order_base[2],
+    stream_body<8, ELEM, DEPTH, OP, true>(EMB_ARGS, f.seg[2], order, f.order_base[2],
                                                 blk - f.end_block[1]);
   else if (blk < f.end_block[3])
-    stream_body<16, ELEM, DEPTH, WEIGHTED, true>(EMB_ARGS, f.seg[3], order, f.order_base[3],
+    stream_body<16, ELEM, DEPTH, OP, true>(EMB_ARGS, f.seg[3], order, f.order_base[3],
                                                  blk - f.end_block[2]);
   else if (blk < f.end_block[4])
-    stream_body<32, ELEM, DEPTH, WEIGHTED, true>(EMB_ARGS, f.seg[4], order, f.order_base[4],
+    stream_body<32, ELEM, DEPTH, OP, true>(EMB_ARGS, f.seg[4], order, f.order_base[4],
                                                  blk - f.end_block[3]);
   else if (blk < f.end_block[5])
-    stream_body<64, ELEM, DEPTH, WEIGHTED, true>(EMB_ARGS, f.seg[5], order, f.order_base[5],
+    stream_body<64, ELEM, DEPTH, OP, true>(EMB_ARGS, f.seg[5], order, f.order_base[5],
                                                  blk - f.end_block[4]);
 #undef EMB_ARGS
 }

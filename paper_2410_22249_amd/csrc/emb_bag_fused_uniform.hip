@@ -42,7 +42,7 @@ emb_bag_fused_uniform_kernel(const char* __restrict__ tables,
                                           table_hints, hot_rows, out_offsets, out, f.seg[0], order,
                                           f.order_base[0], blk);
   else if (blk < f.end_block[1])
-    stream_body<LPR, ELEM, STREAM_DEPTH, WEIGHTED, false>(tables, table_offsets, indices, offsets,
+    stream_body<LPR, ELEM, STREAM_DEPTH, OP, false>(tables, table_offsets, indices, offsets,
                                                           weights, table_hints, hot_rows, out_offsets, out,
                                                           f.seg[1], order, f.order_base[1],
                                                           blk - f.end_block[0]);

@@ -111,9 +111,9 @@ EMB_DECLARE_FUSED_UNIFORM(64)
 #define EMB_PASTE(a, b) EMB_PASTE_(a, b)
 #define EMB_DECLARE_PICKERS(n)                                                                  \
   __attribute__((visibility("hidden"))) KernelFn pick_wave_kernel_lpr##n(                       \
-      int elem, int depth, int op, bool buf, int hot);                                          \
+      int elem, int depth, int op, bool buf, int variant);                                      \
   __attribute__((visibility("hidden"))) KernelFn pick_stream_kernel_lpr##n(                     \
-      int elem, int depth, bool weighted, bool mixed);
+      int elem, int depth, int op, bool mixed);
 EMB_DECLARE_PICKERS(0)  // (there is no stream kernel for class 0; the declaration is unused)
 EMB_DECLARE_PICKERS(4)
 EMB_DECLARE_PICKERS(8)

@@ -59,13 +59,13 @@ KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf, int variant
   }
 }
 
-KernelFn pick_stream_kernel(int lpr, int elem, int depth, bool weighted, bool mixed) {
+KernelFn pick_stream_kernel(int lpr, int elem, int depth, int op, bool mixed) {
   switch (lpr) {
-    case 4: return pick_stream_kernel_lpr4(elem, depth, weighted, mixed);
-    case 8: return pick_stream_kernel_lpr8(elem, depth, weighted, mixed);
-    case 16: return pick_stream_kernel_lpr16(elem, depth, weighted, mixed);
-    case 32: return pick_stream_kernel_lpr32(elem, depth, weighted, mixed);
-    case 64: return pick_stream_kernel_lpr64(elem, depth, weighted, mixed);
+    case 4: return pick_stream_kernel_lpr4(elem, depth, op, mixed);
+    case 8: return pick_stream_kernel_lpr8(elem, depth, op, mixed);
+    case 16: return pick_stream_kernel_lpr16(elem, depth, op, mixed);
+    case 32: return pick_stream_kernel_lpr32(elem, depth, op, mixed);
+    case 64: return pick_stream_kernel_lpr64(elem, depth, op, mixed);
     default: return nullptr;
   }
 }
@@ -253,14 +253,14 @@ void add_launches(const Launch& proto, int64_t T, const std::vector<uint16_t>& i
 
 // Turn `proto` (a wave-kernel launch of a uniform call) into a stream-kernel launch over
 // `tables` tables of average bag length avg_len; false if the stream kernel cannot take it.
-bool make_stream(const Tuning& tu, Launch* L, const emb_bag_desc* desc, bool weighted, int depth,
+bool make_stream(const Tuning& tu, Launch* L, const emb_bag_desc* desc, int op, int depth,
                  double avg_len, int64_t tables, int64_t out_ld) {
   const int lpr = L->lpr, groups = kWaveSize / lpr;
   const int64_t B = desc->batch;
   const int64_t m = stream_bags_per_group(tu, avg_len, lpr, tables, B);
   // the wavefront's output rows are addressed through one buffer with 32-bit offsets
   if ((uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u > kBufMaxBytes) return false;
-  KernelFn fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted, false);
+  KernelFn fn = pick_stream_kernel(lpr, desc->table_dtype, depth, op, false);
   if (!fn) return false;
   L->fn = fn;
   L->kernel = EMB_KERNEL_STREAM;
@@ -392,6 +392,7 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   wave.depth = depth;
   wave.buf = buf;
   const int op = desc->mode == EMB_MAX ? kOpMax : (weighted ? kOpWeighted : kOpSum);
+  wave.op = op;
   if (op == kOpMax) wave.depth = depth <= 4 ? 4 : 8;
   // tables with a hot head: the kernel that reads hot and other rows with different cache
   // policies, where it is built (buffer addressing, depth 4 or 8); otherwise the head is ignored
@@ -412,13 +413,13 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   // per-table lengths the host knows the call's average bag length, NL / (T * B), and nothing
   // else; with them each table is judged by its own.
   const double threshold = kStreamBelowRowLoads * groups;
-  const bool can_stream = tu.stream != 0 && slabs == 1 && buf && desc->mode != EMB_MAX;
+  const bool can_stream = tu.stream != 0 && slabs == 1 && buf;
   const std::vector<uint16_t> none;
   if (base.per_table_launch == 1 && T <= 65535) {
     // the paper's launch structure, for comparison: the tables one after the other
     Launch stream = wave;
     const bool s = can_stream && (tu.stream == 1 || avg_len < threshold) &&
-                   make_stream(tu, &stream, desc, weighted, depth, avg_len, 1, out_ld);
+                   make_stream(tu, &stream, desc, op, depth, avg_len, 1, out_ld);
     for (int64_t t = 0; t < T; ++t)
       add_launches(s ? stream : wave, T, std::vector<uint16_t>(1, (uint16_t)t), none, launches);
     return EMB_OK;
@@ -437,7 +438,7 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
     }
     Launch stream = wave;
     if (!short_ids.empty() && !long_ids.empty() &&
-        make_stream(tu, &stream, desc, weighted, depth, short_sum / (double)short_ids.size(),
+        make_stream(tu, &stream, desc, op, depth, short_sum / (double)short_ids.size(),
                     (int64_t)short_ids.size(), out_ld)) {
       // the wave part's bags per wavefront follow its own tables
       p.bags_per_wave = (uint32_t)wave_bags_per_wave(tu, long_sum / (double)long_ids.size(), groups,
@@ -448,7 +449,7 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
       return EMB_OK;
     }
     // all tables on one side: one launch without a list
-    if (long_ids.empty() && make_stream(tu, &stream, desc, weighted, depth, avg_len, T, out_ld))
+    if (long_ids.empty() && make_stream(tu, &stream, desc, op, depth, avg_len, T, out_ld))
       add_launches(stream, T, none, none, launches);
     else
       add_launches(wave, T, none, none, launches);
@@ -456,7 +457,7 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   }
   Launch stream = wave;
   if (can_stream && (tu.stream == 1 || avg_len < threshold) &&
-      make_stream(tu, &stream, desc, weighted, depth, avg_len, T, out_ld))
+      make_stream(tu, &stream, desc, op, depth, avg_len, T, out_ld))
     add_launches(stream, T, none, none, launches);
   else
     add_launches(wave, T, none, none, launches);
@@ -528,6 +529,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
   base.lpr = 0;
   base.depth = depth <= 4 ? 4 : 8;  // the depths the mixed-width kernels are built with
   base.buf = buf;
+  base.op = op;
   base.fn = pick_kernel(0, desc->table_dtype, depth, op, buf);
   if (!base.fn) return EMB_ERR_BAD_TUNING;
 
@@ -540,7 +542,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
     p.wpt = (uint32_t)((B + p.bags_per_wave - 1) / p.bags_per_wave);
   }
   // (judged by the call's average bag length, or table by table with desc->table_avg_len)
-  const bool can_stream = tu.stream != 0 && buf && desc->mode != EMB_MAX;
+  const bool can_stream = tu.stream != 0 && buf;
   const bool per_table = tu.stream == -1 && desc->table_avg_len != nullptr;
   bool fits[7] = {false, false, false, false, false, false, false};  // by log2(lanes per row)
   for (int lg = 2; lg <= 6 && can_stream; ++lg) {
@@ -597,7 +599,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
       const int groups = kWaveSize / lpr;
       const int64_t m = stream_bags_per_group(tu, len_sum / (double)ids.size(), lpr,
                                               (int64_t)ids.size(), B);
-      L.fn = pick_stream_kernel(lpr, desc->table_dtype, depth, weighted, true);
+      L.fn = pick_stream_kernel(lpr, desc->table_dtype, depth, op, true);
       if (!L.fn) return EMB_ERR_BAD_TUNING;
       L.kernel = EMB_KERNEL_STREAM;
       L.lpr = lpr;
@@ -620,6 +622,7 @@ bool plan_fused(const std::vector<Launch>& segs, bool mixed, int table_dtype, bo
                 FusedLaunch* F) {
   if (segs.size() < 2 || segs.size() > (size_t)kFusedSegments || segs[0].tuning.fuse == 0)
     return false;
+  if (segs[0].op == kOpMax) return false;  // the fused kernels are built for sums
   const Launch* by_slot[kFusedSegments] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   int64_t tables = 0;
   int depth = 0, lpr = 0;

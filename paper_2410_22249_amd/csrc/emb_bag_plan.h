@@ -48,6 +48,7 @@ struct Launch {
   int lpr = 0;
   int depth = 0;
   bool buf = false;
+  int op = kOpSum;        // pooling of the call: kOpSum (sum and mean), kOpWeighted, kOpMax
   bool hot = false;       // the kernel splits a table's lookups into hot-head and other rows
   uint32_t lds_bytes = 0; // dynamic LDS the kernel uses (the LDS station), else 0
   Tuning tuning;          // what the call was planned from (the descriptor's, or process-wide)

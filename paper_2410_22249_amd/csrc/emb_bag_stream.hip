@@ -40,7 +40,7 @@ namespace {
 using namespace embbag;
 
 // The kernel proper is embbag::stream_body (emb_bag_bodies.h), shared with the fused launch.
-template <int LPR, int ELEM, int DEPTH, bool WEIGHTED, bool MIXED>
+template <int LPR, int ELEM, int DEPTH, int OP, bool MIXED>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                       const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
@@ -48,29 +48,35 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
                       const int64_t* __restrict__ hot_rows,
                       const int64_t* __restrict__ out_offsets, float* __restrict__ out,
                       KParams p, TableOrder order) {
-  stream_body<LPR, ELEM, DEPTH, WEIGHTED, MIXED>(tables, table_offsets, indices, offsets, weights,
-                                                 table_hints, hot_rows, out_offsets, out, p, order, 0u,
-                                                 blockIdx.x);
+  stream_body<LPR, ELEM, DEPTH, OP, MIXED>(tables, table_offsets, indices, offsets, weights,
+                                           table_hints, hot_rows, out_offsets, out, p, order, 0u,
+                                           blockIdx.x);
+}
+
+template <int LPR, int ELEM, int DEPTH, bool MIXED>
+KernelFn pick_op(int op) {
+  switch (op) {
+    case kOpSum: return emb_bag_stream_kernel<LPR, ELEM, DEPTH, kOpSum, MIXED>;
+    case kOpWeighted: return emb_bag_stream_kernel<LPR, ELEM, DEPTH, kOpWeighted, MIXED>;
+    case kOpMax: return emb_bag_stream_kernel<LPR, ELEM, DEPTH, kOpMax, MIXED>;
+    default: return nullptr;
+  }
 }
 
 template <int LPR, int ELEM, bool MIXED>
-KernelFn pick_w(int depth, bool weighted) {
+KernelFn pick_d(int depth, int op) {
   constexpr int D8 = LPR >= 8 ? 8 : 4;  // a group holds LPR lookups per chunk: DEPTH <= LPR
-  if (depth <= 4)
-    return weighted ? emb_bag_stream_kernel<LPR, ELEM, 4, true, MIXED>
-                    : emb_bag_stream_kernel<LPR, ELEM, 4, false, MIXED>;
-  return weighted ? emb_bag_stream_kernel<LPR, ELEM, D8, true, MIXED>
-                  : emb_bag_stream_kernel<LPR, ELEM, D8, false, MIXED>;
+  return depth <= 4 ? pick_op<LPR, ELEM, 4, MIXED>(op) : pick_op<LPR, ELEM, D8, MIXED>(op);
 }
 
 template <int LPR, bool MIXED>
-KernelFn pick_e(int elem, int depth, bool weighted) {
+KernelFn pick_e(int elem, int depth, int op) {
   switch (elem) {
-    case EMB_F32: return pick_w<LPR, EMB_F32, MIXED>(depth, weighted);
-    case EMB_F16: return pick_w<LPR, EMB_F16, MIXED>(depth, weighted);
-    case EMB_BF16: return pick_w<LPR, EMB_BF16, MIXED>(depth, weighted);
-    case EMB_U8ROW: return pick_w<LPR, EMB_U8ROW, MIXED>(depth, weighted);
-    case EMB_FP8ROW: return pick_w<LPR, EMB_FP8ROW, MIXED>(depth, weighted);
+    case EMB_F32: return pick_d<LPR, EMB_F32, MIXED>(depth, op);
+    case EMB_F16: return pick_d<LPR, EMB_F16, MIXED>(depth, op);
+    case EMB_BF16: return pick_d<LPR, EMB_BF16, MIXED>(depth, op);
+    case EMB_U8ROW: return pick_d<LPR, EMB_U8ROW, MIXED>(depth, op);
+    case EMB_FP8ROW: return pick_d<LPR, EMB_FP8ROW, MIXED>(depth, op);
     default: return nullptr;
   }
 }
@@ -79,10 +85,8 @@ KernelFn pick_e(int elem, int depth, bool weighted) {
 
 namespace embbag {
 
-KernelFn EMB_PASTE(pick_stream_kernel_lpr, EMB_LPR)(int elem, int depth, bool weighted,
-                                                     bool mixed) {
-  return mixed ? pick_e<EMB_LPR, true>(elem, depth, weighted)
-               : pick_e<EMB_LPR, false>(elem, depth, weighted);
+KernelFn EMB_PASTE(pick_stream_kernel_lpr, EMB_LPR)(int elem, int depth, int op, bool mixed) {
+  return mixed ? pick_e<EMB_LPR, true>(elem, depth, op) : pick_e<EMB_LPR, false>(elem, depth, op);
 }
 
 }  // namespace embbag

@@ -33,7 +33,8 @@ def test_max_pooling_matches_oracle(oracle, name):
     ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "max")
     dev = upload_arena(arena)
     for kw in (dict(), dict(addressing=1), dict(depth=1), dict(depth=8), dict(depth=16, xcd_remap=1),
-               dict(blocks_per_cu=2), dict(stream=1)):
+               dict(blocks_per_cu=2), dict(stream=1), dict(stream=1, bags_per_group=1),
+               dict(stream=1, bags_per_group=3, depth=8), dict(stream=1, bags_per_group=63, depth=4)):
         with tuning(**kw):
             got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "max").cpu().numpy()
         _check(got, ref, bound, wl.dtype, f"max/{name}/{kw}")
@@ -43,11 +44,18 @@ def test_max_pooling_matches_oracle(oracle, name):
 def test_max_pooling_short_and_empty_bags(oracle, name):
     wl, batch, arena = _problem(name, pooling=("uniform", 0, 3))
     ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B, "max")
-    got = forward(upload_arena(arena), wl.table_offsets(), batch.indices, batch.offsets, wl.B,
-                  "max").cpu().numpy()
-    _check(got, ref, bound, wl.dtype, f"max short/{name}")
-    empty = np.repeat(np.diff(batch.offsets).reshape(wl.T, wl.B).T == 0, wl.D, axis=1)
-    assert empty.any() and np.all(got[empty] == 0) and not np.signbit(got[empty]).any()
+    dev = upload_arena(arena)
+    desc = emb.make_desc(wl.T, wl.B, wl.D, emb.DTYPES[wl.dtype], emb.EMB_MAX, batch.num_lookups, 0,
+                         max(wl.rows))
+    # bags this short take the stream kernel by themselves; the wave kernel must agree
+    assert emb.emb_bag_plan_forward(desc).kernel == emb.EMB_KERNEL_STREAM
+    for kw in (dict(), dict(stream=0), dict(stream=1, bags_per_group=2), dict(stream=1, bags_per_group=15)):
+        with tuning(**kw):
+            got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                          "max").cpu().numpy()
+        _check(got, ref, bound, wl.dtype, f"max short/{name}/{kw}")
+        empty = np.repeat(np.diff(batch.offsets).reshape(wl.T, wl.B).T == 0, wl.D, axis=1)
+        assert empty.any() and np.all(got[empty] == 0) and not np.signbit(got[empty]).any()
 
 
 @pytest.mark.parametrize("D,dtype", [(4, "f32"), (12, "f32"), (96, "f32"), (320, "f32"), (24, "f16"),
@@ -87,12 +95,12 @@ def test_max_pooling_skips_invalid_lookups(oracle):
     ref, bound = oracle.emb_bag(arena, toff, batch.indices[keep], gen.lengths_to_offsets(lens),
                                 wl.B, "max")
     dev = upload_arena(arena)
-    for addressing in (0, 1):
-        with tuning(addressing=addressing):
+    for kw in (dict(addressing=0), dict(addressing=1), dict(stream=1), dict(stream=1, bags_per_group=4)):
+        with tuning(**kw):
             got = forward(dev, toff, idx, batch.offsets, wl.B, "max").cpu().numpy()
-        assert np.array_equal(got.astype(np.float64), ref), addressing
-    t, b = divmod(g, wl.B)
-    assert np.all(got[b, t * wl.D:(t + 1) * wl.D] == 0)
+        assert np.array_equal(got.astype(np.float64), ref), kw
+        t, b = divmod(g, wl.B)
+        assert np.all(got[b, t * wl.D:(t + 1) * wl.D] == 0)
 
 
 def test_max_pooling_mixed_widths_and_hints(oracle):
@@ -103,11 +111,33 @@ def test_max_pooling_mixed_widths_and_hints(oracle):
     ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, "max")
     total = int(sum(wl.dims))
     for hints in (None, to_dev(np.ones(wl.T, np.uint8))):
-        out = torch.full((wl.B, total), float("nan"), dtype=torch.float32, device=DEV)
-        desc = emb.make_mixed_desc(wl.dims, wl.B, emb.EMB_F32, emb.EMB_MAX, batch.num_lookups, 0,
-                                   int(np.diff(wl.table_byte_offsets()).max()), hints)
-        emb.emb_bag_forward_mixed(desc, arena, to_dev(wl.table_byte_offsets()),
-                                  to_dev(wl.out_offsets()), to_dev(batch.indices),
-                                  to_dev(batch.offsets), None, out)
-        torch.cuda.synchronize()
-        assert np.array_equal(out.cpu().numpy().astype(np.float64), ref)
+        for own in (None, dict(stream=1), dict(stream=1, bags_per_group=3, fuse=0)):
+            out = torch.full((wl.B, total), float("nan"), dtype=torch.float32, device=DEV)
+            desc = emb.make_mixed_desc(wl.dims, wl.B, emb.EMB_F32, emb.EMB_MAX, batch.num_lookups, 0,
+                                       int(np.diff(wl.table_byte_offsets()).max()), hints, tuning=own)
+            if own:     # one stream launch per lanes-per-row class, never fused for max pooling
+                plan = emb.emb_bag_plan_forward_mixed(desc)
+                assert plan.kernel == emb.EMB_KERNEL_STREAM and plan.fused == 0
+            emb.emb_bag_forward_mixed(desc, arena, to_dev(wl.table_byte_offsets()),
+                                      to_dev(wl.out_offsets()), to_dev(batch.indices),
+                                      to_dev(batch.offsets), None, out)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy().astype(np.float64), ref), own
+
+
+def test_max_pooling_one_hot_takes_the_stream_kernel_and_returns_the_rows(oracle):
+    """One lookup per bag: the maximum of a bag is its row; the short-bag kernel serves it."""
+    wl = gen.Workload(name="onehot_max", T=5, rows=(1000, 33, 1, 5000, 64), D=32, dtype="f16", B=700,
+                      pooling=("fixed", 1), dists=(("uniform",),) * 5, seed=0x5EED1207)
+    batch = gen.make_batches(wl, 1)[0]
+    arena = gen.host_arena(wl)
+    desc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F16, emb.EMB_MAX, batch.num_lookups, 0, max(wl.rows))
+    assert emb.emb_bag_plan_forward(desc).kernel == emb.EMB_KERNEL_STREAM
+    got = forward(upload_arena(arena), wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                  "max").cpu().numpy()
+    toff = wl.table_offsets()
+    for t in range(wl.T):
+        rows = arena[toff[t] + batch.indices[t * wl.B:(t + 1) * wl.B]].astype(np.float32)
+        assert np.array_equal(got[:, t * wl.D:(t + 1) * wl.D], rows), t
+    ref, _ = oracle.emb_bag(arena, toff, batch.indices, batch.offsets, wl.B, "max")
+    assert np.array_equal(got.astype(np.float64), ref)

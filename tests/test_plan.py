@@ -33,8 +33,10 @@ def test_stream_kernel_threshold_is_three_row_loads_per_bag(D, threshold):
     at = _plan(26, B, D, threshold)
     assert below.kernel == emb.EMB_KERNEL_STREAM and at.kernel == emb.EMB_KERNEL_WAVE
     assert below.bags_per_group >= 1 and at.bags_per_group == 0
+    # every pooling mode streams short bags
+    assert _plan(26, B, D, 1, mode=emb.EMB_MAX).kernel == emb.EMB_KERNEL_STREAM
+    assert _plan(26, B, D, threshold, mode=emb.EMB_MAX).kernel == emb.EMB_KERNEL_WAVE
     # what rules the stream kernel out whatever the bag length
-    assert _plan(26, B, D, 1, mode=emb.EMB_MAX).kernel == emb.EMB_KERNEL_WAVE
     assert _plan(26, B, D, 1, rows=0).kernel == emb.EMB_KERNEL_WAVE             # no row bound: 64-bit
     assert _plan(26, B, D, 1, rows=1 << 40).buffer_addressing == 0
     with tuning(addressing=1):
@@ -227,9 +229,11 @@ def test_short_bags_split_a_mixed_call_into_one_launch_per_row_class(seed, L):
         _mixed_plan(dims, B, L, which=first.num_launches)
 
 
-def test_mixed_plan_never_streams_max_pooling_or_unbounded_tables():
+def test_mixed_plan_never_streams_unbounded_tables_and_never_fuses_max_pooling():
     dims = [32, 64, 128, 256] * 5
-    assert _mixed_plan(dims, 5000, 1, mode=emb.EMB_MAX)[0].num_launches == 1
+    first = _mixed_plan(dims, 5000, 1, mode=emb.EMB_MAX)[0]
+    assert first.num_launches == 4 and first.kernel == emb.EMB_KERNEL_STREAM and first.fused == 0
+    assert _mixed_plan(dims, 5000, 1)[0].fused == 1
     with tuning(stream=0):
         assert _mixed_plan(dims, 5000, 1)[0].num_launches == 1
     with tuning(addressing=1):
@@ -283,12 +287,15 @@ def test_per_table_bag_lengths_split_a_uniform_call_in_two():
     assert len(one) == 1 and one[0][0].kernel == emb.EMB_KERNEL_STREAM and one[0][0].listed == 0
     one = plans(avg=[50.0] * T)
     assert len(one) == 1 and one[0][0].kernel == emb.EMB_KERNEL_WAVE and one[0][0].listed == 0
-    # the explicit settings and max pooling override the per-table choice
+    # the explicit settings override the per-table choice
     with tuning(stream=0):
         assert len(plans()) == 1 and plans()[0][0].kernel == emb.EMB_KERNEL_WAVE
     with tuning(stream=1):
         assert len(plans()) == 1 and plans()[0][0].kernel == emb.EMB_KERNEL_STREAM
-    assert len(plans(mode=emb.EMB_MAX)) == 1
+    # max pooling splits the same way, as two launches (the fused kernels are built for sums)
+    split = plans(mode=emb.EMB_MAX)
+    assert [p.kernel for p, _ in split] == [emb.EMB_KERNEL_WAVE, emb.EMB_KERNEL_STREAM]
+    assert all(p.fused == 0 for p, _ in split)
     with pytest.raises(ValueError):
         emb.make_desc(T, B, 64, emb.EMB_F32, emb.EMB_SUM, nl, 0, 0, table_avg_len=[1.0])
 
