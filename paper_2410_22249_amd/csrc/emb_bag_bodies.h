@@ -229,11 +229,11 @@ __device__ __forceinline__ bool any_lane(bool c) { return __builtin_amdgcn_ballo
 // gw (weights); `pk` holds, in lane r of the group, (relative end << 6 | bag number within the
 // group) of the group's r-th non-empty bag, kNoBag beyond; out_rsrc covers the wavefront's
 // output rows and `store0` is the byte offset of this lane's elements in its group's first bag.
-template <int LPR, int ELEM, int DEPTH, int OP, bool NT>
+template <int LPR, int ELEM, int DEPTH, int OP, bool NT, bool BUF>
 __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
                                               const float* __restrict__ gw, uint32_t glen,
                                               uint32_t pk, int64_t R, uint32_t row_bytes,
-                                              __amdgpu_buffer_rsrc_t rsrc,
+                                              const char* tbase, __amdgpu_buffer_rsrc_t rsrc,
                                               __amdgpu_buffer_rsrc_t out_rsrc, uint32_t store0,
                                               uint32_t out_ld_bytes, uint32_t D, bool mean,
                                               int lane, uint32_t col, bool lane_ok,
@@ -276,7 +276,7 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
       if constexpr (WEIGHTED) wt_next = __builtin_nontemporal_load(gw + qn);
     }
     // a lookup past the group's range has idx = -1: out of range like any invalid row id
-    const uint32_t voff = (uint64_t)idx < (uint64_t)R ? (uint32_t)idx * row_bytes : kBufSentinel;
+    const ChunkLookups<BUF> q = chunk_offsets<BUF>(idx, wt, R, row_bytes);
 
 #pragma unroll 1
     for (int k0 = 0; k0 < LPR; k0 += DEPTH) {
@@ -285,15 +285,28 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
       float wj[DEPTH];
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
-        uint32_t vo = (uint32_t)__shfl((int)voff, group_base + k0 + d);
+        bool row_exists;
+        if constexpr (BUF) {
+          uint32_t vo = (uint32_t)__shfl((int)q.voff, group_base + k0 + d);
+          row_exists = vo != kBufSentinel;
+          vo = lane_ok ? vo : kBufSentinel;
+          r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
+        } else {  // 64-bit addressing: the load is skipped where the buffer would return zeros
+          const int64_t ro = shfl64(q.roff, group_base + k0 + d);
+          row_exists = ro >= 0;
+          u32x4 v = {0u, 0u, 0u, 0u};
+          if (row_exists && lane_ok) {
+            const u32x4* srcp = reinterpret_cast<const u32x4*>(tbase + ro + col);
+            v = NT ? __builtin_nontemporal_load(srcp) : *srcp;
+          }
+          r[d] = v;
+        }
         if constexpr (WEIGHTED)
           wj[d] = __shfl(wt, group_base + k0 + d);
         else if constexpr (MAXP)
-          wj[d] = vo != kBufSentinel ? 1.0f : 0.0f;  // marks a lookup of a row that exists
+          wj[d] = row_exists ? 1.0f : 0.0f;  // marks a lookup of a row that exists
         else
           wj[d] = 1.0f;
-        vo = lane_ok ? vo : kBufSentinel;
-        r[d] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(vo + col), 0, kAux);
       }
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
@@ -343,7 +356,7 @@ __device__ __forceinline__ void stream_groups(const int64_t* __restrict__ gi,
 // different widths that share LPR lanes per row; table t is then described by table_offsets[t]
 // (its BYTE offset in the arena) and out_offsets[t] (its first output column; its width is the
 // difference to the next entry), as for the wave kernel.
-template <int LPR, int ELEM, int DEPTH, int OP, bool MIXED>
+template <int LPR, int ELEM, int DEPTH, int OP, bool MIXED, bool BUF = true>
 __device__ __forceinline__ void stream_body(
     const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
     const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
@@ -374,7 +387,8 @@ __device__ __forceinline__ void stream_body(
   const uint32_t gb0 = (uint32_t)g * M;                            // group's first bag, wave-relative
   const uint32_t m = gb0 < nbw ? (nbw - gb0 < M ? nbw - gb0 : M) : 0u;  // group's bags
 
-  // table geometry (buffer addressing only)
+  static_assert(BUF || !MIXED, "64-bit addressing: tables of one width only");
+  // table geometry
   uint32_t D_t = p.D, row_bytes = p.row_bytes;
   int64_t out_col = (int64_t)t * p.D;
   const char* tbase;
@@ -401,11 +415,11 @@ __device__ __forceinline__ void stream_body(
     const int64_t row0 = uniform64(table_offsets[t]);
     R = uniform64(table_offsets[t + 1]) - row0;
     if (R < 0) R = 0;
-    if (R > p.max_rows) R = p.max_rows;
+    if (BUF && R > p.max_rows) R = p.max_rows;
     tbase = tables + row0 * (int64_t)row_bytes;
   }
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<char*>(tbase), 0, (uint32_t)((uint64_t)R * row_bytes), kBufWord3);
+      const_cast<char*>(tbase), 0, BUF ? (uint32_t)((uint64_t)R * row_bytes) : 0u, kBufWord3);
   const uint32_t col = (uint32_t)l * 16u;
   const bool lane_ok = col < row_bytes;
   const int meta_lane = group_base + (int)(D_t >> 4);
@@ -434,8 +448,8 @@ __device__ __forceinline__ void stream_body(
       e = e < s ? s : (e > p.num_lookups ? p.num_lookups : e);
       float acc[NACC];
       init_acc<ELEM, OP>(acc);
-      gather_bag<LPR, ELEM, 2, OP, true, false>(acc, indices, weights, s, e, R, row_bytes, tbase,
-                                                rsrc, lane, g, col, lane_ok, meta_lane, GL);
+      gather_bag<LPR, ELEM, 2, OP, BUF, false>(acc, indices, weights, s, e, R, row_bytes, tbase,
+                                               rsrc, lane, g, col, lane_ok, meta_lane, GL);
       finish_bag<LPR, ELEM, OP>(acc, LPR, lane, lane_ok, col, D_t, e - s, p.mean != 0, out,
                                 p.out_ld, b0 + i, out_col);
     }
@@ -482,13 +496,13 @@ __device__ __forceinline__ void stream_body(
   const int64_t* gi = indices + S;
   const float* gw = WEIGHTED ? weights + S : nullptr;
   if (streaming)
-    stream_groups<LPR, ELEM, DEPTH, OP, true>(gi, gw, glen, pk, R, row_bytes, rsrc, out_rsrc,
-                                              store0, out_ld_bytes, D_t, p.mean != 0, lane, col,
-                                              lane_ok, meta_lane);
+    stream_groups<LPR, ELEM, DEPTH, OP, true, BUF>(gi, gw, glen, pk, R, row_bytes, tbase, rsrc,
+                                                   out_rsrc, store0, out_ld_bytes, D_t,
+                                                   p.mean != 0, lane, col, lane_ok, meta_lane);
   else
-    stream_groups<LPR, ELEM, DEPTH, OP, false>(gi, gw, glen, pk, R, row_bytes, rsrc, out_rsrc,
-                                               store0, out_ld_bytes, D_t, p.mean != 0, lane, col,
-                                               lane_ok, meta_lane);
+    stream_groups<LPR, ELEM, DEPTH, OP, false, BUF>(gi, gw, glen, pk, R, row_bytes, tbase, rsrc,
+                                                    out_rsrc, store0, out_ld_bytes, D_t,
+                                                    p.mean != 0, lane, col, lane_ok, meta_lane);
 }
 
 }  // namespace embbag

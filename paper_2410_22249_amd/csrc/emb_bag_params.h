@@ -105,15 +105,15 @@ EMB_DECLARE_FUSED_UNIFORM(64)
 // The forward kernels are built one lanes-per-row class per translation unit; each unit exports
 // one function that picks an instantiation (nullptr if there is none):
 //   wave kernel (emb_bag_wave.hip):     lanes per row 0 (different widths), 4 .. 64
-//   stream kernel (emb_bag_stream.hip): lanes per row 4 .. 64, rows of at most 1 KiB, buffer
-//     addressing; `mixed`: tables of different widths within the class
+//   stream kernel (emb_bag_stream.hip): lanes per row 4 .. 64, rows of at most 1 KiB; `mixed`:
+//     tables of different widths within the class (buffer addressing only)
 #define EMB_PASTE_(a, b) a##b
 #define EMB_PASTE(a, b) EMB_PASTE_(a, b)
 #define EMB_DECLARE_PICKERS(n)                                                                  \
   __attribute__((visibility("hidden"))) KernelFn pick_wave_kernel_lpr##n(                       \
       int elem, int depth, int op, bool buf, int variant);                                      \
   __attribute__((visibility("hidden"))) KernelFn pick_stream_kernel_lpr##n(                     \
-      int elem, int depth, int op, bool mixed);
+      int elem, int depth, int op, bool mixed, bool buf);
 EMB_DECLARE_PICKERS(0)  // (there is no stream kernel for class 0; the declaration is unused)
 EMB_DECLARE_PICKERS(4)
 EMB_DECLARE_PICKERS(8)

@@ -59,13 +59,13 @@ KernelFn pick_kernel(int lpr, int elem, int depth, int op, bool buf, int variant
   }
 }
 
-KernelFn pick_stream_kernel(int lpr, int elem, int depth, int op, bool mixed) {
+KernelFn pick_stream_kernel(int lpr, int elem, int depth, int op, bool mixed, bool buf) {
   switch (lpr) {
-    case 4: return pick_stream_kernel_lpr4(elem, depth, op, mixed);
-    case 8: return pick_stream_kernel_lpr8(elem, depth, op, mixed);
-    case 16: return pick_stream_kernel_lpr16(elem, depth, op, mixed);
-    case 32: return pick_stream_kernel_lpr32(elem, depth, op, mixed);
-    case 64: return pick_stream_kernel_lpr64(elem, depth, op, mixed);
+    case 4: return pick_stream_kernel_lpr4(elem, depth, op, mixed, buf);
+    case 8: return pick_stream_kernel_lpr8(elem, depth, op, mixed, buf);
+    case 16: return pick_stream_kernel_lpr16(elem, depth, op, mixed, buf);
+    case 32: return pick_stream_kernel_lpr32(elem, depth, op, mixed, buf);
+    case 64: return pick_stream_kernel_lpr64(elem, depth, op, mixed, buf);
     default: return nullptr;
   }
 }
@@ -260,7 +260,7 @@ bool make_stream(const Tuning& tu, Launch* L, const emb_bag_desc* desc, int op, 
   const int64_t m = stream_bags_per_group(tu, avg_len, lpr, tables, B);
   // the wavefront's output rows are addressed through one buffer with 32-bit offsets
   if ((uint64_t)groups * (uint64_t)m * (uint64_t)out_ld * 4u > kBufMaxBytes) return false;
-  KernelFn fn = pick_stream_kernel(lpr, desc->table_dtype, depth, op, false);
+  KernelFn fn = pick_stream_kernel(lpr, desc->table_dtype, depth, op, false, L->buf);
   if (!fn) return false;
   L->fn = fn;
   L->kernel = EMB_KERNEL_STREAM;
@@ -413,7 +413,7 @@ int plan_uniform(const emb_bag_desc* desc, bool weighted, uint32_t row_bytes, in
   // per-table lengths the host knows the call's average bag length, NL / (T * B), and nothing
   // else; with them each table is judged by its own.
   const double threshold = kStreamBelowRowLoads * groups;
-  const bool can_stream = tu.stream != 0 && slabs == 1 && buf;
+  const bool can_stream = tu.stream != 0 && slabs == 1;
   const std::vector<uint16_t> none;
   if (base.per_table_launch == 1 && T <= 65535) {
     // the paper's launch structure, for comparison: the tables one after the other
@@ -599,7 +599,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
       const int groups = kWaveSize / lpr;
       const int64_t m = stream_bags_per_group(tu, len_sum / (double)ids.size(), lpr,
                                               (int64_t)ids.size(), B);
-      L.fn = pick_stream_kernel(lpr, desc->table_dtype, depth, op, true);
+      L.fn = pick_stream_kernel(lpr, desc->table_dtype, depth, op, true, true);
       if (!L.fn) return EMB_ERR_BAD_TUNING;
       L.kernel = EMB_KERNEL_STREAM;
       L.lpr = lpr;
@@ -628,8 +628,9 @@ bool plan_fused(const std::vector<Launch>& segs, bool mixed, int table_dtype, bo
   int depth = 0, lpr = 0;
   for (const Launch& L : segs) {
     int slot = 0;
+    if (!L.buf) return false;  // the fused kernels address rows through buffer resources
     if (L.kernel == EMB_KERNEL_WAVE) {
-      if ((L.lpr == 0) != mixed || !L.buf) return false;
+      if ((L.lpr == 0) != mixed) return false;
       depth = L.depth;
     } else if (mixed) {
       while ((2 << slot) < L.lpr) ++slot;  // 4 -> 1, 8 -> 2, ... 64 -> 5

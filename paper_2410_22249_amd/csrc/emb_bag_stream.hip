@@ -15,6 +15,9 @@
 //     accumulator to that bag's output and clears it.  The store is a buffer store whose offset
 //     is out of range for lanes that have nothing to store, so the row pipeline has no branches
 //     around memory instructions;
+//   * rows are read through the table's buffer resource, or - tables of one width that are
+//     beyond a buffer's reach or have no row bound - with 64-bit addresses, the load skipped
+//     where the range check would have returned zeros; sum, mean, weighted sum and max pooling;
 //   * empty bags are zero-filled before the stream starts; a wavefront whose bag bounds are not
 //     monotone (malformed input) or whose group covers 2^25 lookups or more handles its bags one
 //     after the other with the whole wavefront instead, with the semantics of the wave kernel.
@@ -40,7 +43,7 @@ namespace {
 using namespace embbag;
 
 // The kernel proper is embbag::stream_body (emb_bag_bodies.h), shared with the fused launch.
-template <int LPR, int ELEM, int DEPTH, int OP, bool MIXED>
+template <int LPR, int ELEM, int DEPTH, int OP, bool MIXED, bool BUF>
 __global__ void __launch_bounds__(kBlock)
 emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict__ table_offsets,
                       const int64_t* __restrict__ indices, const int64_t* __restrict__ offsets,
@@ -48,35 +51,45 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
                       const int64_t* __restrict__ hot_rows,
                       const int64_t* __restrict__ out_offsets, float* __restrict__ out,
                       KParams p, TableOrder order) {
-  stream_body<LPR, ELEM, DEPTH, OP, MIXED>(tables, table_offsets, indices, offsets, weights,
+  stream_body<LPR, ELEM, DEPTH, OP, MIXED, BUF>(tables, table_offsets, indices, offsets, weights,
                                            table_hints, hot_rows, out_offsets, out, p, order, 0u,
                                            blockIdx.x);
 }
 
+// rows through a buffer resource, or (tables of one width only) with 64-bit addresses
+template <int LPR, int ELEM, int DEPTH, int OP, bool MIXED>
+KernelFn pick_addr(bool buf) {
+  if (buf) return emb_bag_stream_kernel<LPR, ELEM, DEPTH, OP, MIXED, true>;
+  if constexpr (!MIXED)
+    return emb_bag_stream_kernel<LPR, ELEM, DEPTH, OP, false, false>;
+  else
+    return nullptr;
+}
+
 template <int LPR, int ELEM, int DEPTH, bool MIXED>
-KernelFn pick_op(int op) {
+KernelFn pick_op(int op, bool buf) {
   switch (op) {
-    case kOpSum: return emb_bag_stream_kernel<LPR, ELEM, DEPTH, kOpSum, MIXED>;
-    case kOpWeighted: return emb_bag_stream_kernel<LPR, ELEM, DEPTH, kOpWeighted, MIXED>;
-    case kOpMax: return emb_bag_stream_kernel<LPR, ELEM, DEPTH, kOpMax, MIXED>;
+    case kOpSum: return pick_addr<LPR, ELEM, DEPTH, kOpSum, MIXED>(buf);
+    case kOpWeighted: return pick_addr<LPR, ELEM, DEPTH, kOpWeighted, MIXED>(buf);
+    case kOpMax: return pick_addr<LPR, ELEM, DEPTH, kOpMax, MIXED>(buf);
     default: return nullptr;
   }
 }
 
 template <int LPR, int ELEM, bool MIXED>
-KernelFn pick_d(int depth, int op) {
+KernelFn pick_d(int depth, int op, bool buf) {
   constexpr int D8 = LPR >= 8 ? 8 : 4;  // a group holds LPR lookups per chunk: DEPTH <= LPR
-  return depth <= 4 ? pick_op<LPR, ELEM, 4, MIXED>(op) : pick_op<LPR, ELEM, D8, MIXED>(op);
+  return depth <= 4 ? pick_op<LPR, ELEM, 4, MIXED>(op, buf) : pick_op<LPR, ELEM, D8, MIXED>(op, buf);
 }
 
 template <int LPR, bool MIXED>
-KernelFn pick_e(int elem, int depth, int op) {
+KernelFn pick_e(int elem, int depth, int op, bool buf) {
   switch (elem) {
-    case EMB_F32: return pick_d<LPR, EMB_F32, MIXED>(depth, op);
-    case EMB_F16: return pick_d<LPR, EMB_F16, MIXED>(depth, op);
-    case EMB_BF16: return pick_d<LPR, EMB_BF16, MIXED>(depth, op);
-    case EMB_U8ROW: return pick_d<LPR, EMB_U8ROW, MIXED>(depth, op);
-    case EMB_FP8ROW: return pick_d<LPR, EMB_FP8ROW, MIXED>(depth, op);
+    case EMB_F32: return pick_d<LPR, EMB_F32, MIXED>(depth, op, buf);
+    case EMB_F16: return pick_d<LPR, EMB_F16, MIXED>(depth, op, buf);
+    case EMB_BF16: return pick_d<LPR, EMB_BF16, MIXED>(depth, op, buf);
+    case EMB_U8ROW: return pick_d<LPR, EMB_U8ROW, MIXED>(depth, op, buf);
+    case EMB_FP8ROW: return pick_d<LPR, EMB_FP8ROW, MIXED>(depth, op, buf);
     default: return nullptr;
   }
 }
@@ -85,8 +98,10 @@ KernelFn pick_e(int elem, int depth, int op) {
 
 namespace embbag {
 
-KernelFn EMB_PASTE(pick_stream_kernel_lpr, EMB_LPR)(int elem, int depth, int op, bool mixed) {
-  return mixed ? pick_e<EMB_LPR, true>(elem, depth, op) : pick_e<EMB_LPR, false>(elem, depth, op);
+KernelFn EMB_PASTE(pick_stream_kernel_lpr, EMB_LPR)(int elem, int depth, int op, bool mixed,
+                                                     bool buf) {
+  return mixed ? pick_e<EMB_LPR, true>(elem, depth, op, buf)
+               : pick_e<EMB_LPR, false>(elem, depth, op, buf);
 }
 
 }  // namespace embbag

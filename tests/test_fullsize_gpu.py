@@ -272,6 +272,39 @@ def test_buffer_addressing_beyond_2_pow_31_bytes(oracle, dtype, D, R):
     assert_close_to_oracle(got, ref, bound, dtype == "f16", f"buffer addressing, {dtype} table of {R * row_bytes} bytes")
 
 
+def test_short_bags_on_a_table_beyond_buffer_addressing(oracle):
+    """A 4.1 GB table with one or two lookups per bag: the short-bag kernel with 64-bit row
+    addresses (the table is beyond the 3.5 GiB a buffer covers); the last rows, ids at and
+    beyond R; the one-wavefront-per-bag kernel must give the same sums to rounding."""
+    R = 8_000_000
+    wl = gen.Workload(name="big_short", T=2, rows=(R, 1000), D=128, dtype="f32", B=20_000,
+                      pooling=("uniform", 0, 2), dists=(("uniform",), ("uniform",)), seed=0x5EED0B10)
+    batch = gen.make_batches(wl, 1)[0]
+    idx = batch.indices.copy()
+    n0 = int(batch.offsets[wl.B])
+    idx[:16] = np.arange(R - 16, R)
+    bad = np.array([16, 17, n0 - 1])
+    idx[bad] = [R, -1, (1 << 40) + 3]
+    assert int((idx[:n0] * 512 >= (7 << 29)).sum()) > 100          # lookups beyond 3.5 GiB
+    arena = device_arena(wl)
+    toff = wl.table_offsets()
+    desc = emb.make_desc(wl.T, wl.B, wl.D, emb.EMB_F32, emb.EMB_SUM, len(idx), 0, R)
+    plan = emb.emb_bag_plan_forward(desc)
+    assert plan.kernel == emb.EMB_KERNEL_STREAM and plan.buffer_addressing == 0
+    got_stream = forward(arena, toff, idx, batch.offsets, wl.B, max_table_rows=R)
+    with tuning(stream=0):
+        got_wave = forward(arena, toff, idx, batch.offsets, wl.B, max_table_rows=R)
+    clean, w = idx.copy(), np.ones(len(idx), np.float32)
+    clean[bad], w[bad] = 0, 0.0
+    bags = np.arange(wl.num_bags)
+    small, ix, soff, ws = gen.compact_rows(wl, gen.Batch(offsets=batch.offsets, indices=clean, weights=w), bags)
+    ref, bound = oracle.emb_bag(small, np.array([0, len(small)], np.int64), ix, soff, len(bags), "sum",
+                                weights=ws)
+    for what, out in (("stream", got_stream), ("wave", got_wave)):
+        got = out.view(wl.B, wl.T, wl.D).permute(1, 0, 2).reshape(wl.num_bags, wl.D).cpu().numpy()
+        assert_close_to_oracle(got, ref, bound, False, f"4.1 GB table, short bags, {what} kernel")
+
+
 def test_the_largest_grid_a_launch_can_hold(oracle):
     """67,108,800 bags with a wavefront each are 16,777,200 workgroups, the most one dispatch
     takes (its work-items are counted in 32 bits); the XCD-affine order would pad that to 2^24

@@ -95,7 +95,8 @@ def test_max_pooling_skips_invalid_lookups(oracle):
     ref, bound = oracle.emb_bag(arena, toff, batch.indices[keep], gen.lengths_to_offsets(lens),
                                 wl.B, "max")
     dev = upload_arena(arena)
-    for kw in (dict(addressing=0), dict(addressing=1), dict(stream=1), dict(stream=1, bags_per_group=4)):
+    for kw in (dict(addressing=0), dict(addressing=1), dict(stream=1), dict(stream=1, bags_per_group=4),
+               dict(stream=1, addressing=1)):
         with tuning(**kw):
             got = forward(dev, toff, idx, batch.offsets, wl.B, "max").cpu().numpy()
         assert np.array_equal(got.astype(np.float64), ref), kw

@@ -36,11 +36,14 @@ def test_stream_kernel_threshold_is_three_row_loads_per_bag(D, threshold):
     # every pooling mode streams short bags
     assert _plan(26, B, D, 1, mode=emb.EMB_MAX).kernel == emb.EMB_KERNEL_STREAM
     assert _plan(26, B, D, threshold, mode=emb.EMB_MAX).kernel == emb.EMB_KERNEL_WAVE
-    # what rules the stream kernel out whatever the bag length
-    assert _plan(26, B, D, 1, rows=0).kernel == emb.EMB_KERNEL_WAVE             # no row bound: 64-bit
-    assert _plan(26, B, D, 1, rows=1 << 40).buffer_addressing == 0
+    # ... with either addressing (no row bound, or tables beyond 3.5 GiB: 64-bit)
+    for kw in (dict(rows=0), dict(rows=1 << 40)):
+        p = _plan(26, B, D, 1, **kw)
+        assert p.kernel == emb.EMB_KERNEL_STREAM and p.buffer_addressing == 0
     with tuning(addressing=1):
-        assert _plan(26, B, D, 1).kernel == emb.EMB_KERNEL_WAVE
+        p = _plan(26, B, D, 1)
+        assert p.kernel == emb.EMB_KERNEL_STREAM and p.buffer_addressing == 0
+    # what rules the stream kernel out whatever the bag length
     with tuning(stream=0):
         assert _plan(26, B, D, 1).kernel == emb.EMB_KERNEL_WAVE
     with tuning(stream=1):

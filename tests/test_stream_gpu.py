@@ -29,7 +29,8 @@ def test_stream_kernel_matches_oracle(oracle, name, mode):
     first = None
     for kw in (dict(), dict(bags_per_group=1), dict(bags_per_group=2), dict(bags_per_group=3),
                dict(bags_per_group=7, depth=4), dict(bags_per_group=63, depth=8),
-               dict(bags_per_group=5, xcd_remap=1), dict(bags_per_group=2, blocks_per_cu=2)):
+               dict(bags_per_group=5, xcd_remap=1), dict(bags_per_group=2, blocks_per_cu=2),
+               dict(addressing=1), dict(addressing=1, bags_per_group=3, depth=8)):   # 64-bit rows
         with tuning(stream=1, **kw):
             got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
                           mode).cpu().numpy()
@@ -49,10 +50,12 @@ def test_stream_kernel_short_and_empty_bags(oracle, name):
         ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
                                     mode)
         for m in (0, 1, 3, 15):
-            with tuning(stream=1, bags_per_group=m):
-                got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
-                              mode).cpu().numpy()
-            assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"short/{name}/{mode}/M{m}")
+            for addressing in (0, 1):
+                with tuning(stream=1, bags_per_group=m, addressing=addressing):
+                    got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
+                                  mode).cpu().numpy()
+                assert_close_to_oracle(got, ref, bound, wl.dtype != "f32",
+                                       f"short/{name}/{mode}/M{m}/addressing {addressing}")
 
 
 @pytest.mark.parametrize("name", ["small_f32_d64", "small_f32_d128", "small_f16_d256",
@@ -75,11 +78,12 @@ def test_stream_kernel_per_sample_weights(oracle, name):
     wl, batch, arena = _problem(name, weighted=True)
     ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
                                 "sum", weights=batch.weights)
-    for m in (0, 2, 6):
-        with tuning(stream=1, bags_per_group=m):
+    for m, addressing in ((0, 0), (2, 0), (6, 0), (0, 1), (5, 1)):
+        with tuning(stream=1, bags_per_group=m, addressing=addressing):
             got = forward(upload_arena(arena), wl.table_offsets(), batch.indices, batch.offsets,
                           wl.B, weights=batch.weights).cpu().numpy()
-        assert_close_to_oracle(got, ref, bound, wl.dtype != "f32", f"stream weighted/{name}/M{m}")
+        assert_close_to_oracle(got, ref, bound, wl.dtype != "f32",
+                               f"stream weighted/{name}/M{m}/addressing {addressing}")
 
 
 @pytest.mark.parametrize("D,dtype", [(4, "f32"), (12, "f32"), (32, "f32"), (96, "f32"), (200, "f32"),
@@ -98,13 +102,13 @@ def test_stream_kernel_row_widths_and_ragged_batches(oracle, D, dtype, B):
     for mode in ("sum", "mean"):
         ref, bound = oracle.emb_bag(arena, wl.table_offsets(), batch.indices, batch.offsets, wl.B,
                                     mode)
-        for m in (0, 1, 3):
-            with tuning(stream=1, bags_per_group=m):
+        for m, addressing in ((0, 0), (1, 0), (3, 0), (2, 1)):
+            with tuning(stream=1, bags_per_group=m, addressing=addressing):
                 got = forward(dev, wl.table_offsets(), batch.indices, batch.offsets, wl.B, mode,
                               out_ld=3 * D + 8, fill=-3.0).cpu().numpy()
             assert np.all(got[:, 3 * D:] == -3.0)
             assert_close_to_oracle(got[:, :3 * D], ref, bound, dtype != "f32",
-                                   f"widths/{dtype}/D{D}/B{B}/{mode}/M{m}")
+                                   f"widths/{dtype}/D{D}/B{B}/{mode}/M{m}/addressing {addressing}")
 
 
 def test_stream_kernel_all_bags_empty_and_single_lookup():
@@ -140,20 +144,21 @@ def test_stream_kernel_bad_indices_and_malformed_offsets(oracle):
     w[pos] = 0.0
     ref, bound = oracle.emb_bag(arena, toff, batch.indices, batch.offsets, wl.B, "sum", weights=w)
     dev = upload_arena(arena)
-    with tuning(stream=1):
-        got = forward(dev, toff, idx, batch.offsets, wl.B).cpu().numpy()
-    assert_close_to_oracle(got, ref, bound, False, "stream/bad indices")
+    for addressing in (0, 1):     # (64-bit rows: a row that does not exist is not read at all)
+        with tuning(stream=1, addressing=addressing):
+            got = forward(dev, toff, idx, batch.offsets, wl.B).cpu().numpy()
+        assert_close_to_oracle(got, ref, bound, False, f"stream/bad indices/addressing {addressing}")
     off = batch.offsets.copy()
     for g in (10, 11, 200, len(off) - 3):
         off[g + 1] = max(off[g] - 3, 0)                   # decreasing pairs
     off[3] = -(1 << 40)
     off[-1] = 1 << 40
-    for m in (0, 1, 4):
-        with tuning(stream=1, bags_per_group=m):
+    for m, addressing in ((0, 0), (1, 0), (4, 0), (2, 1)):
+        with tuning(stream=1, bags_per_group=m, addressing=addressing):
             s = forward(dev, toff, batch.indices, off, wl.B).cpu().numpy()
         with tuning(stream=0):
             v = forward(dev, toff, batch.indices, off, wl.B).cpu().numpy()
-        assert np.isfinite(s).all() and np.array_equal(s, v), m
+        assert np.isfinite(s).all() and np.array_equal(s, v), (m, addressing)
 
 
 def test_stream_kernel_group_of_2_pow_25_lookups_takes_the_slow_path(oracle):
