@@ -118,3 +118,70 @@ def test_unmutated_copy_passes_every_pin(tmp_path):
     clean = _load_mutant(tmp_path, "identity", "acc += w * x;", "acc += w * x; ")
     for f in PIN_FUNCS:
         f(clean)
+
+
+# ---- the two integer oracles written in Python (reuse profile, hot rows) ------------------------
+PY_ORACLES = {"reuse_oracle": os.path.join(ROOT, "oracle", "reuse_oracle.py"),
+              "hot_rows_oracle": os.path.join(ROOT, "oracle", "hot_rows_oracle.py")}
+
+PY_MUTATIONS = {
+    "reuse: repeats counted as distinct ids": ("reuse_oracle", "d = w - len(set(seg))", "d = len(set(seg))"),
+    "reuse: the batch taken to be the window": ("reuse_oracle", "w, n_t = len(seg), e - s", "w, n_t = len(seg), len(seg)"),
+    "reuse: share bar not strict": ("reuse_oracle", "few_repeats = n_t * d * 1000 * 128 < thr", "few_repeats = n_t * d * 1000 * 128 <= thr"),
+    "reuse: cache bar not strict": ("reuse_oracle", "min(int(row_bytes), 128) > d * (1 << 36)", "min(int(row_bytes), 128) >= d * (1 << 36)"),
+    "reuse: cache of half the size": ("reuse_oracle", "> d * (1 << 36)", "> d * (1 << 35)"),
+    "reuse: rows per line ignored in the share": ("reuse_oracle", "thr * w * w * min(int(row_bytes), 128)", "thr * w * w * 128"),
+    "reuse: rows per line ignored in the cache bar": ("reuse_oracle", "w * w * int(row_bytes) * min(int(row_bytes), 128) >", "w * w * int(row_bytes) * 128 >"),
+    "reuse: threshold not capped": ("reuse_oracle", "thr = min(int(threshold_permille), 1_000_000)", "thr = int(threshold_permille)"),
+    "reuse: an empty table is not streaming": ("reuse_oracle", "(w == 0 or beyond_cache or few_repeats)", "(beyond_cache or few_repeats)"),
+    "reuse: window clamped at 4096": ("reuse_oracle", "min(max(int(window), 1), 16384)", "min(max(int(window), 1), 4096)"),
+    "reuse: window not applied": ("reuse_oracle", "indices[s:e][:window]", "indices[s:e]"),
+    "reuse: table boundaries off by one bag": ("reuse_oracle", "int(offsets[t * B]), int(offsets[(t + 1) * B])", "int(offsets[t * B]), int(offsets[(t + 1) * B - 1])"),
+    "hot rows: ties to the larger id": ("hot_rows_oracle", "(-int(counts[i]), int(ids[i]))", "(-int(counts[i]), -int(ids[i]))"),
+    "hot rows: least frequent first": ("hot_rows_oracle", "(-int(counts[i]), int(ids[i]))", "(int(counts[i]), int(ids[i]))"),
+    "hot rows: window not applied": ("hot_rows_oracle", "indices[s:e][:window]", "indices[s:e]"),
+    "hot rows: the id 2^40 - 1 counted": ("hot_rows_oracle", "(seg >= 0) & (seg < ID_LIMIT)", "(seg >= 0) & (seg <= ID_LIMIT)"),
+    "hot rows: negative ids counted": ("hot_rows_oracle", "seg[(seg >= 0) & (seg < ID_LIMIT)]", "seg[seg < ID_LIMIT]"),
+    "hot rows: one row short": ("hot_rows_oracle", "[:k]\n", "[:k - 1]\n"),
+    "hot rows: table boundaries off by one bag": ("hot_rows_oracle", "int(offsets[t * B]), int(offsets[(t + 1) * B])", "int(offsets[t * B]), int(offsets[(t + 1) * B - 1])"),
+}
+
+PY_PINS = {
+    "reuse_oracle": [pins.test_reuse_profile_hand_worked, pins.test_reuse_profile_closed_forms,
+                     pins.test_reuse_profile_counts_the_whole_batch,
+                     pins.test_reuse_profile_rows_in_use_beyond_the_cache],
+    "hot_rows_oracle": [pins.test_hot_rows_hand_worked, pins.test_hot_rows_closed_forms_and_second_route],
+}
+
+
+def _run_py_pins(monkeypatch, which, source):
+    """Run the pins of one Python oracle against a module built from `source`; the names of the
+    exception types they raised."""
+    import types
+    import oracle
+    mod = types.ModuleType(f"oracle.{which}")
+    mod.__file__ = PY_ORACLES[which]
+    sys.modules[f"oracle.{which}_mutant"] = mod     # (dataclasses and typing look modules up by name)
+    exec(compile(source, PY_ORACLES[which], "exec"), mod.__dict__)
+    monkeypatch.setitem(sys.modules, f"oracle.{which}", mod)
+    monkeypatch.setattr(oracle, which, mod, raising=False)
+    caught = []
+    for f in PY_PINS[which]:
+        try:
+            f()
+        except (AssertionError, ValueError, IndexError) as ex:
+            caught.append(type(ex).__name__)
+    return caught
+
+
+@pytest.mark.parametrize("name", sorted(PY_MUTATIONS))
+def test_planted_mistake_in_a_python_oracle_is_caught(monkeypatch, name):
+    which, old, new = PY_MUTATIONS[name]
+    src = open(PY_ORACLES[which]).read()
+    assert src.count(old) == 1, f"mutation {name!r}: pattern must occur exactly once"
+    assert _run_py_pins(monkeypatch, which, src.replace(old, new)), f"no pin noticed: {name}"
+
+
+@pytest.mark.parametrize("which", sorted(PY_ORACLES))
+def test_unmutated_python_oracle_passes_its_pins(monkeypatch, which):
+    assert _run_py_pins(monkeypatch, which, open(PY_ORACLES[which]).read()) == []
