@@ -11,8 +11,9 @@
  *
  * Conventions
  *   - Pointers marked DEVICE are device (HBM) addresses valid on the current HIP device;
- *     pointers marked HOST are ordinary host addresses.  The library allocates nothing, frees
- *     nothing and keeps no pointer after a call returns.
+ *     pointers marked HOST are ordinary host addresses.  The library allocates and frees no
+ *     device memory (its only device memory of its own is the fixed scratch array of
+ *     emb_bag_profile_hot_rows_noalloc) and keeps no pointer after a call returns.
  *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the default
  *     stream) and never synchronise.
  *   - Every function returns an int status: EMB_OK (0) or a negative EMB_ERR_* code.  Nothing is
