@@ -1,7 +1,7 @@
 """Seeded random problems over everything the forward calls accept: uniform and mixed widths, all
 element types, the three pooling modes, weights, short / long / per-table bag lengths (with and
 without table_avg_len), hints, padded outputs, and every tuning key (fused and separate launches
-of split mixed-width calls alternate).  Each case is checked against
+of split mixed-width calls alternate), set process-wide or carried by the descriptor.  Each case is checked against
 the CPU oracle, and guard rows around the output show that no store leaves it; a failure names its
 case, which the seed reproduces."""
 import numpy as np
@@ -56,7 +56,9 @@ def test_random_problems(oracle, block):
         kw = dict(addressing=int(rng.choice([0, 0, 1])), depth=int(rng.choice([0, 1, 2, 4, 8, 16])),
                   xcd_remap=int(rng.integers(-1, 2)), blocks_per_cu=int(rng.choice([0, 0, 0, 3])),
                   stream=int(rng.integers(-1, 2)), bags_per_group=int(rng.choice([0, 0, 1, 2, 3, 7])),
-                  use_hints=int(rng.integers(0, 2)), fuse=case % 2)
+                  use_hints=int(rng.integers(0, 2)), fuse=case % 2,
+                  station=int(rng.integers(0, 2)), bags_per_wave=int(rng.choice([0, 0, 1, 3, 32])))
+        own = rng.random() < 0.5      # the keys travel in the descriptor instead of process-wide
         hints = to_dev(rng.integers(0, 2, size=T).astype(np.uint8)) if rng.random() < 0.5 else None
         pad = int(rng.choice([0, 0, 4, 64]))
         if mixed:
@@ -73,7 +75,8 @@ def test_random_problems(oracle, block):
         avg = gen.table_avg_len(wl, batch) if rng.random() < 0.5 else None
         ld = total + pad
         what = (f"block {block} case {case}: {'mixed' if mixed else 'uniform'} T={T} B={B} {dtype} "
-                f"{mode} w={weighted} pooling={pooling[0]} avg_len={'yes' if avg is not None else 'no'} {kw}")
+                f"{mode} w={weighted} pooling={pooling[0]} avg_len={'yes' if avg is not None else 'no'} "
+                f"{'desc.tuning' if own else 'process-wide'} {kw}")
         print(what, flush=True)
         idx = to_dev(batch.indices) if batch.num_lookups else None
         off, w = to_dev(batch.offsets), to_dev(batch.weights)
@@ -86,8 +89,9 @@ def test_random_problems(oracle, block):
                                               weights=batch.weights, out_ld=ld, codes=wl.codes)
             arena = torch.from_numpy(np.concatenate([t.view(np.uint8).reshape(-1) for t in tabs])).to(DEV)
             desc = emb.make_mixed_desc(dims, B, emb.DTYPES[dtype], emb.MODES[mode], batch.num_lookups,
-                                       ld, int(np.diff(wl.table_byte_offsets()).max()), hints, avg)
-            with tuning(**kw):
+                                       ld, int(np.diff(wl.table_byte_offsets()).max()), hints, avg,
+                                       tuning=kw if own else None)
+            with tuning(**({} if own else kw)):
                 emb.emb_bag_forward_mixed(desc, arena, to_dev(wl.table_byte_offsets()),
                                           to_dev(wl.out_offsets()), idx, off, w, out)
         else:
@@ -96,8 +100,8 @@ def test_random_problems(oracle, block):
                                         weights=batch.weights, out_ld=ld, codes=wl.codes)
             arena = torch.from_numpy(host.view(np.uint8).reshape(-1)).to(DEV)
             desc = emb.make_desc(T, B, wl.D, emb.DTYPES[dtype], emb.MODES[mode], batch.num_lookups, ld,
-                                 max(rows), hints, avg)
-            with tuning(**kw):
+                                 max(rows), hints, avg, tuning=kw if own else None)
+            with tuning(**({} if own else kw)):
                 emb.emb_bag_forward(desc, arena, to_dev(wl.table_offsets()), idx, off, w, out)
         torch.cuda.synchronize()
         whole = big.cpu().numpy()
