@@ -26,10 +26,15 @@ from typing import Tuple
 import numpy as np
 
 
+MAX_WINDOW = 16384   # the largest window the interface examines
+
+
 def profile_reuse(indices: np.ndarray, offsets: np.ndarray, T: int, B: int, window: int,
                   threshold_permille: int = 75, *, row_bytes: int
                   ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    window = min(max(int(window), 1), 16384)
+    window = int(window)
+    if not 1 <= window <= MAX_WINDOW:
+        raise ValueError(f"window must be in [1, {MAX_WINDOW}] (the interface clamps; this definition does not)")
     dup = np.zeros(T, dtype=np.int32)
     used = np.zeros(T, dtype=np.int32)
     hints = np.zeros(T, dtype=np.uint8)

@@ -134,7 +134,7 @@ PY_MUTATIONS = {
     "reuse: rows per line ignored in the cache bar": ("reuse_oracle", "w * w * int(row_bytes) * min(int(row_bytes), 128) >", "w * w * int(row_bytes) * 128 >"),
     "reuse: threshold not capped": ("reuse_oracle", "thr = min(int(threshold_permille), 1_000_000)", "thr = int(threshold_permille)"),
     "reuse: an empty table is not streaming": ("reuse_oracle", "(w == 0 or beyond_cache or few_repeats)", "(beyond_cache or few_repeats)"),
-    "reuse: window clamped at 4096": ("reuse_oracle", "min(max(int(window), 1), 16384)", "min(max(int(window), 1), 4096)"),
+    "reuse: the largest window refused": ("reuse_oracle", "if not 1 <= window <= MAX_WINDOW:", "if not 1 <= window < MAX_WINDOW:"),
     "reuse: window not applied": ("reuse_oracle", "indices[s:e][:window]", "indices[s:e]"),
     "reuse: table boundaries off by one bag": ("reuse_oracle", "int(offsets[t * B]), int(offsets[(t + 1) * B])", "int(offsets[t * B]), int(offsets[(t + 1) * B - 1])"),
     "hot rows: ties to the larger id": ("hot_rows_oracle", "(-int(counts[i]), int(ids[i]))", "(-int(counts[i]), -int(ids[i]))"),

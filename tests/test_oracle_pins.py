@@ -559,10 +559,14 @@ def test_reuse_profile_rows_in_use_beyond_the_cache():
         assert reuse_oracle.profile_reuse(idx, off, 1, 1, 16384, 75, row_bytes=row_bytes)[2].tolist() == [want]
     # the largest window: 16384 draws, 1024-byte rows: 2^38 > d * 2^29 for d < 512
     idx, off = _one_table_with_repeats(16384, 511, n)
-    assert reuse_oracle.profile_reuse(idx, off, 1, 1, 1 << 20, 75, row_bytes=1024)[2].tolist() == [1]
+    assert reuse_oracle.profile_reuse(idx, off, 1, 1, 16384, 75, row_bytes=1024)[2].tolist() == [1]
     idx, off = _one_table_with_repeats(16384, 512, n)
-    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 1, 1, 1 << 20, 75, row_bytes=1024)
+    dup, used, hints = reuse_oracle.profile_reuse(idx, off, 1, 1, 16384, 75, row_bytes=1024)
     assert used.tolist() == [16384] and dup.tolist() == [512] and hints.tolist() == [0]
+    # windows outside the interface's range are not defined here (the interface clamps them)
+    for bad in (0, 16385, 1 << 20):
+        with pytest.raises(ValueError):
+            reuse_oracle.profile_reuse(idx, off, 1, 1, bad, 75, row_bytes=1024)
 
 
 @pytest.mark.parametrize("name,seeds,want", [

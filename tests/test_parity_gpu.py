@@ -376,9 +376,10 @@ def test_reuse_profile_matches_oracle_bit_for_bit():
                 hints = torch.full((wl.T,), 9, dtype=torch.uint8, device=DEV)
                 emb.emb_bag_profile_reuse(desc, idx, off, window, thr, dup, used, hints)
                 torch.cuda.synchronize()
+                # (a window beyond the interface's range is clamped to it)
                 rd, ru, rh = reuse_oracle.profile_reuse(batch.indices, batch.offsets, wl.T, wl.B,
-                                                        window, 75 if thr < 0 else thr,
-                                                        row_bytes=D * 4)
+                                                        min(window, reuse_oracle.MAX_WINDOW),
+                                                        75 if thr < 0 else thr, row_bytes=D * 4)
                 assert np.array_equal(dup.cpu().numpy(), rd), (wl.name, window)
                 assert np.array_equal(used.cpu().numpy(), ru)
                 assert np.array_equal(hints.cpu().numpy(), rh), (wl.name, D, window, thr)
