@@ -460,9 +460,8 @@ int emb_bag_plan_forward_mixed(const emb_bag_mixed_desc* desc, int has_weights, 
  *                   -1 = automatic (average bag length num_lookups / (T * batch) below three
  *                   load instructions' worth of rows, i.e. 3 * 1024 / row bytes rounded to a
  *                   power of two: 24 at 128-byte rows, 12 at 256, 6 at 512, 3 at 1 KiB; rows of
- *                   at most 1 KiB; every pooling mode; either addressing, for tables of
- *                   different widths buffer addressing only), 0 = never, 1 = whenever rows and
- *                   addressing allow it.  It adds a bag's rows in the order of its lookups; the
+ *                   at most 1 KiB; every pooling mode; either addressing), 0 = never, 1 =
+ *                   whenever the row size allows it.  It adds a bag's rows in the order of its lookups; the
  *                   one-wavefront-per-bag kernel keeps several partial sums, so the two agree
  *                   to rounding, not to the bit.
  *                   With desc->table_avg_len the automatic choice is made per table.

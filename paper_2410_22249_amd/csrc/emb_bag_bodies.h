@@ -387,7 +387,6 @@ __device__ __forceinline__ void stream_body(
   const uint32_t gb0 = (uint32_t)g * M;                            // group's first bag, wave-relative
   const uint32_t m = gb0 < nbw ? (nbw - gb0 < M ? nbw - gb0 : M) : 0u;  // group's bags
 
-  static_assert(BUF || !MIXED, "64-bit addressing: tables of one width only");
   // table geometry
   uint32_t D_t = p.D, row_bytes = p.row_bytes;
   int64_t out_col = (int64_t)t * p.D;
@@ -408,7 +407,7 @@ __device__ __forceinline__ void stream_body(
     const int64_t byte0 = uniform64(table_offsets[t]);
     int64_t bytes = uniform64(table_offsets[t + 1]) - byte0;
     if (bytes < 0) bytes = 0;
-    if (bytes > (int64_t)kBufMaxBytes) bytes = (int64_t)kBufMaxBytes;
+    if (BUF && bytes > (int64_t)kBufMaxBytes) bytes = (int64_t)kBufMaxBytes;
     R = bytes / row_bytes;
     tbase = tables + byte0;
   } else {

@@ -106,7 +106,7 @@ EMB_DECLARE_FUSED_UNIFORM(64)
 // one function that picks an instantiation (nullptr if there is none):
 //   wave kernel (emb_bag_wave.hip):     lanes per row 0 (different widths), 4 .. 64
 //   stream kernel (emb_bag_stream.hip): lanes per row 4 .. 64, rows of at most 1 KiB; `mixed`:
-//     tables of different widths within the class (buffer addressing only)
+//     tables of different widths within the class
 #define EMB_PASTE_(a, b) a##b
 #define EMB_PASTE(a, b) EMB_PASTE_(a, b)
 #define EMB_DECLARE_PICKERS(n)                                                                  \

@@ -542,7 +542,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
     p.wpt = (uint32_t)((B + p.bags_per_wave - 1) / p.bags_per_wave);
   }
   // (judged by the call's average bag length, or table by table with desc->table_avg_len)
-  const bool can_stream = tu.stream != 0 && buf;
+  const bool can_stream = tu.stream != 0;
   const bool per_table = tu.stream == -1 && desc->table_avg_len != nullptr;
   bool fits[7] = {false, false, false, false, false, false, false};  // by log2(lanes per row)
   for (int lg = 2; lg <= 6 && can_stream; ++lg) {
@@ -599,7 +599,7 @@ int plan_mixed(const emb_bag_mixed_desc* desc, bool weighted, uint32_t max_row_b
       const int groups = kWaveSize / lpr;
       const int64_t m = stream_bags_per_group(tu, len_sum / (double)ids.size(), lpr,
                                               (int64_t)ids.size(), B);
-      L.fn = pick_stream_kernel(lpr, desc->table_dtype, depth, op, true, true);
+      L.fn = pick_stream_kernel(lpr, desc->table_dtype, depth, op, true, buf);
       if (!L.fn) return EMB_ERR_BAD_TUNING;
       L.kernel = EMB_KERNEL_STREAM;
       L.lpr = lpr;

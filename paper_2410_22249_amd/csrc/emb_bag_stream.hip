@@ -15,9 +15,9 @@
 //     accumulator to that bag's output and clears it.  The store is a buffer store whose offset
 //     is out of range for lanes that have nothing to store, so the row pipeline has no branches
 //     around memory instructions;
-//   * rows are read through the table's buffer resource, or - tables of one width that are
-//     beyond a buffer's reach or have no row bound - with 64-bit addresses, the load skipped
-//     where the range check would have returned zeros; sum, mean, weighted sum and max pooling;
+//   * rows are read through the table's buffer resource, or - tables that are beyond a
+//     buffer's reach or have no size bound - with 64-bit addresses, the load skipped where the
+//     range check would have returned zeros; sum, mean, weighted sum and max pooling;
 //   * empty bags are zero-filled before the stream starts; a wavefront whose bag bounds are not
 //     monotone (malformed input) or whose group covers 2^25 lookups or more handles its bags one
 //     after the other with the whole wavefront instead, with the semantics of the wave kernel.
@@ -56,14 +56,11 @@ emb_bag_stream_kernel(const char* __restrict__ tables, const int64_t* __restrict
                                            blockIdx.x);
 }
 
-// rows through a buffer resource, or (tables of one width only) with 64-bit addresses
+// rows through a buffer resource, or with 64-bit addresses
 template <int LPR, int ELEM, int DEPTH, int OP, bool MIXED>
 KernelFn pick_addr(bool buf) {
-  if (buf) return emb_bag_stream_kernel<LPR, ELEM, DEPTH, OP, MIXED, true>;
-  if constexpr (!MIXED)
-    return emb_bag_stream_kernel<LPR, ELEM, DEPTH, OP, false, false>;
-  else
-    return nullptr;
+  return buf ? emb_bag_stream_kernel<LPR, ELEM, DEPTH, OP, MIXED, true>
+             : emb_bag_stream_kernel<LPR, ELEM, DEPTH, OP, MIXED, false>;
 }
 
 template <int LPR, int ELEM, int DEPTH, bool MIXED>

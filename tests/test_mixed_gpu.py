@@ -230,8 +230,15 @@ def test_mixed_widths_with_short_bags_use_the_stream_kernel(oracle, dtype, pooli
     for mode in ("sum", "mean"):
         ref, bound = oracle.emb_bag_mixed(tabs, batch.indices, batch.offsets, wl.B, mode)
         first = None
-        for kw in (dict(), dict(xcd_remap=1), dict(bags_per_group=3), dict(stream=1, depth=4)):
+        for kw in (dict(), dict(xcd_remap=1), dict(bags_per_group=3), dict(addressing=1),
+                   dict(addressing=1, bags_per_group=2, fuse=0), dict(stream=1, depth=4),
+                   dict(stream=1, depth=8, addressing=1)):          # (addressing 1: 64-bit rows)
             with tuning(**kw):
+                if kw.get("addressing") == 1:
+                    n = emb.emb_bag_plan_forward_mixed(desc).num_launches
+                    p64 = [emb.emb_bag_plan_forward_mixed(desc, which=k) for k in range(n)]
+                    assert all(p.buffer_addressing == 0 for p in p64)
+                    assert any(p.kernel == emb.EMB_KERNEL_STREAM for p in p64)
                 got = _forward(wl, arena, batch, mode).cpu().numpy()
             assert_close_to_oracle(got, ref, bound, dtype != "f32", f"mixed short/{dtype}/{mode}/{kw}")
             if first is None:

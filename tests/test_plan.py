@@ -232,17 +232,22 @@ def test_short_bags_split_a_mixed_call_into_one_launch_per_row_class(seed, L):
         _mixed_plan(dims, B, L, which=first.num_launches)
 
 
-def test_mixed_plan_never_streams_unbounded_tables_and_never_fuses_max_pooling():
+def test_mixed_plan_streams_with_either_addressing_and_never_fuses_max_pooling_or_64_bit_rows():
     dims = [32, 64, 128, 256] * 5
     first = _mixed_plan(dims, 5000, 1, mode=emb.EMB_MAX)[0]
     assert first.num_launches == 4 and first.kernel == emb.EMB_KERNEL_STREAM and first.fused == 0
     assert _mixed_plan(dims, 5000, 1)[0].fused == 1
     with tuning(stream=0):
         assert _mixed_plan(dims, 5000, 1)[0].num_launches == 1
+    # 64-bit addressing (forced, or no bound on the table sizes): the same launches, not fused
     with tuning(addressing=1):
-        assert _mixed_plan(dims, 5000, 1)[0].num_launches == 1
+        first = _mixed_plan(dims, 5000, 1)[0]
+        assert (first.num_launches, first.kernel, first.buffer_addressing, first.fused) == \
+            (4, emb.EMB_KERNEL_STREAM, 0, 0)
     desc = emb.make_mixed_desc(dims, 5000, emb.EMB_F32, emb.EMB_SUM, 20 * 5000, 0, 0)   # no size bound
-    assert emb.emb_bag_plan_forward_mixed(desc).num_launches == 1
+    first = emb.emb_bag_plan_forward_mixed(desc)
+    assert (first.num_launches, first.kernel, first.buffer_addressing, first.fused) == \
+        (4, emb.EMB_KERNEL_STREAM, 0, 0)
     with tuning(stream=1):                                      # forced on: every class streams
         first, _ = _mixed_plan(dims, 5000, 100)
         assert first.num_launches == 4 and first.kernel == emb.EMB_KERNEL_STREAM
